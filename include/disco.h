@@ -1,0 +1,356 @@
+/*
+ * disco.h -- C ABI of libdisco: batched, trace-driven evaluation of the DiSCo
+ * device/server dispatch and token-level migration policies (arXiv 2502.11417)
+ * over (request x policy-column) pairs on one AMD MI355X (gfx950).
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ *  - "host" pointers are ordinary process memory, read during the call only.
+ *    "device" pointers are HIP device memory that the caller allocated, owns
+ *    and keeps alive until the work enqueued by the call has finished.  The
+ *    library never allocates, frees or retains device memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    All work is enqueued on it and the calls return without waiting, except
+ *    where a call says it synchronises.
+ *  - Return value: DISCO_OK or a negative DISCO_ERR_* code.  Shapes, null
+ *    pointers and workspace sizes are checked on the host before anything is
+ *    launched; a failed check launches nothing.  No exceptions, no abort.
+ *  - Times are fp32 seconds, lengths int32 tokens, CSR offsets int64, token
+ *    totals int64, sums and costs fp64.
+ *  - Per-pair arrays are policy-major: element (column j, request i) is at
+ *    [j * n_req + i].
+ */
+#ifndef DISCO_H
+#define DISCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DISCO_OK              0
+#define DISCO_ERR_NULL      (-1)  /* a required pointer is NULL */
+#define DISCO_ERR_SHAPE     (-2)  /* negative or inconsistent sizes, P outside [1, DISCO_MAX_COLS] */
+#define DISCO_ERR_RANGE     (-3)  /* a parameter outside its documented range */
+#define DISCO_ERR_CSR       (-4)  /* token arrays required by the call are missing */
+#define DISCO_ERR_WORKSPACE (-5)  /* workspace missing or smaller than disco_workspace_bytes() */
+#define DISCO_ERR_HIP       (-6)  /* a HIP runtime call failed; see disco_last_hip_error() */
+
+#define DISCO_MAX_COLS   64       /* policy columns per call */
+#define DISCO_MAX_Q       4       /* quantiles per call */
+#define DISCO_MAX_STEPS  64       /* bisection steps per search */
+
+/* ---- trace ------------------------------------------------------------- */
+
+/* One batch of requests, structure-of-arrays, all arrays on the device.
+ * The per-request measurements are the inputs the paper's policies assume to
+ * be known (Sec. 4.2: the server TTFT distribution from profiling, the device
+ * TTFT linear in prompt length, T_d(l) = k l + c).
+ *   prompt_len[i]  l_i                       output_len[i]  n_i >= 1
+ *   srv_ttft[i]    s_i > 0, server time to first token (network + queue + prefill)
+ *   srv_tbt[i]     constant server gap, used only when tok_arr is NULL
+ *   dev_pre_spt[i] k_i, device seconds per prompt token   (NULL: dev_pre_spt_s for all)
+ *   dev_dec_spt[i] g_i, device seconds per decoded token  (NULL: dev_dec_spt_s for all)
+ *   tok_off[n_req+1], tok_arr[n_tok]  CSR: server arrival offset of token t of
+ *       request i, in seconds since that request's first token, at
+ *       tok_arr[tok_off[i] + t]; tok_off[i+1] - tok_off[i] == output_len[i],
+ *       tok_arr[tok_off[i]] == 0, non-decreasing inside a request.  Both NULL
+ *       when the batch carries no per-token timeline.
+ *   dev_ttft_c     c, the intercept of the device TTFT. */
+typedef struct disco_trace {
+    int64_t n_req;
+    int64_t n_tok;
+    int32_t* prompt_len;
+    int32_t* output_len;
+    float* srv_ttft;
+    float* srv_tbt;
+    float* dev_pre_spt;
+    float* dev_dec_spt;
+    int64_t* tok_off;
+    float* tok_arr;
+    float dev_pre_spt_s;
+    float dev_dec_spt_s;
+    float dev_ttft_c;
+    float reserved;
+} disco_trace;
+
+/* Parameters of the synthetic trace that stands in for the measured server
+ * traces and device profiles of Sec. 5.1 (recipe of the scalability study in
+ * Sec. 5.3: log-normal prompt lengths and server TTFT; server TTFT independent
+ * of prompt length, Sec. 3).  Element `index` of field f is a function of
+ * (seed, f, index) alone: Philox4x32-10 with key = seed and counter =
+ * (index_lo, index_hi, f, 0); f = 0 prompt_len, 1 output_len, 2 srv_ttft,
+ * 3 srv_tbt, 4 device speed (index = request), 5 per-token gap (index =
+ * global token index). */
+typedef struct disco_gen_params {
+    uint64_t seed;
+    int64_t n_req;
+    float prompt_mu, prompt_sigma; int32_t prompt_lo, prompt_hi;  /* l = clamp(floor(LN)) */
+    float out_mu, out_sigma; int32_t out_lo, out_hi;              /* n = clamp(floor(LN)) */
+    float ttft_mu, ttft_sigma;        /* s ~ LN(mu, sigma) with probability 1 - ttft_pareto_p */
+    float ttft_pareto_p, ttft_pareto_xm, ttft_pareto_alpha;       /* else Pareto(xm, alpha) */
+    float tbt_mu, tbt_sigma;          /* per-request constant server gap ~ LN */
+    int32_t dev_mode;                 /* 0: g = dev_a s/token, k = dev_b s/token;
+                                         1: decode rate uniform on [dev_a, dev_b] tokens/s;
+                                         2: rate dev_a tokens/s with probability dev_p, else dev_b;
+                                         modes 1, 2: k = g / dev_pre_ratio */
+    float dev_a, dev_b, dev_p, dev_pre_ratio;
+    float gap_mu, gap_sigma;          /* per-token server gap ~ LN, replaced with probability */
+    float gap_stall_p, gap_stall_lo, gap_stall_hi;   /* gap_stall_p by U[lo, hi] seconds */
+} disco_gen_params;
+
+#define DISCO_GEN_REQUESTS 1   /* per-request arrays and tok_off */
+#define DISCO_GEN_TOKENS   2   /* tok_arr from tok_off (after DISCO_GEN_REQUESTS) */
+
+/* Fill a trace on the device.  `trace` is a host struct whose device arrays
+ * the caller allocated: n_req elements each (tok_off: n_req + 1; every
+ * per-request array including dev_pre_spt / dev_dec_spt is required).
+ * stages & DISCO_GEN_REQUESTS: writes the per-request arrays and tok_off,
+ *   then SYNCHRONISES the stream and stores the token total in trace->n_tok
+ *   so that the caller can size tok_arr.
+ * stages & DISCO_GEN_TOKENS: writes tok_arr[0 .. trace->n_tok) (asynchronous);
+ *   trace->n_tok must equal tok_off[n_req].  The arrival offsets of a request
+ *   are the running fp32 sum, in index order, of its per-token gaps.
+ * Errors: NULL (struct or a required array), SHAPE (n_req < 0, lo > hi),
+ * RANGE (sigma < 0, probabilities outside [0,1], rates <= 0), HIP. */
+int32_t disco_gen_trace(const disco_gen_params* params /*host*/, disco_trace* trace /*host, device arrays*/,
+                        int32_t stages, void* stream);
+
+/* ---- policy and cost ---------------------------------------------------- */
+
+#define DISCO_MODE_SERVER_CONSTRAINED 0   /* length threshold, Sec. 4.2 Eq. 3 / Alg. 3 */
+#define DISCO_MODE_DEVICE_CONSTRAINED 1   /* wait time, Sec. 4.2 Eq. 1 / Alg. 2 */
+#define DISCO_MIG_NONE 0
+#define DISCO_MIG_LAG  1                  /* hand-off to the device when a server token is overdue */
+
+/* One policy column (32 bytes).
+ * Server-constrained: prompts with l < l_th run on the device alone, the
+ *   rest start on both endpoints at time 0 (Alg. 3).
+ * Device-constrained: the server starts at 0; the device starts after the
+ *   wait w(l) = 0 if l <= l_th; w_mid if l == l_mid; else min(beta * l,
+ *   w_tail) -- but only if the server's first token has not arrived by then
+ *   (s > w).  beta = +inf gives the step map of Alg. 2, l_mid = -1 the ramp
+ *   of Eq. 1, w_tail = +inf a server-only column.
+ * In both modes the endpoint with the strictly earlier first token decodes
+ * and the other is terminated (Sec. 4.2); a tie goes to the server. */
+typedef struct disco_policy {
+    int32_t mode;
+    int32_t l_th;
+    int32_t l_mid;
+    float w_mid;
+    float beta;
+    float w_tail;
+    int32_t mig_mode;
+    int32_t reserved;
+} disco_policy;
+
+/* Unified cost (Sec. 4.1, App. E): server money per token plus lambda times
+ * device energy per token, prefill and decode priced separately.
+ * total = cs_pre*S_pre + cs_dec*S_dec + lambda*(e_pre*D_pre + e_dec*D_dec). */
+typedef struct disco_cost_params {
+    double cs_pre, cs_dec;   /* $ per server prefill / decode token */
+    double e_pre, e_dec;     /* J per device prefill / decode token (linear in FLOPs) */
+    double lambda;           /* $ per J */
+} disco_cost_params;
+
+/* Pacing of the token buffer (Sec. 4.3): tokens leave the buffer no faster
+ * than one per `tau` seconds (the user's consumption rate r_c = 1/tau); a
+ * lag hand-off fires when a token is more than kappa_lag * tau overdue. */
+typedef struct disco_timeline_params {
+    float tau;
+    float kappa_lag;
+} disco_timeline_params;
+
+/* ---- per-pair outputs and per-column accumulators ----------------------- */
+
+/* Optional materialised dispatch outputs, device, [P][n_req]; either member
+ * may be NULL.  decision: bit0 server started, bit1 device started, bit2
+ * device won (1 server only, 6 device only, 3 race won by the server, 7 race
+ * won by the device).  ttft: time to first token of the pair. */
+typedef struct disco_pair_out {
+    uint8_t* decision;
+    float* ttft;
+} disco_pair_out;
+
+/* Optional materialised timeline outputs, device; members may be NULL.
+ * mig_idx [P][n_req]: index of the first token produced by the device after
+ *   a hand-off, -1 if none.  n_src_tok [P][n_req]: tokens produced by the
+ *   endpoint that won the first token.  t_last [P][n_req]: delivery offset of
+ *   the last token since the first one.
+ * delivered [n_tok] (column `delivered_col` only; needs tok_off): delivery
+ *   offset of every token. */
+typedef struct disco_mig_out {
+    int32_t* mig_idx;
+    int32_t* n_src_tok;
+    float* t_last;
+    float* delivered;
+    int32_t delivered_col;
+    int32_t reserved;
+} disco_mig_out;
+
+/* Per-column accumulator, device, 128 bytes.  disco_eval_dispatch overwrites
+ * the first block, disco_eval_migration the second. */
+typedef struct disco_accum {
+    /* dispatch: every started endpoint is charged the prompt; the winner is
+     * charged the n output tokens (the paper's "w/o Migration" accounting) */
+    int64_t s_pre, s_dec, d_pre, d_dec;
+    int64_t n_dev_started, n_dev_win;
+    double ttft_sum;
+    /* timelines: decode tokens per endpoint with hand-offs, extra device
+     * re-prefill tokens (prompt + tokens already produced, Sec. 4.3: only
+     * token ids are transferred), hand-off count, number of TBT values,
+     * sum of last delivery offsets (= sum of all TBT values) */
+    int64_t m_s_dec, m_d_dec, m_d_repre;
+    int64_t n_migrated, tbt_count;
+    double tlast_sum;
+    /* smallest and largest fp32 bit pattern among the column's TTFT / TBT
+     * values (non-negative floats order like their bit patterns); they bound
+     * the key range of the order-statistic selection */
+    uint32_t ttft_min_bits, ttft_max_bits;
+    uint32_t tbt_min_bits, tbt_max_bits;
+    int64_t reserved[1];
+} disco_accum;
+
+/* ---- evaluation --------------------------------------------------------- */
+
+/* Dispatch of every (request, column) pair (Sec. 4.2, Alg. 2 and 3):
+ * device TTFT d = fma(l, k, c); wait; which endpoints start; winner; TTFT.
+ * pol: host, P entries.  out: host struct of device arrays, may be NULL.
+ * acc: device, P entries, dispatch block overwritten.
+ * ws: device workspace of disco_workspace_bytes(n_req, P) bytes.
+ * Asynchronous.  n_req == 0 is valid (zero totals).
+ * Errors: NULL, SHAPE, RANGE (unknown mode), WORKSPACE, HIP. */
+int32_t disco_eval_dispatch(const disco_trace* trace /*host*/, const disco_policy* pol /*host*/, int32_t P,
+                            const disco_pair_out* out /*host, nullable*/, disco_accum* acc /*device*/,
+                            void* ws /*device*/, size_t ws_bytes, void* stream);
+
+/* Token timelines of every pair (Sec. 4.3).  The source of a pair is the
+ * winner of its dispatch (recomputed from `pol`).  Arrival offsets r_t since
+ * the first token: server = tok_arr (or t * srv_tbt without a token trace),
+ * device = t * g.  Paced delivery delta_0 = 0, delta_t = max(r_t,
+ * delta_{t-1} + tau), evaluated as delta_t = fma(t, tau, max_{v<=t}
+ * fma(-v, tau, r_v)).  With mig_mode == DISCO_MIG_LAG and a server source:
+ * m = first t >= 1 with r_t - (delta_{t-1} + tau) > kappa_lag * tau; the
+ * device then produces tokens m.. with r'_t = fma(t - m + 1, g, ((delta_{m-1}
+ * + tau) + kappa_lag*tau) + fma(l + m, k, c)).
+ * acc: device, P entries, timeline block overwritten.  Asynchronous.
+ * Errors: NULL, SHAPE, RANGE (tau <= 0, kappa_lag < 0), CSR (delivered
+ * requested without tok_off), WORKSPACE, HIP. */
+int32_t disco_eval_migration(const disco_trace* trace /*host*/, const disco_timeline_params* tl /*host*/,
+                             const disco_policy* pol /*host*/, int32_t P,
+                             const disco_mig_out* out /*host, nullable*/, disco_accum* acc /*device*/,
+                             void* ws /*device*/, size_t ws_bytes, void* stream);
+
+/* ---- statistics --------------------------------------------------------- */
+
+/* Per-column result (Sec. 5.1 metrics), device or host memory, 256 bytes. */
+typedef struct disco_stats {
+    double mean_ttft, mean_tbt;
+    double server_cost, device_energy, device_cost, total_cost;
+    int64_t s_pre, s_dec, d_pre, d_dec;       /* totals used for the cost */
+    int64_t n_req, tbt_count, n_migrated, n_dev_started, n_dev_win;
+    int64_t ttft_rank[DISCO_MAX_Q];            /* 1-based rank selected for each quantile */
+    int64_t tbt_rank[DISCO_MAX_Q];
+    float ttft_q[DISCO_MAX_Q];                 /* the order statistic of that rank */
+    float tbt_q[DISCO_MAX_Q];
+    int64_t reserved[5];
+} disco_stats;
+
+typedef struct disco_quantile { int32_t num, den; } disco_quantile;   /* q = num/den in [0,1] */
+
+/* Reduce the accumulators of the eval calls to per-column statistics and
+ * select order statistics.  Quantile q of M values is the nearest-rank order
+ * statistic: rank k = ceil(q M) clamped to [1, M], computed in integers;
+ * M == 0 gives rank 0 and NaN.  TTFT quantiles are over the n_req pairs of a
+ * column; TBT quantiles pool every gap delta_t - delta_{t-1} of every request
+ * of the column (sum of n_i - 1 values).  Selection is exact: a most-
+ * significant-digit-first radix histogram select over the fp32 bit patterns
+ * (times are non-negative, so the patterns order like the values); the pairs
+ * are recomputed from the trace for every digit rather than stored.
+ * tl == NULL: dispatch statistics only (decode charged to the winner).
+ * tl != NULL: acc must also hold disco_eval_migration's block; decode and
+ *   re-prefill tokens come from it and TBT statistics are produced.
+ * out: device, P entries.  Asynchronous.
+ * Errors: NULL, SHAPE (nq outside [0, DISCO_MAX_Q]), RANGE (den <= 0, num
+ * outside [0, den]), WORKSPACE, HIP. */
+int32_t disco_reduce_stats(const disco_trace* trace /*host*/, const disco_cost_params* cost /*host*/,
+                           const disco_timeline_params* tl /*host, nullable*/,
+                           const disco_policy* pol /*host*/, int32_t P,
+                           const disco_accum* acc /*device*/, const disco_quantile* q /*host*/, int32_t nq,
+                           disco_stats* out /*device*/, void* ws /*device*/, size_t ws_bytes, void* stream);
+
+/* ---- budget search ------------------------------------------------------ */
+
+#define DISCO_PARAM_L_TH    0   /* integer bisection on disco_policy.l_th */
+#define DISCO_PARAM_W_TAIL  1   /* fp32 bisection on disco_policy.w_tail */
+
+#define DISCO_ACC_TOTAL_COST          0
+#define DISCO_ACC_SERVER_COST         1
+#define DISCO_ACC_DEVICE_COST         2   /* lambda * device energy */
+#define DISCO_ACC_SERVER_PREFILL_TOK  3   /* input tokens the server processes (budget of Eq. 3) */
+#define DISCO_ACC_DEVICE_PREFILL_TOK  4   /* input tokens the device processes (budget of Sec. 4.2) */
+
+/* One search: bisect one parameter of `templ` so that an accumulator that
+ * does not increase with the parameter meets `target` (the budget of Sec. 4.2
+ * is an allowance for the constrained endpoint; Eq. 3 and Alg. 2 ask for the
+ * threshold / wait that meets it).  The accumulator is computed from exact
+ * int64 token totals of a dispatch pass (decode charged to the winner).
+ * W_TAIL: mid = 0.5f * (lo + hi) in fp32; A(mid) > target ? lo = mid : hi = mid;
+ *   after n_steps the answer is hi.
+ * L_TH: mid = lo + (hi - lo) / 2; while lo < hi: A(mid) > target ? lo = mid + 1
+ *   : hi = mid; later steps re-evaluate at the answer hi.
+ * The caller guarantees A(hi) <= target at entry (e.g. hi = longest prompt + 1
+ * for L_TH). */
+typedef struct disco_search_spec {
+    int32_t which_param;
+    int32_t which_acc;
+    int32_t n_steps;      /* 1 .. DISCO_MAX_STEPS */
+    int32_t reserved;
+    double lo, hi;
+    double target;
+} disco_search_spec;
+
+/* Result of one search, device memory. */
+typedef struct disco_search_out {
+    double param;                         /* the answer (hi) */
+    double acc_at_param;                  /* accumulator re-evaluated at the answer */
+    double lo, hi;                        /* final bracket */
+    double hist_param[DISCO_MAX_STEPS];   /* midpoint tried at each step */
+    double hist_acc[DISCO_MAX_STEPS];     /* accumulator at that midpoint */
+    disco_accum at_param;                 /* dispatch totals at the answer */
+} disco_search_out;
+
+/* Run n_search independent searches over the same trace; every step is one
+ * fused dispatch-and-reduce pass that evaluates all searches' midpoints, and
+ * the brackets are updated on the device, so there is no host round trip
+ * between steps.  All searches must have the same n_steps.
+ * templ, spec: host, n_search entries.  out: device, n_search entries.
+ * pol_out: device, n_search entries (nullable): the template with the found
+ * parameter, ready to be copied into a policy table.
+ * Asynchronous.  Errors: NULL, SHAPE (n_search outside [1, DISCO_MAX_COLS],
+ * n_steps out of range or unequal), RANGE (unknown selector, lo > hi),
+ * WORKSPACE, HIP. */
+int32_t disco_budget_search(const disco_trace* trace /*host*/, const disco_cost_params* cost /*host*/,
+                            const disco_policy* templ /*host*/, const disco_search_spec* spec /*host*/,
+                            int32_t n_search, disco_search_out* out /*device*/,
+                            disco_policy* pol_out /*device, nullable*/,
+                            void* ws /*device*/, size_t ws_bytes, void* stream);
+
+/* ---- helpers ------------------------------------------------------------ */
+
+/* Bytes of device workspace that any call above needs for n_req requests and
+ * P columns (or searches).  The workspace holds partial results only; its
+ * contents need not be preserved between calls, and calls that share one
+ * workspace must not overlap in time. */
+size_t disco_workspace_bytes(int64_t n_req, int32_t P);
+
+const char* disco_strerror(int32_t code);
+const char* disco_last_hip_error(void);   /* text of the last HIP failure seen by this thread */
+int32_t disco_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISCO_H */

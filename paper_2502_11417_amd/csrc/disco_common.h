@@ -1,0 +1,36 @@
+// Host-side helpers of libdisco: HIP error capture and workspace layout.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+#include "disco.h"
+
+void disco_set_hip_error(hipError_t e, const char* what);
+
+#define DISCO_HIP(expr)                                   \
+    do {                                                  \
+        hipError_t e_ = (expr);                           \
+        if (e_ != hipSuccess) {                           \
+            disco_set_hip_error(e_, #expr);               \
+            return DISCO_ERR_HIP;                         \
+        }                                                 \
+    } while (0)
+
+// Launch geometry shared by the streaming kernels.
+enum {
+    DISCO_BLOCK = 256,           // threads per workgroup (4 waves)
+    DISCO_MAX_BLOCKS = 2048,     // upper bound of workgroups per launch (8 per CU on 256 CUs)
+    DISCO_MAX_SLOTS = 128,       // (columns x quantiles) selected together
+};
+
+// Workspace carve-up.  Every region is 256-byte aligned.
+struct WsLayout {
+    size_t pol;        // disco_policy[64]
+    size_t ticket;     // unsigned[64] counters (zeroed by the library before use)
+    size_t search;     // SearchState[64]
+    size_t sel;        // select state (globals + slots)
+    size_t ghist;      // unsigned[DISCO_MAX_SLOTS][256]
+    size_t part;       // per-workgroup partials
+    size_t total;
+};
+WsLayout disco_ws_layout(int32_t P);

@@ -1,0 +1,105 @@
+// Device-side building blocks shared by the kernels of libdisco (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "disco.h"
+
+typedef uint64_t u64;
+typedef int64_t i64;
+
+// Read-only view of a trace batch as the kernels see it.
+struct TraceView {
+    i64 n_req;
+    const int32_t* l;      // prompt_len
+    const int32_t* n;      // output_len
+    const float* s;        // srv_ttft
+    const float* tbt;      // srv_tbt (constant gap) or nullptr
+    const float* k;        // dev_pre_spt or nullptr
+    const float* g;        // dev_dec_spt or nullptr
+    const i64* off;        // tok_off or nullptr
+    const float* arr;      // tok_arr or nullptr
+    float k_s, g_s, c;
+};
+
+__device__ __forceinline__ unsigned f2u(float x) { return __float_as_uint(x); }
+__device__ __forceinline__ float u2f(unsigned x) { return __uint_as_float(x); }
+
+// ---------------------------------------------------------------------------
+// Dispatch of one (request, column) pair: Sec. 4.2, Alg. 2 (wait time) and
+// Alg. 3 (length threshold).  Both modes are evaluated branch-free so that
+// lanes holding different columns stay converged.
+//   decision bit0 = server started, bit1 = device started, bit2 = device won.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void dispatch_pair(const disco_policy& p, int l, float s, float d,
+                                              unsigned& decision, float& ttft)
+{
+    // device-constrained wait (Eq. 1 united with Alg. 2's step map)
+    float ramp = p.beta * (float)l;
+    float w = (ramp < p.w_tail) ? ramp : p.w_tail;     // a NaN ramp falls through to w_tail
+    w = (l == p.l_mid) ? p.w_mid : w;
+    w = (l <= p.l_th) ? 0.0f : w;
+    bool d_started = s > w;                             // strict: a server token at exactly w cancels the device
+    float x = w + d;
+    bool d_win = d_started && (x < s);                  // ties go to the server
+    unsigned d_dec = 1u | (d_started ? 2u : 0u) | (d_win ? 4u : 0u);
+    float d_ttft = d_win ? x : s;
+    // server-constrained threshold (Alg. 3: strict l < l_th runs on the device alone)
+    bool dev_only = l < p.l_th;
+    bool s_win = dev_only || (d < s);
+    unsigned s_dec = dev_only ? 6u : (s_win ? 7u : 3u);
+    float s_ttft = s_win ? d : s;
+    bool srv_mode = (p.mode == DISCO_MODE_SERVER_CONSTRAINED);
+    decision = srv_mode ? s_dec : d_dec;
+    ttft = srv_mode ? s_ttft : d_ttft;
+}
+
+// ---------------------------------------------------------------------------
+// Wave-level helpers (64 lanes).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_incl_max(float v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        float o = __shfl_up(v, d, 64);
+        if (lane >= d) v = fmaxf(v, o);
+    }
+    return v;
+}
+
+__device__ __forceinline__ float bcast_f(float v, int src_lane)
+{
+    return u2f((unsigned)__builtin_amdgcn_readlane((int)f2u(v), src_lane));
+}
+__device__ __forceinline__ int bcast_i(int v, int src_lane)
+{
+    return __builtin_amdgcn_readlane(v, src_lane);
+}
+
+__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m)
+{
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+    lo = (unsigned)__shfl_xor((int)lo, m, 64);
+    hi = (unsigned)__shfl_xor((int)hi, m, 64);
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ double shfl_xor_f64(double v, int m)
+{
+    return __longlong_as_double((long long)shfl_xor_u64((u64)__double_as_longlong(v), m));
+}
+
+// ---------------------------------------------------------------------------
+// Unified cost (Sec. 4.1, App. E): written one fp64 operation at a time, in
+// the order server = a + b, energy = c + d, total = server + lambda * energy.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double server_cost_of(const disco_cost_params& c, i64 s_pre, i64 s_dec)
+{
+    double a = c.cs_pre * (double)s_pre;
+    double b = c.cs_dec * (double)s_dec;
+    return a + b;
+}
+__device__ __forceinline__ double device_energy_of(const disco_cost_params& c, i64 d_pre, i64 d_dec)
+{
+    double a = c.e_pre * (double)d_pre;
+    double b = c.e_dec * (double)d_dec;
+    return a + b;
+}

@@ -1,0 +1,1111 @@
+// Evaluation kernels and entry points of libdisco: dispatch, token timelines
+// with lag-triggered migration, order-statistic selection, budget search.
+//
+// Work decomposition
+//   dispatch-type passes: a wave holds up to 64 policy columns in its lanes
+//     (lane = sub * G + column, G = columns rounded up to a power of two) and
+//     walks the requests in batches of 64; the batch is loaded coalesced, one
+//     request per lane, and handed to the column lanes with lane broadcasts.
+//     Per-column totals stay in registers until the end of the kernel.
+//   timeline passes: one wave per request, one token per lane, 64-token
+//     chunks with a carried running maximum; the per-request scalars of each
+//     column are accumulated by lane = column.
+//   every pass ends in the workgroup that takes the last ticket: it folds the
+//     per-workgroup partials in a fixed order (bit-reproducible sums) and, for
+//     select and search passes, advances the device-resident state, so a
+//     sequence of passes needs no host round trip.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "disco_common.h"
+#include "disco_device.h"
+
+namespace {
+
+// ------------------------------------------------------------------ state --
+
+struct PolTable { disco_policy p[DISCO_MAX_COLS]; };
+
+struct SearchState {
+    double lo, hi, target;
+    int32_t which_param, which_acc, step, n_steps;
+};
+struct SpecTable { SearchState s[DISCO_MAX_COLS]; };
+
+struct SelGlobal { unsigned minb, maxb; int nb; int pad; };       // key = bits - minb, nb significant bits
+struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
+struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; };   // [0] TTFT, [1] TBT
+
+struct DispPartial { u64 s_pre, d_pre, d_dec, n_tot, started, won; double ttft_sum; unsigned minb, maxb; };
+struct MigPartial { u64 s_dec, d_dec, d_repre, migrated, tbt_count; double tlast_sum; unsigned minb, maxb; u64 pad; };
+static_assert(sizeof(DispPartial) == 64 && sizeof(MigPartial) == 64, "partials are 64 bytes");
+static_assert(sizeof(disco_accum) == 128 && sizeof(disco_stats) == 256 && sizeof(disco_policy) == 32, "ABI sizes");
+
+struct DispFin {
+    int kind;                     // 0: write disco_accum, 1: advance a search
+    disco_accum* acc;
+    disco_cost_params cost;
+    SearchState* st;
+    disco_search_out* sout;
+    disco_policy* pol_out;
+    disco_policy* pol_rw;         // the table the next pass reads
+};
+
+__global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets)
+{
+    int i = threadIdx.x;
+    if (i < P) dst[i] = t.p[i];
+    if (i < 64) tickets[i] = 0u;
+}
+
+// Last-ticket test: true in every thread of the workgroup that finishes last.
+__device__ __forceinline__ bool take_last_ticket(unsigned* ticket)
+{
+    __shared__ int is_last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned t = atomicAdd(ticket, 1u);
+        is_last = (t == gridDim.x - 1);
+    }
+    __syncthreads();
+    bool last = is_last != 0;
+    if (last) __threadfence();
+    return last;
+}
+
+__device__ __forceinline__ double acc_value(int which, const disco_cost_params& c, i64 s_pre, i64 s_dec, i64 d_pre,
+                                            i64 d_dec)
+{
+    switch (which) {
+    case DISCO_ACC_TOTAL_COST: {
+        double server = server_cost_of(c, s_pre, s_dec);
+        double energy = device_energy_of(c, d_pre, d_dec);
+        double priced = c.lambda * energy;
+        return server + priced;
+    }
+    case DISCO_ACC_SERVER_COST: return server_cost_of(c, s_pre, s_dec);
+    case DISCO_ACC_DEVICE_COST: {
+        double energy = device_energy_of(c, d_pre, d_dec);
+        return c.lambda * energy;
+    }
+    case DISCO_ACC_SERVER_PREFILL_TOK: return (double)s_pre;
+    default: return (double)d_pre;
+    }
+}
+
+// Bisection step or final evaluation of search `col` (Sec. 4.2: find the
+// threshold / wait that meets the constrained endpoint's budget).
+__device__ void search_advance(int col, const DispFin& fin, i64 s_pre, i64 s_dec, i64 d_pre, i64 d_dec, i64 started,
+                               i64 won, double ttft_sum, unsigned minb, unsigned maxb)
+{
+    SearchState st = fin.st[col];
+    disco_policy p = fin.pol_rw[col];
+    double A = acc_value(st.which_acc, fin.cost, s_pre, s_dec, d_pre, d_dec);
+    bool is_w = st.which_param == DISCO_PARAM_W_TAIL;
+    if (st.step < st.n_steps) {
+        double mid = is_w ? (double)p.w_tail : (double)p.l_th;
+        fin.sout[col].hist_param[st.step] = mid;
+        fin.sout[col].hist_acc[st.step] = A;
+        if (is_w) {
+            if (A > st.target) st.lo = mid; else st.hi = mid;
+        } else if (st.lo < st.hi) {
+            if (A > st.target) st.lo = mid + 1.0; else st.hi = mid;
+        }
+        st.step += 1;
+        if (is_w) {
+            float next = (st.step < st.n_steps) ? 0.5f * ((float)st.lo + (float)st.hi) : (float)st.hi;
+            p.w_tail = next;
+        } else {
+            int lo = (int)st.lo, hi = (int)st.hi;
+            p.l_th = (st.step < st.n_steps) ? lo + (hi - lo) / 2 : hi;
+        }
+        fin.st[col] = st;
+        fin.pol_rw[col] = p;
+    } else {
+        disco_search_out* o = &fin.sout[col];
+        o->param = st.hi;
+        o->acc_at_param = A;
+        o->lo = st.lo;
+        o->hi = st.hi;
+        disco_accum a;
+        memset(&a, 0, sizeof(a));
+        a.s_pre = s_pre; a.s_dec = s_dec; a.d_pre = d_pre; a.d_dec = d_dec;
+        a.n_dev_started = started; a.n_dev_win = won; a.ttft_sum = ttft_sum;
+        a.ttft_min_bits = minb; a.ttft_max_bits = maxb;
+        o->at_param = a;
+        if (fin.pol_out) fin.pol_out[col] = p;
+    }
+}
+
+// --------------------------------------------------------------- dispatch --
+
+template <int G>
+__device__ __forceinline__ void fetch(int& l, float& s, int& n, float& d, int lv, float sv, int nv, float dv, int src)
+{
+    if (G == 64) {            // the whole wave looks at one request: scalar broadcast
+        l = bcast_i(lv, src); s = bcast_f(sv, src); n = bcast_i(nv, src); d = bcast_f(dv, src);
+    } else if (G == 1) {      // every lane keeps its own request
+        l = lv; s = sv; n = nv; d = dv;
+    } else {
+        l = __shfl(lv, src, 64); s = __shfl(sv, src, 64); n = __shfl(nv, src, 64); d = __shfl(dv, src, 64);
+    }
+}
+
+// Fused dispatch + per-column reduction (Sec. 4.2; token accounting of the
+// budget definitions: a started endpoint is charged the prompt, the winner
+// the output tokens).  part: [gridDim.x][G].
+template <int G>
+__global__ __launch_bounds__(DISCO_BLOCK) void k_dispatch_acc(TraceView tr, const disco_policy* __restrict__ pol, int P,
+                                                              DispPartial* __restrict__ part, unsigned* ticket,
+                                                              DispFin fin)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & (G - 1), sub = lane / G;
+    const bool colv = col < P;
+    const disco_policy p = pol[colv ? col : 0];
+    u64 s_pre = 0, d_pre = 0, d_dec = 0, n_tot = 0, started = 0, won = 0;
+    double ttft_sum = 0.0;
+    unsigned minb = 0xFFFFFFFFu, maxb = 0u;
+    const i64 nbatch = (tr.n_req + 63) >> 6;
+    for (i64 b = (i64)blockIdx.x * (DISCO_BLOCK / 64) + wave; b < nbatch; b += (i64)gridDim.x * (DISCO_BLOCK / 64)) {
+        const i64 i = b * 64 + lane;
+        const bool v = i < tr.n_req;
+        int lv = v ? tr.l[i] : 0;
+        int nv = v ? tr.n[i] : 0;
+        float sv = v ? tr.s[i] : 0.0f;
+        float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
+        float dv = __fmaf_rn((float)lv, kv, tr.c);          // device TTFT T_d(l) = k l + c
+        const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
+        for (int it = 0; it < G; ++it) {
+            const int src = sub * G + it;
+            if (G == 64 && src >= cnt) break;
+            int l, n; float s, d;
+            fetch<G>(l, s, n, d, lv, sv, nv, dv, src);
+            unsigned dec; float ttft;
+            dispatch_pair(p, l, s, d, dec, ttft);
+            if (src < cnt) {
+                s_pre += (dec & 1u) ? (u64)l : 0ull;
+                d_pre += (dec & 2u) ? (u64)l : 0ull;
+                d_dec += (dec & 4u) ? (u64)n : 0ull;
+                n_tot += (u64)n;
+                started += (dec >> 1) & 1u;
+                won += (dec >> 2) & 1u;
+                ttft_sum += (double)ttft;
+                unsigned tb = f2u(ttft);
+                minb = min(minb, tb); maxb = max(maxb, tb);
+            }
+        }
+    }
+    // fold the request sub-groups of the wave, then the waves of the workgroup
+#pragma unroll
+    for (int m = G; m < 64; m <<= 1) {
+        s_pre += shfl_xor_u64(s_pre, m); d_pre += shfl_xor_u64(d_pre, m); d_dec += shfl_xor_u64(d_dec, m);
+        n_tot += shfl_xor_u64(n_tot, m); started += shfl_xor_u64(started, m); won += shfl_xor_u64(won, m);
+        ttft_sum += shfl_xor_f64(ttft_sum, m);
+        minb = min(minb, (unsigned)__shfl_xor((int)minb, m, 64));
+        maxb = max(maxb, (unsigned)__shfl_xor((int)maxb, m, 64));
+    }
+    __shared__ DispPartial sh[DISCO_BLOCK / 64][G];
+    if (sub == 0) sh[wave][col] = DispPartial{s_pre, d_pre, d_dec, n_tot, started, won, ttft_sum, minb, maxb};
+    __syncthreads();
+    if (threadIdx.x < G) {
+        DispPartial a = sh[0][threadIdx.x];
+        for (int w = 1; w < DISCO_BLOCK / 64; ++w) {
+            const DispPartial& o = sh[w][threadIdx.x];
+            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
+            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
+            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
+        }
+        part[(size_t)blockIdx.x * G + threadIdx.x] = a;
+    }
+    if (!take_last_ticket(ticket)) return;
+    // last workgroup: fixed-order fold over workgroups, Q threads per column
+    constexpr int Q = DISCO_BLOCK / G;
+    __shared__ DispPartial fold[Q][G];
+    {
+        const int c = threadIdx.x % G, q = threadIdx.x / G;
+        DispPartial a{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+        for (unsigned b = q; b < gridDim.x; b += Q) {
+            const DispPartial o = part[(size_t)b * G + c];
+            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
+            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
+            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
+        }
+        fold[q][c] = a;
+    }
+    __syncthreads();
+    if (threadIdx.x < P) {
+        const int c = threadIdx.x;
+        DispPartial a = fold[0][c];
+        for (int q = 1; q < Q; ++q) {
+            const DispPartial& o = fold[q][c];
+            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
+            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
+            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
+        }
+        const i64 s_dec = (i64)(a.n_tot - a.d_dec);
+        if (fin.kind == 0) {
+            disco_accum* o = &fin.acc[c];
+            o->s_pre = (i64)a.s_pre; o->s_dec = s_dec; o->d_pre = (i64)a.d_pre; o->d_dec = (i64)a.d_dec;
+            o->n_dev_started = (i64)a.started; o->n_dev_win = (i64)a.won; o->ttft_sum = a.ttft_sum;
+            o->ttft_min_bits = a.minb; o->ttft_max_bits = a.maxb;
+        } else {
+            search_advance(c, fin, (i64)a.s_pre, s_dec, (i64)a.d_pre, (i64)a.d_dec, (i64)a.started, (i64)a.won,
+                           a.ttft_sum, a.minb, a.maxb);
+        }
+    }
+    if (threadIdx.x == 0) *ticket = 0u;
+}
+
+// Materialised per-pair outputs, lane = request so that every column is
+// written coalesced.
+__global__ __launch_bounds__(DISCO_BLOCK) void k_dispatch_mat(TraceView tr, const disco_policy* __restrict__ pol, int P,
+                                                              uint8_t* __restrict__ decision, float* __restrict__ ttft)
+{
+    __shared__ disco_policy sp[DISCO_MAX_COLS];
+    if (threadIdx.x < P) sp[threadIdx.x] = pol[threadIdx.x];
+    __syncthreads();
+    for (i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x; i < tr.n_req; i += (i64)gridDim.x * blockDim.x) {
+        int l = tr.l[i];
+        float s = tr.s[i];
+        float k = tr.k ? tr.k[i] : tr.k_s;
+        float d = __fmaf_rn((float)l, k, tr.c);
+        for (int j = 0; j < P; ++j) {
+            unsigned dec; float t;
+            dispatch_pair(sp[j], l, s, d, dec, t);
+            if (decision) decision[(size_t)j * tr.n_req + i] = (uint8_t)dec;
+            if (ttft) ttft[(size_t)j * tr.n_req + i] = t;
+        }
+    }
+}
+
+// ----------------------------------------------------------------- select --
+// Exact order statistics by most-significant-digit-first radix histograms over
+// key = bits(value) - min_bits (non-negative floats order like their bit
+// patterns), 8 bits per pass, nb = bit length of (max_bits - min_bits).
+
+__device__ __forceinline__ void digit_of_pass(int nb, int pass, int& shift, int& width)
+{
+    int hi = nb - 8 * pass;               // bits still undecided before this pass
+    width = hi < 0 ? 0 : (hi < 8 ? hi : 8);
+    shift = hi - width;
+}
+
+// One thread per slot: rank from (num, den, M), empty prefix.
+__global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quantile q0, disco_quantile q1,
+                              disco_quantile q2, disco_quantile q3, const disco_accum* acc, i64 n_req,
+                              unsigned* ghist)
+{
+    const disco_quantile qs[4] = {q0, q1, q2, q3};
+    __shared__ unsigned smin, smax;
+    if (threadIdx.x == 0) { smin = 0xFFFFFFFFu; smax = 0u; }
+    __syncthreads();
+    if ((int)threadIdx.x < P) {
+        unsigned a = which ? acc[threadIdx.x].tbt_min_bits : acc[threadIdx.x].ttft_min_bits;
+        unsigned b = which ? acc[threadIdx.x].tbt_max_bits : acc[threadIdx.x].ttft_max_bits;
+        atomicMin(&smin, a); atomicMax(&smax, b);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        SelGlobal g;
+        g.minb = smin <= smax ? smin : 0u;
+        g.maxb = smin <= smax ? smax : 0u;
+        unsigned range = g.maxb - g.minb;
+        g.nb = range ? 32 - __clz(range) : 0;
+        g.pad = 0;
+        S->g[which] = g;
+    }
+    for (int s = threadIdx.x; s < P * nq; s += blockDim.x) {
+        int c = s / nq, qi = s % nq;
+        i64 M = which ? acc[c].tbt_count : n_req;
+        SelSlot sl;
+        sl.M = M;
+        i64 k = M > 0 ? ((i64)qs[qi].num * M + qs[qi].den - 1) / qs[qi].den : 0;
+        if (M > 0 && k < 1) k = 1;
+        if (k > M) k = M;
+        sl.rank = k; sl.k_rem = k; sl.prefix = 0u; sl.done = (M <= 0);
+        S->slot[which][s] = sl;
+    }
+    for (int i = threadIdx.x; i < DISCO_MAX_SLOTS * 256; i += blockDim.x) ghist[i] = 0u;
+}
+
+// After a histogram pass: walk the 256 bins of every slot to the digit that
+// holds the remaining rank, extend the prefix, clear the bins.
+__device__ void select_advance(SelState* S, int which, int pass, int P, int nq, unsigned* ghist)
+{
+    const SelGlobal g = S->g[which];
+    int shift, width;
+    digit_of_pass(g.nb, pass, shift, width);
+    __syncthreads();
+    for (int s = threadIdx.x; s < P * nq; s += blockDim.x) {
+        SelSlot sl = S->slot[which][s];
+        if (!sl.done && width > 0) {
+            const unsigned* h = ghist + (size_t)((pass == 0) ? (s / nq) * nq : s) * 256;
+            i64 k = sl.k_rem;
+            int dsel = (1 << width) - 1;
+            for (int dgt = 0; dgt < (1 << width); ++dgt) {
+                i64 cnt = h[dgt];
+                if (k <= cnt) { dsel = dgt; break; }
+                k -= cnt;
+            }
+            sl.k_rem = k;
+            sl.prefix = (sl.prefix << width) | (unsigned)dsel;
+            S->slot[which][s] = sl;
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < P * nq * 256; i += blockDim.x) ghist[i] = 0u;
+}
+
+// TTFT histogram pass: same traversal as k_dispatch_acc; each pair whose key
+// matches the slot's prefix bumps that slot's bin in an LDS histogram.
+template <int G, int SLOTCAP>
+__global__ __launch_bounds__(DISCO_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
+                                                           int pass, SelState* S, unsigned* ghist, unsigned* ticket)
+{
+    __shared__ unsigned hist[SLOTCAP * 256];
+    const SelGlobal g = S->g[0];
+    int shift, width;
+    digit_of_pass(g.nb, pass, shift, width);
+    if (width > 0) {
+        for (int i = threadIdx.x; i < P * nq * 256; i += DISCO_BLOCK) hist[i] = 0u;
+        __syncthreads();
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int col = lane & (G - 1), sub = lane / G;
+        const bool colv = col < P;
+        const disco_policy p = pol[colv ? col : 0];
+        unsigned prefix[DISCO_MAX_Q];
+        bool live[DISCO_MAX_Q];
+#pragma unroll
+        for (int qi = 0; qi < DISCO_MAX_Q; ++qi) {
+            bool on = colv && qi < nq;
+            SelSlot sl = S->slot[0][on ? col * nq + qi : 0];
+            prefix[qi] = sl.prefix;
+            live[qi] = on && !sl.done;
+        }
+        const unsigned dmask = (1u << width) - 1u;
+        const int up = shift + width;          // bits above this digit; up == 32 only when the prefix is empty
+        const i64 nbatch = (tr.n_req + 63) >> 6;
+        for (i64 b = (i64)blockIdx.x * (DISCO_BLOCK / 64) + wave; b < nbatch; b += (i64)gridDim.x * (DISCO_BLOCK / 64)) {
+            const i64 i = b * 64 + lane;
+            const bool v = i < tr.n_req;
+            int lv = v ? tr.l[i] : 0;
+            float sv = v ? tr.s[i] : 0.0f;
+            float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
+            float dv = __fmaf_rn((float)lv, kv, tr.c);
+            const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
+            for (int it = 0; it < G; ++it) {
+                const int src = sub * G + it;
+                if (G == 64 && src >= cnt) break;
+                int l, n; float s, d;
+                fetch<G>(l, s, n, d, lv, sv, 0, dv, src);
+                unsigned dec; float ttft;
+                dispatch_pair(p, l, s, d, dec, ttft);
+                if (src < cnt) {
+                    const unsigned key = f2u(ttft) - g.minb;
+                    const unsigned dgt = (key >> shift) & dmask;
+                    const unsigned hi = (up >= 32) ? 0u : (key >> up);
+                    if (pass == 0) {
+                        if (live[0] || live[1] || live[2] || live[3]) atomicAdd(&hist[(col * nq) * 256 + dgt], 1u);
+                    } else {
+#pragma unroll
+                        for (int qi = 0; qi < DISCO_MAX_Q; ++qi)
+                            if (live[qi] && hi == prefix[qi]) atomicAdd(&hist[(col * nq + qi) * 256 + dgt], 1u);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < P * nq * 256; i += DISCO_BLOCK) {
+            unsigned c = hist[i];
+            if (c) atomicAdd(&ghist[i], c);
+        }
+    }
+    if (!take_last_ticket(ticket)) return;
+    select_advance(S, 0, pass, P, nq, ghist);
+    if (threadIdx.x == 0) *ticket = 0u;
+}
+
+// -------------------------------------------------------------- timelines --
+
+struct TimelineArgs {
+    float tau, kt;            // pacing interval, kappa_lag * tau
+    int P, nq, pass;          // pass < 0: statistics pass, else histogram pass
+    int32_t* mig_idx; int32_t* n_src_tok; float* t_last; float* delivered; int delivered_col;
+    MigPartial* part; unsigned* ticket; disco_accum* acc;
+    SelState* S; unsigned* ghist;
+};
+
+// Paced delivery of one source timeline of one request by one wave
+// (Sec. 4.3; recurrence delta_t = max(r_t, delta_{t-1} + tau) evaluated in
+// the shifted domain, where it is a running maximum).  VARIANT 0: device
+// source (r_t = t g), 1: server source without hand-off, 2: server source
+// with the lag trigger.  On return m and t_last are wave-uniform.
+// `sink(t, tbt_bits, valid)` is called once per 64-token chunk by all lanes.
+template <class Sink>
+__device__ __forceinline__ void run_timeline(int variant, int n, const float* __restrict__ r_src, float gap_src, float g_dev,
+                                             int l, float k, float c, float tau, float kt, int lane, float* deliv,
+                                             int& m_out, float& tlast_out, Sink&& sink)
+{
+    float carryM = -INFINITY, carryD = 0.0f, base = 0.0f;
+    int m = -1;
+    for (int t0 = 0; t0 < n; t0 += 64) {
+        const int t = t0 + lane;
+        const bool v = t < n;
+        float r;
+        if (m >= 0) r = __fmaf_rn((float)(t - m + 1), g_dev, base);
+        else if (variant == 0) r = (float)t * g_dev;
+        else if (r_src) r = v ? r_src[t] : 0.0f;
+        else r = (float)t * gap_src;
+        float u = v ? __fmaf_rn(-(float)t, tau, r) : -INFINITY;
+        float M = fmaxf(wave_incl_max(u, lane), carryM);
+        float del = __fmaf_rn((float)t, tau, M);
+        float prev = __shfl_up(del, 1, 64);
+        if (lane == 0) prev = carryD;
+        if (variant == 2 && m < 0) {
+            float slot = prev + tau;
+            float lag = r - slot;
+            u64 trig = __ballot(v && t >= 1 && lag > kt);
+            if (trig) {
+                const int ml = __ffsll((long long)trig) - 1;       // first overdue token of the chunk
+                m = t0 + ml;
+                // hand-off: decision when the token is kappa tau overdue, then the device
+                // re-prefills prompt + produced tokens and continues at its own pace
+                float slot_m = bcast_f(slot, ml);
+                float t_dec = slot_m + kt;
+                float t_mig = __fmaf_rn((float)(l + m), k, c);
+                base = t_dec + t_mig;
+                if (t >= m) {
+                    r = __fmaf_rn((float)(t - m + 1), g_dev, base);
+                    u = v ? __fmaf_rn(-(float)t, tau, r) : -INFINITY;
+                }
+                M = fmaxf(wave_incl_max(u, lane), carryM);
+                del = __fmaf_rn((float)t, tau, M);
+                prev = __shfl_up(del, 1, 64);
+                if (lane == 0) prev = carryD;
+            }
+        }
+        if (deliv && v) deliv[t] = del;
+        float tbt = del - prev;
+        sink(t, f2u(tbt), v && t >= 1);
+        const int last = (n - t0 < 64) ? (n - t0 - 1) : 63;
+        carryM = bcast_f(M, last);
+        carryD = bcast_f(del, last);
+    }
+    m_out = m;
+    tlast_out = carryD;
+}
+
+// Wave-aggregated histogram update: lanes holding the same bin are counted
+// with a ballot and added once per column, lane = column doing the add.
+__device__ __forceinline__ void hist_add_grouped(unsigned* hist, bool pending, unsigned bin, u64 colmask, int nq, int qi_or_all,
+                                                 int lane)
+{
+    u64 todo = __ballot(pending);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const unsigned b0 = (unsigned)bcast_i((int)bin, leader);
+        const u64 same = __ballot(pending && bin == b0);
+        const unsigned cnt = (unsigned)__popcll(same);
+        if (lane < 64 && ((colmask >> lane) & 1ull)) atomicAdd(&hist[(lane * nq + qi_or_all) * 256 + b0], cnt);
+        todo &= ~same;
+        if ((same >> lane) & 1ull) pending = false;
+    }
+}
+
+template <int SLOTCAP>
+__global__ __launch_bounds__(DISCO_BLOCK) void k_timeline(TraceView tr, const disco_policy* __restrict__ pol, TimelineArgs a)
+{
+    // one LDS buffer: histograms in a histogram pass, partials in the statistics pass
+    constexpr int WORDS = SLOTCAP * 256 > 8192 ? SLOTCAP * 256 : 8192;
+    __shared__ __align__(16) unsigned smem[WORDS];
+    unsigned* hist = smem;
+    __shared__ unsigned sprefix[DISCO_MAX_SLOTS];
+    __shared__ int slive[DISCO_MAX_SLOTS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int P = a.P, nq = a.nq;
+    const bool colv = lane < P;
+    const disco_policy p = pol[colv ? lane : 0];
+    const bool hist_pass = a.pass >= 0;
+    SelGlobal g{0, 0, 0, 0};
+    int shift = 0, width = 0;
+    if (hist_pass) {
+        g = a.S->g[1];
+        digit_of_pass(g.nb, a.pass, shift, width);
+        for (int i = threadIdx.x; i < P * nq * 256; i += DISCO_BLOCK) hist[i] = 0u;
+        for (int i = threadIdx.x; i < P * nq; i += DISCO_BLOCK) {
+            SelSlot sl = a.S->slot[1][i];
+            sprefix[i] = sl.prefix;
+            slive[i] = !sl.done;
+        }
+        __syncthreads();
+    }
+    const unsigned dmask = width ? ((1u << width) - 1u) : 0u;
+    const int up = shift + width;
+    u64 acc_s_dec = 0, acc_d_dec = 0, acc_repre = 0, acc_mig = 0, acc_cnt = 0;
+    double acc_tlast = 0.0;
+    unsigned minb = 0xFFFFFFFFu, maxb = 0u;
+    const bool work = !hist_pass || width > 0;
+    const i64 nwaves = (i64)gridDim.x * (DISCO_BLOCK / 64);
+    for (i64 i = (i64)blockIdx.x * (DISCO_BLOCK / 64) + wave; work && i < tr.n_req; i += nwaves) {
+        const int l = tr.l[i], n = tr.n[i];
+        const float s = tr.s[i];
+        const float k = tr.k ? tr.k[i] : tr.k_s;
+        const float gd = tr.g ? tr.g[i] : tr.g_s;
+        const float d = __fmaf_rn((float)l, k, tr.c);
+        unsigned dec; float ttft;
+        dispatch_pair(p, l, s, d, dec, ttft);
+        const bool dev_src = (dec & 4u) != 0u;
+        const u64 mask_dev = __ballot(colv && dev_src);
+        const u64 mask_plain = __ballot(colv && !dev_src && p.mig_mode != DISCO_MIG_LAG);
+        const u64 mask_lag = __ballot(colv && !dev_src && p.mig_mode == DISCO_MIG_LAG);
+        const i64 off = tr.off ? tr.off[i] : 0;
+        const float* r_src = tr.arr ? tr.arr + off : nullptr;
+        const float gap_src = tr.tbt ? tr.tbt[i] : 0.0f;
+        const bool want_deliv = a.delivered != nullptr && !hist_pass;
+        const u64 dcol = want_deliv ? (1ull << a.delivered_col) : 0ull;
+        int m_lag = -1;
+        float tl_lag = 0.0f;
+        bool lag_done = false;
+        // variants in the order lag, plain, device; a lag run without a trigger is also the plain result
+#pragma unroll 1
+        for (int variant = 2; variant >= 0; --variant) {
+            const u64 mask = variant == 2 ? mask_lag : (variant == 1 ? mask_plain : mask_dev);
+            if (!mask) continue;
+            int m; float tl;
+            const bool reuse = (variant == 1 && lag_done && m_lag < 0 && !hist_pass && !(dcol & mask));
+            if (reuse) { m = -1; tl = tl_lag; }
+            else {
+                float* deliv = (dcol & mask) ? a.delivered + off : nullptr;
+                unsigned lmin = 0xFFFFFFFFu, lmax = 0u;
+                run_timeline(variant, n, r_src, gap_src, gd, l, k, tr.c, a.tau, a.kt, lane, deliv, m, tl,
+                             [&](int t, unsigned bits, bool ok) {
+                                 if (!hist_pass) {
+                                     if (ok) { lmin = min(lmin, bits); lmax = max(lmax, bits); }
+                                 } else {
+                                     const unsigned key = bits - g.minb;
+                                     const unsigned dgt = (key >> shift) & dmask;
+                                     const unsigned hi = (up >= 32) ? 0u : (key >> up);
+                                     if (a.pass == 0) {
+                                         hist_add_grouped(hist, ok, dgt, mask, nq, 0, lane);
+                                     } else {
+                                         for (int qi = 0; qi < nq; ++qi) {
+                                             // columns of this variant whose slot qi still selects and shares the prefix
+                                             u64 cm = mask;
+                                             while (cm) {
+                                                 const int c0 = __ffsll((long long)cm) - 1;
+                                                 const unsigned pf = sprefix[c0 * nq + qi];
+                                                 u64 grp = 0ull;      // columns with the same prefix as c0
+                                                 for (u64 rest = cm; rest;) {
+                                                     const int c1 = __ffsll((long long)rest) - 1;
+                                                     rest &= rest - 1;
+                                                     if (sprefix[c1 * nq + qi] == pf && slive[c1 * nq + qi]) grp |= 1ull << c1;
+                                                 }
+                                                 if (grp) hist_add_grouped(hist, ok && hi == pf, dgt, grp, nq, qi, lane);
+                                                 cm &= ~(grp | (1ull << c0));
+                                             }
+                                         }
+                                     }
+                                 }
+                                 (void)t;
+                             });
+                if (!hist_pass) {
+                    // range of the TBT bit patterns of this timeline, folded over the wave
+#pragma unroll
+                    for (int sft = 1; sft < 64; sft <<= 1) {
+                        lmin = min(lmin, (unsigned)__shfl_xor((int)lmin, sft, 64));
+                        lmax = max(lmax, (unsigned)__shfl_xor((int)lmax, sft, 64));
+                    }
+                    if ((mask >> lane) & 1ull) { minb = min(minb, lmin); maxb = max(maxb, lmax); }
+                }
+            }
+            if (variant == 2) { m_lag = m; tl_lag = tl; lag_done = true; }
+            if (!hist_pass && ((mask >> lane) & 1ull)) {
+                const int nsrc = (m >= 0) ? m : n;
+                if (variant == 0) acc_d_dec += (u64)n;
+                else { acc_s_dec += (u64)nsrc; acc_d_dec += (u64)(n - nsrc); }
+                if (m >= 0) { acc_mig += 1; acc_repre += (u64)l + (u64)m; }
+                acc_cnt += (u64)(n - 1);
+                acc_tlast += (double)tl;
+                if (a.mig_idx) a.mig_idx[(size_t)lane * tr.n_req + i] = m;
+                if (a.n_src_tok) a.n_src_tok[(size_t)lane * tr.n_req + i] = nsrc;
+                if (a.t_last) a.t_last[(size_t)lane * tr.n_req + i] = tl;
+            }
+        }
+    }
+    if (hist_pass) {
+        __syncthreads();
+        if (width > 0)
+            for (int i = threadIdx.x; i < P * nq * 256; i += DISCO_BLOCK) {
+                unsigned c = hist[i];
+                if (c) atomicAdd(&a.ghist[i], c);
+            }
+        if (!take_last_ticket(a.ticket)) return;
+        select_advance(a.S, 1, a.pass, P, nq, a.ghist);
+        if (threadIdx.x == 0) *a.ticket = 0u;
+        return;
+    }
+    // statistics pass: fold waves, then workgroups
+    MigPartial (*sh)[64] = reinterpret_cast<MigPartial (*)[64]>(smem);
+    MigPartial (*fold)[64] = sh + DISCO_BLOCK / 64;
+    sh[wave][lane] = MigPartial{acc_s_dec, acc_d_dec, acc_repre, acc_mig, acc_cnt, acc_tlast, minb, maxb, 0};
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        MigPartial x = sh[0][threadIdx.x];
+        for (int w = 1; w < DISCO_BLOCK / 64; ++w) {
+            const MigPartial& o = sh[w][threadIdx.x];
+            x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
+            x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
+            x.minb = min(x.minb, o.minb); x.maxb = max(x.maxb, o.maxb);
+        }
+        a.part[(size_t)blockIdx.x * 64 + threadIdx.x] = x;
+    }
+    if (!take_last_ticket(a.ticket)) return;
+    {
+        const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+        MigPartial x{0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u, 0};
+        for (unsigned b = q; b < gridDim.x; b += DISCO_BLOCK / 64) {
+            const MigPartial o = a.part[(size_t)b * 64 + c];
+            x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
+            x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
+            x.minb = min(x.minb, o.minb); x.maxb = max(x.maxb, o.maxb);
+        }
+        fold[q][c] = x;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < P) {
+        const int c = threadIdx.x;
+        MigPartial x = fold[0][c];
+        for (int q = 1; q < DISCO_BLOCK / 64; ++q) {
+            const MigPartial& o = fold[q][c];
+            x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
+            x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
+            x.minb = min(x.minb, o.minb); x.maxb = max(x.maxb, o.maxb);
+        }
+        disco_accum* o = &a.acc[c];
+        o->m_s_dec = (i64)x.s_dec; o->m_d_dec = (i64)x.d_dec; o->m_d_repre = (i64)x.d_repre;
+        o->n_migrated = (i64)x.migrated; o->tbt_count = (i64)x.tbt_count; o->tlast_sum = x.tlast_sum;
+        o->tbt_min_bits = x.minb; o->tbt_max_bits = x.maxb;
+    }
+    if (threadIdx.x == 0) *a.ticket = 0u;
+}
+
+// ------------------------------------------------------------ final stats --
+
+__global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, int with_tl, const disco_accum* acc,
+                              const SelState* S, disco_stats* out)
+{
+    const int c = threadIdx.x;
+    if (c >= P) return;
+    const disco_accum a = acc[c];
+    disco_stats st;
+    memset(&st, 0, sizeof(st));
+    st.n_req = n_req;
+    st.s_pre = a.s_pre;
+    st.d_pre = a.d_pre + (with_tl ? a.m_d_repre : 0);
+    st.s_dec = with_tl ? a.m_s_dec : a.s_dec;
+    st.d_dec = with_tl ? a.m_d_dec : a.d_dec;
+    st.n_dev_started = a.n_dev_started;
+    st.n_dev_win = a.n_dev_win;
+    st.n_migrated = with_tl ? a.n_migrated : 0;
+    st.tbt_count = with_tl ? a.tbt_count : 0;
+    st.mean_ttft = a.ttft_sum / (double)n_req;                       // 0/0 = NaN for an empty batch
+    st.mean_tbt = with_tl ? a.tlast_sum / (double)a.tbt_count : NAN;  // telescoped sum of gaps
+    st.server_cost = server_cost_of(cost, st.s_pre, st.s_dec);
+    st.device_energy = device_energy_of(cost, st.d_pre, st.d_dec);
+    st.device_cost = cost.lambda * st.device_energy;
+    st.total_cost = st.server_cost + st.device_cost;
+    for (int qi = 0; qi < DISCO_MAX_Q; ++qi) {
+        st.ttft_q[qi] = NAN; st.tbt_q[qi] = NAN;
+        if (qi < nq) {
+            const SelSlot s0 = S->slot[0][c * nq + qi];
+            st.ttft_rank[qi] = s0.rank;
+            if (s0.M > 0) st.ttft_q[qi] = u2f(S->g[0].minb + s0.prefix);
+            if (with_tl) {
+                const SelSlot s1 = S->slot[1][c * nq + qi];
+                st.tbt_rank[qi] = s1.rank;
+                if (s1.M > 0) st.tbt_q[qi] = u2f(S->g[1].minb + s1.prefix);
+            }
+        }
+    }
+    out[c] = st;
+}
+
+// ----------------------------------------------------------- search setup --
+
+__global__ void k_search_init(SpecTable t, int n, SearchState* st, disco_policy* pol)
+{
+    const int c = threadIdx.x;
+    if (c >= n) return;
+    SearchState s = t.s[c];
+    disco_policy p = pol[c];
+    if (s.which_param == DISCO_PARAM_W_TAIL) {
+        s.lo = (double)(float)s.lo; s.hi = (double)(float)s.hi;
+        p.w_tail = 0.5f * ((float)s.lo + (float)s.hi);
+    } else {
+        int lo = (int)s.lo, hi = (int)s.hi;
+        s.lo = lo; s.hi = hi;
+        p.l_th = lo + (hi - lo) / 2;
+    }
+    s.step = 0;
+    st[c] = s;
+    pol[c] = p;
+}
+
+// ------------------------------------------------------------- host side --
+
+thread_local char g_hip_error[256] = "";
+
+TraceView view_of(const disco_trace* t)
+{
+    TraceView v;
+    v.n_req = t->n_req;
+    v.l = t->prompt_len; v.n = t->output_len; v.s = t->srv_ttft; v.tbt = t->srv_tbt;
+    v.k = t->dev_pre_spt; v.g = t->dev_dec_spt;
+    v.off = t->tok_arr ? t->tok_off : nullptr;
+    v.arr = t->tok_arr;
+    v.k_s = t->dev_pre_spt_s; v.g_s = t->dev_dec_spt_s; v.c = t->dev_ttft_c;
+    return v;
+}
+
+int check_trace(const disco_trace* t)
+{
+    if (!t) return DISCO_ERR_NULL;
+    if (t->n_req < 0 || t->n_tok < 0) return DISCO_ERR_SHAPE;
+    if (t->n_req > 0 && (!t->prompt_len || !t->output_len || !t->srv_ttft)) return DISCO_ERR_NULL;
+    if ((t->tok_arr != nullptr) != (t->tok_off != nullptr) && t->tok_arr) return DISCO_ERR_CSR;
+    return DISCO_OK;
+}
+
+int check_policies(const disco_policy* pol, int P)
+{
+    if (!pol) return DISCO_ERR_NULL;
+    if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
+    for (int j = 0; j < P; ++j) {
+        if (pol[j].mode != DISCO_MODE_SERVER_CONSTRAINED && pol[j].mode != DISCO_MODE_DEVICE_CONSTRAINED)
+            return DISCO_ERR_RANGE;
+        if (pol[j].mig_mode != DISCO_MIG_NONE && pol[j].mig_mode != DISCO_MIG_LAG) return DISCO_ERR_RANGE;
+        if (pol[j].w_mid != pol[j].w_mid || pol[j].beta != pol[j].beta || pol[j].w_tail != pol[j].w_tail)
+            return DISCO_ERR_RANGE;
+    }
+    return DISCO_OK;
+}
+
+int check_ws(void* ws, size_t ws_bytes, int P)
+{
+    if (!ws) return DISCO_ERR_WORKSPACE;
+    if (ws_bytes < disco_ws_layout(P).total) return DISCO_ERR_WORKSPACE;
+    if (((uintptr_t)ws & 255u) != 0) return DISCO_ERR_WORKSPACE;
+    return DISCO_OK;
+}
+
+int pow2_cols(int P)
+{
+    int g = 1;
+    while (g < P) g <<= 1;
+    return g;
+}
+
+unsigned dispatch_blocks(i64 n_req)
+{
+    i64 b = (n_req + DISCO_BLOCK - 1) / DISCO_BLOCK;
+    if (b < 1) b = 1;
+    if (b > 1024) b = 1024;
+    return (unsigned)b;
+}
+
+unsigned timeline_blocks(i64 n_req)
+{
+    i64 b = (n_req + 3) / 4;
+    if (b < 1) b = 1;
+    if (b > DISCO_MAX_BLOCKS) b = DISCO_MAX_BLOCKS;
+    return (unsigned)b;
+}
+
+void store_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, hipStream_t stream)
+{
+    PolTable t;
+    memset(&t, 0, sizeof(t));
+    memcpy(t.p, pol, sizeof(disco_policy) * (size_t)P);
+    hipLaunchKernelGGL(k_store_policies, dim3(1), dim3(64), 0, stream, t, P, (disco_policy*)(ws + L.pol),
+                       (unsigned*)(ws + L.ticket));
+}
+
+template <int G>
+void launch_dispatch_acc(const TraceView& v, int P, char* ws, const WsLayout& L, const DispFin& fin, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_dispatch_acc<G>, dim3(dispatch_blocks(v.n_req)), dim3(DISCO_BLOCK), 0, stream, v,
+                       (const disco_policy*)(ws + L.pol), P, (DispPartial*)(ws + L.part), (unsigned*)(ws + L.ticket), fin);
+}
+
+void launch_dispatch_acc_g(int G, const TraceView& v, int P, char* ws, const WsLayout& L, const DispFin& fin,
+                           hipStream_t stream)
+{
+    switch (G) {
+    case 1: launch_dispatch_acc<1>(v, P, ws, L, fin, stream); break;
+    case 2: launch_dispatch_acc<2>(v, P, ws, L, fin, stream); break;
+    case 4: launch_dispatch_acc<4>(v, P, ws, L, fin, stream); break;
+    case 8: launch_dispatch_acc<8>(v, P, ws, L, fin, stream); break;
+    case 16: launch_dispatch_acc<16>(v, P, ws, L, fin, stream); break;
+    case 32: launch_dispatch_acc<32>(v, P, ws, L, fin, stream); break;
+    default: launch_dispatch_acc<64>(v, P, ws, L, fin, stream); break;
+    }
+}
+
+template <int G>
+void launch_ttft_hist(const TraceView& v, int P, int nq, int pass, char* ws, const WsLayout& L, hipStream_t stream)
+{
+    const int slots = P * nq;
+    dim3 grid(dispatch_blocks(v.n_req)), block(DISCO_BLOCK);
+    const disco_policy* pol = (const disco_policy*)(ws + L.pol);
+    SelState* S = (SelState*)(ws + L.sel);
+    unsigned* gh = (unsigned*)(ws + L.ghist);
+    unsigned* tk = (unsigned*)(ws + L.ticket);
+    if (slots <= 8) hipLaunchKernelGGL((k_ttft_hist<G, 8>), grid, block, 0, stream, v, pol, P, nq, pass, S, gh, tk);
+    else if (slots <= 32) hipLaunchKernelGGL((k_ttft_hist<G, 32>), grid, block, 0, stream, v, pol, P, nq, pass, S, gh, tk);
+    else hipLaunchKernelGGL((k_ttft_hist<G, DISCO_MAX_SLOTS>), grid, block, 0, stream, v, pol, P, nq, pass, S, gh, tk);
+}
+
+void launch_ttft_hist_g(int G, const TraceView& v, int P, int nq, int pass, char* ws, const WsLayout& L, hipStream_t stream)
+{
+    switch (G) {
+    case 1: launch_ttft_hist<1>(v, P, nq, pass, ws, L, stream); break;
+    case 2: launch_ttft_hist<2>(v, P, nq, pass, ws, L, stream); break;
+    case 4: launch_ttft_hist<4>(v, P, nq, pass, ws, L, stream); break;
+    case 8: launch_ttft_hist<8>(v, P, nq, pass, ws, L, stream); break;
+    case 16: launch_ttft_hist<16>(v, P, nq, pass, ws, L, stream); break;
+    case 32: launch_ttft_hist<32>(v, P, nq, pass, ws, L, stream); break;
+    default: launch_ttft_hist<64>(v, P, nq, pass, ws, L, stream); break;
+    }
+}
+
+void launch_timeline(const TraceView& v, const TimelineArgs& a, char* ws, const WsLayout& L, hipStream_t stream)
+{
+    dim3 grid(timeline_blocks(v.n_req)), block(DISCO_BLOCK);
+    const disco_policy* pol = (const disco_policy*)(ws + L.pol);
+    const int slots = a.pass >= 0 ? a.P * a.nq : 1;
+    if (slots <= 8) hipLaunchKernelGGL((k_timeline<8>), grid, block, 0, stream, v, pol, a);
+    else if (slots <= 32) hipLaunchKernelGGL((k_timeline<32>), grid, block, 0, stream, v, pol, a);
+    else hipLaunchKernelGGL((k_timeline<DISCO_MAX_SLOTS>), grid, block, 0, stream, v, pol, a);
+}
+
+}  // namespace
+
+void disco_set_hip_error(hipError_t e, const char* what)
+{
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+}
+
+WsLayout disco_ws_layout(int32_t P)
+{
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    WsLayout L;
+    size_t o = 0;
+    L.pol = o; o += up(sizeof(disco_policy) * DISCO_MAX_COLS);
+    L.ticket = o; o += up(sizeof(unsigned) * 64);
+    L.search = o; o += up(sizeof(SearchState) * DISCO_MAX_COLS);
+    L.sel = o; o += up(sizeof(SelState));
+    L.ghist = o; o += up(sizeof(unsigned) * DISCO_MAX_SLOTS * 256);
+    L.part = o;
+    (void)P;
+    o += up((size_t)DISCO_MAX_BLOCKS * 64 * 64);     // workgroups x columns x 64-byte partial
+    L.total = o;
+    return L;
+}
+
+extern "C" size_t disco_workspace_bytes(int64_t n_req, int32_t P)
+{
+    (void)n_req;
+    return disco_ws_layout(P).total;
+}
+
+extern "C" const char* disco_strerror(int32_t code)
+{
+    switch (code) {
+    case DISCO_OK: return "ok";
+    case DISCO_ERR_NULL: return "a required pointer is NULL";
+    case DISCO_ERR_SHAPE: return "negative or inconsistent sizes";
+    case DISCO_ERR_RANGE: return "parameter out of range";
+    case DISCO_ERR_CSR: return "token arrays missing or inconsistent";
+    case DISCO_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case DISCO_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error code";
+    }
+}
+
+extern "C" const char* disco_last_hip_error(void) { return g_hip_error; }
+extern "C" int32_t disco_version(void) { return 100; }
+
+extern "C" int32_t disco_eval_dispatch(const disco_trace* trace, const disco_policy* pol, int32_t P,
+                                       const disco_pair_out* out, disco_accum* acc, void* ws_, size_t ws_bytes,
+                                       void* stream_)
+{
+    int rc = check_trace(trace);
+    if (rc) return rc;
+    rc = check_policies(pol, P);
+    if (rc) return rc;
+    if (!acc) return DISCO_ERR_NULL;
+    rc = check_ws(ws_, ws_bytes, P);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)ws_;
+    const WsLayout L = disco_ws_layout(P);
+    const TraceView v = view_of(trace);
+    store_policies(pol, P, ws, L, stream);
+    DispFin fin;
+    memset(&fin, 0, sizeof(fin));
+    fin.kind = 0;
+    fin.acc = acc;
+    launch_dispatch_acc_g(pow2_cols(P), v, P, ws, L, fin, stream);
+    if (out && (out->decision || out->ttft) && v.n_req > 0) {
+        hipLaunchKernelGGL(k_dispatch_mat, dim3(dispatch_blocks(v.n_req)), dim3(DISCO_BLOCK), 0, stream, v,
+                           (const disco_policy*)(ws + L.pol), P, out->decision, out->ttft);
+    }
+    DISCO_HIP(hipGetLastError());
+    return DISCO_OK;
+}
+
+extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_timeline_params* tl,
+                                        const disco_policy* pol, int32_t P, const disco_mig_out* out,
+                                        disco_accum* acc, void* ws_, size_t ws_bytes, void* stream_)
+{
+    int rc = check_trace(trace);
+    if (rc) return rc;
+    if (!tl) return DISCO_ERR_NULL;
+    rc = check_policies(pol, P);
+    if (rc) return rc;
+    if (!acc) return DISCO_ERR_NULL;
+    if (!(tl->tau > 0.0f) || !(tl->kappa_lag >= 0.0f)) return DISCO_ERR_RANGE;
+    if (trace->n_req > 0 && !trace->tok_arr && !trace->srv_tbt) return DISCO_ERR_CSR;
+    if (out && out->delivered && (!trace->tok_off || out->delivered_col < 0 || out->delivered_col >= P))
+        return DISCO_ERR_CSR;
+    rc = check_ws(ws_, ws_bytes, P);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)ws_;
+    const WsLayout L = disco_ws_layout(P);
+    TraceView v = view_of(trace);
+    if (out && out->delivered) v.off = trace->tok_off;      // offsets index `delivered` even without tok_arr
+    store_policies(pol, P, ws, L, stream);
+    TimelineArgs a;
+    memset(&a, 0, sizeof(a));
+    a.tau = tl->tau;
+    a.kt = tl->kappa_lag * tl->tau;
+    a.P = P; a.nq = 1; a.pass = -1;
+    if (out) {
+        a.mig_idx = out->mig_idx; a.n_src_tok = out->n_src_tok; a.t_last = out->t_last;
+        a.delivered = out->delivered; a.delivered_col = out->delivered_col;
+    }
+    a.part = (MigPartial*)(ws + L.part);
+    a.ticket = (unsigned*)(ws + L.ticket);
+    a.acc = acc;
+    a.S = (SelState*)(ws + L.sel);
+    a.ghist = (unsigned*)(ws + L.ghist);
+    launch_timeline(v, a, ws, L, stream);
+    DISCO_HIP(hipGetLastError());
+    return DISCO_OK;
+}
+
+extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost_params* cost,
+                                      const disco_timeline_params* tl, const disco_policy* pol, int32_t P,
+                                      const disco_accum* acc, const disco_quantile* q, int32_t nq, disco_stats* out,
+                                      void* ws_, size_t ws_bytes, void* stream_)
+{
+    int rc = check_trace(trace);
+    if (rc) return rc;
+    if (!cost || !acc || !out) return DISCO_ERR_NULL;
+    rc = check_policies(pol, P);
+    if (rc) return rc;
+    if (nq < 0 || nq > DISCO_MAX_Q || (nq > 0 && !q)) return nq > 0 && !q ? DISCO_ERR_NULL : DISCO_ERR_SHAPE;
+    if (P * nq > DISCO_MAX_SLOTS) return DISCO_ERR_SHAPE;
+    for (int i = 0; i < nq; ++i)
+        if (q[i].den <= 0 || q[i].num < 0 || q[i].num > q[i].den) return DISCO_ERR_RANGE;
+    if (tl && (!(tl->tau > 0.0f) || !(tl->kappa_lag >= 0.0f))) return DISCO_ERR_RANGE;
+    if (tl && trace->n_req > 0 && !trace->tok_arr && !trace->srv_tbt) return DISCO_ERR_CSR;
+    rc = check_ws(ws_, ws_bytes, P);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)ws_;
+    const WsLayout L = disco_ws_layout(P);
+    const TraceView v = view_of(trace);
+    SelState* S = (SelState*)(ws + L.sel);
+    unsigned* gh = (unsigned*)(ws + L.ghist);
+    store_policies(pol, P, ws, L, stream);
+    disco_quantile qs[4] = {{0, 1}, {0, 1}, {0, 1}, {0, 1}};
+    for (int i = 0; i < nq; ++i) qs[i] = q[i];
+    if (nq > 0) {
+        const int G = pow2_cols(P);
+        hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 0, P, nq, qs[0], qs[1], qs[2], qs[3], acc,
+                           v.n_req, gh);
+        for (int pass = 0; pass < 4; ++pass) launch_ttft_hist_g(G, v, P, nq, pass, ws, L, stream);
+        if (tl) {
+            hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 1, P, nq, qs[0], qs[1], qs[2], qs[3],
+                               acc, v.n_req, gh);
+            TimelineArgs a;
+            memset(&a, 0, sizeof(a));
+            a.tau = tl->tau;
+            a.kt = tl->kappa_lag * tl->tau;
+            a.P = P; a.nq = nq;
+            a.ticket = (unsigned*)(ws + L.ticket);
+            a.S = S; a.ghist = gh;
+            for (int pass = 0; pass < 4; ++pass) {
+                a.pass = pass;
+                launch_timeline(v, a, ws, L, stream);
+            }
+        }
+    }
+    hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, stream, P, nq, v.n_req, *cost, tl ? 1 : 0, acc, S, out);
+    DISCO_HIP(hipGetLastError());
+    return DISCO_OK;
+}
+
+extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cost_params* cost,
+                                       const disco_policy* templ, const disco_search_spec* spec, int32_t n_search,
+                                       disco_search_out* out, disco_policy* pol_out, void* ws_, size_t ws_bytes,
+                                       void* stream_)
+{
+    int rc = check_trace(trace);
+    if (rc) return rc;
+    if (!cost || !spec || !out) return DISCO_ERR_NULL;
+    rc = check_policies(templ, n_search);
+    if (rc) return rc;
+    const int n_steps = spec[0].n_steps;
+    if (n_steps < 1 || n_steps > DISCO_MAX_STEPS) return DISCO_ERR_SHAPE;
+    SpecTable t;
+    memset(&t, 0, sizeof(t));
+    for (int j = 0; j < n_search; ++j) {
+        if (spec[j].n_steps != n_steps) return DISCO_ERR_SHAPE;
+        if (spec[j].which_param != DISCO_PARAM_L_TH && spec[j].which_param != DISCO_PARAM_W_TAIL) return DISCO_ERR_RANGE;
+        if (spec[j].which_acc < DISCO_ACC_TOTAL_COST || spec[j].which_acc > DISCO_ACC_DEVICE_PREFILL_TOK)
+            return DISCO_ERR_RANGE;
+        if (!(spec[j].lo <= spec[j].hi) || spec[j].target != spec[j].target) return DISCO_ERR_RANGE;
+        if (spec[j].which_param == DISCO_PARAM_L_TH && (spec[j].lo < -2147483647.0 || spec[j].hi > 2147483647.0))
+            return DISCO_ERR_RANGE;
+        t.s[j].lo = spec[j].lo; t.s[j].hi = spec[j].hi; t.s[j].target = spec[j].target;
+        t.s[j].which_param = spec[j].which_param; t.s[j].which_acc = spec[j].which_acc;
+        t.s[j].step = 0; t.s[j].n_steps = n_steps;
+    }
+    rc = check_ws(ws_, ws_bytes, n_search);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)ws_;
+    const WsLayout L = disco_ws_layout(n_search);
+    const TraceView v = view_of(trace);
+    store_policies(templ, n_search, ws, L, stream);
+    hipLaunchKernelGGL(k_search_init, dim3(1), dim3(64), 0, stream, t, n_search, (SearchState*)(ws + L.search),
+                       (disco_policy*)(ws + L.pol));
+    DispFin fin;
+    memset(&fin, 0, sizeof(fin));
+    fin.kind = 1;
+    fin.cost = *cost;
+    fin.st = (SearchState*)(ws + L.search);
+    fin.sout = out;
+    fin.pol_out = pol_out;
+    fin.pol_rw = (disco_policy*)(ws + L.pol);
+    const int G = pow2_cols(n_search);
+    for (int step = 0; step <= n_steps; ++step) launch_dispatch_acc_g(G, v, n_search, ws, L, fin, stream);
+    DISCO_HIP(hipGetLastError());
+    return DISCO_OK;
+}

@@ -1,0 +1,77 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function the public header declares, keeps the documented struct sizes,
+and rejects bad arguments before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "disco.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(disco_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported(B):
+    names = declared_functions()
+    assert {"disco_gen_trace", "disco_eval_dispatch", "disco_eval_migration", "disco_reduce_stats",
+            "disco_budget_search"} <= set(names)
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_struct_sizes_match_the_header(B):
+    assert C.sizeof(B.CPolicy) == 32
+    assert B.ACCUM_DTYPE.itemsize == 128 and B.STATS_DTYPE.itemsize == 256
+    assert C.sizeof(B.CTrace) == 96
+    assert B.disco_workspace_bytes(1000, 64) >= 1 << 20
+    assert B._lib.disco_version() >= 100
+
+
+def test_error_strings(B):
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
+        assert len(B._lib.disco_strerror(code)) > 0
+
+
+def test_bad_arguments_are_rejected_on_the_host(B):
+    lib = B._lib
+    tr = B.CTrace()
+    tr.n_req = 0
+    pol = (B.CPolicy * 1)(B.CPolicy(0, 0, -1, 0.0, float("inf"), float("inf"), 0, 0))
+    # null trace / null accumulators / bad column count / missing workspace
+    assert lib.disco_eval_dispatch(None, pol, 1, None, None, None, 0, None) == B.ERR["null"]
+    assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, None, None, 0, None) == B.ERR["null"]
+    assert lib.disco_eval_dispatch(C.byref(tr), pol, 0, None, 8, None, 0, None) == B.ERR["shape"]
+    assert lib.disco_eval_dispatch(C.byref(tr), pol, 65, None, 8, None, 0, None) == B.ERR["shape"]
+    assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, 256, None, 0, None) == B.ERR["workspace"]
+    assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, 256, 256, 16, None) == B.ERR["workspace"]
+    bad = (B.CPolicy * 1)(B.CPolicy(7, 0, -1, 0.0, 1.0, 1.0, 0, 0))
+    assert lib.disco_eval_dispatch(C.byref(tr), bad, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
+    tr.n_req = -1
+    assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, 256, 256, 1 << 30, None) == B.ERR["shape"]
+    tr.n_req = 5          # arrays missing
+    assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, 256, 256, 1 << 30, None) == B.ERR["null"]
+    tr.n_req = 0
+    tl = B.CTimeline(0.0, 3.0)
+    assert lib.disco_eval_migration(C.byref(tr), C.byref(tl), pol, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
+    q = (B.CQuantile * 1)(B.CQuantile(3, 2))
+    cost = B.CCost(1, 1, 1, 1, 1)
+    assert lib.disco_reduce_stats(C.byref(tr), C.byref(cost), None, pol, 1, 256, q, 1, 256, 256, 1 << 30, None) == B.ERR["range"]
+    assert lib.disco_reduce_stats(C.byref(tr), C.byref(cost), None, pol, 1, 256, q, 9, 256, 256, 1 << 30, None) == B.ERR["shape"]
+    spec = (B.CSearchSpec * 1)(B.CSearchSpec(1, 2, 0, 0, 0.0, 5.0, 1.0))
+    assert lib.disco_budget_search(C.byref(tr), C.byref(cost), pol, spec, 1, 256, None, 256, 1 << 30, None) == B.ERR["shape"]
+    spec[0].n_steps = 4
+    spec[0].lo = 6.0
+    assert lib.disco_budget_search(C.byref(tr), C.byref(cost), pol, spec, 1, 256, None, 256, 1 << 30, None) == B.ERR["range"]
+    g = B.CGenParams()
+    assert lib.disco_gen_trace(None, None, 1, None) == B.ERR["null"]
+    g.n_req = -3
+    tr.n_req = -3
+    assert lib.disco_gen_trace(C.byref(g), C.byref(tr), 1, None) == B.ERR["shape"]

@@ -1,0 +1,322 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Bars: decisions, token indices, token totals, selected ranks and every fp32
+time that both sides obtain by the same sequence of IEEE operations are
+compared bit for bit; fp64 sums and costs (whose summation order differs) to
+1e-9 relative, far inside the 1e-5 the method's statement asks for."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import disco_inputs as DI
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-9
+
+
+def both(B, O, specs):
+    """Policy columns for both sides from one list of dicts."""
+    return [B.Policy(**s) for s in specs], [O.Policy(**s) for s in specs]
+
+
+def mixed_policies(lag=False):
+    mg = 1 if lag else 0
+    inf = math.inf
+    return [
+        dict(mode=0, l_th=0, mig_mode=mg),                       # race everything
+        dict(mode=0, l_th=10 ** 9, mig_mode=mg),                 # device only
+        dict(mode=0, l_th=240, mig_mode=mg),
+        dict(mode=0, l_th=1500, mig_mode=0),
+        dict(mode=1, l_th=-1, w_tail=inf, mig_mode=mg),          # server only
+        dict(mode=1, l_th=-1, w_tail=0.0, mig_mode=mg),
+        dict(mode=1, l_th=-1, w_tail=DI.f32(0.35), mig_mode=mg),
+        dict(mode=1, l_th=200, l_mid=201, w_mid=DI.f32(0.1), w_tail=DI.f32(0.6), mig_mode=0),      # Alg. 2 step map
+        dict(mode=1, l_th=100, beta=DI.f32(0.0005), w_tail=DI.f32(0.5), mig_mode=mg),              # Eq. 1 ramp
+    ]
+
+
+def assert_same_bits(a, b, what=""):
+    a = np.ascontiguousarray(a)
+    b = np.ascontiguousarray(b)
+    assert a.shape == b.shape, what
+    if a.dtype.kind == "f":
+        a, b = a.view(np.uint32), b.view(np.uint32)
+    bad = np.flatnonzero(a.ravel() != b.ravel())
+    assert bad.size == 0, f"{what}: {bad.size} mismatches, first at {bad[:5]}"
+
+
+def close(a, b, rel=REL):
+    return abs(a - b) <= rel * max(abs(a), abs(b), 1e-300)
+
+
+# --------------------------------------------------------------- generator
+
+@pytest.mark.parametrize("idx,n_req", [(0, 20_000), (2, 3_001), (3, 20_000), (4, 2_500)])
+def test_gen_trace_is_bit_identical(B, oracle, idx, n_req):
+    cfg = DI.config(idx, n_req=n_req, seed=idx + 3)
+    print(f"gen parity config{idx} n_req={n_req}", flush=True)
+    want = oracle.gen_trace(cfg["gen"])
+    got = B.disco_gen_trace(cfg["gen"])
+    torch.cuda.synchronize()
+    for name in ("prompt_len", "output_len", "srv_ttft", "srv_tbt", "dev_pre_spt", "dev_dec_spt", "tok_off"):
+        assert_same_bits(getattr(got, name).cpu().numpy(), want[name], name)
+    if cfg["gen"]["tokens"]:
+        assert got.n_tok == want["n_tok"]
+        assert_same_bits(got.tok_arr.cpu().numpy(), want["tok_arr"], "tok_arr")
+
+
+def test_gen_trace_empty(B):
+    cfg = DI.config(2, n_req=1)
+    g = dict(cfg["gen"], n_req=0)
+    t = B.disco_gen_trace(g)
+    assert t.n_tok == 0 and t.tok_off.cpu().tolist() == [0]
+
+
+# ---------------------------------------------------------------- dispatch
+
+def check_dispatch(B, O, tr, specs, materialise=True):
+    bp, op = both(B, O, specs)
+    P = len(specs)
+    dt = B.upload_trace(tr)
+    got = B.disco_eval_dispatch(dt, bp, materialise=materialise)
+    want = O.dispatch(tr, op, materialise=materialise)
+    acc = B.accum_to_host(got["acc"], P)
+    for j in range(P):
+        for f in ("s_pre", "s_dec", "d_pre", "d_dec", "n_dev_started", "n_dev_win"):
+            assert int(acc[f][j]) == int(want[f][j]), (f, j)
+        if tr["n_req"]:
+            assert close(float(acc["ttft_sum"][j]), float(want["ttft_sum"][j])), j
+    if materialise and tr["n_req"]:
+        assert_same_bits(got["decision"].cpu().numpy(), want["decision"], "decision")
+        assert_same_bits(got["ttft"].cpu().numpy(), want["ttft"], "ttft")
+        t = want["ttft"].view(np.uint32)
+        assert (acc["ttft_min_bits"] == t.min(axis=1)).all() and (acc["ttft_max_bits"] == t.max(axis=1)).all()
+    return dt, acc
+
+
+@pytest.mark.parametrize("n_req", [0, 1, 63, 64, 65, 1000, 10_007])
+def test_dispatch_matches_oracle_on_handmade_traces(B, oracle, n_req):
+    print(f"dispatch parity handmade n_req={n_req}", flush=True)
+    tr = DI.handmade_trace(100 + n_req, n_req, tokens=False, ties=True, per_request_device=(n_req % 2 == 1))
+    check_dispatch(B, oracle, tr, mixed_policies())
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 5, 16, 33, 64])
+def test_dispatch_column_counts(B, oracle, P):
+    print(f"dispatch parity columns P={P}", flush=True)
+    tr = oracle.gen_trace(DI.config(0, n_req=5_003, seed=P)["gen"])
+    rng = np.random.default_rng(P)
+    specs = []
+    for j in range(P):
+        if j % 2 == 0:
+            specs.append(dict(mode=0, l_th=int(rng.integers(0, 3000))))
+        else:
+            specs.append(dict(mode=1, l_th=int(rng.integers(-1, 300)), w_tail=DI.f32(rng.uniform(0, 2))))
+    check_dispatch(B, oracle, tr, specs)
+
+
+# --------------------------------------------------------------- timelines
+
+def check_migration(B, O, tr, specs, tau, kappa, delivered_col=0):
+    bp, op = both(B, O, specs)
+    P = len(specs)
+    dt = B.upload_trace(tr)
+    got = B.disco_eval_migration(dt, tau, kappa, bp, materialise=True, delivered_col=delivered_col)
+    want = O.migration(tr, op, tau, kappa, materialise=True)
+    acc = B.accum_to_host(got["acc"], P)
+    for j in range(P):
+        for f in ("m_s_dec", "m_d_dec", "m_d_repre", "n_migrated", "tbt_count"):
+            assert int(acc[f][j]) == int(want[f][j]), (f, j)
+        if tr["n_req"]:
+            assert close(float(acc["tlast_sum"][j]), float(want["tlast_sum"][j])), j
+    if tr["n_req"]:
+        assert_same_bits(got["mig_idx"].cpu().numpy(), want["mig_idx"], "mig_idx")
+        assert_same_bits(got["n_src_tok"].cpu().numpy(), want["n_src_tok"], "n_src_tok")
+        assert_same_bits(got["t_last"].cpu().numpy(), want["t_last"], "t_last")
+    if delivered_col is not None:
+        w1 = O.migration(tr, [op[delivered_col]], tau, kappa, materialise=False, tbt_col=0, want_delivered=True)
+        assert_same_bits(got["delivered"].cpu().numpy(), w1["delivered"], "delivered")
+        if w1["tbt"].size:
+            b = w1["tbt"].view(np.uint32)
+            assert int(acc["tbt_min_bits"][delivered_col]) == int(b.min())
+            assert int(acc["tbt_max_bits"][delivered_col]) == int(b.max())
+    return dt, acc, want
+
+
+@pytest.mark.parametrize("n_req,max_out", [(0, 10), (1, 1), (1, 4096), (257, 300), (1500, 200)])
+def test_migration_matches_oracle_on_token_traces(B, oracle, n_req, max_out):
+    print(f"migration parity handmade n_req={n_req} max_out={max_out}", flush=True)
+    tr = DI.handmade_trace(7 + n_req, n_req, tokens=True, max_out=max_out, stall_p=0.03, ties=True)
+    if n_req == 1 and max_out == 4096:
+        tr = DI.handmade_trace(8, 3, tokens=True, max_out=4096, stall_p=0.002)
+        tr["output_len"][:] = [4096, 1, 129]
+        tr = _rebuild_tokens(tr, 9)
+    for col in (0, 6):
+        _, acc, want = check_migration(B, oracle, tr, mixed_policies(lag=True), DI.TAU, DI.KAPPA_LAG, delivered_col=col)
+    if n_req >= 257:
+        assert want["n_migrated"].max() > 0
+
+
+def _rebuild_tokens(tr, seed):
+    rng = np.random.default_rng(seed)
+    n = tr["output_len"]
+    off = np.zeros(len(n) + 1, np.int64)
+    np.cumsum(n, out=off[1:])
+    gaps = rng.lognormal(-3.5, 0.6, int(off[-1])).astype(np.float32)
+    gaps[rng.random(gaps.size) < 0.002] = np.float32(1.7)
+    arr = np.empty(int(off[-1]), np.float32)
+    for i in range(len(n)):
+        a, b = int(off[i]), int(off[i + 1])
+        arr[a] = 0
+        arr[a + 1:b] = np.cumsum(gaps[a + 1:b], dtype=np.float32)
+    tr = dict(tr, tok_off=off, tok_arr=arr, n_tok=int(off[-1]))
+    return tr
+
+
+def test_migration_constant_gap_server(B, oracle):
+    # no per-token trace: the server's arrivals are t * srv_tbt (the per-request constant gap of workload 0)
+    print("migration parity constant-gap", flush=True)
+    tr = oracle.gen_trace(DI.config(0, n_req=2_001, seed=5)["gen"])
+    tr["tok_arr"] = None
+    check_migration(B, oracle, tr, mixed_policies(lag=True), DI.TAU, DI.KAPPA_LAG, delivered_col=2)
+
+
+def test_migration_generated_tokens(B, oracle):
+    print("migration parity config2-like", flush=True)
+    cfg = DI.config(2, n_req=4_000, seed=11)
+    tr = oracle.gen_trace(cfg["gen"])
+    specs = [dict(mode=0, l_th=0, mig_mode=1), dict(mode=1, l_th=-1, w_tail=math.inf, mig_mode=1)]
+    _, acc, want = check_migration(B, oracle, tr, specs, cfg["tau"], cfg["kappa"], delivered_col=1)
+    assert want["n_migrated"][1] > 100
+
+
+# -------------------------------------------------------------- statistics
+
+def check_stats(B, O, tr, specs, cost, tau=None, kappa=3.0, quantiles=((50, 100), (99, 100))):
+    bp, op = both(B, O, specs)
+    P = len(specs)
+    dt = B.upload_trace(tr)
+    ws = B.workspace(tr["n_req"], P)
+    r = B.disco_eval_dispatch(dt, bp, ws=ws)
+    if tau is not None:
+        B.disco_eval_migration(dt, tau, kappa, bp, ws=ws, acc=r["acc"])
+    out = B.disco_reduce_stats(dt, cost, bp, r["acc"], quantiles=quantiles, tau=tau, kappa=kappa, ws=ws)
+    got = B.stats_to_host(out, P)
+    want = O.stats(tr, op, cost, quantiles=quantiles, tau=tau, kappa=kappa)
+    for j in range(P):
+        w, g = want[j], got[j]
+        for f in ("s_pre", "s_dec", "d_pre", "d_dec", "n_dev_started", "n_dev_win", "n_migrated", "tbt_count", "n_req"):
+            assert int(g[f]) == int(w[f]), (f, j)
+        for f in ("server_cost", "device_energy", "device_cost", "total_cost"):
+            assert close(float(g[f]), float(w[f]), 1e-12), (f, j)
+        if tr["n_req"]:
+            assert close(float(g["mean_ttft"]), w["mean_ttft"]), j
+        for qi in range(len(quantiles)):
+            assert int(g["ttft_rank"][qi]) == w["ttft_rank"][qi], (j, qi)
+            if tr["n_req"]:
+                assert np.float32(g["ttft_q"][qi]).view(np.uint32) == np.float32(w["ttft_q"][qi]).view(np.uint32), (j, qi, g["ttft_q"][qi], w["ttft_q"][qi])
+            else:
+                assert math.isnan(g["ttft_q"][qi])
+            if tau is not None:
+                assert int(g["tbt_rank"][qi]) == w["tbt_rank"][qi], (j, qi)
+                if w["tbt_count"]:
+                    assert np.float32(g["tbt_q"][qi]).view(np.uint32) == np.float32(w["tbt_q"][qi]).view(np.uint32), (j, qi, g["tbt_q"][qi], w["tbt_q"][qi])
+                else:
+                    assert math.isnan(g["tbt_q"][qi])
+        if tau is not None and w["tbt_count"]:
+            assert close(float(g["mean_tbt"]), w["mean_tbt"]), j
+    return got, want
+
+
+@pytest.mark.parametrize("n_req", [0, 1, 100, 4_097])
+def test_stats_dispatch_only(B, oracle, n_req):
+    print(f"stats parity dispatch-only n_req={n_req}", flush=True)
+    tr = DI.handmade_trace(31 + n_req, n_req, tokens=False, ties=True)
+    check_stats(B, oracle, tr, mixed_policies(), DI.COST_S,
+                quantiles=((50, 100), (99, 100), (0, 1), (1, 1)))
+
+
+def test_stats_all_values_equal(B, oracle):
+    print("stats parity ties", flush=True)
+    tr = DI.handmade_trace(3, 500, tokens=False)
+    tr["srv_ttft"][:] = np.float32(0.25)
+    tr["prompt_len"][:] = 40
+    tr["dev_pre_spt"] = None
+    check_stats(B, oracle, tr, [dict(mode=1, l_th=-1, w_tail=math.inf), dict(mode=0, l_th=0)], DI.COST_D)
+
+
+@pytest.mark.parametrize("n_req,max_out", [(1, 1), (40, 1), (300, 250), (1200, 120)])
+def test_stats_with_timelines(B, oracle, n_req, max_out):
+    print(f"stats parity timelines n_req={n_req} max_out={max_out}", flush=True)
+    tr = DI.handmade_trace(51 + n_req, n_req, tokens=True, max_out=max_out, stall_p=0.03)
+    specs = mixed_policies(lag=True)
+    check_stats(B, oracle, tr, specs, DI.COST_S, tau=DI.TAU, kappa=DI.KAPPA_LAG)
+
+
+def test_config0_end_to_end(B, oracle):
+    """Workload 0 at full size: 10^4 requests x 16 budget levels, thresholds from the search, all statistics."""
+    print("config0 end to end", flush=True)
+    cfg = DI.config(0)
+    tr = oracle.gen_trace(cfg["gen"])
+    dt = B.disco_gen_trace(cfg["gen"])
+    levels = DI.budget_levels(cfg["levels"])
+    total = int(tr["prompt_len"].astype(np.int64).sum())
+    lmax = int(tr["prompt_len"].max())
+    templ = [B.Policy(mode=0, mig_mode=1) for _ in levels]
+    specs = [dict(which_param=B.PARAM_L_TH, which_acc="server_prefill_tok", n_steps=14, lo=0, hi=lmax + 1,
+                  target=num * total / den) for num, den in levels]
+    res = B.disco_budget_search(dt, cfg["cost"], templ, specs)
+    found = B.policies_to_host(res["pol_out"], len(levels))
+    so = B.search_to_host(res["out"], len(levels))
+    for j, (num, den) in enumerate(levels):
+        l_th, hp, ha = oracle.search_lth(tr, oracle.Policy(mode=0), 0, lmax + 1, 14, "server_prefill_tok",
+                                         cfg["cost"], num * total / den)
+        assert found[j].l_th == l_th == int(so["param"][j])
+        assert (so["hist_param"][j][:14] == hp).all() and (so["hist_acc"][j][:14] == ha).all()
+    pol_specs = [dict(mode=0, l_th=p.l_th, mig_mode=1) for p in found]
+    tr_host = dict(tr, tok_arr=None)
+    got, want = check_stats(B, oracle, tr_host, pol_specs, cfg["cost"], tau=cfg["tau"], kappa=cfg["kappa"])
+    assert want[0]["s_pre"] == 0 and want[-1]["s_pre"] == total
+
+
+# ----------------------------------------------------------- budget search
+
+def test_wait_search_history_is_bit_identical(B, oracle):
+    print("search parity wait", flush=True)
+    cfg = DI.config(3, n_req=50_003)
+    tr = oracle.gen_trace(cfg["gen"])
+    dt = B.upload_trace(tr)
+    cost = cfg["cost"]
+    c_all = cost["cs_pre"] * (int(tr["prompt_len"].astype(np.int64).sum()) + int(tr["output_len"].astype(np.int64).sum()))
+    cases = [("device_cost", 0.30 * c_all), ("device_prefill_tok", 0.2 * int(tr["prompt_len"].astype(np.int64).sum())),
+             ("total_cost", 1.30 * c_all)]
+    templ = [B.Policy(mode=1, l_th=-1) for _ in cases]
+    specs = [dict(which_param=B.PARAM_W_TAIL, which_acc=a, n_steps=32, lo=0.0, hi=5.0, target=t) for a, t in cases]
+    res = B.disco_budget_search(dt, cost, templ, specs)
+    so = B.search_to_host(res["out"], len(cases))
+    pol = B.policies_to_host(res["pol_out"], len(cases))
+    for j, (a, t) in enumerate(cases):
+        w, hp, ha = oracle.search_wait(tr, oracle.Policy(mode=1, l_th=-1), 0.0, 5.0, 32, a, cost, t)
+        assert np.float32(so["param"][j]) == w == np.float32(pol[j].w_tail), (a, so["param"][j], w)
+        assert (so["hist_param"][j][:32].astype(np.float32) == hp).all(), a
+        assert (so["hist_acc"][j][:32] == ha).all(), a
+        d = oracle.dispatch(tr, [oracle.Policy(mode=1, l_th=-1, w_tail=float(w))], materialise=False)
+        at = so["at_param"][j]
+        assert int(at["d_pre"]) == int(d["d_pre"][0]) and int(at["d_dec"]) == int(d["d_dec"][0])
+        assert int(at["s_dec"]) == int(d["s_dec"][0])
+
+
+def test_single_search_single_step(B, oracle):
+    print("search parity single", flush=True)
+    tr = DI.handmade_trace(77, 999, tokens=False)
+    dt = B.upload_trace(tr)
+    res = B.disco_budget_search(dt, DI.COST_D, [B.Policy(mode=1, l_th=50)],
+                                [dict(which_param=B.PARAM_W_TAIL, which_acc="device_prefill_tok", n_steps=1, lo=0.0,
+                                      hi=1.0, target=1e5)])
+    so = B.search_to_host(res["out"], 1)
+    w, hp, ha = oracle.search_wait(tr, oracle.Policy(mode=1, l_th=50), 0.0, 1.0, 1, "device_prefill_tok", DI.COST_D, 1e5)
+    assert np.float32(so["param"][0]) == w and so["hist_acc"][0][0] == ha[0]
