@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the DiSCo policy-evaluation path on one MI355X.
+
+A step is one pass of the whole path over one resident batch: budget search
+(one length threshold per budget level), fused dispatch + reduction, order
+statistics -- and, for workloads with token timelines, the timeline pass and
+the TBT order statistics.  The headline workload is configuration 1
+(10^6 requests x 64 budget levels, dispatch only); the other configurations
+are reported as extra fields of the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1] [--extras config2,config3,config4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
+# plain (non-packed) fp32 vector rate: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one operation per lane and clock
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config1")
+    ap.add_argument("--extras", default="config2,config3,config4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-reps", type=int, default=20)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on one GPU; --gpus must be 1 (requests shard trivially, see DESIGN.md)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    import disco_inputs as DI
+    import paper_2502_11417_amd as D
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    def sync():
+        torch.cuda.synchronize()
+
+    class Workload:
+        """Resident trace + everything a step needs, allocated once."""
+
+        def __init__(self, idx):
+            self.idx = idx
+            self.cfg = DI.config(idx)
+            g = self.cfg["gen"]
+            t0 = time.perf_counter()
+            self.trace = D.disco_gen_trace(g)
+            sync()
+            self.gen_s = time.perf_counter() - t0
+            self.N = self.trace.n_req
+            self.T = self.trace.n_tok
+            self.P = self.cfg["levels"]
+            self.ws = D.workspace(self.N, max(self.P, 1))
+            self.acc = torch.zeros(self.P * 128, dtype=torch.uint8, device="cuda")
+            self.stats = torch.zeros(self.P * 256, dtype=torch.uint8, device="cuda")
+            self.sum_l = int(self.trace.prompt_len.sum(dtype=torch.int64).item())
+            self.sum_n = int(self.trace.output_len.sum(dtype=torch.int64).item())
+            self.lmax = int(self.trace.prompt_len.max().item())
+            self.levels = DI.budget_levels(self.P)
+            self.lth_steps = max(1, (self.lmax + 1).bit_length())
+            mig = D.MIG_LAG if self.cfg["timelines"] else D.MIG_NONE
+            self.templ = [D.Policy(mode=D.MODE_S, mig_mode=mig) for _ in self.levels]
+            self.specs = [dict(which_param=D.PARAM_L_TH, which_acc="server_prefill_tok", n_steps=self.lth_steps,
+                               lo=0, hi=self.lmax + 1, target=num * self.sum_l / den) for num, den in self.levels]
+            self.sout = torch.zeros(self.P * D.binding.SEARCH_DTYPE.itemsize, dtype=torch.uint8, device="cuda")
+            self.pol_out = torch.zeros(self.P * 32, dtype=torch.uint8, device="cuda")
+            self.pols = None
+
+        def search(self):
+            """Budget levels -> length thresholds; the found columns stay on the device."""
+            res = D.disco_budget_search(self.trace, self.cfg["cost"], self.templ, self.specs, ws=self.ws,
+                                        out=self.sout, pol_out=self.pol_out)
+            self.pols = res["policies"]
+
+        def step(self):
+            cfg = self.cfg
+            if self.idx == 3:
+                c_all = cfg["cost"]["cs_pre"] * (self.sum_l + self.sum_n)
+                s = cfg["search"]
+                return D.disco_budget_search(
+                    self.trace, cfg["cost"], [D.Policy(mode=D.MODE_D, l_th=-1)],
+                    [dict(which_param=D.PARAM_W_TAIL, which_acc="device_cost", n_steps=s["steps"], lo=s["lo"],
+                          hi=s["hi"], target=s["budget_frac"] * c_all)], ws=self.ws)
+            # budget levels -> thresholds (device-resident bisection), then evaluate the found columns
+            # straight from the device-resident policy table: no host round trip inside a step
+            self.search()
+            tau = cfg["tau"] if cfg["timelines"] else None
+            D.disco_eval_dispatch(self.trace, self.pols, ws=self.ws, acc=self.acc)
+            if tau is not None:
+                D.disco_eval_migration(self.trace, tau, cfg["kappa"], self.pols, ws=self.ws, acc=self.acc)
+            return D.disco_reduce_stats(self.trace, cfg["cost"], self.pols, self.acc, tau=tau, kappa=cfg["kappa"],
+                                        ws=self.ws, out=self.stats)
+
+        def time_steps(self, steps, warmup):
+            if self.idx != 3:
+                self.search()
+            for _ in range(warmup):
+                self.step()
+            sync()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                self.step()
+            sync()
+            return (time.perf_counter() - t0) / steps
+
+    def event_time(fn, reps):
+        """Average duration of `fn` over `reps` back-to-back calls, HIP events on the launch stream."""
+        fn()
+        sync()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        sync()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    idx = int(args.workload.replace("config", ""))
+    log(f"[bench] generating {args.workload} ...")
+    w = Workload(idx)
+    log(f"[bench] {args.workload}: N={w.N} P={w.P} T={w.T} gen {w.gen_s * 1e3:.1f} ms; timing {args.steps} steps")
+    sec = w.time_steps(args.steps, args.warmup)
+    pairs = w.N * (w.cfg["search"]["steps"] if idx == 3 else w.P)
+    value = pairs / sec
+
+    # dominant kernel of the step: the fused dispatch-and-reduce pass (it runs once per bisection step of
+    # the budget search and once for the evaluation).  Algorithmic bytes: 12 B per request (prompt length,
+    # server TTFT, output length), independent of the number of columns.
+    bytes_per_launch = 12.0 * w.N
+    if idx == 3:
+        one = [D.Policy(mode=D.MODE_D, l_th=-1, w_tail=0.6)]
+        t_k = event_time(lambda: D.disco_eval_dispatch(w.trace, one, ws=w.ws, acc=w.acc), args.kernel_reps)
+        pairs_per_launch = w.N
+    else:
+        t_k = event_time(lambda: D.disco_eval_dispatch(w.trace, w.pols, ws=w.ws, acc=w.acc), args.kernel_reps)
+        pairs_per_launch = w.N * w.P
+    achieved = bytes_per_launch / t_k / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_dispatch_acc", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "launch_us": round(t_k * 1e6, 2), "pairs_per_s_in_kernel": pairs_per_launch / t_k}
+
+    result = {
+        "metric": "request x policy evaluations/s", "value": value, "unit": "pairs/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "n_req": w.N, "policy_columns": w.P, "token_events": w.T,
+                   "step": "budget search + fused dispatch/reduce + order statistics"},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(idx)
+
+    extras = {}
+    for name in [e for e in args.extras.split(",") if e and e != args.workload]:
+        k = int(name.replace("config", ""))
+        del w
+        torch.cuda.empty_cache()
+        log(f"[bench] extra {name} ...")
+        w = Workload(k)
+        steps = 3 if k == 4 else 10
+        s = w.time_steps(steps, 1)
+        ex = {"n_req": w.N, "policy_columns": w.P, "token_events": w.T, "ms_per_step": s * 1e3}
+        if k == 3:
+            ex["pairs_per_s"] = w.N * w.cfg["search"]["steps"] / s
+            ex["hbm_frac_of_peak"] = 12.0 * w.N * (w.cfg["search"]["steps"] + 1) / s / 1e9 / HBM_PEAK_GBS
+        else:
+            ex["pairs_per_s"] = w.N * w.P / s
+            ex["token_events_per_s_raw"] = w.T / s
+            ex["token_events_per_s_pair_weighted"] = w.T * w.P / s
+            # timeline pass alone: 4 B per token event + 28 B per request, read once for all columns
+            tau = w.cfg["tau"]
+            t_tl = event_time(lambda: D.disco_eval_migration(w.trace, tau, w.cfg["kappa"], w.pols, ws=w.ws, acc=w.acc),
+                              3 if k == 4 else 10)
+            gb = (4.0 * w.T + 28.0 * w.N) / 1e9
+            ex["timeline_kernel"] = {"bound": "hbm", "launch_ms": t_tl * 1e3, "achieved_GBs": gb / t_tl,
+                                     "frac": gb / t_tl / HBM_PEAK_GBS}
+        extras[name] = ex
+        log(f"[bench] {name}: {json.dumps(ex)}")
+    if extras:
+        result["extras"] = extras
+    print(json.dumps(result))
+    return 0
+
+
+def cpu_baseline(idx: int) -> dict:
+    """The oracle as it stands, on a bounded sample of the same workload, on the host's cores."""
+    import numpy as np
+
+    import disco_inputs as DI
+    from oracle import disco_oracle as O
+
+    n_sample = {0: 10_000, 1: 250_000, 2: 20_000, 3: 1_000_000, 4: 5_000}[idx]
+    cfg = DI.config(idx, n_req=n_sample)
+    tr = O.gen_trace(cfg["gen"])
+    t0 = time.perf_counter()
+    if idx == 3:
+        c_all = cfg["cost"]["cs_pre"] * (int(tr["prompt_len"].astype(np.int64).sum()) + int(tr["output_len"].astype(np.int64).sum()))
+        s = cfg["search"]
+        O.search_wait(tr, O.Policy(mode=1, l_th=-1), s["lo"], s["hi"], s["steps"], "device_cost", cfg["cost"],
+                      s["budget_frac"] * c_all)
+        pairs = n_sample * s["steps"]
+    else:
+        levels = DI.budget_levels(cfg["levels"])
+        total = int(tr["prompt_len"].astype(np.int64).sum())
+        lmax = int(tr["prompt_len"].max())
+        steps = max(1, (lmax + 1).bit_length())
+        mig = 1 if cfg["timelines"] else 0
+        pols = []
+        for num, den in levels:
+            l_th, _, _ = O.search_lth(tr, O.Policy(mode=0), 0, lmax + 1, steps, "server_prefill_tok", cfg["cost"],
+                                      num * total / den)
+            pols.append(O.Policy(mode=0, l_th=l_th, mig_mode=mig))
+        O.stats(tr, pols, cfg["cost"], tau=cfg["tau"] if cfg["timelines"] else None, kappa=cfg["kappa"])
+        pairs = n_sample * len(levels)
+    dt = time.perf_counter() - t0
+    return {"value": pairs / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n_sample} requests of config{idx} (same generator and seed), same step, {dt:.1f} s"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

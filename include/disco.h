@@ -12,6 +12,11 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    All work is enqueued on it and the calls return without waiting, except
  *    where a call says it synchronises.
+ *  - Policy tables (`pol`, `templ`) may live in host or in device memory; the
+ *    library asks the HIP runtime which it is.  A host table is validated
+ *    (DISCO_ERR_RANGE for unknown modes or NaN parameters); a device table,
+ *    e.g. the pol_out of disco_budget_search, is used as it is, which keeps a
+ *    search -> evaluate -> reduce sequence free of host round trips.
  *  - Return value: DISCO_OK or a negative DISCO_ERR_* code.  Shapes, null
  *    pointers and workspace sizes are checked on the host before anything is
  *    launched; a failed check launches nothing.  No exceptions, no abort.
@@ -217,7 +222,7 @@ typedef struct disco_accum {
 
 /* Dispatch of every (request, column) pair (Sec. 4.2, Alg. 2 and 3):
  * device TTFT d = fma(l, k, c); wait; which endpoints start; winner; TTFT.
- * pol: host, P entries.  out: host struct of device arrays, may be NULL.
+ * pol: host or device, P entries.  out: host struct of device arrays, may be NULL.
  * acc: device, P entries, dispatch block overwritten.
  * ws: device workspace of disco_workspace_bytes(n_req, P) bytes.
  * Asynchronous.  n_req == 0 is valid (zero totals).

@@ -197,7 +197,19 @@ def _check(rc: int, where: str):
         raise DiscoError(rc, where)
 
 
-def _policies(policies) -> C.Array:
+class DevicePolicies:
+    """A policy table that already lives on the device (P records of 32 bytes)."""
+
+    def __init__(self, buf: torch.Tensor, P: int):
+        self.buf, self.P = buf, P
+
+    def __len__(self):
+        return self.P
+
+
+def _policies(policies):
+    if isinstance(policies, DevicePolicies):
+        return C.cast(C.c_void_p(policies.buf.data_ptr()), C.POINTER(CPolicy))
     arr = (CPolicy * max(len(policies), 1))()
     for j, p in enumerate(policies):
         arr[j] = CPolicy(p.mode, p.l_th, p.l_mid, p.w_mid, p.beta, p.w_tail, p.mig_mode, 0)
@@ -336,7 +348,8 @@ def disco_reduce_stats(trace: Trace, cost: dict, policies, acc: torch.Tensor, qu
     return out
 
 
-def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Tensor | None = None) -> dict:
+def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Tensor | None = None,
+                        out: torch.Tensor | None = None, pol_out: torch.Tensor | None = None) -> dict:
     """specs: dicts with which_param, which_acc (names or ints), n_steps, lo, hi, target."""
     n = len(templates)
     dev = trace.prompt_len.device if trace.prompt_len is not None else "cuda"
@@ -347,14 +360,16 @@ def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Te
         wa = s["which_acc"]
         sp[j] = CSearchSpec(int(s["which_param"]), ACC[wa] if isinstance(wa, str) else int(wa), int(s["n_steps"]), 0,
                             float(s["lo"]), float(s["hi"]), float(s["target"]))
-    out = torch.zeros(max(n, 1) * SEARCH_DTYPE.itemsize, dtype=torch.uint8, device=dev)
-    pol_out = torch.zeros(max(n, 1) * 32, dtype=torch.uint8, device=dev)
+    if out is None:
+        out = torch.zeros(max(n, 1) * SEARCH_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+    if pol_out is None:
+        pol_out = torch.zeros(max(n, 1) * 32, dtype=torch.uint8, device=dev)
     cs = trace.c_struct()
     cc = _cost(cost)
     rc = _lib.disco_budget_search(C.byref(cs), C.byref(cc), _policies(templates), sp, n, out.data_ptr(),
                                   pol_out.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "disco_budget_search")
-    return {"out": out, "pol_out": pol_out}
+    return {"out": out, "pol_out": pol_out, "policies": DevicePolicies(pol_out, n)}
 
 
 # ------------------------------------------------------- host-side parsing

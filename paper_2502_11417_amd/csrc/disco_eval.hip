@@ -59,6 +59,13 @@ __global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned*
     if (i < 64) tickets[i] = 0u;
 }
 
+__global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* dst, unsigned* tickets)
+{
+    int i = threadIdx.x;
+    if (i < P) dst[i] = src[i];
+    if (i < 64) tickets[i] = 0u;
+}
+
 // Last-ticket test: true in every thread of the workgroup that finishes last.
 __device__ __forceinline__ bool take_last_ticket(unsigned* ticket)
 {
@@ -824,13 +831,35 @@ unsigned timeline_blocks(i64 n_req)
     return (unsigned)b;
 }
 
-void store_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, hipStream_t stream)
+bool is_device_pointer(const void* p)
 {
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();          // ordinary host memory is not known to the runtime
+        return false;
+    }
+    return attr.type == hipMemoryTypeDevice;
+}
+
+// Host tables are validated and travel as a kernel argument; device tables
+// (e.g. the pol_out of a budget search) are copied on the device, unvalidated.
+int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, hipStream_t stream)
+{
+    if (!pol) return DISCO_ERR_NULL;
+    if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
+    if (is_device_pointer(pol)) {
+        hipLaunchKernelGGL(k_copy_policies, dim3(1), dim3(64), 0, stream, pol, P, (disco_policy*)(ws + L.pol),
+                           (unsigned*)(ws + L.ticket));
+        return DISCO_OK;
+    }
+    int rc = check_policies(pol, P);
+    if (rc) return rc;
     PolTable t;
     memset(&t, 0, sizeof(t));
     memcpy(t.p, pol, sizeof(disco_policy) * (size_t)P);
     hipLaunchKernelGGL(k_store_policies, dim3(1), dim3(64), 0, stream, t, P, (disco_policy*)(ws + L.pol),
                        (unsigned*)(ws + L.ticket));
+    return DISCO_OK;
 }
 
 template <int G>
@@ -944,16 +973,16 @@ extern "C" int32_t disco_eval_dispatch(const disco_trace* trace, const disco_pol
 {
     int rc = check_trace(trace);
     if (rc) return rc;
-    rc = check_policies(pol, P);
-    if (rc) return rc;
-    if (!acc) return DISCO_ERR_NULL;
+    if (!pol || !acc) return DISCO_ERR_NULL;
+    if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
     rc = check_ws(ws_, ws_bytes, P);
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)ws_;
     const WsLayout L = disco_ws_layout(P);
     const TraceView v = view_of(trace);
-    store_policies(pol, P, ws, L, stream);
+    rc = stage_policies(pol, P, ws, L, stream);
+    if (rc) return rc;
     DispFin fin;
     memset(&fin, 0, sizeof(fin));
     fin.kind = 0;
@@ -973,10 +1002,8 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
 {
     int rc = check_trace(trace);
     if (rc) return rc;
-    if (!tl) return DISCO_ERR_NULL;
-    rc = check_policies(pol, P);
-    if (rc) return rc;
-    if (!acc) return DISCO_ERR_NULL;
+    if (!tl || !pol || !acc) return DISCO_ERR_NULL;
+    if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
     if (!(tl->tau > 0.0f) || !(tl->kappa_lag >= 0.0f)) return DISCO_ERR_RANGE;
     if (trace->n_req > 0 && !trace->tok_arr && !trace->srv_tbt) return DISCO_ERR_CSR;
     if (out && out->delivered && (!trace->tok_off || out->delivered_col < 0 || out->delivered_col >= P))
@@ -988,7 +1015,8 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
     const WsLayout L = disco_ws_layout(P);
     TraceView v = view_of(trace);
     if (out && out->delivered) v.off = trace->tok_off;      // offsets index `delivered` even without tok_arr
-    store_policies(pol, P, ws, L, stream);
+    rc = stage_policies(pol, P, ws, L, stream);
+    if (rc) return rc;
     TimelineArgs a;
     memset(&a, 0, sizeof(a));
     a.tau = tl->tau;
@@ -1015,9 +1043,8 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
 {
     int rc = check_trace(trace);
     if (rc) return rc;
-    if (!cost || !acc || !out) return DISCO_ERR_NULL;
-    rc = check_policies(pol, P);
-    if (rc) return rc;
+    if (!cost || !acc || !out || !pol) return DISCO_ERR_NULL;
+    if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
     if (nq < 0 || nq > DISCO_MAX_Q || (nq > 0 && !q)) return nq > 0 && !q ? DISCO_ERR_NULL : DISCO_ERR_SHAPE;
     if (P * nq > DISCO_MAX_SLOTS) return DISCO_ERR_SHAPE;
     for (int i = 0; i < nq; ++i)
@@ -1032,7 +1059,8 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     const TraceView v = view_of(trace);
     SelState* S = (SelState*)(ws + L.sel);
     unsigned* gh = (unsigned*)(ws + L.ghist);
-    store_policies(pol, P, ws, L, stream);
+    rc = stage_policies(pol, P, ws, L, stream);
+    if (rc) return rc;
     disco_quantile qs[4] = {{0, 1}, {0, 1}, {0, 1}, {0, 1}};
     for (int i = 0; i < nq; ++i) qs[i] = q[i];
     if (nq > 0) {
@@ -1068,9 +1096,8 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
 {
     int rc = check_trace(trace);
     if (rc) return rc;
-    if (!cost || !spec || !out) return DISCO_ERR_NULL;
-    rc = check_policies(templ, n_search);
-    if (rc) return rc;
+    if (!cost || !spec || !out || !templ) return DISCO_ERR_NULL;
+    if (n_search < 1 || n_search > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
     const int n_steps = spec[0].n_steps;
     if (n_steps < 1 || n_steps > DISCO_MAX_STEPS) return DISCO_ERR_SHAPE;
     SpecTable t;
@@ -1093,7 +1120,8 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
     char* ws = (char*)ws_;
     const WsLayout L = disco_ws_layout(n_search);
     const TraceView v = view_of(trace);
-    store_policies(templ, n_search, ws, L, stream);
+    rc = stage_policies(templ, n_search, ws, L, stream);
+    if (rc) return rc;
     hipLaunchKernelGGL(k_search_init, dim3(1), dim3(64), 0, stream, t, n_search, (SearchState*)(ws + L.search),
                        (disco_policy*)(ws + L.pol));
     DispFin fin;

@@ -320,3 +320,27 @@ def test_single_search_single_step(B, oracle):
     so = B.search_to_host(res["out"], 1)
     w, hp, ha = oracle.search_wait(tr, oracle.Policy(mode=1, l_th=50), 0.0, 1.0, 1, "device_prefill_tok", DI.COST_D, 1e5)
     assert np.float32(so["param"][0]) == w and so["hist_acc"][0][0] == ha[0]
+
+
+def test_device_resident_policy_table(B, oracle):
+    """search -> dispatch -> statistics with the found columns never leaving the device."""
+    print("device policy table", flush=True)
+    cfg = DI.config(1, n_req=30_011, seed=2)
+    tr = oracle.gen_trace(cfg["gen"])
+    dt = B.disco_gen_trace(cfg["gen"])
+    levels = DI.budget_levels(8)
+    total = int(tr["prompt_len"].astype(np.int64).sum())
+    lmax = int(tr["prompt_len"].max())
+    specs = [dict(which_param=B.PARAM_L_TH, which_acc="server_prefill_tok", n_steps=13, lo=0, hi=lmax + 1,
+                  target=num * total / den) for num, den in levels]
+    res = B.disco_budget_search(dt, cfg["cost"], [B.Policy(mode=0) for _ in levels], specs)
+    r = B.disco_eval_dispatch(dt, res["policies"])
+    got = B.stats_to_host(B.disco_reduce_stats(dt, cfg["cost"], res["policies"], r["acc"]), len(levels))
+    opol = [oracle.Policy(mode=0, l_th=oracle.search_lth(tr, oracle.Policy(mode=0), 0, lmax + 1, 13, "server_prefill_tok",
+                                                        cfg["cost"], num * total / den)[0]) for num, den in levels]
+    want = oracle.stats(tr, opol, cfg["cost"])
+    for j, w in enumerate(want):
+        assert int(got[j]["s_pre"]) == w["s_pre"] and int(got[j]["d_dec"]) == w["d_dec"]
+        for qi in range(2):
+            assert int(got[j]["ttft_rank"][qi]) == w["ttft_rank"][qi]
+            assert np.float32(got[j]["ttft_q"][qi]) == np.float32(w["ttft_q"][qi])
