@@ -210,12 +210,11 @@ typedef struct disco_accum {
     int64_t m_s_dec, m_d_dec, m_d_repre;
     int64_t n_migrated, tbt_count;
     double tlast_sum;
-    /* smallest and largest fp32 bit pattern among the column's TTFT / TBT
-     * values (non-negative floats order like their bit patterns); they bound
-     * the key range of the order-statistic selection */
+    /* smallest and largest fp32 bit pattern among the column's TTFT values
+     * (non-negative floats order like their bit patterns); they bound the key
+     * range of the TTFT order-statistic selection */
     uint32_t ttft_min_bits, ttft_max_bits;
-    uint32_t tbt_min_bits, tbt_max_bits;
-    int64_t reserved[1];
+    int64_t reserved[2];
 } disco_accum;
 
 /* ---- evaluation --------------------------------------------------------- */

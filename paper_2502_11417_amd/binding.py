@@ -104,8 +104,7 @@ ACCUM_DTYPE = np.dtype([
     ("n_dev_started", "<i8"), ("n_dev_win", "<i8"), ("ttft_sum", "<f8"),
     ("m_s_dec", "<i8"), ("m_d_dec", "<i8"), ("m_d_repre", "<i8"), ("n_migrated", "<i8"), ("tbt_count", "<i8"),
     ("tlast_sum", "<f8"),
-    ("ttft_min_bits", "<u4"), ("ttft_max_bits", "<u4"), ("tbt_min_bits", "<u4"), ("tbt_max_bits", "<u4"),
-    ("reserved", "<i8", (1,))])
+    ("ttft_min_bits", "<u4"), ("ttft_max_bits", "<u4"), ("reserved", "<i8", (2,))])
 STATS_DTYPE = np.dtype([
     ("mean_ttft", "<f8"), ("mean_tbt", "<f8"),
     ("server_cost", "<f8"), ("device_energy", "<f8"), ("device_cost", "<f8"), ("total_cost", "<f8"),

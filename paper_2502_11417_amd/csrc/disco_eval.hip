@@ -18,29 +18,10 @@
 #include <stdio.h>
 #include <string.h>
 
-#include "disco_common.h"
-#include "disco_device.h"
+#include "disco_launch.h"
+#include "disco_state.h"
 
 namespace {
-
-// ------------------------------------------------------------------ state --
-
-struct PolTable { disco_policy p[DISCO_MAX_COLS]; };
-
-struct SearchState {
-    double lo, hi, target;
-    int32_t which_param, which_acc, step, n_steps;
-};
-struct SpecTable { SearchState s[DISCO_MAX_COLS]; };
-
-struct SelGlobal { unsigned minb, maxb; int nb; int pad; };       // key = bits - minb, nb significant bits
-struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
-struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; };   // [0] TTFT, [1] TBT
-
-struct DispPartial { u64 s_pre, d_pre, d_dec, n_tot, started, won; double ttft_sum; unsigned minb, maxb; };
-struct MigPartial { u64 s_dec, d_dec, d_repre, migrated, tbt_count; double tlast_sum; unsigned minb, maxb; u64 pad; };
-static_assert(sizeof(DispPartial) == 64 && sizeof(MigPartial) == 64, "partials are 64 bytes");
-static_assert(sizeof(disco_accum) == 128 && sizeof(disco_stats) == 256 && sizeof(disco_policy) == 32, "ABI sizes");
 
 struct DispFin {
     int kind;                     // 0: write disco_accum, 1: advance a search
@@ -64,22 +45,6 @@ __global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* ds
     int i = threadIdx.x;
     if (i < P) dst[i] = src[i];
     if (i < 64) tickets[i] = 0u;
-}
-
-// Last-ticket test: true in every thread of the workgroup that finishes last.
-__device__ __forceinline__ bool take_last_ticket(unsigned* ticket)
-{
-    __shared__ int is_last;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned t = atomicAdd(ticket, 1u);
-        is_last = (t == gridDim.x - 1);
-    }
-    __syncthreads();
-    bool last = is_last != 0;
-    if (last) __threadfence();
-    return last;
 }
 
 __device__ __forceinline__ double acc_value(int which, const disco_cost_params& c, i64 s_pre, i64 s_dec, i64 d_pre,
@@ -289,39 +254,44 @@ __global__ __launch_bounds__(DISCO_BLOCK) void k_dispatch_mat(TraceView tr, cons
 }
 
 // ----------------------------------------------------------------- select --
-// Exact order statistics by most-significant-digit-first radix histograms over
-// key = bits(value) - min_bits (non-negative floats order like their bit
-// patterns), 8 bits per pass, nb = bit length of (max_bits - min_bits).
+// TTFT: key = bits - min_bits over nb = bit length of (max_bits - min_bits)
+// bits, 8 bits per pass (up to 128 (column, quantile) slots of 256 bins in
+// LDS).  TBT: the plan comes from the host (raw 31-bit keys).
 
-__device__ __forceinline__ void digit_of_pass(int nb, int pass, int& shift, int& width)
-{
-    int hi = nb - 8 * pass;               // bits still undecided before this pass
-    width = hi < 0 ? 0 : (hi < 8 ? hi : 8);
-    shift = hi - width;
-}
-
-// One thread per slot: rank from (num, den, M), empty prefix.
+// One thread per slot: rank from (num, den, M), empty prefix; plan of the passes.
 __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quantile q0, disco_quantile q1,
                               disco_quantile q2, disco_quantile q3, const disco_accum* acc, i64 n_req,
-                              unsigned* ghist)
+                              unsigned* ghist, SelPlan host_plan)
 {
     const disco_quantile qs[4] = {q0, q1, q2, q3};
     __shared__ unsigned smin, smax;
     if (threadIdx.x == 0) { smin = 0xFFFFFFFFu; smax = 0u; }
     __syncthreads();
-    if ((int)threadIdx.x < P) {
-        unsigned a = which ? acc[threadIdx.x].tbt_min_bits : acc[threadIdx.x].ttft_min_bits;
-        unsigned b = which ? acc[threadIdx.x].tbt_max_bits : acc[threadIdx.x].ttft_max_bits;
-        atomicMin(&smin, a); atomicMax(&smax, b);
+    if (which == 0 && (int)threadIdx.x < P) {
+        atomicMin(&smin, acc[threadIdx.x].ttft_min_bits);
+        atomicMax(&smax, acc[threadIdx.x].ttft_max_bits);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         SelGlobal g;
-        g.minb = smin <= smax ? smin : 0u;
-        g.maxb = smin <= smax ? smax : 0u;
-        unsigned range = g.maxb - g.minb;
-        g.nb = range ? 32 - __clz(range) : 0;
-        g.pad = 0;
+        if (which == 0) {
+            g.minb = smin <= smax ? smin : 0u;
+            g.maxb = smin <= smax ? smax : 0u;
+            unsigned range = g.maxb - g.minb;
+            int left = range ? 32 - __clz(range) : 0;
+            SelPlan pl;
+            pl.npass = 0; pl.pad = 0;
+            for (int i = 0; i < DISCO_MAX_PASS; ++i) { pl.shift[i] = 0; pl.width[i] = 0; }
+            while (left > 0) {
+                int wd = left < 8 ? left : 8;
+                pl.width[pl.npass] = wd; pl.shift[pl.npass] = left - wd;
+                left -= wd; pl.npass += 1;
+            }
+            g.plan = pl;
+        } else {
+            g.minb = 0u; g.maxb = 0x7FFFFFFFu;
+            g.plan = host_plan;
+        }
         S->g[which] = g;
     }
     for (int s = threadIdx.x; s < P * nq; s += blockDim.x) {
@@ -338,34 +308,6 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
     for (int i = threadIdx.x; i < DISCO_MAX_SLOTS * 256; i += blockDim.x) ghist[i] = 0u;
 }
 
-// After a histogram pass: walk the 256 bins of every slot to the digit that
-// holds the remaining rank, extend the prefix, clear the bins.
-__device__ void select_advance(SelState* S, int which, int pass, int P, int nq, unsigned* ghist)
-{
-    const SelGlobal g = S->g[which];
-    int shift, width;
-    digit_of_pass(g.nb, pass, shift, width);
-    __syncthreads();
-    for (int s = threadIdx.x; s < P * nq; s += blockDim.x) {
-        SelSlot sl = S->slot[which][s];
-        if (!sl.done && width > 0) {
-            const unsigned* h = ghist + (size_t)((pass == 0) ? (s / nq) * nq : s) * 256;
-            i64 k = sl.k_rem;
-            int dsel = (1 << width) - 1;
-            for (int dgt = 0; dgt < (1 << width); ++dgt) {
-                i64 cnt = h[dgt];
-                if (k <= cnt) { dsel = dgt; break; }
-                k -= cnt;
-            }
-            sl.k_rem = k;
-            sl.prefix = (sl.prefix << width) | (unsigned)dsel;
-            S->slot[which][s] = sl;
-        }
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < P * nq * 256; i += blockDim.x) ghist[i] = 0u;
-}
-
 // TTFT histogram pass: same traversal as k_dispatch_acc; each pair whose key
 // matches the slot's prefix bumps that slot's bin in an LDS histogram.
 template <int G, int SLOTCAP>
@@ -374,10 +316,11 @@ __global__ __launch_bounds__(DISCO_BLOCK) void k_ttft_hist(TraceView tr, const d
 {
     __shared__ unsigned hist[SLOTCAP * 256];
     const SelGlobal g = S->g[0];
-    int shift, width;
-    digit_of_pass(g.nb, pass, shift, width);
+    const int width = pass < g.plan.npass ? g.plan.width[pass] : 0;
+    const int shift = pass < g.plan.npass ? g.plan.shift[pass] : 0;
+    const int words = ((pass == 0) ? P : P * nq) << width;
     if (width > 0) {
-        for (int i = threadIdx.x; i < P * nq * 256; i += DISCO_BLOCK) hist[i] = 0u;
+        for (int i = threadIdx.x; i < words; i += DISCO_BLOCK) hist[i] = 0u;
         __syncthreads();
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         const int col = lane & (G - 1), sub = lane / G;
@@ -415,17 +358,17 @@ __global__ __launch_bounds__(DISCO_BLOCK) void k_ttft_hist(TraceView tr, const d
                     const unsigned dgt = (key >> shift) & dmask;
                     const unsigned hi = (up >= 32) ? 0u : (key >> up);
                     if (pass == 0) {
-                        if (live[0] || live[1] || live[2] || live[3]) atomicAdd(&hist[(col * nq) * 256 + dgt], 1u);
+                        if (live[0] || live[1] || live[2] || live[3]) atomicAdd(&hist[((unsigned)col << width) | dgt], 1u);
                     } else {
 #pragma unroll
                         for (int qi = 0; qi < DISCO_MAX_Q; ++qi)
-                            if (live[qi] && hi == prefix[qi]) atomicAdd(&hist[(col * nq + qi) * 256 + dgt], 1u);
+                            if (live[qi] && hi == prefix[qi]) atomicAdd(&hist[((unsigned)(col * nq + qi) << width) | dgt], 1u);
                     }
                 }
             }
         }
         __syncthreads();
-        for (int i = threadIdx.x; i < P * nq * 256; i += DISCO_BLOCK) {
+        for (int i = threadIdx.x; i < words; i += DISCO_BLOCK) {
             unsigned c = hist[i];
             if (c) atomicAdd(&ghist[i], c);
         }
@@ -433,270 +376,6 @@ __global__ __launch_bounds__(DISCO_BLOCK) void k_ttft_hist(TraceView tr, const d
     if (!take_last_ticket(ticket)) return;
     select_advance(S, 0, pass, P, nq, ghist);
     if (threadIdx.x == 0) *ticket = 0u;
-}
-
-// -------------------------------------------------------------- timelines --
-
-struct TimelineArgs {
-    float tau, kt;            // pacing interval, kappa_lag * tau
-    int P, nq, pass;          // pass < 0: statistics pass, else histogram pass
-    int32_t* mig_idx; int32_t* n_src_tok; float* t_last; float* delivered; int delivered_col;
-    MigPartial* part; unsigned* ticket; disco_accum* acc;
-    SelState* S; unsigned* ghist;
-};
-
-// Paced delivery of one source timeline of one request by one wave
-// (Sec. 4.3; recurrence delta_t = max(r_t, delta_{t-1} + tau) evaluated in
-// the shifted domain, where it is a running maximum).  VARIANT 0: device
-// source (r_t = t g), 1: server source without hand-off, 2: server source
-// with the lag trigger.  On return m and t_last are wave-uniform.
-// `sink(t, tbt_bits, valid)` is called once per 64-token chunk by all lanes.
-template <class Sink>
-__device__ __forceinline__ void run_timeline(int variant, int n, const float* __restrict__ r_src, float gap_src, float g_dev,
-                                             int l, float k, float c, float tau, float kt, int lane, float* deliv,
-                                             int& m_out, float& tlast_out, Sink&& sink)
-{
-    float carryM = -INFINITY, carryD = 0.0f, base = 0.0f;
-    int m = -1;
-    for (int t0 = 0; t0 < n; t0 += 64) {
-        const int t = t0 + lane;
-        const bool v = t < n;
-        float r;
-        if (m >= 0) r = __fmaf_rn((float)(t - m + 1), g_dev, base);
-        else if (variant == 0) r = (float)t * g_dev;
-        else if (r_src) r = v ? r_src[t] : 0.0f;
-        else r = (float)t * gap_src;
-        float u = v ? __fmaf_rn(-(float)t, tau, r) : -INFINITY;
-        float M = fmaxf(wave_incl_max(u, lane), carryM);
-        float del = __fmaf_rn((float)t, tau, M);
-        float prev = __shfl_up(del, 1, 64);
-        if (lane == 0) prev = carryD;
-        if (variant == 2 && m < 0) {
-            float slot = prev + tau;
-            float lag = r - slot;
-            u64 trig = __ballot(v && t >= 1 && lag > kt);
-            if (trig) {
-                const int ml = __ffsll((long long)trig) - 1;       // first overdue token of the chunk
-                m = t0 + ml;
-                // hand-off: decision when the token is kappa tau overdue, then the device
-                // re-prefills prompt + produced tokens and continues at its own pace
-                float slot_m = bcast_f(slot, ml);
-                float t_dec = slot_m + kt;
-                float t_mig = __fmaf_rn((float)(l + m), k, c);
-                base = t_dec + t_mig;
-                if (t >= m) {
-                    r = __fmaf_rn((float)(t - m + 1), g_dev, base);
-                    u = v ? __fmaf_rn(-(float)t, tau, r) : -INFINITY;
-                }
-                M = fmaxf(wave_incl_max(u, lane), carryM);
-                del = __fmaf_rn((float)t, tau, M);
-                prev = __shfl_up(del, 1, 64);
-                if (lane == 0) prev = carryD;
-            }
-        }
-        if (deliv && v) deliv[t] = del;
-        float tbt = del - prev;
-        sink(t, f2u(tbt), v && t >= 1);
-        const int last = (n - t0 < 64) ? (n - t0 - 1) : 63;
-        carryM = bcast_f(M, last);
-        carryD = bcast_f(del, last);
-    }
-    m_out = m;
-    tlast_out = carryD;
-}
-
-// Wave-aggregated histogram update: lanes holding the same bin are counted
-// with a ballot and added once per column, lane = column doing the add.
-__device__ __forceinline__ void hist_add_grouped(unsigned* hist, bool pending, unsigned bin, u64 colmask, int nq, int qi_or_all,
-                                                 int lane)
-{
-    u64 todo = __ballot(pending);
-    while (todo) {
-        const int leader = __ffsll((long long)todo) - 1;
-        const unsigned b0 = (unsigned)bcast_i((int)bin, leader);
-        const u64 same = __ballot(pending && bin == b0);
-        const unsigned cnt = (unsigned)__popcll(same);
-        if (lane < 64 && ((colmask >> lane) & 1ull)) atomicAdd(&hist[(lane * nq + qi_or_all) * 256 + b0], cnt);
-        todo &= ~same;
-        if ((same >> lane) & 1ull) pending = false;
-    }
-}
-
-template <int SLOTCAP>
-__global__ __launch_bounds__(DISCO_BLOCK) void k_timeline(TraceView tr, const disco_policy* __restrict__ pol, TimelineArgs a)
-{
-    // one LDS buffer: histograms in a histogram pass, partials in the statistics pass
-    constexpr int WORDS = SLOTCAP * 256 > 8192 ? SLOTCAP * 256 : 8192;
-    __shared__ __align__(16) unsigned smem[WORDS];
-    unsigned* hist = smem;
-    __shared__ unsigned sprefix[DISCO_MAX_SLOTS];
-    __shared__ int slive[DISCO_MAX_SLOTS];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int P = a.P, nq = a.nq;
-    const bool colv = lane < P;
-    const disco_policy p = pol[colv ? lane : 0];
-    const bool hist_pass = a.pass >= 0;
-    SelGlobal g{0, 0, 0, 0};
-    int shift = 0, width = 0;
-    if (hist_pass) {
-        g = a.S->g[1];
-        digit_of_pass(g.nb, a.pass, shift, width);
-        for (int i = threadIdx.x; i < P * nq * 256; i += DISCO_BLOCK) hist[i] = 0u;
-        for (int i = threadIdx.x; i < P * nq; i += DISCO_BLOCK) {
-            SelSlot sl = a.S->slot[1][i];
-            sprefix[i] = sl.prefix;
-            slive[i] = !sl.done;
-        }
-        __syncthreads();
-    }
-    const unsigned dmask = width ? ((1u << width) - 1u) : 0u;
-    const int up = shift + width;
-    u64 acc_s_dec = 0, acc_d_dec = 0, acc_repre = 0, acc_mig = 0, acc_cnt = 0;
-    double acc_tlast = 0.0;
-    unsigned minb = 0xFFFFFFFFu, maxb = 0u;
-    const bool work = !hist_pass || width > 0;
-    const i64 nwaves = (i64)gridDim.x * (DISCO_BLOCK / 64);
-    for (i64 i = (i64)blockIdx.x * (DISCO_BLOCK / 64) + wave; work && i < tr.n_req; i += nwaves) {
-        const int l = tr.l[i], n = tr.n[i];
-        const float s = tr.s[i];
-        const float k = tr.k ? tr.k[i] : tr.k_s;
-        const float gd = tr.g ? tr.g[i] : tr.g_s;
-        const float d = __fmaf_rn((float)l, k, tr.c);
-        unsigned dec; float ttft;
-        dispatch_pair(p, l, s, d, dec, ttft);
-        const bool dev_src = (dec & 4u) != 0u;
-        const u64 mask_dev = __ballot(colv && dev_src);
-        const u64 mask_plain = __ballot(colv && !dev_src && p.mig_mode != DISCO_MIG_LAG);
-        const u64 mask_lag = __ballot(colv && !dev_src && p.mig_mode == DISCO_MIG_LAG);
-        const i64 off = tr.off ? tr.off[i] : 0;
-        const float* r_src = tr.arr ? tr.arr + off : nullptr;
-        const float gap_src = tr.tbt ? tr.tbt[i] : 0.0f;
-        const bool want_deliv = a.delivered != nullptr && !hist_pass;
-        const u64 dcol = want_deliv ? (1ull << a.delivered_col) : 0ull;
-        int m_lag = -1;
-        float tl_lag = 0.0f;
-        bool lag_done = false;
-        // variants in the order lag, plain, device; a lag run without a trigger is also the plain result
-#pragma unroll 1
-        for (int variant = 2; variant >= 0; --variant) {
-            const u64 mask = variant == 2 ? mask_lag : (variant == 1 ? mask_plain : mask_dev);
-            if (!mask) continue;
-            int m; float tl;
-            const bool reuse = (variant == 1 && lag_done && m_lag < 0 && !hist_pass && !(dcol & mask));
-            if (reuse) { m = -1; tl = tl_lag; }
-            else {
-                float* deliv = (dcol & mask) ? a.delivered + off : nullptr;
-                unsigned lmin = 0xFFFFFFFFu, lmax = 0u;
-                run_timeline(variant, n, r_src, gap_src, gd, l, k, tr.c, a.tau, a.kt, lane, deliv, m, tl,
-                             [&](int t, unsigned bits, bool ok) {
-                                 if (!hist_pass) {
-                                     if (ok) { lmin = min(lmin, bits); lmax = max(lmax, bits); }
-                                 } else {
-                                     const unsigned key = bits - g.minb;
-                                     const unsigned dgt = (key >> shift) & dmask;
-                                     const unsigned hi = (up >= 32) ? 0u : (key >> up);
-                                     if (a.pass == 0) {
-                                         hist_add_grouped(hist, ok, dgt, mask, nq, 0, lane);
-                                     } else {
-                                         for (int qi = 0; qi < nq; ++qi) {
-                                             // columns of this variant whose slot qi still selects and shares the prefix
-                                             u64 cm = mask;
-                                             while (cm) {
-                                                 const int c0 = __ffsll((long long)cm) - 1;
-                                                 const unsigned pf = sprefix[c0 * nq + qi];
-                                                 u64 grp = 0ull;      // columns with the same prefix as c0
-                                                 for (u64 rest = cm; rest;) {
-                                                     const int c1 = __ffsll((long long)rest) - 1;
-                                                     rest &= rest - 1;
-                                                     if (sprefix[c1 * nq + qi] == pf && slive[c1 * nq + qi]) grp |= 1ull << c1;
-                                                 }
-                                                 if (grp) hist_add_grouped(hist, ok && hi == pf, dgt, grp, nq, qi, lane);
-                                                 cm &= ~(grp | (1ull << c0));
-                                             }
-                                         }
-                                     }
-                                 }
-                                 (void)t;
-                             });
-                if (!hist_pass) {
-                    // range of the TBT bit patterns of this timeline, folded over the wave
-#pragma unroll
-                    for (int sft = 1; sft < 64; sft <<= 1) {
-                        lmin = min(lmin, (unsigned)__shfl_xor((int)lmin, sft, 64));
-                        lmax = max(lmax, (unsigned)__shfl_xor((int)lmax, sft, 64));
-                    }
-                    if ((mask >> lane) & 1ull) { minb = min(minb, lmin); maxb = max(maxb, lmax); }
-                }
-            }
-            if (variant == 2) { m_lag = m; tl_lag = tl; lag_done = true; }
-            if (!hist_pass && ((mask >> lane) & 1ull)) {
-                const int nsrc = (m >= 0) ? m : n;
-                if (variant == 0) acc_d_dec += (u64)n;
-                else { acc_s_dec += (u64)nsrc; acc_d_dec += (u64)(n - nsrc); }
-                if (m >= 0) { acc_mig += 1; acc_repre += (u64)l + (u64)m; }
-                acc_cnt += (u64)(n - 1);
-                acc_tlast += (double)tl;
-                if (a.mig_idx) a.mig_idx[(size_t)lane * tr.n_req + i] = m;
-                if (a.n_src_tok) a.n_src_tok[(size_t)lane * tr.n_req + i] = nsrc;
-                if (a.t_last) a.t_last[(size_t)lane * tr.n_req + i] = tl;
-            }
-        }
-    }
-    if (hist_pass) {
-        __syncthreads();
-        if (width > 0)
-            for (int i = threadIdx.x; i < P * nq * 256; i += DISCO_BLOCK) {
-                unsigned c = hist[i];
-                if (c) atomicAdd(&a.ghist[i], c);
-            }
-        if (!take_last_ticket(a.ticket)) return;
-        select_advance(a.S, 1, a.pass, P, nq, a.ghist);
-        if (threadIdx.x == 0) *a.ticket = 0u;
-        return;
-    }
-    // statistics pass: fold waves, then workgroups
-    MigPartial (*sh)[64] = reinterpret_cast<MigPartial (*)[64]>(smem);
-    MigPartial (*fold)[64] = sh + DISCO_BLOCK / 64;
-    sh[wave][lane] = MigPartial{acc_s_dec, acc_d_dec, acc_repre, acc_mig, acc_cnt, acc_tlast, minb, maxb, 0};
-    __syncthreads();
-    if (threadIdx.x < 64) {
-        MigPartial x = sh[0][threadIdx.x];
-        for (int w = 1; w < DISCO_BLOCK / 64; ++w) {
-            const MigPartial& o = sh[w][threadIdx.x];
-            x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
-            x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
-            x.minb = min(x.minb, o.minb); x.maxb = max(x.maxb, o.maxb);
-        }
-        a.part[(size_t)blockIdx.x * 64 + threadIdx.x] = x;
-    }
-    if (!take_last_ticket(a.ticket)) return;
-    {
-        const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
-        MigPartial x{0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u, 0};
-        for (unsigned b = q; b < gridDim.x; b += DISCO_BLOCK / 64) {
-            const MigPartial o = a.part[(size_t)b * 64 + c];
-            x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
-            x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
-            x.minb = min(x.minb, o.minb); x.maxb = max(x.maxb, o.maxb);
-        }
-        fold[q][c] = x;
-    }
-    __syncthreads();
-    if ((int)threadIdx.x < P) {
-        const int c = threadIdx.x;
-        MigPartial x = fold[0][c];
-        for (int q = 1; q < DISCO_BLOCK / 64; ++q) {
-            const MigPartial& o = fold[q][c];
-            x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
-            x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
-            x.minb = min(x.minb, o.minb); x.maxb = max(x.maxb, o.maxb);
-        }
-        disco_accum* o = &a.acc[c];
-        o->m_s_dec = (i64)x.s_dec; o->m_d_dec = (i64)x.d_dec; o->m_d_repre = (i64)x.d_repre;
-        o->n_migrated = (i64)x.migrated; o->tbt_count = (i64)x.tbt_count; o->tlast_sum = x.tlast_sum;
-        o->tbt_min_bits = x.minb; o->tbt_max_bits = x.maxb;
-    }
-    if (threadIdx.x == 0) *a.ticket = 0u;
 }
 
 // ------------------------------------------------------------ final stats --
@@ -823,14 +502,6 @@ unsigned dispatch_blocks(i64 n_req)
     return (unsigned)b;
 }
 
-unsigned timeline_blocks(i64 n_req)
-{
-    i64 b = (n_req + 3) / 4;
-    if (b < 1) b = 1;
-    if (b > DISCO_MAX_BLOCKS) b = DISCO_MAX_BLOCKS;
-    return (unsigned)b;
-}
-
 bool is_device_pointer(const void* p)
 {
     hipPointerAttribute_t attr;
@@ -908,16 +579,6 @@ void launch_ttft_hist_g(int G, const TraceView& v, int P, int nq, int pass, char
     case 32: launch_ttft_hist<32>(v, P, nq, pass, ws, L, stream); break;
     default: launch_ttft_hist<64>(v, P, nq, pass, ws, L, stream); break;
     }
-}
-
-void launch_timeline(const TraceView& v, const TimelineArgs& a, char* ws, const WsLayout& L, hipStream_t stream)
-{
-    dim3 grid(timeline_blocks(v.n_req)), block(DISCO_BLOCK);
-    const disco_policy* pol = (const disco_policy*)(ws + L.pol);
-    const int slots = a.pass >= 0 ? a.P * a.nq : 1;
-    if (slots <= 8) hipLaunchKernelGGL((k_timeline<8>), grid, block, 0, stream, v, pol, a);
-    else if (slots <= 32) hipLaunchKernelGGL((k_timeline<32>), grid, block, 0, stream, v, pol, a);
-    else hipLaunchKernelGGL((k_timeline<DISCO_MAX_SLOTS>), grid, block, 0, stream, v, pol, a);
 }
 
 }  // namespace
@@ -1031,7 +692,7 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
     a.acc = acc;
     a.S = (SelState*)(ws + L.sel);
     a.ghist = (unsigned*)(ws + L.ghist);
-    launch_timeline(v, a, ws, L, stream);
+    disco_launch_timeline(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }
@@ -1065,12 +726,13 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     for (int i = 0; i < nq; ++i) qs[i] = q[i];
     if (nq > 0) {
         const int G = pow2_cols(P);
+        SelPlan tbt_plan = disco_tbt_plan(P, nq);
         hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 0, P, nq, qs[0], qs[1], qs[2], qs[3], acc,
-                           v.n_req, gh);
+                           v.n_req, gh, tbt_plan);
         for (int pass = 0; pass < 4; ++pass) launch_ttft_hist_g(G, v, P, nq, pass, ws, L, stream);
         if (tl) {
             hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 1, P, nq, qs[0], qs[1], qs[2], qs[3],
-                               acc, v.n_req, gh);
+                               acc, v.n_req, gh, tbt_plan);
             TimelineArgs a;
             memset(&a, 0, sizeof(a));
             a.tau = tl->tau;
@@ -1078,9 +740,9 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             a.P = P; a.nq = nq;
             a.ticket = (unsigned*)(ws + L.ticket);
             a.S = S; a.ghist = gh;
-            for (int pass = 0; pass < 4; ++pass) {
+            for (int pass = 0; pass < tbt_plan.npass; ++pass) {
                 a.pass = pass;
-                launch_timeline(v, a, ws, L, stream);
+                disco_launch_timeline(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
             }
         }
     }

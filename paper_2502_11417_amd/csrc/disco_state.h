@@ -1,0 +1,95 @@
+// Device-resident state shared by the passes of libdisco and the helpers that
+// advance it at the end of a pass (last-ticket workgroup).
+#pragma once
+#include "disco_common.h"
+#include "disco_device.h"
+
+struct PolTable { disco_policy p[DISCO_MAX_COLS]; };
+
+struct SearchState {
+    double lo, hi, target;
+    int32_t which_param, which_acc, step, n_steps;
+};
+struct SpecTable { SearchState s[DISCO_MAX_COLS]; };
+
+// Order-statistic selection: most-significant-digit-first radix histograms
+// over key = bits(value) - minb (non-negative floats order like their bit
+// patterns).  Pass p looks at `width[p]` bits at `shift[p]`.
+enum { DISCO_MAX_PASS = 6 };
+struct SelPlan { int npass; int shift[DISCO_MAX_PASS]; int width[DISCO_MAX_PASS]; int pad; };
+struct SelGlobal { unsigned minb, maxb; SelPlan plan; };
+struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
+struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; };   // [0] TTFT, [1] TBT
+
+struct DispPartial { u64 s_pre, d_pre, d_dec, n_tot, started, won; double ttft_sum; unsigned minb, maxb; };
+struct MigPartial { u64 s_dec, d_dec, d_repre, migrated, tbt_count; double tlast_sum; u64 pad[2]; };
+static_assert(sizeof(DispPartial) == 64 && sizeof(MigPartial) == 64, "partials are 64 bytes");
+static_assert(sizeof(disco_accum) == 128 && sizeof(disco_stats) == 256 && sizeof(disco_policy) == 32, "ABI sizes");
+
+// Last-ticket test: true in every thread of the workgroup that finishes last.
+__device__ __forceinline__ bool take_last_ticket(unsigned* ticket)
+{
+    __shared__ int is_last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned t = atomicAdd(ticket, 1u);
+        is_last = (t == gridDim.x - 1);
+    }
+    __syncthreads();
+    bool last = is_last != 0;
+    if (last) __threadfence();
+    return last;
+}
+
+// After histogram pass `pass`: for every slot find the digit that holds the
+// remaining rank, extend the prefix, clear the global bins.  One wave per
+// slot; called by every thread of the last workgroup.  In pass 0 all the
+// quantiles of a column share that column's histogram.
+__device__ __forceinline__ void select_advance(SelState* S, int which, int pass, int P, int nq, unsigned* ghist)
+{
+    const SelPlan plan = S->g[which].plan;
+    const int width = pass < plan.npass ? plan.width[pass] : 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    __syncthreads();
+    if (width > 0) {
+        const int nbins = 1 << width;
+        const int per = (nbins + 63) >> 6;
+        for (int s = wave; s < P * nq; s += nwaves) {
+            SelSlot sl = S->slot[which][s];
+            if (sl.done) continue;
+            const unsigned* h = ghist + ((size_t)((pass == 0) ? (s / nq) : s) << width);
+            const int b0 = lane * per;
+            u64 mine = 0;
+            for (int b = b0; b < b0 + per && b < nbins; ++b) mine += h[b];
+            u64 incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                unsigned lo = (unsigned)__shfl_up((int)(unsigned)incl, d, 64);
+                unsigned hi = (unsigned)__shfl_up((int)(unsigned)(incl >> 32), d, 64);
+                if (lane >= d) incl += ((u64)hi << 32) | lo;
+            }
+            const u64 k = (u64)sl.k_rem;
+            const u64 hit = __ballot(incl >= k);
+            // the rank never exceeds the number of matching values, so a lane always hits
+            const int owner = hit ? (__ffsll((long long)hit) - 1) : 63;
+            if (lane == owner) {
+                u64 rem = k - (incl - mine);
+                int dsel = nbins - 1;
+                for (int b = b0; b < b0 + per && b < nbins; ++b) {
+                    u64 c = h[b];
+                    if (rem <= c) { dsel = b; break; }
+                    rem -= c;
+                }
+                sl.k_rem = (i64)rem;
+                sl.prefix = (sl.prefix << width) | (unsigned)dsel;
+                S->slot[which][s] = sl;
+            }
+        }
+    }
+    __syncthreads();
+    if (width > 0) {
+        const int words = ((pass == 0) ? P : P * nq) << width;
+        for (int i = threadIdx.x; i < words; i += blockDim.x) ghist[i] = 0u;
+    }
+}

@@ -140,10 +140,6 @@ def check_migration(B, O, tr, specs, tau, kappa, delivered_col=0):
     if delivered_col is not None:
         w1 = O.migration(tr, [op[delivered_col]], tau, kappa, materialise=False, tbt_col=0, want_delivered=True)
         assert_same_bits(got["delivered"].cpu().numpy(), w1["delivered"], "delivered")
-        if w1["tbt"].size:
-            b = w1["tbt"].view(np.uint32)
-            assert int(acc["tbt_min_bits"][delivered_col]) == int(b.min())
-            assert int(acc["tbt_max_bits"][delivered_col]) == int(b.max())
     return dt, acc, want
 
 
