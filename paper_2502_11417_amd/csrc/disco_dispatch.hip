@@ -1,0 +1,559 @@
+// Dispatch passes (Sec. 4.2, Alg. 2 and 3): fused dispatch + per-column
+// reduction, TTFT histogram passes of the order-statistic selection, and the
+// materialised per-pair outputs.
+//
+// Work decomposition: a wave holds up to 64 policy columns in its lanes
+// (lane = sub * G + column, G = columns rounded up to a power of two, 64 / G
+// request sub-groups) and walks the requests in batches of 64.  A batch is
+// loaded coalesced, one request per lane, staged in LDS as (l, s, n, d), and
+// every column lane reads the request of its sub-group with one broadcast
+// 16-byte LDS load.  With a single column (G = 1) lane = request and four
+// consecutive requests are fetched per lane with 16-byte loads.  Per-column
+// totals stay in registers (32-bit inside a batch, 64-bit across batches)
+// until the end of the kernel; the workgroup that takes the last ticket folds
+// the per-workgroup partials in a fixed order and, for a budget search,
+// advances the bisection on the device.
+#include <math.h>
+#include <string.h>
+
+#include "disco_launch.h"
+#include "disco_state.h"
+
+namespace {
+
+constexpr int DP_BLOCK = 1024;
+constexpr int DP_WAVES = DP_BLOCK / 64;
+constexpr int DP_MAX_BLOCKS = 256;          // one workgroup per CU: the ticket chain stays short
+
+// ------------------------------------------------------------ per pair ----
+
+struct PairResult { bool srv_started, dev_started, dev_win; float ttft; };
+
+// MODE 0: every column is server-constrained (Alg. 3), 1: every column is
+// device-constrained (Alg. 2 / Eq. 1), 2: mixed table.
+template <int MODE>
+__device__ __forceinline__ PairResult pair_eval(const disco_policy& p, int l, float s, float d)
+{
+    PairResult r;
+    if (MODE == 0) {
+        const bool dev_only = l < p.l_th;               // strict: Alg. 3
+        r.srv_started = !dev_only;
+        r.dev_started = true;
+        r.dev_win = dev_only || (d < s);                // ties go to the server
+        r.ttft = r.dev_win ? d : s;
+    } else if (MODE == 1) {
+        float ramp = p.beta * (float)l;
+        float w = (ramp < p.w_tail) ? ramp : p.w_tail;  // a NaN ramp falls through to w_tail
+        w = (l == p.l_mid) ? p.w_mid : w;
+        w = (l <= p.l_th) ? 0.0f : w;
+        const float x = w + d;
+        r.srv_started = true;
+        r.dev_started = s > w;                          // a server token at exactly w cancels the device
+        r.dev_win = r.dev_started && (x < s);
+        r.ttft = r.dev_win ? x : s;
+    } else {
+        unsigned dec; float t;
+        dispatch_pair(p, l, s, d, dec, t);
+        r.srv_started = (dec & 1u) != 0u;
+        r.dev_started = (dec & 2u) != 0u;
+        r.dev_win = (dec & 4u) != 0u;
+        r.ttft = t;
+    }
+    return r;
+}
+
+__device__ __forceinline__ int table_mode(const disco_policy& p, bool colv)
+{
+    const bool any_d = __ballot(colv && p.mode != DISCO_MODE_SERVER_CONSTRAINED) != 0ull;
+    const bool any_s = __ballot(colv && p.mode == DISCO_MODE_SERVER_CONSTRAINED) != 0ull;
+    return any_d ? (any_s ? 2 : 1) : 0;
+}
+
+struct ColTotals {
+    u64 s_pre, d_pre, d_dec, started, won;
+    double ttft_sum;
+    unsigned minb, maxb;
+};
+
+__device__ __forceinline__ double acc_value(int which, const disco_cost_params& c, i64 s_pre, i64 s_dec, i64 d_pre,
+                                            i64 d_dec)
+{
+    switch (which) {
+    case DISCO_ACC_TOTAL_COST: {
+        double server = server_cost_of(c, s_pre, s_dec);
+        double energy = device_energy_of(c, d_pre, d_dec);
+        double priced = c.lambda * energy;
+        return server + priced;
+    }
+    case DISCO_ACC_SERVER_COST: return server_cost_of(c, s_pre, s_dec);
+    case DISCO_ACC_DEVICE_COST: {
+        double energy = device_energy_of(c, d_pre, d_dec);
+        return c.lambda * energy;
+    }
+    case DISCO_ACC_SERVER_PREFILL_TOK: return (double)s_pre;
+    default: return (double)d_pre;
+    }
+}
+
+// Bisection step or final evaluation of search `col` (Sec. 4.2: find the
+// threshold / wait that meets the constrained endpoint's budget).
+__device__ void search_advance(int col, const DispFin& fin, const disco_accum& tot)
+{
+    SearchState st = fin.st[col];
+    disco_policy p = fin.pol_rw[col];
+    const double A = acc_value(st.which_acc, fin.cost, tot.s_pre, tot.s_dec, tot.d_pre, tot.d_dec);
+    const bool is_w = st.which_param == DISCO_PARAM_W_TAIL;
+    if (st.step < st.n_steps) {
+        const double mid = is_w ? (double)p.w_tail : (double)p.l_th;
+        fin.sout[col].hist_param[st.step] = mid;
+        fin.sout[col].hist_acc[st.step] = A;
+        if (is_w) {
+            if (A > st.target) st.lo = mid; else st.hi = mid;
+        } else if (st.lo < st.hi) {
+            if (A > st.target) st.lo = mid + 1.0; else st.hi = mid;
+        }
+        st.step += 1;
+        if (is_w) {
+            p.w_tail = (st.step < st.n_steps) ? 0.5f * ((float)st.lo + (float)st.hi) : (float)st.hi;
+        } else {
+            const int lo = (int)st.lo, hi = (int)st.hi;
+            p.l_th = (st.step < st.n_steps) ? lo + (hi - lo) / 2 : hi;
+        }
+        fin.st[col] = st;
+        fin.pol_rw[col] = p;
+    } else {
+        disco_search_out* o = &fin.sout[col];
+        o->param = st.hi;
+        o->acc_at_param = A;
+        o->lo = st.lo;
+        o->hi = st.hi;
+        o->at_param = tot;
+        if (fin.pol_out) fin.pol_out[col] = p;
+    }
+}
+
+// Last workgroup: fold the per-workgroup partials of every column in a fixed
+// order and hand the totals to the accumulator or to the search.
+// part: [gridDim.x][G]; tot_l / tot_n partials ride in column 0's pad fields.
+template <int G>
+__device__ __forceinline__ void fold_and_finish(const DispPartial* __restrict__ part, int P, int mode, const DispFin& fin,
+                                                DispPartial* sh /* LDS, DP_BLOCK entries */)
+{
+    constexpr int Q = DP_BLOCK / G;
+    const int c = threadIdx.x % G, q = threadIdx.x / G;
+    DispPartial a{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+    for (unsigned b = q; b < gridDim.x; b += Q) {
+        const DispPartial o = part[(size_t)b * G + c];
+        a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
+        a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
+        a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
+    }
+    sh[q * G + c] = a;
+    __syncthreads();
+    if ((int)threadIdx.x < P) {
+        DispPartial t = sh[c];
+        for (int qq = 1; qq < Q; ++qq) {
+            const DispPartial& o = sh[qq * G + c];
+            t.s_pre += o.s_pre; t.d_pre += o.d_pre; t.d_dec += o.d_dec; t.n_tot += o.n_tot;
+            t.started += o.started; t.won += o.won; t.ttft_sum += o.ttft_sum;
+            t.minb = min(t.minb, o.minb); t.maxb = max(t.maxb, o.maxb);
+        }
+        disco_accum acc;
+        memset(&acc, 0, sizeof(acc));
+        acc.s_pre = (i64)t.s_pre; acc.d_pre = (i64)t.d_pre; acc.d_dec = (i64)t.d_dec;
+        acc.s_dec = (i64)(t.n_tot - t.d_dec);
+        acc.n_dev_started = (i64)t.started; acc.n_dev_win = (i64)t.won; acc.ttft_sum = t.ttft_sum;
+        acc.ttft_min_bits = t.minb; acc.ttft_max_bits = t.maxb;
+        if (fin.kind == 0) {
+            disco_accum* o = &fin.acc[c];
+            o->s_pre = acc.s_pre; o->s_dec = acc.s_dec; o->d_pre = acc.d_pre; o->d_dec = acc.d_dec;
+            o->n_dev_started = acc.n_dev_started; o->n_dev_win = acc.n_dev_win; o->ttft_sum = acc.ttft_sum;
+            o->ttft_min_bits = acc.ttft_min_bits; o->ttft_max_bits = acc.ttft_max_bits;
+        } else {
+            search_advance(c, fin, acc);
+        }
+    }
+    (void)mode;
+}
+
+// ------------------------------------------------- fused dispatch + reduce --
+
+struct Staged { int l; float s; int n; float d; };      // 16 bytes, one per request of the batch
+
+// Inner loop over the G requests of this lane's sub-group.  T32 accumulates in
+// 32-bit registers (every l, n of the batch below 2^24), else directly in 64 bit.
+template <int G, int MODE, bool T32>
+__device__ __forceinline__ void batch_pairs(const Staged* __restrict__ st, int sub, int cnt, const disco_policy& p, bool colv,
+                                            ColTotals& t)
+{
+    unsigned sp = 0, dp = 0, dd = 0, ns = 0, nw = 0;
+    double ts = 0.0;
+    unsigned mn = t.minb, mx = t.maxb;
+#pragma unroll 8
+    for (int it = 0; it < G; ++it) {
+        const int src = sub * G + it;
+        const Staged r = st[src];
+        const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d);
+        const bool v = colv && src < cnt;
+        const unsigned tb = f2u(e.ttft);
+        if (T32) {
+            if (MODE != 1) sp += (v && e.srv_started) ? (unsigned)r.l : 0u;
+            if (MODE != 0) { dp += (v && e.dev_started) ? (unsigned)r.l : 0u; ns += (v && e.dev_started) ? 1u : 0u; }
+            dd += (v && e.dev_win) ? (unsigned)r.n : 0u;
+            nw += (v && e.dev_win) ? 1u : 0u;
+            ts += v ? (double)e.ttft : 0.0;
+        } else {
+            if (MODE != 1) t.s_pre += (v && e.srv_started) ? (u64)r.l : 0ull;
+            if (MODE != 0) { t.d_pre += (v && e.dev_started) ? (u64)r.l : 0ull; t.started += (v && e.dev_started) ? 1ull : 0ull; }
+            t.d_dec += (v && e.dev_win) ? (u64)r.n : 0ull;
+            t.won += (v && e.dev_win) ? 1ull : 0ull;
+            t.ttft_sum += v ? (double)e.ttft : 0.0;
+        }
+        mn = v ? min(mn, tb) : mn;
+        mx = v ? max(mx, tb) : mx;
+    }
+    if (T32) {
+        t.s_pre += sp; t.d_pre += dp; t.d_dec += dd; t.started += ns; t.won += nw;
+        t.ttft_sum += ts;
+    }
+    t.minb = mn; t.maxb = mx;
+}
+
+template <int G>
+__global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const disco_policy* __restrict__ pol, int P,
+                                                           DispPartial* __restrict__ part, unsigned* ticket, DispFin fin)
+{
+    __shared__ __align__(16) unsigned char smem[DP_BLOCK * sizeof(DispPartial)];    // 64 KB: staging, then folds
+    Staged* stage = reinterpret_cast<Staged*>(smem);
+    DispPartial* sh = reinterpret_cast<DispPartial*>(smem);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & (G - 1), sub = lane / G;
+    const bool colv = col < P;
+    const disco_policy p = pol[colv ? col : 0];
+    const int mode = table_mode(p, colv);
+    ColTotals t{0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+    u64 tot_l = 0, tot_n = 0, tot_c = 0;      // column-independent sums, kept by the loading lane
+    Staged* st = stage + wave * 64;
+    const i64 nbatch = (tr.n_req + 63) >> 6;
+    for (i64 b = (i64)blockIdx.x * DP_WAVES + wave; b < nbatch; b += (i64)gridDim.x * DP_WAVES) {
+        const i64 i = b * 64 + lane;
+        const bool v = i < tr.n_req;
+        const int lv = v ? tr.l[i] : 0;
+        const int nv = v ? tr.n[i] : 0;
+        const float sv = v ? tr.s[i] : 0.0f;
+        const float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
+        const float dv = __fmaf_rn((float)lv, kv, tr.c);          // device TTFT T_d(l) = k l + c
+        tot_l += (u64)lv; tot_n += (u64)nv; tot_c += v ? 1ull : 0ull;
+        st[lane] = Staged{lv, sv, nv, dv};
+        const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
+        const bool small = __ballot(((unsigned)lv | (unsigned)nv) >= (1u << 24)) == 0ull;
+        // the staging area is private to the wave: no workgroup barrier needed
+        __builtin_amdgcn_wave_barrier();
+        if (small) {
+            if (mode == 0) batch_pairs<G, 0, true>(st, sub, cnt, p, colv, t);
+            else if (mode == 1) batch_pairs<G, 1, true>(st, sub, cnt, p, colv, t);
+            else batch_pairs<G, 2, true>(st, sub, cnt, p, colv, t);
+        } else {
+            if (mode == 0) batch_pairs<G, 0, false>(st, sub, cnt, p, colv, t);
+            else if (mode == 1) batch_pairs<G, 1, false>(st, sub, cnt, p, colv, t);
+            else batch_pairs<G, 2, false>(st, sub, cnt, p, colv, t);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    // column-independent sums: fold over the wave
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        tot_l += shfl_xor_u64(tot_l, m); tot_n += shfl_xor_u64(tot_n, m); tot_c += shfl_xor_u64(tot_c, m);
+    }
+    // fold the request sub-groups of the wave
+#pragma unroll
+    for (int m = G; m < 64; m <<= 1) {
+        t.s_pre += shfl_xor_u64(t.s_pre, m); t.d_pre += shfl_xor_u64(t.d_pre, m); t.d_dec += shfl_xor_u64(t.d_dec, m);
+        t.started += shfl_xor_u64(t.started, m); t.won += shfl_xor_u64(t.won, m);
+        t.ttft_sum += shfl_xor_f64(t.ttft_sum, m);
+        t.minb = min(t.minb, (unsigned)__shfl_xor((int)t.minb, m, 64));
+        t.maxb = max(t.maxb, (unsigned)__shfl_xor((int)t.maxb, m, 64));
+    }
+    // a column that never skips an endpoint charges it every prompt; the device is always started in Alg. 3
+    if (mode == 0) { t.d_pre = tot_l; t.started = tot_c; }
+    if (mode == 1) t.s_pre = tot_l;
+    __syncthreads();                          // staging no longer needed: reuse the LDS for the folds
+    if (sub == 0) sh[wave * G + col] = DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb};
+    __syncthreads();
+    if (threadIdx.x < G) {
+        DispPartial a = sh[threadIdx.x];
+        for (int w = 1; w < DP_WAVES; ++w) {
+            const DispPartial& o = sh[w * G + threadIdx.x];
+            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
+            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
+            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
+        }
+        part[(size_t)blockIdx.x * G + threadIdx.x] = a;
+    }
+    if (!take_last_ticket(ticket)) return;
+    fold_and_finish<G>(part, P, mode, fin, sh);
+    if (threadIdx.x == 0) *ticket = 0u;
+}
+
+// Single column: lane = request, four consecutive requests per lane and
+// iteration (16-byte loads when VEC, i.e. all arrays 16-byte aligned).
+template <bool VEC>
+__global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc1(TraceView tr, const disco_policy* __restrict__ pol,
+                                                            DispPartial* __restrict__ part, unsigned* ticket, DispFin fin)
+{
+    __shared__ __align__(16) unsigned char smem[DP_BLOCK * sizeof(DispPartial)];
+    DispPartial* sh = reinterpret_cast<DispPartial*>(smem);
+    const disco_policy p = pol[0];
+    const int mode = p.mode == DISCO_MODE_SERVER_CONSTRAINED ? 0 : 1;
+    ColTotals t{0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+    u64 tot_n = 0;
+    const i64 ngroups = (tr.n_req + 3) >> 2;
+    const i64 stride = (i64)gridDim.x * DP_BLOCK;
+    for (i64 g4 = (i64)blockIdx.x * DP_BLOCK + threadIdx.x; g4 < ngroups; g4 += stride) {
+        int l[4], n[4];
+        float s[4], k[4];
+        const i64 i0 = g4 * 4;
+        if (VEC && i0 + 3 < tr.n_req) {
+            const int4 lv = *reinterpret_cast<const int4*>(tr.l + i0);
+            const int4 nv = *reinterpret_cast<const int4*>(tr.n + i0);
+            const float4 sv = *reinterpret_cast<const float4*>(tr.s + i0);
+            l[0] = lv.x; l[1] = lv.y; l[2] = lv.z; l[3] = lv.w;
+            n[0] = nv.x; n[1] = nv.y; n[2] = nv.z; n[3] = nv.w;
+            s[0] = sv.x; s[1] = sv.y; s[2] = sv.z; s[3] = sv.w;
+            if (tr.k) {
+                const float4 kv = *reinterpret_cast<const float4*>(tr.k + i0);
+                k[0] = kv.x; k[1] = kv.y; k[2] = kv.z; k[3] = kv.w;
+            } else { k[0] = k[1] = k[2] = k[3] = tr.k_s; }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool v = i0 + q < tr.n_req;
+                l[q] = v ? tr.l[i0 + q] : 0; n[q] = v ? tr.n[i0 + q] : 0; s[q] = v ? tr.s[i0 + q] : 0.0f;
+                k[q] = tr.k ? (v ? tr.k[i0 + q] : 0.0f) : tr.k_s;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bool v = i0 + q < tr.n_req;
+            const float d = __fmaf_rn((float)l[q], k[q], tr.c);
+            const PairResult e = (mode == 0) ? pair_eval<0>(p, l[q], s[q], d) : pair_eval<1>(p, l[q], s[q], d);
+            t.s_pre += (v && e.srv_started) ? (u64)l[q] : 0ull;
+            t.d_pre += (v && e.dev_started) ? (u64)l[q] : 0ull;
+            t.started += (v && e.dev_started) ? 1ull : 0ull;
+            t.d_dec += (v && e.dev_win) ? (u64)n[q] : 0ull;
+            t.won += (v && e.dev_win) ? 1ull : 0ull;
+            t.ttft_sum += v ? (double)e.ttft : 0.0;
+            tot_n += v ? (u64)n[q] : 0ull;
+            const unsigned tb = f2u(e.ttft);
+            t.minb = v ? min(t.minb, tb) : t.minb;
+            t.maxb = v ? max(t.maxb, tb) : t.maxb;
+        }
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        t.s_pre += shfl_xor_u64(t.s_pre, m); t.d_pre += shfl_xor_u64(t.d_pre, m); t.d_dec += shfl_xor_u64(t.d_dec, m);
+        t.started += shfl_xor_u64(t.started, m); t.won += shfl_xor_u64(t.won, m); tot_n += shfl_xor_u64(tot_n, m);
+        t.ttft_sum += shfl_xor_f64(t.ttft_sum, m);
+        t.minb = min(t.minb, (unsigned)__shfl_xor((int)t.minb, m, 64));
+        t.maxb = max(t.maxb, (unsigned)__shfl_xor((int)t.maxb, m, 64));
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) sh[wave] = DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb};
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        DispPartial a = sh[0];
+        for (int w = 1; w < DP_WAVES; ++w) {
+            const DispPartial& o = sh[w];
+            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
+            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
+            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
+        }
+        part[blockIdx.x] = a;
+    }
+    if (!take_last_ticket(ticket)) return;
+    fold_and_finish<1>(part, 1, mode, fin, sh);
+    if (threadIdx.x == 0) *ticket = 0u;
+}
+
+// Materialised per-pair outputs, lane = request so that every column is
+// written coalesced.
+__global__ __launch_bounds__(256) void k_dispatch_mat(TraceView tr, const disco_policy* __restrict__ pol, int P,
+                                                      uint8_t* __restrict__ decision, float* __restrict__ ttft)
+{
+    __shared__ disco_policy sp[DISCO_MAX_COLS];
+    if ((int)threadIdx.x < P) sp[threadIdx.x] = pol[threadIdx.x];
+    __syncthreads();
+    for (i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x; i < tr.n_req; i += (i64)gridDim.x * blockDim.x) {
+        const int l = tr.l[i];
+        const float s = tr.s[i];
+        const float k = tr.k ? tr.k[i] : tr.k_s;
+        const float d = __fmaf_rn((float)l, k, tr.c);
+        for (int j = 0; j < P; ++j) {
+            unsigned dec; float t;
+            dispatch_pair(sp[j], l, s, d, dec, t);
+            if (decision) decision[(size_t)j * tr.n_req + i] = (uint8_t)dec;
+            if (ttft) ttft[(size_t)j * tr.n_req + i] = t;
+        }
+    }
+}
+
+// ------------------------------------------------------ TTFT histograms ----
+
+constexpr int TH_WORDS = DISCO_MAX_SLOTS * 256;         // 128 KB of LDS bins
+constexpr int TH_PAD = 1;                               // skew: equal digits of different slots hit different banks
+
+// Same traversal as k_dispatch_acc; every pair whose key matches the prefix of
+// a (column, quantile) slot bumps that slot's bin in an LDS histogram; the
+// workgroup's bins are merged with global atomics and the last workgroup
+// advances the selection.
+template <int G>
+__global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
+                                                        int pass, SelState* S, unsigned* ghist, unsigned* ticket)
+{
+    __shared__ unsigned hist[TH_WORDS + DISCO_MAX_SLOTS * TH_PAD];
+    __shared__ __align__(16) Staged stage[DP_BLOCK];
+    const SelGlobal g = S->g[0];
+    const int width = pass < g.plan.npass ? g.plan.width[pass] : 0;
+    const int shift = pass < g.plan.npass ? g.plan.shift[pass] : 0;
+    const int nslot = (pass == 0) ? P : P * nq;
+    const int stride = (1 << width) + TH_PAD;
+    if (width > 0) {
+        for (int i = threadIdx.x; i < nslot * stride; i += DP_BLOCK) hist[i] = 0u;
+        __syncthreads();
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int col = lane & (G - 1), sub = lane / G;
+        const bool colv = col < P;
+        const disco_policy p = pol[colv ? col : 0];
+        unsigned prefix[DISCO_MAX_Q];
+        bool live[DISCO_MAX_Q];
+        bool any_live = false;
+#pragma unroll
+        for (int qi = 0; qi < DISCO_MAX_Q; ++qi) {
+            const bool on = colv && qi < nq;
+            const SelSlot sl = S->slot[0][on ? col * nq + qi : 0];
+            prefix[qi] = sl.prefix;
+            live[qi] = on && !sl.done;
+            any_live = any_live || live[qi];
+        }
+        const unsigned dmask = (1u << width) - 1u;
+        const int up = shift + width;          // up == 32 only when the prefix is empty
+        Staged* st = stage + wave * 64;
+        const i64 nbatch = (tr.n_req + 63) >> 6;
+        for (i64 b = (i64)blockIdx.x * DP_WAVES + wave; b < nbatch; b += (i64)gridDim.x * DP_WAVES) {
+            const i64 i = b * 64 + lane;
+            const bool v = i < tr.n_req;
+            const int lv = v ? tr.l[i] : 0;
+            const float sv = v ? tr.s[i] : 0.0f;
+            const float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
+            const float dv = __fmaf_rn((float)lv, kv, tr.c);
+            st[lane] = Staged{lv, sv, 0, dv};
+            const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll 4
+            for (int it = 0; it < G; ++it) {
+                const int src = sub * G + it;
+                const Staged r = st[src];
+                const PairResult e = pair_eval<2>(p, r.l, r.s, r.d);
+                if (src < cnt) {
+                    const unsigned key = f2u(e.ttft) - g.minb;
+                    const unsigned dgt = (key >> shift) & dmask;
+                    const unsigned hi = (up >= 32) ? 0u : (key >> up);
+                    if (pass == 0) {
+                        if (any_live) atomicAdd(&hist[col * stride + dgt], 1u);
+                    } else {
+#pragma unroll
+                        for (int qi = 0; qi < DISCO_MAX_Q; ++qi)
+                            if (live[qi] && hi == prefix[qi]) atomicAdd(&hist[(col * nq + qi) * stride + dgt], 1u);
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < nslot << width; i += DP_BLOCK) {
+            const unsigned c = hist[(i >> width) * stride + (i & (int)dmask)];
+            if (c) atomicAdd(&ghist[i], c);
+        }
+    }
+    if (!take_last_ticket(ticket)) return;
+    select_advance(S, 0, pass, P, nq, ghist);
+    if (threadIdx.x == 0) *ticket = 0u;
+}
+
+unsigned dispatch_blocks(i64 units, i64 per_block)
+{
+    i64 b = (units + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > DP_MAX_BLOCKS) b = DP_MAX_BLOCKS;
+    return (unsigned)b;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+template <int G>
+void launch_acc(const TraceView& v, const disco_policy* pol, int P, DispPartial* part, unsigned* ticket, const DispFin& fin,
+                hipStream_t stream)
+{
+    const unsigned blocks = dispatch_blocks((v.n_req + 63) / 64, DP_WAVES);
+    hipLaunchKernelGGL(k_dispatch_acc<G>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, P, part, ticket, fin);
+}
+
+template <int G>
+void launch_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S, unsigned* gh,
+                 unsigned* ticket, hipStream_t stream)
+{
+    const unsigned blocks = dispatch_blocks((v.n_req + 63) / 64, DP_WAVES);
+    hipLaunchKernelGGL(k_ttft_hist<G>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, P, nq, pass, S, gh, ticket);
+}
+
+int pow2_cols(int P)
+{
+    int g = 1;
+    while (g < P) g <<= 1;
+    return g;
+}
+
+}  // namespace
+
+void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, DispPartial* part, unsigned* ticket,
+                               const DispFin& fin, hipStream_t stream)
+{
+    switch (pow2_cols(P)) {
+    case 1: {
+        const unsigned blocks = dispatch_blocks((v.n_req + 3) / 4, DP_BLOCK);
+        const bool vec = aligned16(v.l) && aligned16(v.n) && aligned16(v.s) && (!v.k || aligned16(v.k));
+        if (vec) hipLaunchKernelGGL(k_dispatch_acc1<true>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, part, ticket, fin);
+        else hipLaunchKernelGGL(k_dispatch_acc1<false>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, part, ticket, fin);
+        break;
+    }
+    case 2: launch_acc<2>(v, pol, P, part, ticket, fin, stream); break;
+    case 4: launch_acc<4>(v, pol, P, part, ticket, fin, stream); break;
+    case 8: launch_acc<8>(v, pol, P, part, ticket, fin, stream); break;
+    case 16: launch_acc<16>(v, pol, P, part, ticket, fin, stream); break;
+    case 32: launch_acc<32>(v, pol, P, part, ticket, fin, stream); break;
+    default: launch_acc<64>(v, pol, P, part, ticket, fin, stream); break;
+    }
+}
+
+void disco_launch_ttft_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S, unsigned* gh,
+                            unsigned* ticket, hipStream_t stream)
+{
+    switch (pow2_cols(P)) {
+    case 1: launch_hist<1>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
+    case 2: launch_hist<2>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
+    case 4: launch_hist<4>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
+    case 8: launch_hist<8>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
+    case 16: launch_hist<16>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
+    case 32: launch_hist<32>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
+    default: launch_hist<64>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
+    }
+}
+
+void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,
+                               hipStream_t stream)
+{
+    i64 b = (v.n_req + 255) / 256;
+    if (b > 4096) b = 4096;
+    if (b < 1) b = 1;
+    hipLaunchKernelGGL(k_dispatch_mat, dim3((unsigned)b), dim3(256), 0, stream, v, pol, P, decision, ttft);
+}

@@ -23,16 +23,6 @@
 
 namespace {
 
-struct DispFin {
-    int kind;                     // 0: write disco_accum, 1: advance a search
-    disco_accum* acc;
-    disco_cost_params cost;
-    SearchState* st;
-    disco_search_out* sout;
-    disco_policy* pol_out;
-    disco_policy* pol_rw;         // the table the next pass reads
-};
-
 __global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets)
 {
     int i = threadIdx.x;
@@ -45,212 +35,6 @@ __global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* ds
     int i = threadIdx.x;
     if (i < P) dst[i] = src[i];
     if (i < 64) tickets[i] = 0u;
-}
-
-__device__ __forceinline__ double acc_value(int which, const disco_cost_params& c, i64 s_pre, i64 s_dec, i64 d_pre,
-                                            i64 d_dec)
-{
-    switch (which) {
-    case DISCO_ACC_TOTAL_COST: {
-        double server = server_cost_of(c, s_pre, s_dec);
-        double energy = device_energy_of(c, d_pre, d_dec);
-        double priced = c.lambda * energy;
-        return server + priced;
-    }
-    case DISCO_ACC_SERVER_COST: return server_cost_of(c, s_pre, s_dec);
-    case DISCO_ACC_DEVICE_COST: {
-        double energy = device_energy_of(c, d_pre, d_dec);
-        return c.lambda * energy;
-    }
-    case DISCO_ACC_SERVER_PREFILL_TOK: return (double)s_pre;
-    default: return (double)d_pre;
-    }
-}
-
-// Bisection step or final evaluation of search `col` (Sec. 4.2: find the
-// threshold / wait that meets the constrained endpoint's budget).
-__device__ void search_advance(int col, const DispFin& fin, i64 s_pre, i64 s_dec, i64 d_pre, i64 d_dec, i64 started,
-                               i64 won, double ttft_sum, unsigned minb, unsigned maxb)
-{
-    SearchState st = fin.st[col];
-    disco_policy p = fin.pol_rw[col];
-    double A = acc_value(st.which_acc, fin.cost, s_pre, s_dec, d_pre, d_dec);
-    bool is_w = st.which_param == DISCO_PARAM_W_TAIL;
-    if (st.step < st.n_steps) {
-        double mid = is_w ? (double)p.w_tail : (double)p.l_th;
-        fin.sout[col].hist_param[st.step] = mid;
-        fin.sout[col].hist_acc[st.step] = A;
-        if (is_w) {
-            if (A > st.target) st.lo = mid; else st.hi = mid;
-        } else if (st.lo < st.hi) {
-            if (A > st.target) st.lo = mid + 1.0; else st.hi = mid;
-        }
-        st.step += 1;
-        if (is_w) {
-            float next = (st.step < st.n_steps) ? 0.5f * ((float)st.lo + (float)st.hi) : (float)st.hi;
-            p.w_tail = next;
-        } else {
-            int lo = (int)st.lo, hi = (int)st.hi;
-            p.l_th = (st.step < st.n_steps) ? lo + (hi - lo) / 2 : hi;
-        }
-        fin.st[col] = st;
-        fin.pol_rw[col] = p;
-    } else {
-        disco_search_out* o = &fin.sout[col];
-        o->param = st.hi;
-        o->acc_at_param = A;
-        o->lo = st.lo;
-        o->hi = st.hi;
-        disco_accum a;
-        memset(&a, 0, sizeof(a));
-        a.s_pre = s_pre; a.s_dec = s_dec; a.d_pre = d_pre; a.d_dec = d_dec;
-        a.n_dev_started = started; a.n_dev_win = won; a.ttft_sum = ttft_sum;
-        a.ttft_min_bits = minb; a.ttft_max_bits = maxb;
-        o->at_param = a;
-        if (fin.pol_out) fin.pol_out[col] = p;
-    }
-}
-
-// --------------------------------------------------------------- dispatch --
-
-template <int G>
-__device__ __forceinline__ void fetch(int& l, float& s, int& n, float& d, int lv, float sv, int nv, float dv, int src)
-{
-    if (G == 64) {            // the whole wave looks at one request: scalar broadcast
-        l = bcast_i(lv, src); s = bcast_f(sv, src); n = bcast_i(nv, src); d = bcast_f(dv, src);
-    } else if (G == 1) {      // every lane keeps its own request
-        l = lv; s = sv; n = nv; d = dv;
-    } else {
-        l = __shfl(lv, src, 64); s = __shfl(sv, src, 64); n = __shfl(nv, src, 64); d = __shfl(dv, src, 64);
-    }
-}
-
-// Fused dispatch + per-column reduction (Sec. 4.2; token accounting of the
-// budget definitions: a started endpoint is charged the prompt, the winner
-// the output tokens).  part: [gridDim.x][G].
-template <int G>
-__global__ __launch_bounds__(DISCO_BLOCK) void k_dispatch_acc(TraceView tr, const disco_policy* __restrict__ pol, int P,
-                                                              DispPartial* __restrict__ part, unsigned* ticket,
-                                                              DispFin fin)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int col = lane & (G - 1), sub = lane / G;
-    const bool colv = col < P;
-    const disco_policy p = pol[colv ? col : 0];
-    u64 s_pre = 0, d_pre = 0, d_dec = 0, n_tot = 0, started = 0, won = 0;
-    double ttft_sum = 0.0;
-    unsigned minb = 0xFFFFFFFFu, maxb = 0u;
-    const i64 nbatch = (tr.n_req + 63) >> 6;
-    for (i64 b = (i64)blockIdx.x * (DISCO_BLOCK / 64) + wave; b < nbatch; b += (i64)gridDim.x * (DISCO_BLOCK / 64)) {
-        const i64 i = b * 64 + lane;
-        const bool v = i < tr.n_req;
-        int lv = v ? tr.l[i] : 0;
-        int nv = v ? tr.n[i] : 0;
-        float sv = v ? tr.s[i] : 0.0f;
-        float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
-        float dv = __fmaf_rn((float)lv, kv, tr.c);          // device TTFT T_d(l) = k l + c
-        const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
-        for (int it = 0; it < G; ++it) {
-            const int src = sub * G + it;
-            if (G == 64 && src >= cnt) break;
-            int l, n; float s, d;
-            fetch<G>(l, s, n, d, lv, sv, nv, dv, src);
-            unsigned dec; float ttft;
-            dispatch_pair(p, l, s, d, dec, ttft);
-            if (src < cnt) {
-                s_pre += (dec & 1u) ? (u64)l : 0ull;
-                d_pre += (dec & 2u) ? (u64)l : 0ull;
-                d_dec += (dec & 4u) ? (u64)n : 0ull;
-                n_tot += (u64)n;
-                started += (dec >> 1) & 1u;
-                won += (dec >> 2) & 1u;
-                ttft_sum += (double)ttft;
-                unsigned tb = f2u(ttft);
-                minb = min(minb, tb); maxb = max(maxb, tb);
-            }
-        }
-    }
-    // fold the request sub-groups of the wave, then the waves of the workgroup
-#pragma unroll
-    for (int m = G; m < 64; m <<= 1) {
-        s_pre += shfl_xor_u64(s_pre, m); d_pre += shfl_xor_u64(d_pre, m); d_dec += shfl_xor_u64(d_dec, m);
-        n_tot += shfl_xor_u64(n_tot, m); started += shfl_xor_u64(started, m); won += shfl_xor_u64(won, m);
-        ttft_sum += shfl_xor_f64(ttft_sum, m);
-        minb = min(minb, (unsigned)__shfl_xor((int)minb, m, 64));
-        maxb = max(maxb, (unsigned)__shfl_xor((int)maxb, m, 64));
-    }
-    __shared__ DispPartial sh[DISCO_BLOCK / 64][G];
-    if (sub == 0) sh[wave][col] = DispPartial{s_pre, d_pre, d_dec, n_tot, started, won, ttft_sum, minb, maxb};
-    __syncthreads();
-    if (threadIdx.x < G) {
-        DispPartial a = sh[0][threadIdx.x];
-        for (int w = 1; w < DISCO_BLOCK / 64; ++w) {
-            const DispPartial& o = sh[w][threadIdx.x];
-            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
-            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
-            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
-        }
-        part[(size_t)blockIdx.x * G + threadIdx.x] = a;
-    }
-    if (!take_last_ticket(ticket)) return;
-    // last workgroup: fixed-order fold over workgroups, Q threads per column
-    constexpr int Q = DISCO_BLOCK / G;
-    __shared__ DispPartial fold[Q][G];
-    {
-        const int c = threadIdx.x % G, q = threadIdx.x / G;
-        DispPartial a{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
-        for (unsigned b = q; b < gridDim.x; b += Q) {
-            const DispPartial o = part[(size_t)b * G + c];
-            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
-            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
-            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
-        }
-        fold[q][c] = a;
-    }
-    __syncthreads();
-    if (threadIdx.x < P) {
-        const int c = threadIdx.x;
-        DispPartial a = fold[0][c];
-        for (int q = 1; q < Q; ++q) {
-            const DispPartial& o = fold[q][c];
-            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
-            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
-            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
-        }
-        const i64 s_dec = (i64)(a.n_tot - a.d_dec);
-        if (fin.kind == 0) {
-            disco_accum* o = &fin.acc[c];
-            o->s_pre = (i64)a.s_pre; o->s_dec = s_dec; o->d_pre = (i64)a.d_pre; o->d_dec = (i64)a.d_dec;
-            o->n_dev_started = (i64)a.started; o->n_dev_win = (i64)a.won; o->ttft_sum = a.ttft_sum;
-            o->ttft_min_bits = a.minb; o->ttft_max_bits = a.maxb;
-        } else {
-            search_advance(c, fin, (i64)a.s_pre, s_dec, (i64)a.d_pre, (i64)a.d_dec, (i64)a.started, (i64)a.won,
-                           a.ttft_sum, a.minb, a.maxb);
-        }
-    }
-    if (threadIdx.x == 0) *ticket = 0u;
-}
-
-// Materialised per-pair outputs, lane = request so that every column is
-// written coalesced.
-__global__ __launch_bounds__(DISCO_BLOCK) void k_dispatch_mat(TraceView tr, const disco_policy* __restrict__ pol, int P,
-                                                              uint8_t* __restrict__ decision, float* __restrict__ ttft)
-{
-    __shared__ disco_policy sp[DISCO_MAX_COLS];
-    if (threadIdx.x < P) sp[threadIdx.x] = pol[threadIdx.x];
-    __syncthreads();
-    for (i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x; i < tr.n_req; i += (i64)gridDim.x * blockDim.x) {
-        int l = tr.l[i];
-        float s = tr.s[i];
-        float k = tr.k ? tr.k[i] : tr.k_s;
-        float d = __fmaf_rn((float)l, k, tr.c);
-        for (int j = 0; j < P; ++j) {
-            unsigned dec; float t;
-            dispatch_pair(sp[j], l, s, d, dec, t);
-            if (decision) decision[(size_t)j * tr.n_req + i] = (uint8_t)dec;
-            if (ttft) ttft[(size_t)j * tr.n_req + i] = t;
-        }
-    }
 }
 
 // ----------------------------------------------------------------- select --
@@ -306,76 +90,6 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
         S->slot[which][s] = sl;
     }
     for (int i = threadIdx.x; i < DISCO_MAX_SLOTS * 256; i += blockDim.x) ghist[i] = 0u;
-}
-
-// TTFT histogram pass: same traversal as k_dispatch_acc; each pair whose key
-// matches the slot's prefix bumps that slot's bin in an LDS histogram.
-template <int G, int SLOTCAP>
-__global__ __launch_bounds__(DISCO_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
-                                                           int pass, SelState* S, unsigned* ghist, unsigned* ticket)
-{
-    __shared__ unsigned hist[SLOTCAP * 256];
-    const SelGlobal g = S->g[0];
-    const int width = pass < g.plan.npass ? g.plan.width[pass] : 0;
-    const int shift = pass < g.plan.npass ? g.plan.shift[pass] : 0;
-    const int words = ((pass == 0) ? P : P * nq) << width;
-    if (width > 0) {
-        for (int i = threadIdx.x; i < words; i += DISCO_BLOCK) hist[i] = 0u;
-        __syncthreads();
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        const int col = lane & (G - 1), sub = lane / G;
-        const bool colv = col < P;
-        const disco_policy p = pol[colv ? col : 0];
-        unsigned prefix[DISCO_MAX_Q];
-        bool live[DISCO_MAX_Q];
-#pragma unroll
-        for (int qi = 0; qi < DISCO_MAX_Q; ++qi) {
-            bool on = colv && qi < nq;
-            SelSlot sl = S->slot[0][on ? col * nq + qi : 0];
-            prefix[qi] = sl.prefix;
-            live[qi] = on && !sl.done;
-        }
-        const unsigned dmask = (1u << width) - 1u;
-        const int up = shift + width;          // bits above this digit; up == 32 only when the prefix is empty
-        const i64 nbatch = (tr.n_req + 63) >> 6;
-        for (i64 b = (i64)blockIdx.x * (DISCO_BLOCK / 64) + wave; b < nbatch; b += (i64)gridDim.x * (DISCO_BLOCK / 64)) {
-            const i64 i = b * 64 + lane;
-            const bool v = i < tr.n_req;
-            int lv = v ? tr.l[i] : 0;
-            float sv = v ? tr.s[i] : 0.0f;
-            float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
-            float dv = __fmaf_rn((float)lv, kv, tr.c);
-            const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
-            for (int it = 0; it < G; ++it) {
-                const int src = sub * G + it;
-                if (G == 64 && src >= cnt) break;
-                int l, n; float s, d;
-                fetch<G>(l, s, n, d, lv, sv, 0, dv, src);
-                unsigned dec; float ttft;
-                dispatch_pair(p, l, s, d, dec, ttft);
-                if (src < cnt) {
-                    const unsigned key = f2u(ttft) - g.minb;
-                    const unsigned dgt = (key >> shift) & dmask;
-                    const unsigned hi = (up >= 32) ? 0u : (key >> up);
-                    if (pass == 0) {
-                        if (live[0] || live[1] || live[2] || live[3]) atomicAdd(&hist[((unsigned)col << width) | dgt], 1u);
-                    } else {
-#pragma unroll
-                        for (int qi = 0; qi < DISCO_MAX_Q; ++qi)
-                            if (live[qi] && hi == prefix[qi]) atomicAdd(&hist[((unsigned)(col * nq + qi) << width) | dgt], 1u);
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        for (int i = threadIdx.x; i < words; i += DISCO_BLOCK) {
-            unsigned c = hist[i];
-            if (c) atomicAdd(&ghist[i], c);
-        }
-    }
-    if (!take_last_ticket(ticket)) return;
-    select_advance(S, 0, pass, P, nq, ghist);
-    if (threadIdx.x == 0) *ticket = 0u;
 }
 
 // ------------------------------------------------------------ final stats --
@@ -487,21 +201,6 @@ int check_ws(void* ws, size_t ws_bytes, int P)
     return DISCO_OK;
 }
 
-int pow2_cols(int P)
-{
-    int g = 1;
-    while (g < P) g <<= 1;
-    return g;
-}
-
-unsigned dispatch_blocks(i64 n_req)
-{
-    i64 b = (n_req + DISCO_BLOCK - 1) / DISCO_BLOCK;
-    if (b < 1) b = 1;
-    if (b > 1024) b = 1024;
-    return (unsigned)b;
-}
-
 bool is_device_pointer(const void* p)
 {
     hipPointerAttribute_t attr;
@@ -531,54 +230,6 @@ int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, 
     hipLaunchKernelGGL(k_store_policies, dim3(1), dim3(64), 0, stream, t, P, (disco_policy*)(ws + L.pol),
                        (unsigned*)(ws + L.ticket));
     return DISCO_OK;
-}
-
-template <int G>
-void launch_dispatch_acc(const TraceView& v, int P, char* ws, const WsLayout& L, const DispFin& fin, hipStream_t stream)
-{
-    hipLaunchKernelGGL(k_dispatch_acc<G>, dim3(dispatch_blocks(v.n_req)), dim3(DISCO_BLOCK), 0, stream, v,
-                       (const disco_policy*)(ws + L.pol), P, (DispPartial*)(ws + L.part), (unsigned*)(ws + L.ticket), fin);
-}
-
-void launch_dispatch_acc_g(int G, const TraceView& v, int P, char* ws, const WsLayout& L, const DispFin& fin,
-                           hipStream_t stream)
-{
-    switch (G) {
-    case 1: launch_dispatch_acc<1>(v, P, ws, L, fin, stream); break;
-    case 2: launch_dispatch_acc<2>(v, P, ws, L, fin, stream); break;
-    case 4: launch_dispatch_acc<4>(v, P, ws, L, fin, stream); break;
-    case 8: launch_dispatch_acc<8>(v, P, ws, L, fin, stream); break;
-    case 16: launch_dispatch_acc<16>(v, P, ws, L, fin, stream); break;
-    case 32: launch_dispatch_acc<32>(v, P, ws, L, fin, stream); break;
-    default: launch_dispatch_acc<64>(v, P, ws, L, fin, stream); break;
-    }
-}
-
-template <int G>
-void launch_ttft_hist(const TraceView& v, int P, int nq, int pass, char* ws, const WsLayout& L, hipStream_t stream)
-{
-    const int slots = P * nq;
-    dim3 grid(dispatch_blocks(v.n_req)), block(DISCO_BLOCK);
-    const disco_policy* pol = (const disco_policy*)(ws + L.pol);
-    SelState* S = (SelState*)(ws + L.sel);
-    unsigned* gh = (unsigned*)(ws + L.ghist);
-    unsigned* tk = (unsigned*)(ws + L.ticket);
-    if (slots <= 8) hipLaunchKernelGGL((k_ttft_hist<G, 8>), grid, block, 0, stream, v, pol, P, nq, pass, S, gh, tk);
-    else if (slots <= 32) hipLaunchKernelGGL((k_ttft_hist<G, 32>), grid, block, 0, stream, v, pol, P, nq, pass, S, gh, tk);
-    else hipLaunchKernelGGL((k_ttft_hist<G, DISCO_MAX_SLOTS>), grid, block, 0, stream, v, pol, P, nq, pass, S, gh, tk);
-}
-
-void launch_ttft_hist_g(int G, const TraceView& v, int P, int nq, int pass, char* ws, const WsLayout& L, hipStream_t stream)
-{
-    switch (G) {
-    case 1: launch_ttft_hist<1>(v, P, nq, pass, ws, L, stream); break;
-    case 2: launch_ttft_hist<2>(v, P, nq, pass, ws, L, stream); break;
-    case 4: launch_ttft_hist<4>(v, P, nq, pass, ws, L, stream); break;
-    case 8: launch_ttft_hist<8>(v, P, nq, pass, ws, L, stream); break;
-    case 16: launch_ttft_hist<16>(v, P, nq, pass, ws, L, stream); break;
-    case 32: launch_ttft_hist<32>(v, P, nq, pass, ws, L, stream); break;
-    default: launch_ttft_hist<64>(v, P, nq, pass, ws, L, stream); break;
-    }
 }
 
 }  // namespace
@@ -648,11 +299,10 @@ extern "C" int32_t disco_eval_dispatch(const disco_trace* trace, const disco_pol
     memset(&fin, 0, sizeof(fin));
     fin.kind = 0;
     fin.acc = acc;
-    launch_dispatch_acc_g(pow2_cols(P), v, P, ws, L, fin, stream);
-    if (out && (out->decision || out->ttft) && v.n_req > 0) {
-        hipLaunchKernelGGL(k_dispatch_mat, dim3(dispatch_blocks(v.n_req)), dim3(DISCO_BLOCK), 0, stream, v,
-                           (const disco_policy*)(ws + L.pol), P, out->decision, out->ttft);
-    }
+    disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), P, (DispPartial*)(ws + L.part),
+                              (unsigned*)(ws + L.ticket), fin, stream);
+    if (out && (out->decision || out->ttft) && v.n_req > 0)
+        disco_launch_dispatch_mat(v, (const disco_policy*)(ws + L.pol), P, out->decision, out->ttft, stream);
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }
@@ -725,11 +375,12 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     disco_quantile qs[4] = {{0, 1}, {0, 1}, {0, 1}, {0, 1}};
     for (int i = 0; i < nq; ++i) qs[i] = q[i];
     if (nq > 0) {
-        const int G = pow2_cols(P);
         SelPlan tbt_plan = disco_tbt_plan(P, nq);
         hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 0, P, nq, qs[0], qs[1], qs[2], qs[3], acc,
                            v.n_req, gh, tbt_plan);
-        for (int pass = 0; pass < 4; ++pass) launch_ttft_hist_g(G, v, P, nq, pass, ws, L, stream);
+        for (int pass = 0; pass < 4; ++pass)
+            disco_launch_ttft_hist(v, (const disco_policy*)(ws + L.pol), P, nq, pass, S, gh, (unsigned*)(ws + L.ticket),
+                                   stream);
         if (tl) {
             hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 1, P, nq, qs[0], qs[1], qs[2], qs[3],
                                acc, v.n_req, gh, tbt_plan);
@@ -794,8 +445,9 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
     fin.sout = out;
     fin.pol_out = pol_out;
     fin.pol_rw = (disco_policy*)(ws + L.pol);
-    const int G = pow2_cols(n_search);
-    for (int step = 0; step <= n_steps; ++step) launch_dispatch_acc_g(G, v, n_search, ws, L, fin, stream);
+    for (int step = 0; step <= n_steps; ++step)
+        disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search, (DispPartial*)(ws + L.part),
+                                  (unsigned*)(ws + L.ticket), fin, stream);
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }

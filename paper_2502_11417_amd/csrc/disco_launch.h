@@ -10,6 +10,23 @@ struct TimelineArgs {
     SelState* S; unsigned* ghist;
 };
 
+// How the last workgroup of a dispatch pass hands on the column totals.
+struct DispFin {
+    int kind;                     // 0: write disco_accum, 1: advance a budget search
+    disco_accum* acc;
+    disco_cost_params cost;
+    SearchState* st;
+    disco_search_out* sout;
+    disco_policy* pol_out;
+    disco_policy* pol_rw;         // the table the next pass reads
+};
+
+void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, DispPartial* part, unsigned* ticket,
+                               const DispFin& fin, hipStream_t stream);
+void disco_launch_ttft_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S,
+                            unsigned* gh, unsigned* ticket, hipStream_t stream);
+void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,
+                               hipStream_t stream);
 SelPlan disco_tbt_plan(int P, int nq);
 void disco_launch_timeline(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                            hipStream_t stream);

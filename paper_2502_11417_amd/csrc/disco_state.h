@@ -30,9 +30,9 @@ static_assert(sizeof(disco_accum) == 128 && sizeof(disco_stats) == 256 && sizeof
 __device__ __forceinline__ bool take_last_ticket(unsigned* ticket)
 {
     __shared__ int is_last;
-    __threadfence();
-    __syncthreads();
+    __syncthreads();                       // the workgroup's writes are ordered before thread 0 ...
     if (threadIdx.x == 0) {
+        __threadfence();                   // ... which releases them at device scope (one fence per workgroup)
         unsigned t = atomicAdd(ticket, 1u);
         is_last = (t == gridDim.x - 1);
     }
