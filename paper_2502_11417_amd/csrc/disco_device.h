@@ -87,6 +87,60 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int m)
     return __longlong_as_double((long long)shfl_xor_u64((u64)__double_as_longlong(v), m));
 }
 
+// Wave-wide reductions with DPP row shifts (row = 16 lanes): four shifted
+// adds leave each row's total in its last lane; the four row totals are then
+// combined through scalar registers.  The order of the additions is fixed, so
+// floating-point sums are reproducible.  The result is uniform over the wave.
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_u32(unsigned old, unsigned src)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp((int)old, (int)src, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ u64 dpp_u64(u64 src)      // lanes without a source receive 0
+{
+    const unsigned lo = dpp_u32<CTRL>(0u, (unsigned)src);
+    const unsigned hi = dpp_u32<CTRL>(0u, (unsigned)(src >> 32));
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ u64 bcast_u64(u64 v, int lane)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, lane);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), lane);
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ u64 wave_sum_u64(u64 v)
+{
+    v += dpp_u64<0x111>(v); v += dpp_u64<0x112>(v); v += dpp_u64<0x114>(v); v += dpp_u64<0x118>(v);
+    return bcast_u64(v, 15) + bcast_u64(v, 31) + bcast_u64(v, 47) + bcast_u64(v, 63);
+}
+__device__ __forceinline__ double wave_sum_f64(double x)
+{
+    u64 b = (u64)__double_as_longlong(x);
+    // +0.0 has the all-zero pattern, so the zero fill of dpp_u64 is the additive identity
+    x += __longlong_as_double((long long)dpp_u64<0x111>(b)); b = (u64)__double_as_longlong(x);
+    x += __longlong_as_double((long long)dpp_u64<0x112>(b)); b = (u64)__double_as_longlong(x);
+    x += __longlong_as_double((long long)dpp_u64<0x114>(b)); b = (u64)__double_as_longlong(x);
+    x += __longlong_as_double((long long)dpp_u64<0x118>(b)); b = (u64)__double_as_longlong(x);
+    const double r0 = __longlong_as_double((long long)bcast_u64(b, 15)), r1 = __longlong_as_double((long long)bcast_u64(b, 31));
+    const double r2 = __longlong_as_double((long long)bcast_u64(b, 47)), r3 = __longlong_as_double((long long)bcast_u64(b, 63));
+    return ((r0 + r1) + r2) + r3;
+}
+__device__ __forceinline__ unsigned wave_min_u32(unsigned v)
+{
+    v = min(v, dpp_u32<0x111>(0xFFFFFFFFu, v)); v = min(v, dpp_u32<0x112>(0xFFFFFFFFu, v));
+    v = min(v, dpp_u32<0x114>(0xFFFFFFFFu, v)); v = min(v, dpp_u32<0x118>(0xFFFFFFFFu, v));
+    return min(min((unsigned)bcast_i((int)v, 15), (unsigned)bcast_i((int)v, 31)),
+               min((unsigned)bcast_i((int)v, 47), (unsigned)bcast_i((int)v, 63)));
+}
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v)
+{
+    v = max(v, dpp_u32<0x111>(0u, v)); v = max(v, dpp_u32<0x112>(0u, v));
+    v = max(v, dpp_u32<0x114>(0u, v)); v = max(v, dpp_u32<0x118>(0u, v));
+    return max(max((unsigned)bcast_i((int)v, 15), (unsigned)bcast_i((int)v, 31)),
+               max((unsigned)bcast_i((int)v, 47), (unsigned)bcast_i((int)v, 63)));
+}
+
 // ---------------------------------------------------------------------------
 // Unified cost (Sec. 4.1, App. E): written one fp64 operation at a time, in
 // the order server = a + b, energy = c + d, total = server + lambda * energy.

@@ -132,32 +132,60 @@ __device__ void search_advance(int col, const DispFin& fin, const disco_accum& t
     }
 }
 
-// Last workgroup: fold the per-workgroup partials of every column in a fixed
-// order and hand the totals to the accumulator or to the search.
-// part: [gridDim.x][G]; tot_l / tot_n partials ride in column 0's pad fields.
-template <int G>
-__device__ __forceinline__ void fold_and_finish(const DispPartial* __restrict__ part, int P, int mode, const DispFin& fin,
-                                                DispPartial* sh /* LDS, DP_BLOCK entries */)
+__device__ __forceinline__ void add_partial(DispPartial& a, const DispPartial& o)
 {
-    constexpr int Q = DP_BLOCK / G;
-    const int c = threadIdx.x % G, q = threadIdx.x / G;
-    DispPartial a{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
-    for (unsigned b = q; b < gridDim.x; b += Q) {
-        const DispPartial o = part[(size_t)b * G + c];
-        a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
-        a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
-        a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
+    a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
+    a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
+    a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
+}
+
+// A workgroup adds its column totals into the device-wide totals (exact
+// integer atomics; the fp64 TTFT sum is order-dependent in its last bits).
+__device__ __forceinline__ void add_to_totals(DispPartial* tot, const DispPartial& a, int need)
+{
+    atomicAdd((unsigned long long*)&tot->s_pre, (unsigned long long)a.s_pre);
+    atomicAdd((unsigned long long*)&tot->d_pre, (unsigned long long)a.d_pre);
+    if (need >= 1) {
+        atomicAdd((unsigned long long*)&tot->d_dec, (unsigned long long)a.d_dec);
+        atomicAdd((unsigned long long*)&tot->n_tot, (unsigned long long)a.n_tot);
+        atomicAdd((unsigned long long*)&tot->started, (unsigned long long)a.started);
+        atomicAdd((unsigned long long*)&tot->won, (unsigned long long)a.won);
     }
-    sh[q * G + c] = a;
+    if (need >= 2) {
+        unsafeAtomicAdd(&tot->ttft_sum, a.ttft_sum);      // hardware fp64 add (the workspace is ordinary device memory)
+        atomicMin(&tot->minb, a.minb);
+        atomicMax(&tot->maxb, a.maxb);
+    }
+}
+
+// Last workgroup: read the copies of the device-wide totals, put them back to
+// their identity for the next pass, add the copies of a column in order and
+// hand the sums to the accumulator or to the search.
+__device__ __forceinline__ void finish_columns(DispPartial* totals, int P, const DispFin& fin, u64* sh /* LDS */)
+{
+    for (int idx = threadIdx.x; idx < DISCO_NCOPY * 64; idx += DP_BLOCK) {
+        const int c = idx & 63;
+        if (c < P) {
+            DispPartial* src = &totals[idx];
+            DispPartial t;
+            t.s_pre = __hip_atomic_load(&src->s_pre, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.d_pre = __hip_atomic_load(&src->d_pre, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.d_dec = __hip_atomic_load(&src->d_dec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.n_tot = __hip_atomic_load(&src->n_tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.started = __hip_atomic_load(&src->started, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.won = __hip_atomic_load(&src->won, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.ttft_sum = __hip_atomic_load(&src->ttft_sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.minb = __hip_atomic_load(&src->minb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.maxb = __hip_atomic_load(&src->maxb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *src = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+            lds_put(sh, DP_BLOCK, idx, t);
+        }
+    }
     __syncthreads();
     if ((int)threadIdx.x < P) {
-        DispPartial t = sh[c];
-        for (int qq = 1; qq < Q; ++qq) {
-            const DispPartial& o = sh[qq * G + c];
-            t.s_pre += o.s_pre; t.d_pre += o.d_pre; t.d_dec += o.d_dec; t.n_tot += o.n_tot;
-            t.started += o.started; t.won += o.won; t.ttft_sum += o.ttft_sum;
-            t.minb = min(t.minb, o.minb); t.maxb = max(t.maxb, o.maxb);
-        }
+        const int c = threadIdx.x;
+        DispPartial t = lds_get<DispPartial>(sh, DP_BLOCK, c);
+        for (int k = 1; k < DISCO_NCOPY; ++k) add_partial(t, lds_get<DispPartial>(sh, DP_BLOCK, k * 64 + c));
         disco_accum acc;
         memset(&acc, 0, sizeof(acc));
         acc.s_pre = (i64)t.s_pre; acc.d_pre = (i64)t.d_pre; acc.d_dec = (i64)t.d_dec;
@@ -173,50 +201,83 @@ __device__ __forceinline__ void fold_and_finish(const DispPartial* __restrict__ 
             search_advance(c, fin, acc);
         }
     }
-    (void)mode;
 }
 
 // ------------------------------------------------- fused dispatch + reduce --
 
 struct Staged { int l; float s; int n; float d; };      // 16 bytes, one per request of the batch
 
-// Inner loop over the G requests of this lane's sub-group.  T32 accumulates in
-// 32-bit registers (every l, n of the batch below 2^24), else directly in 64 bit.
-template <int G, int MODE, bool T32>
-__device__ __forceinline__ void batch_pairs(const Staged* __restrict__ st, int sub, int cnt, const disco_policy& p, bool colv,
-                                            ColTotals& t)
+// Inner loop over the G requests of this lane's sub-group.
+// NEED 0: prefill token totals only; 1: + decode split and winner counts;
+// 2: + TTFT sum and range (a budget search needs less than an evaluation).
+// Fast form: full batch (no validity masks; lanes of unused columns compute
+// garbage nobody reads) and every l, n of the batch below 2^24, so the batch
+// totals fit 32-bit registers.
+template <int G, int MODE, int NEED, bool RAGGED>
+__device__ __forceinline__ void batch_pairs_fast(const Staged* __restrict__ st, int sub, int cnt, const disco_policy& p, ColTotals& t)
 {
     unsigned sp = 0, dp = 0, dd = 0, ns = 0, nw = 0;
     double ts = 0.0;
     unsigned mn = t.minb, mx = t.maxb;
 #pragma unroll 8
     for (int it = 0; it < G; ++it) {
+        const Staged r = st[sub * G + it];
+        PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d);
+        if (RAGGED) {                                  // requests past the end of the trace count for nothing
+            const bool v = sub * G + it < cnt;
+            e.srv_started = e.srv_started && v; e.dev_started = e.dev_started && v; e.dev_win = e.dev_win && v;
+            if (NEED >= 2 && !v) continue;
+        }
+        if (MODE != 1) sp += e.srv_started ? (unsigned)r.l : 0u;
+        if (MODE != 0) dp += e.dev_started ? (unsigned)r.l : 0u;
+        if (NEED >= 1) {
+            if (MODE != 0) ns += e.dev_started ? 1u : 0u;
+            dd += e.dev_win ? (unsigned)r.n : 0u;
+            nw += e.dev_win ? 1u : 0u;
+        }
+        if (NEED >= 2) {
+            const unsigned tb = f2u(e.ttft);
+            ts += (double)e.ttft;
+            mn = min(mn, tb); mx = max(mx, tb);
+        }
+    }
+    t.s_pre += sp; t.d_pre += dp; t.d_dec += dd; t.started += ns; t.won += nw;
+    t.ttft_sum += ts;
+    t.minb = mn; t.maxb = mx;
+}
+
+// General form: ragged last batch or huge lengths; everything in 64 bit, every update masked.
+template <int G>
+__device__ __forceinline__ void batch_pairs_slow(const Staged* __restrict__ st, int sub, int cnt, const disco_policy& p, bool colv,
+                                                 int mode, ColTotals& t)
+{
+    for (int it = 0; it < G; ++it) {
         const int src = sub * G + it;
         const Staged r = st[src];
-        const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d);
+        const PairResult e = pair_eval<2>(p, r.l, r.s, r.d);
         const bool v = colv && src < cnt;
+        if (mode != 1) t.s_pre += (v && e.srv_started) ? (u64)r.l : 0ull;
+        if (mode != 0) { t.d_pre += (v && e.dev_started) ? (u64)r.l : 0ull; t.started += (v && e.dev_started) ? 1ull : 0ull; }
+        t.d_dec += (v && e.dev_win) ? (u64)r.n : 0ull;
+        t.won += (v && e.dev_win) ? 1ull : 0ull;
+        t.ttft_sum += v ? (double)e.ttft : 0.0;
         const unsigned tb = f2u(e.ttft);
-        if (T32) {
-            if (MODE != 1) sp += (v && e.srv_started) ? (unsigned)r.l : 0u;
-            if (MODE != 0) { dp += (v && e.dev_started) ? (unsigned)r.l : 0u; ns += (v && e.dev_started) ? 1u : 0u; }
-            dd += (v && e.dev_win) ? (unsigned)r.n : 0u;
-            nw += (v && e.dev_win) ? 1u : 0u;
-            ts += v ? (double)e.ttft : 0.0;
-        } else {
-            if (MODE != 1) t.s_pre += (v && e.srv_started) ? (u64)r.l : 0ull;
-            if (MODE != 0) { t.d_pre += (v && e.dev_started) ? (u64)r.l : 0ull; t.started += (v && e.dev_started) ? 1ull : 0ull; }
-            t.d_dec += (v && e.dev_win) ? (u64)r.n : 0ull;
-            t.won += (v && e.dev_win) ? 1ull : 0ull;
-            t.ttft_sum += v ? (double)e.ttft : 0.0;
-        }
-        mn = v ? min(mn, tb) : mn;
-        mx = v ? max(mx, tb) : mx;
+        t.minb = v ? min(t.minb, tb) : t.minb;
+        t.maxb = v ? max(t.maxb, tb) : t.maxb;
     }
-    if (T32) {
-        t.s_pre += sp; t.d_pre += dp; t.d_dec += dd; t.started += ns; t.won += nw;
-        t.ttft_sum += ts;
+}
+
+template <int G, int MODE>
+__device__ __forceinline__ void batch_pairs_need(const Staged* __restrict__ st, int sub, int cnt, const disco_policy& p, int need,
+                                                 ColTotals& t)
+{
+    if (cnt == 64) {
+        if (need == 0) batch_pairs_fast<G, MODE, 0, false>(st, sub, cnt, p, t);
+        else if (need == 1) batch_pairs_fast<G, MODE, 1, false>(st, sub, cnt, p, t);
+        else batch_pairs_fast<G, MODE, 2, false>(st, sub, cnt, p, t);
+    } else {
+        batch_pairs_fast<G, MODE, 2, true>(st, sub, cnt, p, t);
     }
-    t.minb = mn; t.maxb = mx;
 }
 
 template <int G>
@@ -225,7 +286,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
 {
     __shared__ __align__(16) unsigned char smem[DP_BLOCK * sizeof(DispPartial)];    // 64 KB: staging, then folds
     Staged* stage = reinterpret_cast<Staged*>(smem);
-    DispPartial* sh = reinterpret_cast<DispPartial*>(smem);
+    u64* sh = reinterpret_cast<u64*>(smem);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & (G - 1), sub = lane / G;
     const bool colv = col < P;
@@ -250,21 +311,16 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
         // the staging area is private to the wave: no workgroup barrier needed
         __builtin_amdgcn_wave_barrier();
         if (small) {
-            if (mode == 0) batch_pairs<G, 0, true>(st, sub, cnt, p, colv, t);
-            else if (mode == 1) batch_pairs<G, 1, true>(st, sub, cnt, p, colv, t);
-            else batch_pairs<G, 2, true>(st, sub, cnt, p, colv, t);
+            if (mode == 0) batch_pairs_need<G, 0>(st, sub, cnt, p, fin.need, t);
+            else if (mode == 1) batch_pairs_need<G, 1>(st, sub, cnt, p, fin.need, t);
+            else batch_pairs_need<G, 2>(st, sub, cnt, p, fin.need, t);
         } else {
-            if (mode == 0) batch_pairs<G, 0, false>(st, sub, cnt, p, colv, t);
-            else if (mode == 1) batch_pairs<G, 1, false>(st, sub, cnt, p, colv, t);
-            else batch_pairs<G, 2, false>(st, sub, cnt, p, colv, t);
+            batch_pairs_slow<G>(st, sub, cnt, p, colv, mode, t);
         }
         __builtin_amdgcn_wave_barrier();
     }
     // column-independent sums: fold over the wave
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-        tot_l += shfl_xor_u64(tot_l, m); tot_n += shfl_xor_u64(tot_n, m); tot_c += shfl_xor_u64(tot_c, m);
-    }
+    tot_l = wave_sum_u64(tot_l); tot_n = wave_sum_u64(tot_n); tot_c = wave_sum_u64(tot_c);
     // fold the request sub-groups of the wave
 #pragma unroll
     for (int m = G; m < 64; m <<= 1) {
@@ -278,20 +334,17 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
     if (mode == 0) { t.d_pre = tot_l; t.started = tot_c; }
     if (mode == 1) t.s_pre = tot_l;
     __syncthreads();                          // staging no longer needed: reuse the LDS for the folds
-    if (sub == 0) sh[wave * G + col] = DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb};
+    if (sub == 0)
+        lds_put(sh, DP_BLOCK, wave * G + col,
+                DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb});
     __syncthreads();
     if (threadIdx.x < G) {
-        DispPartial a = sh[threadIdx.x];
-        for (int w = 1; w < DP_WAVES; ++w) {
-            const DispPartial& o = sh[w * G + threadIdx.x];
-            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
-            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
-            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
-        }
-        part[(size_t)blockIdx.x * G + threadIdx.x] = a;
+        DispPartial a = lds_get<DispPartial>(sh, DP_BLOCK, threadIdx.x);
+        for (int w = 1; w < DP_WAVES; ++w) add_partial(a, lds_get<DispPartial>(sh, DP_BLOCK, w * G + threadIdx.x));
+        if ((int)threadIdx.x < P) add_to_totals(&part[(blockIdx.x % DISCO_NCOPY) * 64 + threadIdx.x], a, fin.need);
     }
     if (!take_last_ticket(ticket)) return;
-    fold_and_finish<G>(part, P, mode, fin, sh);
+    finish_columns(part, P, fin, sh);
     if (threadIdx.x == 0) *ticket = 0u;
 }
 
@@ -302,7 +355,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc1(TraceView tr, const 
                                                             DispPartial* __restrict__ part, unsigned* ticket, DispFin fin)
 {
     __shared__ __align__(16) unsigned char smem[DP_BLOCK * sizeof(DispPartial)];
-    DispPartial* sh = reinterpret_cast<DispPartial*>(smem);
+    u64* sh = reinterpret_cast<u64*>(smem);
     const disco_policy p = pol[0];
     const int mode = p.mode == DISCO_MODE_SERVER_CONSTRAINED ? 0 : 1;
     ColTotals t{0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
@@ -339,39 +392,40 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc1(TraceView tr, const 
             const PairResult e = (mode == 0) ? pair_eval<0>(p, l[q], s[q], d) : pair_eval<1>(p, l[q], s[q], d);
             t.s_pre += (v && e.srv_started) ? (u64)l[q] : 0ull;
             t.d_pre += (v && e.dev_started) ? (u64)l[q] : 0ull;
-            t.started += (v && e.dev_started) ? 1ull : 0ull;
-            t.d_dec += (v && e.dev_win) ? (u64)n[q] : 0ull;
-            t.won += (v && e.dev_win) ? 1ull : 0ull;
-            t.ttft_sum += v ? (double)e.ttft : 0.0;
-            tot_n += v ? (u64)n[q] : 0ull;
-            const unsigned tb = f2u(e.ttft);
-            t.minb = v ? min(t.minb, tb) : t.minb;
-            t.maxb = v ? max(t.maxb, tb) : t.maxb;
+            if (fin.need >= 1) {
+                t.started += (v && e.dev_started) ? 1ull : 0ull;
+                t.d_dec += (v && e.dev_win) ? (u64)n[q] : 0ull;
+                t.won += (v && e.dev_win) ? 1ull : 0ull;
+                tot_n += v ? (u64)n[q] : 0ull;
+            }
+            if (fin.need >= 2) {
+                t.ttft_sum += v ? (double)e.ttft : 0.0;
+                const unsigned tb = f2u(e.ttft);
+                t.minb = v ? min(t.minb, tb) : t.minb;
+                t.maxb = v ? max(t.maxb, tb) : t.maxb;
+            }
         }
     }
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-        t.s_pre += shfl_xor_u64(t.s_pre, m); t.d_pre += shfl_xor_u64(t.d_pre, m); t.d_dec += shfl_xor_u64(t.d_dec, m);
-        t.started += shfl_xor_u64(t.started, m); t.won += shfl_xor_u64(t.won, m); tot_n += shfl_xor_u64(tot_n, m);
-        t.ttft_sum += shfl_xor_f64(t.ttft_sum, m);
-        t.minb = min(t.minb, (unsigned)__shfl_xor((int)t.minb, m, 64));
-        t.maxb = max(t.maxb, (unsigned)__shfl_xor((int)t.maxb, m, 64));
+    t.s_pre = wave_sum_u64(t.s_pre); t.d_pre = wave_sum_u64(t.d_pre);
+    if (fin.need >= 1) {
+        t.d_dec = wave_sum_u64(t.d_dec); t.started = wave_sum_u64(t.started); t.won = wave_sum_u64(t.won);
+        tot_n = wave_sum_u64(tot_n);
+    }
+    if (fin.need >= 2) {
+        t.ttft_sum = wave_sum_f64(t.ttft_sum);
+        t.minb = wave_min_u32(t.minb); t.maxb = wave_max_u32(t.maxb);
     }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) sh[wave] = DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb};
+    if (lane == 0)
+        lds_put(sh, DP_BLOCK, wave, DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb});
     __syncthreads();
     if (threadIdx.x == 0) {
-        DispPartial a = sh[0];
-        for (int w = 1; w < DP_WAVES; ++w) {
-            const DispPartial& o = sh[w];
-            a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
-            a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
-            a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
-        }
-        part[blockIdx.x] = a;
+        DispPartial a = lds_get<DispPartial>(sh, DP_BLOCK, 0);
+        for (int w = 1; w < DP_WAVES; ++w) add_partial(a, lds_get<DispPartial>(sh, DP_BLOCK, w));
+        add_to_totals(&part[(blockIdx.x % DISCO_NCOPY) * 64], a, fin.need);
     }
     if (!take_last_ticket(ticket)) return;
-    fold_and_finish<1>(part, 1, mode, fin, sh);
+    finish_columns(part, 1, fin, sh);
     if (threadIdx.x == 0) *ticket = 0u;
 }
 

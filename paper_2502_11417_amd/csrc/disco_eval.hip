@@ -23,18 +23,26 @@
 
 namespace {
 
-__global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets)
+// Staging of the policy table; also puts the tickets and the per-column
+// totals that the workgroups of a dispatch pass add into at their identity.
+__global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets, DispPartial* totals)
 {
     int i = threadIdx.x;
     if (i < P) dst[i] = t.p[i];
-    if (i < 64) tickets[i] = 0u;
+    if (i < 64) {
+        tickets[i] = 0u;
+        for (int k = 0; k < DISCO_NCOPY; ++k) totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+    }
 }
 
-__global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* dst, unsigned* tickets)
+__global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* dst, unsigned* tickets, DispPartial* totals)
 {
     int i = threadIdx.x;
     if (i < P) dst[i] = src[i];
-    if (i < 64) tickets[i] = 0u;
+    if (i < 64) {
+        tickets[i] = 0u;
+        for (int k = 0; k < DISCO_NCOPY; ++k) totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+    }
 }
 
 // ----------------------------------------------------------------- select --
@@ -219,7 +227,7 @@ int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, 
     if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
     if (is_device_pointer(pol)) {
         hipLaunchKernelGGL(k_copy_policies, dim3(1), dim3(64), 0, stream, pol, P, (disco_policy*)(ws + L.pol),
-                           (unsigned*)(ws + L.ticket));
+                           (unsigned*)(ws + L.ticket), (DispPartial*)(ws + L.part));
         return DISCO_OK;
     }
     int rc = check_policies(pol, P);
@@ -228,7 +236,7 @@ int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, 
     memset(&t, 0, sizeof(t));
     memcpy(t.p, pol, sizeof(disco_policy) * (size_t)P);
     hipLaunchKernelGGL(k_store_policies, dim3(1), dim3(64), 0, stream, t, P, (disco_policy*)(ws + L.pol),
-                       (unsigned*)(ws + L.ticket));
+                       (unsigned*)(ws + L.ticket), (DispPartial*)(ws + L.part));
     return DISCO_OK;
 }
 
@@ -298,6 +306,7 @@ extern "C" int32_t disco_eval_dispatch(const disco_trace* trace, const disco_pol
     DispFin fin;
     memset(&fin, 0, sizeof(fin));
     fin.kind = 0;
+    fin.need = 2;
     fin.acc = acc;
     disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), P, (DispPartial*)(ws + L.part),
                               (unsigned*)(ws + L.ticket), fin, stream);
@@ -445,9 +454,15 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
     fin.sout = out;
     fin.pol_out = pol_out;
     fin.pol_rw = (disco_policy*)(ws + L.pol);
-    for (int step = 0; step <= n_steps; ++step)
+    // bisection steps only need the totals their accumulators are made of; the last pass evaluates everything
+    int need = 0;
+    for (int j = 0; j < n_search; ++j)
+        if (spec[j].which_acc != DISCO_ACC_SERVER_PREFILL_TOK && spec[j].which_acc != DISCO_ACC_DEVICE_PREFILL_TOK) need = 1;
+    for (int step = 0; step <= n_steps; ++step) {
+        fin.need = step < n_steps ? need : 2;
         disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search, (DispPartial*)(ws + L.part),
                                   (unsigned*)(ws + L.ticket), fin, stream);
+    }
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }

@@ -13,6 +13,7 @@ struct TimelineArgs {
 // How the last workgroup of a dispatch pass hands on the column totals.
 struct DispFin {
     int kind;                     // 0: write disco_accum, 1: advance a budget search
+    int need;                     // totals wanted: 0 prefill tokens, 1 + decode split, 2 + TTFT sum and range
     disco_accum* acc;
     disco_cost_params cost;
     SearchState* st;

@@ -21,10 +21,34 @@ struct SelGlobal { unsigned minb, maxb; SelPlan plan; };
 struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
 struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; };   // [0] TTFT, [1] TBT
 
+// Device-wide totals are kept in DISCO_NCOPY copies (workgroup b adds into copy b % DISCO_NCOPY) so that
+// the atomics of different workgroups do not all queue up on one cache line.
+enum { DISCO_NCOPY = 16 };
 struct DispPartial { u64 s_pre, d_pre, d_dec, n_tot, started, won; double ttft_sum; unsigned minb, maxb; };
 struct MigPartial { u64 s_dec, d_dec, d_repre, migrated, tbt_count; double tlast_sum; u64 pad[2]; };
 static_assert(sizeof(DispPartial) == 64 && sizeof(MigPartial) == 64, "partials are 64 bytes");
 static_assert(sizeof(disco_accum) == 128 && sizeof(disco_stats) == 256 && sizeof(disco_policy) == 32, "ABI sizes");
+
+// 64-byte partials are parked in LDS field by field (structure of arrays):
+// consecutive threads then touch consecutive 8-byte words and the accesses
+// are free of bank conflicts, which a 64-byte stride would serialise 32-fold.
+template <class T>
+__device__ __forceinline__ void lds_put(u64* sh, int cap, int idx, const T& v)
+{
+    static_assert(sizeof(T) == 64, "partials are 64 bytes");
+    const u64* w = reinterpret_cast<const u64*>(&v);
+#pragma unroll
+    for (int f = 0; f < 8; ++f) sh[f * cap + idx] = w[f];
+}
+template <class T>
+__device__ __forceinline__ T lds_get(const u64* sh, int cap, int idx)
+{
+    T v;
+    u64* w = reinterpret_cast<u64*>(&v);
+#pragma unroll
+    for (int f = 0; f < 8; ++f) w[f] = sh[f * cap + idx];
+    return v;
+}
 
 // Last-ticket test: true in every thread of the workgroup that finishes last.
 __device__ __forceinline__ bool take_last_ticket(unsigned* ticket)

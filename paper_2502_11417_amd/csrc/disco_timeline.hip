@@ -397,39 +397,31 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
         return;
     }
     // statistics pass: fold the waves of the workgroup, then the workgroups (fixed order)
-    MigPartial (*sh)[64] = reinterpret_cast<MigPartial (*)[64]>(smem);      // 8 x 64 x 64 B = 32 KB
-    sh[wave][lane] = MigPartial{acc_s_dec, acc_d_dec, acc_repre, acc_mig, acc_cnt, acc_tlast, {0, 0}};
+    u64* sh = reinterpret_cast<u64*>(smem);                                  // 8 fields x TL_BLOCK entries = 32 KB
+    auto add = [](MigPartial& x, const MigPartial& o) {
+        x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
+        x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
+    };
+    lds_put(sh, TL_BLOCK, wave * 64 + lane, MigPartial{acc_s_dec, acc_d_dec, acc_repre, acc_mig, acc_cnt, acc_tlast, {0, 0}});
     __syncthreads();
     if (threadIdx.x < 64) {
-        MigPartial x = sh[0][threadIdx.x];
-        for (int w = 1; w < TL_WAVES; ++w) {
-            const MigPartial& o = sh[w][threadIdx.x];
-            x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
-            x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
-        }
+        MigPartial x = lds_get<MigPartial>(sh, TL_BLOCK, threadIdx.x);
+        for (int w = 1; w < TL_WAVES; ++w) add(x, lds_get<MigPartial>(sh, TL_BLOCK, w * 64 + threadIdx.x));
         a.part[(size_t)blockIdx.x * 64 + threadIdx.x] = x;
     }
     if (!take_last_ticket(a.ticket)) return;
     {
         const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
         MigPartial x{0, 0, 0, 0, 0, 0.0, {0, 0}};
-        for (unsigned b = q; b < gridDim.x; b += TL_WAVES) {
-            const MigPartial o = a.part[(size_t)b * 64 + c];
-            x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
-            x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
-        }
+        for (unsigned b = q; b < gridDim.x; b += TL_WAVES) add(x, a.part[(size_t)b * 64 + c]);
         __syncthreads();
-        sh[q][c] = x;
+        lds_put(sh, TL_BLOCK, q * 64 + c, x);
     }
     __syncthreads();
     if ((int)threadIdx.x < P) {
         const int c = threadIdx.x;
-        MigPartial x = sh[0][c];
-        for (int q = 1; q < TL_WAVES; ++q) {
-            const MigPartial& o = sh[q][c];
-            x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
-            x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
-        }
+        MigPartial x = lds_get<MigPartial>(sh, TL_BLOCK, c);
+        for (int q = 1; q < TL_WAVES; ++q) add(x, lds_get<MigPartial>(sh, TL_BLOCK, q * 64 + c));
         disco_accum* o = &a.acc[c];
         o->m_s_dec = (i64)x.s_dec; o->m_d_dec = (i64)x.d_dec; o->m_d_repre = (i64)x.d_repre;
         o->n_migrated = (i64)x.migrated; o->tbt_count = (i64)x.tbt_count; o->tlast_sum = x.tlast_sum;
