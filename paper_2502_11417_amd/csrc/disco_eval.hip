@@ -53,7 +53,7 @@ __global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* ds
 // One thread per slot: rank from (num, den, M), empty prefix; plan of the passes.
 __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quantile q0, disco_quantile q1,
                               disco_quantile q2, disco_quantile q3, const disco_accum* acc, i64 n_req,
-                              unsigned* ghist, SelPlan host_plan)
+                              unsigned* ghist)
 {
     const disco_quantile qs[4] = {q0, q1, q2, q3};
     __shared__ unsigned smin, smax;
@@ -80,11 +80,19 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
                 left -= wd; pl.npass += 1;
             }
             g.plan = pl;
-        } else {
+        } else {                      // TBT: raw keys; the passes are planned on the device (TlSel)
             g.minb = 0u; g.maxb = 0x7FFFFFFFu;
-            g.plan = host_plan;
+            g.plan.npass = 0; g.plan.pad = 0;
+            for (int i = 0; i < DISCO_MAX_PASS; ++i) { g.plan.shift[i] = 0; g.plan.width[i] = 0; }
+            TlSel& tl = S->tl;
+            tl.ncls = 0; tl.fallback = 0; tl.error = 0; tl.left = 31; tl.shift = 0; tl.width = 0; tl.G = 0;
+            for (int i = 0; i < DISCO_MAX_GRP; ++i) tl.grp_prefix[i] = 0u;
         }
         S->g[which] = g;
+    }
+    if (which == 1) {
+        for (int i = threadIdx.x; i < DISCO_MAX_CLS; i += blockDim.x) S->tl.cls_mask[i] = 0ull;
+        for (int i = threadIdx.x; i < DISCO_MAX_SLOTS; i += blockDim.x) S->tl.slot_grp[i] = -1;
     }
     for (int s = threadIdx.x; s < P * nq; s += blockDim.x) {
         int c = s / nq, qi = s % nq;
@@ -134,7 +142,7 @@ __global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, 
             if (with_tl) {
                 const SelSlot s1 = S->slot[1][c * nq + qi];
                 st.tbt_rank[qi] = s1.rank;
-                if (s1.M > 0) st.tbt_q[qi] = u2f(S->g[1].minb + s1.prefix);
+                if (s1.M > 0 && !S->tl.error && S->tl.left == 0) st.tbt_q[qi] = u2f(s1.prefix);
             }
         }
     }
@@ -384,15 +392,14 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     disco_quantile qs[4] = {{0, 1}, {0, 1}, {0, 1}, {0, 1}};
     for (int i = 0; i < nq; ++i) qs[i] = q[i];
     if (nq > 0) {
-        SelPlan tbt_plan = disco_tbt_plan(P, nq);
         hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 0, P, nq, qs[0], qs[1], qs[2], qs[3], acc,
-                           v.n_req, gh, tbt_plan);
+                           v.n_req, gh);
         for (int pass = 0; pass < 4; ++pass)
             disco_launch_ttft_hist(v, (const disco_policy*)(ws + L.pol), P, nq, pass, S, gh, (unsigned*)(ws + L.ticket),
                                    stream);
         if (tl) {
             hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 1, P, nq, qs[0], qs[1], qs[2], qs[3],
-                               acc, v.n_req, gh, tbt_plan);
+                               acc, v.n_req, gh);
             TimelineArgs a;
             memset(&a, 0, sizeof(a));
             a.tau = tl->tau;
@@ -400,7 +407,11 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             a.P = P; a.nq = nq;
             a.ticket = (unsigned*)(ws + L.ticket);
             a.S = S; a.ghist = gh;
-            for (int pass = 0; pass < tbt_plan.npass; ++pass) {
+            // column sets -> classes, then the radix passes; the digits are sized on the device and
+            // launches after the last needed pass return at once
+            a.pass = -2;
+            disco_launch_timeline(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
+            for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;
                 disco_launch_timeline(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
             }

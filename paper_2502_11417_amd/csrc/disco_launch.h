@@ -4,7 +4,7 @@
 
 struct TimelineArgs {
     float tau, kt;            // pacing interval, kappa_lag * tau
-    int P, nq, pass;          // pass < 0: statistics pass, else histogram pass `pass` of the TBT selection
+    int P, nq, pass;          // -1: statistics pass, -2: classification of the column sets, >= 0: TBT histogram pass
     int32_t* mig_idx; int32_t* n_src_tok; float* t_last; float* delivered; int delivered_col;
     MigPartial* part; unsigned* ticket; disco_accum* acc;
     SelState* S; unsigned* ghist;
@@ -28,6 +28,5 @@ void disco_launch_ttft_hist(const TraceView& v, const disco_policy* pol, int P, 
                             unsigned* gh, unsigned* ticket, hipStream_t stream);
 void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,
                                hipStream_t stream);
-SelPlan disco_tbt_plan(int P, int nq);
 void disco_launch_timeline(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                            hipStream_t stream);

@@ -19,7 +19,25 @@ enum { DISCO_MAX_PASS = 6 };
 struct SelPlan { int npass; int shift[DISCO_MAX_PASS]; int width[DISCO_MAX_PASS]; int pad; };
 struct SelGlobal { unsigned minb, maxb; SelPlan plan; };
 struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
-struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; };   // [0] TTFT, [1] TBT
+// TBT selection: a timeline is histogrammed once per *class* = set of policy
+// columns that use it (for threshold- or wait-ordered tables the sets are
+// nested, so there are at most P + 1 of them), not once per column.  Keys are
+// the raw 31-bit patterns of the gaps.  The digit of each pass is sized on the
+// device from the number of classes and of distinct prefixes still alive.
+enum { DISCO_MAX_CLS = 64, DISCO_MAX_GRP = 4, DISCO_TBT_MAX_PASS = 6, DISCO_TL_HIST_WORDS = 16384 };
+struct TlSel {
+    u64 cls_mask[DISCO_MAX_CLS];   // column set of each class, 0 = free
+    int ncls;
+    int fallback;                  // 1: one histogram per (column, quantile) slot instead of per class
+    int error;                     // a column set could not be placed (never expected)
+    int left;                      // undecided key bits
+    int shift, width;              // digit of the pass about to run (width 0: finished)
+    int G;                         // distinct prefixes among the live slots
+    unsigned grp_prefix[DISCO_MAX_GRP];
+    int slot_grp[DISCO_MAX_SLOTS]; // prefix group of each live slot, -1 otherwise
+    int pad[3];
+};
+struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; TlSel tl; };   // [0] TTFT, [1] TBT
 
 // Device-wide totals are kept in DISCO_NCOPY copies (workgroup b adds into copy b % DISCO_NCOPY) so that
 // the atomics of different workgroups do not all queue up on one cache line.

@@ -57,53 +57,84 @@ __device__ __forceinline__ float wave_prev(float v, float first)
 
 // ------------------------------------------------------------ histogram ----
 
+// What a histogram pass needs, cached in LDS / registers per workgroup.
 struct HistCtx {
-    unsigned* hist;          // LDS
-    int pass, shift, width, up, nq;
-    const unsigned* sprefix; // LDS, per slot
+    unsigned* hist;          // LDS bins
+    int shift, width, up;    // digit of this pass; up = shift + width
+    int fallback, ncls, G, nq;
+    unsigned grp_prefix[DISCO_MAX_GRP];
+    const u64* s_cls;        // LDS copy of the class table
+    const unsigned* sprefix; // LDS, per slot (fallback path)
     const int* slive;        // LDS, per slot
 };
 
-// Adds `cnt` to bin `bin` of every column in `cols` (pass 0) or of slot
-// (column, qi) for the columns in `cols`; lane = column performs the add.
-__device__ __forceinline__ void hist_add_cols(const HistCtx& h, u64 cols, int qi, unsigned bin, unsigned cnt, int lane)
+// Class of a column set: index in the device-wide table, claimed on first use.
+// Wave-uniform.  Returns -1 when the table is full.
+__device__ __forceinline__ int cls_lookup(u64 mask, u64* s_cls, TlSel* tl, int lane)
 {
-    if ((cols >> lane) & 1ull) {
-        const unsigned idx = (h.pass == 0) ? (((unsigned)lane << h.width) | bin)
-                                           : ((((unsigned)lane * h.nq + qi) << h.width) | bin);
-        atomicAdd(&h.hist[idx], cnt);
+    for (int attempt = 0; attempt < 2 * DISCO_MAX_CLS; ++attempt) {
+        u64 m = s_cls[lane];
+        u64 hit = __ballot(m == mask);
+        if (hit) return __ffsll((long long)hit) - 1;
+        m = __hip_atomic_load(&tl->cls_mask[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_cls[lane] = m;
+        hit = __ballot(m == mask);
+        if (hit) return __ffsll((long long)hit) - 1;
+        const u64 free = __ballot(m == 0ull);
+        if (!free) return -1;
+        const int e = __ffsll((long long)free) - 1;
+        unsigned long long old = 0ull;
+        if (lane == 0) old = atomicCAS((unsigned long long*)&tl->cls_mask[e], 0ull, (unsigned long long)mask);
+        old = (unsigned long long)bcast_u64((u64)old, 0);
+        if (old == 0ull || old == (unsigned long long)mask) {
+            if (lane == 0) s_cls[e] = mask;
+            return e;
+        }
     }
+    return -1;
 }
 
-// Four keys per lane (ok[k] marks real gaps).  Keys that share their bin
-// across the wave are counted with ballots and added once per column.
-__device__ __forceinline__ void hist_keys(const HistCtx& h, const unsigned key[4], const bool ok[4], u64 cols, int lane)
+// Class path: every key of the chunk goes to one histogram (prefix group g of
+// the key, class c of the timeline).  The bin shared by most of the wave is
+// counted with ballots and added once; the rest is added lane by lane.
+__device__ __forceinline__ void hist_keys_cls(const HistCtx& h, const unsigned key[4], const bool ok[4], int cls, int lane)
 {
     const unsigned dmask = (1u << h.width) - 1u;
-    if (h.pass == 0) {
-        unsigned bin[4];
-        bool pend[4];
+    unsigned idx[4];
+    bool pend[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) { bin[k] = (key[k] >> h.shift) & dmask; pend[k] = ok[k]; }
-        u64 todo = __ballot(pend[0] || pend[1] || pend[2] || pend[3]);
-        while (todo) {
-            const int leader = __ffsll((long long)todo) - 1;
-            const unsigned mine = pend[0] ? bin[0] : (pend[1] ? bin[1] : (pend[2] ? bin[2] : bin[3]));
-            const unsigned b0 = (unsigned)bcast_i((int)mine, leader);
-            unsigned cnt = 0;
+    for (int q = 0; q < 4; ++q) {
+        const unsigned hi = h.up >= 32 ? 0u : (key[q] >> h.up);
+        int g = -1;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const bool same = pend[k] && bin[k] == b0;
-                cnt += (unsigned)__popcll(__ballot(same));
-                pend[k] = pend[k] && !same;
-            }
-            hist_add_cols(h, cols, 0, b0, cnt, lane);
-            todo = __ballot(pend[0] || pend[1] || pend[2] || pend[3]);
-        }
-        return;
+        for (int k = 0; k < DISCO_MAX_GRP; ++k) g = (k < h.G && hi == h.grp_prefix[k] && g < 0) ? k : g;
+        pend[q] = ok[q] && g >= 0;
+        idx[q] = ((unsigned)((g < 0 ? 0 : g) * h.ncls + cls) << h.width) | ((key[q] >> h.shift) & dmask);
     }
-    // later passes: a key counts for slot (column, qi) if its upper bits equal the slot's prefix;
-    // columns that share a prefix are served together
+    const u64 todo = __ballot(pend[0] || pend[1] || pend[2] || pend[3]);
+    if (!todo) return;
+    const int leader = __ffsll((long long)todo) - 1;
+    const unsigned mine = pend[0] ? idx[0] : (pend[1] ? idx[1] : (pend[2] ? idx[2] : idx[3]));
+    const unsigned i0 = (unsigned)bcast_i((int)mine, leader);
+    unsigned cnt = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const bool same = pend[q] && idx[q] == i0;
+        cnt += (unsigned)__popcll(__ballot(same));
+        pend[q] = pend[q] && !same;
+    }
+    if (lane == leader) atomicAdd(&h.hist[i0], cnt);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (pend[q]) atomicAdd(&h.hist[idx[q]], 1u);
+}
+
+// Fallback path: one histogram per (column, quantile) slot; a key counts for a
+// slot if its upper bits equal the slot's prefix.  Columns that share a prefix
+// are served together; equal bins are counted with ballots, lane = column adds.
+__device__ __forceinline__ void hist_keys_cols(const HistCtx& h, const unsigned key[4], const bool ok[4], u64 cols, int lane)
+{
+    const unsigned dmask = (1u << h.width) - 1u;
     for (int qi = 0; qi < h.nq; ++qi) {
         u64 cm = cols;
         while (cm) {
@@ -135,10 +166,117 @@ __device__ __forceinline__ void hist_keys(const HistCtx& h, const unsigned key[4
                     cnt += (unsigned)__popcll(__ballot(same));
                     pend[k] = pend[k] && !same;
                 }
-                hist_add_cols(h, grp, qi, b0, cnt, lane);
+                if ((grp >> lane) & 1ull) atomicAdd(&h.hist[(((unsigned)lane * h.nq + qi) << h.width) | b0], cnt);
                 todo = __ballot(pend[0] || pend[1] || pend[2] || pend[3]);
             }
         }
+    }
+}
+
+// Largest digit width whose `groups` histograms fit the LDS bins.
+__device__ __host__ __forceinline__ int fit_width(int groups)
+{
+    int w = 0;
+    while (w < 14 && ((size_t)groups << (w + 1)) <= (size_t)DISCO_TL_HIST_WORDS) ++w;
+    return w;
+}
+
+// Prepares the next pass: prefix groups of the live slots, digit width that
+// fits, or the per-slot fallback.  One thread.
+__device__ void tbt_plan_next(SelState* S, int P, int nq)
+{
+    TlSel& tl = S->tl;
+    int G = 0;
+    bool over = tl.ncls > DISCO_MAX_CLS || tl.ncls < 1;
+    for (int s = 0; s < P * nq; ++s) {
+        const SelSlot sl = S->slot[1][s];
+        int g = -1;
+        if (!sl.done) {
+            for (int k = 0; k < G && k < DISCO_MAX_GRP; ++k)
+                if (tl.grp_prefix[k] == sl.prefix) g = k;
+            if (g < 0) {
+                if (G < DISCO_MAX_GRP) { tl.grp_prefix[G] = sl.prefix; g = G; }
+                else g = 0;            // too many distinct prefixes: the per-slot fallback does not use groups
+                G += 1;
+            }
+        }
+        tl.slot_grp[s] = g;
+    }
+    if (G > DISCO_MAX_GRP) over = true;
+    if (over) tl.fallback = 1;
+    tl.G = G;
+    int w = tl.fallback ? fit_width(P * nq) : fit_width((G > 0 ? G : 1) * tl.ncls);
+    if (w < 1) w = 1;
+    if (w > tl.left) w = tl.left;
+    if (G == 0) w = 0;                 // nothing left to select
+    tl.width = w;
+    tl.shift = tl.left - w;
+}
+
+// After a TBT histogram pass: per live slot, add up the class histograms of
+// the classes that contain the slot's column (or take the slot's own
+// histogram in the fallback), walk to the digit that holds the remaining
+// rank, extend the prefix; then plan the next pass and clear the bins.
+__device__ void tbt_advance(SelState* S, int P, int nq, unsigned* ghist)
+{
+    TlSel& tl = S->tl;
+    const int width = tl.width, ncls = tl.ncls, fallback = tl.fallback;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int Gused = tl.G < DISCO_MAX_GRP ? tl.G : DISCO_MAX_GRP;
+    __syncthreads();
+    if (width > 0) {
+        const int nbins = 1 << width;
+        const int per = (nbins + 63) >> 6;
+        for (int s = wave; s < P * nq; s += nwaves) {
+            SelSlot sl = S->slot[1][s];
+            const int g = tl.slot_grp[s];
+            if (sl.done || g < 0) continue;
+            const int col = s / nq;
+            const int b0 = lane * per;
+            auto bin_count = [&](int b) -> u64 {
+                if (fallback) return ghist[((size_t)s << width) | b];
+                u64 c = 0;
+                for (int k = 0; k < ncls; ++k)
+                    if ((tl.cls_mask[k] >> col) & 1ull) c += ghist[((size_t)(g * ncls + k) << width) | b];
+                return c;
+            };
+            u64 mine = 0;
+            for (int b = b0; b < b0 + per && b < nbins; ++b) mine += bin_count(b);
+            u64 incl = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                unsigned lo = (unsigned)__shfl_up((int)(unsigned)incl, d, 64);
+                unsigned hi = (unsigned)__shfl_up((int)(unsigned)(incl >> 32), d, 64);
+                if (lane >= d) incl += ((u64)hi << 32) | lo;
+            }
+            const u64 k = (u64)sl.k_rem;
+            const u64 hit = __ballot(incl >= k);
+            const int owner = hit ? (__ffsll((long long)hit) - 1) : 63;
+            if (lane == owner) {
+                u64 rem = k - (incl - mine);
+                int dsel = nbins - 1;
+                for (int b = b0; b < b0 + per && b < nbins; ++b) {
+                    const u64 c = bin_count(b);
+                    if (rem <= c) { dsel = b; break; }
+                    rem -= c;
+                }
+                sl.k_rem = (i64)rem;
+                sl.prefix = (sl.prefix << width) | (unsigned)dsel;
+                S->slot[1][s] = sl;
+            }
+        }
+    }
+    __syncthreads();
+    if (width > 0) {
+        const int words = (fallback ? P * nq : Gused * ncls) << width;
+        for (int i = threadIdx.x; i < words; i += blockDim.x) ghist[i] = 0u;
+    }
+    __threadfence_block();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        tl.left -= width;
+        if (tl.left <= 0) { tl.left = 0; tl.width = 0; tl.G = 0; }
+        else tbt_plan_next(S, P, nq);
     }
 }
 
@@ -304,30 +442,40 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
     __shared__ __align__(16) unsigned smem[TL_HIST_WORDS];
     __shared__ unsigned sprefix[DISCO_MAX_SLOTS];
     __shared__ int slive[DISCO_MAX_SLOTS];
+    __shared__ u64 s_cls[DISCO_MAX_CLS];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int P = a.P, nq = a.nq;
     const bool colv = lane < P;
     const disco_policy p = pol[colv ? lane : 0];
-    const bool hist_pass = a.pass >= 0;
-    HistCtx h{smem, a.pass, 0, 0, 0, nq, sprefix, slive};
-    bool work = true;
-    if (hist_pass) {
-        const SelPlan plan = a.S->g[1].plan;
-        work = a.pass < plan.npass && plan.width[a.pass] > 0;
-        if (work) {
-            h.shift = plan.shift[a.pass];
-            h.width = plan.width[a.pass];
-            h.up = h.shift + h.width;
-            const int words = ((a.pass == 0) ? P : P * nq) << h.width;
-            for (int i = threadIdx.x; i < words; i += TL_BLOCK) smem[i] = 0u;
-            for (int i = threadIdx.x; i < P * nq; i += TL_BLOCK) {
-                const SelSlot sl = a.S->slot[1][i];
-                sprefix[i] = sl.prefix;
-                slive[i] = !sl.done;
-            }
-        }
-        __syncthreads();
+    const bool hist_pass = a.pass >= 0;       // pass -1: statistics, -2: classification of the column sets
+    const bool classify = a.pass == -2;
+    HistCtx h;
+    h.hist = smem; h.shift = 0; h.width = 0; h.up = 0; h.fallback = 0; h.ncls = 1; h.G = 0; h.nq = nq;
+    h.s_cls = s_cls; h.sprefix = sprefix; h.slive = slive;
+    for (int k = 0; k < DISCO_MAX_GRP; ++k) h.grp_prefix[k] = 0u;
+    if (hist_pass || classify) {
+        TlSel* tl = &a.S->tl;
+        if (threadIdx.x < DISCO_MAX_CLS)
+            s_cls[threadIdx.x] = __hip_atomic_load(&tl->cls_mask[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    if (hist_pass) {
+        const TlSel* tl = &a.S->tl;
+        h.width = tl->width;
+        if (h.width <= 0) return;             // selection finished: nothing to do in this launch
+        h.shift = tl->shift;
+        h.up = h.shift + h.width;
+        h.fallback = tl->fallback; h.ncls = tl->ncls; h.G = tl->G < DISCO_MAX_GRP ? tl->G : DISCO_MAX_GRP;
+        for (int k = 0; k < DISCO_MAX_GRP; ++k) h.grp_prefix[k] = tl->grp_prefix[k];
+        const int words = (h.fallback ? P * nq : h.G * h.ncls) << h.width;
+        for (int i = threadIdx.x; i < words; i += TL_BLOCK) smem[i] = 0u;
+        for (int i = threadIdx.x; i < P * nq; i += TL_BLOCK) {
+            const SelSlot sl = a.S->slot[1][i];
+            sprefix[i] = sl.prefix;
+            slive[i] = !sl.done;
+        }
+    }
+    __syncthreads();
+    const bool work = true;
     u64 acc_s_dec = 0, acc_d_dec = 0, acc_repre = 0, acc_mig = 0, acc_cnt = 0;
     double acc_tlast = 0.0;
     const i64 nwaves = (i64)gridDim.x * TL_WAVES;
@@ -355,8 +503,19 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
             if (!mask) continue;
             float* deliv = (dcol & mask) ? a.delivered + off : nullptr;
             TimelineResult res;
+            int cls = 0;
+            if (classify || (hist_pass && !h.fallback)) {
+                cls = cls_lookup(mask, s_cls, &a.S->tl, lane);
+                if (cls < 0) {                      // table full: the selection falls back to per-column histograms
+                    if (lane == 0) a.S->tl.error = 1;
+                    cls = 0;
+                }
+            }
+            if (classify) continue;
             auto sink = [&](const unsigned key[4], const bool ok[4]) {
-                if (hist_pass) hist_keys(h, key, ok, mask, lane);
+                if (!hist_pass) return;
+                if (h.fallback) hist_keys_cols(h, key, ok, mask, lane);
+                else hist_keys_cls(h, key, ok, cls, lane);
             };
             const float gap = variant == 0 ? gd : gap_src;
             const bool constant = variant == 0 || tr.arr == nullptr;
@@ -382,17 +541,30 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
             }
         }
     }
+    if (classify) {
+        if (!take_last_ticket(a.ticket)) return;
+        if (threadIdx.x == 0) {                     // all column sets are known: plan the first histogram pass
+            TlSel& tl = a.S->tl;
+            int n = 0;
+            for (int k = 0; k < DISCO_MAX_CLS; ++k)
+                if (__hip_atomic_load(&tl.cls_mask[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0ull) n = k + 1;
+            tl.ncls = n > 0 ? n : 1;
+            if (tl.error) { tl.fallback = 1; tl.error = 0; }
+            tl.left = 31;
+            tbt_plan_next(a.S, P, nq);
+            *a.ticket = 0u;
+        }
+        return;
+    }
     if (hist_pass) {
         __syncthreads();
-        if (work) {
-            const int words = ((a.pass == 0) ? P : P * nq) << h.width;
-            for (int i = threadIdx.x; i < words; i += TL_BLOCK) {
-                const unsigned cnt = smem[i];
-                if (cnt) atomicAdd(&a.ghist[i], cnt);
-            }
+        const int words = (h.fallback ? P * nq : h.G * h.ncls) << h.width;
+        for (int i = threadIdx.x; i < words; i += TL_BLOCK) {
+            const unsigned cnt = smem[i];
+            if (cnt) atomicAdd(&a.ghist[i], cnt);
         }
         if (!take_last_ticket(a.ticket)) return;
-        select_advance(a.S, 1, a.pass, P, nq, a.ghist);
+        tbt_advance(a.S, P, nq, a.ghist);
         if (threadIdx.x == 0) *a.ticket = 0u;
         return;
     }
@@ -430,32 +602,6 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
 }
 
 }  // namespace
-
-// Histogram plan of the TBT selection: raw 31-bit keys (gaps are never
-// negative), pass 0 shared by the quantiles of a column, 64 KB of bins.
-SelPlan disco_tbt_plan(int P, int nq)
-{
-    auto fit = [](int slots) {
-        int w = 0;
-        while (w < 14 && ((size_t)slots << (w + 1)) <= (size_t)TL_HIST_WORDS) ++w;
-        return w;
-    };
-    SelPlan pl;
-    memset(&pl, 0, sizeof(pl));
-    int left = 31;
-    const int w0 = fit(P), w = fit(P * (nq > 0 ? nq : 1));
-    int np = 0;
-    while (left > 0 && np < DISCO_MAX_PASS) {
-        int wd = (np == 0) ? w0 : w;
-        if (wd > left) wd = left;
-        pl.width[np] = wd;
-        pl.shift[np] = left - wd;
-        left -= wd;
-        ++np;
-    }
-    pl.npass = np;
-    return pl;
-}
 
 void disco_launch_timeline(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a, hipStream_t stream)
 {

@@ -340,3 +340,27 @@ def test_device_resident_policy_table(B, oracle):
         for qi in range(2):
             assert int(got[j]["ttft_rank"][qi]) == w["ttft_rank"][qi]
             assert np.float32(got[j]["ttft_q"][qi]) == np.float32(w["ttft_q"][qi])
+
+
+def test_stats_timelines_many_column_sets(B, oracle):
+    """Tables whose winner sets are not nested: more distinct column sets than the class table holds
+    (per-column histograms), and a few sets with several distinct prefixes."""
+    print("stats parity irregular column sets", flush=True)
+    rng = np.random.default_rng(5)
+    tr = DI.handmade_trace(91, 900, tokens=True, max_out=150, stall_p=0.04)
+    specs = []
+    for j in range(12):
+        if j % 3 == 0:
+            specs.append(dict(mode=0, l_th=int(rng.integers(0, 3000)), mig_mode=int(rng.integers(0, 2))))
+        elif j % 3 == 1:
+            specs.append(dict(mode=1, l_th=int(rng.integers(-1, 2000)), w_tail=DI.f32(rng.uniform(0, 1.5)),
+                              mig_mode=int(rng.integers(0, 2))))
+        else:
+            specs.append(dict(mode=1, l_th=-1, beta=DI.f32(rng.uniform(1e-4, 2e-3)), w_tail=DI.f32(rng.uniform(0.2, 2.0)),
+                              mig_mode=1))
+    check_stats(B, oracle, tr, specs, DI.COST_S, tau=DI.TAU, kappa=DI.KAPPA_LAG,
+                quantiles=((50, 100), (99, 100), (1, 100), (999, 1000)))
+    # slow devices (gap above the pacing interval): the device timeline needs the scan as well
+    tr2 = DI.handmade_trace(92, 400, tokens=True, max_out=300, stall_p=0.03)
+    tr2["dev_dec_spt"] = (tr2["dev_dec_spt"] * np.float32(2.5)).astype(np.float32)
+    check_stats(B, oracle, tr2, mixed_policies(lag=True), DI.COST_S, tau=DI.TAU, kappa=DI.KAPPA_LAG)
