@@ -31,6 +31,7 @@ struct WsLayout {
     size_t sel;        // select state (globals + slots)
     size_t ghist;      // unsigned[DISCO_MAX_SLOTS][256]
     size_t part;       // per-workgroup partials
+    size_t ppcnt;      // unsigned[DISCO_MAX_CLS][DISCO_PP_NMAX + 1]: pure-pacing requests per class and length
     size_t total;
 };
 WsLayout disco_ws_layout(int32_t P);

@@ -268,6 +268,7 @@ WsLayout disco_ws_layout(int32_t P)
     L.part = o;
     (void)P;
     o += up((size_t)DISCO_MAX_BLOCKS * 64 * 64);     // workgroups x columns x 64-byte partial
+    L.ppcnt = o; o += up(sizeof(unsigned) * DISCO_MAX_CLS * (DISCO_PP_NMAX + 1));
     L.total = o;
     return L;
 }
@@ -409,8 +410,9 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             a.S = S; a.ghist = gh;
             // column sets -> classes, then the radix passes; the digits are sized on the device and
             // launches after the last needed pass return at once
-            a.pass = -2;
-            disco_launch_timeline(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
+            a.ppcnt = (unsigned*)(ws + L.ppcnt);
+            disco_launch_tl_prepare(v, (const disco_policy*)(ws + L.pol), P, nq, tl->tau, S, a.ppcnt,
+                                    (unsigned*)(ws + L.ticket), stream);
             for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;
                 disco_launch_timeline(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);

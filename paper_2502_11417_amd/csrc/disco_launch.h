@@ -4,10 +4,11 @@
 
 struct TimelineArgs {
     float tau, kt;            // pacing interval, kappa_lag * tau
-    int P, nq, pass;          // -1: statistics pass, -2: classification of the column sets, >= 0: TBT histogram pass
+    int P, nq, pass;          // -1: statistics pass, >= 0: TBT histogram pass
     int32_t* mig_idx; int32_t* n_src_tok; float* t_last; float* delivered; int delivered_col;
     MigPartial* part; unsigned* ticket; disco_accum* acc;
     SelState* S; unsigned* ghist;
+    unsigned* ppcnt;          // pure-pacing suffix counts per class and token index (histogram passes)
 };
 
 // How the last workgroup of a dispatch pass hands on the column totals.
@@ -28,5 +29,7 @@ void disco_launch_ttft_hist(const TraceView& v, const disco_policy* pol, int P, 
                             unsigned* gh, unsigned* ticket, hipStream_t stream);
 void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,
                                hipStream_t stream);
+void disco_launch_tl_prepare(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
+                             unsigned* ppcnt, unsigned* ticket, hipStream_t stream);
 void disco_launch_timeline(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                            hipStream_t stream);

@@ -24,7 +24,8 @@ struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
 // nested, so there are at most P + 1 of them), not once per column.  Keys are
 // the raw 31-bit patterns of the gaps.  The digit of each pass is sized on the
 // device from the number of classes and of distinct prefixes still alive.
-enum { DISCO_MAX_CLS = 64, DISCO_MAX_GRP = 4, DISCO_TBT_MAX_PASS = 6, DISCO_TL_HIST_WORDS = 16384 };
+enum { DISCO_MAX_CLS = 64, DISCO_MAX_GRP = 4, DISCO_TBT_MAX_PASS = 6, DISCO_TL_HIST_WORDS = 16384,
+       DISCO_PP_NMAX = 4096 };    // pure-pacing timelines up to this length are histogrammed analytically
 struct TlSel {
     u64 cls_mask[DISCO_MAX_CLS];   // column set of each class, 0 = free
     int ncls;

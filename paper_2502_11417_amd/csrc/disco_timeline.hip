@@ -217,13 +217,37 @@ __device__ void tbt_plan_next(SelState* S, int P, int nq)
 // the classes that contain the slot's column (or take the slot's own
 // histogram in the fallback), walk to the digit that holds the remaining
 // rank, extend the prefix; then plan the next pass and clear the bins.
-__device__ void tbt_advance(SelState* S, int P, int nq, unsigned* ghist)
+__device__ void tbt_advance(SelState* S, int P, int nq, unsigned* ghist, const unsigned* ppcnt, float tau, unsigned* lds)
 {
     TlSel& tl = S->tl;
     const int width = tl.width, ncls = tl.ncls, fallback = tl.fallback;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int Gused = tl.G < DISCO_MAX_GRP ? tl.G : DISCO_MAX_GRP;
     __syncthreads();
+    if (width > 0 && !fallback) {
+        // pure-pacing timelines: delta_t = round(t tau), so the gap in front of token t is the same for all
+        // of them; ppcnt[c][t] timelines of class c have a token t.  Bins are gathered in LDS first.
+        const int words = (Gused * ncls) << width;
+        const int shift = tl.shift, up = tl.shift + width;
+        const unsigned dmask = (1u << width) - 1u;
+        for (int i = threadIdx.x; i < words; i += blockDim.x) lds[i] = 0u;
+        __syncthreads();
+        for (int t = 1 + (int)threadIdx.x; t < DISCO_PP_NMAX; t += blockDim.x) {
+            const unsigned key = f2u((float)t * tau - (float)(t - 1) * tau);
+            const unsigned hi = up >= 32 ? 0u : (key >> up);
+            int g = -1;
+            for (int k = 0; k < Gused; ++k) g = (hi == tl.grp_prefix[k] && g < 0) ? k : g;
+            if (g < 0) continue;
+            for (int c = 0; c < ncls; ++c) {
+                const unsigned cnt = ppcnt[(size_t)c * (DISCO_PP_NMAX + 1) + t];
+                if (cnt) atomicAdd(&lds[((unsigned)(g * ncls + c) << width) | ((key >> shift) & dmask)], cnt);
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < words; i += blockDim.x) ghist[i] += lds[i];
+        __threadfence_block();
+        __syncthreads();
+    }
     if (width > 0) {
         const int nbins = 1 << width;
         const int per = (nbins + 63) >> 6;
@@ -432,23 +456,24 @@ __device__ __forceinline__ TimelineResult run_pure_pacing(int n, float tau, int 
     return TimelineResult{-1, (float)(n - 1) * tau};
 }
 
-constexpr int TL_BLOCK = 512;
+constexpr int TL_BLOCK = 1024;
 constexpr int TL_WAVES = TL_BLOCK / 64;
+constexpr int TL_RB = 16;                   // requests per wave batch
 constexpr int TL_HIST_WORDS = 16384;        // 64 KB of LDS histogram: two workgroups per CU
 
-__global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, int align,
+__global__ __launch_bounds__(TL_BLOCK, 2) void k_timeline(TraceView tr, i64 n_tok, int align,
                                                        const disco_policy* __restrict__ pol, TimelineArgs a)
 {
     __shared__ __align__(16) unsigned smem[TL_HIST_WORDS];
     __shared__ unsigned sprefix[DISCO_MAX_SLOTS];
     __shared__ int slive[DISCO_MAX_SLOTS];
     __shared__ u64 s_cls[DISCO_MAX_CLS];
+    __shared__ disco_policy spol[DISCO_MAX_COLS];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int P = a.P, nq = a.nq;
-    const bool colv = lane < P;
-    const disco_policy p = pol[colv ? lane : 0];
-    const bool hist_pass = a.pass >= 0;       // pass -1: statistics, -2: classification of the column sets
-    const bool classify = a.pass == -2;
+    if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
+    const bool hist_pass = a.pass >= 0;       // pass -1: statistics
+    const bool classify = false;
     HistCtx h;
     h.hist = smem; h.shift = 0; h.width = 0; h.up = 0; h.fallback = 0; h.ncls = 1; h.G = 0; h.nq = nq;
     h.s_cls = s_cls; h.sprefix = sprefix; h.slive = slive;
@@ -479,20 +504,43 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
     u64 acc_s_dec = 0, acc_d_dec = 0, acc_repre = 0, acc_mig = 0, acc_cnt = 0;
     double acc_tlast = 0.0;
     const i64 nwaves = (i64)gridDim.x * TL_WAVES;
-    for (i64 i = (i64)blockIdx.x * TL_WAVES + wave; work && i < tr.n_req; i += nwaves) {
-        const int l = tr.l[i], n = tr.n[i];
-        const float s = tr.s[i];
-        const float k = tr.k ? tr.k[i] : tr.k_s;
-        const float gd = tr.g ? tr.g[i] : tr.g_s;
-        const float d = __fmaf_rn((float)l, k, tr.c);
-        unsigned dec; float ttft;
-        dispatch_pair(p, l, s, d, dec, ttft);
-        const bool dev_src = (dec & 4u) != 0u;
-        const u64 mask_dev = __ballot(colv && dev_src);
-        const u64 mask_plain = __ballot(colv && !dev_src && p.mig_mode != DISCO_MIG_LAG);
-        const u64 mask_lag = __ballot(colv && !dev_src && p.mig_mode == DISCO_MIG_LAG);
-        const i64 off = tr.off ? tr.off[i] : 0;
-        const float gap_src = tr.tbt ? tr.tbt[i] : 0.0f;
+    // A wave takes TL_RB consecutive requests at a time.  Phase A, lane = request: the fields are
+    // loaded coalesced and every column's dispatch is evaluated, giving the three column sets of the
+    // request (device source, server source, server source with lag hand-off).  Phase B walks the
+    // requests one by one with the whole wave on the tokens.
+    const i64 nbatch = (tr.n_req + TL_RB - 1) / TL_RB;
+    for (i64 bt = (i64)blockIdx.x * TL_WAVES + wave; work && bt < nbatch; bt += nwaves) {
+        const i64 ia = bt * TL_RB + lane;
+        const bool va = lane < TL_RB && ia < tr.n_req;
+        int l_v = 0, n_v = 1;
+        float s_v = 0.0f, k_v = tr.k_s, g_v = tr.g_s, gap_v = 0.0f;
+        i64 off_v = 0;
+        if (va) {
+            l_v = tr.l[ia]; n_v = tr.n[ia]; s_v = tr.s[ia];
+            if (tr.k) k_v = tr.k[ia];
+            if (tr.g) g_v = tr.g[ia];
+            if (tr.off) off_v = tr.off[ia];
+            if (tr.tbt) gap_v = tr.tbt[ia];
+        }
+        u64 m_v[3] = {0ull, 0ull, 0ull};
+        {
+            const float d_v = __fmaf_rn((float)l_v, k_v, tr.c);
+            for (int j = 0; j < P; ++j) {
+                unsigned dec; float t;
+                dispatch_pair(spol[j], l_v, s_v, d_v, dec, t);
+                const int kind = (dec & 4u) ? 0 : (spol[j].mig_mode == DISCO_MIG_LAG ? 2 : 1);
+                m_v[kind] |= va ? (1ull << j) : 0ull;
+            }
+        }
+        const int cnt = (int)((tr.n_req - bt * TL_RB < TL_RB) ? (tr.n_req - bt * TL_RB) : TL_RB);
+#pragma unroll 1
+      for (int rq = 0; rq < cnt; ++rq) {
+        const i64 i = bt * TL_RB + rq;
+        const int l = bcast_i(l_v, rq), n = bcast_i(n_v, rq);
+        const float k = bcast_f(k_v, rq), gd = bcast_f(g_v, rq);
+        const float gap_src = bcast_f(gap_v, rq);
+        const i64 off = (i64)bcast_u64((u64)off_v, rq);
+        const u64 mask_dev = bcast_u64(m_v[0], rq), mask_plain = bcast_u64(m_v[1], rq), mask_lag = bcast_u64(m_v[2], rq);
         const u64 dcol = (a.delivered != nullptr && !hist_pass) ? (1ull << a.delivered_col) : 0ull;
         TimelineResult res_lag{-1, 0.0f};
         bool lag_done = false;
@@ -522,7 +570,9 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
             if (variant == 1 && lag_done && res_lag.m < 0 && !hist_pass && !deliv) {
                 res = res_lag;
             } else if (constant && gap < 0.999f * a.tau) {
-                res = run_pure_pacing(n, a.tau, lane, deliv, hist_pass, sink);
+                // in a class-mode histogram pass the bins of short pure-pacing timelines are filled analytically
+                const bool walk = hist_pass && (h.fallback || n > DISCO_PP_NMAX);
+                res = run_pure_pacing(n, a.tau, lane, deliv, walk, sink);
             } else {
                 res = run_timeline(variant, n, tr.arr, off, n_tok, align, gap_src, gd, l, k, tr.c, a.tau, a.kt, lane,
                                    deliv, sink);
@@ -540,21 +590,7 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
                 if (a.t_last) a.t_last[(size_t)lane * tr.n_req + i] = res.t_last;
             }
         }
-    }
-    if (classify) {
-        if (!take_last_ticket(a.ticket)) return;
-        if (threadIdx.x == 0) {                     // all column sets are known: plan the first histogram pass
-            TlSel& tl = a.S->tl;
-            int n = 0;
-            for (int k = 0; k < DISCO_MAX_CLS; ++k)
-                if (__hip_atomic_load(&tl.cls_mask[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0ull) n = k + 1;
-            tl.ncls = n > 0 ? n : 1;
-            if (tl.error) { tl.fallback = 1; tl.error = 0; }
-            tl.left = 31;
-            tbt_plan_next(a.S, P, nq);
-            *a.ticket = 0u;
-        }
-        return;
+      }
     }
     if (hist_pass) {
         __syncthreads();
@@ -564,12 +600,12 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
             if (cnt) atomicAdd(&a.ghist[i], cnt);
         }
         if (!take_last_ticket(a.ticket)) return;
-        tbt_advance(a.S, P, nq, a.ghist);
+        tbt_advance(a.S, P, nq, a.ghist, a.ppcnt, a.tau, smem);
         if (threadIdx.x == 0) *a.ticket = 0u;
         return;
     }
     // statistics pass: fold the waves of the workgroup, then the workgroups (fixed order)
-    u64* sh = reinterpret_cast<u64*>(smem);                                  // 8 fields x TL_BLOCK entries = 32 KB
+    u64* sh = reinterpret_cast<u64*>(smem);                                  // 8 fields x TL_BLOCK entries = 64 KB
     auto add = [](MigPartial& x, const MigPartial& o) {
         x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
         x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
@@ -601,11 +637,172 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
     if (threadIdx.x == 0) *a.ticket = 0u;
 }
 
+// The three column sets of a request, lane = request.
+__device__ __forceinline__ void request_sets(const TraceView& tr, const disco_policy* sp, int P, i64 i, bool v, u64 m[3],
+                                             int& n, float& gd, float& gap)
+{
+    m[0] = m[1] = m[2] = 0ull;
+    n = 1; gd = tr.g_s; gap = 0.0f;
+    if (!v) return;
+    const int l = tr.l[i];
+    const float s = tr.s[i];
+    const float k = tr.k ? tr.k[i] : tr.k_s;
+    const float d = __fmaf_rn((float)l, k, tr.c);
+    n = tr.n[i];
+    if (tr.g) gd = tr.g[i];
+    if (tr.tbt) gap = tr.tbt[i];
+    for (int j = 0; j < P; ++j) {
+        unsigned dec; float t;
+        dispatch_pair(sp[j], l, s, d, dec, t);
+        const int kind = (dec & 4u) ? 0 : (sp[j].mig_mode == DISCO_MIG_LAG ? 2 : 1);
+        m[kind] |= 1ull << j;
+    }
+}
+
+// Column sets of every request -> classes.  The distinct sets of a workgroup
+// are first collected in LDS and then claimed in the device-wide table by one
+// wave, so the few hot table lines are touched once per workgroup; the last
+// workgroup plans the first histogram pass.  Also clears the length counts.
+__global__ __launch_bounds__(256) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
+                                                     SelState* S, unsigned* ppcnt, unsigned* ticket)
+{
+    __shared__ disco_policy sp[DISCO_MAX_COLS];
+    __shared__ u64 loc[DISCO_MAX_CLS];
+    __shared__ u64 s_cls[DISCO_MAX_CLS];
+    __shared__ int overflow;
+    if ((int)threadIdx.x < P) sp[threadIdx.x] = pol[threadIdx.x];
+    if (threadIdx.x < DISCO_MAX_CLS) { loc[threadIdx.x] = 0ull; s_cls[threadIdx.x] = 0ull; }
+    if (threadIdx.x == 0) overflow = 0;
+    for (i64 w = (i64)blockIdx.x * 256 + threadIdx.x; w < (i64)DISCO_MAX_CLS * (DISCO_PP_NMAX + 1); w += (i64)gridDim.x * 256)
+        ppcnt[w] = 0u;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const i64 nround = (tr.n_req + 255) / 256;
+    for (i64 rnd = blockIdx.x; rnd < nround; rnd += gridDim.x) {
+        const i64 i = rnd * 256 + threadIdx.x;
+        u64 m[3];
+        int n; float gd, gap;
+        request_sets(tr, sp, P, i, i < tr.n_req, m, n, gd, gap);
+#pragma unroll
+        for (int kind = 0; kind < 3; ++kind) {
+            u64 pend = __ballot(m[kind] != 0ull);
+            while (pend) {
+                const int leader = __ffsll((long long)pend) - 1;
+                const u64 m0 = bcast_u64(m[kind], leader);
+                pend &= ~__ballot(m[kind] == m0);
+                for (int attempt = 0; attempt < DISCO_MAX_CLS + 1; ++attempt) {     // insert m0 into the workgroup's table
+                    const u64 cur = loc[lane];
+                    if (__ballot(cur == m0)) break;
+                    const u64 free = __ballot(cur == 0ull);
+                    if (!free) { if (lane == 0) overflow = 1; break; }
+                    const int e = __ffsll((long long)free) - 1;
+                    if (lane == 0) atomicCAS((unsigned long long*)&loc[e], 0ull, (unsigned long long)m0);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        u64 mine = __ballot(loc[lane] != 0ull);
+        bool bad = overflow != 0;
+        while (mine) {
+            const int e = __ffsll((long long)mine) - 1;
+            mine &= mine - 1;
+            if (cls_lookup(loc[e], s_cls, &S->tl, lane) < 0) bad = true;
+        }
+        if (bad && lane == 0) S->tl.error = 1;
+    }
+    if (!take_last_ticket(ticket)) return;
+    if (threadIdx.x == 0) {
+        TlSel& tl = S->tl;
+        int n = 0;
+        for (int k = 0; k < DISCO_MAX_CLS; ++k)
+            if (__hip_atomic_load(&tl.cls_mask[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0ull) n = k + 1;
+        tl.ncls = n > 0 ? n : 1;
+        if (__hip_atomic_load(&tl.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { tl.fallback = 1; tl.error = 0; }
+        tl.left = 31;
+        tbt_plan_next(S, P, nq);
+        *ticket = 0u;
+    }
+}
+
+// Is the timeline of this kind pure pacing (see run_pure_pacing) and short
+// enough for the analytic histogram?
+__device__ __forceinline__ bool analytic_kind(const TraceView& tr, int kind, int n, float gd, float gap, float tau)
+{
+    const bool constant = kind == 0 || tr.arr == nullptr;
+    const float gp = kind == 0 ? gd : gap;
+    return constant && gp < 0.999f * tau && n <= DISCO_PP_NMAX;
+}
+
+// Pure-pacing timelines depend on their length alone: count them per class
+// and length instead of walking their tokens in every histogram pass.
+__global__ __launch_bounds__(256) void k_pp_count(TraceView tr, const disco_policy* __restrict__ pol, int P, float tau,
+                                                  SelState* S, unsigned* ppcnt)
+{
+    __shared__ disco_policy sp[DISCO_MAX_COLS];
+    __shared__ u64 s_cls[DISCO_MAX_CLS];
+    if (S->tl.fallback) return;
+    if ((int)threadIdx.x < P) sp[threadIdx.x] = pol[threadIdx.x];
+    if (threadIdx.x < DISCO_MAX_CLS) s_cls[threadIdx.x] = S->tl.cls_mask[threadIdx.x];
+    __syncthreads();
+    for (i64 i = (i64)blockIdx.x * 256 + threadIdx.x; i < tr.n_req; i += (i64)gridDim.x * 256) {
+        u64 m[3];
+        int n; float gd, gap;
+        request_sets(tr, sp, P, i, true, m, n, gd, gap);
+#pragma unroll
+        for (int kind = 0; kind < 3; ++kind) {
+            if (m[kind] == 0ull || !analytic_kind(tr, kind, n, gd, gap, tau)) continue;
+            int c = -1;
+            for (int k = 0; k < DISCO_MAX_CLS; ++k) c = (s_cls[k] == m[kind]) ? k : c;
+            if (c >= 0) atomicAdd(&ppcnt[(size_t)c * (DISCO_PP_NMAX + 1) + n], 1u);
+            else S->tl.error = 1;          // a set the classification did not see: never expected
+        }
+    }
+}
+
+// Per class: counts by length -> number of timelines longer than t (in place).
+__global__ __launch_bounds__(1024) void k_pp_suffix(SelState* S, unsigned* ppcnt)
+{
+    __shared__ unsigned part[1024];
+    if (S->tl.fallback || (int)blockIdx.x >= S->tl.ncls) return;
+    unsigned* row = ppcnt + (size_t)blockIdx.x * (DISCO_PP_NMAX + 1);
+    constexpr int PER = (DISCO_PP_NMAX + 1 + 1023) / 1024;
+    const int t0 = threadIdx.x * PER;
+    unsigned v[PER];
+    unsigned sum = 0;
+    for (int q = 0; q < PER; ++q) { v[q] = (t0 + q <= DISCO_PP_NMAX) ? row[t0 + q] : 0u; sum += v[q]; }
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {            // inclusive suffix sums of the per-thread totals
+        const unsigned o = (threadIdx.x + d < 1024) ? part[threadIdx.x + d] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += o;
+        __syncthreads();
+    }
+    unsigned above = (threadIdx.x + 1 < 1024) ? part[threadIdx.x + 1] : 0u;       // lengths beyond this thread's slice
+    for (int q = PER - 1; q >= 0; --q) {
+        if (t0 + q <= DISCO_PP_NMAX) row[t0 + q] = above;                         // timelines with n > t0 + q
+        above += v[q];
+    }
+}
+
 }  // namespace
+
+void disco_launch_tl_prepare(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
+                             unsigned* ppcnt, unsigned* ticket, hipStream_t stream)
+{
+    i64 b = (v.n_req + 255) / 256;
+    if (b < 1) b = 1;
+    if (b > 512) b = 512;
+    hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(256), 0, stream, v, pol, P, nq, S, ppcnt, ticket);
+    hipLaunchKernelGGL(k_pp_count, dim3((unsigned)b), dim3(256), 0, stream, v, pol, P, tau, S, ppcnt);
+    hipLaunchKernelGGL(k_pp_suffix, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ppcnt);
+}
 
 void disco_launch_timeline(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a, hipStream_t stream)
 {
-    i64 b = (v.n_req + TL_WAVES - 1) / TL_WAVES;
+    i64 b = (v.n_req + (i64)TL_WAVES * TL_RB - 1) / ((i64)TL_WAVES * TL_RB);
     if (b < 1) b = 1;
     if (b > 512) b = 512;                     // two resident workgroups per CU
     const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
