@@ -29,9 +29,9 @@ struct WsLayout {
     size_t ticket;     // unsigned[64] counters (zeroed by the library before use)
     size_t search;     // SearchState[64]
     size_t sel;        // select state (globals + slots)
-    size_t ghist;      // unsigned[DISCO_MAX_SLOTS][256]
-    size_t part;       // per-workgroup partials
-    size_t ppcnt;      // unsigned[DISCO_MAX_CLS][DISCO_PP_NMAX + 1]: pure-pacing requests per class and length
+    size_t ghist;      // unsigned[DISCO_GHIST_WORDS] device-wide histogram bins
+    size_t part;       // device-wide totals (dispatch, then timeline), per-workgroup partials of the general timeline kernel
+    size_t ppcnt;      // unsigned[DISCO_MAX_CLS][DISCO_PP_NMAX + 1]: pure-pacing timelines per class and length
     size_t total;
 };
 WsLayout disco_ws_layout(int32_t P);

@@ -3,17 +3,12 @@
 //
 // Work decomposition
 //   dispatch-type passes: a wave holds up to 64 policy columns in its lanes
-//     (lane = sub * G + column, G = columns rounded up to a power of two) and
-//     walks the requests in batches of 64; the batch is loaded coalesced, one
-//     request per lane, and handed to the column lanes with lane broadcasts.
-//     Per-column totals stay in registers until the end of the kernel.
-//   timeline passes: one wave per request, one token per lane, 64-token
-//     chunks with a carried running maximum; the per-request scalars of each
-//     column are accumulated by lane = column.
-//   every pass ends in the workgroup that takes the last ticket: it folds the
-//     per-workgroup partials in a fixed order (bit-reproducible sums) and, for
-//     select and search passes, advances the device-resident state, so a
-//     sequence of passes needs no host round trip.
+//     and walks the requests in batches; per-column totals stay in registers
+//     until the end of the kernel and are then added into device-wide totals.
+//   timeline passes: one wave per request, four tokens per lane, 256-token
+//     chunks with a carried running maximum.
+//   a sequence of passes (budget search, radix selection) advances its state
+//     on the device, so it needs no host round trip.
 #include <math.h>
 #include <stdio.h>
 #include <string.h>
@@ -23,15 +18,24 @@
 
 namespace {
 
+// The timeline totals follow the dispatch totals in the same workspace region.
+__host__ __device__ inline MigPartial* tl_totals(DispPartial* totals)
+{
+    return reinterpret_cast<MigPartial*>(totals + DISCO_NCOPY * 64);
+}
+
 // Staging of the policy table; also puts the tickets and the per-column
-// totals that the workgroups of a dispatch pass add into at their identity.
+// totals that the workgroups of a pass add into at their identity.
 __global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets, DispPartial* totals)
 {
     int i = threadIdx.x;
     if (i < P) dst[i] = t.p[i];
     if (i < 64) {
         tickets[i] = 0u;
-        for (int k = 0; k < DISCO_NCOPY; ++k) totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+        for (int k = 0; k < DISCO_NCOPY; ++k) {
+            totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+            tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
+        }
     }
 }
 
@@ -41,7 +45,10 @@ __global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* ds
     if (i < P) dst[i] = src[i];
     if (i < 64) {
         tickets[i] = 0u;
-        for (int k = 0; k < DISCO_NCOPY; ++k) totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+        for (int k = 0; k < DISCO_NCOPY; ++k) {
+            totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
+            tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
+        }
     }
 }
 
@@ -85,7 +92,7 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
             g.plan.npass = 0; g.plan.pad = 0;
             for (int i = 0; i < DISCO_MAX_PASS; ++i) { g.plan.shift[i] = 0; g.plan.width[i] = 0; }
             TlSel& tl = S->tl;
-            tl.ncls = 0; tl.fallback = 0; tl.error = 0; tl.left = 31; tl.shift = 0; tl.width = 0; tl.G = 0;
+            tl.ncls = 0; tl.nwalk = 0; tl.walk_mask = 0ull; tl.fallback = 0; tl.error = 0; tl.left = 31; tl.shift = 0; tl.width = 0; tl.G = 0;
             for (int i = 0; i < DISCO_MAX_GRP; ++i) tl.grp_prefix[i] = 0u;
         }
         S->g[which] = g;
@@ -105,7 +112,8 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
         sl.rank = k; sl.k_rem = k; sl.prefix = 0u; sl.done = (M <= 0);
         S->slot[which][s] = sl;
     }
-    for (int i = threadIdx.x; i < DISCO_MAX_SLOTS * 256; i += blockDim.x) ghist[i] = 0u;
+    if (which == 0)
+        for (int i = threadIdx.x; i < DISCO_MAX_SLOTS * 256; i += blockDim.x) ghist[i] = 0u;     // TBT: cleared by the classification
 }
 
 // ------------------------------------------------------------ final stats --
@@ -264,7 +272,7 @@ WsLayout disco_ws_layout(int32_t P)
     L.ticket = o; o += up(sizeof(unsigned) * 64);
     L.search = o; o += up(sizeof(SearchState) * DISCO_MAX_COLS);
     L.sel = o; o += up(sizeof(SelState));
-    L.ghist = o; o += up(sizeof(unsigned) * DISCO_MAX_SLOTS * 256);
+    L.ghist = o; o += up(sizeof(unsigned) * DISCO_GHIST_WORDS);
     L.part = o;
     (void)P;
     o += up((size_t)DISCO_MAX_BLOCKS * 64 * 64);     // workgroups x columns x 64-byte partial
@@ -360,7 +368,11 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
     a.acc = acc;
     a.S = (SelState*)(ws + L.sel);
     a.ghist = (unsigned*)(ws + L.ghist);
-    disco_launch_timeline(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
+    if (a.delivered)
+        disco_launch_timeline_general(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
+    else
+        disco_launch_tl_stats_fast(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a,
+                                   tl_totals((DispPartial*)(ws + L.part)), stream);
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }
@@ -411,11 +423,13 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             // column sets -> classes, then the radix passes; the digits are sized on the device and
             // launches after the last needed pass return at once
             a.ppcnt = (unsigned*)(ws + L.ppcnt);
-            disco_launch_tl_prepare(v, (const disco_policy*)(ws + L.pol), P, nq, tl->tau, S, a.ppcnt,
-                                    (unsigned*)(ws + L.ticket), stream);
+            const disco_policy* dpol = (const disco_policy*)(ws + L.pol);
+            disco_launch_tl_classify(v, dpol, P, nq, tl->tau, S, a.ppcnt, gh, (unsigned*)(ws + L.ticket), stream);
             for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;
-                disco_launch_timeline(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
+                disco_launch_tl_hist_fast(v, trace->n_tok, dpol, a, stream);
+                disco_launch_timeline_general(v, trace->n_tok, dpol, a, stream);
+                disco_launch_tbt_advance(S, P, nq, gh, a.ppcnt, tl->tau, pass, stream);
             }
         }
     }

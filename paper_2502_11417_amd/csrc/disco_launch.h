@@ -8,7 +8,7 @@ struct TimelineArgs {
     int32_t* mig_idx; int32_t* n_src_tok; float* t_last; float* delivered; int delivered_col;
     MigPartial* part; unsigned* ticket; disco_accum* acc;
     SelState* S; unsigned* ghist;
-    unsigned* ppcnt;          // pure-pacing suffix counts per class and token index (histogram passes)
+    unsigned* ppcnt;          // pure-pacing timelines per class and length (histogram passes)
 };
 
 // How the last workgroup of a dispatch pass hands on the column totals.
@@ -29,7 +29,17 @@ void disco_launch_ttft_hist(const TraceView& v, const disco_policy* pol, int P, 
                             unsigned* gh, unsigned* ticket, hipStream_t stream);
 void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,
                                hipStream_t stream);
-void disco_launch_tl_prepare(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
-                             unsigned* ppcnt, unsigned* ticket, hipStream_t stream);
-void disco_launch_timeline(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
-                           hipStream_t stream);
+// Token timelines.  Statistics pass (a.pass = -1): streaming kernel, or the general kernel when the
+// per-token deliveries of a column are wanted.  TBT selection: classification, then per pass the class
+// histograms (streaming kernel) or the per-slot histograms (general kernel; exactly one of the two acts,
+// decided on the device), then the digit selection.
+void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
+                                MigPartial* totals, hipStream_t stream);
+void disco_launch_timeline_general(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
+                                   hipStream_t stream);
+void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
+                              unsigned* ppcnt, unsigned* ghist, unsigned* ticket, hipStream_t stream);
+void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
+                               hipStream_t stream);
+void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,
+                              hipStream_t stream);

@@ -24,11 +24,14 @@ struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
 // nested, so there are at most P + 1 of them), not once per column.  Keys are
 // the raw 31-bit patterns of the gaps.  The digit of each pass is sized on the
 // device from the number of classes and of distinct prefixes still alive.
-enum { DISCO_MAX_CLS = 64, DISCO_MAX_GRP = 4, DISCO_TBT_MAX_PASS = 6, DISCO_TL_HIST_WORDS = 16384,
-       DISCO_PP_NMAX = 4096 };    // pure-pacing timelines up to this length are histogrammed analytically
+enum { DISCO_MAX_CLS = 64, DISCO_MAX_GRP = 4, DISCO_TBT_MAX_PASS = 6,
+       DISCO_TL_HIST_WORDS = 16384,   // LDS bins of a timeline workgroup (64 KB: two workgroups per CU)
+       DISCO_GHIST_WORDS = 262144,    // device-wide bins (1 MB)
+       DISCO_PP_NMAX = 4096 };        // pure-pacing timelines up to this length are histogrammed analytically
 struct TlSel {
     u64 cls_mask[DISCO_MAX_CLS];   // column set of each class, 0 = free
-    int ncls;
+    u64 walk_mask;                 // classes with a timeline whose tokens have to be walked
+    int ncls, nwalk;
     int fallback;                  // 1: one histogram per (column, quantile) slot instead of per class
     int error;                     // a column set could not be placed (never expected)
     int left;                      // undecided key bits
@@ -36,7 +39,8 @@ struct TlSel {
     int G;                         // distinct prefixes among the live slots
     unsigned grp_prefix[DISCO_MAX_GRP];
     int slot_grp[DISCO_MAX_SLOTS]; // prefix group of each live slot, -1 otherwise
-    int pad[3];
+    signed char cls_slot[DISCO_MAX_CLS];     // row of a walked class in the workgroups' LDS histogram, -1 otherwise
+    unsigned char slot_cls[DISCO_MAX_CLS];   // class of an LDS row
 };
 struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; TlSel tl; };   // [0] TTFT, [1] TBT
 

@@ -1,0 +1,143 @@
+// Device-side pieces shared by the token-timeline kernels (Sec. 4.3): wave
+// scans of the running maximum, the column sets of a request, the class table
+// of the TBT selection.
+#pragma once
+#include <math.h>
+
+#include "disco_launch.h"
+#include "disco_state.h"
+
+namespace {
+
+// ---------------------------------------------------------------- scans ----
+
+// dpp_ctrl encodings (GFX9): row_shr:n = 0x110 + n, wave_shr:1 = 0x138.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float old, float src)
+{
+    return u2f((unsigned)__builtin_amdgcn_update_dpp((int)f2u(old), (int)f2u(src), CTRL, 0xF, 0xF, false));
+}
+
+// Inclusive running maximum over the 64 lanes: Hillis-Steele inside each row
+// of 16 lanes with DPP row shifts (lanes whose source falls off the row keep
+// -inf), then the three row totals are handed on through scalar registers.
+__device__ __forceinline__ float wave_incl_max_dpp(float v, int lane)
+{
+    const float ninf = -INFINITY;
+    v = fmaxf(v, dpp_mov<0x111>(ninf, v));
+    v = fmaxf(v, dpp_mov<0x112>(ninf, v));
+    v = fmaxf(v, dpp_mov<0x114>(ninf, v));
+    v = fmaxf(v, dpp_mov<0x118>(ninf, v));
+    const float t0 = bcast_f(v, 15), t1 = bcast_f(v, 31), t2 = bcast_f(v, 47);
+    const float p1 = t0, p2 = fmaxf(t0, t1), p3 = fmaxf(p2, t2);
+    const int row = lane >> 4;
+    const float add = row == 0 ? ninf : (row == 1 ? p1 : (row == 2 ? p2 : p3));
+    return fmaxf(v, add);
+}
+
+// Maximum over the wave, uniform.
+__device__ __forceinline__ float wave_max_f32(float v)
+{
+    const float ninf = -INFINITY;
+    v = fmaxf(v, dpp_mov<0x111>(ninf, v));
+    v = fmaxf(v, dpp_mov<0x112>(ninf, v));
+    v = fmaxf(v, dpp_mov<0x114>(ninf, v));
+    v = fmaxf(v, dpp_mov<0x118>(ninf, v));
+    return fmaxf(fmaxf(bcast_f(v, 15), bcast_f(v, 31)), fmaxf(bcast_f(v, 47), bcast_f(v, 63)));
+}
+
+// Value of the previous lane (lane 0 receives `first`).
+__device__ __forceinline__ float wave_prev(float v, float first)
+{
+    return dpp_mov<0x138>(first, v);
+}
+
+// Loads the four arrival offsets of a lane: `g` is the global index of the
+// lane's first element (a multiple of four elements away from a 16-byte
+// boundary of the array); elements outside [0, n_tok) read as 0.
+__device__ __forceinline__ void load4(const float* __restrict__ arr, i64 g, i64 n_tok, float r[4])
+{
+    if (g >= 0 && g + 3 < n_tok) {
+        const float4 v = *reinterpret_cast<const float4*>(arr + g);
+        r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r[k] = (g + k >= 0 && g + k < n_tok) ? arr[g + k] : 0.0f;
+    }
+}
+
+// ---------------------------------------------------------- column sets ----
+
+// The three column sets of a request (lane = request): columns whose source is
+// the device [0], the server without hand-off [1], the server with the lag
+// trigger [2].
+__device__ __forceinline__ void request_sets(const disco_policy* sp, int P, int l, float s, float d, u64 m[3])
+{
+    u64 m0 = 0ull, m1 = 0ull, m2 = 0ull;
+    for (int j = 0; j < P; ++j) {
+        unsigned dec; float t;
+        dispatch_pair(sp[j], l, s, d, dec, t);
+        const bool dev = (dec & 4u) != 0u;
+        const bool lagm = sp[j].mig_mode == DISCO_MIG_LAG;
+        const u64 bit = 1ull << j;
+        m0 |= dev ? bit : 0ull;
+        m1 |= (!dev && !lagm) ? bit : 0ull;
+        m2 |= (!dev && lagm) ? bit : 0ull;
+    }
+    m[0] = m0; m[1] = m1; m[2] = m2;
+}
+
+// Pure pacing: a source whose constant gap is safely below tau (gap < 0.999 tau).
+// Then u_0 = 0 and u_t = round(round(t gap) - t tau) < 0 for t >= 1 (the
+// product's rounding error is below 2^-24 relative, far inside the 1e-3
+// margin), the running maximum stays 0, delta_t = fma(t, tau, 0) = round(t tau),
+// and no token is ever overdue.  The timeline depends on its length alone.
+__device__ __forceinline__ bool pure_pacing(bool constant_gap, float gap, float tau)
+{
+    return constant_gap && gap < 0.999f * tau;
+}
+
+// Class of a column set: index in the device-wide table, claimed on first use.
+// Wave-uniform.  Returns -1 when the table is full.
+__device__ __forceinline__ int cls_lookup(u64 mask, u64* s_cls, TlSel* tl, int lane)
+{
+    for (int attempt = 0; attempt < 2 * DISCO_MAX_CLS; ++attempt) {
+        u64 m = s_cls[lane];
+        u64 hit = __ballot(m == mask);
+        if (hit) return __ffsll((long long)hit) - 1;
+        m = __hip_atomic_load(&tl->cls_mask[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_cls[lane] = m;
+        hit = __ballot(m == mask);
+        if (hit) return __ffsll((long long)hit) - 1;
+        const u64 free = __ballot(m == 0ull);
+        if (!free) return -1;
+        const int e = __ffsll((long long)free) - 1;
+        unsigned long long old = 0ull;
+        if (lane == 0) old = atomicCAS((unsigned long long*)&tl->cls_mask[e], 0ull, (unsigned long long)mask);
+        old = (unsigned long long)bcast_u64((u64)old, 0);
+        if (old == 0ull || old == (unsigned long long)mask) {
+            if (lane == 0) s_cls[e] = mask;
+            return e;
+        }
+    }
+    return -1;
+}
+
+// Index of `mask` in a workgroup's copy of the class table (lane-private
+// search over `ncls` entries), -1 if absent.
+__device__ __forceinline__ int cls_find(const u64* s_cls, int ncls, u64 mask)
+{
+    int c = -1;
+    for (int k = 0; k < ncls; ++k) c = (s_cls[k] == mask) ? k : c;
+    return c;
+}
+
+// Largest digit width whose `groups` histograms fit `words` bins.
+__device__ __host__ __forceinline__ int fit_width(long groups, long words)
+{
+    int w = 0;
+    while (w < 14 && (groups << (w + 1)) <= words) ++w;
+    return w;
+}
+
+}  // namespace

@@ -1,0 +1,333 @@
+// TBT order statistics over token timelines (Sec. 5.1 metrics on the
+// timelines of Sec. 4.3): classes of timelines, analytic histogram of
+// pure-pacing timelines, digit selection between the histogram passes.
+//
+// A timeline is histogrammed once per class = set of policy columns that use
+// it, not once per column.  For threshold- or wait-ordered tables the sets
+// are nested, so there are at most P + 1 of them per source.  Classes whose
+// members are all short pure-pacing timelines (constant source gap below the
+// pacing interval) need no token walk at all: the gap in front of token t is
+// round(t tau) - round((t-1) tau) for every one of them, so counting the
+// timelines per class and length gives their histogram.
+#include "disco_tl_device.h"
+
+namespace {
+
+// Prepares the next pass: prefix groups of the live slots, digit width that
+// fits, or the per-slot fallback.  One thread.
+__device__ void tbt_plan_next(SelState* S, int P, int nq)
+{
+    TlSel& tl = S->tl;
+    int G = 0;
+    bool over = tl.ncls > DISCO_MAX_CLS || tl.ncls < 1;
+    for (int s = 0; s < P * nq; ++s) {
+        const SelSlot sl = S->slot[1][s];
+        int g = -1;
+        if (!sl.done) {
+            for (int k = 0; k < G && k < DISCO_MAX_GRP; ++k)
+                if (tl.grp_prefix[k] == sl.prefix) g = k;
+            if (g < 0) {
+                if (G < DISCO_MAX_GRP) { tl.grp_prefix[G] = sl.prefix; g = G; }
+                else g = 0;            // too many distinct prefixes: the per-slot fallback does not use groups
+                G += 1;
+            }
+        }
+        tl.slot_grp[s] = g;
+    }
+    if (G > DISCO_MAX_GRP) over = true;
+    if (over) tl.fallback = 1;
+    tl.G = G;
+    int w;
+    if (tl.fallback) {
+        w = fit_width(P * nq, DISCO_TL_HIST_WORDS);
+    } else {
+        const int g1 = G > 0 ? G : 1;
+        w = fit_width((long)g1 * (tl.nwalk > 0 ? tl.nwalk : 1), DISCO_TL_HIST_WORDS);
+        const int wg = fit_width((long)g1 * tl.ncls, DISCO_GHIST_WORDS);
+        if (wg < w) w = wg;
+    }
+    if (w < 1) w = 1;
+    if (w > tl.left) w = tl.left;
+    if (G == 0) w = 0;                 // nothing left to select
+    tl.width = w;
+    tl.shift = tl.left - w;
+}
+
+// Column sets of every request -> classes.  The distinct sets of a workgroup
+// are first collected in LDS and then claimed in the device-wide table by one
+// wave, so the few hot table lines are touched once per workgroup; the last
+// workgroup numbers the classes that need a token walk and plans the first
+// histogram pass.  Also clears the length counts and the device-wide bins.
+__global__ __launch_bounds__(256) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
+                                                     float tau, SelState* S, unsigned* ppcnt, unsigned* ghist,
+                                                     unsigned* ticket)
+{
+    __shared__ disco_policy sp[DISCO_MAX_COLS];
+    __shared__ u64 loc[DISCO_MAX_CLS];
+    __shared__ u64 s_cls[DISCO_MAX_CLS];
+    __shared__ u64 loc_walk;
+    __shared__ int overflow;
+    if ((int)threadIdx.x < P) sp[threadIdx.x] = pol[threadIdx.x];
+    if (threadIdx.x < DISCO_MAX_CLS) { loc[threadIdx.x] = 0ull; s_cls[threadIdx.x] = 0ull; }
+    if (threadIdx.x == 0) { overflow = 0; loc_walk = 0ull; }
+    for (i64 w = (i64)blockIdx.x * 256 + threadIdx.x; w < (i64)DISCO_MAX_CLS * (DISCO_PP_NMAX + 1); w += (i64)gridDim.x * 256)
+        ppcnt[w] = 0u;
+    for (i64 w = (i64)blockIdx.x * 256 + threadIdx.x; w < (i64)DISCO_GHIST_WORDS; w += (i64)gridDim.x * 256) ghist[w] = 0u;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const volatile u64* vloc = loc;
+    u64 seen = 0ull, seen_walk = 0ull;        // lane e: entry e of the workgroup's table as last read; walk flags set by this wave
+    const i64 nround = (tr.n_req + 255) / 256;
+    for (i64 rnd = blockIdx.x; rnd < nround; rnd += gridDim.x) {
+        const i64 i = rnd * 256 + threadIdx.x;
+        u64 m[3] = {0ull, 0ull, 0ull};
+        bool walked[3] = {false, false, false};
+        if (i < tr.n_req) {
+            const int l = tr.l[i], n = tr.n[i];
+            const float s = tr.s[i];
+            const float k = tr.k ? tr.k[i] : tr.k_s;
+            const float gd = tr.g ? tr.g[i] : tr.g_s;
+            const float gap = tr.tbt ? tr.tbt[i] : 0.0f;
+            request_sets(sp, P, l, s, __fmaf_rn((float)l, k, tr.c), m);
+            const bool short_n = n <= DISCO_PP_NMAX;
+            walked[0] = !(short_n && pure_pacing(true, gd, tau));
+            walked[1] = walked[2] = !(short_n && pure_pacing(tr.arr == nullptr, gap, tau));
+        }
+#pragma unroll
+        for (int kind = 0; kind < 3; ++kind) {
+            u64 pend = __ballot(m[kind] != 0ull);
+            while (pend) {
+                const int leader = __ffsll((long long)pend) - 1;
+                const u64 m0 = bcast_u64(m[kind], leader);
+                const u64 same = __ballot(m[kind] == m0);
+                const bool wk = __ballot(m[kind] == m0 && walked[kind]) != 0ull;
+                pend &= ~same;
+                // what this wave already knows to be in the workgroup's table needs no LDS traffic
+                const u64 known = __ballot(seen == m0);
+                if (known) {
+                    const int e0 = __ffsll((long long)known) - 1;
+                    if (!wk || ((seen_walk >> e0) & 1ull)) continue;
+                }
+                int e = -1;
+                for (int attempt = 0; attempt < DISCO_MAX_CLS + 1 && e < 0; ++attempt) {   // insert m0 into the workgroup's table
+                    const u64 cur = vloc[lane];
+                    const u64 hit = __ballot(cur == m0);
+                    if (hit) { e = __ffsll((long long)hit) - 1; seen = cur; break; }
+                    const u64 free = __ballot(cur == 0ull);
+                    if (!free) { if (lane == 0) overflow = 1; break; }
+                    const int f = __ffsll((long long)free) - 1;
+                    if (lane == 0) atomicCAS((unsigned long long*)&loc[f], 0ull, (unsigned long long)m0);
+                }
+                if (e >= 0 && wk) {
+                    if (lane == 0) atomicOr((unsigned long long*)&loc_walk, 1ull << e);
+                    seen_walk |= 1ull << e;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        u64 mine = __ballot(loc[lane] != 0ull);
+        const u64 lw = loc_walk;
+        bool bad = overflow != 0;
+        u64 wbits = 0ull;
+        while (mine) {
+            const int e = __ffsll((long long)mine) - 1;
+            mine &= mine - 1;
+            const int c = cls_lookup(loc[e], s_cls, &S->tl, lane);
+            if (c < 0) bad = true;
+            else if ((lw >> e) & 1ull) wbits |= 1ull << c;
+        }
+        // one atomic per workgroup, and none once the bits are known to be set (every workgroup sees the same few classes)
+        if (lane == 0 && wbits) {
+            const u64 cur = __hip_atomic_load(&S->tl.walk_mask, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((cur & wbits) != wbits) atomicOr((unsigned long long*)&S->tl.walk_mask, (unsigned long long)wbits);
+        }
+        if (bad && lane == 0) S->tl.error = 1;
+    }
+    if (!take_last_ticket(ticket)) return;
+    if (threadIdx.x == 0) {
+        TlSel& tl = S->tl;
+        int n = 0;
+        for (int k = 0; k < DISCO_MAX_CLS; ++k)
+            if (__hip_atomic_load(&tl.cls_mask[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0ull) n = k + 1;
+        tl.ncls = n > 0 ? n : 1;
+        const u64 wm = __hip_atomic_load(&tl.walk_mask, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int nw = 0;
+        for (int k = 0; k < DISCO_MAX_CLS; ++k) {
+            tl.slot_cls[k] = 0;
+            if ((wm >> k) & 1ull) { tl.cls_slot[k] = (signed char)nw; tl.slot_cls[nw] = (unsigned char)k; nw += 1; }
+            else tl.cls_slot[k] = -1;
+        }
+        tl.nwalk = nw;
+        if (__hip_atomic_load(&tl.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { tl.fallback = 1; tl.error = 0; }
+        tl.left = 31;
+        tbt_plan_next(S, P, nq);
+        *ticket = 0u;
+    }
+}
+
+// Per class: counts by length -> number of timelines longer than t (in place).
+__global__ __launch_bounds__(1024) void k_pp_suffix(SelState* S, unsigned* ppcnt)
+{
+    __shared__ unsigned part[1024];
+    if (S->tl.fallback || (int)blockIdx.x >= S->tl.ncls) return;
+    unsigned* row = ppcnt + (size_t)blockIdx.x * (DISCO_PP_NMAX + 1);
+    constexpr int PER = (DISCO_PP_NMAX + 1 + 1023) / 1024;
+    const int t0 = threadIdx.x * PER;
+    unsigned v[PER];
+    unsigned sum = 0;
+    for (int q = 0; q < PER; ++q) { v[q] = (t0 + q <= DISCO_PP_NMAX) ? row[t0 + q] : 0u; sum += v[q]; }
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {            // inclusive suffix sums of the per-thread totals
+        const unsigned o = (threadIdx.x + d < 1024) ? part[threadIdx.x + d] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += o;
+        __syncthreads();
+    }
+    unsigned above = (threadIdx.x + 1 < 1024) ? part[threadIdx.x + 1] : 0u;       // lengths beyond this thread's slice
+    for (int q = PER - 1; q >= 0; --q) {
+        if (t0 + q <= DISCO_PP_NMAX) row[t0 + q] = above;                         // timelines with n > t0 + q
+        above += v[q];
+    }
+}
+
+// After a TBT histogram pass, step 1 (workgroup = class): add the analytic
+// bins of the class's pure-pacing timelines to its device-wide rows.
+// ppcnt[c][t] timelines of class c have a token t, and the gap in front of it
+// is the same number for all of them.
+__global__ __launch_bounds__(1024) void k_tbt_analytic(SelState* S, unsigned* ghist, const unsigned* ppcnt, float tau)
+{
+    __shared__ unsigned lds[DISCO_TL_HIST_WORDS];
+    const TlSel& tl = S->tl;
+    const int width = tl.width, ncls = tl.ncls, c = blockIdx.x;
+    if (width <= 0 || tl.fallback || c >= ncls) return;
+    const unsigned* row = ppcnt + (size_t)c * (DISCO_PP_NMAX + 1);
+    if (row[0] == 0u) return;                             // no pure-pacing timeline in this class (uniform)
+    const int Gused = tl.G < DISCO_MAX_GRP ? tl.G : DISCO_MAX_GRP;
+    const unsigned dmask = (1u << width) - 1u;
+    const int words = Gused << width;
+    const int shift = tl.shift, up = tl.shift + width;
+    for (int i = threadIdx.x; i < words; i += blockDim.x) lds[i] = 0u;
+    __syncthreads();
+    for (int t = 1 + (int)threadIdx.x; t < DISCO_PP_NMAX; t += blockDim.x) {
+        const unsigned cnt = row[t];
+        if (!cnt) continue;
+        const unsigned key = f2u((float)t * tau - (float)(t - 1) * tau);
+        const unsigned hi = key >> up;                     // up <= 31
+        int g = -1;
+        for (int k = 0; k < Gused; ++k) g = (hi == tl.grp_prefix[k] && g < 0) ? k : g;
+        if (g >= 0) atomicAdd(&lds[((unsigned)g << width) | ((key >> shift) & dmask)], cnt);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < words; i += blockDim.x) {
+        const unsigned v = lds[i];
+        if (v) ghist[((size_t)((i >> width) * ncls + c) << width) | (i & dmask)] += v;
+    }
+}
+
+// Step 2 (workgroup = (column, quantile) slot): add up the class histograms
+// of the classes that contain the slot's column (or take the slot's own
+// histogram in the fallback), walk to the digit that holds the remaining
+// rank, extend the prefix.
+__global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const unsigned* ghist)
+{
+    __shared__ u64 wsum[4];
+    __shared__ int s_digit;
+    __shared__ u64 s_rem;
+    const TlSel& tl = S->tl;
+    const int width = tl.width, ncls = tl.ncls, fallback = tl.fallback;
+    const int s = blockIdx.x;
+    if (width <= 0) return;
+    SelSlot sl = S->slot[1][s];
+    const int g = tl.slot_grp[s];
+    if (sl.done || g < 0) return;
+    const int col = s / nq;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nbins = 1 << width;
+    const int per = (nbins + 255) >> 8;                   // consecutive bins per thread (<= 64)
+    const int b0 = threadIdx.x * per;
+    auto bin_count = [&](int b) -> u64 {
+        if (fallback) return ghist[((size_t)s << width) | b];
+        u64 c = 0;
+        for (int k = 0; k < ncls; ++k)
+            if ((tl.cls_mask[k] >> col) & 1ull) c += ghist[((size_t)(g * ncls + k) << width) | b];
+        return c;
+    };
+    u64 mine = 0;
+    for (int b = b0; b < b0 + per && b < nbins; ++b) mine += bin_count(b);
+    u64 incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        unsigned lo = (unsigned)__shfl_up((int)(unsigned)incl, d, 64);
+        unsigned hi = (unsigned)__shfl_up((int)(unsigned)(incl >> 32), d, 64);
+        if (lane >= d) incl += ((u64)hi << 32) | lo;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    if (threadIdx.x == 0) s_digit = -1;
+    __syncthreads();
+    u64 before = 0;
+    for (int w = 0; w < wave; ++w) before += wsum[w];
+    incl += before;
+    const u64 k = (u64)sl.k_rem;
+    // the rank never exceeds the number of matching values: exactly one thread sees it fall into its bins
+    if (incl >= k && incl - mine < k) {
+        u64 rem = k - (incl - mine);
+        int dsel = b0;
+        for (int b = b0; b < b0 + per && b < nbins; ++b) {
+            const u64 c = bin_count(b);
+            dsel = b;
+            if (rem <= c) break;
+            rem -= c;
+        }
+        s_digit = dsel;
+        s_rem = rem;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int dsel = s_digit;
+        u64 rem = s_rem;
+        if (dsel < 0) { dsel = nbins - 1; rem = 1; }      // not reachable for a consistent histogram
+        sl.k_rem = (i64)rem;
+        sl.prefix = (sl.prefix << width) | (unsigned)dsel;
+        S->slot[1][s] = sl;
+    }
+}
+
+// Step 3 (one workgroup): clear the bins that were used and plan the next pass.
+__global__ __launch_bounds__(1024) void k_tbt_plan(SelState* S, int P, int nq, unsigned* ghist)
+{
+    TlSel& tl = S->tl;
+    const int width = tl.width;
+    if (width <= 0) return;
+    const int Gused = tl.G < DISCO_MAX_GRP ? tl.G : DISCO_MAX_GRP;
+    const int words = (tl.fallback ? P * nq : Gused * tl.ncls) << width;
+    for (int i = threadIdx.x; i < words; i += blockDim.x) ghist[i] = 0u;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        tl.left -= width;
+        if (tl.left <= 0) { tl.left = 0; tl.width = 0; tl.G = 0; }
+        else tbt_plan_next(S, P, nq);
+    }
+}
+
+}  // namespace
+
+void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
+                              unsigned* ppcnt, unsigned* ghist, unsigned* ticket, hipStream_t stream)
+{
+    i64 b = (v.n_req + 255) / 256;
+    if (b < 1) b = 1;
+    if (b > 1024) b = 1024;
+    hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(256), 0, stream, v, pol, P, nq, tau, S, ppcnt, ghist, ticket);
+}
+
+void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,
+                              hipStream_t stream)
+{
+    if (pass == 0) hipLaunchKernelGGL(k_pp_suffix, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ppcnt);
+    hipLaunchKernelGGL(k_tbt_analytic, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ghist, ppcnt, tau);
+    hipLaunchKernelGGL(k_tbt_select, dim3((unsigned)(P * nq)), dim3(256), 0, stream, S, nq, ghist);
+    hipLaunchKernelGGL(k_tbt_plan, dim3(1), dim3(1024), 0, stream, S, P, nq, ghist);
+}
