@@ -16,6 +16,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "disco_launch.h"
 #include "disco_state.h"
 
@@ -95,6 +97,29 @@ __device__ __forceinline__ double acc_value(int which, const disco_cost_params& 
     }
 }
 
+// One bisection step of a search: record (parameter, accumulator), halve the
+// bracket, set the parameter of the next evaluation (after the last step: the
+// feasible end of the bracket).
+__device__ __forceinline__ void search_step(SearchState& st, disco_policy& p, double A, disco_search_out* o)
+{
+    const bool is_w = st.which_param == DISCO_PARAM_W_TAIL;
+    const double mid = is_w ? (double)p.w_tail : (double)p.l_th;
+    o->hist_param[st.step] = mid;
+    o->hist_acc[st.step] = A;
+    if (is_w) {
+        if (A > st.target) st.lo = mid; else st.hi = mid;
+    } else if (st.lo < st.hi) {
+        if (A > st.target) st.lo = mid + 1.0; else st.hi = mid;
+    }
+    st.step += 1;
+    if (is_w) {
+        p.w_tail = (st.step < st.n_steps) ? 0.5f * ((float)st.lo + (float)st.hi) : (float)st.hi;
+    } else {
+        const int lo = (int)st.lo, hi = (int)st.hi;
+        p.l_th = (st.step < st.n_steps) ? lo + (hi - lo) / 2 : hi;
+    }
+}
+
 // Bisection step or final evaluation of search `col` (Sec. 4.2: find the
 // threshold / wait that meets the constrained endpoint's budget).
 __device__ void search_advance(int col, const DispFin& fin, const disco_accum& tot)
@@ -102,23 +127,8 @@ __device__ void search_advance(int col, const DispFin& fin, const disco_accum& t
     SearchState st = fin.st[col];
     disco_policy p = fin.pol_rw[col];
     const double A = acc_value(st.which_acc, fin.cost, tot.s_pre, tot.s_dec, tot.d_pre, tot.d_dec);
-    const bool is_w = st.which_param == DISCO_PARAM_W_TAIL;
     if (st.step < st.n_steps) {
-        const double mid = is_w ? (double)p.w_tail : (double)p.l_th;
-        fin.sout[col].hist_param[st.step] = mid;
-        fin.sout[col].hist_acc[st.step] = A;
-        if (is_w) {
-            if (A > st.target) st.lo = mid; else st.hi = mid;
-        } else if (st.lo < st.hi) {
-            if (A > st.target) st.lo = mid + 1.0; else st.hi = mid;
-        }
-        st.step += 1;
-        if (is_w) {
-            p.w_tail = (st.step < st.n_steps) ? 0.5f * ((float)st.lo + (float)st.hi) : (float)st.hi;
-        } else {
-            const int lo = (int)st.lo, hi = (int)st.hi;
-            p.l_th = (st.step < st.n_steps) ? lo + (hi - lo) / 2 : hi;
-        }
+        search_step(st, p, A, &fin.sout[col]);
         fin.st[col] = st;
         fin.pol_rw[col] = p;
     } else {
@@ -493,36 +503,44 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disc
         const int up = shift + width;          // up == 32 only when the prefix is empty
         Staged* st = stage + wave * 64;
         const i64 nbatch = (tr.n_req + 63) >> 6;
-        for (i64 b = (i64)blockIdx.x * DP_WAVES + wave; b < nbatch; b += (i64)gridDim.x * DP_WAVES) {
-            const i64 i = b * 64 + lane;
-            const bool v = i < tr.n_req;
-            const int lv = v ? tr.l[i] : 0;
-            const float sv = v ? tr.s[i] : 0.0f;
-            const float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
-            const float dv = __fmaf_rn((float)lv, kv, tr.c);
-            st[lane] = Staged{lv, sv, 0, dv};
-            const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
-            __builtin_amdgcn_wave_barrier();
+        // the pair evaluation is specialised on the kind of table (all Alg. 3, all Alg. 2, mixed)
+        auto run = [&](auto mode_c) {
+            constexpr int MODE = decltype(mode_c)::value;
+            for (i64 b = (i64)blockIdx.x * DP_WAVES + wave; b < nbatch; b += (i64)gridDim.x * DP_WAVES) {
+                const i64 i = b * 64 + lane;
+                const bool v = i < tr.n_req;
+                const int lv = v ? tr.l[i] : 0;
+                const float sv = v ? tr.s[i] : 0.0f;
+                const float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
+                const float dv = __fmaf_rn((float)lv, kv, tr.c);
+                st[lane] = Staged{lv, sv, 0, dv};
+                const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll 4
-            for (int it = 0; it < G; ++it) {
-                const int src = sub * G + it;
-                const Staged r = st[src];
-                const PairResult e = pair_eval<2>(p, r.l, r.s, r.d);
-                if (src < cnt) {
-                    const unsigned key = f2u(e.ttft) - g.minb;
-                    const unsigned dgt = (key >> shift) & dmask;
-                    const unsigned hi = (up >= 32) ? 0u : (key >> up);
-                    if (pass == 0) {
-                        if (any_live) atomicAdd(&hist[col * stride + dgt], 1u);
-                    } else {
+                for (int it = 0; it < G; ++it) {
+                    const int src = sub * G + it;
+                    const Staged r = st[src];
+                    const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d);
+                    if (src < cnt) {
+                        const unsigned key = f2u(e.ttft) - g.minb;
+                        const unsigned dgt = (key >> shift) & dmask;
+                        const unsigned hi = (up >= 32) ? 0u : (key >> up);
+                        if (pass == 0) {
+                            if (any_live) atomicAdd(&hist[col * stride + dgt], 1u);
+                        } else {
 #pragma unroll
-                        for (int qi = 0; qi < DISCO_MAX_Q; ++qi)
-                            if (live[qi] && hi == prefix[qi]) atomicAdd(&hist[(col * nq + qi) * stride + dgt], 1u);
+                            for (int qi = 0; qi < DISCO_MAX_Q; ++qi)
+                                if (live[qi] && hi == prefix[qi]) atomicAdd(&hist[(col * nq + qi) * stride + dgt], 1u);
+                        }
                     }
                 }
+                __builtin_amdgcn_wave_barrier();
             }
-            __builtin_amdgcn_wave_barrier();
-        }
+        };
+        const int mode = table_mode(p, colv);
+        if (mode == 0) run(std::integral_constant<int, 0>{});
+        else if (mode == 1) run(std::integral_constant<int, 1>{});
+        else run(std::integral_constant<int, 2>{});
         __syncthreads();
         for (int i = threadIdx.x; i < nslot << width; i += DP_BLOCK) {
             const unsigned c = hist[(i >> width) * stride + (i & (int)dmask)];
@@ -532,6 +550,91 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disc
     if (!take_last_ticket(ticket)) return;
     select_advance(S, 0, pass, P, nq, ghist);
     if (threadIdx.x == 0) *ticket = 0u;
+}
+
+// ---------------------------------------------- threshold search, Alg. 3 ----
+//
+// Server-constrained columns (Alg. 3): the server's share of the prompt tokens
+// is A(L) = sum of l_i over requests with l_i >= L, a function of the length
+// threshold alone.  As in Alg. 3 (lengths in order, running totals) the whole
+// function is tabulated once -- requests per prompt length, then suffix sums
+// of count x length -- and every bisection step of every column reads the
+// table instead of passing over the requests.  The steps, their order and the
+// recorded history are those of the generic search.
+
+constexpr int LH_MAX_BINS = 32772;          // 128 KB of LDS counts: prompt lengths 0 .. 32771
+
+// Requests per prompt length, one slice of `nbins` counts per workgroup; the
+// lengths of requests outside [0, nbins) are added up in `other`.
+__global__ __launch_bounds__(DP_BLOCK) void k_len_hist(TraceView tr, int nbins, unsigned* __restrict__ slices, u64* other)
+{
+    __shared__ unsigned cnt[LH_MAX_BINS];
+    for (int i = threadIdx.x; i < nbins; i += DP_BLOCK) cnt[i] = 0u;
+    __syncthreads();
+    u64 out = 0;
+    for (i64 i = (i64)blockIdx.x * DP_BLOCK + threadIdx.x; i < tr.n_req; i += (i64)gridDim.x * DP_BLOCK) {
+        const int l = tr.l[i];
+        if (l >= 0 && l < nbins) atomicAdd(&cnt[l], 1u);
+        else if (l > 0) out += (u64)l;
+    }
+    out = wave_sum_u64(out);
+    if ((threadIdx.x & 63) == 0 && out) atomicAdd((unsigned long long*)other, (unsigned long long)out);
+    __syncthreads();
+    unsigned* mine = slices + (size_t)blockIdx.x * nbins;
+    for (int i = threadIdx.x; i < nbins; i += DP_BLOCK) mine[i] = cnt[i];
+}
+
+// table[v] = v x (requests of length v), summed over the slices.
+__global__ __launch_bounds__(256) void k_len_reduce(int nbins, int nslices, const unsigned* __restrict__ slices, u64* table)
+{
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    if (v >= nbins) return;
+    u64 c = 0;
+    for (int b = 0; b < nslices; ++b) c += slices[(size_t)b * nbins + v];
+    table[v] = c * (u64)v;
+}
+
+// In place: table[L] = sum over v >= L of table[v], plus the lengths beyond
+// the table; table[nbins] = those lengths alone.  One workgroup.
+__global__ __launch_bounds__(1024) void k_len_suffix(int nbins, u64* table, u64* other)
+{
+    __shared__ u64 part[1024];
+    const int per = (nbins + 1023) / 1024;
+    const int t0 = threadIdx.x * per;
+    u64 sum = 0;
+    for (int q = 0; q < per; ++q) if (t0 + q < nbins) sum += table[t0 + q];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {            // inclusive suffix sums of the per-thread totals
+        const u64 o = (threadIdx.x + d < 1024) ? part[threadIdx.x + d] : 0;
+        __syncthreads();
+        part[threadIdx.x] += o;
+        __syncthreads();
+    }
+    const u64 beyond = *other;
+    u64 above = ((threadIdx.x + 1 < 1024) ? part[threadIdx.x + 1] : 0) + beyond;
+    for (int q = per - 1; q >= 0; --q) {
+        if (t0 + q < nbins) { above += table[t0 + q]; table[t0 + q] = above; }
+    }
+    if (threadIdx.x == 0) { table[nbins] = beyond; *other = 0; }
+}
+
+// All bisection steps of every column from the table (thread = column).
+__global__ void k_search_table(int n, int nbins, const u64* __restrict__ table, SearchState* st_, disco_policy* pol,
+                               disco_search_out* sout)
+{
+    const int c = threadIdx.x;
+    if (c >= n) return;
+    SearchState st = st_[c];
+    disco_policy p = pol[c];
+    while (st.step < st.n_steps) {
+        const int L = p.l_th;
+        const u64 s_pre = L <= 0 ? table[0] : (L < nbins ? table[L] : table[nbins]);
+        const double A = st.which_acc == DISCO_ACC_SERVER_PREFILL_TOK ? (double)(i64)s_pre : (double)(i64)table[0];
+        search_step(st, p, A, &sout[c]);
+    }
+    st_[c] = st;
+    pol[c] = p;
 }
 
 unsigned dispatch_blocks(i64 units, i64 per_block)
@@ -611,3 +714,22 @@ void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int 
     if (b < 1) b = 1;
     hipLaunchKernelGGL(k_dispatch_mat, dim3((unsigned)b), dim3(256), 0, stream, v, pol, P, decision, ttft);
 }
+
+// Tabulated threshold search (see k_len_hist).  `scratch` holds the workgroup slices, `table` nbins + 1 sums.
+void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsigned* scratch, size_t scratch_bytes,
+                               u64* table, u64* other, SearchState* st, disco_policy* pol, disco_search_out* sout,
+                               hipStream_t stream)
+{
+    i64 blocks = (v.n_req + DP_BLOCK - 1) / DP_BLOCK;
+    const i64 fit = (i64)(scratch_bytes / ((size_t)nbins * sizeof(unsigned)));
+    if (blocks > fit) blocks = fit;
+    if (blocks > DP_MAX_BLOCKS) blocks = DP_MAX_BLOCKS;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_len_hist, dim3((unsigned)blocks), dim3(DP_BLOCK), 0, stream, v, nbins, scratch, other);
+    hipLaunchKernelGGL(k_len_reduce, dim3((unsigned)((nbins + 255) / 256)), dim3(256), 0, stream, nbins, (int)blocks, scratch,
+                       table);
+    hipLaunchKernelGGL(k_len_suffix, dim3(1), dim3(1024), 0, stream, nbins, table, other);
+    hipLaunchKernelGGL(k_search_table, dim3(1), dim3(64), 0, stream, n_search, nbins, table, st, pol, sout);
+}
+
+int disco_search_table_max_bins(void) { return LH_MAX_BINS; }

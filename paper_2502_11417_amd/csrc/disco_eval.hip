@@ -481,11 +481,31 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
     fin.sout = out;
     fin.pol_out = pol_out;
     fin.pol_rw = (disco_policy*)(ws + L.pol);
+    // Length thresholds of server-constrained columns against a prompt-token budget: the accumulator is a
+    // function of the threshold alone and is tabulated once (Alg. 3's sorted running totals); all bisection
+    // steps then read the table.  Needs a host-resident template table (its modes are inspected here).
+    bool tabulated = v.n_req > 0 && !is_device_pointer(templ);
+    double max_hi = 0.0;
+    for (int j = 0; j < n_search && tabulated; ++j) {
+        tabulated = templ[j].mode == DISCO_MODE_SERVER_CONSTRAINED && spec[j].which_param == DISCO_PARAM_L_TH &&
+                    (spec[j].which_acc == DISCO_ACC_SERVER_PREFILL_TOK || spec[j].which_acc == DISCO_ACC_DEVICE_PREFILL_TOK) &&
+                    spec[j].lo >= 0.0 && spec[j].hi + 2.0 <= (double)disco_search_table_max_bins();
+        if (spec[j].hi > max_hi) max_hi = spec[j].hi;
+    }
+    int first_step = 0;
+    if (tabulated) {
+        const size_t totals_bytes = (size_t)2 * DISCO_NCOPY * 64 * 64;          // the totals at the head of the region stay
+        disco_launch_search_table(v, n_search, (int)max_hi + 2, (unsigned*)(ws + L.part + totals_bytes),
+                                  (size_t)DISCO_MAX_BLOCKS * 64 * 64 - totals_bytes, (u64*)(ws + L.ppcnt),
+                                  (u64*)((unsigned*)(ws + L.ticket) + 32), (SearchState*)(ws + L.search),
+                                  (disco_policy*)(ws + L.pol), out, stream);
+        first_step = n_steps;
+    }
     // bisection steps only need the totals their accumulators are made of; the last pass evaluates everything
     int need = 0;
     for (int j = 0; j < n_search; ++j)
         if (spec[j].which_acc != DISCO_ACC_SERVER_PREFILL_TOK && spec[j].which_acc != DISCO_ACC_DEVICE_PREFILL_TOK) need = 1;
-    for (int step = 0; step <= n_steps; ++step) {
+    for (int step = first_step; step <= n_steps; ++step) {
         fin.need = step < n_steps ? need : 2;
         disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search, (DispPartial*)(ws + L.part),
                                   (unsigned*)(ws + L.ticket), fin, stream);

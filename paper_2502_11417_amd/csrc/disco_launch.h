@@ -25,6 +25,11 @@ struct DispFin {
 
 void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, DispPartial* part, unsigned* ticket,
                                const DispFin& fin, hipStream_t stream);
+// Threshold search of server-constrained columns from a table of prompt-token sums by length.
+void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsigned* scratch, size_t scratch_bytes,
+                               u64* table, u64* other, SearchState* st, disco_policy* pol, disco_search_out* sout,
+                               hipStream_t stream);
+int disco_search_table_max_bins(void);
 void disco_launch_ttft_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S,
                             unsigned* gh, unsigned* ticket, hipStream_t stream);
 void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,

@@ -364,3 +364,85 @@ def test_stats_timelines_many_column_sets(B, oracle):
     tr2 = DI.handmade_trace(92, 400, tokens=True, max_out=300, stall_p=0.03)
     tr2["dev_dec_spt"] = (tr2["dev_dec_spt"] * np.float32(2.5)).astype(np.float32)
     check_stats(B, oracle, tr2, mixed_policies(lag=True), DI.COST_S, tau=DI.TAU, kappa=DI.KAPPA_LAG)
+
+
+@pytest.mark.parametrize("hi_extra,which", [(1, "server_prefill_tok"), (60_000, "server_prefill_tok"),
+                                            (1, "device_prefill_tok"), (1, "total_cost")])
+def test_threshold_search_paths(B, oracle, hi_extra, which):
+    """Length-threshold searches through the tabulated path (brackets inside the length table, prompt-token
+    accumulators) and through the generic passes (bracket beyond the table, cost accumulator): same history."""
+    print(f"search parity thresholds hi_extra={hi_extra} acc={which}", flush=True)
+    tr = DI.handmade_trace(123, 6_001, tokens=False)
+    dt = B.upload_trace(tr)
+    total = int(tr["prompt_len"].astype(np.int64).sum())
+    lmax = int(tr["prompt_len"].max())
+    hi = lmax + hi_extra
+    steps = max(1, hi.bit_length())
+    fracs = [0.0, 0.13, 0.5, 0.77, 1.0]
+    if which == "total_cost":
+        c_all = DI.COST_S["cs_pre"] * (total + int(tr["output_len"].astype(np.int64).sum()))
+        targets = [f * c_all for f in fracs]
+    else:
+        targets = [f * total for f in fracs]
+    specs = [dict(which_param=B.PARAM_L_TH, which_acc=which, n_steps=steps, lo=0, hi=hi, target=t) for t in targets]
+    res = B.disco_budget_search(dt, DI.COST_S, [B.Policy(mode=0) for _ in targets], specs)
+    so = B.search_to_host(res["out"], len(targets))
+    pol = B.policies_to_host(res["pol_out"], len(targets))
+    for j, t in enumerate(targets):
+        l_th, hp, ha = oracle.search_lth(tr, oracle.Policy(mode=0), 0, hi, steps, which, DI.COST_S, t)
+        assert pol[j].l_th == l_th == int(so["param"][j]), (j, pol[j].l_th, l_th)
+        assert (so["hist_param"][j][:steps] == hp).all(), j
+        if which == "total_cost":
+            assert np.allclose(so["hist_acc"][j][:steps], ha, rtol=1e-12, atol=0), j
+        else:
+            assert (so["hist_acc"][j][:steps] == ha).all(), j
+        d = oracle.dispatch(tr, [oracle.Policy(mode=0, l_th=l_th)], materialise=False)
+        at = so["at_param"][j]
+        for f in ("s_pre", "s_dec", "d_pre", "d_dec", "n_dev_win"):
+            assert int(at[f]) == int(d[f][0]), (f, j)
+
+
+def test_threshold_search_device_constrained_template(B, oracle):
+    """A length threshold searched on a device-constrained template (Eq. 1: no wait up to l_th) takes the generic passes."""
+    print("search parity threshold on a wait-time template", flush=True)
+    tr = DI.handmade_trace(124, 3_000, tokens=False)
+    dt = B.upload_trace(tr)
+    total = int(tr["prompt_len"].astype(np.int64).sum())
+    lmax = int(tr["prompt_len"].max())
+    steps = (lmax + 1).bit_length()
+    templ = dict(mode=1, w_tail=DI.f32(0.4))
+    res = B.disco_budget_search(dt, DI.COST_D, [B.Policy(**templ)],
+                                [dict(which_param=B.PARAM_L_TH, which_acc="device_prefill_tok", n_steps=steps, lo=0,
+                                      hi=lmax + 1, target=0.6 * total)])
+    so = B.search_to_host(res["out"], 1)
+    l_th, hp, ha = oracle.search_lth(tr, oracle.Policy(**templ), 0, lmax + 1, steps, "device_prefill_tok", DI.COST_D,
+                                     0.6 * total)
+    assert int(so["param"][0]) == l_th
+    assert (so["hist_param"][0][:steps] == hp).all() and (so["hist_acc"][0][:steps] == ha).all()
+
+
+@pytest.mark.parametrize("kappa,tau", [(3.0, 0.2), (0.0, 0.2), (1e-4, 0.2), (3.0, 0.05), (8.0, 0.02), (40.0, 0.01)])
+def test_migration_late_handoffs(B, oracle, kappa, tau):
+    """A server whose gaps hover around the pacing interval keeps the buffer near empty, so stalls trigger the
+    hand-off deep inside long requests (chunks after the first), also for degenerate trigger thresholds."""
+    print(f"migration parity late hand-offs kappa={kappa} tau={tau}", flush=True)
+    rng = np.random.default_rng(17)
+    tr = DI.handmade_trace(200, 700, tokens=True, max_out=1500, stall_p=0.0)
+    n = tr["output_len"]
+    off = tr["tok_off"]
+    gaps = rng.lognormal(math.log(tau) + 0.05, 0.5, int(off[-1])).astype(np.float32)
+    stall = rng.random(gaps.size) < 0.002
+    gaps[stall] = rng.uniform(2.0 * tau, 12.0 * tau, int(stall.sum())).astype(np.float32)
+    arr = np.empty(int(off[-1]), np.float32)
+    for i in range(len(n)):
+        a, b = int(off[i]), int(off[i + 1])
+        arr[a] = 0
+        arr[a + 1:b] = np.cumsum(gaps[a + 1:b], dtype=np.float32)
+    tr = dict(tr, tok_arr=arr)
+    specs = [dict(mode=1, l_th=-1, w_tail=math.inf, mig_mode=1), dict(mode=0, l_th=0, mig_mode=1),
+             dict(mode=1, l_th=-1, w_tail=math.inf, mig_mode=0)]
+    _, acc, want = check_migration(B, oracle, tr, specs, tau, kappa, delivered_col=0)
+    m = want["mig_idx"][0]
+    if kappa >= 1.0 and tau >= 0.05:
+        assert (m >= 256).sum() > 10 and (m >= 512).sum() > 3, ((m >= 256).sum(), (m >= 512).sum())
+    check_stats(B, oracle, tr, specs, DI.COST_S, tau=tau, kappa=kappa)
