@@ -19,57 +19,11 @@
 #include <type_traits>
 
 #include "disco_launch.h"
+#include "disco_pair.h"
 #include "disco_state.h"
 
 namespace {
 
-constexpr int DP_BLOCK = 1024;
-constexpr int DP_WAVES = DP_BLOCK / 64;
-constexpr int DP_MAX_BLOCKS = 256;          // one workgroup per CU: the ticket chain stays short
-
-// ------------------------------------------------------------ per pair ----
-
-struct PairResult { bool srv_started, dev_started, dev_win; float ttft; };
-
-// MODE 0: every column is server-constrained (Alg. 3), 1: every column is
-// device-constrained (Alg. 2 / Eq. 1), 2: mixed table.
-template <int MODE>
-__device__ __forceinline__ PairResult pair_eval(const disco_policy& p, int l, float s, float d)
-{
-    PairResult r;
-    if (MODE == 0) {
-        const bool dev_only = l < p.l_th;               // strict: Alg. 3
-        r.srv_started = !dev_only;
-        r.dev_started = true;
-        r.dev_win = dev_only || (d < s);                // ties go to the server
-        r.ttft = r.dev_win ? d : s;
-    } else if (MODE == 1) {
-        float ramp = p.beta * (float)l;
-        float w = (ramp < p.w_tail) ? ramp : p.w_tail;  // a NaN ramp falls through to w_tail
-        w = (l == p.l_mid) ? p.w_mid : w;
-        w = (l <= p.l_th) ? 0.0f : w;
-        const float x = w + d;
-        r.srv_started = true;
-        r.dev_started = s > w;                          // a server token at exactly w cancels the device
-        r.dev_win = r.dev_started && (x < s);
-        r.ttft = r.dev_win ? x : s;
-    } else {
-        unsigned dec; float t;
-        dispatch_pair(p, l, s, d, dec, t);
-        r.srv_started = (dec & 1u) != 0u;
-        r.dev_started = (dec & 2u) != 0u;
-        r.dev_win = (dec & 4u) != 0u;
-        r.ttft = t;
-    }
-    return r;
-}
-
-__device__ __forceinline__ int table_mode(const disco_policy& p, bool colv)
-{
-    const bool any_d = __ballot(colv && p.mode != DISCO_MODE_SERVER_CONSTRAINED) != 0ull;
-    const bool any_s = __ballot(colv && p.mode == DISCO_MODE_SERVER_CONSTRAINED) != 0ull;
-    return any_d ? (any_s ? 2 : 1) : 0;
-}
 
 struct ColTotals {
     u64 s_pre, d_pre, d_dec, started, won;
@@ -215,7 +169,6 @@ __device__ __forceinline__ void finish_columns(DispPartial* totals, int P, const
 
 // ------------------------------------------------- fused dispatch + reduce --
 
-struct Staged { int l; float s; int n; float d; };      // 16 bytes, one per request of the batch
 
 // Inner loop over the G requests of this lane's sub-group.
 // NEED 0: prefill token totals only; 1: + decode split and winner counts;
@@ -461,97 +414,6 @@ __global__ __launch_bounds__(256) void k_dispatch_mat(TraceView tr, const disco_
     }
 }
 
-// ------------------------------------------------------ TTFT histograms ----
-
-constexpr int TH_WORDS = DISCO_MAX_SLOTS * 256;         // 128 KB of LDS bins
-constexpr int TH_PAD = 1;                               // skew: equal digits of different slots hit different banks
-
-// Same traversal as k_dispatch_acc; every pair whose key matches the prefix of
-// a (column, quantile) slot bumps that slot's bin in an LDS histogram; the
-// workgroup's bins are merged with global atomics and the last workgroup
-// advances the selection.
-template <int G>
-__global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
-                                                        int pass, SelState* S, unsigned* ghist, unsigned* ticket)
-{
-    __shared__ unsigned hist[TH_WORDS + DISCO_MAX_SLOTS * TH_PAD];
-    __shared__ __align__(16) Staged stage[DP_BLOCK];
-    const SelGlobal g = S->g[0];
-    const int width = pass < g.plan.npass ? g.plan.width[pass] : 0;
-    const int shift = pass < g.plan.npass ? g.plan.shift[pass] : 0;
-    const int nslot = (pass == 0) ? P : P * nq;
-    const int stride = (1 << width) + TH_PAD;
-    if (width > 0) {
-        for (int i = threadIdx.x; i < nslot * stride; i += DP_BLOCK) hist[i] = 0u;
-        __syncthreads();
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        const int col = lane & (G - 1), sub = lane / G;
-        const bool colv = col < P;
-        const disco_policy p = pol[colv ? col : 0];
-        unsigned prefix[DISCO_MAX_Q];
-        bool live[DISCO_MAX_Q];
-        bool any_live = false;
-#pragma unroll
-        for (int qi = 0; qi < DISCO_MAX_Q; ++qi) {
-            const bool on = colv && qi < nq;
-            const SelSlot sl = S->slot[0][on ? col * nq + qi : 0];
-            prefix[qi] = sl.prefix;
-            live[qi] = on && !sl.done;
-            any_live = any_live || live[qi];
-        }
-        const unsigned dmask = (1u << width) - 1u;
-        const int up = shift + width;          // up == 32 only when the prefix is empty
-        Staged* st = stage + wave * 64;
-        const i64 nbatch = (tr.n_req + 63) >> 6;
-        // the pair evaluation is specialised on the kind of table (all Alg. 3, all Alg. 2, mixed)
-        auto run = [&](auto mode_c) {
-            constexpr int MODE = decltype(mode_c)::value;
-            for (i64 b = (i64)blockIdx.x * DP_WAVES + wave; b < nbatch; b += (i64)gridDim.x * DP_WAVES) {
-                const i64 i = b * 64 + lane;
-                const bool v = i < tr.n_req;
-                const int lv = v ? tr.l[i] : 0;
-                const float sv = v ? tr.s[i] : 0.0f;
-                const float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
-                const float dv = __fmaf_rn((float)lv, kv, tr.c);
-                st[lane] = Staged{lv, sv, 0, dv};
-                const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll 4
-                for (int it = 0; it < G; ++it) {
-                    const int src = sub * G + it;
-                    const Staged r = st[src];
-                    const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d);
-                    if (src < cnt) {
-                        const unsigned key = f2u(e.ttft) - g.minb;
-                        const unsigned dgt = (key >> shift) & dmask;
-                        const unsigned hi = (up >= 32) ? 0u : (key >> up);
-                        if (pass == 0) {
-                            if (any_live) atomicAdd(&hist[col * stride + dgt], 1u);
-                        } else {
-#pragma unroll
-                            for (int qi = 0; qi < DISCO_MAX_Q; ++qi)
-                                if (live[qi] && hi == prefix[qi]) atomicAdd(&hist[(col * nq + qi) * stride + dgt], 1u);
-                        }
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
-            }
-        };
-        const int mode = table_mode(p, colv);
-        if (mode == 0) run(std::integral_constant<int, 0>{});
-        else if (mode == 1) run(std::integral_constant<int, 1>{});
-        else run(std::integral_constant<int, 2>{});
-        __syncthreads();
-        for (int i = threadIdx.x; i < nslot << width; i += DP_BLOCK) {
-            const unsigned c = hist[(i >> width) * stride + (i & (int)dmask)];
-            if (c) atomicAdd(&ghist[i], c);
-        }
-    }
-    if (!take_last_ticket(ticket)) return;
-    select_advance(S, 0, pass, P, nq, ghist);
-    if (threadIdx.x == 0) *ticket = 0u;
-}
-
 // ---------------------------------------------- threshold search, Alg. 3 ----
 //
 // Server-constrained columns (Alg. 3): the server's share of the prompt tokens
@@ -584,14 +446,22 @@ __global__ __launch_bounds__(DP_BLOCK) void k_len_hist(TraceView tr, int nbins, 
     for (int i = threadIdx.x; i < nbins; i += DP_BLOCK) mine[i] = cnt[i];
 }
 
-// table[v] = v x (requests of length v), summed over the slices.
+// table[v] = v x (requests of length v), summed over the slices: 64 lengths
+// per workgroup, each wave takes every fourth slice.
 __global__ __launch_bounds__(256) void k_len_reduce(int nbins, int nslices, const unsigned* __restrict__ slices, u64* table)
 {
-    const int v = blockIdx.x * 256 + threadIdx.x;
-    if (v >= nbins) return;
-    u64 c = 0;
-    for (int b = 0; b < nslices; ++b) c += slices[(size_t)b * nbins + v];
-    table[v] = c * (u64)v;
+    __shared__ u64 part[256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int v = blockIdx.x * 64 + lane;
+    u64 a0 = 0, a1 = 0;
+    if (v < nbins) {
+        int b = wave;
+        for (; b + 4 < nslices; b += 8) { a0 += slices[(size_t)b * nbins + v]; a1 += slices[(size_t)(b + 4) * nbins + v]; }
+        for (; b < nslices; b += 4) a0 += slices[(size_t)b * nbins + v];
+    }
+    part[threadIdx.x] = a0 + a1;
+    __syncthreads();
+    if (wave == 0 && v < nbins) table[v] = (part[lane] + part[64 + lane] + part[128 + lane] + part[192 + lane]) * (u64)v;
 }
 
 // In place: table[L] = sum over v >= L of table[v], plus the lengths beyond
@@ -655,14 +525,6 @@ void launch_acc(const TraceView& v, const disco_policy* pol, int P, DispPartial*
     hipLaunchKernelGGL(k_dispatch_acc<G>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, P, part, ticket, fin);
 }
 
-template <int G>
-void launch_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S, unsigned* gh,
-                 unsigned* ticket, hipStream_t stream)
-{
-    const unsigned blocks = dispatch_blocks((v.n_req + 63) / 64, DP_WAVES);
-    hipLaunchKernelGGL(k_ttft_hist<G>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, P, nq, pass, S, gh, ticket);
-}
-
 int pow2_cols(int P)
 {
     int g = 1;
@@ -692,20 +554,6 @@ void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int 
     }
 }
 
-void disco_launch_ttft_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S, unsigned* gh,
-                            unsigned* ticket, hipStream_t stream)
-{
-    switch (pow2_cols(P)) {
-    case 1: launch_hist<1>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
-    case 2: launch_hist<2>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
-    case 4: launch_hist<4>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
-    case 8: launch_hist<8>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
-    case 16: launch_hist<16>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
-    case 32: launch_hist<32>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
-    default: launch_hist<64>(v, pol, P, nq, pass, S, gh, ticket, stream); break;
-    }
-}
-
 void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,
                                hipStream_t stream)
 {
@@ -726,7 +574,7 @@ void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsi
     if (blocks > DP_MAX_BLOCKS) blocks = DP_MAX_BLOCKS;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(k_len_hist, dim3((unsigned)blocks), dim3(DP_BLOCK), 0, stream, v, nbins, scratch, other);
-    hipLaunchKernelGGL(k_len_reduce, dim3((unsigned)((nbins + 255) / 256)), dim3(256), 0, stream, nbins, (int)blocks, scratch,
+    hipLaunchKernelGGL(k_len_reduce, dim3((unsigned)((nbins + 63) / 64)), dim3(256), 0, stream, nbins, (int)blocks, scratch,
                        table);
     hipLaunchKernelGGL(k_len_suffix, dim3(1), dim3(1024), 0, stream, nbins, table, other);
     hipLaunchKernelGGL(k_search_table, dim3(1), dim3(64), 0, stream, n_search, nbins, table, st, pol, sout);

@@ -60,12 +60,33 @@ __global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* ds
 // One thread per slot: rank from (num, den, M), empty prefix; plan of the passes.
 __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quantile q0, disco_quantile q1,
                               disco_quantile q2, disco_quantile q3, const disco_accum* acc, i64 n_req,
-                              unsigned* ghist)
+                              const disco_policy* pol)
 {
     const disco_quantile qs[4] = {q0, q1, q2, q3};
     __shared__ unsigned smin, smax;
-    if (threadIdx.x == 0) { smin = 0xFFFFFFFFu; smax = 0u; }
+    __shared__ int all_thresholds;
+    if (threadIdx.x == 0) { smin = 0xFFFFFFFFu; smax = 0u; all_thresholds = 1; }
     __syncthreads();
+    if (which == 0) {
+        // a table of length-threshold columns (Alg. 3) is selected by classes: thresholds in ascending order
+        const int t = threadIdx.x;
+        __shared__ int lth_s[DISCO_MAX_COLS];
+        if (t < P) {
+            if (pol[t].mode != DISCO_MODE_SERVER_CONSTRAINED) all_thresholds = 0;
+            lth_s[t] = pol[t].l_th;
+        }
+        __syncthreads();
+        if (t < P) {
+            const int lth = lth_s[t];
+            int rank = 0;
+            for (int k = 0; k < P; ++k) rank += (lth_s[k] < lth || (lth_s[k] == lth && k < t)) ? 1 : 0;
+            S->tc.sorted_lth[rank] = lth;
+            S->tc.col_of_pos[rank] = (unsigned char)t;
+            S->tc.pos_of_col[t] = (unsigned char)rank;
+        }
+        __syncthreads();
+        if (t == 0) S->tc.on = all_thresholds;
+    }
     if (which == 0 && (int)threadIdx.x < P) {
         atomicMin(&smin, acc[threadIdx.x].ttft_min_bits);
         atomicMax(&smax, acc[threadIdx.x].ttft_max_bits);
@@ -112,8 +133,6 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
         sl.rank = k; sl.k_rem = k; sl.prefix = 0u; sl.done = (M <= 0);
         S->slot[which][s] = sl;
     }
-    if (which == 0)
-        for (int i = threadIdx.x; i < DISCO_MAX_SLOTS * 256; i += blockDim.x) ghist[i] = 0u;     // TBT: cleared by the classification
 }
 
 // ------------------------------------------------------------ final stats --
@@ -277,6 +296,7 @@ WsLayout disco_ws_layout(int32_t P)
     (void)P;
     o += up((size_t)DISCO_MAX_BLOCKS * 64 * 64);     // workgroups x columns x 64-byte partial
     L.ppcnt = o; o += up(sizeof(unsigned) * DISCO_MAX_CLS * (DISCO_PP_NMAX + 1));
+    L.slices = o; o += up((size_t)256 * DISCO_MAX_SLOTS * 256 * sizeof(unsigned));
     L.total = o;
     return L;
 }
@@ -406,13 +426,13 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     for (int i = 0; i < nq; ++i) qs[i] = q[i];
     if (nq > 0) {
         hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 0, P, nq, qs[0], qs[1], qs[2], qs[3], acc,
-                           v.n_req, gh);
+                           v.n_req, (const disco_policy*)(ws + L.pol));
         for (int pass = 0; pass < 4; ++pass)
-            disco_launch_ttft_hist(v, (const disco_policy*)(ws + L.pol), P, nq, pass, S, gh, (unsigned*)(ws + L.ticket),
+            disco_launch_ttft_pass(v, (const disco_policy*)(ws + L.pol), P, nq, pass, S, (unsigned*)(ws + L.slices), gh,
                                    stream);
         if (tl) {
             hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 1, P, nq, qs[0], qs[1], qs[2], qs[3],
-                               acc, v.n_req, gh);
+                               acc, v.n_req, (const disco_policy*)(ws + L.pol));
             TimelineArgs a;
             memset(&a, 0, sizeof(a));
             a.tau = tl->tau;
@@ -494,11 +514,9 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
     }
     int first_step = 0;
     if (tabulated) {
-        const size_t totals_bytes = (size_t)2 * DISCO_NCOPY * 64 * 64;          // the totals at the head of the region stay
-        disco_launch_search_table(v, n_search, (int)max_hi + 2, (unsigned*)(ws + L.part + totals_bytes),
-                                  (size_t)DISCO_MAX_BLOCKS * 64 * 64 - totals_bytes, (u64*)(ws + L.ppcnt),
-                                  (u64*)((unsigned*)(ws + L.ticket) + 32), (SearchState*)(ws + L.search),
-                                  (disco_policy*)(ws + L.pol), out, stream);
+        disco_launch_search_table(v, n_search, (int)max_hi + 2, (unsigned*)(ws + L.slices), L.total - L.slices,
+                                  (u64*)(ws + L.ppcnt), (u64*)((unsigned*)(ws + L.ticket) + 32),
+                                  (SearchState*)(ws + L.search), (disco_policy*)(ws + L.pol), out, stream);
         first_step = n_steps;
     }
     // bisection steps only need the totals their accumulators are made of; the last pass evaluates everything

@@ -30,8 +30,10 @@ void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsi
                                u64* table, u64* other, SearchState* st, disco_policy* pol, disco_search_out* sout,
                                hipStream_t stream);
 int disco_search_table_max_bins(void);
-void disco_launch_ttft_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S,
-                            unsigned* gh, unsigned* ticket, hipStream_t stream);
+// One TTFT radix pass: histograms per workgroup slice (class kernel or pair kernel, decided on the device),
+// row sums, digit selection.
+void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S,
+                            unsigned* slices, unsigned* rowsum, hipStream_t stream);
 void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,
                                hipStream_t stream);
 // Token timelines.  Statistics pass (a.pass = -1): streaming kernel, or the general kernel when the

@@ -42,7 +42,15 @@ struct TlSel {
     signed char cls_slot[DISCO_MAX_CLS];     // row of a walked class in the workgroups' LDS histogram, -1 otherwise
     unsigned char slot_cls[DISCO_MAX_CLS];   // class of an LDS row
 };
-struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; TlSel tl; };   // [0] TTFT, [1] TBT
+// TTFT selection by classes: set when every column is a length-threshold column (Alg. 3).
+struct TtftCls {
+    int on;
+    int sorted_lth[DISCO_MAX_COLS];              // thresholds in ascending order
+    unsigned char pos_of_col[DISCO_MAX_COLS];    // position of a column in that order
+    unsigned char col_of_pos[DISCO_MAX_COLS];
+    int pad[3];
+};
+struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; TlSel tl; TtftCls tc; };   // [0] TTFT, [1] TBT
 
 // Device-wide totals are kept in DISCO_NCOPY copies (workgroup b adds into copy b % DISCO_NCOPY) so that
 // the atomics of different workgroups do not all queue up on one cache line.
@@ -87,56 +95,4 @@ __device__ __forceinline__ bool take_last_ticket(unsigned* ticket)
     bool last = is_last != 0;
     if (last) __threadfence();
     return last;
-}
-
-// After histogram pass `pass`: for every slot find the digit that holds the
-// remaining rank, extend the prefix, clear the global bins.  One wave per
-// slot; called by every thread of the last workgroup.  In pass 0 all the
-// quantiles of a column share that column's histogram.
-__device__ __forceinline__ void select_advance(SelState* S, int which, int pass, int P, int nq, unsigned* ghist)
-{
-    const SelPlan plan = S->g[which].plan;
-    const int width = pass < plan.npass ? plan.width[pass] : 0;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    __syncthreads();
-    if (width > 0) {
-        const int nbins = 1 << width;
-        const int per = (nbins + 63) >> 6;
-        for (int s = wave; s < P * nq; s += nwaves) {
-            SelSlot sl = S->slot[which][s];
-            if (sl.done) continue;
-            const unsigned* h = ghist + ((size_t)((pass == 0) ? (s / nq) : s) << width);
-            const int b0 = lane * per;
-            u64 mine = 0;
-            for (int b = b0; b < b0 + per && b < nbins; ++b) mine += h[b];
-            u64 incl = mine;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                unsigned lo = (unsigned)__shfl_up((int)(unsigned)incl, d, 64);
-                unsigned hi = (unsigned)__shfl_up((int)(unsigned)(incl >> 32), d, 64);
-                if (lane >= d) incl += ((u64)hi << 32) | lo;
-            }
-            const u64 k = (u64)sl.k_rem;
-            const u64 hit = __ballot(incl >= k);
-            // the rank never exceeds the number of matching values, so a lane always hits
-            const int owner = hit ? (__ffsll((long long)hit) - 1) : 63;
-            if (lane == owner) {
-                u64 rem = k - (incl - mine);
-                int dsel = nbins - 1;
-                for (int b = b0; b < b0 + per && b < nbins; ++b) {
-                    u64 c = h[b];
-                    if (rem <= c) { dsel = b; break; }
-                    rem -= c;
-                }
-                sl.k_rem = (i64)rem;
-                sl.prefix = (sl.prefix << width) | (unsigned)dsel;
-                S->slot[which][s] = sl;
-            }
-        }
-    }
-    __syncthreads();
-    if (width > 0) {
-        const int words = ((pass == 0) ? P : P * nq) << width;
-        for (int i = threadIdx.x; i < words; i += blockDim.x) ghist[i] = 0u;
-    }
 }

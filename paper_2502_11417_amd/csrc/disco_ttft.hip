@@ -1,0 +1,381 @@
+// TTFT order statistics (Sec. 5.1 metrics: median and tail TTFT per budget
+// level): most-significant-digit-first radix selection over
+// key = bits(TTFT) - min_bits, 8 bits per pass.
+//
+// Two histogram kernels; which one acts is decided on the device.
+//
+//   class kernel -- every column is a length-threshold column (Alg. 3).  With
+//     the thresholds in ascending order t_0 <= ... <= t_{P-1} a request of
+//     prompt length l runs device-only in the columns p >= ub and races in the
+//     columns p < ub, ub = #{p : t_p <= l}; its TTFT is d in the former and
+//     min(s, d) in the latter (the winner of a race does not depend on the
+//     column).  So a request has at most two distinct TTFT values over the
+//     whole table, each valid for a contiguous range of sorted columns:
+//     lane = request, two histogram updates per request instead of one per
+//     (request, column) pair.
+//       pass 0: rows (device, ub) and (race, ub); column p's histogram is the
+//         sum of the device rows ub <= p and the race rows ub > p.
+//       later passes: one row per (column, quantile) slot; a value goes to the
+//         slots of its column range whose prefix equals the value's upper bits
+//         (looked up in the sorted list of distinct prefixes).
+//   pair kernel -- any table: lane = column, every (request, column) pair is
+//     evaluated and bumps the rows of its column.
+//
+// A workgroup stores its LDS bins as one slice; k_ttft_reduce adds the slices
+// (merging them with device-wide atomics would serialise on the few hundred
+// cache lines of the bins) and k_ttft_select extends every slot's prefix.
+#include <math.h>
+#include <string.h>
+
+#include <type_traits>
+
+#include "disco_launch.h"
+#include "disco_pair.h"
+#include "disco_state.h"
+
+namespace {
+
+constexpr int TH_ROWS = 2 * DISCO_MAX_COLS + 2;         // class pass 0: (device, ub) 0..P and (race, ub) 0..P
+constexpr int TH_PAD = 1;                               // skew: equal digits of different rows hit different banks
+constexpr int TH_STRIDE = 256 + TH_PAD;
+constexpr int TH_WORDS = TH_ROWS * TH_STRIDE;           // 131 KB of LDS bins
+constexpr int TC_MAX_BLOCKS = 128;                      // class kernel: little arithmetic, fewer slices to add up
+
+struct PassDigit { int width, shift, up; unsigned dmask; };
+
+__device__ __forceinline__ PassDigit pass_digit(const SelGlobal& g, int pass)
+{
+    PassDigit d;
+    d.width = pass < g.plan.npass ? g.plan.width[pass] : 0;
+    d.shift = pass < g.plan.npass ? g.plan.shift[pass] : 0;
+    d.up = d.shift + d.width;                           // 32 only when the prefix is empty
+    d.dmask = (1u << d.width) - 1u;
+    return d;
+}
+
+__device__ __forceinline__ void store_slice(const unsigned* hist, int rows, int width, unsigned* __restrict__ slices)
+{
+    unsigned* mine = slices + (size_t)blockIdx.x * ((size_t)rows << width);
+    const int dmask = (1 << width) - 1;
+    for (int i = threadIdx.x; i < rows << width; i += DP_BLOCK) mine[i] = hist[(i >> width) * TH_STRIDE + (i & dmask)];
+}
+
+// ------------------------------------------------------------ pair kernel --
+
+// Same traversal as the fused dispatch pass; every pair whose key matches the
+// prefix of a (column, quantile) slot bumps that slot's bin.  Pass 0: one row
+// per column (all quantiles share it).
+template <int G>
+__global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
+                                                        int pass, const SelState* S, unsigned* __restrict__ slices)
+{
+    __shared__ unsigned hist[TH_WORDS];
+    __shared__ __align__(16) Staged stage[DP_BLOCK];
+    if (S->tc.on) return;                               // the class kernel acts
+    const SelGlobal g = S->g[0];
+    const PassDigit dg = pass_digit(g, pass);
+    if (dg.width <= 0) return;
+    const int width = dg.width, shift = dg.shift, up = dg.up;
+    const unsigned dmask = dg.dmask;
+    const int nslot = (pass == 0) ? P : P * nq;
+    for (int i = threadIdx.x; i < nslot * TH_STRIDE; i += DP_BLOCK) hist[i] = 0u;
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & (G - 1), sub = lane / G;
+    const bool colv = col < P;
+    const disco_policy p = pol[colv ? col : 0];
+    unsigned prefix[DISCO_MAX_Q];
+    bool live[DISCO_MAX_Q];
+    bool any_live = false;
+#pragma unroll
+    for (int qi = 0; qi < DISCO_MAX_Q; ++qi) {
+        const bool on = colv && qi < nq;
+        const SelSlot sl = S->slot[0][on ? col * nq + qi : 0];
+        prefix[qi] = sl.prefix;
+        live[qi] = on && !sl.done;
+        any_live = any_live || live[qi];
+    }
+    Staged* st = stage + wave * 64;
+    const i64 nbatch = (tr.n_req + 63) >> 6;
+    // the pair evaluation is specialised on the kind of table (all Alg. 3, all Alg. 2, mixed)
+    auto run = [&](auto mode_c) {
+        constexpr int MODE = decltype(mode_c)::value;
+        for (i64 b = (i64)blockIdx.x * DP_WAVES + wave; b < nbatch; b += (i64)gridDim.x * DP_WAVES) {
+            const i64 i = b * 64 + lane;
+            const bool v = i < tr.n_req;
+            const int lv = v ? tr.l[i] : 0;
+            const float sv = v ? tr.s[i] : 0.0f;
+            const float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
+            const float dv = __fmaf_rn((float)lv, kv, tr.c);
+            st[lane] = Staged{lv, sv, 0, dv};
+            const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll 4
+            for (int it = 0; it < G; ++it) {
+                const int src = sub * G + it;
+                const Staged r = st[src];
+                const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d);
+                if (src < cnt) {
+                    const unsigned key = f2u(e.ttft) - g.minb;
+                    const unsigned dgt = (key >> shift) & dmask;
+                    const unsigned hi = (up >= 32) ? 0u : (key >> up);
+                    if (pass == 0) {
+                        if (any_live) atomicAdd(&hist[col * TH_STRIDE + dgt], 1u);
+                    } else {
+#pragma unroll
+                        for (int qi = 0; qi < DISCO_MAX_Q; ++qi)
+                            if (live[qi] && hi == prefix[qi]) atomicAdd(&hist[(col * nq + qi) * TH_STRIDE + dgt], 1u);
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    };
+    const int mode = table_mode(p, colv);
+    if (mode == 0) run(std::integral_constant<int, 0>{});
+    else if (mode == 1) run(std::integral_constant<int, 1>{});
+    else run(std::integral_constant<int, 2>{});
+    __syncthreads();
+    store_slice(hist, nslot, width, slices);
+}
+
+// ----------------------------------------------------------- class kernel --
+
+// LDS tables of the class kernel's later passes.
+struct ClsTables {
+    int sorted[DISCO_MAX_COLS];                  // thresholds in ascending order (unused tail: INT_MAX)
+    u64 dslots[DISCO_MAX_COLS + 1][2];           // slots of the columns p >= ub, as a 128-bit set
+    unsigned dist[DISCO_MAX_SLOTS];              // distinct prefixes of the live slots, ascending
+    u64 dmask[DISCO_MAX_SLOTS][2];               // live slots holding each distinct prefix
+    unsigned sprefix[DISCO_MAX_SLOTS];
+    int slive[DISCO_MAX_SLOTS];
+    int first[DISCO_MAX_SLOTS];
+    int rank[DISCO_MAX_SLOTS];
+    int ndist;
+    unsigned char col_of_pos[DISCO_MAX_COLS];
+};
+
+__global__ __launch_bounds__(DP_BLOCK) void k_ttft_cls(TraceView tr, int P, int nq, int pass, const SelState* S,
+                                                       unsigned* __restrict__ slices)
+{
+    __shared__ unsigned hist[TH_WORDS];
+    __shared__ ClsTables T;
+    if (!S->tc.on) return;                              // the pair kernel acts
+    const SelGlobal g = S->g[0];
+    const PassDigit dg = pass_digit(g, pass);
+    if (dg.width <= 0) return;
+    const int width = dg.width, shift = dg.shift, up = dg.up;
+    const unsigned dmask = dg.dmask;
+    const int nslot = P * nq;
+    const int rows = (pass == 0) ? 2 * (P + 1) : nslot;
+    const int t = threadIdx.x;
+    for (int i = t; i < rows * TH_STRIDE; i += DP_BLOCK) hist[i] = 0u;
+    if (t < DISCO_MAX_COLS) { T.sorted[t] = t < P ? S->tc.sorted_lth[t] : 0x7FFFFFFF; T.col_of_pos[t] = S->tc.col_of_pos[t]; }
+    if (pass > 0) {
+        // tables of this pass, built pairwise-parallel by the whole workgroup
+        if (t < DISCO_MAX_SLOTS) {
+            const bool in = t < nslot;
+            SelSlot sl;
+            if (in) sl = S->slot[0][t];
+            T.sprefix[t] = in ? sl.prefix : 0u;
+            T.slive[t] = in && !sl.done;
+            T.first[t] = in && !sl.done;                // cleared below if an earlier live slot holds the same prefix
+            T.rank[t] = 0;
+            T.dmask[t][0] = 0ull; T.dmask[t][1] = 0ull;
+        }
+        if (t <= DISCO_MAX_COLS) { T.dslots[t][0] = 0ull; T.dslots[t][1] = 0ull; }
+        if (t == 0) T.ndist = 0;
+        __syncthreads();
+        for (int pr = t; pr < DISCO_MAX_SLOTS * DISCO_MAX_SLOTS; pr += DP_BLOCK) {
+            const int a = pr >> 7, z = pr & (DISCO_MAX_SLOTS - 1);
+            if (z < a && T.slive[z] && T.slive[a] && T.sprefix[z] == T.sprefix[a]) T.first[a] = 0;
+        }
+        // slots of the sorted columns p >= ub
+        for (int pr = t; pr < (P + 1) * P; pr += DP_BLOCK) {
+            const int ub = pr / P, p = pr - ub * P;
+            if (p >= ub) {
+                const int c = T.col_of_pos[p];
+                for (int qi = 0; qi < nq; ++qi) {
+                    const int sidx = c * nq + qi;
+                    atomicOr((unsigned long long*)&T.dslots[ub][sidx >> 6], 1ull << (sidx & 63));
+                }
+            }
+        }
+        __syncthreads();
+        for (int pr = t; pr < DISCO_MAX_SLOTS * DISCO_MAX_SLOTS; pr += DP_BLOCK) {     // rank among the distinct prefixes
+            const int a = pr >> 7, o = pr & (DISCO_MAX_SLOTS - 1);
+            if (T.first[a] && T.first[o] && T.sprefix[o] < T.sprefix[a]) atomicAdd(&T.rank[a], 1);
+        }
+        __syncthreads();
+        if (t < DISCO_MAX_SLOTS && T.first[t]) { T.dist[T.rank[t]] = T.sprefix[t]; atomicAdd(&T.ndist, 1); }
+        for (int pr = t; pr < DISCO_MAX_SLOTS * DISCO_MAX_SLOTS; pr += DP_BLOCK) {     // slots holding each distinct prefix
+            const int a = pr >> 7, o = pr & (DISCO_MAX_SLOTS - 1);
+            if (T.first[a] && T.slive[o] && T.sprefix[o] == T.sprefix[a])
+                atomicOr((unsigned long long*)&T.dmask[T.rank[a]][o >> 6], 1ull << (o & 63));
+        }
+    }
+    __syncthreads();
+    const int ndist = pass > 0 ? T.ndist : 0;
+    for (i64 i = (i64)blockIdx.x * DP_BLOCK + t; i < tr.n_req; i += (i64)gridDim.x * DP_BLOCK) {
+        const int l = tr.l[i];
+        const float s = tr.s[i];
+        const float k = tr.k ? tr.k[i] : tr.k_s;
+        const float d = __fmaf_rn((float)l, k, tr.c);
+        int ub = 0;                                     // #{p : t_p <= l}: binary search over 64 padded entries
+#pragma unroll
+        for (int step = 64; step >= 1; step >>= 1)
+            if (ub + step <= DISCO_MAX_COLS && T.sorted[ub + step - 1] <= l) ub += step;
+        ub = ub < P ? ub : P;
+        const bool dev_wins = d < s;                    // ties go to the server
+        // value 0: d for the columns p >= ub (for every column if the device also wins the races);
+        // value 1: s for the columns p < ub
+        const int ub0 = dev_wins ? 0 : ub;
+        const bool two = !dev_wins && ub > 0;
+        const unsigned key0 = f2u(d) - g.minb, key1 = f2u(s) - g.minb;
+        if (pass == 0) {
+            if (ub0 < P) atomicAdd(&hist[ub0 * TH_STRIDE + ((key0 >> shift) & dmask)], 1u);
+            if (two) atomicAdd(&hist[(P + 1 + ub) * TH_STRIDE + ((key1 >> shift) & dmask)], 1u);
+        } else {
+#pragma unroll
+            for (int which = 0; which < 2; ++which) {
+                if (which == 1 && !two) continue;
+                if (which == 0 && ub0 >= P) continue;
+                const unsigned key = which ? key1 : key0;
+                const unsigned hi = key >> up;          // up < 32 after the first pass
+                int lo_i = 0, hi_i = ndist;             // first distinct prefix >= hi
+                while (lo_i < hi_i) {
+                    const int mid = (lo_i + hi_i) >> 1;
+                    if (T.dist[mid] < hi) lo_i = mid + 1; else hi_i = mid;
+                }
+                if (lo_i >= ndist || T.dist[lo_i] != hi) continue;
+                const int u = which ? ub : ub0;
+                u64 m0 = T.dmask[lo_i][0], m1 = T.dmask[lo_i][1];
+                if (which) { m0 &= ~T.dslots[u][0]; m1 &= ~T.dslots[u][1]; }
+                else { m0 &= T.dslots[u][0]; m1 &= T.dslots[u][1]; }
+                const unsigned dgt = (key >> shift) & dmask;
+                while (m0) { const int sidx = __ffsll((long long)m0) - 1; m0 &= m0 - 1; atomicAdd(&hist[sidx * TH_STRIDE + dgt], 1u); }
+                while (m1) { const int sidx = 64 + __ffsll((long long)m1) - 1; m1 &= m1 - 1; atomicAdd(&hist[sidx * TH_STRIDE + dgt], 1u); }
+            }
+        }
+    }
+    __syncthreads();
+    store_slice(hist, rows, width, slices);
+}
+
+// ------------------------------------------------------ reduce and select --
+
+// Adds the workgroup slices of one histogram row (workgroup = row; thread =
+// (bin, quarter of the slices)).
+__global__ __launch_bounds__(1024) void k_ttft_reduce(const SelState* S, int pass, int rows_pair, int rows_cls, int nsl_pair,
+                                                      int nsl_cls, const unsigned* __restrict__ slices, unsigned* rowsum)
+{
+    __shared__ unsigned part[1024];
+    const PassDigit dg = pass_digit(S->g[0], pass);
+    if (dg.width <= 0) return;
+    const int cls = S->tc.on;
+    const int rows = cls ? rows_cls : rows_pair, nsl = cls ? nsl_cls : nsl_pair;
+    const int row = blockIdx.x;
+    if (row >= rows) return;
+    const int bin = threadIdx.x & 255, q = threadIdx.x >> 8;
+    unsigned a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    if (bin < (1 << dg.width)) {
+        const size_t step = (size_t)rows << dg.width;
+        const unsigned* src = slices + ((size_t)row << dg.width) + bin;
+        int b = q;
+        for (; b + 12 < nsl; b += 16) {
+            a0 += src[(size_t)b * step]; a1 += src[(size_t)(b + 4) * step];
+            a2 += src[(size_t)(b + 8) * step]; a3 += src[(size_t)(b + 12) * step];
+        }
+        for (; b < nsl; b += 4) a0 += src[(size_t)b * step];
+    }
+    part[threadIdx.x] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (q == 0 && bin < (1 << dg.width))
+        rowsum[((size_t)row << dg.width) + bin] = part[bin] + part[256 + bin] + part[512 + bin] + part[768 + bin];
+}
+
+// Workgroup = (column, quantile) slot: the slot's histogram from the row sums
+// (thread = (bin, quarter of the rows)), the digit that holds the remaining
+// rank, the extended prefix.
+__global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int P, int nq, const unsigned* __restrict__ rowsum)
+{
+    __shared__ u64 part[1024];
+    __shared__ u64 wsum[4];
+    const PassDigit dg = pass_digit(S->g[0], pass);
+    if (dg.width <= 0) return;
+    const int width = dg.width;
+    const int s = blockIdx.x;
+    SelSlot sl = S->slot[0][s];
+    if (sl.done) return;
+    const int col = s / nq;
+    const int nbins = 1 << width;                          // <= 256
+    const int t = threadIdx.x & 255, q = threadIdx.x >> 8, lane = t & 63, wave = t >> 6;
+    u64 mine = 0;
+    if (t < nbins) {
+        if (pass > 0) {
+            if (q == 0) mine = rowsum[((size_t)s << width) + t];
+        } else if (!S->tc.on) {
+            if (q == 0) mine = rowsum[((size_t)col << width) + t];
+        } else {                                           // device rows ub <= p, race rows ub > p
+            const int p = S->tc.pos_of_col[col];
+            for (int ub = q; ub <= P; ub += 4) mine += rowsum[((size_t)(ub <= p ? ub : P + 1 + ub) << width) + t];
+        }
+    }
+    part[threadIdx.x] = mine;
+    __syncthreads();
+    mine = part[t] + part[256 + t] + part[512 + t] + part[768 + t];     // every quarter computes the same sums
+    u64 incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        unsigned lo = (unsigned)__shfl_up((int)(unsigned)incl, d, 64);
+        unsigned hi = (unsigned)__shfl_up((int)(unsigned)(incl >> 32), d, 64);
+        if (lane >= d) incl += ((u64)hi << 32) | lo;
+    }
+    if (q == 0 && lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) incl += wsum[w];
+    const u64 k = (u64)sl.k_rem;
+    // the rank never exceeds the number of matching values: exactly one bin takes it
+    if (q == 0 && t < nbins && incl >= k && incl - mine < k) {
+        sl.k_rem = (i64)(k - (incl - mine));
+        sl.prefix = (sl.prefix << width) | (unsigned)t;
+        S->slot[0][s] = sl;
+    }
+}
+
+template <int G>
+void launch_pair(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S, unsigned* slices,
+                 unsigned blocks, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_ttft_hist<G>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, P, nq, pass, S, slices);
+}
+
+}  // namespace
+
+void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S,
+                            unsigned* slices, unsigned* rowsum, hipStream_t stream)
+{
+    i64 bp = ((v.n_req + 63) / 64 + DP_WAVES - 1) / DP_WAVES;
+    if (bp < 1) bp = 1;
+    if (bp > DP_MAX_BLOCKS) bp = DP_MAX_BLOCKS;
+    i64 bc = (v.n_req + DP_BLOCK - 1) / DP_BLOCK;
+    if (bc < 1) bc = 1;
+    if (bc > TC_MAX_BLOCKS) bc = TC_MAX_BLOCKS;
+    int g = 1;
+    while (g < P) g <<= 1;
+    hipLaunchKernelGGL(k_ttft_cls, dim3((unsigned)bc), dim3(DP_BLOCK), 0, stream, v, P, nq, pass, S, slices);
+    switch (g) {
+    case 1: launch_pair<1>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
+    case 2: launch_pair<2>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
+    case 4: launch_pair<4>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
+    case 8: launch_pair<8>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
+    case 16: launch_pair<16>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
+    case 32: launch_pair<32>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
+    default: launch_pair<64>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
+    }
+    const int rows_pair = pass == 0 ? P : P * nq, rows_cls = pass == 0 ? 2 * (P + 1) : P * nq;
+    const int rows_max = rows_pair > rows_cls ? rows_pair : rows_cls;
+    hipLaunchKernelGGL(k_ttft_reduce, dim3((unsigned)rows_max), dim3(1024), 0, stream, S, pass, rows_pair, rows_cls, (int)bp,
+                       (int)bc, slices, rowsum);
+    hipLaunchKernelGGL(k_ttft_select, dim3((unsigned)(P * nq)), dim3(1024), 0, stream, S, pass, P, nq, rowsum);
+}
