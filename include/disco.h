@@ -326,10 +326,15 @@ typedef struct disco_search_out {
     disco_accum at_param;                 /* dispatch totals at the answer */
 } disco_search_out;
 
-/* Run n_search independent searches over the same trace; every step is one
- * fused dispatch-and-reduce pass that evaluates all searches' midpoints, and
- * the brackets are updated on the device, so there is no host round trip
- * between steps.  All searches must have the same n_steps.
+/* Run n_search independent searches over the same trace.  In general every
+ * step is one fused dispatch-and-reduce pass that evaluates all searches'
+ * midpoints; the brackets are updated on the device, so there is no host
+ * round trip between steps.  When every search is a length threshold of a
+ * server-constrained template (Alg. 3) against a prompt-token accumulator,
+ * with 0 <= lo and hi <= 32770, the accumulator is tabulated for every
+ * threshold in one pass (Alg. 3's running totals over the sorted lengths)
+ * and the steps read the table; results and recorded history are the same.
+ * All searches must have the same n_steps.
  * templ, spec: host, n_search entries.  out: device, n_search entries.
  * pol_out: device, n_search entries (nullable): the template with the found
  * parameter, ready to be copied into a policy table.
@@ -345,9 +350,11 @@ int32_t disco_budget_search(const disco_trace* trace /*host*/, const disco_cost_
 /* ---- helpers ------------------------------------------------------------ */
 
 /* Bytes of device workspace that any call above needs for n_req requests and
- * P columns (or searches).  The workspace holds partial results only; its
- * contents need not be preserved between calls, and calls that share one
- * workspace must not overlap in time. */
+ * P columns (or searches); about 44 MB, independent of both today.  The
+ * workspace holds partial results only; its contents need not be initialised
+ * or preserved between calls, and calls that share one workspace must not
+ * overlap in time.  It must be ordinary (coarse-grained) device memory,
+ * 256-byte aligned: the kernels use hardware floating-point atomics on it. */
 size_t disco_workspace_bytes(int64_t n_req, int32_t P);
 
 const char* disco_strerror(int32_t code);
