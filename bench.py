@@ -252,7 +252,7 @@ def cpu_baseline(idx: int) -> dict:
     import disco_inputs as DI
     from oracle import disco_oracle as O
 
-    n_sample = {0: 10_000, 1: 250_000, 2: 20_000, 3: 1_000_000, 4: 5_000}[idx]
+    n_sample = {0: 10_000, 1: 1_000_000, 2: 100_000, 3: 4_000_000, 4: 20_000}[idx]
     cfg = DI.config(idx, n_req=n_sample)
     tr = O.gen_trace(cfg["gen"])
     t0 = time.perf_counter()

@@ -114,6 +114,7 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
             for (int i = 0; i < DISCO_MAX_PASS; ++i) { g.plan.shift[i] = 0; g.plan.width[i] = 0; }
             TlSel& tl = S->tl;
             tl.ncls = 0; tl.nwalk = 0; tl.walk_mask = 0ull; tl.fallback = 0; tl.error = 0; tl.left = 31; tl.shift = 0; tl.width = 0; tl.G = 0;
+            tl.key_lo = 0u; tl.window = 0; tl.restart = 0;
             for (int i = 0; i < DISCO_MAX_GRP; ++i) tl.grp_prefix[i] = 0u;
         }
         S->g[which] = g;
@@ -169,7 +170,7 @@ __global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, 
             if (with_tl) {
                 const SelSlot s1 = S->slot[1][c * nq + qi];
                 st.tbt_rank[qi] = s1.rank;
-                if (s1.M > 0 && !S->tl.error && S->tl.left == 0) st.tbt_q[qi] = u2f(s1.prefix);
+                if (s1.M > 0 && !S->tl.error && S->tl.left == 0) st.tbt_q[qi] = u2f(s1.prefix + S->tl.key_lo);
             }
         }
     }

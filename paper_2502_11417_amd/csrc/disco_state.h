@@ -39,6 +39,13 @@ struct TlSel {
     int G;                         // distinct prefixes among the live slots
     unsigned grp_prefix[DISCO_MAX_GRP];
     int slot_grp[DISCO_MAX_SLOTS]; // prefix group of each live slot, -1 otherwise
+    // Window mode: keys are offsets from key_lo, clamped to 2^window ("outside", never counted).  Gaps sit just
+    // above the pacing interval, so a 21-bit window above it holds the usual order statistics and two passes
+    // decide them; a rank that falls outside (or into the clamped bottom bin) restarts the selection on raw keys.
+    unsigned key_lo;
+    int window;                    // key bits of the window, 0 = raw 31-bit keys
+    int restart;
+    int pad1;
     signed char cls_slot[DISCO_MAX_CLS];     // row of a walked class in the workgroups' LDS histogram, -1 otherwise
     unsigned char slot_cls[DISCO_MAX_CLS];   // class of an LDS row
 };

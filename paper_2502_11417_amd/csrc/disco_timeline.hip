@@ -25,6 +25,7 @@ struct HistCtx {
     unsigned* hist;          // LDS bins
     int shift, width, up;    // digit of this pass; up = shift + width
     int nq;
+    unsigned key_lo, key_cap; // see tbt_key
     const unsigned* sprefix; // LDS, per slot
     const int* slive;        // LDS, per slot
 };
@@ -51,8 +52,9 @@ __device__ __forceinline__ void hist_keys_cols(const HistCtx& h, const unsigned 
             bool pend[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                bin[k] = (key[k] >> h.shift) & dmask;
-                pend[k] = ok[k] && (key[k] >> h.up) == pf;        // up <= 31
+                const unsigned kk = tbt_key(key[k], h.key_lo, h.key_cap);
+                bin[k] = (kk >> h.shift) & dmask;
+                pend[k] = ok[k] && (kk >> h.up) == pf;           // clamped keys have a bit above every prefix
             }
             u64 todo = __ballot(pend[0] || pend[1] || pend[2] || pend[3]);
             while (todo) {
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
     if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
     const bool hist_pass = a.pass >= 0;       // pass -1: statistics
     HistCtx h;
-    h.hist = smem; h.shift = 0; h.width = 0; h.up = 0; h.nq = nq;
+    h.hist = smem; h.shift = 0; h.width = 0; h.up = 0; h.nq = nq; h.key_lo = 0u; h.key_cap = 0xFFFFFFFFu;
     h.sprefix = sprefix; h.slive = slive;
     if (hist_pass) {
         const TlSel* tl = &a.S->tl;
@@ -235,6 +237,7 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
         if (h.width <= 0 || !tl->fallback) return;     // selection finished, or class histograms (other kernel)
         h.shift = tl->shift;
         h.up = h.shift + h.width;
+        h.key_lo = tl->key_lo; h.key_cap = tl->window ? (1u << tl->window) : 0xFFFFFFFFu;
         const int words = (P * nq) << h.width;
         for (int i = threadIdx.x; i < words; i += TL_BLOCK) smem[i] = 0u;
         for (int i = threadIdx.x; i < P * nq; i += TL_BLOCK) {

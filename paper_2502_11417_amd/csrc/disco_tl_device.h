@@ -132,6 +132,15 @@ __device__ __forceinline__ int cls_find(const u64* s_cls, int ncls, u64 mask)
     return c;
 }
 
+// TBT selection key of a gap: its bit pattern minus key_lo (saturating at 0), clamped to key_cap.  Raw keys:
+// key_lo = 0, key_cap = 0xFFFFFFFF.  Window mode: key_cap = 2^window; clamped keys (and the sign-flagged keys of
+// tokens without a gap) have a bit above the window and match no prefix.
+__device__ __forceinline__ unsigned tbt_key(unsigned bits, unsigned key_lo, unsigned key_cap)
+{
+    const unsigned off = __builtin_elementwise_sub_sat(bits, key_lo);
+    return off < key_cap ? off : key_cap;
+}
+
 // Largest digit width whose `groups` histograms fit `words` bins.
 __device__ __host__ __forceinline__ int fit_width(long groups, long words)
 {

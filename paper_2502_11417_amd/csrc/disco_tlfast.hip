@@ -18,8 +18,8 @@
 //     histogram of the timeline's class.
 //
 // Lag trigger (token t is overdue by more than kappa tau): evaluated exactly,
-// with the oracle's operations, in the first chunk of a request and in every
-// later chunk that passes a cheap necessary condition (see `walk`).
+// with the oracle's operations, in every chunk that passes a cheap necessary
+// condition (see walk_hist); the other chunks provably cannot trigger.
 //
 // A timeline is computed once per request and source, never per policy
 // column: the recurrence does not depend on the pair's TTFT, so every column
@@ -37,72 +37,95 @@ constexpr unsigned KEY_SKIP = 0x80000000u;   // a key with the sign bit never ma
 
 struct WalkOut { int m; float M; };          // hand-off index (-1 none), running maximum over all tokens
 
-// Walks the timeline of one request and source.
+// Four arrival offsets of a lane from the token array; `safe` (wave-uniform)
+// says that every 16-byte load of the request's window lies inside the array.
+__device__ __forceinline__ void load4s(const float* __restrict__ arr, i64 g, i64 n_tok, bool safe, float r[4])
+{
+    if (safe) {
+        const float4 v = *reinterpret_cast<const float4*>(arr + g);
+        r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
+    } else {
+        load4(arr, g, n_tok, r);
+    }
+}
+
+// Can the lag trigger be screened by its necessary condition (see walk_hist)?
+__device__ __forceinline__ bool lag_fast_ok(int n, float tau, float kt)
+{
+    return (float)n + 2.0f <= 262144.0f * (kt / tau) && kt >= tau * 0.0009765625f;
+}
+
+// Histogram walk of one request and source: the delivery of every token and
+// the gap in front of it -> sink(key[4]) once per chunk (tokens without a gap
+// carry KEY_SKIP).
 //   mem    arrivals from the CSR token array (else t * gap)
 //   lag    evaluate the lag trigger (server source of a column with hand-off)
-//   HIST   per-token deliveries and gap keys -> sink(key[4]), invalid tokens flagged KEY_SKIP
+//   first  the lane's elements of the first chunk, if `have_first` (loaded ahead by the caller with load_first)
 //
-// Necessary condition for the trigger in chunks after the first.  With
-// C <= M_{t-1} (C = a running maximum taken earlier) and monotone rounding,
+// Necessary condition for the trigger.  With C <= M_{t-1} (C = a running
+// maximum taken earlier: u_0 in the first chunk, the carried maximum later)
+// and monotone rounding,
 //   lag_t = fl(r_t - fl(fl((t-1) tau + M_{t-1}) + tau)) <= fl(r_t - fl(fl((t-1) tau + C) + tau)),
 // which differs from u_t - C = fl(r_t - t tau) - C by at most four roundings
-// of magnitudes below 2 t tau + 2 |C| + kappa tau.  `fast_ok` bounds t and
-// `c_ok` bounds |C| so that this error stays below kappa tau / 4; hence
+// of magnitudes below 2 t tau + 2 |C| + kappa tau.  lag_fast_ok bounds t and
+// `cheap` bounds |C| so that this error stays below kappa tau / 4; hence
 // lag_t > kappa tau implies u_t > C + kappa tau / 2, and a chunk where no
 // token satisfies the latter cannot trigger.
-//   first  the lane's elements of the first chunk, if `have_first` (loaded ahead by the caller with load_first)
-template <bool HIST, class Sink>
-__device__ __forceinline__ WalkOut walk(bool mem, int n, const float* __restrict__ arr, i64 off, i64 n_tok, int align,
-                                        const float first[4], bool have_first, float gap, bool lag, float g_dev, int l, float k, float c, float tau, float kt, bool fast_ok,
-                                        int lane, Sink&& sink)
+template <class Sink>
+__device__ __forceinline__ WalkOut walk_hist(bool mem, int n, const float* __restrict__ arr, i64 off, i64 n_tok, int align,
+                                             const float first[4], bool have_first, float gap, bool lag, float g_dev, int l,
+                                             float k, float c, float tau, float kt, int lane, Sink&& sink)
 {
     const float ninf = -INFINITY;
     const float ntau = -tau;
     const int mis = mem ? (int)((off + align) & 3) : 0;      // the window starts at the 16-byte boundary below the request
-    const i64 gbase = off - mis + 4 * lane;
+    const int lane4 = 4 * lane - mis;                        // token index of this lane's first element in chunk 0
+    const i64 gbase = off + lane4;
     const int total = n + mis;
+    const bool safe = mem && off - mis >= 0 && off + n + 3 <= n_tok;
+    const bool fast_ok = lag_fast_ok(n, tau, kt);
     int m = -1;
     float base = 0.0f;
-    float Mlane = ninf;            // !HIST: per-lane maximum of u over the chunks so far
-    float carryM = ninf;           // HIST: maximum over the chunks so far; !HIST: maximum of the first chunk
-    float carryD = 0.0f;           // HIST: delivery of the last token of the previous chunk
+    float carryM = ninf;           // running maximum over the chunks so far
+    float carryD = 0.0f;           // delivery of the last token of the previous chunk
     float nxt[4] = {first[0], first[1], first[2], first[3]};
-    if (mem && !have_first && 4 * lane - mis < n) load4(arr, gbase, n_tok, nxt);
+    if (mem && !have_first && lane4 < n) load4s(arr, gbase, n_tok, safe, nxt);
 #pragma unroll 1
     for (int e0 = 0; e0 < total; e0 += 256) {
-        const int tk0 = e0 + 4 * lane - mis;                 // token index of this lane's first element
-        float r[4], tf[4], u[4];
-        bool val[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            tf[q] = (float)(tk0 + q);
-            val[q] = (unsigned)(tk0 + q) < (unsigned)n;
-        }
+        const int tk0 = lane4 + e0;
+        const float tf0 = (float)tk0;
+        const float tf[4] = {tf0, tf0 + 1.0f, tf0 + 2.0f, tf0 + 3.0f};
+        float r[4], u[4];
         if (m >= 0) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) r[q] = __fmaf_rn((float)(tk0 + q - m + 1), g_dev, base);
         } else if (mem) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) r[q] = nxt[q];
-            if (e0 + 256 < total && tk0 + 256 < n) load4(arr, gbase + e0 + 256, n_tok, nxt);   // next chunk in flight
+            if (e0 + 256 < total && tk0 + 256 < n) load4s(arr, gbase + e0 + 256, n_tok, safe, nxt);   // next chunk in flight
         } else {
 #pragma unroll
             for (int q = 0; q < 4; ++q) r[q] = tf[q] * gap;
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) u[q] = val[q] ? __fmaf_rn(tf[q], ntau, r[q]) : ninf;
+        for (int q = 0; q < 4; ++q) u[q] = __fmaf_rn(tf[q], ntau, r[q]);
+        const bool full = e0 > 0 && e0 + 256 <= total;      // every element of the chunk is a token of the request
+        if (!full) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) u[q] = ((unsigned)(tk0 + q) < (unsigned)n) ? u[q] : ninf;
+        }
         float i0 = u[0], i1 = fmaxf(i0, u[1]), i2 = fmaxf(i1, u[2]), i3 = fmaxf(i2, u[3]);
         bool exact = false;
         if (lag && m < 0) {
-            const bool c_ok = fabsf(carryM) <= 262144.0f * kt;
-            exact = e0 == 0 || !fast_ok || !c_ok || __ballot(i3 > carryM + 0.5f * kt) != 0ull;
+            float C = carryM;
+            if (e0 == 0) {                                  // u_0 = r_0: element `mis` of lane 0
+                const float r0 = mis == 0 ? r[0] : (mis == 1 ? r[1] : (mis == 2 ? r[2] : r[3]));
+                C = bcast_f(r0, 0);
+            }
+            const bool cheap = fast_ok && fabsf(C) <= 262144.0f * kt;
+            exact = !cheap || __ballot(i3 > C + 0.5f * kt) != 0ull;
         }
-        float E = ninf;            // running maximum over every token before this lane's first
-        if (HIST || exact) {
-            const float before = HIST ? carryM : wave_max_f32(Mlane);
-            const float incl = wave_incl_max_dpp(i3, lane);
-            E = fmaxf(wave_prev(incl, ninf), before);
-        }
+        float E = fmaxf(wave_prev(wave_incl_max_dpp(i3, lane), ninf), carryM);      // running maximum before this lane's tokens
         if (exact) {
             const float ex[4] = {E, fmaxf(E, i0), fmaxf(E, i1), fmaxf(E, i2)};
             bool trig[4];
@@ -111,7 +134,7 @@ __device__ __forceinline__ WalkOut walk(bool mem, int n, const float* __restrict
             for (int q = 0; q < 4; ++q) {
                 slot[q] = __fmaf_rn(tf[q] - 1.0f, tau, ex[q]) + tau;        // delta_{t-1} + tau
                 const float lg = r[q] - slot[q];
-                trig[q] = val[q] && tk0 + q >= 1 && lg > kt;
+                trig[q] = (unsigned)(tk0 + q - 1) < (unsigned)(n - 1) && lg > kt;      // tokens 1 .. n-1
             }
             const u64 any = __ballot(trig[0] || trig[1] || trig[2] || trig[3]);
             if (any) {
@@ -128,36 +151,30 @@ __device__ __forceinline__ WalkOut walk(bool mem, int n, const float* __restrict
                 for (int q = 0; q < 4; ++q)
                     if (tk0 + q >= m) {
                         r[q] = __fmaf_rn((float)(tk0 + q - m + 1), g_dev, base);
-                        u[q] = val[q] ? __fmaf_rn(tf[q], ntau, r[q]) : ninf;
+                        u[q] = ((unsigned)(tk0 + q) < (unsigned)n) ? __fmaf_rn(tf[q], ntau, r[q]) : ninf;
                     }
                 i0 = u[0]; i1 = fmaxf(i0, u[1]); i2 = fmaxf(i1, u[2]); i3 = fmaxf(i2, u[3]);
-                if (HIST) {
-                    const float incl = wave_incl_max_dpp(i3, lane);
-                    E = fmaxf(wave_prev(incl, ninf), carryM);
-                }
+                E = fmaxf(wave_prev(wave_incl_max_dpp(i3, lane), ninf), carryM);
             }
         }
-        if (HIST) {
-            const float M0 = fmaxf(E, i0), M1 = fmaxf(E, i1), M2 = fmaxf(E, i2), M3 = fmaxf(E, i3);
-            const float d0 = __fmaf_rn(tf[0], tau, M0), d1 = __fmaf_rn(tf[1], tau, M1);
-            const float d2 = __fmaf_rn(tf[2], tau, M2), d3 = __fmaf_rn(tf[3], tau, M3);
-            const float p0 = wave_prev(d3, carryD);
-            unsigned key[4] = {f2u(d0 - p0), f2u(d1 - d0), f2u(d2 - d1), f2u(d3 - d2)};
+        const float M0 = fmaxf(E, i0), M1 = fmaxf(E, i1), M2 = fmaxf(E, i2), M3 = fmaxf(E, i3);
+        const float d0 = __fmaf_rn(tf[0], tau, M0), d1 = __fmaf_rn(tf[1], tau, M1);
+        const float d2 = __fmaf_rn(tf[2], tau, M2), d3 = __fmaf_rn(tf[3], tau, M3);
+        const float p0 = wave_prev(d3, carryD);
+        unsigned key[4] = {f2u(d0 - p0), f2u(d1 - d0), f2u(d2 - d1), f2u(d3 - d2)};
+        if (!full) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
                 key[q] = ((unsigned)(tk0 + q - 1) < (unsigned)(n - 1)) ? key[q] : KEY_SKIP;     // tokens 1 .. n-1 have a gap
-            sink(key);
-            carryM = bcast_f(M3, 63);
-            carryD = bcast_f(d3, 63);
-        } else {
-            Mlane = fmaxf(Mlane, i3);
-            if (lag && e0 == 0) carryM = wave_max_f32(i3);
         }
+        sink(key);
+        carryM = bcast_f(M3, 63);
+        carryD = bcast_f(d3, 63);
     }
-    return WalkOut{m, HIST ? carryM : wave_max_f32(Mlane)};
+    return WalkOut{m, carryM};
 }
 
-// The lane's elements of the first chunk of a request's token window (see walk).
+// The lane's elements of the first chunk of a request's token window (see walk_hist).
 __device__ __forceinline__ void load_first(const float* __restrict__ arr, i64 off, int n, i64 n_tok, int align, int lane,
                                            float out[4])
 {
@@ -192,12 +209,6 @@ __device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_pol
     return b;
 }
 
-// Can chunks after the first use the necessary condition of the lag trigger?
-__device__ __forceinline__ bool lag_fast_ok(int n, float tau, float kt)
-{
-    return (float)n + 2.0f <= 262144.0f * (kt / tau) && kt >= tau * 0.0009765625f;
-}
-
 // ------------------------------------------------------------ statistics ---
 
 struct StatsArgs {
@@ -206,6 +217,104 @@ struct StatsArgs {
     int32_t* mig_idx; int32_t* n_src_tok; float* t_last;
     MigPartial* totals;            // DISCO_NCOPY x 64 device-wide totals
 };
+
+// Statistics walk of one request and source: the hand-off index and the
+// running maximum over all tokens (the last delivery is fma(n-1, tau, M)).
+// Only a maximum is needed, not a scan: every lane keeps the maximum of its
+// own tokens and the wave reduces once at the end.  The lag trigger is
+// evaluated exactly only in chunks that pass the necessary condition stated
+// above walk_hist, here with C = u_0 (the first token's shifted arrival, a lower
+// bound of every later running maximum).
+//   src: 0 token array, 1 constant gap
+__device__ __forceinline__ WalkOut walk_stats(bool mem, int n, const float* __restrict__ arr, i64 off, i64 n_tok, int align,
+                                              const float first[4], bool have_first, float gap, bool lag, float g_dev,
+                                              int l, float k, float c, float tau, float kt, int lane)
+{
+    const float ninf = -INFINITY;
+    const float ntau = -tau;
+    const int mis = mem ? (int)((off + align) & 3) : 0;      // the window starts at the 16-byte boundary below the request
+    const int lane4 = 4 * lane - mis;                        // token index of this lane's first element in chunk 0
+    const i64 gbase = off + lane4;
+    const int total = n + mis;
+    const bool safe = mem && off - mis >= 0 && off + n + 3 <= n_tok;
+    const bool fast_ok = lag_fast_ok(n, tau, kt);
+    int m = -1;
+    float base = 0.0f;
+    float Mlane = ninf;            // maximum of u over this lane's tokens so far
+    float C = 0.0f;                // u_0
+    float nxt[4] = {first[0], first[1], first[2], first[3]};
+    if (mem && !have_first && lane4 < n) load4s(arr, gbase, n_tok, safe, nxt);
+#pragma unroll 1
+    for (int e0 = 0; e0 < total; e0 += 256) {
+        const int tk0 = lane4 + e0;
+        const float tf0 = (float)tk0;
+        const float tf[4] = {tf0, tf0 + 1.0f, tf0 + 2.0f, tf0 + 3.0f};
+        float r[4], u[4];
+        if (m >= 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) r[q] = __fmaf_rn((float)(tk0 + q - m + 1), g_dev, base);
+        } else if (mem) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) r[q] = nxt[q];
+            if (e0 + 256 < total && tk0 + 256 < n) load4s(arr, gbase + e0 + 256, n_tok, safe, nxt);   // next chunk in flight
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) r[q] = tf[q] * gap;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) u[q] = __fmaf_rn(tf[q], ntau, r[q]);
+        const bool full = e0 > 0 && e0 + 256 <= total;      // every element of the chunk is a token of the request
+        if (!full) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) u[q] = ((unsigned)(tk0 + q) < (unsigned)n) ? u[q] : ninf;
+        }
+        float i3 = fmaxf(fmaxf(u[0], u[1]), fmaxf(u[2], u[3]));
+        if (lag && m < 0) {
+            if (e0 == 0) {                                  // u_0 = r_0: element `mis` of lane 0
+                const float r0 = mis == 0 ? r[0] : (mis == 1 ? r[1] : (mis == 2 ? r[2] : r[3]));
+                C = bcast_f(r0, 0);
+            }
+            const bool cheap = fast_ok && fabsf(C) <= 262144.0f * kt;
+            if (!cheap || __ballot(i3 > C + 0.5f * kt) != 0ull) {
+                // exact evaluation: running maximum before each token, the oracle's operations for the lag
+                const float before = wave_max_f32(Mlane);
+                const float i0 = u[0], i1 = fmaxf(i0, u[1]), i2 = fmaxf(i1, u[2]);
+                const float incl = wave_incl_max_dpp(i3, lane);
+                const float E = fmaxf(wave_prev(incl, ninf), before);
+                const float ex[4] = {E, fmaxf(E, i0), fmaxf(E, i1), fmaxf(E, i2)};
+                bool trig[4];
+                float slot[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    slot[q] = __fmaf_rn(tf[q] - 1.0f, tau, ex[q]) + tau;        // delta_{t-1} + tau
+                    const float lg = r[q] - slot[q];
+                    trig[q] = (unsigned)(tk0 + q - 1) < (unsigned)(n - 1) && lg > kt;      // tokens 1 .. n-1
+                }
+                const u64 any = __ballot(trig[0] || trig[1] || trig[2] || trig[3]);
+                if (any) {
+                    const int ml = __ffsll((long long)any) - 1;
+                    const int qf = trig[0] ? 0 : (trig[1] ? 1 : (trig[2] ? 2 : 3));
+                    const float sl = trig[0] ? slot[0] : (trig[1] ? slot[1] : (trig[2] ? slot[2] : slot[3]));
+                    m = bcast_i(tk0, ml) + bcast_i(qf, ml);
+                    // hand-off: decided once the token is kappa*tau overdue; the device re-prefills the
+                    // prompt plus the m tokens already produced, then generates at its own pace
+                    const float t_dec = bcast_f(sl, ml) + kt;
+                    const float t_mig = __fmaf_rn((float)(l + m), k, c);
+                    base = t_dec + t_mig;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (tk0 + q >= m) {
+                            r[q] = __fmaf_rn((float)(tk0 + q - m + 1), g_dev, base);
+                            u[q] = ((unsigned)(tk0 + q) < (unsigned)n) ? __fmaf_rn(tf[q], ntau, r[q]) : ninf;
+                        }
+                    i3 = fmaxf(fmaxf(u[0], u[1]), fmaxf(u[2], u[3]));
+                }
+            }
+        }
+        Mlane = fmaxf(Mlane, i3);
+    }
+    return WalkOut{m, wave_max_f32(Mlane)};
+}
 
 __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, int align, const disco_policy* __restrict__ pol,
                                                        StatsArgs a)
@@ -223,57 +332,66 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
     double acc_tlast = 0.0;
     const float tau = a.tau, kt = a.kt;
     const bool mem = tr.arr != nullptr;
-    auto nosink = [](const unsigned*) {};
+    const bool mat = a.mig_idx != nullptr || a.n_src_tok != nullptr || a.t_last != nullptr;
     const i64 nwaves = (i64)gridDim.x * (TS_BLOCK / 64);
     const i64 nbatch = (tr.n_req + TF_RB - 1) / TF_RB;
     for (i64 bt = (i64)blockIdx.x * (TS_BLOCK / 64) + wave; bt < nbatch; bt += nwaves) {
         const Batch b = load_batch(tr, spol, P, bt * TF_RB, lane);
         const int cnt = (int)((tr.n_req - bt * TF_RB < TF_RB) ? (tr.n_req - bt * TF_RB) : TF_RB);
-        const u64 memw = mem ? __ballot((b.m[1] | b.m[2]) != 0ull) : 0ull;     // requests that read the token array
+        const u64 srvw = __ballot((b.m[1] | b.m[2]) != 0ull);                  // requests with a server-sourced column
+        const u64 memw = mem ? srvw : 0ull;                                    // ... that read the token array
+        const bool any_plain = __ballot(b.m[1] != 0ull) != 0ull;
         float pre[4] = {0.f, 0.f, 0.f, 0.f};
         if (memw & 1ull) load_first(tr.arr, (i64)bcast_u64((u64)b.off, 0), bcast_i(b.n, 0), n_tok, align, lane, pre);
 #pragma unroll 1
         for (int rq = 0; rq < cnt; ++rq) {
             const i64 i = bt * TF_RB + rq;
-            const int n = bcast_i(b.n, rq), l = bcast_i(b.l, rq);
-            const float gd = bcast_f(b.gd, rq);
-            const u64 mask_dev = bcast_u64(b.m[0], rq), mask_plain = bcast_u64(b.m[1], rq), mask_lag = bcast_u64(b.m[2], rq);
+            const int n = bcast_i(b.n, rq);
             const float cur[4] = {pre[0], pre[1], pre[2], pre[3]};
-            bool have = (memw >> rq) & 1ull;
             if ((memw >> (rq + 1)) & 1ull)          // the next request's first chunk is loaded while this one is walked
                 load_first(tr.arr, (i64)bcast_u64((u64)b.off, rq + 1), bcast_i(b.n, rq + 1), n_tok, align, lane, pre);
             tot_n += (u64)n;
             tot_cnt += (u64)(n - 1);
-            WalkOut res_lag{-1, 0.0f};
-            bool lag_done = false;
-            // order lag, plain, device; a lag run that never fired is also the plain result
-#pragma unroll 1
-            for (int variant = 2; variant >= 0; --variant) {
-                const u64 mask = variant == 2 ? mask_lag : (variant == 1 ? mask_plain : mask_dev);
-                if (!mask) continue;
-                WalkOut res;
-                const bool dev = variant == 0;
-                const float gap = dev ? gd : bcast_f(b.gap, rq);
-                const bool from_mem = !dev && mem;
-                if (variant == 1 && lag_done && res_lag.m < 0) {
-                    res = res_lag;
-                } else if (!from_mem && pure_pacing(true, gap, tau)) {
-                    res = WalkOut{-1, 0.0f};
-                } else {
-                    const i64 off = from_mem ? (i64)bcast_u64((u64)b.off, rq) : 0;
-                    res = walk<false>(from_mem, n, tr.arr, off, n_tok, align, cur, from_mem && have, gap, variant == 2, gd, l,
-                                      bcast_f(b.k, rq), tr.c, tau, kt, lag_fast_ok(n, tau, kt), lane, nosink);
-                    if (from_mem) have = false;
+            const u64 mask_lag = bcast_u64(b.m[2], rq);
+            const u64 mask_plain = any_plain ? bcast_u64(b.m[1], rq) : 0ull;
+            // server source: one walk (with the lag trigger if a column wants it); a second, plain one only if
+            // columns without hand-off share the request with a hand-off that fired
+            WalkOut lagw{-1, 0.0f}, plainw{-1, 0.0f};
+            if ((srvw >> rq) & 1ull) {
+                const float gap = mem ? 0.0f : bcast_f(b.gap, rq);
+                const bool closed = !mem && pure_pacing(true, gap, tau);        // M = 0, no hand-off
+                if (!closed) {
+                    const i64 off = mem ? (i64)bcast_u64((u64)b.off, rq) : 0;
+                    const bool lag = mask_lag != 0ull;
+                    const float gd = bcast_f(b.gd, rq), k = bcast_f(b.k, rq);
+                    const int l = bcast_i(b.l, rq);
+                    lagw = walk_stats(mem, n, tr.arr, off, n_tok, align, cur, mem, gap, lag, gd, l, k, tr.c, tau, kt, lane);
+                    plainw = lagw;
+                    if (lag && lagw.m >= 0 && mask_plain != 0ull)
+                        plainw = walk_stats(mem, n, tr.arr, off, n_tok, align, cur, false, gap, false, gd, l, k, tr.c, tau, kt, lane);
                 }
-                if (variant == 2) { res_lag = res; lag_done = true; }
-                if ((mask >> lane) & 1ull) {
-                    const float t_last = __fmaf_rn((float)(n - 1), tau, res.M);
-                    const int nsrc = dev ? 0 : ((res.m >= 0) ? res.m : n);
-                    acc_s_dec += (u64)nsrc;
-                    if (res.m >= 0) { acc_mig += 1u; acc_repre += (u64)l + (u64)res.m; }
-                    acc_tlast += (double)t_last;
-                    if (a.mig_idx) a.mig_idx[(size_t)lane * tr.n_req + i] = res.m;
-                    if (a.n_src_tok) a.n_src_tok[(size_t)lane * tr.n_req + i] = dev ? n : nsrc;
+            }
+            // device source: constant gap
+            WalkOut devw{-1, 0.0f};
+            const u64 mask_dev = bcast_u64(b.m[0], rq);
+            if (mask_dev != 0ull) {
+                const float gd = bcast_f(b.gd, rq);
+                if (!pure_pacing(true, gd, tau))
+                    devw = walk_stats(false, n, nullptr, 0, 0, 0, cur, false, gd, false, gd, 0, 0.0f, 0.0f, tau, kt, lane);
+            }
+            // lane = column picks the timeline of its source
+            const bool in_lag = (mask_lag >> lane) & 1ull, in_plain = (mask_plain >> lane) & 1ull;
+            const bool in_dev = (mask_dev >> lane) & 1ull;
+            if (in_lag || in_plain || in_dev) {
+                const WalkOut w = in_lag ? lagw : (in_plain ? plainw : devw);
+                const float t_last = __fmaf_rn((float)(n - 1), tau, w.M);
+                const int nsrc = in_dev ? 0 : ((w.m >= 0) ? w.m : n);
+                acc_s_dec += (u64)nsrc;
+                if (w.m >= 0) { acc_mig += 1u; acc_repre += (u64)bcast_i(b.l, rq) + (u64)w.m; }
+                acc_tlast += (double)t_last;
+                if (mat) {
+                    if (a.mig_idx) a.mig_idx[(size_t)lane * tr.n_req + i] = w.m;
+                    if (a.n_src_tok) a.n_src_tok[(size_t)lane * tr.n_req + i] = in_dev ? n : nsrc;
                     if (a.t_last) a.t_last[(size_t)lane * tr.n_req + i] = t_last;
                 }
             }
@@ -333,6 +451,7 @@ struct HistArgs {
 struct HistCtx {
     unsigned* hist;
     int shift, width, up, G;
+    unsigned key_lo, key_cap;      // see tbt_key
     unsigned stride;               // words per prefix group = nwalk << width
     unsigned grp_prefix[DISCO_MAX_GRP];
 };
@@ -347,7 +466,8 @@ __device__ __forceinline__ void hist_keys(const HistCtx& h, const unsigned key[4
     bool pend[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const unsigned hi = key[q] >> h.up;                      // up <= 31: the sign flag of skipped keys stays in
+        const unsigned kq = tbt_key(key[q], h.key_lo, h.key_cap);
+        const unsigned hi = kq >> h.up;                          // the flag of skipped or clamped keys stays in
         unsigned g = 0;
         bool hit = hi == h.grp_prefix[0];
         if (h.G > 1) {
@@ -359,7 +479,7 @@ __device__ __forceinline__ void hist_keys(const HistCtx& h, const unsigned key[4
             }
         }
         pend[q] = hit;
-        idx[q] = g * h.stride + row_base + ((key[q] >> h.shift) & dmask);
+        idx[q] = g * h.stride + row_base + ((kq >> h.shift) & dmask);
     }
     const u64 todo = __ballot(pend[0] || pend[1] || pend[2] || pend[3]);
     if (!todo) return;
@@ -395,6 +515,7 @@ __global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok
     h.hist = smem; h.width = width; h.shift = tl->shift; h.up = h.shift + width;
     h.G = tl->G < DISCO_MAX_GRP ? tl->G : DISCO_MAX_GRP;
     h.stride = (unsigned)nwalk << width;
+    h.key_lo = tl->key_lo; h.key_cap = tl->window ? (1u << tl->window) : 0xFFFFFFFFu;
     for (int k = 0; k < DISCO_MAX_GRP; ++k) h.grp_prefix[k] = tl->grp_prefix[k];
     if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
     if (threadIdx.x < DISCO_MAX_CLS) { s_cls[threadIdx.x] = tl->cls_mask[threadIdx.x]; s_slot[threadIdx.x] = tl->cls_slot[threadIdx.x]; }
@@ -457,8 +578,8 @@ __global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok
                 const float gap = dev ? gd : bcast_f(b.gap, rq);
                 const bool from_mem = !dev && mem;
                 const i64 off = from_mem ? (i64)bcast_u64((u64)b.off, rq) : 0;
-                walk<true>(from_mem, n, tr.arr, off, n_tok, align, cur, from_mem && have, gap, variant == 2, gd, l,
-                           bcast_f(b.k, rq), tr.c, tau, kt, lag_fast_ok(n, tau, kt), lane, sink);
+                walk_hist(from_mem, n, tr.arr, off, n_tok, align, cur, from_mem && have, gap, variant == 2, gd, l,
+                          bcast_f(b.k, rq), tr.c, tau, kt, lane, sink);
                 if (from_mem) have = false;
             }
         }

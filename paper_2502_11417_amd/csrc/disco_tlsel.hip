@@ -161,7 +161,12 @@ __global__ __launch_bounds__(256) void k_tl_classify(TraceView tr, const disco_p
         }
         tl.nwalk = nw;
         if (__hip_atomic_load(&tl.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { tl.fallback = 1; tl.error = 0; }
-        tl.left = 31;
+        // gaps sit just above the pacing interval (down to a few thousand ulps below it after rounding): try a
+        // 21-bit window of keys first
+        const unsigned tb = f2u(tau);
+        tl.restart = 0;
+        if (tb >= 8192u) { tl.key_lo = tb - 8192u; tl.window = 21; tl.left = 21; }
+        else { tl.key_lo = 0u; tl.window = 0; tl.left = 31; }
         tbt_plan_next(S, P, nq);
         *ticket = 0u;
     }
@@ -209,13 +214,14 @@ __global__ __launch_bounds__(1024) void k_tbt_analytic(SelState* S, unsigned* gh
     const unsigned dmask = (1u << width) - 1u;
     const int words = Gused << width;
     const int shift = tl.shift, up = tl.shift + width;
+    const unsigned key_cap = tl.window ? (1u << tl.window) : 0xFFFFFFFFu;
     for (int i = threadIdx.x; i < words; i += blockDim.x) lds[i] = 0u;
     __syncthreads();
     for (int t = 1 + (int)threadIdx.x; t < DISCO_PP_NMAX; t += blockDim.x) {
         const unsigned cnt = row[t];
         if (!cnt) continue;
-        const unsigned key = f2u((float)t * tau - (float)(t - 1) * tau);
-        const unsigned hi = key >> up;                     // up <= 31
+        const unsigned key = tbt_key(f2u((float)t * tau - (float)(t - 1) * tau), tl.key_lo, key_cap);
+        const unsigned hi = key >> up;                     // clamped keys match no prefix
         int g = -1;
         for (int k = 0; k < Gused; ++k) g = (hi == tl.grp_prefix[k] && g < 0) ? k : g;
         if (g >= 0) atomicAdd(&lds[((unsigned)g << width) | ((key >> shift) & dmask)], cnt);
@@ -288,7 +294,10 @@ __global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const u
     if (threadIdx.x == 0) {
         int dsel = s_digit;
         u64 rem = s_rem;
-        if (dsel < 0) { dsel = nbins - 1; rem = 1; }      // not reachable for a consistent histogram
+        // window mode: a rank beyond the counted keys, or in the bottom bin (which also holds the keys below the
+        // window), is not decided here -> start over on raw keys.  Raw keys: the rank is always found.
+        if (tl.window && (dsel < 0 || (dsel == 0 && tl.left == tl.window))) S->tl.restart = 1;
+        if (dsel < 0) { dsel = nbins - 1; rem = 1; }
         sl.k_rem = (i64)rem;
         sl.prefix = (sl.prefix << width) | (unsigned)dsel;
         S->slot[1][s] = sl;
@@ -306,9 +315,19 @@ __global__ __launch_bounds__(1024) void k_tbt_plan(SelState* S, int P, int nq, u
     for (int i = threadIdx.x; i < words; i += blockDim.x) ghist[i] = 0u;
     __syncthreads();
     if (threadIdx.x == 0) {
-        tl.left -= width;
-        if (tl.left <= 0) { tl.left = 0; tl.width = 0; tl.G = 0; }
-        else tbt_plan_next(S, P, nq);
+        if (tl.window && tl.restart) {                     // the window missed a rank: all slots start over on raw keys
+            tl.window = 0; tl.key_lo = 0u; tl.restart = 0; tl.left = 31;
+            for (int s = 0; s < P * nq; ++s) {
+                SelSlot sl = S->slot[1][s];
+                sl.prefix = 0u; sl.k_rem = sl.rank;
+                S->slot[1][s] = sl;
+            }
+            tbt_plan_next(S, P, nq);
+        } else {
+            tl.left -= width;
+            if (tl.left <= 0) { tl.left = 0; tl.width = 0; tl.G = 0; }
+            else tbt_plan_next(S, P, nq);
+        }
     }
 }
 
