@@ -445,7 +445,8 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             // launches after the last needed pass return at once
             a.ppcnt = (unsigned*)(ws + L.ppcnt);
             const disco_policy* dpol = (const disco_policy*)(ws + L.pol);
-            disco_launch_tl_classify(v, dpol, P, nq, tl->tau, S, a.ppcnt, gh, (unsigned*)(ws + L.ticket), stream);
+            disco_launch_tl_classify(v, dpol, P, nq, tl->tau, S, a.ppcnt, gh, (u64*)(ws + L.slices), (unsigned*)(ws + L.ticket),
+                                     stream);
             for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;
                 disco_launch_tl_hist_fast(v, trace->n_tok, dpol, a, stream);

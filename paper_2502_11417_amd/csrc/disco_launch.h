@@ -45,7 +45,8 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
 void disco_launch_timeline_general(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                    hipStream_t stream);
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
-                              unsigned* ppcnt, unsigned* ghist, unsigned* ticket, hipStream_t stream);
+                              unsigned* ppcnt, unsigned* ghist, u64* parts /* 1024 x 66 words of scratch */,
+                              unsigned* ticket, hipStream_t stream);
 void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                hipStream_t stream);
 void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,

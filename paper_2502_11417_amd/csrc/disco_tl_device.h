@@ -97,32 +97,6 @@ __device__ __forceinline__ bool pure_pacing(bool constant_gap, float gap, float 
     return constant_gap && gap < 0.999f * tau;
 }
 
-// Class of a column set: index in the device-wide table, claimed on first use.
-// Wave-uniform.  Returns -1 when the table is full.
-__device__ __forceinline__ int cls_lookup(u64 mask, u64* s_cls, TlSel* tl, int lane)
-{
-    for (int attempt = 0; attempt < 2 * DISCO_MAX_CLS; ++attempt) {
-        u64 m = s_cls[lane];
-        u64 hit = __ballot(m == mask);
-        if (hit) return __ffsll((long long)hit) - 1;
-        m = __hip_atomic_load(&tl->cls_mask[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_cls[lane] = m;
-        hit = __ballot(m == mask);
-        if (hit) return __ffsll((long long)hit) - 1;
-        const u64 free = __ballot(m == 0ull);
-        if (!free) return -1;
-        const int e = __ffsll((long long)free) - 1;
-        unsigned long long old = 0ull;
-        if (lane == 0) old = atomicCAS((unsigned long long*)&tl->cls_mask[e], 0ull, (unsigned long long)mask);
-        old = (unsigned long long)bcast_u64((u64)old, 0);
-        if (old == 0ull || old == (unsigned long long)mask) {
-            if (lane == 0) s_cls[e] = mask;
-            return e;
-        }
-    }
-    return -1;
-}
-
 // Index of `mask` in a workgroup's copy of the class table (lane-private
 // search over `ncls` entries), -1 if absent.
 __device__ __forceinline__ int cls_find(const u64* s_cls, int ncls, u64 mask)

@@ -53,33 +53,75 @@ __device__ void tbt_plan_next(SelState* S, int P, int nq)
     tl.shift = tl.left - w;
 }
 
-// Column sets of every request -> classes.  The distinct sets of a workgroup
-// are first collected in LDS and then claimed in the device-wide table by one
-// wave, so the few hot table lines are touched once per workgroup; the last
-// workgroup numbers the classes that need a token walk and plans the first
-// histogram pass.  Also clears the length counts and the device-wide bins.
-__global__ __launch_bounds__(256) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
-                                                     float tau, SelState* S, unsigned* ppcnt, unsigned* ghist,
+// Inserts the column sets held by the lanes of a wave (0 = none) into a
+// workgroup's LDS table `loc` (entries are claimed in order, so the table is
+// dense) and records in `loc_walk` which entries have a member that needs a
+// token walk.  Common case, lane-private: the set is among the entries this
+// wave has already seen (`tab`: lane e holds entry e) and so is its walk flag;
+// only new sets or flags go through the cooperative insertion.
+struct WaveTable { u64 tab; int nknown; u64 seen_walk; };
+
+constexpr int CL_BLOCK = 1024;              // classification: 16 waves share one LDS table, few tables to merge
+
+__device__ __forceinline__ void insert_sets(u64 m, bool walked, u64* loc, u64* loc_walk, int* overflow, WaveTable& w, int lane)
+{
+    const volatile u64* vloc = loc;
+    int c = -1;
+    for (int e = 0; e < w.nknown; ++e) c = (bcast_u64(w.tab, e) == m) ? e : c;
+    const bool todo = m != 0ull && (c < 0 || (walked && !((w.seen_walk >> c) & 1ull)));
+    u64 pend = __ballot(todo);
+    while (pend) {
+        const int leader = __ffsll((long long)pend) - 1;
+        const u64 m0 = bcast_u64(m, leader);
+        const u64 same = __ballot(todo && m == m0);
+        const bool wk = __ballot(todo && m == m0 && walked) != 0ull;
+        pend &= ~same;
+        int e = -1;
+        for (int attempt = 0; attempt < DISCO_MAX_CLS + 1 && e < 0; ++attempt) {
+            const u64 cur = vloc[lane];
+            const u64 hit = __ballot(cur == m0);
+            if (hit) { e = __ffsll((long long)hit) - 1; break; }
+            const u64 free = __ballot(cur == 0ull);
+            if (!free) { if (lane == 0) *overflow = 1; break; }
+            const int f = __ffsll((long long)free) - 1;
+            if (lane == 0) atomicCAS((unsigned long long*)&loc[f], 0ull, (unsigned long long)m0);
+        }
+        if (e >= 0 && wk) {
+            if (lane == 0) atomicOr((unsigned long long*)loc_walk, 1ull << e);
+            w.seen_walk |= 1ull << e;
+        }
+        w.tab = vloc[lane];
+        w.nknown = __popcll(__ballot(w.tab != 0ull));
+    }
+}
+
+// Column sets of every request -> classes.  Every workgroup collects its
+// distinct sets in LDS and stores that table; the last workgroup merges the
+// tables (a device-wide table claimed with atomics made a thousand workgroups
+// queue up on a few cache lines), numbers the classes that need a token walk
+// and plans the first histogram pass.  Also clears the length counts and the
+// device-wide bins.
+//   parts: gridDim.x x (DISCO_MAX_CLS + 2) words of scratch
+__global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
+                                                     float tau, SelState* S, unsigned* ppcnt, unsigned* ghist, u64* parts,
                                                      unsigned* ticket)
 {
     __shared__ disco_policy sp[DISCO_MAX_COLS];
     __shared__ u64 loc[DISCO_MAX_CLS];
-    __shared__ u64 s_cls[DISCO_MAX_CLS];
     __shared__ u64 loc_walk;
     __shared__ int overflow;
     if ((int)threadIdx.x < P) sp[threadIdx.x] = pol[threadIdx.x];
-    if (threadIdx.x < DISCO_MAX_CLS) { loc[threadIdx.x] = 0ull; s_cls[threadIdx.x] = 0ull; }
+    if (threadIdx.x < DISCO_MAX_CLS) loc[threadIdx.x] = 0ull;
     if (threadIdx.x == 0) { overflow = 0; loc_walk = 0ull; }
-    for (i64 w = (i64)blockIdx.x * 256 + threadIdx.x; w < (i64)DISCO_MAX_CLS * (DISCO_PP_NMAX + 1); w += (i64)gridDim.x * 256)
+    for (i64 w = (i64)blockIdx.x * CL_BLOCK + threadIdx.x; w < (i64)DISCO_MAX_CLS * (DISCO_PP_NMAX + 1); w += (i64)gridDim.x * CL_BLOCK)
         ppcnt[w] = 0u;
-    for (i64 w = (i64)blockIdx.x * 256 + threadIdx.x; w < (i64)DISCO_GHIST_WORDS; w += (i64)gridDim.x * 256) ghist[w] = 0u;
+    for (i64 w = (i64)blockIdx.x * CL_BLOCK + threadIdx.x; w < (i64)DISCO_GHIST_WORDS; w += (i64)gridDim.x * CL_BLOCK) ghist[w] = 0u;
     __syncthreads();
-    const int lane = threadIdx.x & 63;
-    const volatile u64* vloc = loc;
-    u64 seen = 0ull, seen_walk = 0ull;        // lane e: entry e of the workgroup's table as last read; walk flags set by this wave
-    const i64 nround = (tr.n_req + 255) / 256;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    WaveTable wt{0ull, 0, 0ull};
+    const i64 nround = (tr.n_req + CL_BLOCK - 1) / CL_BLOCK;
     for (i64 rnd = blockIdx.x; rnd < nround; rnd += gridDim.x) {
-        const i64 i = rnd * 256 + threadIdx.x;
+        const i64 i = rnd * CL_BLOCK + threadIdx.x;
         u64 m[3] = {0ull, 0ull, 0ull};
         bool walked[3] = {false, false, false};
         if (i < tr.n_req) {
@@ -94,65 +136,36 @@ __global__ __launch_bounds__(256) void k_tl_classify(TraceView tr, const disco_p
             walked[1] = walked[2] = !(short_n && pure_pacing(tr.arr == nullptr, gap, tau));
         }
 #pragma unroll
-        for (int kind = 0; kind < 3; ++kind) {
-            u64 pend = __ballot(m[kind] != 0ull);
-            while (pend) {
-                const int leader = __ffsll((long long)pend) - 1;
-                const u64 m0 = bcast_u64(m[kind], leader);
-                const u64 same = __ballot(m[kind] == m0);
-                const bool wk = __ballot(m[kind] == m0 && walked[kind]) != 0ull;
-                pend &= ~same;
-                // what this wave already knows to be in the workgroup's table needs no LDS traffic
-                const u64 known = __ballot(seen == m0);
-                if (known) {
-                    const int e0 = __ffsll((long long)known) - 1;
-                    if (!wk || ((seen_walk >> e0) & 1ull)) continue;
-                }
-                int e = -1;
-                for (int attempt = 0; attempt < DISCO_MAX_CLS + 1 && e < 0; ++attempt) {   // insert m0 into the workgroup's table
-                    const u64 cur = vloc[lane];
-                    const u64 hit = __ballot(cur == m0);
-                    if (hit) { e = __ffsll((long long)hit) - 1; seen = cur; break; }
-                    const u64 free = __ballot(cur == 0ull);
-                    if (!free) { if (lane == 0) overflow = 1; break; }
-                    const int f = __ffsll((long long)free) - 1;
-                    if (lane == 0) atomicCAS((unsigned long long*)&loc[f], 0ull, (unsigned long long)m0);
-                }
-                if (e >= 0 && wk) {
-                    if (lane == 0) atomicOr((unsigned long long*)&loc_walk, 1ull << e);
-                    seen_walk |= 1ull << e;
-                }
-            }
-        }
+        for (int kind = 0; kind < 3; ++kind) insert_sets(m[kind], walked[kind], loc, &loc_walk, &overflow, wt, lane);
     }
     __syncthreads();
-    if (threadIdx.x < 64) {
-        u64 mine = __ballot(loc[lane] != 0ull);
-        const u64 lw = loc_walk;
-        bool bad = overflow != 0;
-        u64 wbits = 0ull;
-        while (mine) {
-            const int e = __ffsll((long long)mine) - 1;
-            mine &= mine - 1;
-            const int c = cls_lookup(loc[e], s_cls, &S->tl, lane);
-            if (c < 0) bad = true;
-            else if ((lw >> e) & 1ull) wbits |= 1ull << c;
-        }
-        // one atomic per workgroup, and none once the bits are known to be set (every workgroup sees the same few classes)
-        if (lane == 0 && wbits) {
-            const u64 cur = __hip_atomic_load(&S->tl.walk_mask, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((cur & wbits) != wbits) atomicOr((unsigned long long*)&S->tl.walk_mask, (unsigned long long)wbits);
-        }
-        if (bad && lane == 0) S->tl.error = 1;
-    }
+    u64* mine = parts + (size_t)blockIdx.x * (DISCO_MAX_CLS + 2);
+    if (threadIdx.x < DISCO_MAX_CLS) mine[threadIdx.x] = loc[threadIdx.x];
+    if (threadIdx.x == 0) { mine[DISCO_MAX_CLS] = loc_walk; mine[DISCO_MAX_CLS + 1] = (u64)overflow; }
     if (!take_last_ticket(ticket)) return;
+    // last workgroup: merge the tables of all workgroups with the same insertion
+    __syncthreads();
+    if (threadIdx.x < DISCO_MAX_CLS) loc[threadIdx.x] = 0ull;
+    if (threadIdx.x == 0) loc_walk = 0ull;
+    __syncthreads();
+    wt = WaveTable{0ull, 0, 0ull};
+    for (unsigned b = wave; b < gridDim.x; b += CL_BLOCK / 64) {
+        const u64* part = parts + (size_t)b * (DISCO_MAX_CLS + 2);
+        const u64 m = part[lane];
+        const u64 wbits = part[DISCO_MAX_CLS];
+        if (part[DISCO_MAX_CLS + 1] != 0ull && lane == 0) overflow = 1;
+        insert_sets(m, (wbits >> lane) & 1ull, loc, &loc_walk, &overflow, wt, lane);
+    }
+    __syncthreads();
+    TlSel& tl = S->tl;
+    if (threadIdx.x < DISCO_MAX_CLS) tl.cls_mask[threadIdx.x] = loc[threadIdx.x];
     if (threadIdx.x == 0) {
-        TlSel& tl = S->tl;
         int n = 0;
         for (int k = 0; k < DISCO_MAX_CLS; ++k)
-            if (__hip_atomic_load(&tl.cls_mask[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0ull) n = k + 1;
+            if (loc[k] != 0ull) n = k + 1;
         tl.ncls = n > 0 ? n : 1;
-        const u64 wm = __hip_atomic_load(&tl.walk_mask, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const u64 wm = loc_walk;
+        tl.walk_mask = wm;
         int nw = 0;
         for (int k = 0; k < DISCO_MAX_CLS; ++k) {
             tl.slot_cls[k] = 0;
@@ -160,7 +173,8 @@ __global__ __launch_bounds__(256) void k_tl_classify(TraceView tr, const disco_p
             else tl.cls_slot[k] = -1;
         }
         tl.nwalk = nw;
-        if (__hip_atomic_load(&tl.error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) { tl.fallback = 1; tl.error = 0; }
+        tl.error = 0;
+        if (overflow) tl.fallback = 1;                 // more than DISCO_MAX_CLS distinct sets: per-slot histograms
         // gaps sit just above the pacing interval (down to a few thousand ulps below it after rounding): try a
         // 21-bit window of keys first
         const unsigned tb = f2u(tau);
@@ -198,16 +212,14 @@ __global__ __launch_bounds__(1024) void k_pp_suffix(SelState* S, unsigned* ppcnt
     }
 }
 
-// After a TBT histogram pass, step 1 (workgroup = class): add the analytic
-// bins of the class's pure-pacing timelines to its device-wide rows.
-// ppcnt[c][t] timelines of class c have a token t, and the gap in front of it
-// is the same number for all of them.
-__global__ __launch_bounds__(1024) void k_tbt_analytic(SelState* S, unsigned* ghist, const unsigned* ppcnt, float tau)
+// After a TBT histogram pass, step 1 (all threads of a workgroup, class c):
+// add the analytic bins of the class's pure-pacing timelines to its
+// device-wide rows.  ppcnt[c][t] timelines of class c have a token t, and the
+// gap in front of it is the same number for all of them.
+__device__ void analytic_class(SelState* S, unsigned* ghist, const unsigned* ppcnt, float tau, int c, unsigned* lds)
 {
-    __shared__ unsigned lds[DISCO_TL_HIST_WORDS];
     const TlSel& tl = S->tl;
-    const int width = tl.width, ncls = tl.ncls, c = blockIdx.x;
-    if (width <= 0 || tl.fallback || c >= ncls) return;
+    const int width = tl.width, ncls = tl.ncls;
     const unsigned* row = ppcnt + (size_t)c * (DISCO_PP_NMAX + 1);
     if (row[0] == 0u) return;                             // no pure-pacing timeline in this class (uniform)
     const int Gused = tl.G < DISCO_MAX_GRP ? tl.G : DISCO_MAX_GRP;
@@ -215,6 +227,7 @@ __global__ __launch_bounds__(1024) void k_tbt_analytic(SelState* S, unsigned* gh
     const int words = Gused << width;
     const int shift = tl.shift, up = tl.shift + width;
     const unsigned key_cap = tl.window ? (1u << tl.window) : 0xFFFFFFFFu;
+    __syncthreads();
     for (int i = threadIdx.x; i < words; i += blockDim.x) lds[i] = 0u;
     __syncthreads();
     for (int t = 1 + (int)threadIdx.x; t < DISCO_PP_NMAX; t += blockDim.x) {
@@ -233,26 +246,21 @@ __global__ __launch_bounds__(1024) void k_tbt_analytic(SelState* S, unsigned* gh
     }
 }
 
-// Step 2 (workgroup = (column, quantile) slot): add up the class histograms
-// of the classes that contain the slot's column (or take the slot's own
-// histogram in the fallback), walk to the digit that holds the remaining
-// rank, extend the prefix.
-__global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const unsigned* ghist)
+// Step 2 (all threads of a workgroup, (column, quantile) slot s): add up the
+// class histograms of the classes that contain the slot's column (or take the
+// slot's own histogram in the fallback), walk to the digit that holds the
+// remaining rank, extend the prefix.
+__device__ void select_slot(SelState* S, int nq, const unsigned* ghist, int s, u64* wsum /* LDS, 16 */, int* s_digit, u64* s_rem)
 {
-    __shared__ u64 wsum[4];
-    __shared__ int s_digit;
-    __shared__ u64 s_rem;
     const TlSel& tl = S->tl;
     const int width = tl.width, ncls = tl.ncls, fallback = tl.fallback;
-    const int s = blockIdx.x;
-    if (width <= 0) return;
     SelSlot sl = S->slot[1][s];
     const int g = tl.slot_grp[s];
-    if (sl.done || g < 0) return;
+    if (sl.done || g < 0) return;                         // uniform
     const int col = s / nq;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nbins = 1 << width;
-    const int per = (nbins + 255) >> 8;                   // consecutive bins per thread (<= 64)
+    const int per = (nbins + (int)blockDim.x - 1) / (int)blockDim.x;      // consecutive bins per thread
     const int b0 = threadIdx.x * per;
     auto bin_count = [&](int b) -> u64 {
         if (fallback) return ghist[((size_t)s << width) | b];
@@ -270,15 +278,15 @@ __global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const u
         unsigned hi = (unsigned)__shfl_up((int)(unsigned)(incl >> 32), d, 64);
         if (lane >= d) incl += ((u64)hi << 32) | lo;
     }
+    __syncthreads();
     if (lane == 63) wsum[wave] = incl;
-    if (threadIdx.x == 0) s_digit = -1;
+    if (threadIdx.x == 0) *s_digit = -1;
     __syncthreads();
     u64 before = 0;
     for (int w = 0; w < wave; ++w) before += wsum[w];
     incl += before;
     const u64 k = (u64)sl.k_rem;
-    // the rank never exceeds the number of matching values: exactly one thread sees it fall into its bins
-    if (incl >= k && incl - mine < k) {
+    if (incl >= k && incl - mine < k) {                   // at most one thread: the rank falls into its bins
         u64 rem = k - (incl - mine);
         int dsel = b0;
         for (int b = b0; b < b0 + per && b < nbins; ++b) {
@@ -287,13 +295,13 @@ __global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const u
             if (rem <= c) break;
             rem -= c;
         }
-        s_digit = dsel;
-        s_rem = rem;
+        *s_digit = dsel;
+        *s_rem = rem;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int dsel = s_digit;
-        u64 rem = s_rem;
+        int dsel = *s_digit;
+        u64 rem = *s_rem;
         // window mode: a rank beyond the counted keys, or in the bottom bin (which also holds the keys below the
         // window), is not decided here -> start over on raw keys.  Raw keys: the rank is always found.
         if (tl.window && (dsel < 0 || (dsel == 0 && tl.left == tl.window))) S->tl.restart = 1;
@@ -305,13 +313,13 @@ __global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const u
 }
 
 // Step 3 (one workgroup): clear the bins that were used and plan the next pass.
-__global__ __launch_bounds__(1024) void k_tbt_plan(SelState* S, int P, int nq, unsigned* ghist)
+__device__ void plan_pass(SelState* S, int P, int nq, unsigned* ghist)
 {
     TlSel& tl = S->tl;
     const int width = tl.width;
-    if (width <= 0) return;
     const int Gused = tl.G < DISCO_MAX_GRP ? tl.G : DISCO_MAX_GRP;
     const int words = (tl.fallback ? P * nq : Gused * tl.ncls) << width;
+    __syncthreads();
     for (int i = threadIdx.x; i < words; i += blockDim.x) ghist[i] = 0u;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -331,22 +339,73 @@ __global__ __launch_bounds__(1024) void k_tbt_plan(SelState* S, int P, int nq, u
     }
 }
 
+__global__ __launch_bounds__(1024) void k_tbt_analytic(SelState* S, unsigned* ghist, const unsigned* ppcnt, float tau)
+{
+    __shared__ unsigned lds[DISCO_TL_HIST_WORDS];
+    const TlSel& tl = S->tl;
+    if (tl.width <= 0 || tl.fallback || (int)blockIdx.x >= tl.ncls) return;
+    analytic_class(S, ghist, ppcnt, tau, blockIdx.x, lds);
+}
+
+__global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const unsigned* ghist)
+{
+    __shared__ u64 wsum[16];
+    __shared__ int s_digit;
+    __shared__ u64 s_rem;
+    if (S->tl.width <= 0) return;
+    select_slot(S, nq, ghist, blockIdx.x, wsum, &s_digit, &s_rem);
+}
+
+__global__ __launch_bounds__(1024) void k_tbt_plan(SelState* S, int P, int nq, unsigned* ghist)
+{
+    if (S->tl.width <= 0) return;
+    plan_pass(S, P, nq, ghist);
+}
+
+// The three steps in one workgroup: for the launches after the passes that
+// normally finish the selection (they return at once unless the window was
+// missed or the digits are narrow), where one launch instead of three matters
+// more than speed.
+__global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, int nq, unsigned* ghist, const unsigned* ppcnt,
+                                                          float tau)
+{
+    __shared__ unsigned lds[DISCO_TL_HIST_WORDS];
+    __shared__ u64 wsum[16];
+    __shared__ int s_digit;
+    __shared__ u64 s_rem;
+    const TlSel& tl = S->tl;
+    if (tl.width <= 0) return;
+    if (!tl.fallback)
+        for (int c = 0; c < tl.ncls; ++c) analytic_class(S, ghist, ppcnt, tau, c, lds);
+    __syncthreads();
+    for (int s = 0; s < P * nq; ++s) {
+        select_slot(S, nq, ghist, s, wsum, &s_digit, &s_rem);
+        __syncthreads();
+    }
+    plan_pass(S, P, nq, ghist);
+}
+
 }  // namespace
 
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
-                              unsigned* ppcnt, unsigned* ghist, unsigned* ticket, hipStream_t stream)
+                              unsigned* ppcnt, unsigned* ghist, u64* parts, unsigned* ticket, hipStream_t stream)
 {
-    i64 b = (v.n_req + 255) / 256;
+    i64 b = (v.n_req + CL_BLOCK - 1) / CL_BLOCK;
     if (b < 1) b = 1;
-    if (b > 1024) b = 1024;
-    hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(256), 0, stream, v, pol, P, nq, tau, S, ppcnt, ghist, ticket);
+    if (b > 256) b = 256;
+    hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau, S, ppcnt, ghist, parts,
+                       ticket);
 }
 
 void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,
                               hipStream_t stream)
 {
     if (pass == 0) hipLaunchKernelGGL(k_pp_suffix, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ppcnt);
-    hipLaunchKernelGGL(k_tbt_analytic, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ghist, ppcnt, tau);
-    hipLaunchKernelGGL(k_tbt_select, dim3((unsigned)(P * nq)), dim3(256), 0, stream, S, nq, ghist);
-    hipLaunchKernelGGL(k_tbt_plan, dim3(1), dim3(1024), 0, stream, S, P, nq, ghist);
+    if (pass < 2) {
+        hipLaunchKernelGGL(k_tbt_analytic, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ghist, ppcnt, tau);
+        hipLaunchKernelGGL(k_tbt_select, dim3((unsigned)(P * nq)), dim3(256), 0, stream, S, nq, ghist);
+        hipLaunchKernelGGL(k_tbt_plan, dim3(1), dim3(1024), 0, stream, S, P, nq, ghist);
+    } else {
+        hipLaunchKernelGGL(k_tbt_advance_one, dim3(1), dim3(1024), 0, stream, S, P, nq, ghist, ppcnt, tau);
+    }
 }

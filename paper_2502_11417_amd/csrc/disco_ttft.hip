@@ -2,7 +2,7 @@
 // level): most-significant-digit-first radix selection over
 // key = bits(TTFT) - min_bits, 8 bits per pass.
 //
-// Two histogram kernels; which one acts is decided on the device.
+// Two kinds of histogram workgroups in one launch; which kind acts is decided on the device.
 //
 //   class kernel -- every column is a length-threshold column (Alg. 3).  With
 //     the thresholds in ascending order t_0 <= ... <= t_{P-1} a request of
@@ -53,9 +53,9 @@ __device__ __forceinline__ PassDigit pass_digit(const SelGlobal& g, int pass)
     return d;
 }
 
-__device__ __forceinline__ void store_slice(const unsigned* hist, int rows, int width, unsigned* __restrict__ slices)
+__device__ __forceinline__ void store_slice(const unsigned* hist, int rows, int width, unsigned* __restrict__ slices, int bid)
 {
-    unsigned* mine = slices + (size_t)blockIdx.x * ((size_t)rows << width);
+    unsigned* mine = slices + (size_t)bid * ((size_t)rows << width);
     const int dmask = (1 << width) - 1;
     for (int i = threadIdx.x; i < rows << width; i += DP_BLOCK) mine[i] = hist[(i >> width) * TH_STRIDE + (i & dmask)];
 }
@@ -66,12 +66,10 @@ __device__ __forceinline__ void store_slice(const unsigned* hist, int rows, int 
 // prefix of a (column, quantile) slot bumps that slot's bin.  Pass 0: one row
 // per column (all quantiles share it).
 template <int G>
-__global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
-                                                        int pass, const SelState* S, unsigned* __restrict__ slices)
+__device__ __forceinline__ void pair_body(const TraceView& tr, const disco_policy* __restrict__ pol, int P, int nq, int pass,
+                                          const SelState* S, unsigned* __restrict__ slices, unsigned* hist, Staged* stage,
+                                          int bid, int nblk)
 {
-    __shared__ unsigned hist[TH_WORDS];
-    __shared__ __align__(16) Staged stage[DP_BLOCK];
-    if (S->tc.on) return;                               // the class kernel acts
     const SelGlobal g = S->g[0];
     const PassDigit dg = pass_digit(g, pass);
     if (dg.width <= 0) return;
@@ -100,7 +98,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disc
     // the pair evaluation is specialised on the kind of table (all Alg. 3, all Alg. 2, mixed)
     auto run = [&](auto mode_c) {
         constexpr int MODE = decltype(mode_c)::value;
-        for (i64 b = (i64)blockIdx.x * DP_WAVES + wave; b < nbatch; b += (i64)gridDim.x * DP_WAVES) {
+        for (i64 b = (i64)bid * DP_WAVES + wave; b < nbatch; b += (i64)nblk * DP_WAVES) {
             const i64 i = b * 64 + lane;
             const bool v = i < tr.n_req;
             const int lv = v ? tr.l[i] : 0;
@@ -136,7 +134,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disc
     else if (mode == 1) run(std::integral_constant<int, 1>{});
     else run(std::integral_constant<int, 2>{});
     __syncthreads();
-    store_slice(hist, nslot, width, slices);
+    store_slice(hist, nslot, width, slices, bid);
 }
 
 // ----------------------------------------------------------- class kernel --
@@ -155,12 +153,9 @@ struct ClsTables {
     unsigned char col_of_pos[DISCO_MAX_COLS];
 };
 
-__global__ __launch_bounds__(DP_BLOCK) void k_ttft_cls(TraceView tr, int P, int nq, int pass, const SelState* S,
-                                                       unsigned* __restrict__ slices)
+__device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int pass, const SelState* S,
+                                         unsigned* __restrict__ slices, unsigned* hist, ClsTables& T, int bid, int nblk)
 {
-    __shared__ unsigned hist[TH_WORDS];
-    __shared__ ClsTables T;
-    if (!S->tc.on) return;                              // the pair kernel acts
     const SelGlobal g = S->g[0];
     const PassDigit dg = pass_digit(g, pass);
     if (dg.width <= 0) return;
@@ -216,7 +211,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_cls(TraceView tr, int P, int 
     }
     __syncthreads();
     const int ndist = pass > 0 ? T.ndist : 0;
-    for (i64 i = (i64)blockIdx.x * DP_BLOCK + t; i < tr.n_req; i += (i64)gridDim.x * DP_BLOCK) {
+    for (i64 i = (i64)bid * DP_BLOCK + t; i < tr.n_req; i += (i64)nblk * DP_BLOCK) {
         const int l = tr.l[i];
         const float s = tr.s[i];
         const float k = tr.k ? tr.k[i] : tr.k_s;
@@ -259,7 +254,23 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_cls(TraceView tr, int P, int 
         }
     }
     __syncthreads();
-    store_slice(hist, rows, width, slices);
+    store_slice(hist, rows, width, slices, bid);
+}
+
+// One launch for both histogram kernels: workgroups [0, ncls_blocks) are the class kernel, the rest the pair
+// kernel; the ones whose kind does not apply to the table return at once.
+template <int G>
+__global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
+                                                        int pass, const SelState* S, unsigned* __restrict__ slices,
+                                                        int ncls_blocks)
+{
+    __shared__ unsigned hist[TH_WORDS];
+    __shared__ __align__(16) Staged stage[DP_BLOCK];
+    __shared__ ClsTables T;
+    const bool cls_block = (int)blockIdx.x < ncls_blocks;
+    if (cls_block != (S->tc.on != 0)) return;
+    if (cls_block) cls_body(tr, P, nq, pass, S, slices, hist, T, blockIdx.x, ncls_blocks);
+    else pair_body<G>(tr, pol, P, nq, pass, S, slices, hist, stage, (int)blockIdx.x - ncls_blocks, (int)gridDim.x - ncls_blocks);
 }
 
 // ------------------------------------------------------ reduce and select --
@@ -344,10 +355,10 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
 }
 
 template <int G>
-void launch_pair(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S, unsigned* slices,
-                 unsigned blocks, hipStream_t stream)
+void launch_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S, unsigned* slices,
+                 unsigned bp, unsigned bc, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_ttft_hist<G>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, P, nq, pass, S, slices);
+    hipLaunchKernelGGL(k_ttft_hist<G>, dim3(bc + bp), dim3(DP_BLOCK), 0, stream, v, pol, P, nq, pass, S, slices, (int)bc);
 }
 
 }  // namespace
@@ -363,15 +374,14 @@ void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, 
     if (bc > TC_MAX_BLOCKS) bc = TC_MAX_BLOCKS;
     int g = 1;
     while (g < P) g <<= 1;
-    hipLaunchKernelGGL(k_ttft_cls, dim3((unsigned)bc), dim3(DP_BLOCK), 0, stream, v, P, nq, pass, S, slices);
     switch (g) {
-    case 1: launch_pair<1>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
-    case 2: launch_pair<2>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
-    case 4: launch_pair<4>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
-    case 8: launch_pair<8>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
-    case 16: launch_pair<16>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
-    case 32: launch_pair<32>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
-    default: launch_pair<64>(v, pol, P, nq, pass, S, slices, (unsigned)bp, stream); break;
+    case 1: launch_hist<1>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
+    case 2: launch_hist<2>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
+    case 4: launch_hist<4>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
+    case 8: launch_hist<8>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
+    case 16: launch_hist<16>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
+    case 32: launch_hist<32>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
+    default: launch_hist<64>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
     }
     const int rows_pair = pass == 0 ? P : P * nq, rows_cls = pass == 0 ? 2 * (P + 1) : P * nq;
     const int rows_max = rows_pair > rows_cls ? rows_pair : rows_cls;
