@@ -26,12 +26,14 @@
  *   dispatch          zero budget / full budget / long wait special cases
  *   max-plus pacing   O(n^2) brute force in exact rational arithmetic
  *   LAG migration     constructed single-stall cases + closed-form tail
+ *   buffer migration  constant-gap closed forms (hand-off index, delayed tokens), sequential
+ *                     buffer simulation in exact rational arithmetic, cost-condition breakpoints
  *   quantile          numpy sort + nearest rank
  *   budget search     sort + prefix-sum solve; breakpoint enumeration
  * parity unpinned (conventions the paper does not fix; both sides follow the
  * same written reading): exchange rate lambda, pacing interval, budget-level
  * grid, tie-breaks, charging of a terminated loser, migration overhead time,
- * definition of "server lag".
+ * definition of "server lag", arrival process of the target after a buffer hand-off.
  */
 #include <math.h>
 #include <stdint.h>
@@ -417,26 +419,99 @@ void orc_timeline(int32_t n, const float* r_srv, float gap_const, int32_t src_is
     *t_last = prev;
 }
 
+/* Buffer-based, cost-triggered migration (Sec. 4.3, "Theoretical Migration
+ * Framework" and "Buffer-Based Migration Protocol").  The constrained
+ * endpoint produced the first token; decoding is handed to the other endpoint
+ * as soon as (a) the buffer holds enough undelivered tokens to hide the
+ * hand-off, B = r_c t_m tokens of playback, i.e. the playback time ahead of
+ * the newest token covers the migration time:  delta_t - r_t >= t_mig(t)
+ * (the rounding-free form of "buffer contains B tokens"), and (b) the decode
+ * cost saved on the remaining tokens exceeds the overhead of prefilling the
+ * target:  dc (n - 1 - t) > cp (l + t + 1)  (C_migration > Overhead).
+ * The source stops after token m = the first such t; the target re-prefills
+ * the prompt plus the m + 1 tokens produced so far (token ids only) and
+ * delivers token m + 1 one gap after its prefill:
+ *   t_mig(t)  device target: k (l + t + 1) + c;  server target: its TTFT s
+ *   base      r_m + t_mig(m)
+ *   r'_t      device: base + (t - m) g_dev;  server with a token trace:
+ *             base + (r^S_t - r^S_m);  server with a constant gap:
+ *             base + (t - m) gap_srv                            for t > m.
+ * delay_num = number of tokens after the hand-off that reach the user later
+ * than one pacing interval after their predecessor (TBT_t > tau).
+ * Outputs: mig_last = m (-1 none), delay_num, t_last; nullable delivered, tbt. */
+void orc_timeline_buffer(int32_t n, const float* r_srv, float gap_srv, int32_t src_is_device,
+                         double dc, double cp, float srv_ttft, float tau, int32_t l, float k, float c,
+                         float g_dev, int32_t* mig_last, int32_t* delay_num, float* t_last,
+                         float* delivered, float* tbt)
+{
+    float M = 0.0f, prev = 0.0f, base = 0.0f, r_m = 0.0f;
+    int32_t m = -1, delayed = 0;
+    for (int32_t t = 0; t < n; ++t) {
+        float r;
+        if (m >= 0) {
+            if (src_is_device) {                        /* target = server */
+                if (r_srv) { float since = r_srv[t] - r_m; r = base + since; }
+                else r = fmaf((float)(t - m), gap_srv, base);
+            } else {
+                r = fmaf((float)(t - m), g_dev, base);
+            }
+        } else if (src_is_device) r = (float)t * g_dev;
+        else if (r_srv) r = r_srv[t];
+        else r = (float)t * gap_srv;
+        float u = fmaf(-(float)t, tau, r);
+        if (t == 0 || u > M) M = u;
+        float del = fmaf((float)t, tau, M);
+        if (delivered) delivered[t] = del;
+        if (t >= 1) {
+            float gap = del - prev;
+            if (tbt) tbt[t - 1] = gap;
+            if (m >= 0 && gap > tau) delayed += 1;
+        }
+        if (m < 0 && t + 1 < n) {
+            float slack = del - r;
+            float t_mig = src_is_device ? srv_ttft : fmaf((float)(l + t + 1), k, c);
+            double saved = dc * (double)(n - 1 - t);
+            double overhead = cp * (double)(l + t + 1);
+            if (slack >= t_mig && saved > overhead) {
+                m = t;
+                base = r + t_mig;
+                r_m = (src_is_device && r_srv) ? r_srv[t] : 0.0f;
+            }
+        }
+        prev = del;
+    }
+    *mig_last = m;
+    *delay_num = delayed;
+    *t_last = prev;
+}
+
 /* All pairs: each pair's source is the dispatch winner; timelines are
- * recomputed per pair (no sharing between columns).  Per pair [P][N]
- * (nullable): mig_idx, n_src_tok (tokens produced by the source), t_last.
- * Per column: mtok[j] = {server decode tokens, device decode tokens, device
- * re-prefill tokens}, cnt[j] = {migrated requests, number of TBT values},
- * tlast_sum[j].  If tbt_col >= 0 the TBT values of that column are written
- * to tbt_out (request order, token order), and delivered_out (indexed like
- * the token array) receives its delivery offsets. */
+ * recomputed per pair (no sharing between columns).  mig_mode 1: lag hand-off
+ * (server source).  mig_mode 2: buffer hand-off when the source is the
+ * constrained endpoint of the column (mode 0: server -> device, price
+ * difference dc = cs_dec - lambda e_dec, target prefill price cp = lambda
+ * e_pre; mode 1: device -> server, dc = lambda e_dec - cs_dec, cp = cs_pre);
+ * `rates` = {cs_pre, cs_dec, e_pre, e_dec, lambda} (needed for mode 2 only).
+ * Per pair [P][N] (nullable): mig_idx (index of the first token produced by
+ * the target, -1 none), n_src_tok (tokens produced by the source), t_last,
+ * delay_num.  Per column: mtok[j] = {server decode tokens, device decode
+ * tokens, device re-prefill tokens, server re-prefill tokens}, cnt[j] =
+ * {migrated requests, number of TBT values, sum of delay_num}, tlast_sum[j].
+ * If tbt_col >= 0 the TBT values of that column are written to tbt_out
+ * (request order, token order), and delivered_out (indexed like the token
+ * array) receives its delivery offsets. */
 void orc_migration(int64_t N, int32_t P, const int32_t* prompt_len, const float* srv_ttft,
                    const int32_t* output_len, const float* srv_tbt,
                    const float* dev_pre_spt, float dev_pre_spt_s,
                    const float* dev_dec_spt, float dev_dec_spt_s, float dev_ttft_c,
                    const int64_t* tok_off, const float* tok_arr,
-                   const orc_policy* pol, float tau, float kappa,
-                   int32_t* mig_idx, int32_t* n_src_tok, float* t_last,
+                   const orc_policy* pol, float tau, float kappa, const double* rates,
+                   int32_t* mig_idx, int32_t* n_src_tok, float* t_last, int32_t* delay_num,
                    int64_t* mtok, int64_t* cnt, double* tlast_sum,
                    int32_t tbt_col, float* tbt_out, float* delivered_out)
 {
     for (int32_t j = 0; j < P; ++j) {
-        int64_t s_dec = 0, d_dec = 0, d_repre = 0, migrated = 0, n_tbt = 0;
+        int64_t s_dec = 0, d_dec = 0, d_repre = 0, s_repre = 0, migrated = 0, n_tbt = 0, delay_sum = 0;
         double sum = 0.0;
         int64_t tbt_pos = 0, run_off = 0;
         for (int64_t i = 0; i < N; ++i) {
@@ -449,16 +524,32 @@ void orc_migration(int64_t N, int32_t P, const int32_t* prompt_len, const float*
             int32_t src_dev = (dec & 4) ? 1 : 0;
             const float* r = (tok_arr && tok_off) ? tok_arr + tok_off[i] : NULL;
             int64_t off = tok_off ? tok_off[i] : run_off;
-            int32_t m; float tl;
+            int32_t m = -1, nsrc = n, delayed = 0; float tl;
             int want = (j == tbt_col);
-            orc_timeline(n, r, srv_tbt ? srv_tbt[i] : 0.0f, src_dev, pol[j].mig_mode == 1,
-                         tau, kappa, l, k, dev_ttft_c, g, &m, &tl,
-                         (want && delivered_out) ? delivered_out + off : NULL,
-                         (want && tbt_out) ? tbt_out + tbt_pos : NULL);
-            int32_t nsrc = (m >= 0) ? m : n;
-            if (src_dev) d_dec += n;
+            float* dl = (want && delivered_out) ? delivered_out + off : NULL;
+            float* tb = (want && tbt_out) ? tbt_out + tbt_pos : NULL;
+            float gap_srv = srv_tbt ? srv_tbt[i] : 0.0f;
+            int buffer = pol[j].mig_mode == 2 && rates && ((pol[j].mode == 0 && !src_dev) || (pol[j].mode == 1 && src_dev));
+            if (buffer) {
+                double dev_dec_price = rates[4] * rates[3], dev_pre_price = rates[4] * rates[2];
+                double dc = src_dev ? dev_dec_price - rates[1] : rates[1] - dev_dec_price;
+                double cp = src_dev ? rates[0] : dev_pre_price;
+                int32_t last;
+                orc_timeline_buffer(n, r, gap_srv, src_dev, dc, cp, srv_ttft[i], tau, l, k, dev_ttft_c, g,
+                                    &last, &delayed, &tl, dl, tb);
+                if (last >= 0) { m = last + 1; nsrc = last + 1; }
+            } else {
+                orc_timeline(n, r, gap_srv, src_dev, pol[j].mig_mode == 1, tau, kappa, l, k, dev_ttft_c, g,
+                             &m, &tl, dl, tb);
+                if (m >= 0) nsrc = m;
+            }
+            if (src_dev) { d_dec += nsrc; s_dec += n - nsrc; }
             else { s_dec += nsrc; d_dec += n - nsrc; }
-            if (m >= 0) { migrated += 1; d_repre += (int64_t)l + m; }
+            if (m >= 0) {
+                migrated += 1;
+                if (src_dev) s_repre += (int64_t)l + nsrc; else d_repre += (int64_t)l + nsrc;
+                delay_sum += delayed;
+            }
             n_tbt += n - 1;
             tbt_pos += n - 1;
             run_off += n;
@@ -466,9 +557,10 @@ void orc_migration(int64_t N, int32_t P, const int32_t* prompt_len, const float*
             if (mig_idx) mig_idx[(int64_t)j * N + i] = m;
             if (n_src_tok) n_src_tok[(int64_t)j * N + i] = nsrc;
             if (t_last) t_last[(int64_t)j * N + i] = tl;
+            if (delay_num) delay_num[(int64_t)j * N + i] = delayed;
         }
-        mtok[3 * j + 0] = s_dec; mtok[3 * j + 1] = d_dec; mtok[3 * j + 2] = d_repre;
-        cnt[2 * j + 0] = migrated; cnt[2 * j + 1] = n_tbt;
+        mtok[4 * j + 0] = s_dec; mtok[4 * j + 1] = d_dec; mtok[4 * j + 2] = d_repre; mtok[4 * j + 3] = s_repre;
+        cnt[3 * j + 0] = migrated; cnt[3 * j + 1] = n_tbt; cnt[3 * j + 2] = delay_sum;
         tlast_sum[j] = sum;
     }
 }

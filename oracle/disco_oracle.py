@@ -231,32 +231,51 @@ def timeline(n, r_srv, gap_const, src_is_device, lag_mode, tau, kappa, l, k, c, 
     return m.value, tl.value, delivered, tbt
 
 
+def timeline_buffer(n, r_srv, gap_srv, src_is_device, dc, cp, srv_ttft, tau, l, k, c, g_dev):
+    """One request with the buffer hand-off: (mig_last, delay_num, t_last, delivered[n], tbt[n-1])."""
+    r = None if r_srv is None else np.ascontiguousarray(r_srv, np.float32)
+    delivered = np.empty(n, np.float32)
+    tbt = np.empty(max(n - 1, 0), np.float32)
+    m = C.c_int32()
+    dn = C.c_int32()
+    tl = C.c_float()
+    lib().orc_timeline_buffer(C.c_int32(n), _ptr(r, C.c_float), C.c_float(gap_srv), C.c_int32(int(src_is_device)),
+                              C.c_double(dc), C.c_double(cp), C.c_float(srv_ttft), C.c_float(tau), C.c_int32(l),
+                              C.c_float(k), C.c_float(c), C.c_float(g_dev), C.byref(m), C.byref(dn), C.byref(tl),
+                              _ptr(delivered, C.c_float), _ptr(tbt, C.c_float))
+    return m.value, dn.value, tl.value, delivered, tbt
+
+
 def migration(tr: dict, policies, tau: float, kappa: float, materialise: bool = True,
-              tbt_col: int = -1, want_delivered: bool = False) -> dict:
+              tbt_col: int = -1, want_delivered: bool = False, cost: dict | None = None) -> dict:
+    """``cost`` (rates) is needed by columns with the buffer hand-off (mig_mode 2)."""
     a = _trace_args(tr)
     N, P = tr["n_req"], len(policies)
     mig_idx = np.empty((P, N), np.int32) if materialise else None
     n_src = np.empty((P, N), np.int32) if materialise else None
     t_last = np.empty((P, N), np.float32) if materialise else None
-    mtok = np.zeros((P, 3), np.int64)
-    cnt = np.zeros((P, 2), np.int64)
+    delay_num = np.empty((P, N), np.int32) if materialise else None
+    mtok = np.zeros((P, 4), np.int64)
+    cnt = np.zeros((P, 3), np.int64)
     tlast_sum = np.zeros(P, np.float64)
     n_total = int(np.sum(tr["output_len"], dtype=np.int64))
     tbt_out = np.empty(max(n_total - N, 0), np.float32) if tbt_col >= 0 else None
     delivered = np.empty(n_total, np.float32) if (tbt_col >= 0 and want_delivered) else None
+    rates = _rates(cost) if cost is not None else None
     lib().orc_migration(a["N"], C.c_int32(P), a["l"], a["s"], a["n"], _ptr(tr.get("srv_tbt"), C.c_float),
                         a["k"], a["ks"], _ptr(tr.get("dev_dec_spt"), C.c_float),
                         C.c_float(tr.get("dev_dec_spt_s", 0.0)), a["c"],
                         _ptr(tr.get("tok_off"), C.c_int64) if tr.get("tok_arr") is not None else None,
                         _ptr(tr.get("tok_arr"), C.c_float), _pols(policies), C.c_float(tau),
-                        C.c_float(kappa), _ptr(mig_idx, C.c_int32), _ptr(n_src, C.c_int32),
-                        _ptr(t_last, C.c_float), _ptr(mtok, C.c_int64), _ptr(cnt, C.c_int64),
-                        _ptr(tlast_sum, C.c_double), C.c_int32(tbt_col), _ptr(tbt_out, C.c_float),
-                        _ptr(delivered, C.c_float))
-    return {"mig_idx": mig_idx, "n_src_tok": n_src, "t_last": t_last,
+                        C.c_float(kappa), rates, _ptr(mig_idx, C.c_int32), _ptr(n_src, C.c_int32),
+                        _ptr(t_last, C.c_float), _ptr(delay_num, C.c_int32), _ptr(mtok, C.c_int64),
+                        _ptr(cnt, C.c_int64), _ptr(tlast_sum, C.c_double), C.c_int32(tbt_col),
+                        _ptr(tbt_out, C.c_float), _ptr(delivered, C.c_float))
+    return {"mig_idx": mig_idx, "n_src_tok": n_src, "t_last": t_last, "delay_num": delay_num,
             "m_s_dec": mtok[:, 0].copy(), "m_d_dec": mtok[:, 1].copy(), "m_d_repre": mtok[:, 2].copy(),
-            "n_migrated": cnt[:, 0].copy(), "tbt_count": cnt[:, 1].copy(), "tlast_sum": tlast_sum,
-            "tbt": tbt_out, "delivered": delivered}
+            "m_s_repre": mtok[:, 3].copy(),
+            "n_migrated": cnt[:, 0].copy(), "tbt_count": cnt[:, 1].copy(), "delay_sum": cnt[:, 2].copy(),
+            "tlast_sum": tlast_sum, "tbt": tbt_out, "delivered": delivered}
 
 
 # --------------------------------------------------------------- statistics
@@ -302,10 +321,12 @@ def stats(tr: dict, policies, cost: dict, quantiles=((50, 100), (99, 100)),
             st["ttft_rank"].append(k)
             st["ttft_q"].append(v)
         if tau is not None:
-            mg = migration(tr, [policies[j]], tau, kappa, materialise=False, tbt_col=0)
+            mg = migration(tr, [policies[j]], tau, kappa, materialise=False, tbt_col=0, cost=cost)
             st["s_dec"] = int(mg["m_s_dec"][0])
             st["d_dec"] = int(mg["m_d_dec"][0])
             st["d_pre"] += int(mg["m_d_repre"][0])
+            st["s_pre"] += int(mg["m_s_repre"][0])
+            st["delay_sum"] = int(mg["delay_sum"][0])
             st["n_migrated"] = int(mg["n_migrated"][0])
             st["tbt_count"] = int(mg["tbt_count"][0])
             st["mean_tbt"] = (float(mg["tlast_sum"][0]) / st["tbt_count"]
