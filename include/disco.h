@@ -129,6 +129,8 @@ int32_t disco_gen_trace(const disco_gen_params* params /*host*/, disco_trace* tr
 #define DISCO_MODE_DEVICE_CONSTRAINED 1   /* wait time, Sec. 4.2 Eq. 1 / Alg. 2 */
 #define DISCO_MIG_NONE 0
 #define DISCO_MIG_LAG  1                  /* hand-off to the device when a server token is overdue */
+#define DISCO_MIG_BUFFER 2                /* Sec. 4.3: the constrained endpoint hands decoding over once the token
+                                           * buffer hides the hand-off and the saving exceeds the overhead */
 
 /* One policy column (32 bytes).
  * Server-constrained: prompts with l < l_th run on the device alone, the
@@ -162,10 +164,13 @@ typedef struct disco_cost_params {
 
 /* Pacing of the token buffer (Sec. 4.3): tokens leave the buffer no faster
  * than one per `tau` seconds (the user's consumption rate r_c = 1/tau); a
- * lag hand-off fires when a token is more than kappa_lag * tau overdue. */
+ * lag hand-off fires when a token is more than kappa_lag * tau overdue.
+ * cost: host, nullable; the prices behind the buffer hand-off's cost test
+ * (columns with DISCO_MIG_BUFFER never hand off without it). */
 typedef struct disco_timeline_params {
     float tau;
     float kappa_lag;
+    const disco_cost_params* cost;
 } disco_timeline_params;
 
 /* ---- per-pair outputs and per-column accumulators ----------------------- */
@@ -180,10 +185,12 @@ typedef struct disco_pair_out {
 } disco_pair_out;
 
 /* Optional materialised timeline outputs, device; members may be NULL.
- * mig_idx [P][n_req]: index of the first token produced by the device after
- *   a hand-off, -1 if none.  n_src_tok [P][n_req]: tokens produced by the
- *   endpoint that won the first token.  t_last [P][n_req]: delivery offset of
- *   the last token since the first one.
+ * mig_idx [P][n_req]: index of the first token produced by the other
+ *   endpoint after a hand-off, -1 if none.  n_src_tok [P][n_req]: tokens
+ *   produced by the endpoint that won the first token.  t_last [P][n_req]:
+ *   delivery offset of the last token since the first one.  delay_num
+ *   [P][n_req]: tokens after a buffer hand-off that reach the user more than
+ *   tau after their predecessor (Sec. 5.2, delay_num), 0 without hand-off.
  * delivered [n_tok] (column `delivered_col` only; needs tok_off): delivery
  *   offset of every token. */
 typedef struct disco_mig_out {
@@ -193,6 +200,7 @@ typedef struct disco_mig_out {
     float* delivered;
     int32_t delivered_col;
     int32_t reserved;
+    int32_t* delay_num;
 } disco_mig_out;
 
 /* Per-column accumulator, device, 128 bytes.  disco_eval_dispatch overwrites
@@ -205,8 +213,9 @@ typedef struct disco_accum {
     double ttft_sum;
     /* timelines: decode tokens per endpoint with hand-offs, extra device
      * re-prefill tokens (prompt + tokens already produced, Sec. 4.3: only
-     * token ids are transferred), hand-off count, number of TBT values,
-     * sum of last delivery offsets (= sum of all TBT values) */
+     * token ids are transferred; m_s_repre below is the server's share after
+     * buffer hand-offs from the device), hand-off count, number of TBT
+     * values, sum of last delivery offsets (= sum of all TBT values) */
     int64_t m_s_dec, m_d_dec, m_d_repre;
     int64_t n_migrated, tbt_count;
     double tlast_sum;
@@ -214,7 +223,8 @@ typedef struct disco_accum {
      * (non-negative floats order like their bit patterns); they bound the key
      * range of the TTFT order-statistic selection */
     uint32_t ttft_min_bits, ttft_max_bits;
-    int64_t reserved[2];
+    int64_t m_s_repre;        /* timelines: extra server re-prefill tokens */
+    int64_t delay_sum;        /* timelines: sum of delay_num over the requests with a buffer hand-off */
 } disco_accum;
 
 /* ---- evaluation --------------------------------------------------------- */
@@ -239,6 +249,18 @@ int32_t disco_eval_dispatch(const disco_trace* trace /*host*/, const disco_polic
  * m = first t >= 1 with r_t - (delta_{t-1} + tau) > kappa_lag * tau; the
  * device then produces tokens m.. with r'_t = fma(t - m + 1, g, ((delta_{m-1}
  * + tau) + kappa_lag*tau) + fma(l + m, k, c)).
+ * With mig_mode == DISCO_MIG_BUFFER and the column's constrained endpoint as
+ * source (server-constrained column: server source, hand-off to the device;
+ * device-constrained column: device source, hand-off to the server): the
+ * source stops after m = first t < n - 1 with delta_t - r_t >= t_mig(t) (the
+ * buffer hides the hand-off) and dc (n - 1 - t) > cp (l + t + 1) in fp64 (the
+ * decode saving exceeds the target's prefill overhead; dc = |price difference
+ * of a decode token|, cp = target's prefill price, from tl->cost), where
+ * t_mig(t) = fma(l + t + 1, k, c) for a device target and the server's TTFT
+ * for a server target; the target's tokens arrive at r'_t = fma(t - m, g,
+ * r_m + t_mig(m)) (device), fma(t - m, srv_tbt, ...) or (r_m + t_mig(m)) +
+ * (tok_arr_t - tok_arr_m) (server without / with a token trace), t > m.
+ * Tables with such columns run in a slower, general kernel.
  * acc: device, P entries, timeline block overwritten.  Asynchronous.
  * Errors: NULL, SHAPE, RANGE (tau <= 0, kappa_lag < 0), CSR (delivered
  * requested without tok_off), WORKSPACE, HIP. */
@@ -259,7 +281,8 @@ typedef struct disco_stats {
     int64_t tbt_rank[DISCO_MAX_Q];
     float ttft_q[DISCO_MAX_Q];                 /* the order statistic of that rank */
     float tbt_q[DISCO_MAX_Q];
-    int64_t reserved[5];
+    double mean_delay_num;                     /* delay_sum / n_migrated (NaN without hand-offs or timelines) */
+    int64_t reserved[4];
 } disco_stats;
 
 typedef struct disco_quantile { int32_t num, den; } disco_quantile;   /* q = num/den in [0,1] */

@@ -28,7 +28,7 @@ _lib = C.CDLL(LIB_PATH)
 MAX_COLS, MAX_Q, MAX_STEPS = 64, 4, 64
 GEN_REQUESTS, GEN_TOKENS = 1, 2
 MODE_S, MODE_D = 0, 1
-MIG_NONE, MIG_LAG = 0, 1
+MIG_NONE, MIG_LAG, MIG_BUFFER = 0, 1, 2
 PARAM_L_TH, PARAM_W_TAIL = 0, 1
 ACC = {"total_cost": 0, "server_cost": 1, "device_cost": 2, "server_prefill_tok": 3, "device_prefill_tok": 4}
 ERR = {"null": -1, "shape": -2, "range": -3, "csr": -4, "workspace": -5, "hip": -6}
@@ -78,7 +78,7 @@ class CCost(C.Structure):
 
 
 class CTimeline(C.Structure):
-    _fields_ = [("tau", C.c_float), ("kappa_lag", C.c_float)]
+    _fields_ = [("tau", C.c_float), ("kappa_lag", C.c_float), ("cost", C.POINTER(CCost))]
 
 
 class CPairOut(C.Structure):
@@ -87,7 +87,8 @@ class CPairOut(C.Structure):
 
 class CMigOut(C.Structure):
     _fields_ = [("mig_idx", C.c_void_p), ("n_src_tok", C.c_void_p), ("t_last", C.c_void_p),
-                ("delivered", C.c_void_p), ("delivered_col", C.c_int32), ("reserved", C.c_int32)]
+                ("delivered", C.c_void_p), ("delivered_col", C.c_int32), ("reserved", C.c_int32),
+                ("delay_num", C.c_void_p)]
 
 
 class CQuantile(C.Structure):
@@ -104,14 +105,15 @@ ACCUM_DTYPE = np.dtype([
     ("n_dev_started", "<i8"), ("n_dev_win", "<i8"), ("ttft_sum", "<f8"),
     ("m_s_dec", "<i8"), ("m_d_dec", "<i8"), ("m_d_repre", "<i8"), ("n_migrated", "<i8"), ("tbt_count", "<i8"),
     ("tlast_sum", "<f8"),
-    ("ttft_min_bits", "<u4"), ("ttft_max_bits", "<u4"), ("reserved", "<i8", (2,))])
+    ("ttft_min_bits", "<u4"), ("ttft_max_bits", "<u4"), ("m_s_repre", "<i8"), ("delay_sum", "<i8")])
 STATS_DTYPE = np.dtype([
     ("mean_ttft", "<f8"), ("mean_tbt", "<f8"),
     ("server_cost", "<f8"), ("device_energy", "<f8"), ("device_cost", "<f8"), ("total_cost", "<f8"),
     ("s_pre", "<i8"), ("s_dec", "<i8"), ("d_pre", "<i8"), ("d_dec", "<i8"),
     ("n_req", "<i8"), ("tbt_count", "<i8"), ("n_migrated", "<i8"), ("n_dev_started", "<i8"), ("n_dev_win", "<i8"),
     ("ttft_rank", "<i8", (MAX_Q,)), ("tbt_rank", "<i8", (MAX_Q,)),
-    ("ttft_q", "<f4", (MAX_Q,)), ("tbt_q", "<f4", (MAX_Q,)), ("reserved", "<i8", (5,))])
+    ("ttft_q", "<f4", (MAX_Q,)), ("tbt_q", "<f4", (MAX_Q,)), ("mean_delay_num", "<f8"),
+    ("reserved", "<i8", (4,))])
 SEARCH_DTYPE = np.dtype([
     ("param", "<f8"), ("acc_at_param", "<f8"), ("lo", "<f8"), ("hi", "<f8"),
     ("hist_param", "<f8", (MAX_STEPS,)), ("hist_acc", "<f8", (MAX_STEPS,)), ("at_param", ACCUM_DTYPE)])
@@ -296,7 +298,9 @@ def disco_eval_dispatch(trace: Trace, policies, materialise: bool = False, ws: t
 
 def disco_eval_migration(trace: Trace, tau: float, kappa: float, policies, materialise: bool = False,
                          delivered_col: int | None = None, ws: torch.Tensor | None = None,
-                         acc: torch.Tensor | None = None) -> dict:
+                         acc: torch.Tensor | None = None, cost: dict | None = None) -> dict:
+    """``cost``: the rates behind the buffer hand-off's cost test (columns with ``MIG_BUFFER``); without
+    them such columns never hand off."""
     P = len(policies)
     dev = trace.prompt_len.device if trace.prompt_len is not None else "cuda"
     if ws is None:
@@ -304,19 +308,22 @@ def disco_eval_migration(trace: Trace, tau: float, kappa: float, policies, mater
     if acc is None:
         acc = torch.zeros(max(P, 1) * 128, dtype=torch.uint8, device=dev)
     res = {"acc": acc}
-    out = CMigOut(None, None, None, None, 0, 0)
+    out = CMigOut(None, None, None, None, 0, 0, None)
     if materialise:
         res["mig_idx"] = torch.empty((P, trace.n_req), dtype=torch.int32, device=dev)
         res["n_src_tok"] = torch.empty((P, trace.n_req), dtype=torch.int32, device=dev)
         res["t_last"] = torch.empty((P, trace.n_req), dtype=torch.float32, device=dev)
+        res["delay_num"] = torch.empty((P, trace.n_req), dtype=torch.int32, device=dev)
         out.mig_idx, out.n_src_tok, out.t_last = (res["mig_idx"].data_ptr(), res["n_src_tok"].data_ptr(),
                                                   res["t_last"].data_ptr())
+        out.delay_num = res["delay_num"].data_ptr()
     if delivered_col is not None:
         total = int(trace.tok_off[-1].item()) if trace.tok_off is not None else 0
         res["delivered"] = torch.empty(total, dtype=torch.float32, device=dev)
         out.delivered = res["delivered"].data_ptr()
         out.delivered_col = delivered_col
-    tl = CTimeline(tau, kappa)
+    cc = _cost(cost) if cost is not None else None
+    tl = CTimeline(tau, kappa, C.pointer(cc) if cc is not None else None)
     cs = trace.c_struct()
     rc = _lib.disco_eval_migration(C.byref(cs), C.byref(tl), _policies(policies), P, C.byref(out),
                                    acc.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
@@ -326,8 +333,9 @@ def disco_eval_migration(trace: Trace, tau: float, kappa: float, policies, mater
 
 def disco_reduce_stats(trace: Trace, cost: dict, policies, acc: torch.Tensor, quantiles=((50, 100), (99, 100)),
                        tau: float | None = None, kappa: float = 3.0, ws: torch.Tensor | None = None,
-                       out: torch.Tensor | None = None) -> torch.Tensor:
-    """Returns the device buffer of P ``disco_stats`` records (see ``stats_to_host``)."""
+                       out: torch.Tensor | None = None, mig_cost: dict | None = None) -> torch.Tensor:
+    """Returns the device buffer of P ``disco_stats`` records (see ``stats_to_host``).  ``tau``, ``kappa`` and
+    ``mig_cost`` must be the timeline parameters ``acc`` was accumulated with."""
     P = len(policies)
     dev = acc.device
     if ws is None:
@@ -337,7 +345,8 @@ def disco_reduce_stats(trace: Trace, cost: dict, policies, acc: torch.Tensor, qu
     q = (CQuantile * max(len(quantiles), 1))()
     for i, (num, den) in enumerate(quantiles):
         q[i] = CQuantile(num, den)
-    tl = CTimeline(tau, kappa) if tau is not None else None
+    mc = _cost(mig_cost) if mig_cost is not None else None
+    tl = CTimeline(tau, kappa, C.pointer(mc) if mc is not None else None) if tau is not None else None
     cs = trace.c_struct()
     cc = _cost(cost)
     rc = _lib.disco_reduce_stats(C.byref(cs), C.byref(cc), C.byref(tl) if tl else None, _policies(policies), P,

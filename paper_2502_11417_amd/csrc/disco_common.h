@@ -21,6 +21,7 @@ enum {
     DISCO_BLOCK = 256,           // threads per workgroup (4 waves)
     DISCO_MAX_BLOCKS = 2048,     // upper bound of workgroups per launch (8 per CU on 256 CUs)
     DISCO_MAX_SLOTS = 128,       // (columns x quantiles) selected together
+    DISCO_FLAG_BUFFER = 40,      // word of the ticket region: 1 if the staged policy table has a buffer hand-off column
 };
 
 // Workspace carve-up.  Every region is 256-byte aligned.

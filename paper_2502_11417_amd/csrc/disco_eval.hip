@@ -30,8 +30,9 @@ __global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned*
 {
     int i = threadIdx.x;
     if (i < P) dst[i] = t.p[i];
+    const bool any_buffer = __ballot(i < P && t.p[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
     if (i < 64) {
-        tickets[i] = 0u;
+        tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
         for (int k = 0; k < DISCO_NCOPY; ++k) {
             totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
             tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
@@ -43,8 +44,9 @@ __global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* ds
 {
     int i = threadIdx.x;
     if (i < P) dst[i] = src[i];
+    const bool any_buffer = __ballot(i < P && src[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
     if (i < 64) {
-        tickets[i] = 0u;
+        tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
         for (int k = 0; k < DISCO_NCOPY; ++k) {
             totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
             tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
@@ -147,7 +149,7 @@ __global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, 
     disco_stats st;
     memset(&st, 0, sizeof(st));
     st.n_req = n_req;
-    st.s_pre = a.s_pre;
+    st.s_pre = a.s_pre + (with_tl ? a.m_s_repre : 0);
     st.d_pre = a.d_pre + (with_tl ? a.m_d_repre : 0);
     st.s_dec = with_tl ? a.m_s_dec : a.s_dec;
     st.d_dec = with_tl ? a.m_d_dec : a.d_dec;
@@ -157,6 +159,7 @@ __global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, 
     st.tbt_count = with_tl ? a.tbt_count : 0;
     st.mean_ttft = a.ttft_sum / (double)n_req;                       // 0/0 = NaN for an empty batch
     st.mean_tbt = with_tl ? a.tlast_sum / (double)a.tbt_count : NAN;  // telescoped sum of gaps
+    st.mean_delay_num = (with_tl && a.n_migrated > 0) ? (double)a.delay_sum / (double)a.n_migrated : NAN;
     st.server_cost = server_cost_of(cost, st.s_pre, st.s_dec);
     st.device_energy = device_energy_of(cost, st.d_pre, st.d_dec);
     st.device_cost = cost.lambda * st.device_energy;
@@ -230,7 +233,8 @@ int check_policies(const disco_policy* pol, int P)
     for (int j = 0; j < P; ++j) {
         if (pol[j].mode != DISCO_MODE_SERVER_CONSTRAINED && pol[j].mode != DISCO_MODE_DEVICE_CONSTRAINED)
             return DISCO_ERR_RANGE;
-        if (pol[j].mig_mode != DISCO_MIG_NONE && pol[j].mig_mode != DISCO_MIG_LAG) return DISCO_ERR_RANGE;
+        if (pol[j].mig_mode != DISCO_MIG_NONE && pol[j].mig_mode != DISCO_MIG_LAG && pol[j].mig_mode != DISCO_MIG_BUFFER)
+            return DISCO_ERR_RANGE;
         if (pol[j].w_mid != pol[j].w_mid || pol[j].beta != pol[j].beta || pol[j].w_tail != pol[j].w_tail)
             return DISCO_ERR_RANGE;
     }
@@ -243,6 +247,20 @@ int check_ws(void* ws, size_t ws_bytes, int P)
     if (ws_bytes < disco_ws_layout(P).total) return DISCO_ERR_WORKSPACE;
     if (((uintptr_t)ws & 255u) != 0) return DISCO_ERR_WORKSPACE;
     return DISCO_OK;
+}
+
+// Prices of the buffer hand-off's cost test from the unified cost rates (Sec. 4.1): a server source saves
+// cs_dec - lambda e_dec per token and pays lambda e_pre per re-prefilled token; a device source the mirror image.
+// Without rates nothing is ever saved (no hand-off).
+BufCostArgs buffer_prices(const disco_cost_params* c)
+{
+    BufCostArgs b{0.0, 0.0, 0.0, 0.0};
+    if (c) {
+        const double dev_dec = c->lambda * c->e_dec, dev_pre = c->lambda * c->e_pre;
+        b.dc_srv = c->cs_dec - dev_dec; b.cp_srv = dev_pre;
+        b.dc_dev = dev_dec - c->cs_dec; b.cp_dev = c->cs_pre;
+    }
+    return b;
 }
 
 bool is_device_pointer(const void* p)
@@ -383,17 +401,29 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
     if (out) {
         a.mig_idx = out->mig_idx; a.n_src_tok = out->n_src_tok; a.t_last = out->t_last;
         a.delivered = out->delivered; a.delivered_col = out->delivered_col;
+        a.delay_num = out->delay_num;
     }
+    a.bc = buffer_prices(tl->cost);
+    a.buffer_flag = (unsigned*)(ws + L.ticket) + DISCO_FLAG_BUFFER;
     a.part = (MigPartial*)(ws + L.part);
     a.ticket = (unsigned*)(ws + L.ticket);
     a.acc = acc;
     a.S = (SelState*)(ws + L.sel);
     a.ghist = (unsigned*)(ws + L.ghist);
-    if (a.delivered)
+    // Streaming kernel, unless per-token deliveries are wanted or the table has a buffer hand-off column (then
+    // the general kernel; for a device-resident table both are launched and one of them returns at once).
+    bool any_buffer = false, table_known = !is_device_pointer(pol);
+    for (int j = 0; j < P && table_known; ++j) any_buffer = any_buffer || pol[j].mig_mode == DISCO_MIG_BUFFER;
+    if (a.delivered || (table_known && any_buffer)) {
         disco_launch_timeline_general(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
-    else
+    } else {
         disco_launch_tl_stats_fast(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a,
                                    tl_totals((DispPartial*)(ws + L.part)), stream);
+        if (!table_known) {
+            a.only_if_buffer = 1;
+            disco_launch_timeline_general(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
+        }
+    }
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }
@@ -441,6 +471,8 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             a.P = P; a.nq = nq;
             a.ticket = (unsigned*)(ws + L.ticket);
             a.S = S; a.ghist = gh;
+            a.bc = buffer_prices(tl->cost);          // the prices the statistics pass used
+            a.buffer_flag = (unsigned*)(ws + L.ticket) + DISCO_FLAG_BUFFER;
             // column sets -> classes, then the radix passes; the digits are sized on the device and
             // launches after the last needed pass return at once
             a.ppcnt = (unsigned*)(ws + L.ppcnt);

@@ -2,6 +2,10 @@
 #pragma once
 #include "disco_state.h"
 
+// dc = price difference of a decode token (source minus target), cp = target's prefill price; _srv: server
+// source handing off to the device, _dev: device source handing off to the server.
+struct BufCostArgs { double dc_srv, cp_srv, dc_dev, cp_dev; };
+
 struct TimelineArgs {
     float tau, kt;            // pacing interval, kappa_lag * tau
     int P, nq, pass;          // -1: statistics pass, >= 0: TBT histogram pass
@@ -9,6 +13,10 @@ struct TimelineArgs {
     MigPartial* part; unsigned* ticket; disco_accum* acc;
     SelState* S; unsigned* ghist;
     unsigned* ppcnt;          // pure-pacing timelines per class and length (histogram passes)
+    int32_t* delay_num;       // materialised delayed-token counts (buffer hand-off), nullable
+    BufCostArgs bc;           // prices of the buffer hand-off's cost test
+    const unsigned* buffer_flag;   // device: 1 if the staged table has a buffer hand-off column
+    int only_if_buffer;       // general statistics kernel: act only when *buffer_flag is set
 };
 
 // How the last workgroup of a dispatch pass hands on the column totals.

@@ -77,50 +77,65 @@ __device__ __forceinline__ void hist_keys_cols(const HistCtx& h, const unsigned 
 
 // ------------------------------------------------------------- timeline ----
 
-struct TimelineResult { int m; float t_last; };
+struct TimelineResult { int m; float t_last; int delay; };
+
+// Prices behind the buffer hand-off's cost test (Sec. 4.3: saving > overhead).
+typedef BufCostArgs BufCost;
 
 // Timeline of one request and source.
-//   variant 0: device source, 1: server source, 2: server source with the lag trigger
-//   arr/off/n_tok: CSR token array or arr == nullptr (constant gap `gap_src`)
+//   variant 0: device source, 1: server source, 2: server source with the lag trigger,
+//           3: server source with the buffer hand-off (target device),
+//           4: device source with the buffer hand-off (target server)
+//   arr/off/n_tok: CSR token array of the server or arr == nullptr (constant gap `gap_srv`)
 //   deliv: nullable, delivery offsets of the request's tokens
 //   sink(key[4], ok[4]): called once per chunk by all lanes (ok marks real gaps)
+// Returns m = the lag trigger's first device token, or the last source token of a buffer hand-off.
 template <class Sink>
 __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const float* __restrict__ arr, i64 off, i64 n_tok,
-                                                       int align, float gap_src, float g_dev, int l, float k, float c,
-                                                       float tau, float kt, int lane, float* __restrict__ deliv, Sink&& sink)
+                                                       int align, float gap_srv, float g_dev, int l, float k, float c,
+                                                       float s_ttft, const BufCost& bc, float tau, float kt, int lane,
+                                                       float* __restrict__ deliv, Sink&& sink)
 {
-    const bool from_mem = (variant != 0) && arr != nullptr;
-    const float gap = (variant == 0) ? g_dev : gap_src;
+    const bool src_dev = variant == 0 || variant == 4;
+    const bool buffer = variant >= 3;
+    const bool from_mem = !src_dev && arr != nullptr;       // source arrivals come from the token array
+    const bool tgt_mem = variant == 4 && arr != nullptr;    // the target's arrivals follow the token array
+    const bool use_mem = from_mem || tgt_mem;
+    const double dc = variant == 3 ? bc.dc_srv : bc.dc_dev, cp = variant == 3 ? bc.cp_srv : bc.cp_dev;
     // element 0 of the window is the aligned-down start: the first `mis` elements precede the request
-    const int mis = from_mem ? (int)((off + align) & 3) : 0;
+    const int mis = use_mem ? (int)((off + align) & 3) : 0;
     const i64 gbase = off - mis + 4 * lane;
-    float carryM = -INFINITY, carryD = INFINITY, base = 0.0f, t_last = 0.0f;
-    int m = -1;
+    float carryM = -INFINITY, carryD = INFINITY, base = 0.0f, t_last = 0.0f, a_m = 0.0f;
+    int m = -1, delay = 0;
     float nxt[4] = {0.f, 0.f, 0.f, 0.f};
-    if (from_mem && 4 * lane - mis < n) load4(arr, gbase, n_tok, nxt);
+    if (use_mem && 4 * lane - mis < n) load4(arr, gbase, n_tok, nxt);
     const int total = n + mis;
     for (int e0 = 0; e0 < total; e0 += 256) {
         const int tb = e0 + 4 * lane - mis;                 // token index of this lane's first element
-        float r[4];
+        float r[4], a[4];
         int tk[4];
         float tf[4];
         bool val[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { tk[q] = tb + q; tf[q] = (float)tk[q]; val[q] = tk[q] >= 0 && tk[q] < n; }
-        if (from_mem && m < 0) {
+        for (int q = 0; q < 4; ++q) { tk[q] = tb + q; tf[q] = (float)tk[q]; val[q] = tk[q] >= 0 && tk[q] < n; a[q] = 0.0f; }
+        if (use_mem && (m < 0 || tgt_mem)) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) r[q] = nxt[q];
+            for (int q = 0; q < 4; ++q) a[q] = nxt[q];
             if (e0 + 256 < total && tb + 256 < n) load4(arr, gbase + e0 + 256, n_tok, nxt);   // next chunk in flight
-        } else if (m < 0) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) r[q] = tf[q] * gap;
         }
-        if (m >= 0) {
+        // arrivals of the spliced sequence
+        auto arrival = [&](int q) -> float {
+            if (m >= 0 && !buffer) return __fmaf_rn((float)(tk[q] - m + 1), g_dev, base);      // lag: device from token m
+            if (m >= 0 && tk[q] > m) {                                                           // buffer: target after token m
+                if (variant == 3) return __fmaf_rn((float)(tk[q] - m), g_dev, base);
+                if (tgt_mem) { const float since = a[q] - a_m; return base + since; }
+                return __fmaf_rn((float)(tk[q] - m), gap_srv, base);
+            }
+            if (src_dev) return tf[q] * g_dev;
+            return from_mem ? a[q] : tf[q] * gap_srv;
+        };
 #pragma unroll
-            for (int q = 0; q < 4; ++q) r[q] = __fmaf_rn((float)(tk[q] - m + 1), g_dev, base);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) r[q] = val[q] ? r[q] : -INFINITY;
+        for (int q = 0; q < 4; ++q) r[q] = val[q] ? arrival(q) : -INFINITY;
         float d[4], prev[4];
         float Mlast;
         auto scan = [&]() {
@@ -160,18 +175,53 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
                 base = t_dec + t_mig;
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    if (tk[q] >= m) r[q] = val[q] ? __fmaf_rn((float)(tk[q] - m + 1), g_dev, base) : -INFINITY;
+                    if (tk[q] >= m) r[q] = val[q] ? arrival(q) : -INFINITY;
+                scan();
+            }
+        }
+        if (buffer && m < 0) {
+            // buffer hand-off after the first token whose playback time ahead covers the migration time and whose
+            // remaining decode saving exceeds the target's prefill overhead
+            bool trig[4];
+            float tm[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float slack = d[q] - r[q];
+                tm[q] = variant == 4 ? s_ttft : __fmaf_rn((float)(l + tk[q] + 1), k, c);
+                const double saved = dc * (double)(n - 1 - tk[q]);
+                const double overhead = cp * (double)(l + tk[q] + 1);
+                trig[q] = val[q] && tk[q] + 1 < n && slack >= tm[q] && saved > overhead;
+            }
+            const u64 any = __ballot(trig[0] || trig[1] || trig[2] || trig[3]);
+            if (any) {
+                const int ml = __ffsll((long long)any) - 1;
+                const int qf = trig[0] ? 0 : (trig[1] ? 1 : (trig[2] ? 2 : 3));
+                const float rm = trig[0] ? r[0] : (trig[1] ? r[1] : (trig[2] ? r[2] : r[3]));
+                const float tmm = trig[0] ? tm[0] : (trig[1] ? tm[1] : (trig[2] ? tm[2] : tm[3]));
+                const float am = trig[0] ? a[0] : (trig[1] ? a[1] : (trig[2] ? a[2] : a[3]));
+                m = bcast_i(tb, ml) + bcast_i(qf, ml);
+                base = bcast_f(rm, ml) + bcast_f(tmm, ml);
+                a_m = bcast_f(am, ml);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (tk[q] > m) r[q] = val[q] ? arrival(q) : -INFINITY;
                 scan();
             }
         }
         unsigned key[4];
         bool ok[4];
+        bool late[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            key[q] = f2u(d[q] - prev[q]);
+            const float gap = d[q] - prev[q];
+            key[q] = f2u(gap);
             ok[q] = val[q] && tk[q] >= 1;
+            late[q] = buffer && m >= 0 && val[q] && tk[q] > m && gap > tau;
             if (deliv && val[q]) deliv[tk[q]] = d[q];
         }
+        if (buffer && m >= 0)
+            delay += __popcll(__ballot(late[0])) + __popcll(__ballot(late[1])) + __popcll(__ballot(late[2])) +
+                     __popcll(__ballot(late[3]));
         sink(key, ok);
         carryM = bcast_f(Mlast, 63);
         carryD = bcast_f(d[3], 63);
@@ -182,7 +232,7 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
             t_last = bcast_f(dl, e >> 2);
         }
     }
-    return TimelineResult{m, t_last};
+    return TimelineResult{m, t_last, delay};
 }
 
 // Pure pacing: a source whose constant gap is safely below tau (gap < 0.999 tau).
@@ -210,7 +260,7 @@ __device__ __forceinline__ TimelineResult run_pure_pacing(int n, float tau, int 
             if (need_keys) sink(key, ok);
         }
     }
-    return TimelineResult{-1, (float)(n - 1) * tau};
+    return TimelineResult{-1, (float)(n - 1) * tau, 0};
 }
 
 constexpr int TL_BLOCK = 1024;
@@ -228,6 +278,7 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
     const int P = a.P, nq = a.nq;
     if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
     const bool hist_pass = a.pass >= 0;       // pass -1: statistics
+    if (!hist_pass && a.only_if_buffer && *a.buffer_flag == 0u) return;      // the streaming kernel does this table
     HistCtx h;
     h.hist = smem; h.shift = 0; h.width = 0; h.up = 0; h.nq = nq; h.key_lo = 0u; h.key_cap = 0xFFFFFFFFu;
     h.sprefix = sprefix; h.slive = slive;
@@ -247,7 +298,7 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
         }
     }
     __syncthreads();
-    u64 acc_s_dec = 0, acc_d_dec = 0, acc_repre = 0, acc_mig = 0, acc_cnt = 0;
+    u64 acc_s_dec = 0, acc_d_dec = 0, acc_repre = 0, acc_srepre = 0, acc_delay = 0, acc_mig = 0, acc_cnt = 0;
     double acc_tlast = 0.0;
     const i64 nwaves = (i64)gridDim.x * TL_WAVES;
     // A wave takes TL_RB consecutive requests at a time.  Phase A, lane = request: the fields are
@@ -268,51 +319,78 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
             if (tr.off) off_v = tr.off[ia];
             if (tr.tbt) gap_v = tr.tbt[ia];
         }
-        u64 m_v[3];
-        request_sets(spol, P, l_v, s_v, __fmaf_rn((float)l_v, k_v, tr.c), m_v);
-        if (!va) m_v[0] = m_v[1] = m_v[2] = 0ull;
+        // column sets by timeline kind: 0 device, 1 server, 2 server + lag trigger, 3 server + buffer hand-off,
+        // 4 device + buffer hand-off (the buffer hand-off applies when the source is the column's constrained endpoint)
+        u64 m_v[5] = {0ull, 0ull, 0ull, 0ull, 0ull};
+        {
+            const float d_v = __fmaf_rn((float)l_v, k_v, tr.c);
+            u64 m0 = 0ull, m1 = 0ull, m2 = 0ull, m3 = 0ull, m4 = 0ull;
+            for (int j = 0; j < P; ++j) {
+                unsigned dec; float t;
+                dispatch_pair(spol[j], l_v, s_v, d_v, dec, t);
+                const bool dev = (dec & 4u) != 0u;
+                const int mg = spol[j].mig_mode;
+                const bool buf = mg == DISCO_MIG_BUFFER &&
+                                 (dev ? spol[j].mode == DISCO_MODE_DEVICE_CONSTRAINED : spol[j].mode == DISCO_MODE_SERVER_CONSTRAINED);
+                const u64 bit = va ? (1ull << j) : 0ull;
+                m4 |= (dev && buf) ? bit : 0ull;
+                m0 |= (dev && !buf) ? bit : 0ull;
+                m3 |= (!dev && buf) ? bit : 0ull;
+                m2 |= (!dev && !buf && mg == DISCO_MIG_LAG) ? bit : 0ull;
+                m1 |= (!dev && !buf && mg != DISCO_MIG_LAG) ? bit : 0ull;
+            }
+            m_v[0] = m0; m_v[1] = m1; m_v[2] = m2; m_v[3] = m3; m_v[4] = m4;
+        }
         const int cnt = (int)((tr.n_req - bt * TL_RB < TL_RB) ? (tr.n_req - bt * TL_RB) : TL_RB);
 #pragma unroll 1
       for (int rq = 0; rq < cnt; ++rq) {
         const i64 i = bt * TL_RB + rq;
         const int l = bcast_i(l_v, rq), n = bcast_i(n_v, rq);
         const float k = bcast_f(k_v, rq), gd = bcast_f(g_v, rq);
-        const float gap_src = bcast_f(gap_v, rq);
+        const float gap_src = bcast_f(gap_v, rq), s_ttft = bcast_f(s_v, rq);
         const i64 off = (i64)bcast_u64((u64)off_v, rq);
-        const u64 mask_dev = bcast_u64(m_v[0], rq), mask_plain = bcast_u64(m_v[1], rq), mask_lag = bcast_u64(m_v[2], rq);
+        const u64 masks[5] = {bcast_u64(m_v[0], rq), bcast_u64(m_v[1], rq), bcast_u64(m_v[2], rq), bcast_u64(m_v[3], rq),
+                              bcast_u64(m_v[4], rq)};
         const u64 dcol = (a.delivered != nullptr && !hist_pass) ? (1ull << a.delivered_col) : 0ull;
-        TimelineResult res_lag{-1, 0.0f};
+        TimelineResult res_lag{-1, 0.0f, 0};
         bool lag_done = false;
-        // order lag, plain, device; a lag run that never fired is also the plain result
+        // order buffer variants, lag, plain, device; a lag run that never fired is also the plain result
 #pragma unroll 1
-        for (int variant = 2; variant >= 0; --variant) {
-            const u64 mask = variant == 2 ? mask_lag : (variant == 1 ? mask_plain : mask_dev);
+        for (int variant = 4; variant >= 0; --variant) {
+            const u64 mask = variant == 4 ? masks[4] : (variant == 3 ? masks[3] : (variant == 2 ? masks[2] : (variant == 1 ? masks[1] : masks[0])));
             if (!mask) continue;
             float* deliv = (dcol & mask) ? a.delivered + off : nullptr;
             TimelineResult res;
             auto sink = [&](const unsigned key[4], const bool ok[4]) {
                 if (hist_pass) hist_keys_cols(h, key, ok, mask, lane);
             };
-            const float gap = variant == 0 ? gd : gap_src;
+            const bool src_dev = variant == 0 || variant == 4;
+            const float gap = src_dev ? gd : gap_src;
             if (variant == 1 && lag_done && res_lag.m < 0 && !hist_pass && !deliv) {
                 res = res_lag;
-            } else if (pure_pacing(variant == 0 || tr.arr == nullptr, gap, a.tau)) {
+            } else if (variant < 3 && pure_pacing(src_dev || tr.arr == nullptr, gap, a.tau)) {
                 res = run_pure_pacing(n, a.tau, lane, deliv, hist_pass, sink);
             } else {
-                res = run_timeline(variant, n, tr.arr, off, n_tok, align, gap_src, gd, l, k, tr.c, a.tau, a.kt, lane,
-                                   deliv, sink);
+                res = run_timeline(variant, n, tr.arr, off, n_tok, align, gap_src, gd, l, k, tr.c, s_ttft, a.bc, a.tau, a.kt,
+                                   lane, deliv, sink);
             }
             if (variant == 2) { res_lag = res; lag_done = true; }
             if (!hist_pass && ((mask >> lane) & 1ull)) {
-                const int nsrc = (res.m >= 0) ? res.m : n;
-                if (variant == 0) acc_d_dec += (u64)n;
+                const bool mig = res.m >= 0;
+                const int nsrc = mig ? (variant >= 3 ? res.m + 1 : res.m) : n;      // tokens produced by the source
+                if (src_dev) { acc_d_dec += (u64)nsrc; acc_s_dec += (u64)(n - nsrc); }
                 else { acc_s_dec += (u64)nsrc; acc_d_dec += (u64)(n - nsrc); }
-                if (res.m >= 0) { acc_mig += 1; acc_repre += (u64)l + (u64)res.m; }
+                if (mig) {
+                    acc_mig += 1;
+                    if (src_dev) acc_srepre += (u64)l + (u64)nsrc; else acc_repre += (u64)l + (u64)nsrc;
+                    acc_delay += (u64)res.delay;
+                }
                 acc_cnt += (u64)(n - 1);
                 acc_tlast += (double)res.t_last;
-                if (a.mig_idx) a.mig_idx[(size_t)lane * tr.n_req + i] = res.m;
+                if (a.mig_idx) a.mig_idx[(size_t)lane * tr.n_req + i] = mig ? nsrc : -1;
                 if (a.n_src_tok) a.n_src_tok[(size_t)lane * tr.n_req + i] = nsrc;
                 if (a.t_last) a.t_last[(size_t)lane * tr.n_req + i] = res.t_last;
+                if (a.delay_num) a.delay_num[(size_t)lane * tr.n_req + i] = mig ? res.delay : 0;
             }
         }
       }
@@ -330,9 +408,9 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
     u64* sh = reinterpret_cast<u64*>(smem);                                  // 8 fields x TL_BLOCK entries = 64 KB
     auto add = [](MigPartial& x, const MigPartial& o) {
         x.s_dec += o.s_dec; x.d_dec += o.d_dec; x.d_repre += o.d_repre; x.migrated += o.migrated;
-        x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum;
+        x.tbt_count += o.tbt_count; x.tlast_sum += o.tlast_sum; x.pad[0] += o.pad[0]; x.pad[1] += o.pad[1];
     };
-    lds_put(sh, TL_BLOCK, wave * 64 + lane, MigPartial{acc_s_dec, acc_d_dec, acc_repre, acc_mig, acc_cnt, acc_tlast, {0, 0}});
+    lds_put(sh, TL_BLOCK, wave * 64 + lane, MigPartial{acc_s_dec, acc_d_dec, acc_repre, acc_mig, acc_cnt, acc_tlast, {acc_srepre, acc_delay}});   // pad: server re-prefill, delayed tokens
     __syncthreads();
     if (threadIdx.x < 64) {
         MigPartial x = lds_get<MigPartial>(sh, TL_BLOCK, threadIdx.x);
@@ -355,6 +433,7 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
         disco_accum* o = &a.acc[c];
         o->m_s_dec = (i64)x.s_dec; o->m_d_dec = (i64)x.d_dec; o->m_d_repre = (i64)x.d_repre;
         o->n_migrated = (i64)x.migrated; o->tbt_count = (i64)x.tbt_count; o->tlast_sum = x.tlast_sum;
+        o->m_s_repre = (i64)x.pad[0]; o->delay_sum = (i64)x.pad[1];
     }
     if (threadIdx.x == 0) *a.ticket = 0u;
 }

@@ -215,7 +215,9 @@ struct StatsArgs {
     float tau, kt;
     int P;
     int32_t* mig_idx; int32_t* n_src_tok; float* t_last;
+    int32_t* delay_num;            // all zero here: only buffer hand-offs count delayed tokens
     MigPartial* totals;            // DISCO_NCOPY x 64 device-wide totals
+    const unsigned* buffer_flag;   // set: the table has a buffer hand-off column and the general kernel takes it
 };
 
 // Statistics walk of one request and source: the hand-off index and the
@@ -323,6 +325,7 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
     __shared__ u64 sh[6 * TS_BLOCK];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int P = a.P;
+    if (*a.buffer_flag != 0u) return;
     if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
     __syncthreads();
     // lane = column: tokens decoded by the server, re-prefilled tokens, hand-offs, sum of last deliveries;
@@ -332,7 +335,7 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
     double acc_tlast = 0.0;
     const float tau = a.tau, kt = a.kt;
     const bool mem = tr.arr != nullptr;
-    const bool mat = a.mig_idx != nullptr || a.n_src_tok != nullptr || a.t_last != nullptr;
+    const bool mat = a.mig_idx != nullptr || a.n_src_tok != nullptr || a.t_last != nullptr || a.delay_num != nullptr;
     const i64 nwaves = (i64)gridDim.x * (TS_BLOCK / 64);
     const i64 nbatch = (tr.n_req + TF_RB - 1) / TF_RB;
     for (i64 bt = (i64)blockIdx.x * (TS_BLOCK / 64) + wave; bt < nbatch; bt += nwaves) {
@@ -393,6 +396,7 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
                     if (a.mig_idx) a.mig_idx[(size_t)lane * tr.n_req + i] = w.m;
                     if (a.n_src_tok) a.n_src_tok[(size_t)lane * tr.n_req + i] = in_dev ? n : nsrc;
                     if (a.t_last) a.t_last[(size_t)lane * tr.n_req + i] = t_last;
+                    if (a.delay_num) a.delay_num[(size_t)lane * tr.n_req + i] = 0;
                 }
             }
         }
@@ -421,10 +425,10 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
 }
 
 // Totals -> accumulators; puts the totals back to zero for the next pass.
-__global__ void k_tl_stats_fin(int P, MigPartial* totals, disco_accum* acc)
+__global__ void k_tl_stats_fin(int P, MigPartial* totals, disco_accum* acc, const unsigned* buffer_flag)
 {
     const int c = threadIdx.x;
-    if (c >= P) return;
+    if (c >= P || *buffer_flag != 0u) return;
     MigPartial x{0, 0, 0, 0, 0, 0.0, {0, 0}};
     for (int k = 0; k < DISCO_NCOPY; ++k) {
         MigPartial* t = &totals[k * 64 + c];
@@ -435,6 +439,7 @@ __global__ void k_tl_stats_fin(int P, MigPartial* totals, disco_accum* acc)
     disco_accum* o = &acc[c];
     o->m_s_dec = (i64)x.s_dec; o->m_d_dec = (i64)x.d_dec; o->m_d_repre = (i64)x.d_repre;
     o->n_migrated = (i64)x.migrated; o->tbt_count = (i64)x.tbt_count; o->tlast_sum = x.tlast_sum;
+    o->m_s_repre = 0; o->delay_sum = 0;
 }
 
 // ------------------------------------------------------------- histogram ---
@@ -605,15 +610,16 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
     StatsArgs s;
     memset(&s, 0, sizeof(s));
     s.tau = a.tau; s.kt = a.kt; s.P = a.P;
-    s.mig_idx = a.mig_idx; s.n_src_tok = a.n_src_tok; s.t_last = a.t_last;
+    s.mig_idx = a.mig_idx; s.n_src_tok = a.n_src_tok; s.t_last = a.t_last; s.delay_num = a.delay_num;
     s.totals = totals;
+    s.buffer_flag = a.buffer_flag;
     const i64 per_block = (i64)(TS_BLOCK / 64) * TF_RB;
     i64 b = (v.n_req + per_block - 1) / per_block;
     if (b < 1) b = 1;
     if (b > 2048) b = 2048;                    // eight resident workgroups per CU
     const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
     hipLaunchKernelGGL(k_tl_stats, dim3((unsigned)b), dim3(TS_BLOCK), 0, stream, v, n_tok, align, pol, s);
-    hipLaunchKernelGGL(k_tl_stats_fin, dim3(1), dim3(64), 0, stream, a.P, totals, a.acc);
+    hipLaunchKernelGGL(k_tl_stats_fin, dim3(1), dim3(64), 0, stream, a.P, totals, a.acc, a.buffer_flag);
 }
 
 void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,

@@ -35,6 +35,35 @@ def test_struct_sizes_match_the_header(B):
     assert B._lib.disco_version() >= 100
 
 
+def test_struct_layouts_match_a_c_compiler(B, tmp_path):
+    """sizeof / offsetof as gcc sees the public header against the binding's ctypes and numpy records."""
+    import subprocess
+    probes = [("disco_timeline_params", ["tau", "kappa_lag", "cost"], B.CTimeline),
+              ("disco_mig_out", ["mig_idx", "n_src_tok", "t_last", "delivered", "delivered_col", "delay_num"], B.CMigOut),
+              ("disco_accum", ["m_s_dec", "tlast_sum", "ttft_min_bits", "m_s_repre", "delay_sum"], B.ACCUM_DTYPE),
+              ("disco_stats", ["mean_tbt", "ttft_rank", "tbt_q", "mean_delay_num"], B.STATS_DTYPE),
+              ("disco_policy", ["mode", "w_tail", "mig_mode"], B.CPolicy)]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "disco.h"', 'int main(void) {']
+    for name, fields, _ in probes:
+        lines.append(f'printf("%zu", sizeof({name}));')
+        for f in fields:
+            lines.append(f'printf(" %zu", offsetof({name}, {f}));')
+        lines.append('printf("\\n");')
+    lines += ['return 0; }']
+    src = tmp_path / "probe.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "probe"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.strip().splitlines()
+    for (name, fields, rec), line in zip(probes, out):
+        want = [int(x) for x in line.split()]
+        if isinstance(rec, type) and issubclass(rec, C.Structure):
+            got = [C.sizeof(rec)] + [getattr(rec, f).offset for f in fields]
+        else:
+            got = [rec.itemsize] + [rec.fields[f][1] for f in fields]
+        assert got == want, (name, got, want)
+
+
 def test_error_strings(B):
     for code in (0, -1, -2, -3, -4, -5, -6, -99):
         assert len(B._lib.disco_strerror(code)) > 0
@@ -54,12 +83,14 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, 256, 256, 16, None) == B.ERR["workspace"]
     bad = (B.CPolicy * 1)(B.CPolicy(7, 0, -1, 0.0, 1.0, 1.0, 0, 0))
     assert lib.disco_eval_dispatch(C.byref(tr), bad, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
+    bad = (B.CPolicy * 1)(B.CPolicy(0, 0, -1, 0.0, 1.0, 1.0, 3, 0))          # unknown migration mode
+    assert lib.disco_eval_dispatch(C.byref(tr), bad, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
     tr.n_req = -1
     assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, 256, 256, 1 << 30, None) == B.ERR["shape"]
     tr.n_req = 5          # arrays missing
     assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, 256, 256, 1 << 30, None) == B.ERR["null"]
     tr.n_req = 0
-    tl = B.CTimeline(0.0, 3.0)
+    tl = B.CTimeline(0.0, 3.0, None)
     assert lib.disco_eval_migration(C.byref(tr), C.byref(tl), pol, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
     q = (B.CQuantile * 1)(B.CQuantile(3, 2))
     cost = B.CCost(1, 1, 1, 1, 1)

@@ -121,15 +121,17 @@ def test_dispatch_column_counts(B, oracle, P):
 
 # --------------------------------------------------------------- timelines
 
-def check_migration(B, O, tr, specs, tau, kappa, delivered_col=0):
+def check_migration(B, O, tr, specs, tau, kappa, delivered_col=0, cost=None, policies=None):
+    """``policies``: a device-resident table holding the same columns as ``specs`` (else a host table is passed)."""
     bp, op = both(B, O, specs)
     P = len(specs)
     dt = B.upload_trace(tr)
-    got = B.disco_eval_migration(dt, tau, kappa, bp, materialise=True, delivered_col=delivered_col)
-    want = O.migration(tr, op, tau, kappa, materialise=True)
+    got = B.disco_eval_migration(dt, tau, kappa, policies if policies is not None else bp, materialise=True,
+                                 delivered_col=delivered_col, cost=cost)
+    want = O.migration(tr, op, tau, kappa, materialise=True, cost=cost)
     acc = B.accum_to_host(got["acc"], P)
     for j in range(P):
-        for f in ("m_s_dec", "m_d_dec", "m_d_repre", "n_migrated", "tbt_count"):
+        for f in ("m_s_dec", "m_d_dec", "m_d_repre", "m_s_repre", "delay_sum", "n_migrated", "tbt_count"):
             assert int(acc[f][j]) == int(want[f][j]), (f, j)
         if tr["n_req"]:
             assert close(float(acc["tlast_sum"][j]), float(want["tlast_sum"][j])), j
@@ -137,8 +139,10 @@ def check_migration(B, O, tr, specs, tau, kappa, delivered_col=0):
         assert_same_bits(got["mig_idx"].cpu().numpy(), want["mig_idx"], "mig_idx")
         assert_same_bits(got["n_src_tok"].cpu().numpy(), want["n_src_tok"], "n_src_tok")
         assert_same_bits(got["t_last"].cpu().numpy(), want["t_last"], "t_last")
+        assert_same_bits(got["delay_num"].cpu().numpy(), want["delay_num"], "delay_num")
     if delivered_col is not None:
-        w1 = O.migration(tr, [op[delivered_col]], tau, kappa, materialise=False, tbt_col=0, want_delivered=True)
+        w1 = O.migration(tr, [op[delivered_col]], tau, kappa, materialise=False, tbt_col=0, want_delivered=True,
+                         cost=cost)
         assert_same_bits(got["delivered"].cpu().numpy(), w1["delivered"], "delivered")
     return dt, acc, want
 
@@ -199,8 +203,8 @@ def check_stats(B, O, tr, specs, cost, tau=None, kappa=3.0, quantiles=((50, 100)
     ws = B.workspace(tr["n_req"], P)
     r = B.disco_eval_dispatch(dt, bp, ws=ws)
     if tau is not None:
-        B.disco_eval_migration(dt, tau, kappa, bp, ws=ws, acc=r["acc"])
-    out = B.disco_reduce_stats(dt, cost, bp, r["acc"], quantiles=quantiles, tau=tau, kappa=kappa, ws=ws)
+        B.disco_eval_migration(dt, tau, kappa, bp, ws=ws, acc=r["acc"], cost=cost)
+    out = B.disco_reduce_stats(dt, cost, bp, r["acc"], quantiles=quantiles, tau=tau, kappa=kappa, ws=ws, mig_cost=cost)
     got = B.stats_to_host(out, P)
     want = O.stats(tr, op, cost, quantiles=quantiles, tau=tau, kappa=kappa)
     for j in range(P):
@@ -225,6 +229,11 @@ def check_stats(B, O, tr, specs, cost, tau=None, kappa=3.0, quantiles=((50, 100)
                     assert math.isnan(g["tbt_q"][qi])
         if tau is not None and w["tbt_count"]:
             assert close(float(g["mean_tbt"]), w["mean_tbt"]), j
+        if tau is not None:
+            if w["n_migrated"]:
+                assert close(float(g["mean_delay_num"]), w["delay_sum"] / w["n_migrated"], 1e-15), j
+            else:
+                assert math.isnan(g["mean_delay_num"]), j
     return got, want
 
 
