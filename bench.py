@@ -8,7 +8,7 @@ the TBT order statistics.  The headline workload is configuration 1
 (10^6 requests x 64 budget levels, dispatch only); the other configurations
 are reported as extra fields of the same JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1] [--extras config2,config3,config4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1] [--extras config2,config3,config4,config4buffer]
     python bench.py --copy-calibration BYTES     # one plain device copy of known size, for scaling HBM counters
 """
 from __future__ import annotations
@@ -24,6 +24,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
+# Vector-ALU peak for the non-packed fp32 / integer / compare instructions this path is made of:
+# 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz, one operation per lane and clock
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# Operations the method needs per evaluated (request, column) pair of a length-threshold column: two compares
+# (l < l_th, d < s) and the TTFT select; two conditional token sums of two operations each (server prefill, device
+# decode); the win count; the fp64 TTFT sum (convert + add); minimum and maximum of the TTFT bits
+OPS_PER_PAIR = 12
 # plain (non-packed) fp32 vector rate: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one operation per lane and clock
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
@@ -38,7 +45,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config1")
-    ap.add_argument("--extras", default="config2,config3,config4")
+    ap.add_argument("--extras", default="config2,config3,config4,config4buffer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=20)
     ap.add_argument("--copy-calibration", type=int, default=0)
@@ -77,7 +84,7 @@ def main() -> int:
     class Workload:
         """Resident trace + everything a step needs, allocated once."""
 
-        def __init__(self, idx):
+        def __init__(self, idx, buffer=False):
             self.idx = idx
             self.cfg = DI.config(idx)
             g = self.cfg["gen"]
@@ -96,7 +103,8 @@ def main() -> int:
             self.lmax = int(self.trace.prompt_len.max().item())
             self.levels = DI.budget_levels(self.P)
             self.lth_steps = max(1, (self.lmax + 1).bit_length())
-            mig = D.MIG_LAG if self.cfg["timelines"] else D.MIG_NONE
+            # buffer: the cost-triggered hand-off of Sec. 4.3 in place of the lag trigger
+            mig = (D.MIG_BUFFER if buffer else D.MIG_LAG) if self.cfg["timelines"] else D.MIG_NONE
             self.templ = [D.Policy(mode=D.MODE_S, mig_mode=mig) for _ in self.levels]
             self.specs = [dict(which_param=D.PARAM_L_TH, which_acc="server_prefill_tok", n_steps=self.lth_steps,
                                lo=0, hi=self.lmax + 1, target=num * self.sum_l / den) for num, den in self.levels]
@@ -125,9 +133,10 @@ def main() -> int:
             tau = cfg["tau"] if cfg["timelines"] else None
             D.disco_eval_dispatch(self.trace, self.pols, ws=self.ws, acc=self.acc)
             if tau is not None:
-                D.disco_eval_migration(self.trace, tau, cfg["kappa"], self.pols, ws=self.ws, acc=self.acc)
+                D.disco_eval_migration(self.trace, tau, cfg["kappa"], self.pols, ws=self.ws, acc=self.acc,
+                                       cost=cfg["cost"])
             return D.disco_reduce_stats(self.trace, cfg["cost"], self.pols, self.acc, tau=tau, kappa=cfg["kappa"],
-                                        ws=self.ws, out=self.stats)
+                                        ws=self.ws, out=self.stats, mig_cost=cfg["cost"])
 
         def time_steps(self, steps, warmup):
             if self.idx != 3:
@@ -163,9 +172,10 @@ def main() -> int:
     value = pairs / sec
 
     # Kernel of the headline path that the roofline is quoted for: the fused dispatch-and-reduce pass (it runs once
-    # inside the budget search and once for the evaluation).  Algorithmic bytes: 12 B per request (prompt length,
-    # server TTFT, output length), independent of the number of columns.  The timed call also launches the 5-us
-    # kernel that stages the policy table, so the figure is slightly conservative.
+    # inside the budget search and once for the evaluation).  With many columns it is bound by vector arithmetic
+    # (OPS_PER_PAIR operations per pair against 12 B per request: prompt length, server TTFT, output length,
+    # independent of the number of columns); with one column by memory.  The timed call also launches the 5-us
+    # kernel that stages the policy table, so the figures are slightly conservative.
     bytes_per_launch = 12.0 * w.N
     if idx == 3:
         one = [D.Policy(mode=D.MODE_D, l_th=-1, w_tail=0.6)]
@@ -174,10 +184,17 @@ def main() -> int:
     else:
         t_k = event_time(lambda: D.disco_eval_dispatch(w.trace, w.pols, ws=w.ws, acc=w.acc), args.kernel_reps)
         pairs_per_launch = w.N * w.P
-    achieved = bytes_per_launch / t_k / 1e9
-    roofline = {"bound": "hbm", "kernel": "k_dispatch_acc", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic("k_dispatch_acc", args.workload),
-                "launch_us": round(t_k * 1e6, 2), "pairs_per_s_in_kernel": pairs_per_launch / t_k}
+    gbs = bytes_per_launch / t_k / 1e9
+    tops = OPS_PER_PAIR * pairs_per_launch / t_k / 1e12
+    common = {"kernel": "k_dispatch_acc", "traffic": measured_traffic("k_dispatch_acc", args.workload),
+              "launch_us": round(t_k * 1e6, 2), "pairs_per_s_in_kernel": pairs_per_launch / t_k}
+    if idx == 3:
+        roofline = {"bound": "hbm", "achieved": round(gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(gbs / HBM_PEAK_GBS, 4), **common}
+    else:
+        roofline = {"bound": "alu", "achieved": round(tops, 3), "peak": round(ALU_PEAK_TOPS, 2), "unit": "Top/s",
+                    "frac": round(tops / ALU_PEAK_TOPS, 4), **common,
+                    "hbm": {"achieved": round(gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}}
 
     result = {
         "metric": "request x policy evaluations/s", "value": value, "unit": "pairs/s", "n_gpus": 1,
@@ -193,11 +210,12 @@ def main() -> int:
 
     extras = {}
     for name in [e for e in args.extras.split(",") if e and e != args.workload]:
-        k = int(name.replace("config", ""))
+        buffer = name.endswith("buffer")
+        k = int(name.replace("config", "").replace("buffer", ""))
         del w
         torch.cuda.empty_cache()
         log(f"[bench] extra {name} ...")
-        w = Workload(k)
+        w = Workload(k, buffer=buffer)
         steps = 3 if k == 4 else 10
         s = w.time_steps(steps, 1)
         ex = {"n_req": w.N, "policy_columns": w.P, "token_events": w.T, "ms_per_step": s * 1e3}
@@ -210,12 +228,17 @@ def main() -> int:
             ex["token_events_per_s_pair_weighted"] = w.T * w.P / s
             # timeline statistics pass alone: 4 B per token event + 28 B per request, read once for all columns
             tau = w.cfg["tau"]
-            t_tl = event_time(lambda: D.disco_eval_migration(w.trace, tau, w.cfg["kappa"], w.pols, ws=w.ws, acc=w.acc),
-                              3 if k == 4 else 10)
+            t_tl = event_time(lambda: D.disco_eval_migration(w.trace, tau, w.cfg["kappa"], w.pols, ws=w.ws, acc=w.acc,
+                                                             cost=w.cfg["cost"]), 3 if k == 4 else 10)
             gb = (4.0 * w.T + 28.0 * w.N) / 1e9
-            ex["timeline_kernel"] = {"bound": "hbm", "kernel": "k_tl_stats", "launch_ms": t_tl * 1e3, "achieved_GBs": gb / t_tl,
+            kern = "k_timeline" if buffer else "k_tl_stats"      # tables with buffer hand-off columns: general kernel
+            ex["timeline_kernel"] = {"bound": "hbm", "kernel": kern, "launch_ms": t_tl * 1e3, "achieved_GBs": gb / t_tl,
                                      "frac": gb / t_tl / HBM_PEAK_GBS,
-                                     "traffic": measured_traffic("k_tl_stats", name)}
+                                     "traffic": measured_traffic(kern, name)}
+            if buffer:
+                st = D.stats_to_host(w.step(), w.P)
+                ex["migrated_requests"] = [int(x) for x in st["n_migrated"]]
+                ex["mean_delay_num"] = [None if x != x else float(x) for x in st["mean_delay_num"]]
         extras[name] = ex
         log(f"[bench] {name}: {json.dumps(ex)}")
     if extras:
