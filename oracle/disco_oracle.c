@@ -30,6 +30,9 @@
  *                     buffer simulation in exact rational arithmetic, cost-condition breakpoints
  *   quantile          numpy sort + nearest rank
  *   budget search     sort + prefix-sum solve; breakpoint enumeration
+ *   stochastic        zero / full budget equal the single-endpoint columns, binomial routing
+ *                     frequency and token share, nesting in the budget, independence of runs,
+ *                     the draw rebuilt from the pinned generator with counter and key spelled out
  * parity unpinned (conventions the paper does not fix; both sides follow the
  * same written reading): exchange rate lambda, pacing interval, budget-level
  * grid, tie-breaks, charging of a terminated loser, migration overhead time,
@@ -203,7 +206,7 @@ typedef struct orc_gen_cfg {
     float gap_mu, gap_sigma, gap_stall_p, gap_stall_lo, gap_stall_hi;
 } orc_gen_cfg;
 
-enum { F_PROMPT = 0, F_OUTPUT = 1, F_TTFT = 2, F_TBT = 3, F_DEVICE = 4, F_GAP = 5 };
+enum { F_PROMPT = 0, F_OUTPUT = 1, F_TTFT = 2, F_TBT = 3, F_DEVICE = 4, F_GAP = 5, F_ROUTE = 6 };
 
 /* Per-request fields and the CSR offsets of the token array. */
 void orc_gen_requests(const orc_gen_cfg* g, int32_t* prompt_len, int32_t* output_len,
@@ -278,7 +281,12 @@ void orc_gen_tokens(const orc_gen_cfg* g, const int64_t* tok_off, int64_t req_lo
 /* ------------------------------------------------------------------------ */
 
 /* One policy column.  mode 0 = server-constrained length threshold (Alg. 3),
- * mode 1 = device-constrained wait time (Sec. 4.2 Eq. 1 and Alg. 2). */
+ * mode 1 = device-constrained wait time (Sec. 4.2 Eq. 1 and Alg. 2),
+ * mode 2 / 3 = the stochastic baselines of Sec. 5.1 (Stoch-S / Stoch-D): each
+ * request goes to one endpoint only, to the constrained one (server in mode
+ * 2, device in mode 3) with probability beta = the budget ratio b, else to
+ * the other; l_mid is the run number (independent draws per run; runs share
+ * nothing, budget levels of one run share the draw and are therefore nested). */
 typedef struct orc_policy {
     int32_t mode;
     int32_t l_th;
@@ -314,9 +322,31 @@ float orc_wait(const orc_policy* p, int32_t l)
  * after w(l) only if the server has produced nothing by then (s > w, strict).
  * The endpoint with the earlier first token decodes; a tie goes to the
  * server. */
-void orc_dispatch_one(const orc_policy* p, int32_t l, float s, float d,
+uint64_t orc_route_seed(int32_t run)
+{
+    return ((uint64_t)0x53544F43u << 32) | (uint64_t)(uint32_t)run;     /* high word: a tag no trace seed uses */
+}
+
+/* Uniform variate of request `i` in run `run` of the stochastic baselines:
+ * word 0 of the generator at key = (run, tag), counter = (i_lo, i_hi, F_ROUTE, 0). */
+float orc_route_uniform(int32_t run, int64_t i)
+{
+    uint32_t w[4];
+    orc_philox(orc_route_seed(run), (uint64_t)i, F_ROUTE, w);
+    return orc_u23(w[0]);
+}
+
+void orc_dispatch_one(const orc_policy* p, int32_t l, float s, float d, int64_t i,
                       uint8_t* decision, float* ttft)
 {
+    if (p->mode == 2 || p->mode == 3) {
+        /* Stoch-S / Stoch-D (Sec. 5.1 baselines): random routing that meets the budget in expectation */
+        int constrained = orc_route_uniform(p->l_mid, i) < p->beta;
+        int to_server = (p->mode == 2) ? constrained : !constrained;
+        if (to_server) { *decision = 1; *ttft = s; }
+        else { *decision = 6; *ttft = d; }
+        return;
+    }
     if (p->mode == 0) {
         if (l < p->l_th) { *decision = 6; *ttft = d; return; }
         if (d < s) { *decision = 7; *ttft = d; }
@@ -347,7 +377,7 @@ void orc_dispatch(int64_t N, int32_t P, const int32_t* prompt_len, const float* 
             float k = dev_pre_spt ? dev_pre_spt[i] : dev_pre_spt_s;
             float d = orc_device_ttft(prompt_len[i], k, dev_ttft_c);
             uint8_t dec; float t;
-            orc_dispatch_one(&pol[j], prompt_len[i], srv_ttft[i], d, &dec, &t);
+            orc_dispatch_one(&pol[j], prompt_len[i], srv_ttft[i], d, i, &dec, &t);
             if (dec & 1) s_pre += prompt_len[i];
             if (dec & 2) { d_pre += prompt_len[i]; started += 1; }
             if (dec & 4) { d_dec += output_len[i]; won += 1; }
@@ -488,9 +518,9 @@ void orc_timeline_buffer(int32_t n, const float* r_srv, float gap_srv, int32_t s
 /* All pairs: each pair's source is the dispatch winner; timelines are
  * recomputed per pair (no sharing between columns).  mig_mode 1: lag hand-off
  * (server source).  mig_mode 2: buffer hand-off when the source is the
- * constrained endpoint of the column (mode 0: server -> device, price
+ * constrained endpoint of the column (modes 0, 2: server -> device, price
  * difference dc = cs_dec - lambda e_dec, target prefill price cp = lambda
- * e_pre; mode 1: device -> server, dc = lambda e_dec - cs_dec, cp = cs_pre);
+ * e_pre; modes 1, 3: device -> server, dc = lambda e_dec - cs_dec, cp = cs_pre);
  * `rates` = {cs_pre, cs_dec, e_pre, e_dec, lambda} (needed for mode 2 only).
  * Per pair [P][N] (nullable): mig_idx (index of the first token produced by
  * the target, -1 none), n_src_tok (tokens produced by the source), t_last,
@@ -520,7 +550,7 @@ void orc_migration(int64_t N, int32_t P, const int32_t* prompt_len, const float*
             int32_t l = prompt_len[i], n = output_len[i];
             float d = orc_device_ttft(l, k, dev_ttft_c);
             uint8_t dec; float ttft;
-            orc_dispatch_one(&pol[j], l, srv_ttft[i], d, &dec, &ttft);
+            orc_dispatch_one(&pol[j], l, srv_ttft[i], d, i, &dec, &ttft);
             int32_t src_dev = (dec & 4) ? 1 : 0;
             const float* r = (tok_arr && tok_off) ? tok_arr + tok_off[i] : NULL;
             int64_t off = tok_off ? tok_off[i] : run_off;
@@ -529,7 +559,7 @@ void orc_migration(int64_t N, int32_t P, const int32_t* prompt_len, const float*
             float* dl = (want && delivered_out) ? delivered_out + off : NULL;
             float* tb = (want && tbt_out) ? tbt_out + tbt_pos : NULL;
             float gap_srv = srv_tbt ? srv_tbt[i] : 0.0f;
-            int buffer = pol[j].mig_mode == 2 && rates && ((pol[j].mode == 0 && !src_dev) || (pol[j].mode == 1 && src_dev));
+            int buffer = pol[j].mig_mode == 2 && rates && (((pol[j].mode == 0 || pol[j].mode == 2) && !src_dev) || ((pol[j].mode == 1 || pol[j].mode == 3) && src_dev));
             if (buffer) {
                 double dev_dec_price = rates[4] * rates[3], dev_pre_price = rates[4] * rates[2];
                 double dc = src_dev ? dev_dec_price - rates[1] : rates[1] - dev_dec_price;
