@@ -127,6 +127,8 @@ int32_t disco_gen_trace(const disco_gen_params* params /*host*/, disco_trace* tr
 
 #define DISCO_MODE_SERVER_CONSTRAINED 0   /* length threshold, Sec. 4.2 Eq. 3 / Alg. 3 */
 #define DISCO_MODE_DEVICE_CONSTRAINED 1   /* wait time, Sec. 4.2 Eq. 1 / Alg. 2 */
+#define DISCO_MODE_STOCH_SERVER       2   /* baseline Stoch-S, Sec. 5.1: random routing, server budget capped */
+#define DISCO_MODE_STOCH_DEVICE       3   /* baseline Stoch-D, Sec. 5.1: random routing, device budget capped */
 #define DISCO_MIG_NONE 0
 #define DISCO_MIG_LAG  1                  /* hand-off to the device when a server token is overdue */
 #define DISCO_MIG_BUFFER 2                /* Sec. 4.3: the constrained endpoint hands decoding over once the token
@@ -141,7 +143,15 @@ int32_t disco_gen_trace(const disco_gen_params* params /*host*/, disco_trace* tr
  *   (s > w).  beta = +inf gives the step map of Alg. 2, l_mid = -1 the ramp
  *   of Eq. 1, w_tail = +inf a server-only column.
  * In both modes the endpoint with the strictly earlier first token decodes
- * and the other is terminated (Sec. 4.2); a tie goes to the server. */
+ * and the other is terminated (Sec. 4.2); a tie goes to the server.
+ * Stochastic baselines (Sec. 5.1, Stoch-S / Stoch-D): one endpoint per
+ *   request, the constrained one (server for STOCH_SERVER, device for
+ *   STOCH_DEVICE) with probability beta = the budget ratio in [0, 1], else
+ *   the other; l_mid is the run number.  Request i of a run draws U = ((x >> 9)
+ *   + 1/2) 2^-23 from word 0 of Philox4x32-10 with key (run, 0x53544F43) and
+ *   counter (i_lo, i_hi, 6, 0) and goes to the constrained endpoint iff
+ *   U < beta: columns of one run are nested in beta, runs are independent.
+ *   Averaging over runs: disco_average_runs. */
 typedef struct disco_policy {
     int32_t mode;
     int32_t l_th;
@@ -235,7 +245,8 @@ typedef struct disco_accum {
  * acc: device, P entries, dispatch block overwritten.
  * ws: device workspace of disco_workspace_bytes(n_req, P) bytes.
  * Asynchronous.  n_req == 0 is valid (zero totals).
- * Errors: NULL, SHAPE, RANGE (unknown mode), WORKSPACE, HIP. */
+ * Errors: NULL, SHAPE, RANGE (unknown mode, routing probability outside
+ * [0, 1]), WORKSPACE, HIP. */
 int32_t disco_eval_dispatch(const disco_trace* trace /*host*/, const disco_policy* pol /*host*/, int32_t P,
                             const disco_pair_out* out /*host, nullable*/, disco_accum* acc /*device*/,
                             void* ws /*device*/, size_t ws_bytes, void* stream);
@@ -308,6 +319,18 @@ int32_t disco_reduce_stats(const disco_trace* trace /*host*/, const disco_cost_p
                            const disco_accum* acc /*device*/, const disco_quantile* q /*host*/, int32_t nq,
                            disco_stats* out /*device*/, void* ws /*device*/, size_t ws_bytes, void* stream);
 
+/* Mean over runs (Sec. 5.1: every experiment is reported as the mean over 10
+ * runs; the runs of a stochastic baseline are columns that differ in l_mid).
+ * in: device, groups * runs records, the runs of group g at g*runs ..
+ * g*runs + runs - 1; out: device, groups records (must not overlap in).
+ * Floating-point fields: arithmetic mean in fp64, summed in run order (order
+ * statistics: the fp64 mean of the fp32 values, rounded to fp32; NaN
+ * propagates); integer totals and counts: summed over the runs; ranks: those
+ * of the first run.  Asynchronous.  Errors: NULL, SHAPE (groups < 0, runs < 1),
+ * HIP. */
+int32_t disco_average_runs(const disco_stats* in /*device*/, int32_t groups, int32_t runs,
+                           disco_stats* out /*device*/, void* stream);
+
 /* ---- budget search ------------------------------------------------------ */
 
 #define DISCO_PARAM_L_TH    0   /* integer bisection on disco_policy.l_th */
@@ -362,7 +385,8 @@ typedef struct disco_search_out {
  * pol_out: device, n_search entries (nullable): the template with the found
  * parameter, ready to be copied into a policy table.
  * Asynchronous.  Errors: NULL, SHAPE (n_search outside [1, DISCO_MAX_COLS],
- * n_steps out of range or unequal), RANGE (unknown selector, lo > hi),
+ * n_steps out of range or unequal), RANGE (unknown selector, lo > hi, a
+ * stochastic baseline as template),
  * WORKSPACE, HIP. */
 int32_t disco_budget_search(const disco_trace* trace /*host*/, const disco_cost_params* cost /*host*/,
                             const disco_policy* templ /*host*/, const disco_search_spec* spec /*host*/,

@@ -343,6 +343,39 @@ def stats(tr: dict, policies, cost: dict, quantiles=((50, 100), (99, 100)),
     return out
 
 
+def average_runs(stats_list: list, runs: int) -> list:
+    """Mean over runs (Sec. 5.1: results are reported as the mean over 10 runs): consecutive groups of ``runs``
+    records of ``stats``; floating-point fields averaged in fp64 in run order (order statistics rounded back to
+    fp32), integer totals summed, ranks of the first run."""
+    assert runs >= 1 and len(stats_list) % runs == 0
+    out = []
+    for g in range(len(stats_list) // runs):
+        grp = stats_list[g * runs:(g + 1) * runs]
+        o = {}
+        for f in ("mean_ttft", "mean_tbt", "server_cost", "device_energy", "device_cost", "total_cost"):
+            acc = 0.0
+            for st in grp:
+                acc += float(st[f])
+            o[f] = acc / runs
+        acc = 0.0
+        for st in grp:                                          # delayed tokens per migrated request (NaN without hand-offs)
+            acc += st.get("delay_sum", 0) / st["n_migrated"] if st["n_migrated"] else math.nan
+        o["mean_delay_num"] = acc / runs
+        for f in ("s_pre", "s_dec", "d_pre", "d_dec", "n_req", "tbt_count", "n_migrated", "n_dev_started", "n_dev_win"):
+            o[f] = sum(int(st[f]) for st in grp)
+        for f in ("ttft_rank", "tbt_rank"):
+            o[f] = list(grp[0][f])
+        for f in ("ttft_q", "tbt_q"):
+            o[f] = []
+            for qi in range(len(grp[0][f])):
+                acc = 0.0
+                for st in grp:
+                    acc += float(np.float32(st[f][qi]))
+                o[f].append(np.float32(acc / runs))
+        out.append(o)
+    return out
+
+
 # ------------------------------------------------------------ budget search
 
 def _rates(cost: dict):

@@ -27,7 +27,7 @@ _lib = C.CDLL(LIB_PATH)
 
 MAX_COLS, MAX_Q, MAX_STEPS = 64, 4, 64
 GEN_REQUESTS, GEN_TOKENS = 1, 2
-MODE_S, MODE_D = 0, 1
+MODE_S, MODE_D, MODE_STOCH_S, MODE_STOCH_D = 0, 1, 2, 3
 MIG_NONE, MIG_LAG, MIG_BUFFER = 0, 1, 2
 PARAM_L_TH, PARAM_W_TAIL = 0, 1
 ACC = {"total_cost": 0, "server_cost": 1, "device_cost": 2, "server_prefill_tok": 3, "device_prefill_tok": 4}
@@ -123,7 +123,7 @@ assert ACCUM_DTYPE.itemsize == 128 and STATS_DTYPE.itemsize == 256 and POLICY_DT
 assert C.sizeof(CPolicy) == 32 and C.sizeof(CSearchSpec) == 40
 
 EXPORTS = ["disco_gen_trace", "disco_eval_dispatch", "disco_eval_migration", "disco_reduce_stats",
-           "disco_budget_search", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
+           "disco_average_runs", "disco_budget_search", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
            "disco_version"]
 
 _lib.disco_strerror.restype = C.c_char_p
@@ -144,6 +144,8 @@ _lib.disco_reduce_stats.restype = C.c_int32
 _lib.disco_reduce_stats.argtypes = [C.POINTER(CTrace), C.POINTER(CCost), C.POINTER(CTimeline), C.POINTER(CPolicy),
                                     C.c_int32, C.c_void_p, C.POINTER(CQuantile), C.c_int32, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.disco_average_runs.restype = C.c_int32
+_lib.disco_average_runs.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
 _lib.disco_budget_search.restype = C.c_int32
 _lib.disco_budget_search.argtypes = [C.POINTER(CTrace), C.POINTER(CCost), C.POINTER(CPolicy),
                                      C.POINTER(CSearchSpec), C.c_int32, C.c_void_p, C.c_void_p,
@@ -353,6 +355,14 @@ def disco_reduce_stats(trace: Trace, cost: dict, policies, acc: torch.Tensor, qu
                                  acc.data_ptr(), q, len(quantiles), out.data_ptr(), ws.data_ptr(), ws.numel(),
                                  _stream())
     _check(rc, "disco_reduce_stats")
+    return out
+
+
+def disco_average_runs(stats: torch.Tensor, groups: int, runs: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Mean over the ``runs`` consecutive columns of each of ``groups`` groups of ``disco_stats`` records."""
+    if out is None:
+        out = torch.zeros(max(groups, 1) * 256, dtype=torch.uint8, device=stats.device)
+    _check(_lib.disco_average_runs(stats.data_ptr(), groups, runs, out.data_ptr(), _stream()), "disco_average_runs")
     return out
 
 

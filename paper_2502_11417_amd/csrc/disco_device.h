@@ -25,14 +25,59 @@ __device__ __forceinline__ unsigned f2u(float x) { return __float_as_uint(x); }
 __device__ __forceinline__ float u2f(unsigned x) { return __uint_as_float(x); }
 
 // ---------------------------------------------------------------------------
+// Counter-based random numbers: Philox4x32-10 (Salmon et al., SC'11), keyed by
+// a 64-bit seed and counted by (element index, field).
+// ---------------------------------------------------------------------------
+struct Words { unsigned w0, w1, w2, w3; };
+
+__device__ __forceinline__ Words philox4x32_10(u64 seed, u64 index, unsigned field)
+{
+    unsigned c0 = (unsigned)index, c1 = (unsigned)(index >> 32), c2 = field, c3 = 0u;
+    unsigned k0 = (unsigned)seed, k1 = (unsigned)(seed >> 32);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return Words{c0, c1, c2, c3};
+}
+
+// 23 random bits to a uniform on (0,1): (x >> 9 + 1/2) 2^-23, exact in fp32.
+__device__ __forceinline__ float u23(unsigned x)
+{
+    return __fmaf_rn((float)(x >> 9), 0x1p-23f, 0x1p-24f);
+}
+
+// Uniform variate of request i in run `run` of the stochastic baselines
+// (Sec. 5.1): key = (run, tag), counter = (i, field 6), word 0.
+__device__ __forceinline__ float route_uniform(int run, i64 i)
+{
+    const u64 seed = ((u64)0x53544F43u << 32) | (u64)(unsigned)run;
+    return u23(philox4x32_10(seed, (u64)i, 6u).w0);
+}
+
+// ---------------------------------------------------------------------------
 // Dispatch of one (request, column) pair: Sec. 4.2, Alg. 2 (wait time) and
 // Alg. 3 (length threshold).  Both modes are evaluated branch-free so that
-// lanes holding different columns stay converged.
+// lanes holding different columns stay converged.  The stochastic baselines
+// of Sec. 5.1 (modes 2 and 3: one endpoint per request, the constrained one
+// with probability beta) take a branch of their own: their draw costs ten
+// times a pair of the method.  i = index of the request in the trace.
 //   decision bit0 = server started, bit1 = device started, bit2 = device won.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void dispatch_pair(const disco_policy& p, int l, float s, float d,
+__device__ __forceinline__ void dispatch_pair(const disco_policy& p, int l, float s, float d, i64 i,
                                               unsigned& decision, float& ttft)
 {
+    if (p.mode >= DISCO_MODE_STOCH_SERVER) {
+        const bool constrained = route_uniform(p.l_mid, i) < p.beta;
+        const bool to_server = (p.mode == DISCO_MODE_STOCH_SERVER) ? constrained : !constrained;
+        decision = to_server ? 1u : 6u;
+        ttft = to_server ? s : d;
+        return;
+    }
     // device-constrained wait (Eq. 1 united with Alg. 2's step map)
     float ramp = p.beta * (float)l;
     float w = (ramp < p.w_tail) ? ramp : p.w_tail;     // a NaN ramp falls through to w_tail

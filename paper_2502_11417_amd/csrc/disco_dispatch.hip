@@ -177,7 +177,8 @@ __device__ __forceinline__ void finish_columns(DispPartial* totals, int P, const
 // garbage nobody reads) and every l, n of the batch below 2^24, so the batch
 // totals fit 32-bit registers.
 template <int G, int MODE, int NEED, bool RAGGED>
-__device__ __forceinline__ void batch_pairs_fast(const Staged* __restrict__ st, int sub, int cnt, const disco_policy& p, ColTotals& t)
+__device__ __forceinline__ void batch_pairs_fast(const Staged* __restrict__ st, int sub, int cnt, i64 base, const disco_policy& p,
+                                                 ColTotals& t)
 {
     unsigned sp = 0, dp = 0, dd = 0, ns = 0, nw = 0;
     double ts = 0.0;
@@ -185,7 +186,7 @@ __device__ __forceinline__ void batch_pairs_fast(const Staged* __restrict__ st, 
 #pragma unroll 8
     for (int it = 0; it < G; ++it) {
         const Staged r = st[sub * G + it];
-        PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d);
+        PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d, base + sub * G + it);
         if (RAGGED) {                                  // requests past the end of the trace count for nothing
             const bool v = sub * G + it < cnt;
             e.srv_started = e.srv_started && v; e.dev_started = e.dev_started && v; e.dev_win = e.dev_win && v;
@@ -211,13 +212,13 @@ __device__ __forceinline__ void batch_pairs_fast(const Staged* __restrict__ st, 
 
 // General form: ragged last batch or huge lengths; everything in 64 bit, every update masked.
 template <int G>
-__device__ __forceinline__ void batch_pairs_slow(const Staged* __restrict__ st, int sub, int cnt, const disco_policy& p, bool colv,
-                                                 int mode, ColTotals& t)
+__device__ __forceinline__ void batch_pairs_slow(const Staged* __restrict__ st, int sub, int cnt, i64 base, const disco_policy& p,
+                                                 bool colv, int mode, ColTotals& t)
 {
     for (int it = 0; it < G; ++it) {
         const int src = sub * G + it;
         const Staged r = st[src];
-        const PairResult e = pair_eval<2>(p, r.l, r.s, r.d);
+        const PairResult e = pair_eval<2>(p, r.l, r.s, r.d, base + src);
         const bool v = colv && src < cnt;
         if (mode != 1) t.s_pre += (v && e.srv_started) ? (u64)r.l : 0ull;
         if (mode != 0) { t.d_pre += (v && e.dev_started) ? (u64)r.l : 0ull; t.started += (v && e.dev_started) ? 1ull : 0ull; }
@@ -231,15 +232,15 @@ __device__ __forceinline__ void batch_pairs_slow(const Staged* __restrict__ st, 
 }
 
 template <int G, int MODE>
-__device__ __forceinline__ void batch_pairs_need(const Staged* __restrict__ st, int sub, int cnt, const disco_policy& p, int need,
-                                                 ColTotals& t)
+__device__ __forceinline__ void batch_pairs_need(const Staged* __restrict__ st, int sub, int cnt, i64 base, const disco_policy& p,
+                                                 int need, ColTotals& t)
 {
     if (cnt == 64) {
-        if (need == 0) batch_pairs_fast<G, MODE, 0, false>(st, sub, cnt, p, t);
-        else if (need == 1) batch_pairs_fast<G, MODE, 1, false>(st, sub, cnt, p, t);
-        else batch_pairs_fast<G, MODE, 2, false>(st, sub, cnt, p, t);
+        if (need == 0) batch_pairs_fast<G, MODE, 0, false>(st, sub, cnt, base, p, t);
+        else if (need == 1) batch_pairs_fast<G, MODE, 1, false>(st, sub, cnt, base, p, t);
+        else batch_pairs_fast<G, MODE, 2, false>(st, sub, cnt, base, p, t);
     } else {
-        batch_pairs_fast<G, MODE, 2, true>(st, sub, cnt, p, t);
+        batch_pairs_fast<G, MODE, 2, true>(st, sub, cnt, base, p, t);
     }
 }
 
@@ -274,11 +275,11 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
         // the staging area is private to the wave: no workgroup barrier needed
         __builtin_amdgcn_wave_barrier();
         if (small) {
-            if (mode == 0) batch_pairs_need<G, 0>(st, sub, cnt, p, fin.need, t);
-            else if (mode == 1) batch_pairs_need<G, 1>(st, sub, cnt, p, fin.need, t);
-            else batch_pairs_need<G, 2>(st, sub, cnt, p, fin.need, t);
+            if (mode == 0) batch_pairs_need<G, 0>(st, sub, cnt, b * 64, p, fin.need, t);
+            else if (mode == 1) batch_pairs_need<G, 1>(st, sub, cnt, b * 64, p, fin.need, t);
+            else batch_pairs_need<G, 2>(st, sub, cnt, b * 64, p, fin.need, t);
         } else {
-            batch_pairs_slow<G>(st, sub, cnt, p, colv, mode, t);
+            batch_pairs_slow<G>(st, sub, cnt, b * 64, p, colv, mode, t);
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -320,7 +321,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc1(TraceView tr, const 
     __shared__ __align__(16) unsigned char smem[DP_BLOCK * sizeof(DispPartial)];
     u64* sh = reinterpret_cast<u64*>(smem);
     const disco_policy p = pol[0];
-    const int mode = p.mode == DISCO_MODE_SERVER_CONSTRAINED ? 0 : 1;
+    const int mode = p.mode == DISCO_MODE_SERVER_CONSTRAINED ? 0 : (p.mode == DISCO_MODE_DEVICE_CONSTRAINED ? 1 : 2);
     ColTotals t{0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
     u64 tot_n = 0;
     const i64 ngroups = (tr.n_req + 3) >> 2;
@@ -352,7 +353,8 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc1(TraceView tr, const 
         for (int q = 0; q < 4; ++q) {
             const bool v = i0 + q < tr.n_req;
             const float d = __fmaf_rn((float)l[q], k[q], tr.c);
-            const PairResult e = (mode == 0) ? pair_eval<0>(p, l[q], s[q], d) : pair_eval<1>(p, l[q], s[q], d);
+            const PairResult e = (mode == 0) ? pair_eval<0>(p, l[q], s[q], d, i0 + q)
+                                             : (mode == 1 ? pair_eval<1>(p, l[q], s[q], d, i0 + q) : pair_eval<2>(p, l[q], s[q], d, i0 + q));
             t.s_pre += (v && e.srv_started) ? (u64)l[q] : 0ull;
             t.d_pre += (v && e.dev_started) ? (u64)l[q] : 0ull;
             if (fin.need >= 1) {
@@ -407,7 +409,7 @@ __global__ __launch_bounds__(256) void k_dispatch_mat(TraceView tr, const disco_
         const float d = __fmaf_rn((float)l, k, tr.c);
         for (int j = 0; j < P; ++j) {
             unsigned dec; float t;
-            dispatch_pair(sp[j], l, s, d, dec, t);
+            dispatch_pair(sp[j], l, s, d, i, dec, t);
             if (decision) decision[(size_t)j * tr.n_req + i] = (uint8_t)dec;
             if (ttft) ttft[(size_t)j * tr.n_req + i] = t;
         }

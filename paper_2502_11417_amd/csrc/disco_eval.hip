@@ -180,6 +180,34 @@ __global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, 
     out[c] = st;
 }
 
+// Mean over the runs of a group of columns: floating-point fields in fp64, summed in run order; integer
+// totals summed; ranks taken from the first run.
+__global__ void k_average_runs(const disco_stats* __restrict__ in, int groups, int runs, disco_stats* __restrict__ out)
+{
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= groups) return;
+    const disco_stats* r = in + (size_t)g * runs;
+    disco_stats o;
+    memset(&o, 0, sizeof(o));
+    double d[7] = {0, 0, 0, 0, 0, 0, 0}, q[2 * DISCO_MAX_Q];
+    for (int k = 0; k < 2 * DISCO_MAX_Q; ++k) q[k] = 0.0;
+    for (int k = 0; k < DISCO_MAX_Q; ++k) { o.ttft_rank[k] = r[0].ttft_rank[k]; o.tbt_rank[k] = r[0].tbt_rank[k]; }
+    for (int j = 0; j < runs; ++j) {
+        const disco_stats s = r[j];
+        d[0] += s.mean_ttft; d[1] += s.mean_tbt; d[2] += s.server_cost; d[3] += s.device_energy;
+        d[4] += s.device_cost; d[5] += s.total_cost; d[6] += s.mean_delay_num;
+        o.s_pre += s.s_pre; o.s_dec += s.s_dec; o.d_pre += s.d_pre; o.d_dec += s.d_dec;
+        o.n_req += s.n_req; o.tbt_count += s.tbt_count; o.n_migrated += s.n_migrated;
+        o.n_dev_started += s.n_dev_started; o.n_dev_win += s.n_dev_win;
+        for (int k = 0; k < DISCO_MAX_Q; ++k) { q[k] += (double)s.ttft_q[k]; q[DISCO_MAX_Q + k] += (double)s.tbt_q[k]; }
+    }
+    const double n = (double)runs;
+    o.mean_ttft = d[0] / n; o.mean_tbt = d[1] / n; o.server_cost = d[2] / n; o.device_energy = d[3] / n;
+    o.device_cost = d[4] / n; o.total_cost = d[5] / n; o.mean_delay_num = d[6] / n;
+    for (int k = 0; k < DISCO_MAX_Q; ++k) { o.ttft_q[k] = (float)(q[k] / n); o.tbt_q[k] = (float)(q[DISCO_MAX_Q + k] / n); }
+    out[g] = o;
+}
+
 // ----------------------------------------------------------- search setup --
 
 __global__ void k_search_init(SpecTable t, int n, SearchState* st, disco_policy* pol)
@@ -231,8 +259,9 @@ int check_policies(const disco_policy* pol, int P)
     if (!pol) return DISCO_ERR_NULL;
     if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
     for (int j = 0; j < P; ++j) {
-        if (pol[j].mode != DISCO_MODE_SERVER_CONSTRAINED && pol[j].mode != DISCO_MODE_DEVICE_CONSTRAINED)
-            return DISCO_ERR_RANGE;
+        if (pol[j].mode < DISCO_MODE_SERVER_CONSTRAINED || pol[j].mode > DISCO_MODE_STOCH_DEVICE) return DISCO_ERR_RANGE;
+        if (pol[j].mode >= DISCO_MODE_STOCH_SERVER && !(pol[j].beta >= 0.0f && pol[j].beta <= 1.0f))
+            return DISCO_ERR_RANGE;                         // the routing probability of a stochastic baseline
         if (pol[j].mig_mode != DISCO_MIG_NONE && pol[j].mig_mode != DISCO_MIG_LAG && pol[j].mig_mode != DISCO_MIG_BUFFER)
             return DISCO_ERR_RANGE;
         if (pol[j].w_mid != pol[j].w_mid || pol[j].beta != pol[j].beta || pol[j].w_tail != pol[j].w_tail)
@@ -492,6 +521,17 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     return DISCO_OK;
 }
 
+extern "C" int32_t disco_average_runs(const disco_stats* in, int32_t groups, int32_t runs, disco_stats* out, void* stream_)
+{
+    if (!in || !out) return DISCO_ERR_NULL;
+    if (groups < 0 || runs < 1) return DISCO_ERR_SHAPE;
+    if (groups == 0) return DISCO_OK;
+    hipLaunchKernelGGL(k_average_runs, dim3((unsigned)((groups + 63) / 64)), dim3(64), 0, (hipStream_t)stream_, in, groups, runs,
+                       out);
+    DISCO_HIP(hipGetLastError());
+    return DISCO_OK;
+}
+
 extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cost_params* cost,
                                        const disco_policy* templ, const disco_search_spec* spec, int32_t n_search,
                                        disco_search_out* out, disco_policy* pol_out, void* ws_, size_t ws_bytes,
@@ -505,6 +545,8 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
     if (n_steps < 1 || n_steps > DISCO_MAX_STEPS) return DISCO_ERR_SHAPE;
     SpecTable t;
     memset(&t, 0, sizeof(t));
+    for (int j = 0; j < n_search && !is_device_pointer(templ); ++j)           // the stochastic baselines have no searched parameter
+        if (templ[j].mode >= DISCO_MODE_STOCH_SERVER) return DISCO_ERR_RANGE;
     for (int j = 0; j < n_search; ++j) {
         if (spec[j].n_steps != n_steps) return DISCO_ERR_SHAPE;
         if (spec[j].which_param != DISCO_PARAM_L_TH && spec[j].which_param != DISCO_PARAM_W_TAIL) return DISCO_ERR_RANGE;

@@ -14,29 +14,6 @@
 
 namespace {
 
-struct Words { unsigned w0, w1, w2, w3; };
-
-__device__ __forceinline__ Words philox4x32_10(u64 seed, u64 index, unsigned field)
-{
-    unsigned c0 = (unsigned)index, c1 = (unsigned)(index >> 32), c2 = field, c3 = 0u;
-    unsigned k0 = (unsigned)seed, k1 = (unsigned)(seed >> 32);
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-        unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
-        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
-        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
-    }
-    return Words{c0, c1, c2, c3};
-}
-
-// 23 random bits to a uniform on (0,1): (x >> 9 + 1/2) 2^-23, exact in fp32.
-__device__ __forceinline__ float u23(unsigned x)
-{
-    return __fmaf_rn((float)(x >> 9), 0x1p-23f, 0x1p-24f);
-}
-
 // ln of a positive normal number: x = 2^e m with m in (sqrt(1/2), sqrt(2)],
 // ln m = 2 atanh(s), s = (m - 1) / (m + 1), odd series through s^11.
 __device__ __forceinline__ float gen_ln(float x)

@@ -16,9 +16,9 @@ struct Staged { int l; float s; int n; float d; };      // 16 bytes, one per req
 struct PairResult { bool srv_started, dev_started, dev_win; float ttft; };
 
 // MODE 0: every column is server-constrained (Alg. 3), 1: every column is
-// device-constrained (Alg. 2 / Eq. 1), 2: mixed table.
+// device-constrained (Alg. 2 / Eq. 1), 2: mixed table or stochastic baseline columns.
 template <int MODE>
-__device__ __forceinline__ PairResult pair_eval(const disco_policy& p, int l, float s, float d)
+__device__ __forceinline__ PairResult pair_eval(const disco_policy& p, int l, float s, float d, i64 i)
 {
     PairResult r;
     if (MODE == 0) {
@@ -39,7 +39,7 @@ __device__ __forceinline__ PairResult pair_eval(const disco_policy& p, int l, fl
         r.ttft = r.dev_win ? x : s;
     } else {
         unsigned dec; float t;
-        dispatch_pair(p, l, s, d, dec, t);
+        dispatch_pair(p, l, s, d, i, dec, t);
         r.srv_started = (dec & 1u) != 0u;
         r.dev_started = (dec & 2u) != 0u;
         r.dev_win = (dec & 4u) != 0u;
@@ -50,9 +50,10 @@ __device__ __forceinline__ PairResult pair_eval(const disco_policy& p, int l, fl
 
 __device__ __forceinline__ int table_mode(const disco_policy& p, bool colv)
 {
-    const bool any_d = __ballot(colv && p.mode != DISCO_MODE_SERVER_CONSTRAINED) != 0ull;
+    const bool any_d = __ballot(colv && p.mode == DISCO_MODE_DEVICE_CONSTRAINED) != 0ull;
     const bool any_s = __ballot(colv && p.mode == DISCO_MODE_SERVER_CONSTRAINED) != 0ull;
-    return any_d ? (any_s ? 2 : 1) : 0;
+    const bool any_x = __ballot(colv && p.mode >= DISCO_MODE_STOCH_SERVER) != 0ull;
+    return any_x ? 2 : (any_d ? (any_s ? 2 : 1) : 0);
 }
 
 }  // namespace

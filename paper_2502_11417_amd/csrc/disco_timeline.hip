@@ -327,11 +327,12 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
             u64 m0 = 0ull, m1 = 0ull, m2 = 0ull, m3 = 0ull, m4 = 0ull;
             for (int j = 0; j < P; ++j) {
                 unsigned dec; float t;
-                dispatch_pair(spol[j], l_v, s_v, d_v, dec, t);
+                dispatch_pair(spol[j], l_v, s_v, d_v, ia, dec, t);
                 const bool dev = (dec & 4u) != 0u;
                 const int mg = spol[j].mig_mode;
                 const bool buf = mg == DISCO_MIG_BUFFER &&
-                                 (dev ? spol[j].mode == DISCO_MODE_DEVICE_CONSTRAINED : spol[j].mode == DISCO_MODE_SERVER_CONSTRAINED);
+                                 (dev ? (spol[j].mode == DISCO_MODE_DEVICE_CONSTRAINED || spol[j].mode == DISCO_MODE_STOCH_DEVICE)
+                                      : (spol[j].mode == DISCO_MODE_SERVER_CONSTRAINED || spol[j].mode == DISCO_MODE_STOCH_SERVER));
                 const u64 bit = va ? (1ull << j) : 0ull;
                 m4 |= (dev && buf) ? bit : 0ull;
                 m0 |= (dev && !buf) ? bit : 0ull;

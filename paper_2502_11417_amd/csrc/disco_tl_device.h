@@ -71,12 +71,12 @@ __device__ __forceinline__ void load4(const float* __restrict__ arr, i64 g, i64 
 // The three column sets of a request (lane = request): columns whose source is
 // the device [0], the server without hand-off [1], the server with the lag
 // trigger [2].
-__device__ __forceinline__ void request_sets(const disco_policy* sp, int P, int l, float s, float d, u64 m[3])
+__device__ __forceinline__ void request_sets(const disco_policy* sp, int P, int l, float s, float d, i64 i, u64 m[3])
 {
     u64 m0 = 0ull, m1 = 0ull, m2 = 0ull;
     for (int j = 0; j < P; ++j) {
         unsigned dec; float t;
-        dispatch_pair(sp[j], l, s, d, dec, t);
+        dispatch_pair(sp[j], l, s, d, i, dec, t);
         const bool dev = (dec & 4u) != 0u;
         const bool lagm = sp[j].mig_mode == DISCO_MIG_LAG;
         const u64 bit = 1ull << j;

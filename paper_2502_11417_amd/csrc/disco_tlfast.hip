@@ -204,7 +204,7 @@ __device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_pol
         if (tr.off) b.off = tr.off[i];
         if (tr.tbt) b.gap = tr.tbt[i];
     }
-    request_sets(spol, P, b.l, s, __fmaf_rn((float)b.l, b.k, tr.c), b.m);
+    request_sets(spol, P, b.l, s, __fmaf_rn((float)b.l, b.k, tr.c), i, b.m);
     if (!v) b.m[0] = b.m[1] = b.m[2] = 0ull;
     return b;
 }

@@ -130,7 +130,7 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
             const float k = tr.k ? tr.k[i] : tr.k_s;
             const float gd = tr.g ? tr.g[i] : tr.g_s;
             const float gap = tr.tbt ? tr.tbt[i] : 0.0f;
-            request_sets(sp, P, l, s, __fmaf_rn((float)l, k, tr.c), m);
+            request_sets(sp, P, l, s, __fmaf_rn((float)l, k, tr.c), i, m);
             const bool short_n = n <= DISCO_PP_NMAX;
             walked[0] = !(short_n && pure_pacing(true, gd, tau));
             walked[1] = walked[2] = !(short_n && pure_pacing(tr.arr == nullptr, gap, tau));

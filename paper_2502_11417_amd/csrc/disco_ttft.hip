@@ -112,7 +112,7 @@ __device__ __forceinline__ void pair_body(const TraceView& tr, const disco_polic
             for (int it = 0; it < G; ++it) {
                 const int src = sub * G + it;
                 const Staged r = st[src];
-                const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d);
+                const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d, b * 64 + src);
                 if (src < cnt) {
                     const unsigned key = f2u(e.ttft) - g.minb;
                     const unsigned dgt = (key >> shift) & dmask;

@@ -83,6 +83,11 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, 256, 256, 16, None) == B.ERR["workspace"]
     bad = (B.CPolicy * 1)(B.CPolicy(7, 0, -1, 0.0, 1.0, 1.0, 0, 0))
     assert lib.disco_eval_dispatch(C.byref(tr), bad, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
+    for b in (1.5, -0.1, float("inf")):                                      # routing probability of a stochastic baseline
+        bad = (B.CPolicy * 1)(B.CPolicy(2, 0, 0, 0.0, b, 0.0, 0, 0))
+        assert lib.disco_eval_dispatch(C.byref(tr), bad, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
+    bad = (B.CPolicy * 1)(B.CPolicy(4, 0, -1, 0.0, 1.0, 1.0, 0, 0))          # unknown mode
+    assert lib.disco_eval_dispatch(C.byref(tr), bad, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
     bad = (B.CPolicy * 1)(B.CPolicy(0, 0, -1, 0.0, 1.0, 1.0, 3, 0))          # unknown migration mode
     assert lib.disco_eval_dispatch(C.byref(tr), bad, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
     tr.n_req = -1
@@ -99,6 +104,10 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     spec = (B.CSearchSpec * 1)(B.CSearchSpec(1, 2, 0, 0, 0.0, 5.0, 1.0))
     assert lib.disco_budget_search(C.byref(tr), C.byref(cost), pol, spec, 1, 256, None, 256, 1 << 30, None) == B.ERR["shape"]
     spec[0].n_steps = 4
+    stoch = (B.CPolicy * 1)(B.CPolicy(2, 0, 0, 0.0, 0.5, 0.0, 0, 0))         # a stochastic baseline has nothing to search
+    assert lib.disco_budget_search(C.byref(tr), C.byref(cost), stoch, spec, 1, 256, None, 256, 1 << 30, None) == B.ERR["range"]
+    assert lib.disco_average_runs(None, 1, 1, 256, None) == B.ERR["null"]
+    assert lib.disco_average_runs(256, 1, 0, 256, None) == B.ERR["shape"]
     spec[0].lo = 6.0
     assert lib.disco_budget_search(C.byref(tr), C.byref(cost), pol, spec, 1, 256, None, 256, 1 << 30, None) == B.ERR["range"]
     g = B.CGenParams()

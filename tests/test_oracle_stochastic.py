@@ -107,3 +107,22 @@ def test_timelines_and_hand_offs_follow_the_routed_endpoint(oracle):
     for f in ("mig_idx", "n_src_tok", "t_last"):
         assert (m[f][0][srv] == m[f][1][srv]).all() and (m[f][0][~srv] == m[f][2][~srv]).all(), f
     assert (m["mig_idx"][0][~srv] == -1).all() and (m["mig_idx"][0][srv] >= 0).sum() > 5
+
+
+def test_average_over_runs_hand_computed(oracle):
+    """Two groups of three runs with values chosen so that every mean is exact."""
+    def rec(mean_ttft, cost, s_pre, q):
+        return {"mean_ttft": mean_ttft, "mean_tbt": 0.25, "server_cost": cost, "device_energy": 0.0, "device_cost": 0.0,
+                "total_cost": cost, "s_pre": s_pre, "s_dec": 1, "d_pre": 2, "d_dec": 3, "n_req": 10, "tbt_count": 4,
+                "n_migrated": 0, "n_dev_started": 5, "n_dev_win": 6, "ttft_rank": [5, 10], "tbt_rank": [2, 4],
+                "ttft_q": [np.float32(q), np.float32(2 * q)], "tbt_q": [np.float32(0.5), np.float32(0.75)]}
+    runs = [rec(1.0, 3.0, 7, 0.5), rec(2.0, 6.0, 8, 1.5), rec(6.0, 0.0, 9, 2.5),
+            rec(0.5, 1.0, 1, 4.0), rec(0.5, 1.0, 1, 4.0), rec(0.5, 1.0, 1, 4.0)]
+    a = oracle.average_runs(runs, 3)
+    assert len(a) == 2
+    assert a[0]["mean_ttft"] == 3.0 and a[0]["server_cost"] == 3.0 and a[0]["total_cost"] == 3.0 and a[0]["mean_tbt"] == 0.25
+    assert a[0]["s_pre"] == 24 and a[0]["n_req"] == 30 and a[0]["d_dec"] == 9
+    assert a[0]["ttft_q"] == [np.float32(1.5), np.float32(3.0)] and a[0]["ttft_rank"] == [5, 10]
+    assert a[1]["mean_ttft"] == 0.5 and a[1]["ttft_q"] == [np.float32(4.0), np.float32(8.0)] and a[1]["s_pre"] == 3
+    same = oracle.average_runs(runs[3:], 1)                    # one run per group: the record itself
+    assert all(same[i]["mean_ttft"] == runs[3 + i]["mean_ttft"] and same[i]["ttft_q"] == runs[3 + i]["ttft_q"] for i in range(3))
