@@ -8,7 +8,7 @@ the TBT order statistics.  The headline workload is configuration 1
 (10^6 requests x 64 budget levels, dispatch only); the other configurations
 are reported as extra fields of the same JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1] [--extras config2,config3,config4,config4buffer]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1] [--extras config2,config3,config4,config4buffer,config1stoch]
     python bench.py --copy-calibration BYTES     # one plain device copy of known size, for scaling HBM counters
 """
 from __future__ import annotations
@@ -45,7 +45,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config1")
-    ap.add_argument("--extras", default="config2,config3,config4,config4buffer")
+    ap.add_argument("--extras", default="config2,config3,config4,config4buffer,config1stoch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-reps", type=int, default=20)
     ap.add_argument("--copy-calibration", type=int, default=0)
@@ -84,8 +84,9 @@ def main() -> int:
     class Workload:
         """Resident trace + everything a step needs, allocated once."""
 
-        def __init__(self, idx, buffer=False):
+        def __init__(self, idx, buffer=False, stoch=False):
             self.idx = idx
+            self.stoch = stoch
             self.cfg = DI.config(idx)
             g = self.cfg["gen"]
             t0 = time.perf_counter()
@@ -111,6 +112,13 @@ def main() -> int:
             self.sout = torch.zeros(self.P * D.binding.SEARCH_DTYPE.itemsize, dtype=torch.uint8, device="cuda")
             self.pol_out = torch.zeros(self.P * 32, dtype=torch.uint8, device="cuda")
             self.pols = None
+            if stoch:
+                # the Stoch-S baseline of Sec. 5.1 on the same budget grid: 8 levels x 8 runs, averaged over the runs
+                self.runs = 8
+                self.levels = DI.budget_levels(self.P // self.runs)
+                self.pols = [D.Policy(mode=D.MODE_STOCH_S, beta=num / den, l_mid=run, mig_mode=mig)
+                             for num, den in self.levels for run in range(self.runs)]
+                self.avg = torch.zeros(len(self.levels) * 256, dtype=torch.uint8, device="cuda")
 
         def search(self):
             """Budget levels -> length thresholds; the found columns stay on the device."""
@@ -129,17 +137,21 @@ def main() -> int:
                           hi=s["hi"], target=s["budget_frac"] * c_all)], ws=self.ws)
             # budget levels -> thresholds (device-resident bisection), then evaluate the found columns
             # straight from the device-resident policy table: no host round trip inside a step
-            self.search()
+            if not self.stoch:
+                self.search()
             tau = cfg["tau"] if cfg["timelines"] else None
             D.disco_eval_dispatch(self.trace, self.pols, ws=self.ws, acc=self.acc)
             if tau is not None:
                 D.disco_eval_migration(self.trace, tau, cfg["kappa"], self.pols, ws=self.ws, acc=self.acc,
                                        cost=cfg["cost"])
-            return D.disco_reduce_stats(self.trace, cfg["cost"], self.pols, self.acc, tau=tau, kappa=cfg["kappa"],
-                                        ws=self.ws, out=self.stats, mig_cost=cfg["cost"])
+            st = D.disco_reduce_stats(self.trace, cfg["cost"], self.pols, self.acc, tau=tau, kappa=cfg["kappa"],
+                                      ws=self.ws, out=self.stats, mig_cost=cfg["cost"])
+            if self.stoch:
+                return D.disco_average_runs(st, len(self.levels), self.runs, out=self.avg)
+            return st
 
         def time_steps(self, steps, warmup):
-            if self.idx != 3:
+            if self.idx != 3 and not self.stoch:
                 self.search()
             for _ in range(warmup):
                 self.step()
@@ -210,18 +222,25 @@ def main() -> int:
 
     extras = {}
     for name in [e for e in args.extras.split(",") if e and e != args.workload]:
-        buffer = name.endswith("buffer")
-        k = int(name.replace("config", "").replace("buffer", ""))
+        buffer, stoch = name.endswith("buffer"), name.endswith("stoch")
+        k = int(name.replace("config", "").replace("buffer", "").replace("stoch", ""))
         del w
         torch.cuda.empty_cache()
         log(f"[bench] extra {name} ...")
-        w = Workload(k, buffer=buffer)
+        w = Workload(k, buffer=buffer, stoch=stoch)
         steps = 3 if k == 4 else 10
         s = w.time_steps(steps, 1)
         ex = {"n_req": w.N, "policy_columns": w.P, "token_events": w.T, "ms_per_step": s * 1e3}
         if k == 3:
             ex["pairs_per_s"] = w.N * w.cfg["search"]["steps"] / s
             ex["hbm_frac_of_peak"] = 12.0 * w.N * (w.cfg["search"]["steps"] + 1) / s / 1e9 / HBM_PEAK_GBS
+        elif not w.cfg["timelines"]:
+            ex["pairs_per_s"] = w.N * w.P / s
+            if stoch:
+                st = D.stats_to_host(w.step(), len(w.levels))
+                ex["runs"] = w.runs
+                ex["mean_ttft_by_level"] = [float(x) for x in st["mean_ttft"]]
+                ex["p99_ttft_by_level"] = [float(x[1]) for x in st["ttft_q"]]
         else:
             ex["pairs_per_s"] = w.N * w.P / s
             ex["token_events_per_s_raw"] = w.T / s
