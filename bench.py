@@ -221,7 +221,19 @@ def main() -> int:
         result["cpu_baseline"] = cpu_baseline(idx)
 
     extras = {}
+    if idx != 3:
+        # closed-form policy solves (Alg. 3 and Alg. 2) for the budget grid of the timed workload: half the columns each
+        half = max(1, w.P // 2)
+        sspecs = [dict(mode=D.MODE_S, b=(j, max(half - 1, 1))) for j in range(half)] + \
+                 [dict(mode=D.MODE_D, b=(j, max(half - 1, 1)), alpha=(1, 10)) for j in range(half)]
+        spol = torch.zeros(len(sspecs) * 32, dtype=torch.uint8, device="cuda")
+        sout = torch.zeros(len(sspecs) * D.binding.SOLVE_DTYPE.itemsize, dtype=torch.uint8, device="cuda")
+        t_s = event_time(lambda: D.disco_solve_policy(w.trace, sspecs, ws=w.ws, pol_out=spol, out=sout), 10)
+        extras["policy_solve"] = {"workload": args.workload, "columns": len(sspecs), "ms": t_s * 1e3,
+                                  "what": "length table + per-column plan + 4-pass multi-rank selection over the server TTFTs"}
     for name in [e for e in args.extras.split(",") if e and e != args.workload]:
+        if not name.startswith("config"):
+            continue
         buffer, stoch = name.endswith("buffer"), name.endswith("stoch")
         k = int(name.replace("config", "").replace("buffer", "").replace("stoch", ""))
         del w

@@ -331,6 +331,57 @@ int32_t disco_reduce_stats(const disco_trace* trace /*host*/, const disco_cost_p
 int32_t disco_average_runs(const disco_stats* in /*device*/, int32_t groups, int32_t runs,
                            disco_stats* out /*device*/, void* stream);
 
+/* ---- closed-form policy solves ------------------------------------------ */
+
+/* One column to solve.  b = b_num / b_den in [0, 1] is the budget ratio: the
+ * constrained endpoint's share of the prompt tokens (Sec. 4.2); alpha = a_num /
+ * a_den in (0, 1) the tail ratio of Alg. 2 (ignored for Alg. 3).  Denominators
+ * in [1, 32768], so that every budget comparison is exact in 128-bit integers. */
+typedef struct disco_solve_spec {
+    int32_t mode;            /* DISCO_MODE_SERVER_CONSTRAINED: Alg. 3; DISCO_MODE_DEVICE_CONSTRAINED: Alg. 2 */
+    int32_t b_num, b_den;
+    int32_t a_num, a_den;
+    int32_t mig_mode;        /* copied into the policy record */
+    int32_t reserved[2];
+} disco_solve_spec;
+
+/* What the solve used, per column (device). */
+typedef struct disco_solve_out {
+    int64_t rank_tail;        /* Alg. 2: rank of the server TTFT taken as w_tail (0: wait 0) */
+    int64_t rank_mid;         /* Alg. 2: rank of the partial wait (0: no partial length) */
+    int64_t zero_wait_tokens; /* Alg. 2: prompt tokens of the lengths that start the device at once;
+                               * Alg. 3: prompt tokens of the device-only prompts */
+    int64_t total_tokens;
+    int32_t status;           /* 1: the trace has prompts of 32772 tokens or more, which the length table
+                               * does not hold: the record is not the solve's answer */
+    int32_t reserved[3];
+} disco_solve_out;
+
+/* Policy columns for budget levels as the paper's dispatch controller solves
+ * them (Sec. 4.2), with the trace's own distributions: p(l) = requests per
+ * prompt length, F = empirical distribution of the server TTFT, taken as
+ * independent of each other; F^-1(q) is the order statistic of rank
+ * ceil(q n_req), rank 0 gives 0.
+ * Alg. 3 / Eq. 3: l_th = the smallest L such that the prompts of length >= L
+ *   hold at most b of the prompt tokens (they race; shorter ones run on the
+ *   device alone).
+ * Alg. 2: w_tail = F^-1(1 - min(alpha, b)); if b <= alpha every length waits
+ *   w_tail.  Otherwise (b - alpha) x total tokens are spent in ascending
+ *   order of length: a length costs (1 - alpha) x its tokens and gets wait 0
+ *   (l_th = the last such length); the first length that is not affordable,
+ *   l_mid, waits w_mid = F^-1((1 - alpha) - left / its tokens) -- the extra
+ *   device prefill at that wait is what is left; the printed equation for this
+ *   wait has the opposite monotonic direction and is read this way.  The
+ *   record has beta = +inf (step map).
+ * pol_out: device, n records; out: device, n records, nullable.  Prompt
+ * lengths must be positive and below 32772 (out.status otherwise), server
+ * TTFTs non-negative.  Asynchronous.  Errors: NULL, SHAPE (n outside [1,
+ * DISCO_MAX_COLS]), RANGE (unknown mode, ratios outside their ranges,
+ * denominators outside [1, 32768]), WORKSPACE, HIP. */
+int32_t disco_solve_policy(const disco_trace* trace /*host*/, const disco_solve_spec* spec /*host*/, int32_t n,
+                           disco_policy* pol_out /*device*/, disco_solve_out* out /*device, nullable*/,
+                           void* ws /*device*/, size_t ws_bytes, void* stream);
+
 /* ---- budget search ------------------------------------------------------ */
 
 #define DISCO_PARAM_L_TH    0   /* integer bisection on disco_policy.l_th */

@@ -100,6 +100,13 @@ class CSearchSpec(C.Structure):
                 ("reserved", C.c_int32), ("lo", C.c_double), ("hi", C.c_double), ("target", C.c_double)]
 
 
+class CSolveSpec(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("b_num", C.c_int32), ("b_den", C.c_int32), ("a_num", C.c_int32),
+                ("a_den", C.c_int32), ("mig_mode", C.c_int32), ("reserved", C.c_int32 * 2)]
+
+
+SOLVE_DTYPE = np.dtype([("rank_tail", "<i8"), ("rank_mid", "<i8"), ("zero_wait_tokens", "<i8"), ("total_tokens", "<i8"),
+                        ("status", "<i4"), ("reserved", "<i4", (3,))])
 ACCUM_DTYPE = np.dtype([
     ("s_pre", "<i8"), ("s_dec", "<i8"), ("d_pre", "<i8"), ("d_dec", "<i8"),
     ("n_dev_started", "<i8"), ("n_dev_win", "<i8"), ("ttft_sum", "<f8"),
@@ -123,7 +130,7 @@ assert ACCUM_DTYPE.itemsize == 128 and STATS_DTYPE.itemsize == 256 and POLICY_DT
 assert C.sizeof(CPolicy) == 32 and C.sizeof(CSearchSpec) == 40
 
 EXPORTS = ["disco_gen_trace", "disco_eval_dispatch", "disco_eval_migration", "disco_reduce_stats",
-           "disco_average_runs", "disco_budget_search", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
+           "disco_average_runs", "disco_solve_policy", "disco_budget_search", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
            "disco_version"]
 
 _lib.disco_strerror.restype = C.c_char_p
@@ -146,6 +153,9 @@ _lib.disco_reduce_stats.argtypes = [C.POINTER(CTrace), C.POINTER(CCost), C.POINT
                                     C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.disco_average_runs.restype = C.c_int32
 _lib.disco_average_runs.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+_lib.disco_solve_policy.restype = C.c_int32
+_lib.disco_solve_policy.argtypes = [C.POINTER(CTrace), C.POINTER(CSolveSpec), C.c_int32, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.disco_budget_search.restype = C.c_int32
 _lib.disco_budget_search.argtypes = [C.POINTER(CTrace), C.POINTER(CCost), C.POINTER(CPolicy),
                                      C.POINTER(CSearchSpec), C.c_int32, C.c_void_p, C.c_void_p,
@@ -364,6 +374,32 @@ def disco_average_runs(stats: torch.Tensor, groups: int, runs: int, out: torch.T
         out = torch.zeros(max(groups, 1) * 256, dtype=torch.uint8, device=stats.device)
     _check(_lib.disco_average_runs(stats.data_ptr(), groups, runs, out.data_ptr(), _stream()), "disco_average_runs")
     return out
+
+
+def disco_solve_policy(trace: Trace, specs, ws: torch.Tensor | None = None, pol_out: torch.Tensor | None = None,
+                       out: torch.Tensor | None = None) -> dict:
+    """specs: dicts with mode, b = (num, den), alpha = (num, den) (Alg. 2 only), optional mig_mode."""
+    n = len(specs)
+    dev = trace.prompt_len.device if trace.prompt_len is not None else "cuda"
+    if ws is None:
+        ws = workspace(trace.n_req, max(n, 1), dev)
+    sp = (CSolveSpec * max(n, 1))()
+    for j, s in enumerate(specs):
+        a = s.get("alpha", (0, 1))
+        sp[j] = CSolveSpec(int(s["mode"]), int(s["b"][0]), int(s["b"][1]), int(a[0]), int(a[1]), int(s.get("mig_mode", 0)))
+    if pol_out is None:
+        pol_out = torch.zeros(max(n, 1) * 32, dtype=torch.uint8, device=dev)
+    if out is None:
+        out = torch.zeros(max(n, 1) * SOLVE_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+    cs = trace.c_struct()
+    rc = _lib.disco_solve_policy(C.byref(cs), sp, n, pol_out.data_ptr(), out.data_ptr(), ws.data_ptr(), ws.numel(),
+                                 _stream())
+    _check(rc, "disco_solve_policy")
+    return {"pol_out": pol_out, "policies": DevicePolicies(pol_out, n), "out": out}
+
+
+def solve_to_host(out: torch.Tensor, n: int) -> np.ndarray:
+    return np.frombuffer(out.cpu().numpy().tobytes(), dtype=SOLVE_DTYPE, count=n)
 
 
 def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Tensor | None = None,

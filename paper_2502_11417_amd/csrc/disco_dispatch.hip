@@ -565,10 +565,10 @@ void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int 
     hipLaunchKernelGGL(k_dispatch_mat, dim3((unsigned)b), dim3(256), 0, stream, v, pol, P, decision, ttft);
 }
 
-// Tabulated threshold search (see k_len_hist).  `scratch` holds the workgroup slices, `table` nbins + 1 sums.
-void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsigned* scratch, size_t scratch_bytes,
-                               u64* table, u64* other, SearchState* st, disco_policy* pol, disco_search_out* sout,
-                               hipStream_t stream)
+// table[L] = prompt tokens of the requests of length >= L for L < nbins, table[nbins] = those of longer requests
+// (see k_len_hist).  `scratch` holds the workgroup slices; *other must be zero and is zero again afterwards.
+void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, size_t scratch_bytes, u64* table, u64* other,
+                            hipStream_t stream)
 {
     i64 blocks = (v.n_req + DP_BLOCK - 1) / DP_BLOCK;
     const i64 fit = (i64)(scratch_bytes / ((size_t)nbins * sizeof(unsigned)));
@@ -579,6 +579,14 @@ void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsi
     hipLaunchKernelGGL(k_len_reduce, dim3((unsigned)((nbins + 63) / 64)), dim3(256), 0, stream, nbins, (int)blocks, scratch,
                        table);
     hipLaunchKernelGGL(k_len_suffix, dim3(1), dim3(1024), 0, stream, nbins, table, other);
+}
+
+// Tabulated threshold search: the table, then every bisection step of every column from it.
+void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsigned* scratch, size_t scratch_bytes,
+                               u64* table, u64* other, SearchState* st, disco_policy* pol, disco_search_out* sout,
+                               hipStream_t stream)
+{
+    disco_launch_len_table(v, nbins, scratch, scratch_bytes, table, other, stream);
     hipLaunchKernelGGL(k_search_table, dim3(1), dim3(64), 0, stream, n_search, nbins, table, st, pol, sout);
 }
 

@@ -532,6 +532,34 @@ extern "C" int32_t disco_average_runs(const disco_stats* in, int32_t groups, int
     return DISCO_OK;
 }
 
+extern "C" int32_t disco_solve_policy(const disco_trace* trace, const disco_solve_spec* spec, int32_t n, disco_policy* pol_out,
+                                      disco_solve_out* out, void* ws_, size_t ws_bytes, void* stream_)
+{
+    int rc = check_trace(trace);
+    if (rc) return rc;
+    if (!spec || !pol_out) return DISCO_ERR_NULL;
+    if (n < 1 || n > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
+    for (int j = 0; j < n; ++j) {
+        const disco_solve_spec& s = spec[j];
+        if (s.mode != DISCO_MODE_SERVER_CONSTRAINED && s.mode != DISCO_MODE_DEVICE_CONSTRAINED) return DISCO_ERR_RANGE;
+        if (s.b_den < 1 || s.b_den > 32768 || s.b_num < 0 || s.b_num > s.b_den) return DISCO_ERR_RANGE;
+        if (s.mode == DISCO_MODE_DEVICE_CONSTRAINED &&
+            (s.a_den < 1 || s.a_den > 32768 || s.a_num <= 0 || s.a_num >= s.a_den))
+            return DISCO_ERR_RANGE;
+        if (s.mig_mode < DISCO_MIG_NONE || s.mig_mode > DISCO_MIG_BUFFER) return DISCO_ERR_RANGE;
+    }
+    rc = check_ws(ws_, ws_bytes, n);
+    if (rc) return rc;
+    char* ws = (char*)ws_;
+    const WsLayout L = disco_ws_layout(n);
+    if (disco_solve_state_bytes() > L.ghist - L.sel) return DISCO_ERR_WORKSPACE;      // the selection state region holds it
+    const TraceView v = view_of(trace);
+    disco_launch_solve(v, spec, n, ws + L.sel, (u64*)(ws + L.ppcnt), (u64*)((unsigned*)(ws + L.ticket) + 32),
+                       (unsigned*)(ws + L.slices), L.total - L.slices, pol_out, out, (hipStream_t)stream_);
+    DISCO_HIP(hipGetLastError());
+    return DISCO_OK;
+}
+
 extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cost_params* cost,
                                        const disco_policy* templ, const disco_search_spec* spec, int32_t n_search,
                                        disco_search_out* out, disco_policy* pol_out, void* ws_, size_t ws_bytes,

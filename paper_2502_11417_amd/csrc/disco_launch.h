@@ -38,6 +38,14 @@ void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsi
                                u64* table, u64* other, SearchState* st, disco_policy* pol, disco_search_out* sout,
                                hipStream_t stream);
 int disco_search_table_max_bins(void);
+void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, size_t scratch_bytes, u64* table, u64* other,
+                            hipStream_t stream);
+// Closed-form policy solves (Alg. 2, Alg. 3): length table, per-column plan, multi-rank selection over the server
+// TTFTs, policy records.  `state` needs disco_solve_state_bytes() bytes.
+size_t disco_solve_state_bytes(void);
+void disco_launch_solve(const TraceView& v, const disco_solve_spec* spec, int n, void* state, u64* table, u64* other,
+                        unsigned* scratch, size_t scratch_bytes, disco_policy* pol_out, disco_solve_out* out,
+                        hipStream_t stream);
 // One TTFT radix pass: histograms per workgroup slice (class kernel or pair kernel, decided on the device),
 // row sums, digit selection.
 void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S,
