@@ -266,6 +266,22 @@ def main() -> int:
             ex["timeline_kernel"] = {"bound": "hbm", "kernel": kern, "launch_ms": t_tl * 1e3, "achieved_GBs": gb / t_tl,
                                      "frac": gb / t_tl / HBM_PEAK_GBS,
                                      "traffic": measured_traffic(kern, name)}
+            if k == 4 and not buffer:
+                # recorded-trace ingest at this size: wall-clock fp64 timestamps -> relative arrays, 8 B read and 4 B
+                # written per token event (+ 28 B per request); the timestamps are rebuilt from the resident trace
+                tr = w.trace
+                base = torch.cumsum(torch.full((w.N,), 0.25, dtype=torch.float64, device="cuda"), 0) + 1.7e9
+                first = base + tr.srv_ttft.double()
+                t_token = torch.repeat_interleave(first, tr.output_len.long()) + tr.tok_arr.double()
+                del first
+                ing = {}
+                t_in = event_time(lambda: ing.update(t=D.disco_ingest_trace(base, t_token, tr.tok_off, tr.prompt_len)), 3)
+                gbi = (12.0 * w.T + 28.0 * w.N) / 1e9
+                ex["ingest_kernel"] = {"bound": "hbm", "kernel": "k_ingest", "launch_ms": t_in * 1e3,
+                                       "achieved_GBs": gbi / t_in, "frac": gbi / t_in / HBM_PEAK_GBS}
+                t_fit = event_time(lambda: D.disco_fit_lognormal(tr.srv_ttft, ws=w.ws), 5)
+                ex["lognormal_fit_ms"] = t_fit * 1e3
+                del t_token, ing, base
             if buffer:
                 st = D.stats_to_host(w.step(), w.P)
                 ex["migrated_requests"] = [int(x) for x in st["n_migrated"]]

@@ -123,6 +123,61 @@ typedef struct disco_gen_params {
 int32_t disco_gen_trace(const disco_gen_params* params /*host*/, disco_trace* trace /*host, device arrays*/,
                         int32_t stages, void* stream);
 
+/* ---- recorded traces ---------------------------------------------------- */
+
+/* A recorded trace (Sec. 5.1: the evaluation is driven by traces of production
+ * services): wall-clock timestamps in seconds, fp64, device arrays.
+ * t_send[i]: request i sent; t_token[tok_off[i] .. tok_off[i+1]): arrival of
+ * each of its output tokens, in order. */
+typedef struct disco_raw_trace {
+    int64_t n_req, n_tok;
+    const double* t_send;
+    const double* t_token;
+    const int64_t* tok_off;       /* [n_req + 1], tok_off[n_req] == n_tok */
+} disco_raw_trace;
+
+/* Fills the relative-time arrays of `trace` from `raw`: srv_ttft[i] = first
+ * token's arrival - send time, tok_arr = arrival offsets since the request's
+ * first token, output_len[i] = number of tokens; every difference is taken in
+ * fp64 and rounded once to fp32.  trace->srv_ttft, output_len and tok_arr must
+ * point to device arrays of n_req / n_req / n_tok elements; n_req, n_tok and
+ * tok_off of `trace` are set from `raw` (the offsets are shared, not copied).
+ * Prompt lengths and device speeds are the caller's (disco_device_profile).
+ * A request without tokens gets output_len 0 and srv_ttft NaN and must be
+ * dropped before evaluation.  Asynchronous.  Errors: NULL, SHAPE, HIP. */
+int32_t disco_ingest_trace(const disco_raw_trace* raw /*host*/, disco_trace* trace /*host, device arrays*/, void* stream);
+
+/* Log-normal law fitted "by the mean and standard deviation of the logarithm"
+ * (Sec. 5.3): mu = mean of ln x, sigma = population standard deviation of
+ * ln x, over the positive values of x (the others are counted in n_skipped);
+ * NaN when no value is positive.  They are the prompt_mu / prompt_sigma and
+ * ttft_mu / ttft_sigma of disco_gen_params. */
+typedef struct disco_lognormal_fit {
+    double mu, sigma;
+    int64_t n_used, n_skipped;
+} disco_lognormal_fit;
+
+#define DISCO_FIT_INT32   0   /* x is int32 (prompt lengths) */
+#define DISCO_FIT_FLOAT32 1   /* x is fp32 (server TTFT) */
+
+/* x: device, n values of the given kind; out: device.  fp64 arithmetic; two
+ * passes (mean, then deviation), partial sums folded in a fixed order.
+ * Asynchronous.  Errors: NULL, SHAPE (n < 0), RANGE (kind), WORKSPACE, HIP. */
+int32_t disco_fit_lognormal(const void* x /*device*/, int32_t kind, int64_t n, disco_lognormal_fit* out /*device*/,
+                            void* ws /*device*/, size_t ws_bytes, void* stream);
+
+/* On-device configurations of the evaluation (Sec. 5.1), index 0..2: Pixel 7
+ * Pro with Bloom 1.1B, Pixel 7 Pro with Bloom 560M, Xiaomi 14 with Qwen 1.5
+ * 0.5B.  The seconds per token are the fp32 reciprocals of the printed
+ * speeds and go into disco_trace.dev_pre_spt_s / dev_dec_spt_s; the device
+ * TTFT is k l with no intercept.  Host only.  Errors: NULL, RANGE (index). */
+typedef struct disco_device_preset {
+    double prefill_tok_per_s, decode_tok_per_s;
+    float dev_pre_spt_s, dev_dec_spt_s, dev_ttft_c;
+    char name[44];
+} disco_device_preset;
+int32_t disco_device_profile(int32_t index, disco_device_preset* out /*host*/);
+
 /* ---- policy and cost ---------------------------------------------------- */
 
 #define DISCO_MODE_SERVER_CONSTRAINED 0   /* length threshold, Sec. 4.2 Eq. 3 / Alg. 3 */

@@ -44,7 +44,11 @@ def ingest(t_send: np.ndarray, t_token: np.ndarray, tok_off: np.ndarray) -> dict
     tok_arr = np.empty(len(t_token), np.float32)
     for i in range(n):
         a, b = int(tok_off[i]), int(tok_off[i + 1])
-        output_len[i] = b - a
+        output_len[i] = max(b - a, 0)
+        if b <= a:                                  # no token, no first token: the request cannot be evaluated
+            output_len[i] = 0
+            srv_ttft[i] = np.nan
+            continue
         first = t_token[a]
         srv_ttft[i] = np.float32(first - t_send[i])
         for j in range(a, b):

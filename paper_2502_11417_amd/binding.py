@@ -130,7 +130,8 @@ assert ACCUM_DTYPE.itemsize == 128 and STATS_DTYPE.itemsize == 256 and POLICY_DT
 assert C.sizeof(CPolicy) == 32 and C.sizeof(CSearchSpec) == 40
 
 EXPORTS = ["disco_gen_trace", "disco_eval_dispatch", "disco_eval_migration", "disco_reduce_stats",
-           "disco_average_runs", "disco_solve_policy", "disco_budget_search", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
+           "disco_average_runs", "disco_solve_policy", "disco_ingest_trace", "disco_fit_lognormal",
+           "disco_device_profile", "disco_budget_search", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
            "disco_version"]
 
 _lib.disco_strerror.restype = C.c_char_p
@@ -153,6 +154,23 @@ _lib.disco_reduce_stats.argtypes = [C.POINTER(CTrace), C.POINTER(CCost), C.POINT
                                     C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.disco_average_runs.restype = C.c_int32
 _lib.disco_average_runs.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+class CRawTrace(C.Structure):
+    _fields_ = [("n_req", C.c_int64), ("n_tok", C.c_int64), ("t_send", C.c_void_p), ("t_token", C.c_void_p),
+                ("tok_off", C.c_void_p)]
+
+
+class CDevicePreset(C.Structure):
+    _fields_ = [("prefill_tok_per_s", C.c_double), ("decode_tok_per_s", C.c_double), ("dev_pre_spt_s", C.c_float),
+                ("dev_dec_spt_s", C.c_float), ("dev_ttft_c", C.c_float), ("name", C.c_char * 44)]
+
+
+FIT_DTYPE = np.dtype([("mu", "<f8"), ("sigma", "<f8"), ("n_used", "<i8"), ("n_skipped", "<i8")])
+_lib.disco_ingest_trace.restype = C.c_int32
+_lib.disco_ingest_trace.argtypes = [C.POINTER(CRawTrace), C.POINTER(CTrace), C.c_void_p]
+_lib.disco_fit_lognormal.restype = C.c_int32
+_lib.disco_fit_lognormal.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.disco_device_profile.restype = C.c_int32
+_lib.disco_device_profile.argtypes = [C.c_int32, C.POINTER(CDevicePreset)]
 _lib.disco_solve_policy.restype = C.c_int32
 _lib.disco_solve_policy.argtypes = [C.POINTER(CTrace), C.POINTER(CSolveSpec), C.c_int32, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
@@ -374,6 +392,47 @@ def disco_average_runs(stats: torch.Tensor, groups: int, runs: int, out: torch.T
         out = torch.zeros(max(groups, 1) * 256, dtype=torch.uint8, device=stats.device)
     _check(_lib.disco_average_runs(stats.data_ptr(), groups, runs, out.data_ptr(), _stream()), "disco_average_runs")
     return out
+
+
+def disco_device_profile(index: int) -> dict:
+    p = CDevicePreset()
+    _check(_lib.disco_device_profile(index, C.byref(p)), "disco_device_profile")
+    return {"name": p.name.decode(), "prefill_tok_per_s": p.prefill_tok_per_s, "decode_tok_per_s": p.decode_tok_per_s,
+            "dev_pre_spt_s": p.dev_pre_spt_s, "dev_dec_spt_s": p.dev_dec_spt_s, "dev_ttft_c": p.dev_ttft_c}
+
+
+def disco_ingest_trace(t_send: torch.Tensor, t_token: torch.Tensor, tok_off: torch.Tensor, prompt_len: torch.Tensor,
+                       profile: dict | None = None) -> Trace:
+    """Recorded timestamps (fp64 device tensors) -> a device-resident ``Trace``; prompt lengths and the device
+    speeds (``disco_device_profile``) are supplied by the caller."""
+    n, T = int(t_send.numel()), int(t_token.numel())
+    dev = t_send.device
+    t = Trace(n_req=n, n_tok=T, prompt_len=prompt_len, tok_off=tok_off)
+    t.output_len = torch.empty(n, dtype=torch.int32, device=dev)
+    t.srv_ttft = torch.empty(n, dtype=torch.float32, device=dev)
+    t.tok_arr = torch.empty(T, dtype=torch.float32, device=dev)
+    if profile:
+        t.dev_pre_spt_s, t.dev_dec_spt_s, t.dev_ttft_c = profile["dev_pre_spt_s"], profile["dev_dec_spt_s"], profile["dev_ttft_c"]
+    raw = CRawTrace(n, T, t_send.data_ptr(), t_token.data_ptr(), tok_off.data_ptr())
+    cs = t.c_struct()
+    _check(_lib.disco_ingest_trace(C.byref(raw), C.byref(cs), _stream()), "disco_ingest_trace")
+    return t
+
+
+def disco_fit_lognormal(x: torch.Tensor, ws: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
+    """mu, sigma of ln x for an int32 or float32 device tensor; returns the device record (see ``fit_to_host``)."""
+    kind = {torch.int32: 0, torch.float32: 1}[x.dtype]
+    if ws is None:
+        ws = workspace(0, 1, x.device)
+    if out is None:
+        out = torch.zeros(FIT_DTYPE.itemsize, dtype=torch.uint8, device=x.device)
+    _check(_lib.disco_fit_lognormal(x.data_ptr(), kind, x.numel(), out.data_ptr(), ws.data_ptr(), ws.numel(), _stream()),
+           "disco_fit_lognormal")
+    return out
+
+
+def fit_to_host(out: torch.Tensor) -> np.ndarray:
+    return np.frombuffer(out.cpu().numpy().tobytes(), dtype=FIT_DTYPE, count=1)[0]
 
 
 def disco_solve_policy(trace: Trace, specs, ws: torch.Tensor | None = None, pol_out: torch.Tensor | None = None,

@@ -532,6 +532,37 @@ extern "C" int32_t disco_average_runs(const disco_stats* in, int32_t groups, int
     return DISCO_OK;
 }
 
+extern "C" int32_t disco_ingest_trace(const disco_raw_trace* raw, disco_trace* trace, void* stream_)
+{
+    if (!raw || !trace) return DISCO_ERR_NULL;
+    if (raw->n_req < 0 || raw->n_tok < 0) return DISCO_ERR_SHAPE;
+    if (raw->n_req > 0 && (!raw->t_send || !raw->tok_off || !trace->srv_ttft || !trace->output_len)) return DISCO_ERR_NULL;
+    if (raw->n_tok > 0 && (!raw->t_token || !trace->tok_arr)) return DISCO_ERR_NULL;
+    trace->n_req = raw->n_req;
+    trace->n_tok = raw->n_tok;
+    trace->tok_off = const_cast<int64_t*>(raw->tok_off);
+    if (raw->n_req == 0) return DISCO_OK;
+    disco_launch_ingest(raw->n_req, raw->t_send, raw->t_token, raw->tok_off, trace->srv_ttft, trace->output_len,
+                        trace->tok_arr, (hipStream_t)stream_);
+    DISCO_HIP(hipGetLastError());
+    return DISCO_OK;
+}
+
+extern "C" int32_t disco_fit_lognormal(const void* x, int32_t kind, int64_t n, disco_lognormal_fit* out, void* ws_,
+                                       size_t ws_bytes, void* stream_)
+{
+    if (!out || (n > 0 && !x)) return DISCO_ERR_NULL;
+    if (n < 0) return DISCO_ERR_SHAPE;
+    if (kind != DISCO_FIT_INT32 && kind != DISCO_FIT_FLOAT32) return DISCO_ERR_RANGE;
+    int rc = check_ws(ws_, ws_bytes, 1);
+    if (rc) return rc;
+    const WsLayout L = disco_ws_layout(1);
+    if (disco_fit_scratch_bytes() > L.total - L.slices) return DISCO_ERR_WORKSPACE;
+    disco_launch_fit(x, kind, n, out, (char*)ws_ + L.slices, (hipStream_t)stream_);
+    DISCO_HIP(hipGetLastError());
+    return DISCO_OK;
+}
+
 extern "C" int32_t disco_solve_policy(const disco_trace* trace, const disco_solve_spec* spec, int32_t n, disco_policy* pol_out,
                                       disco_solve_out* out, void* ws_, size_t ws_bytes, void* stream_)
 {

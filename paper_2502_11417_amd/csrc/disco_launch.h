@@ -40,6 +40,11 @@ void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsi
 int disco_search_table_max_bins(void);
 void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, size_t scratch_bytes, u64* table, u64* other,
                             hipStream_t stream);
+// Recorded traces: timestamps to relative arrays; log-normal fit (`scratch`: disco_fit_scratch_bytes() bytes).
+void disco_launch_ingest(i64 n_req, const double* t_send, const double* t_token, const i64* off, float* srv_ttft,
+                         int32_t* output_len, float* tok_arr, hipStream_t stream);
+size_t disco_fit_scratch_bytes(void);
+void disco_launch_fit(const void* x, int kind, i64 n, disco_lognormal_fit* fit, void* scratch, hipStream_t stream);
 // Closed-form policy solves (Alg. 2, Alg. 3): length table, per-column plan, multi-rank selection over the server
 // TTFTs, policy records.  `state` needs disco_solve_state_bytes() bytes.
 size_t disco_solve_state_bytes(void);

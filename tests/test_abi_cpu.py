@@ -115,3 +115,22 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     g.n_req = -3
     tr.n_req = -3
     assert lib.disco_gen_trace(C.byref(g), C.byref(tr), 1, None) == B.ERR["shape"]
+
+
+def test_device_profiles_match_the_printed_speeds(B):
+    """Host-only entry point: the three on-device configurations of Sec. 5.1 (golden file) as seconds per token."""
+    import numpy as np
+    rows = [ln.split("|") for ln in open(os.path.join(ROOT, "tests", "golden", "device_profiles.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    for idx, (dev, model, pre, dec) in enumerate(rows):
+        p = B.disco_device_profile(idx)
+        assert dev.strip() in p["name"] and model.strip() in p["name"]
+        assert p["prefill_tok_per_s"] == float(pre) and p["decode_tok_per_s"] == float(dec)
+        assert np.float32(p["dev_pre_spt_s"]) == np.float32(1.0 / float(pre))
+        assert np.float32(p["dev_dec_spt_s"]) == np.float32(1.0 / float(dec)) and p["dev_ttft_c"] == 0.0
+    p = B.CDevicePreset()
+    assert B._lib.disco_device_profile(3, C.byref(p)) == B.ERR["range"]
+    assert B._lib.disco_device_profile(0, None) == B.ERR["null"]
+    assert B._lib.disco_fit_lognormal(None, 0, 5, 256, 256, 1 << 30, None) == B.ERR["null"]
+    assert B._lib.disco_fit_lognormal(256, 7, 5, 256, 256, 1 << 30, None) == B.ERR["range"]
+    assert B._lib.disco_ingest_trace(None, None, None) == B.ERR["null"]
