@@ -123,7 +123,7 @@ def main() -> int:
         def search(self):
             """Budget levels -> length thresholds; the found columns stay on the device."""
             res = D.disco_budget_search(self.trace, self.cfg["cost"], self.templ, self.specs, ws=self.ws,
-                                        out=self.sout, pol_out=self.pol_out)
+                                        out=self.sout, pol_out=self.pol_out, acc=self.acc)
             self.pols = res["policies"]
 
         def step(self):
@@ -139,8 +139,10 @@ def main() -> int:
             # straight from the device-resident policy table: no host round trip inside a step
             if not self.stoch:
                 self.search()
+            # (the search's last pass is the evaluation of the found columns: it leaves their accumulators in acc)
             tau = cfg["tau"] if cfg["timelines"] else None
-            D.disco_eval_dispatch(self.trace, self.pols, ws=self.ws, acc=self.acc)
+            if self.stoch:
+                D.disco_eval_dispatch(self.trace, self.pols, ws=self.ws, acc=self.acc)
             if tau is not None:
                 D.disco_eval_migration(self.trace, tau, cfg["kappa"], self.pols, ws=self.ws, acc=self.acc,
                                        cost=cfg["cost"])

@@ -490,6 +490,10 @@ typedef struct disco_search_out {
  * templ, spec: host, n_search entries.  out: device, n_search entries.
  * pol_out: device, n_search entries (nullable): the template with the found
  * parameter, ready to be copied into a policy table.
+ * acc_out: device, n_search entries (nullable): the dispatch block of the
+ * accumulators at the answer, exactly what disco_eval_dispatch would leave
+ * for pol_out (the search's last pass is that evaluation), so a caller that
+ * goes on to disco_reduce_stats need not evaluate again.
  * Asynchronous.  Errors: NULL, SHAPE (n_search outside [1, DISCO_MAX_COLS],
  * n_steps out of range or unequal), RANGE (unknown selector, lo > hi, a
  * stochastic baseline as template),
@@ -497,7 +501,7 @@ typedef struct disco_search_out {
 int32_t disco_budget_search(const disco_trace* trace /*host*/, const disco_cost_params* cost /*host*/,
                             const disco_policy* templ /*host*/, const disco_search_spec* spec /*host*/,
                             int32_t n_search, disco_search_out* out /*device*/,
-                            disco_policy* pol_out /*device, nullable*/,
+                            disco_policy* pol_out /*device, nullable*/, disco_accum* acc_out /*device, nullable*/,
                             void* ws /*device*/, size_t ws_bytes, void* stream);
 
 /* ---- helpers ------------------------------------------------------------ */

@@ -176,7 +176,7 @@ _lib.disco_solve_policy.argtypes = [C.POINTER(CTrace), C.POINTER(CSolveSpec), C.
                                     C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.disco_budget_search.restype = C.c_int32
 _lib.disco_budget_search.argtypes = [C.POINTER(CTrace), C.POINTER(CCost), C.POINTER(CPolicy),
-                                     C.POINTER(CSearchSpec), C.c_int32, C.c_void_p, C.c_void_p,
+                                     C.POINTER(CSearchSpec), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_size_t, C.c_void_p]
 
 
@@ -462,8 +462,10 @@ def solve_to_host(out: torch.Tensor, n: int) -> np.ndarray:
 
 
 def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Tensor | None = None,
-                        out: torch.Tensor | None = None, pol_out: torch.Tensor | None = None) -> dict:
-    """specs: dicts with which_param, which_acc (names or ints), n_steps, lo, hi, target."""
+                        out: torch.Tensor | None = None, pol_out: torch.Tensor | None = None,
+                        acc: torch.Tensor | None = None) -> dict:
+    """specs: dicts with which_param, which_acc (names or ints), n_steps, lo, hi, target.  ``acc``: receives the
+    accumulators at the found parameters (what ``disco_eval_dispatch`` would compute for them)."""
     n = len(templates)
     dev = trace.prompt_len.device if trace.prompt_len is not None else "cuda"
     if ws is None:
@@ -480,7 +482,8 @@ def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Te
     cs = trace.c_struct()
     cc = _cost(cost)
     rc = _lib.disco_budget_search(C.byref(cs), C.byref(cc), _policies(templates), sp, n, out.data_ptr(),
-                                  pol_out.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+                                  pol_out.data_ptr(), acc.data_ptr() if acc is not None else None, ws.data_ptr(),
+                                  ws.numel(), _stream())
     _check(rc, "disco_budget_search")
     return {"out": out, "pol_out": pol_out, "policies": DevicePolicies(pol_out, n)}
 

@@ -93,6 +93,12 @@ __device__ void search_advance(int col, const DispFin& fin, const disco_accum& t
         o->hi = st.hi;
         o->at_param = tot;
         if (fin.pol_out) fin.pol_out[col] = p;
+        if (fin.acc) {                                  // the evaluation at the answer, as disco_eval_dispatch would leave it
+            disco_accum* a = &fin.acc[col];
+            a->s_pre = tot.s_pre; a->s_dec = tot.s_dec; a->d_pre = tot.d_pre; a->d_dec = tot.d_dec;
+            a->n_dev_started = tot.n_dev_started; a->n_dev_win = tot.n_dev_win; a->ttft_sum = tot.ttft_sum;
+            a->ttft_min_bits = tot.ttft_min_bits; a->ttft_max_bits = tot.ttft_max_bits;
+        }
     }
 }
 
@@ -449,21 +455,30 @@ __global__ __launch_bounds__(DP_BLOCK) void k_len_hist(TraceView tr, int nbins, 
 }
 
 // table[v] = v x (requests of length v), summed over the slices: 64 lengths
-// per workgroup, each wave takes every fourth slice.
-__global__ __launch_bounds__(256) void k_len_reduce(int nbins, int nslices, const unsigned* __restrict__ slices, u64* table)
+// per workgroup, each of the 16 waves takes every sixteenth slice with four
+// loads in flight (the pass is a chain of dependent-latency loads otherwise).
+__global__ __launch_bounds__(1024) void k_len_reduce(int nbins, int nslices, const unsigned* __restrict__ slices, u64* table)
 {
-    __shared__ u64 part[256];
+    __shared__ u64 part[1024];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int v = blockIdx.x * 64 + lane;
-    u64 a0 = 0, a1 = 0;
+    u64 a0 = 0, a1 = 0, a2 = 0, a3 = 0;
     if (v < nbins) {
+        const unsigned* src = slices + v;
         int b = wave;
-        for (; b + 4 < nslices; b += 8) { a0 += slices[(size_t)b * nbins + v]; a1 += slices[(size_t)(b + 4) * nbins + v]; }
-        for (; b < nslices; b += 4) a0 += slices[(size_t)b * nbins + v];
+        for (; b + 48 < nslices; b += 64) {
+            a0 += src[(size_t)b * nbins]; a1 += src[(size_t)(b + 16) * nbins];
+            a2 += src[(size_t)(b + 32) * nbins]; a3 += src[(size_t)(b + 48) * nbins];
+        }
+        for (; b < nslices; b += 16) a0 += src[(size_t)b * nbins];
     }
-    part[threadIdx.x] = a0 + a1;
+    part[threadIdx.x] = (a0 + a1) + (a2 + a3);
     __syncthreads();
-    if (wave == 0 && v < nbins) table[v] = (part[lane] + part[64 + lane] + part[128 + lane] + part[192 + lane]) * (u64)v;
+    if (wave == 0 && v < nbins) {
+        u64 sum = 0;
+        for (int w = 0; w < 16; ++w) sum += part[w * 64 + lane];
+        table[v] = sum * (u64)v;
+    }
 }
 
 // In place: table[L] = sum over v >= L of table[v], plus the lengths beyond
@@ -576,7 +591,7 @@ void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, si
     if (blocks > DP_MAX_BLOCKS) blocks = DP_MAX_BLOCKS;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(k_len_hist, dim3((unsigned)blocks), dim3(DP_BLOCK), 0, stream, v, nbins, scratch, other);
-    hipLaunchKernelGGL(k_len_reduce, dim3((unsigned)((nbins + 63) / 64)), dim3(256), 0, stream, nbins, (int)blocks, scratch,
+    hipLaunchKernelGGL(k_len_reduce, dim3((unsigned)((nbins + 63) / 64)), dim3(1024), 0, stream, nbins, (int)blocks, scratch,
                        table);
     hipLaunchKernelGGL(k_len_suffix, dim3(1), dim3(1024), 0, stream, nbins, table, other);
 }

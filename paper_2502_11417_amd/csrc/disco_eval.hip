@@ -593,8 +593,8 @@ extern "C" int32_t disco_solve_policy(const disco_trace* trace, const disco_solv
 
 extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cost_params* cost,
                                        const disco_policy* templ, const disco_search_spec* spec, int32_t n_search,
-                                       disco_search_out* out, disco_policy* pol_out, void* ws_, size_t ws_bytes,
-                                       void* stream_)
+                                       disco_search_out* out, disco_policy* pol_out, disco_accum* acc_out, void* ws_,
+                                       size_t ws_bytes, void* stream_)
 {
     int rc = check_trace(trace);
     if (rc) return rc;
@@ -635,6 +635,7 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
     fin.st = (SearchState*)(ws + L.search);
     fin.sout = out;
     fin.pol_out = pol_out;
+    fin.acc = acc_out;
     fin.pol_rw = (disco_policy*)(ws + L.pol);
     // Length thresholds of server-constrained columns against a prompt-token budget: the accumulator is a
     // function of the threshold alone and is tabulated once (Alg. 3's sorted running totals); all bisection

@@ -308,7 +308,9 @@ __global__ __launch_bounds__(1024) void k_ttft_reduce(const SelState* S, int pas
 // Workgroup = (column, quantile) slot: the slot's histogram from the row sums
 // (thread = (bin, quarter of the rows)), the digit that holds the remaining
 // rank, the extended prefix.
-__global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int P, int nq, const unsigned* __restrict__ rowsum)
+// After the first pass a slot's histogram is its own row: the workgroup adds up the slices itself.
+__global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int P, int nq, const unsigned* __restrict__ rowsum,
+                                                      const unsigned* __restrict__ slices, int nsl_pair, int nsl_cls)
 {
     __shared__ u64 part[1024];
     __shared__ u64 wsum[4];
@@ -324,7 +326,17 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
     u64 mine = 0;
     if (t < nbins) {
         if (pass > 0) {
-            if (q == 0) mine = rowsum[((size_t)s << width) + t];
+            const int nsl = S->tc.on ? nsl_cls : nsl_pair;
+            const size_t step = (size_t)(P * nq) << width;
+            const unsigned* src = slices + ((size_t)s << width) + t;
+            unsigned a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+            int b = q;
+            for (; b + 12 < nsl; b += 16) {
+                a0 += src[(size_t)b * step]; a1 += src[(size_t)(b + 4) * step];
+                a2 += src[(size_t)(b + 8) * step]; a3 += src[(size_t)(b + 12) * step];
+            }
+            for (; b < nsl; b += 4) a0 += src[(size_t)b * step];
+            mine = (u64)a0 + a1 + a2 + a3;
         } else if (!S->tc.on) {
             if (q == 0) mine = rowsum[((size_t)col << width) + t];
         } else {                                           // device rows ub <= p, race rows ub > p
@@ -385,7 +397,9 @@ void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, 
     }
     const int rows_pair = pass == 0 ? P : P * nq, rows_cls = pass == 0 ? 2 * (P + 1) : P * nq;
     const int rows_max = rows_pair > rows_cls ? rows_pair : rows_cls;
-    hipLaunchKernelGGL(k_ttft_reduce, dim3((unsigned)rows_max), dim3(1024), 0, stream, S, pass, rows_pair, rows_cls, (int)bp,
-                       (int)bc, slices, rowsum);
-    hipLaunchKernelGGL(k_ttft_select, dim3((unsigned)(P * nq)), dim3(1024), 0, stream, S, pass, P, nq, rowsum);
+    if (pass == 0)          // the rows of the first pass are shared by many slots: summed once
+        hipLaunchKernelGGL(k_ttft_reduce, dim3((unsigned)rows_max), dim3(1024), 0, stream, S, pass, rows_pair, rows_cls, (int)bp,
+                           (int)bc, slices, rowsum);
+    hipLaunchKernelGGL(k_ttft_select, dim3((unsigned)(P * nq)), dim3(1024), 0, stream, S, pass, P, nq, rowsum, slices, (int)bp,
+                       (int)bc);
 }

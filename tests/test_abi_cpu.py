@@ -102,14 +102,14 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert lib.disco_reduce_stats(C.byref(tr), C.byref(cost), None, pol, 1, 256, q, 1, 256, 256, 1 << 30, None) == B.ERR["range"]
     assert lib.disco_reduce_stats(C.byref(tr), C.byref(cost), None, pol, 1, 256, q, 9, 256, 256, 1 << 30, None) == B.ERR["shape"]
     spec = (B.CSearchSpec * 1)(B.CSearchSpec(1, 2, 0, 0, 0.0, 5.0, 1.0))
-    assert lib.disco_budget_search(C.byref(tr), C.byref(cost), pol, spec, 1, 256, None, 256, 1 << 30, None) == B.ERR["shape"]
+    assert lib.disco_budget_search(C.byref(tr), C.byref(cost), pol, spec, 1, 256, None, None, 256, 1 << 30, None) == B.ERR["shape"]
     spec[0].n_steps = 4
     stoch = (B.CPolicy * 1)(B.CPolicy(2, 0, 0, 0.0, 0.5, 0.0, 0, 0))         # a stochastic baseline has nothing to search
-    assert lib.disco_budget_search(C.byref(tr), C.byref(cost), stoch, spec, 1, 256, None, 256, 1 << 30, None) == B.ERR["range"]
+    assert lib.disco_budget_search(C.byref(tr), C.byref(cost), stoch, spec, 1, 256, None, None, 256, 1 << 30, None) == B.ERR["range"]
     assert lib.disco_average_runs(None, 1, 1, 256, None) == B.ERR["null"]
     assert lib.disco_average_runs(256, 1, 0, 256, None) == B.ERR["shape"]
     spec[0].lo = 6.0
-    assert lib.disco_budget_search(C.byref(tr), C.byref(cost), pol, spec, 1, 256, None, 256, 1 << 30, None) == B.ERR["range"]
+    assert lib.disco_budget_search(C.byref(tr), C.byref(cost), pol, spec, 1, 256, None, None, 256, 1 << 30, None) == B.ERR["range"]
     g = B.CGenParams()
     assert lib.disco_gen_trace(None, None, 1, None) == B.ERR["null"]
     g.n_req = -3

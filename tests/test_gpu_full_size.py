@@ -22,7 +22,8 @@ pytestmark = pytest.mark.gpu
 
 
 def _levels_search(B, oracle, cfg, tr, dt, mig_mode):
-    """Budget levels -> thresholds on both sides; returns (device policies, oracle policies)."""
+    """Budget levels -> thresholds on both sides; returns (device policies, oracle policies, the accumulators the
+    search leaves for the found columns: its last pass is their evaluation, as in the benchmark's step)."""
     P = cfg["levels"]
     levels = DI.budget_levels(P)
     total = int(tr["prompt_len"].astype(np.int64).sum())
@@ -31,7 +32,8 @@ def _levels_search(B, oracle, cfg, tr, dt, mig_mode):
     templ = [B.Policy(mode=0, mig_mode=mig_mode) for _ in levels]
     specs = [dict(which_param=B.PARAM_L_TH, which_acc="server_prefill_tok", n_steps=steps, lo=0, hi=lmax + 1,
                   target=num * total / den) for num, den in levels]
-    res = B.disco_budget_search(dt, cfg["cost"], templ, specs)
+    acc = torch.zeros(P * 128, dtype=torch.uint8, device="cuda")
+    res = B.disco_budget_search(dt, cfg["cost"], templ, specs, acc=acc)
     found = B.policies_to_host(res["pol_out"], P)
     so = B.search_to_host(res["out"], P)
     opol = []
@@ -41,7 +43,7 @@ def _levels_search(B, oracle, cfg, tr, dt, mig_mode):
         assert found[j].l_th == l_th == int(so["param"][j]), j
         assert (so["hist_param"][j][:steps] == hp).all() and (so["hist_acc"][j][:steps] == ha).all(), j
         opol.append(oracle.Policy(mode=0, l_th=l_th, mig_mode=mig_mode))
-    return res["policies"], opol
+    return res["policies"], opol, acc
 
 
 def _compare_stats(got, want, with_tbt):
@@ -72,10 +74,14 @@ def test_workload1_full_size(B, oracle):
     dt = B.disco_gen_trace(cfg["gen"])
     for name in ("prompt_len", "output_len", "srv_ttft"):
         assert_same_bits(getattr(dt, name).cpu().numpy(), tr[name], name)
-    dpol, opol = _levels_search(B, oracle, cfg, tr, dt, 0)
+    dpol, opol, acc = _levels_search(B, oracle, cfg, tr, dt, 0)
     ws = B.workspace(dt.n_req, cfg["levels"])
-    r = B.disco_eval_dispatch(dt, dpol, ws=ws)
-    got = B.stats_to_host(B.disco_reduce_stats(dt, cfg["cost"], dpol, r["acc"], ws=ws), cfg["levels"])
+    got = B.stats_to_host(B.disco_reduce_stats(dt, cfg["cost"], dpol, acc, ws=ws), cfg["levels"])
+    # a separate evaluation of the found columns leaves the same accumulators
+    a0, a1 = B.accum_to_host(acc, cfg["levels"]), B.accum_to_host(B.disco_eval_dispatch(dt, dpol, ws=ws)["acc"], cfg["levels"])
+    for f in ("s_pre", "s_dec", "d_pre", "d_dec", "n_dev_started", "n_dev_win", "ttft_min_bits", "ttft_max_bits"):
+        assert (a0[f] == a1[f]).all(), f
+    assert np.allclose(a0["ttft_sum"], a1["ttft_sum"], rtol=1e-12, atol=0)
     print("full size: workload 1 oracle statistics", flush=True)
     want = oracle.stats(tr, opol, cfg["cost"])
     _compare_stats(got, want, False)
@@ -91,9 +97,9 @@ def test_workload2_full_size(B, oracle):
     dt = B.disco_gen_trace(cfg["gen"])
     assert dt.n_tok == tr["n_tok"]
     assert_same_bits(dt.tok_arr.cpu().numpy(), tr["tok_arr"], "tok_arr")
-    dpol, opol = _levels_search(B, oracle, cfg, tr, dt, 1)
+    dpol, opol, acc = _levels_search(B, oracle, cfg, tr, dt, 1)
     ws = B.workspace(dt.n_req, 1)
-    r = B.disco_eval_dispatch(dt, dpol, ws=ws)
+    r = {"acc": acc}
     mg = B.disco_eval_migration(dt, cfg["tau"], cfg["kappa"], dpol, materialise=True, delivered_col=0, ws=ws, acc=r["acc"])
     got = B.stats_to_host(B.disco_reduce_stats(dt, cfg["cost"], dpol, r["acc"], tau=cfg["tau"], kappa=cfg["kappa"], ws=ws), 1)
     print("full size: workload 2 oracle", flush=True)
@@ -149,9 +155,9 @@ def test_workload4_full_size(B, oracle):
     assert T == tr["n_tok"]
     for name in ("prompt_len", "output_len", "srv_ttft", "dev_pre_spt", "dev_dec_spt", "tok_off"):
         assert_same_bits(getattr(dt, name).cpu().numpy(), tr[name], name)
-    dpol, opol = _levels_search(B, oracle, cfg, tr, dt, 1)
+    dpol, opol, sacc = _levels_search(B, oracle, cfg, tr, dt, 1)
     ws = B.workspace(N, P)
-    r = B.disco_eval_dispatch(dt, dpol, ws=ws)
+    r = {"acc": sacc}
     mg = B.disco_eval_migration(dt, tau, kappa, dpol, materialise=True, delivered_col=0, ws=ws, acc=r["acc"])
     acc = B.accum_to_host(r["acc"], P)
     got = B.stats_to_host(B.disco_reduce_stats(dt, cfg["cost"], dpol, r["acc"], tau=tau, kappa=kappa, ws=ws), P)
