@@ -110,8 +110,10 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
                 left -= wd; pl.npass += 1;
             }
             g.plan = pl;
+            g.gather_bound = 0ull; g.n_list = 0u; g.gather_error = 0;
         } else {                      // TBT: raw keys; the passes are planned on the device (TlSel)
             g.minb = 0u; g.maxb = 0x7FFFFFFFu;
+            g.gather_bound = 0ull; g.n_list = 0u; g.gather_error = 0;
             g.plan.npass = 0; g.plan.pad = 0;
             for (int i = 0; i < DISCO_MAX_PASS; ++i) { g.plan.shift[i] = 0; g.plan.width[i] = 0; }
             TlSel& tl = S->tl;
@@ -169,7 +171,7 @@ __global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, 
         if (qi < nq) {
             const SelSlot s0 = S->slot[0][c * nq + qi];
             st.ttft_rank[qi] = s0.rank;
-            if (s0.M > 0) st.ttft_q[qi] = u2f(S->g[0].minb + s0.prefix);
+            if (s0.M > 0 && !S->g[0].gather_error) st.ttft_q[qi] = u2f(S->g[0].minb + s0.prefix);
             if (with_tl) {
                 const SelSlot s1 = S->slot[1][c * nq + qi];
                 st.tbt_rank[qi] = s1.rank;

@@ -17,7 +17,9 @@ struct SpecTable { SearchState s[DISCO_MAX_COLS]; };
 // patterns).  Pass p looks at `width[p]` bits at `shift[p]`.
 enum { DISCO_MAX_PASS = 6 };
 struct SelPlan { int npass; int shift[DISCO_MAX_PASS]; int width[DISCO_MAX_PASS]; int pad; };
-struct SelGlobal { unsigned minb, maxb; SelPlan plan; };
+// gather_bound: after the second pass, an upper bound of the values that still match some slot's prefix; when it
+// is small they are collected in a list (n_list entries) and the remaining digits are decided from the list.
+struct SelGlobal { unsigned minb, maxb; SelPlan plan; u64 gather_bound; unsigned n_list; int gather_error; };
 struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
 // TBT selection: a timeline is histogrammed once per *class* = set of policy
 // columns that use it (for threshold- or wait-ordered tables the sets are

@@ -21,6 +21,13 @@
 //   pair kernel -- any table: lane = column, every (request, column) pair is
 //     evaluated and bumps the rows of its column.
 //
+// After two passes few values still match a slot's prefix (the second select
+// adds up an upper bound): the third pass then collects them in a list --
+// key and which columns the value belongs to -- and every slot finishes its
+// remaining digits from that list (k_ttft_select, one workgroup per slot),
+// instead of two more passes over the requests.  If the bound is too large
+// (heavy ties) the histogram passes simply go on.
+//
 // A workgroup stores its LDS bins as one slice; k_ttft_reduce adds the slices
 // (merging them with device-wide atomics would serialise on the few hundred
 // cache lines of the bins) and k_ttft_select extends every slot's prefix.
@@ -42,6 +49,61 @@ constexpr int TH_WORDS = TH_ROWS * TH_STRIDE;           // 131 KB of LDS bins
 constexpr int TC_MAX_BLOCKS = 128;                      // class kernel: little arithmetic, fewer slices to add up
 
 struct PassDigit { int width, shift, up; unsigned dmask; };
+
+// Candidate list of the finishing step: 2^21 entries of 8 bytes in the slice region.
+constexpr unsigned TG_CAP = 1u << 21;
+struct GEntry { unsigned key, tag; };           // tag: kind << 16 | u; kind 0: columns at sorted position >= u,
+                                                // 1: columns at sorted position < u, 2: column u
+__device__ __forceinline__ bool gather_on(const SelGlobal& g) { return g.plan.npass > 2 && g.gather_bound <= (u64)TG_CAP; }
+
+// Entries are staged per wave in LDS (the histogram bins are idle in this pass): a wave appends to its own
+// segment without atomics -- the count is wave-uniform -- and spills a full segment to the device-wide list; what is
+// left at the end goes out with one device-wide atomic per workgroup (one per wave would queue up on the counter).
+constexpr unsigned TG_SEG = TH_WORDS / 2 / DP_WAVES;            // entries per wave
+struct WaveList { GEntry* seg; unsigned cnt; };
+
+__device__ __forceinline__ void wl_copy(const WaveList& w, unsigned base, GEntry* __restrict__ list, SelGlobal* g)
+{
+    __builtin_amdgcn_wave_barrier();
+    for (unsigned j = threadIdx.x & 63; j < w.cnt; j += 64) {
+        if (base + j < TG_CAP) list[base + j] = w.seg[j];
+        else g->gather_error = 1;                              // cannot happen while gather_bound holds
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Called by all lanes of the wave.
+__device__ __forceinline__ void wl_append(WaveList& w, bool match, unsigned key, unsigned tag, GEntry* __restrict__ list,
+                                          SelGlobal* g)
+{
+    const int lane = threadIdx.x & 63;
+    if (w.cnt + 64u > TG_SEG) {                                // wave-uniform
+        unsigned base = 0u;
+        if (lane == 0) base = atomicAdd(&g->n_list, w.cnt);
+        base = (unsigned)__shfl((int)base, 0, 64);
+        wl_copy(w, base, list, g);
+        w.cnt = 0u;
+    }
+    const u64 m = __ballot(match);
+    if (match) w.seg[w.cnt + (unsigned)__popcll(m & ((1ull << lane) - 1ull))] = GEntry{key, tag};
+    w.cnt += (unsigned)__popcll(m);
+}
+
+// Called by all threads of the workgroup.
+__device__ __forceinline__ void wl_finish(const WaveList& w, GEntry* __restrict__ list, SelGlobal* g)
+{
+    __shared__ unsigned woff[DP_WAVES + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) woff[wave] = w.cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned total = 0u;
+        for (int k = 0; k < DP_WAVES; ++k) { const unsigned c = woff[k]; woff[k] = total; total += c; }
+        woff[DP_WAVES] = total ? atomicAdd(&g->n_list, total) : 0u;
+    }
+    __syncthreads();
+    wl_copy(w, woff[DP_WAVES] + woff[wave], list, g);
+}
 
 __device__ __forceinline__ PassDigit pass_digit(const SelGlobal& g, int pass)
 {
@@ -67,12 +129,14 @@ __device__ __forceinline__ void store_slice(const unsigned* hist, int rows, int 
 // per column (all quantiles share it).
 template <int G>
 __device__ __forceinline__ void pair_body(const TraceView& tr, const disco_policy* __restrict__ pol, int P, int nq, int pass,
-                                          const SelState* S, unsigned* __restrict__ slices, unsigned* hist, Staged* stage,
-                                          int bid, int nblk)
+                                          SelState* S, unsigned* __restrict__ slices, unsigned* hist, Staged* stage,
+                                          int bid, int nblk, bool gather)
 {
     const SelGlobal g = S->g[0];
     const PassDigit dg = pass_digit(g, pass);
     if (dg.width <= 0) return;
+    GEntry* list = reinterpret_cast<GEntry*>(slices);
+    WaveList wl{reinterpret_cast<GEntry*>(hist) + (threadIdx.x >> 6) * TG_SEG, 0u};
     const int width = dg.width, shift = dg.shift, up = dg.up;
     const unsigned dmask = dg.dmask;
     const int nslot = (pass == 0) ? P : P * nq;
@@ -113,7 +177,14 @@ __device__ __forceinline__ void pair_body(const TraceView& tr, const disco_polic
                 const int src = sub * G + it;
                 const Staged r = st[src];
                 const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d, b * 64 + src);
-                if (src < cnt) {
+                if (gather) {                            // collect the pairs that still match a slot of their column
+                    const unsigned key = f2u(e.ttft) - g.minb;
+                    const unsigned hi = key >> up;
+                    bool match = false;
+#pragma unroll
+                    for (int qi = 0; qi < DISCO_MAX_Q; ++qi) match = match || (live[qi] && hi == prefix[qi]);
+                    wl_append(wl, match && src < cnt, key, 0x20000u | (unsigned)col, list, &S->g[0]);
+                } else if (src < cnt) {
                     const unsigned key = f2u(e.ttft) - g.minb;
                     const unsigned dgt = (key >> shift) & dmask;
                     const unsigned hi = (up >= 32) ? 0u : (key >> up);
@@ -133,6 +204,7 @@ __device__ __forceinline__ void pair_body(const TraceView& tr, const disco_polic
     if (mode == 0) run(std::integral_constant<int, 0>{});
     else if (mode == 1) run(std::integral_constant<int, 1>{});
     else run(std::integral_constant<int, 2>{});
+    if (gather) { wl_finish(wl, list, &S->g[0]); return; }
     __syncthreads();
     store_slice(hist, nslot, width, slices, bid);
 }
@@ -153,8 +225,9 @@ struct ClsTables {
     unsigned char col_of_pos[DISCO_MAX_COLS];
 };
 
-__device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int pass, const SelState* S,
-                                         unsigned* __restrict__ slices, unsigned* hist, ClsTables& T, int bid, int nblk)
+__device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int pass, SelState* S,
+                                         unsigned* __restrict__ slices, unsigned* hist, ClsTables& T, int bid, int nblk,
+                                         bool gather)
 {
     const SelGlobal g = S->g[0];
     const PassDigit dg = pass_digit(g, pass);
@@ -211,6 +284,52 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
     }
     __syncthreads();
     const int ndist = pass > 0 ? T.ndist : 0;
+    if (gather) {
+        // same matching as a histogram pass, but the value is appended to the candidate list (all lanes of a
+        // wave stay together: the append is a wave operation)
+        GEntry* list = reinterpret_cast<GEntry*>(slices);
+        WaveList wl{reinterpret_cast<GEntry*>(hist) + (threadIdx.x >> 6) * TG_SEG, 0u};
+        for (i64 base = (i64)bid * DP_BLOCK; base < tr.n_req; base += (i64)nblk * DP_BLOCK) {
+            const i64 i = base + t;
+            const bool v = i < tr.n_req;
+            const int l = v ? tr.l[i] : 0;
+            const float s = v ? tr.s[i] : 0.0f;
+            const float k = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
+            const float d = __fmaf_rn((float)l, k, tr.c);
+            int ub = 0;
+#pragma unroll
+            for (int step = 64; step >= 1; step >>= 1)
+                if (ub + step <= DISCO_MAX_COLS && T.sorted[ub + step - 1] <= l) ub += step;
+            ub = ub < P ? ub : P;
+            const bool dev_wins = d < s;
+            const int ub0 = dev_wins ? 0 : ub;
+            const bool two = !dev_wins && ub > 0;
+#pragma unroll
+            for (int which = 0; which < 2; ++which) {
+                const unsigned key = (which ? f2u(s) : f2u(d)) - g.minb;
+                const int u = which ? ub : ub0;
+                bool match = v && (which ? two : ub0 < P);
+                if (match) {
+                    const unsigned hi = key >> up;
+                    int lo_i = 0, hi_i = ndist;
+                    while (lo_i < hi_i) {
+                        const int mid = (lo_i + hi_i) >> 1;
+                        if (T.dist[mid] < hi) lo_i = mid + 1; else hi_i = mid;
+                    }
+                    match = lo_i < ndist && T.dist[lo_i] == hi;
+                    if (match) {
+                        u64 m0 = T.dmask[lo_i][0], m1 = T.dmask[lo_i][1];
+                        if (which) { m0 &= ~T.dslots[u][0]; m1 &= ~T.dslots[u][1]; }
+                        else { m0 &= T.dslots[u][0]; m1 &= T.dslots[u][1]; }
+                        match = (m0 | m1) != 0ull;
+                    }
+                }
+                wl_append(wl, match, key, ((unsigned)which << 16) | (unsigned)u, list, &S->g[0]);
+            }
+        }
+        wl_finish(wl, list, &S->g[0]);
+        return;
+    }
     for (i64 i = (i64)bid * DP_BLOCK + t; i < tr.n_req; i += (i64)nblk * DP_BLOCK) {
         const int l = tr.l[i];
         const float s = tr.s[i];
@@ -261,7 +380,7 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
 // kernel; the ones whose kind does not apply to the table return at once.
 template <int G>
 __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
-                                                        int pass, const SelState* S, unsigned* __restrict__ slices,
+                                                        int pass, SelState* S, unsigned* __restrict__ slices,
                                                         int ncls_blocks)
 {
     __shared__ unsigned hist[TH_WORDS];
@@ -269,8 +388,11 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disc
     __shared__ ClsTables T;
     const bool cls_block = (int)blockIdx.x < ncls_blocks;
     if (cls_block != (S->tc.on != 0)) return;
-    if (cls_block) cls_body(tr, P, nq, pass, S, slices, hist, T, blockIdx.x, ncls_blocks);
-    else pair_body<G>(tr, pol, P, nq, pass, S, slices, hist, stage, (int)blockIdx.x - ncls_blocks, (int)gridDim.x - ncls_blocks);
+    const bool gather = pass >= 2 && gather_on(S->g[0]);
+    if (gather && pass > 2) return;                       // the list finished the selection
+    if (cls_block) cls_body(tr, P, nq, pass, S, slices, hist, T, blockIdx.x, ncls_blocks, gather);
+    else pair_body<G>(tr, pol, P, nq, pass, S, slices, hist, stage, (int)blockIdx.x - ncls_blocks, (int)gridDim.x - ncls_blocks,
+                      gather);
 }
 
 // ------------------------------------------------------ reduce and select --
@@ -305,6 +427,75 @@ __global__ __launch_bounds__(1024) void k_ttft_reduce(const SelState* S, int pas
         rowsum[((size_t)row << dg.width) + bin] = part[bin] + part[256 + bin] + part[512 + bin] + part[768 + bin];
 }
 
+// The slot's remaining digits from the candidate list (workgroup = slot): histograms of up to 12 bits at a time
+// (one scan of the list when 12 bits or fewer are left) over the entries that carry the slot's prefix and belong
+// to its column; four entries per thread and iteration are in flight.
+__device__ void finish_from_list(SelState* S, int s, int col, SelSlot sl, const GEntry* __restrict__ list)
+{
+    constexpr int FW = 12, FB = 1 << FW;
+    __shared__ unsigned fh[FB];
+    __shared__ unsigned chosen;
+    __shared__ u64 k_next, fsum[16];
+    const SelGlobal g = S->g[0];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const unsigned pos = S->tc.on ? S->tc.pos_of_col[col] : 0u;
+    const unsigned n = g.n_list < TG_CAP ? g.n_list : TG_CAP;
+    int R = g.plan.shift[1];                         // undecided low bits
+    unsigned prefix = sl.prefix;
+    u64 k = (u64)sl.k_rem;
+    while (R > 0) {
+        const int w = R < FW ? R : FW, sh = R - w;
+        const unsigned dm = (1u << w) - 1u;
+        for (int i = t; i < FB; i += blockDim.x) fh[i] = 0u;
+        if (t == 0) chosen = 0xFFFFFFFFu;
+        __syncthreads();
+        // the list is padded to its capacity, so whole groups of four can be loaded; entries past n are ignored
+        for (unsigned e0 = 4u * t; e0 < n; e0 += 4u * blockDim.x) {
+            const uint4 a = *reinterpret_cast<const uint4*>(&list[e0]);
+            const uint4 b = *reinterpret_cast<const uint4*>(&list[e0 + 2]);
+            const unsigned key[4] = {a.x, a.z, b.x, b.z}, tag[4] = {a.y, a.w, b.y, b.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const unsigned kind = tag[q] >> 16, u = tag[q] & 0xFFFFu;
+                const bool mine = kind == 0u ? pos >= u : (kind == 1u ? pos < u : (unsigned)col == u);
+                if (e0 + q < n && mine && (key[q] >> R) == prefix) atomicAdd(&fh[(key[q] >> sh) & dm], 1u);
+            }
+        }
+        __syncthreads();
+        // bins 4t .. 4t+3 per thread, inclusive prefix over the workgroup
+        unsigned c[4];
+        u64 mine = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { c[q] = fh[4 * t + q]; mine += c[q]; }
+        u64 incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const unsigned lo = (unsigned)__shfl_up((int)(unsigned)incl, d, 64);
+            const unsigned hi = (unsigned)__shfl_up((int)(unsigned)(incl >> 32), d, 64);
+            if (lane >= d) incl += ((u64)hi << 32) | lo;
+        }
+        if (lane == 63) fsum[wave] = incl;
+        __syncthreads();
+        for (int v = 0; v < wave; ++v) incl += fsum[v];
+        u64 below = incl - mine;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (below < k && below + c[q] >= k) { chosen = (unsigned)(4 * t + q); k_next = k - below; }
+            below += c[q];
+        }
+        __syncthreads();
+        if (chosen == 0xFFFFFFFFu) {                 // the rank is always covered: never expected
+            if (t == 0) S->g[0].gather_error = 1;
+            return;
+        }
+        prefix = (prefix << w) | chosen;
+        k = k_next;
+        R = sh;
+        __syncthreads();
+    }
+    if (t == 0) { sl.prefix = prefix; sl.k_rem = (i64)k; S->slot[0][s] = sl; }
+}
+
 // Workgroup = (column, quantile) slot: the slot's histogram from the row sums
 // (thread = (bin, quarter of the rows)), the digit that holds the remaining
 // rank, the extended prefix.
@@ -321,6 +512,10 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
     SelSlot sl = S->slot[0][s];
     if (sl.done) return;
     const int col = s / nq;
+    if (pass >= 2 && gather_on(S->g[0])) {
+        if (pass == 2) finish_from_list(S, s, col, sl, reinterpret_cast<const GEntry*>(slices));
+        return;
+    }
     const int nbins = 1 << width;                          // <= 256
     const int t = threadIdx.x & 255, q = threadIdx.x >> 8, lane = t & 63, wave = t >> 6;
     u64 mine = 0;
@@ -363,6 +558,8 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
         sl.k_rem = (i64)(k - (incl - mine));
         sl.prefix = (sl.prefix << width) | (unsigned)t;
         S->slot[0][s] = sl;
+        // every value that still matches some slot after this pass is counted in that slot's bin
+        if (pass == 1) atomicAdd((unsigned long long*)&S->g[0].gather_bound, (unsigned long long)mine);
     }
 }
 
