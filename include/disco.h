@@ -506,8 +506,11 @@ int32_t disco_budget_search(const disco_trace* trace /*host*/, const disco_cost_
 
 /* ---- helpers ------------------------------------------------------------ */
 
-/* Bytes of device workspace that any call above needs for n_req requests and
- * P columns (or searches); about 44 MB, independent of both today.  The
+/* Bytes of device workspace for n_req requests and P columns (or searches):
+ * about 44 MB plus one byte per request.  Every call accepts a workspace of
+ * disco_workspace_bytes(0, P) bytes; the per-request byte only lets the TTFT
+ * selection of disco_reduce_stats keep a small per-request result between its
+ * passes instead of recomputing it.  The
  * workspace holds partial results only; its contents need not be initialised
  * or preserved between calls, and calls that share one workspace must not
  * overlap in time.  It must be ordinary (coarse-grained) device memory,

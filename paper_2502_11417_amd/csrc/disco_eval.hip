@@ -351,10 +351,11 @@ WsLayout disco_ws_layout(int32_t P)
     return L;
 }
 
+// The fixed regions, then one byte per request (used by the TTFT selection; optional: a workspace without it works).
 extern "C" size_t disco_workspace_bytes(int64_t n_req, int32_t P)
 {
-    (void)n_req;
-    return disco_ws_layout(P).total;
+    const size_t per_request = n_req > 0 ? (((size_t)n_req + 255) & ~(size_t)255) : 0;
+    return disco_ws_layout(P).total + per_request;
 }
 
 extern "C" const char* disco_strerror(int32_t code)
@@ -489,9 +490,10 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     if (nq > 0) {
         hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 0, P, nq, qs[0], qs[1], qs[2], qs[3], acc,
                            v.n_req, (const disco_policy*)(ws + L.pol));
+        unsigned char* ubytes = ws_bytes >= L.total + (size_t)v.n_req ? (unsigned char*)(ws + L.total) : nullptr;
         for (int pass = 0; pass < 4; ++pass)
             disco_launch_ttft_pass(v, (const disco_policy*)(ws + L.pol), P, nq, pass, S, (unsigned*)(ws + L.slices), gh,
-                                   stream);
+                                   ubytes, stream);
         if (tl) {
             hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 1, P, nq, qs[0], qs[1], qs[2], qs[3],
                                acc, v.n_req, (const disco_policy*)(ws + L.pol));

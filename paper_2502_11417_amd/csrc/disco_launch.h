@@ -53,8 +53,10 @@ void disco_launch_solve(const TraceView& v, const disco_solve_spec* spec, int n,
                         hipStream_t stream);
 // One TTFT radix pass: histograms per workgroup slice (class kernel or pair kernel, decided on the device),
 // row sums, digit selection.
+// `ubytes`: n_req bytes of scratch (nullable) where the first pass leaves, per request, the number of thresholds
+// not above its prompt length for the later passes.
 void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S,
-                            unsigned* slices, unsigned* rowsum, hipStream_t stream);
+                            unsigned* slices, unsigned* rowsum, unsigned char* ubytes, hipStream_t stream);
 void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,
                                hipStream_t stream);
 // Token timelines.  Statistics pass (a.pass = -1): streaming kernel, or the general kernel when the

@@ -215,19 +215,44 @@ __device__ __forceinline__ void pair_body(const TraceView& tr, const disco_polic
 struct ClsTables {
     int sorted[DISCO_MAX_COLS];                  // thresholds in ascending order (unused tail: INT_MAX)
     u64 dslots[DISCO_MAX_COLS + 1][2];           // slots of the columns p >= ub, as a 128-bit set
-    unsigned dist[DISCO_MAX_SLOTS];              // distinct prefixes of the live slots, ascending
-    u64 dmask[DISCO_MAX_SLOTS][2];               // live slots holding each distinct prefix
+    u64 dmask[DISCO_MAX_SLOTS][2];               // live slots with the same prefix, kept at the first of them
+    u64 htab[2 * DISCO_MAX_SLOTS];               // open-addressing hash: prefix -> first slot holding it (0: empty)
     unsigned sprefix[DISCO_MAX_SLOTS];
     int slive[DISCO_MAX_SLOTS];
-    int first[DISCO_MAX_SLOTS];
-    int rank[DISCO_MAX_SLOTS];
-    int ndist;
+    int first_of[DISCO_MAX_SLOTS];               // smallest live slot with the same prefix
     unsigned char col_of_pos[DISCO_MAX_COLS];
 };
 
+__device__ __forceinline__ unsigned prefix_hash(unsigned prefix) { return (prefix * 0x9E3779B1u) >> 24; }
+
+// First slot holding `prefix`, -1 if no live slot does.  At most half of the table is occupied.
+__device__ __forceinline__ int prefix_lookup(const ClsTables& T, unsigned prefix)
+{
+    unsigned h = prefix_hash(prefix);
+    for (;;) {
+        const u64 e = T.htab[h];
+        if (e == 0ull) return -1;
+        if ((unsigned)(e >> 8) == prefix) return (int)(e & 0xFFull);
+        h = (h + 1u) & (2 * DISCO_MAX_SLOTS - 1);
+    }
+}
+
+// ub = #{p : t_p <= l}: cached per request by the first pass when the caller's workspace has room for it,
+// otherwise a binary search over the 64 padded thresholds.
+__device__ __forceinline__ int request_ub(const ClsTables& T, int P, int l, const unsigned char* __restrict__ ubytes, i64 i,
+                                          bool cached)
+{
+    if (cached) return (int)ubytes[i];
+    int ub = 0;
+#pragma unroll
+    for (int step = 64; step >= 1; step >>= 1)
+        if (ub + step <= DISCO_MAX_COLS && T.sorted[ub + step - 1] <= l) ub += step;
+    return ub < P ? ub : P;
+}
+
 __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int pass, SelState* S,
                                          unsigned* __restrict__ slices, unsigned* hist, ClsTables& T, int bid, int nblk,
-                                         bool gather)
+                                         bool gather, unsigned char* __restrict__ ubytes)
 {
     const SelGlobal g = S->g[0];
     const PassDigit dg = pass_digit(g, pass);
@@ -237,26 +262,26 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
     const int nslot = P * nq;
     const int rows = (pass == 0) ? 2 * (P + 1) : nslot;
     const int t = threadIdx.x;
-    for (int i = t; i < rows * TH_STRIDE; i += DP_BLOCK) hist[i] = 0u;
+    if (!gather)
+        for (int i = t; i < rows * TH_STRIDE; i += DP_BLOCK) hist[i] = 0u;
     if (t < DISCO_MAX_COLS) { T.sorted[t] = t < P ? S->tc.sorted_lth[t] : 0x7FFFFFFF; T.col_of_pos[t] = S->tc.col_of_pos[t]; }
     if (pass > 0) {
-        // tables of this pass, built pairwise-parallel by the whole workgroup
+        // tables of this pass, built by the whole workgroup
         if (t < DISCO_MAX_SLOTS) {
             const bool in = t < nslot;
             SelSlot sl;
             if (in) sl = S->slot[0][t];
             T.sprefix[t] = in ? sl.prefix : 0u;
             T.slive[t] = in && !sl.done;
-            T.first[t] = in && !sl.done;                // cleared below if an earlier live slot holds the same prefix
-            T.rank[t] = 0;
+            T.first_of[t] = t;
             T.dmask[t][0] = 0ull; T.dmask[t][1] = 0ull;
         }
+        if (t < 2 * DISCO_MAX_SLOTS) T.htab[t] = 0ull;
         if (t <= DISCO_MAX_COLS) { T.dslots[t][0] = 0ull; T.dslots[t][1] = 0ull; }
-        if (t == 0) T.ndist = 0;
         __syncthreads();
-        for (int pr = t; pr < DISCO_MAX_SLOTS * DISCO_MAX_SLOTS; pr += DP_BLOCK) {
+        for (int pr = t; pr < DISCO_MAX_SLOTS * DISCO_MAX_SLOTS; pr += DP_BLOCK) {     // earliest slot with the same prefix
             const int a = pr >> 7, z = pr & (DISCO_MAX_SLOTS - 1);
-            if (z < a && T.slive[z] && T.slive[a] && T.sprefix[z] == T.sprefix[a]) T.first[a] = 0;
+            if (z < a && T.slive[z] && T.slive[a] && T.sprefix[z] == T.sprefix[a]) atomicMin(&T.first_of[a], z);
         }
         // slots of the sorted columns p >= ub
         for (int pr = t; pr < (P + 1) * P; pr += DP_BLOCK) {
@@ -270,20 +295,20 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
             }
         }
         __syncthreads();
-        for (int pr = t; pr < DISCO_MAX_SLOTS * DISCO_MAX_SLOTS; pr += DP_BLOCK) {     // rank among the distinct prefixes
-            const int a = pr >> 7, o = pr & (DISCO_MAX_SLOTS - 1);
-            if (T.first[a] && T.first[o] && T.sprefix[o] < T.sprefix[a]) atomicAdd(&T.rank[a], 1);
-        }
-        __syncthreads();
-        if (t < DISCO_MAX_SLOTS && T.first[t]) { T.dist[T.rank[t]] = T.sprefix[t]; atomicAdd(&T.ndist, 1); }
-        for (int pr = t; pr < DISCO_MAX_SLOTS * DISCO_MAX_SLOTS; pr += DP_BLOCK) {     // slots holding each distinct prefix
-            const int a = pr >> 7, o = pr & (DISCO_MAX_SLOTS - 1);
-            if (T.first[a] && T.slive[o] && T.sprefix[o] == T.sprefix[a])
-                atomicOr((unsigned long long*)&T.dmask[T.rank[a]][o >> 6], 1ull << (o & 63));
+        if (t < DISCO_MAX_SLOTS && T.slive[t]) {
+            const int f = T.first_of[t];
+            atomicOr((unsigned long long*)&T.dmask[f][t >> 6], 1ull << (t & 63));
+            if (f == t) {                               // one entry per distinct prefix
+                const unsigned pf = T.sprefix[t];
+                const u64 entry = ((u64)pf << 8) | (u64)t | (1ull << 63);
+                unsigned h = prefix_hash(pf);
+                while (atomicCAS((unsigned long long*)&T.htab[h], 0ull, (unsigned long long)entry) != 0ull)
+                    h = (h + 1u) & (2 * DISCO_MAX_SLOTS - 1);
+            }
         }
     }
     __syncthreads();
-    const int ndist = pass > 0 ? T.ndist : 0;
+    const bool cached = ubytes != nullptr && pass > 0;
     if (gather) {
         // same matching as a histogram pass, but the value is appended to the candidate list (all lanes of a
         // wave stay together: the append is a wave operation)
@@ -296,11 +321,7 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
             const float s = v ? tr.s[i] : 0.0f;
             const float k = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
             const float d = __fmaf_rn((float)l, k, tr.c);
-            int ub = 0;
-#pragma unroll
-            for (int step = 64; step >= 1; step >>= 1)
-                if (ub + step <= DISCO_MAX_COLS && T.sorted[ub + step - 1] <= l) ub += step;
-            ub = ub < P ? ub : P;
+            const int ub = v ? request_ub(T, P, l, ubytes, i, cached) : 0;
             const bool dev_wins = d < s;
             const int ub0 = dev_wins ? 0 : ub;
             const bool two = !dev_wins && ub > 0;
@@ -310,15 +331,10 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
                 const int u = which ? ub : ub0;
                 bool match = v && (which ? two : ub0 < P);
                 if (match) {
-                    const unsigned hi = key >> up;
-                    int lo_i = 0, hi_i = ndist;
-                    while (lo_i < hi_i) {
-                        const int mid = (lo_i + hi_i) >> 1;
-                        if (T.dist[mid] < hi) lo_i = mid + 1; else hi_i = mid;
-                    }
-                    match = lo_i < ndist && T.dist[lo_i] == hi;
+                    const int f = prefix_lookup(T, key >> up);
+                    match = f >= 0;
                     if (match) {
-                        u64 m0 = T.dmask[lo_i][0], m1 = T.dmask[lo_i][1];
+                        u64 m0 = T.dmask[f][0], m1 = T.dmask[f][1];
                         if (which) { m0 &= ~T.dslots[u][0]; m1 &= ~T.dslots[u][1]; }
                         else { m0 &= T.dslots[u][0]; m1 &= T.dslots[u][1]; }
                         match = (m0 | m1) != 0ull;
@@ -335,11 +351,8 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
         const float s = tr.s[i];
         const float k = tr.k ? tr.k[i] : tr.k_s;
         const float d = __fmaf_rn((float)l, k, tr.c);
-        int ub = 0;                                     // #{p : t_p <= l}: binary search over 64 padded entries
-#pragma unroll
-        for (int step = 64; step >= 1; step >>= 1)
-            if (ub + step <= DISCO_MAX_COLS && T.sorted[ub + step - 1] <= l) ub += step;
-        ub = ub < P ? ub : P;
+        const int ub = request_ub(T, P, l, ubytes, i, cached);
+        if (pass == 0 && ubytes) ubytes[i] = (unsigned char)ub;
         const bool dev_wins = d < s;                    // ties go to the server
         // value 0: d for the columns p >= ub (for every column if the device also wins the races);
         // value 1: s for the columns p < ub
@@ -355,15 +368,10 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
                 if (which == 1 && !two) continue;
                 if (which == 0 && ub0 >= P) continue;
                 const unsigned key = which ? key1 : key0;
-                const unsigned hi = key >> up;          // up < 32 after the first pass
-                int lo_i = 0, hi_i = ndist;             // first distinct prefix >= hi
-                while (lo_i < hi_i) {
-                    const int mid = (lo_i + hi_i) >> 1;
-                    if (T.dist[mid] < hi) lo_i = mid + 1; else hi_i = mid;
-                }
-                if (lo_i >= ndist || T.dist[lo_i] != hi) continue;
+                const int f = prefix_lookup(T, key >> up);          // up < 32 after the first pass
+                if (f < 0) continue;
                 const int u = which ? ub : ub0;
-                u64 m0 = T.dmask[lo_i][0], m1 = T.dmask[lo_i][1];
+                u64 m0 = T.dmask[f][0], m1 = T.dmask[f][1];
                 if (which) { m0 &= ~T.dslots[u][0]; m1 &= ~T.dslots[u][1]; }
                 else { m0 &= T.dslots[u][0]; m1 &= T.dslots[u][1]; }
                 const unsigned dgt = (key >> shift) & dmask;
@@ -381,7 +389,7 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
 template <int G>
 __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
                                                         int pass, SelState* S, unsigned* __restrict__ slices,
-                                                        int ncls_blocks)
+                                                        int ncls_blocks, unsigned char* __restrict__ ubytes)
 {
     __shared__ unsigned hist[TH_WORDS];
     __shared__ __align__(16) Staged stage[DP_BLOCK];
@@ -390,7 +398,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disc
     if (cls_block != (S->tc.on != 0)) return;
     const bool gather = pass >= 2 && gather_on(S->g[0]);
     if (gather && pass > 2) return;                       // the list finished the selection
-    if (cls_block) cls_body(tr, P, nq, pass, S, slices, hist, T, blockIdx.x, ncls_blocks, gather);
+    if (cls_block) cls_body(tr, P, nq, pass, S, slices, hist, T, blockIdx.x, ncls_blocks, gather, ubytes);
     else pair_body<G>(tr, pol, P, nq, pass, S, slices, hist, stage, (int)blockIdx.x - ncls_blocks, (int)gridDim.x - ncls_blocks,
                       gather);
 }
@@ -565,15 +573,16 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
 
 template <int G>
 void launch_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S, unsigned* slices,
-                 unsigned bp, unsigned bc, hipStream_t stream)
+                 unsigned bp, unsigned bc, unsigned char* ubytes, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_ttft_hist<G>, dim3(bc + bp), dim3(DP_BLOCK), 0, stream, v, pol, P, nq, pass, S, slices, (int)bc);
+    hipLaunchKernelGGL(k_ttft_hist<G>, dim3(bc + bp), dim3(DP_BLOCK), 0, stream, v, pol, P, nq, pass, S, slices, (int)bc,
+                       ubytes);
 }
 
 }  // namespace
 
 void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S,
-                            unsigned* slices, unsigned* rowsum, hipStream_t stream)
+                            unsigned* slices, unsigned* rowsum, unsigned char* ubytes, hipStream_t stream)
 {
     i64 bp = ((v.n_req + 63) / 64 + DP_WAVES - 1) / DP_WAVES;
     if (bp < 1) bp = 1;
@@ -584,13 +593,13 @@ void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, 
     int g = 1;
     while (g < P) g <<= 1;
     switch (g) {
-    case 1: launch_hist<1>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
-    case 2: launch_hist<2>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
-    case 4: launch_hist<4>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
-    case 8: launch_hist<8>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
-    case 16: launch_hist<16>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
-    case 32: launch_hist<32>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
-    default: launch_hist<64>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, stream); break;
+    case 1: launch_hist<1>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
+    case 2: launch_hist<2>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
+    case 4: launch_hist<4>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
+    case 8: launch_hist<8>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
+    case 16: launch_hist<16>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
+    case 32: launch_hist<32>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
+    default: launch_hist<64>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
     }
     const int rows_pair = pass == 0 ? P : P * nq, rows_cls = pass == 0 ? 2 * (P + 1) : P * nq;
     const int rows_max = rows_pair > rows_cls ? rows_pair : rows_cls;
