@@ -109,6 +109,8 @@ def main() -> int:
             self.templ = [D.Policy(mode=D.MODE_S, mig_mode=mig) for _ in self.levels]
             self.specs = [dict(which_param=D.PARAM_L_TH, which_acc="server_prefill_tok", n_steps=self.lth_steps,
                                lo=0, hi=self.lmax + 1, target=num * self.sum_l / den) for num, den in self.levels]
+            # the same table and specs every step: marshalled once
+            self.templ_c, self.specs_c = D.prepare_policies(self.templ), D.prepare_specs(self.specs)
             self.sout = torch.zeros(self.P * D.binding.SEARCH_DTYPE.itemsize, dtype=torch.uint8, device="cuda")
             self.pol_out = torch.zeros(self.P * 32, dtype=torch.uint8, device="cuda")
             self.pols = None
@@ -122,7 +124,7 @@ def main() -> int:
 
         def search(self):
             """Budget levels -> length thresholds; the found columns stay on the device."""
-            res = D.disco_budget_search(self.trace, self.cfg["cost"], self.templ, self.specs, ws=self.ws,
+            res = D.disco_budget_search(self.trace, self.cfg["cost"], self.templ_c, self.specs_c, ws=self.ws,
                                         out=self.sout, pol_out=self.pol_out, acc=self.acc)
             self.pols = res["policies"]
 

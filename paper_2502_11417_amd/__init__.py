@@ -7,5 +7,5 @@ from .binding import (  # noqa: F401
     accum_to_host, disco_average_runs, disco_budget_search, disco_solve_policy, solve_to_host,
     disco_device_profile, disco_fit_lognormal, disco_ingest_trace, fit_to_host, disco_eval_dispatch, disco_eval_migration, disco_gen_trace,
     disco_reduce_stats, disco_workspace_bytes, policies_to_host, search_to_host, stats_to_host,
-    upload_trace, workspace,
+    prepare_policies, prepare_specs, upload_trace, workspace,
 )

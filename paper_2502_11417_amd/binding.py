@@ -241,10 +241,28 @@ class DevicePolicies:
 def _policies(policies):
     if isinstance(policies, DevicePolicies):
         return C.cast(C.c_void_p(policies.buf.data_ptr()), C.POINTER(CPolicy))
+    if isinstance(policies, C.Array):              # marshalled before (prepare_policies)
+        return policies
     arr = (CPolicy * max(len(policies), 1))()
     for j, p in enumerate(policies):
         arr[j] = CPolicy(p.mode, p.l_th, p.l_mid, p.w_mid, p.beta, p.w_tail, p.mig_mode, 0)
     return arr
+
+
+def prepare_policies(policies) -> C.Array:
+    """The host policy table as the C array the entry points take; pass it instead of the list to skip the
+    marshalling in a loop that calls with the same table."""
+    return _policies(list(policies))
+
+
+def prepare_specs(specs) -> C.Array:
+    """Search specs (see ``disco_budget_search``) as a C array, for repeated calls."""
+    sp = (CSearchSpec * max(len(specs), 1))()
+    for j, s in enumerate(specs):
+        wa = s["which_acc"]
+        sp[j] = CSearchSpec(int(s["which_param"]), ACC[wa] if isinstance(wa, str) else int(wa), int(s["n_steps"]), 0,
+                            float(s["lo"]), float(s["hi"]), float(s["target"]))
+    return sp
 
 
 def _cost(cost: dict) -> CCost:
@@ -470,11 +488,7 @@ def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Te
     dev = trace.prompt_len.device if trace.prompt_len is not None else "cuda"
     if ws is None:
         ws = workspace(trace.n_req, n, dev)
-    sp = (CSearchSpec * max(n, 1))()
-    for j, s in enumerate(specs):
-        wa = s["which_acc"]
-        sp[j] = CSearchSpec(int(s["which_param"]), ACC[wa] if isinstance(wa, str) else int(wa), int(s["n_steps"]), 0,
-                            float(s["lo"]), float(s["hi"]), float(s["target"]))
+    sp = specs if isinstance(specs, C.Array) else prepare_specs(specs)
     if out is None:
         out = torch.zeros(max(n, 1) * SEARCH_DTYPE.itemsize, dtype=torch.uint8, device=dev)
     if pol_out is None:

@@ -481,37 +481,10 @@ __global__ __launch_bounds__(1024) void k_len_reduce(int nbins, int nslices, con
     }
 }
 
-// In place: table[L] = sum over v >= L of table[v], plus the lengths beyond
-// the table; table[nbins] = those lengths alone.  One workgroup.
-__global__ __launch_bounds__(1024) void k_len_suffix(int nbins, u64* table, u64* other)
+// All bisection steps of search `c` from the table.
+__device__ __forceinline__ void search_from_table(int c, int nbins, const u64* table, SearchState* st_, disco_policy* pol,
+                                                  disco_search_out* sout)
 {
-    __shared__ u64 part[1024];
-    const int per = (nbins + 1023) / 1024;
-    const int t0 = threadIdx.x * per;
-    u64 sum = 0;
-    for (int q = 0; q < per; ++q) if (t0 + q < nbins) sum += table[t0 + q];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    for (int d = 1; d < 1024; d <<= 1) {            // inclusive suffix sums of the per-thread totals
-        const u64 o = (threadIdx.x + d < 1024) ? part[threadIdx.x + d] : 0;
-        __syncthreads();
-        part[threadIdx.x] += o;
-        __syncthreads();
-    }
-    const u64 beyond = *other;
-    u64 above = ((threadIdx.x + 1 < 1024) ? part[threadIdx.x + 1] : 0) + beyond;
-    for (int q = per - 1; q >= 0; --q) {
-        if (t0 + q < nbins) { above += table[t0 + q]; table[t0 + q] = above; }
-    }
-    if (threadIdx.x == 0) { table[nbins] = beyond; *other = 0; }
-}
-
-// All bisection steps of every column from the table (thread = column).
-__global__ void k_search_table(int n, int nbins, const u64* __restrict__ table, SearchState* st_, disco_policy* pol,
-                               disco_search_out* sout)
-{
-    const int c = threadIdx.x;
-    if (c >= n) return;
     SearchState st = st_[c];
     disco_policy p = pol[c];
     while (st.step < st.n_steps) {
@@ -522,6 +495,55 @@ __global__ void k_search_table(int n, int nbins, const u64* __restrict__ table, 
     }
     st_[c] = st;
     pol[c] = p;
+}
+
+// In place: table[L] = sum over v >= L of table[v], plus the lengths beyond
+// the table; table[nbins] = those lengths alone.  One workgroup; with
+// n_search > 0 its first threads then run the searches (thread = column).
+__global__ __launch_bounds__(1024) void k_len_suffix(int nbins, u64* table, u64* other, int n_search, SearchState* st_,
+                                                     disco_policy* pol, disco_search_out* sout)
+{
+    // Tiles of 8192 lengths from the top down: loaded coalesced into LDS, eight consecutive lengths per thread
+    // (rows padded by one element per eight against bank conflicts), suffix scan of the thread totals, stored back
+    // coalesced; `carry` = everything above the tile.
+    constexpr int TILE = 8192;
+    __shared__ u64 tile[TILE + TILE / 8];
+    __shared__ u64 part[1024];
+    __shared__ u64 carry_s;
+    const int t = threadIdx.x;
+    const u64 beyond = *other;
+    u64 carry = beyond;
+    for (int hi = nbins; hi > 0; hi -= TILE) {
+        const int lo = hi > TILE ? hi - TILE : 0, len = hi - lo;
+        for (int i = t; i < len; i += 1024) tile[i + (i >> 3)] = table[lo + i];
+        __syncthreads();
+        u64 sum = 0;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) if (8 * t + q < len) sum += tile[9 * t + q];
+        part[t] = sum;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {        // inclusive suffix sums of the per-thread totals
+            const u64 o = (t + d < 1024) ? part[t + d] : 0;
+            __syncthreads();
+            part[t] += o;
+            __syncthreads();
+        }
+        u64 above = ((t + 1 < 1024) ? part[t + 1] : 0) + carry;
+#pragma unroll
+        for (int q = 7; q >= 0; --q)
+            if (8 * t + q < len) { above += tile[9 * t + q]; tile[9 * t + q] = above; }
+        __syncthreads();
+        for (int i = t; i < len; i += 1024) table[lo + i] = tile[i + (i >> 3)];
+        if (t == 0) carry_s = tile[0];              // all lengths from `lo` up
+        __syncthreads();
+        carry = carry_s;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) { table[nbins] = beyond; *other = 0; }
+    if (n_search <= 0) return;
+    __threadfence();                                // the table is read back by other threads of this workgroup
+    __syncthreads();
+    if ((int)threadIdx.x < n_search) search_from_table(threadIdx.x, nbins, table, st_, pol, sout);
 }
 
 unsigned dispatch_blocks(i64 units, i64 per_block)
@@ -582,8 +604,8 @@ void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int 
 
 // table[L] = prompt tokens of the requests of length >= L for L < nbins, table[nbins] = those of longer requests
 // (see k_len_hist).  `scratch` holds the workgroup slices; *other must be zero and is zero again afterwards.
-void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, size_t scratch_bytes, u64* table, u64* other,
-                            hipStream_t stream)
+static void launch_len_table(const TraceView& v, int nbins, unsigned* scratch, size_t scratch_bytes, u64* table, u64* other,
+                             int n_search, SearchState* st, disco_policy* pol, disco_search_out* sout, hipStream_t stream)
 {
     i64 blocks = (v.n_req + DP_BLOCK - 1) / DP_BLOCK;
     const i64 fit = (i64)(scratch_bytes / ((size_t)nbins * sizeof(unsigned)));
@@ -593,16 +615,22 @@ void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, si
     hipLaunchKernelGGL(k_len_hist, dim3((unsigned)blocks), dim3(DP_BLOCK), 0, stream, v, nbins, scratch, other);
     hipLaunchKernelGGL(k_len_reduce, dim3((unsigned)((nbins + 63) / 64)), dim3(1024), 0, stream, nbins, (int)blocks, scratch,
                        table);
-    hipLaunchKernelGGL(k_len_suffix, dim3(1), dim3(1024), 0, stream, nbins, table, other);
+    hipLaunchKernelGGL(k_len_suffix, dim3(1), dim3(1024), 0, stream, nbins, table, other, n_search, st, pol, sout);
 }
 
-// Tabulated threshold search: the table, then every bisection step of every column from it.
+void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, size_t scratch_bytes, u64* table, u64* other,
+                            hipStream_t stream)
+{
+    launch_len_table(v, nbins, scratch, scratch_bytes, table, other, 0, nullptr, nullptr, nullptr, stream);
+}
+
+// Tabulated threshold search: the table, then every bisection step of every column from it (in the kernel that
+// finishes the table).
 void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsigned* scratch, size_t scratch_bytes,
                                u64* table, u64* other, SearchState* st, disco_policy* pol, disco_search_out* sout,
                                hipStream_t stream)
 {
-    disco_launch_len_table(v, nbins, scratch, scratch_bytes, table, other, stream);
-    hipLaunchKernelGGL(k_search_table, dim3(1), dim3(64), 0, stream, n_search, nbins, table, st, pol, sout);
+    launch_len_table(v, nbins, scratch, scratch_bytes, table, other, n_search, st, pol, sout, stream);
 }
 
 int disco_search_table_max_bins(void) { return LH_MAX_BINS; }

@@ -189,16 +189,26 @@ __global__ __launch_bounds__(SQ_BLOCK) void k_sq_hist(const float* __restrict__ 
     }
 }
 
-// Step 3, digit choice: workgroup = slot, thread = bin.
-__global__ __launch_bounds__(256) void k_sq_select(int nslot, int nslices, const unsigned* __restrict__ slices, SolveState* S)
+// Step 3, digit choice: workgroup = slot, thread = (bin, quarter of the slices).
+__global__ __launch_bounds__(1024) void k_sq_select(int nslot, int nslices, const unsigned* __restrict__ slices, SolveState* S)
 {
+    __shared__ u64 part[1024];
     __shared__ u64 wsum[4];
-    const int sidx = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int sidx = blockIdx.x, t = threadIdx.x & 255, q = threadIdx.x >> 8, lane = t & 63, wave = t >> 6;
     SolveSlot sl = S->slot[sidx];
     if (!sl.live) return;
-    u64 mine = 0;
+    const size_t step = (size_t)nslot << 8;
     const unsigned* src = slices + ((size_t)sidx << 8) + t;
-    for (int b = 0; b < nslices; ++b) mine += src[(size_t)b * ((size_t)nslot << 8)];
+    unsigned a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    int b = q;
+    for (; b + 12 < nslices; b += 16) {
+        a0 += src[(size_t)b * step]; a1 += src[(size_t)(b + 4) * step];
+        a2 += src[(size_t)(b + 8) * step]; a3 += src[(size_t)(b + 12) * step];
+    }
+    for (; b < nslices; b += 4) a0 += src[(size_t)b * step];
+    part[threadIdx.x] = (u64)a0 + a1 + a2 + a3;
+    __syncthreads();
+    const u64 mine = part[t] + part[256 + t] + part[512 + t] + part[768 + t];     // every quarter computes the same sums
     u64 incl = mine;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -206,11 +216,11 @@ __global__ __launch_bounds__(256) void k_sq_select(int nslot, int nslices, const
         const unsigned hi = (unsigned)__shfl_up((int)(unsigned)(incl >> 32), d, 64);
         if (lane >= d) incl += ((u64)hi << 32) | lo;
     }
-    if (lane == 63) wsum[wave] = incl;
+    if (q == 0 && lane == 63) wsum[wave] = incl;
     __syncthreads();
     for (int w = 0; w < wave; ++w) incl += wsum[w];
     const u64 k = (u64)sl.k_rem;
-    if (incl >= k && incl - mine < k) {             // exactly one bin holds the remaining rank
+    if (q == 0 && incl >= k && incl - mine < k) {   // exactly one bin holds the remaining rank
         sl.k_rem = (i64)(k - (incl - mine));
         sl.prefix = (sl.prefix << 8) | (unsigned)t;
         S->slot[sidx] = sl;
@@ -258,7 +268,7 @@ void disco_launch_solve(const TraceView& v, const disco_solve_spec* spec, int n,
     if (blocks < 1) blocks = 1;
     for (int pass = 0; pass < 4; ++pass) {
         hipLaunchKernelGGL(k_sq_hist, dim3((unsigned)blocks), dim3(SQ_BLOCK), 0, stream, v.s, v.n_req, nslot, pass, S, scratch);
-        hipLaunchKernelGGL(k_sq_select, dim3((unsigned)nslot), dim3(256), 0, stream, nslot, (int)blocks, scratch, S);
+        hipLaunchKernelGGL(k_sq_select, dim3((unsigned)nslot), dim3(1024), 0, stream, nslot, (int)blocks, scratch, S);
     }
     hipLaunchKernelGGL(k_solve_final, dim3(1), dim3(64), 0, stream, n, S, pol_out, out);
 }

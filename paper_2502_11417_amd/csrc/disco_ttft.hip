@@ -46,7 +46,7 @@ constexpr int TH_ROWS = 2 * DISCO_MAX_COLS + 2;         // class pass 0: (device
 constexpr int TH_PAD = 1;                               // skew: equal digits of different rows hit different banks
 constexpr int TH_STRIDE = 256 + TH_PAD;
 constexpr int TH_WORDS = TH_ROWS * TH_STRIDE;           // 131 KB of LDS bins
-constexpr int TC_MAX_BLOCKS = 128;                      // class kernel: little arithmetic, fewer slices to add up
+constexpr int TC_MAX_BLOCKS = 240;                      // class kernel: slices of all workgroups must fit the 32 MB slice region
 
 struct PassDigit { int width, shift, up; unsigned dmask; };
 
