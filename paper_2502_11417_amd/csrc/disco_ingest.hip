@@ -42,7 +42,22 @@ __global__ __launch_bounds__(IG_BLOCK) void k_ingest(i64 n_req, const double* __
             output_len[i] = (int32_t)(b - a);
             srv_ttft[i] = (float)(first - t_send[i]);
         }
-        for (i64 j = a + lane; j < b; j += 64) tok_arr[j] = (float)(t_token[j] - first);
+        // two timestamps per lane and step (16-byte loads, 8-byte stores) from the first even token on
+        const i64 a2 = (a + 1) & ~(i64)1;
+        if (lane == 0 && a2 > a) tok_arr[a] = 0.0f;
+        const bool pair_ok = ((((uintptr_t)t_token) & 15u) == 0) && ((((uintptr_t)tok_arr) & 7u) == 0);
+        if (pair_ok) {
+            i64 j = a2 + 2 * lane;
+            for (; j + 1 < b; j += 128) {
+                const double2 v = *reinterpret_cast<const double2*>(t_token + j);
+                float2 o;
+                o.x = (float)(v.x - first); o.y = (float)(v.y - first);
+                *reinterpret_cast<float2*>(tok_arr + j) = o;
+            }
+            if (j < b) tok_arr[j] = (float)(t_token[j] - first);
+        } else {
+            for (i64 j = a2 + lane; j < b; j += 64) tok_arr[j] = (float)(t_token[j] - first);
+        }
     }
 }
 
