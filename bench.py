@@ -266,7 +266,7 @@ def main() -> int:
             t_tl = event_time(lambda: D.disco_eval_migration(w.trace, tau, w.cfg["kappa"], w.pols, ws=w.ws, acc=w.acc,
                                                              cost=w.cfg["cost"]), 3 if k == 4 else 10)
             gb = (4.0 * w.T + 28.0 * w.N) / 1e9
-            kern = "k_timeline" if buffer else "k_tl_stats"      # tables with buffer hand-off columns: general kernel
+            kern = "k_tl_stats_buf" if buffer else "k_tl_stats"    # pairs with a buffer hand-off: their own statistics kernel
             ex["timeline_kernel"] = {"bound": "hbm", "kernel": kern, "launch_ms": t_tl * 1e3, "achieved_GBs": gb / t_tl,
                                      "frac": gb / t_tl / HBM_PEAK_GBS,
                                      "traffic": measured_traffic(kern, name)}

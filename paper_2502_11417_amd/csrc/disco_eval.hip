@@ -442,20 +442,13 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
     a.acc = acc;
     a.S = (SelState*)(ws + L.sel);
     a.ghist = (unsigned*)(ws + L.ghist);
-    // Streaming kernel, unless per-token deliveries are wanted or the table has a buffer hand-off column (then
-    // the general kernel; for a device-resident table both are launched and one of them returns at once).
-    bool any_buffer = false, table_known = !is_device_pointer(pol);
-    for (int j = 0; j < P && table_known; ++j) any_buffer = any_buffer || pol[j].mig_mode == DISCO_MIG_BUFFER;
-    if (a.delivered || (table_known && any_buffer)) {
+    // Streaming kernels (lag-trigger and plain pairs, then the pairs with a buffer hand-off), unless per-token
+    // deliveries are wanted: then the general kernel.
+    if (a.delivered)
         disco_launch_timeline_general(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
-    } else {
+    else
         disco_launch_tl_stats_fast(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a,
                                    tl_totals((DispPartial*)(ws + L.part)), stream);
-        if (!table_known) {
-            a.only_if_buffer = 1;
-            disco_launch_timeline_general(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
-        }
-    }
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }
@@ -515,6 +508,7 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;
                 disco_launch_tl_hist_fast(v, trace->n_tok, dpol, a, stream);
+                disco_launch_tl_hist_buf(v, trace->n_tok, dpol, a, stream);
                 disco_launch_timeline_general(v, trace->n_tok, dpol, a, stream);
                 disco_launch_tbt_advance(S, P, nq, gh, a.ppcnt, tl->tau, pass, stream);
             }

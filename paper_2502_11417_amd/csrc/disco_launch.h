@@ -16,7 +16,6 @@ struct TimelineArgs {
     int32_t* delay_num;       // materialised delayed-token counts (buffer hand-off), nullable
     BufCostArgs bc;           // prices of the buffer hand-off's cost test
     const unsigned* buffer_flag;   // device: 1 if the staged table has a buffer hand-off column
-    int only_if_buffer;       // general statistics kernel: act only when *buffer_flag is set
 };
 
 // How the last workgroup of a dispatch pass hands on the column totals.
@@ -40,6 +39,11 @@ void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsi
 int disco_search_table_max_bins(void);
 void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, size_t scratch_bytes, u64* table, u64* other,
                             hipStream_t stream);
+// Pairs with the buffer hand-off in class mode (both return at once when the staged table has no such column).
+void disco_launch_tl_stats_buf(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
+                               MigPartial* totals, hipStream_t stream);
+void disco_launch_tl_hist_buf(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
+                              hipStream_t stream);
 // Recorded traces: timestamps to relative arrays; log-normal fit (`scratch`: disco_fit_scratch_bytes() bytes).
 void disco_launch_ingest(i64 n_req, const double* t_send, const double* t_token, const i64* off, float* srv_ttft,
                          int32_t* output_len, float* tok_arr, hipStream_t stream);

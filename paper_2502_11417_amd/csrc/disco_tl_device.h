@@ -68,23 +68,35 @@ __device__ __forceinline__ void load4(const float* __restrict__ arr, i64 g, i64 
 
 // ---------------------------------------------------------- column sets ----
 
-// The three column sets of a request (lane = request): columns whose source is
-// the device [0], the server without hand-off [1], the server with the lag
-// trigger [2].
-__device__ __forceinline__ void request_sets(const disco_policy* sp, int P, int l, float s, float d, i64 i, u64 m[3])
+// Kinds of timeline of a (request, column) pair.
+enum { TL_DEV = 0,        // device source
+       TL_SRV = 1,        // server source, no hand-off
+       TL_SRV_LAG = 2,    // server source with the lag trigger
+       TL_SRV_BUF = 3,    // server source with the buffer hand-off (target: device)
+       TL_DEV_BUF = 4,    // device source with the buffer hand-off (target: server)
+       TL_KINDS = 5 };
+
+// The column sets of a request by kind of timeline (lane = request).  The
+// buffer hand-off (Sec. 4.3) applies when the source is the column's
+// constrained endpoint.
+__device__ __forceinline__ void request_sets(const disco_policy* sp, int P, int l, float s, float d, i64 i, u64 m[TL_KINDS])
 {
-    u64 m0 = 0ull, m1 = 0ull, m2 = 0ull;
+    u64 m0 = 0ull, m1 = 0ull, m2 = 0ull, m3 = 0ull, m4 = 0ull;
     for (int j = 0; j < P; ++j) {
         unsigned dec; float t;
         dispatch_pair(sp[j], l, s, d, i, dec, t);
         const bool dev = (dec & 4u) != 0u;
-        const bool lagm = sp[j].mig_mode == DISCO_MIG_LAG;
+        const int mg = sp[j].mig_mode, mode = sp[j].mode;
+        const bool dev_constrained = mode == DISCO_MODE_DEVICE_CONSTRAINED || mode == DISCO_MODE_STOCH_DEVICE;
+        const bool buf = mg == DISCO_MIG_BUFFER && (dev == dev_constrained);
         const u64 bit = 1ull << j;
-        m0 |= dev ? bit : 0ull;
-        m1 |= (!dev && !lagm) ? bit : 0ull;
-        m2 |= (!dev && lagm) ? bit : 0ull;
+        m4 |= (dev && buf) ? bit : 0ull;
+        m0 |= (dev && !buf) ? bit : 0ull;
+        m3 |= (!dev && buf) ? bit : 0ull;
+        m2 |= (!dev && !buf && mg == DISCO_MIG_LAG) ? bit : 0ull;
+        m1 |= (!dev && !buf && mg != DISCO_MIG_LAG) ? bit : 0ull;
     }
-    m[0] = m0; m[1] = m1; m[2] = m2;
+    m[TL_DEV] = m0; m[TL_SRV] = m1; m[TL_SRV_LAG] = m2; m[TL_SRV_BUF] = m3; m[TL_DEV_BUF] = m4;
 }
 
 // Pure pacing: a source whose constant gap is safely below tau (gap < 0.999 tau).

@@ -1,0 +1,199 @@
+// The general walker of a token timeline (Sec. 4.3): every kind of source and
+// hand-off, one scan per chunk, per-token deliveries and gaps handed to a
+// sink.  Used by the general kernel and by the kernels that walk the buffer
+// hand-off timelines; the lag-trigger and plain timelines of the streaming
+// kernels have leaner walkers of their own.
+#pragma once
+#include "disco_tl_device.h"
+
+namespace {
+
+// ------------------------------------------------------------- timeline ----
+
+struct TimelineResult { int m; float t_last; int delay; };
+
+// Prices behind the buffer hand-off's cost test (Sec. 4.3: saving > overhead).
+typedef BufCostArgs BufCost;
+
+// Timeline of one request and source.
+//   variant 0: device source, 1: server source, 2: server source with the lag trigger,
+//           3: server source with the buffer hand-off (target device),
+//           4: device source with the buffer hand-off (target server)
+//   arr/off/n_tok: CSR token array of the server or arr == nullptr (constant gap `gap_srv`)
+//   deliv: nullable, delivery offsets of the request's tokens
+//   sink(key[4], ok[4]): called once per chunk by all lanes (ok marks real gaps)
+// Returns m = the lag trigger's first device token, or the last source token of a buffer hand-off.
+template <class Sink>
+__device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const float* __restrict__ arr, i64 off, i64 n_tok,
+                                                       int align, float gap_srv, float g_dev, int l, float k, float c,
+                                                       float s_ttft, const BufCost& bc, float tau, float kt, int lane,
+                                                       float* __restrict__ deliv, Sink&& sink)
+{
+    const bool src_dev = variant == 0 || variant == 4;
+    const bool buffer = variant >= 3;
+    const bool from_mem = !src_dev && arr != nullptr;       // source arrivals come from the token array
+    const bool tgt_mem = variant == 4 && arr != nullptr;    // the target's arrivals follow the token array
+    const bool use_mem = from_mem || tgt_mem;
+    const double dc = variant == 3 ? bc.dc_srv : bc.dc_dev, cp = variant == 3 ? bc.cp_srv : bc.cp_dev;
+    // element 0 of the window is the aligned-down start: the first `mis` elements precede the request
+    const int mis = use_mem ? (int)((off + align) & 3) : 0;
+    const i64 gbase = off - mis + 4 * lane;
+    float carryM = -INFINITY, carryD = INFINITY, base = 0.0f, t_last = 0.0f, a_m = 0.0f;
+    int m = -1, delay = 0;
+    float nxt[4] = {0.f, 0.f, 0.f, 0.f};
+    if (use_mem && 4 * lane - mis < n) load4(arr, gbase, n_tok, nxt);
+    const int total = n + mis;
+    for (int e0 = 0; e0 < total; e0 += 256) {
+        const int tb = e0 + 4 * lane - mis;                 // token index of this lane's first element
+        float r[4], a[4];
+        int tk[4];
+        float tf[4];
+        bool val[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { tk[q] = tb + q; tf[q] = (float)tk[q]; val[q] = tk[q] >= 0 && tk[q] < n; a[q] = 0.0f; }
+        if (use_mem && (m < 0 || tgt_mem)) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) a[q] = nxt[q];
+            if (e0 + 256 < total && tb + 256 < n) load4(arr, gbase + e0 + 256, n_tok, nxt);   // next chunk in flight
+        }
+        // arrivals of the spliced sequence
+        auto arrival = [&](int q) -> float {
+            if (m >= 0 && !buffer) return __fmaf_rn((float)(tk[q] - m + 1), g_dev, base);      // lag: device from token m
+            if (m >= 0 && tk[q] > m) {                                                           // buffer: target after token m
+                if (variant == 3) return __fmaf_rn((float)(tk[q] - m), g_dev, base);
+                if (tgt_mem) { const float since = a[q] - a_m; return base + since; }
+                return __fmaf_rn((float)(tk[q] - m), gap_srv, base);
+            }
+            if (src_dev) return tf[q] * g_dev;
+            return from_mem ? a[q] : tf[q] * gap_srv;
+        };
+#pragma unroll
+        for (int q = 0; q < 4; ++q) r[q] = val[q] ? arrival(q) : -INFINITY;
+        float d[4], prev[4];
+        float Mlast;
+        auto scan = [&]() {
+            float u[4], mx[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) u[q] = __fmaf_rn(-tf[q], tau, r[q]);      // -inf for lanes outside the request
+            mx[0] = u[0]; mx[1] = fmaxf(mx[0], u[1]); mx[2] = fmaxf(mx[1], u[2]); mx[3] = fmaxf(mx[2], u[3]);
+            const float incl = wave_incl_max_dpp(mx[3], lane);
+            const float excl = fmaxf(wave_prev(incl, -INFINITY), carryM);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) d[q] = __fmaf_rn(tf[q], tau, fmaxf(excl, mx[q]));
+            Mlast = fmaxf(excl, mx[3]);
+            prev[0] = wave_prev(d[3], carryD);
+            prev[1] = d[0]; prev[2] = d[1]; prev[3] = d[2];
+        };
+        scan();
+        if (variant == 2 && m < 0) {
+            bool trig[4];
+            float slot[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                slot[q] = prev[q] + tau;
+                const float lag = r[q] - slot[q];
+                trig[q] = val[q] && tk[q] >= 1 && lag > kt;
+            }
+            const u64 any = __ballot(trig[0] || trig[1] || trig[2] || trig[3]);
+            if (any) {
+                const int ml = __ffsll((long long)any) - 1;
+                const int qf = trig[0] ? 0 : (trig[1] ? 1 : (trig[2] ? 2 : 3));
+                const float sl = trig[0] ? slot[0] : (trig[1] ? slot[1] : (trig[2] ? slot[2] : slot[3]));
+                const int q_m = bcast_i(qf, ml);
+                m = bcast_i(tb, ml) + q_m;
+                // hand-off: decided once the token is kappa*tau overdue; the device re-prefills the
+                // prompt plus the m tokens already produced, then generates at its own pace
+                const float t_dec = bcast_f(sl, ml) + kt;
+                const float t_mig = __fmaf_rn((float)(l + m), k, c);
+                base = t_dec + t_mig;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (tk[q] >= m) r[q] = val[q] ? arrival(q) : -INFINITY;
+                scan();
+            }
+        }
+        if (buffer && m < 0) {
+            // buffer hand-off after the first token whose playback time ahead covers the migration time and whose
+            // remaining decode saving exceeds the target's prefill overhead
+            bool trig[4];
+            float tm[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float slack = d[q] - r[q];
+                tm[q] = variant == 4 ? s_ttft : __fmaf_rn((float)(l + tk[q] + 1), k, c);
+                const double saved = dc * (double)(n - 1 - tk[q]);
+                const double overhead = cp * (double)(l + tk[q] + 1);
+                trig[q] = val[q] && tk[q] + 1 < n && slack >= tm[q] && saved > overhead;
+            }
+            const u64 any = __ballot(trig[0] || trig[1] || trig[2] || trig[3]);
+            if (any) {
+                const int ml = __ffsll((long long)any) - 1;
+                const int qf = trig[0] ? 0 : (trig[1] ? 1 : (trig[2] ? 2 : 3));
+                const float rm = trig[0] ? r[0] : (trig[1] ? r[1] : (trig[2] ? r[2] : r[3]));
+                const float tmm = trig[0] ? tm[0] : (trig[1] ? tm[1] : (trig[2] ? tm[2] : tm[3]));
+                const float am = trig[0] ? a[0] : (trig[1] ? a[1] : (trig[2] ? a[2] : a[3]));
+                m = bcast_i(tb, ml) + bcast_i(qf, ml);
+                base = bcast_f(rm, ml) + bcast_f(tmm, ml);
+                a_m = bcast_f(am, ml);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (tk[q] > m) r[q] = val[q] ? arrival(q) : -INFINITY;
+                scan();
+            }
+        }
+        unsigned key[4];
+        bool ok[4];
+        bool late[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float gap = d[q] - prev[q];
+            key[q] = f2u(gap);
+            ok[q] = val[q] && tk[q] >= 1;
+            late[q] = buffer && m >= 0 && val[q] && tk[q] > m && gap > tau;
+            if (deliv && val[q]) deliv[tk[q]] = d[q];
+        }
+        if (buffer && m >= 0)
+            delay += __popcll(__ballot(late[0])) + __popcll(__ballot(late[1])) + __popcll(__ballot(late[2])) +
+                     __popcll(__ballot(late[3]));
+        sink(key, ok);
+        carryM = bcast_f(Mlast, 63);
+        carryD = bcast_f(d[3], 63);
+        if (e0 + 256 >= total) {            // last chunk: delivery offset of token n-1
+            const int e = n - 1 + mis - e0;
+            const int q_l = e & 3;
+            const float dl = q_l == 0 ? d[0] : (q_l == 1 ? d[1] : (q_l == 2 ? d[2] : d[3]));
+            t_last = bcast_f(dl, e >> 2);
+        }
+    }
+    return TimelineResult{m, t_last, delay};
+}
+
+// Pure pacing: a source whose constant gap is safely below tau (gap < 0.999 tau).
+// Then u_0 = 0 and u_t = round(round(t gap) - t tau) < 0 for t >= 1 (the
+// product's rounding error is below 2^-24 relative, far inside the 1e-3
+// margin), the running maximum stays 0, delta_t = fma(t, tau, 0) = round(t tau),
+// and no token is ever overdue.  The result depends on n alone.
+template <class Sink>
+__device__ __forceinline__ TimelineResult run_pure_pacing(int n, float tau, int lane, float* __restrict__ deliv, bool need_keys,
+                                                          Sink&& sink)
+{
+    if (need_keys || deliv) {
+        for (int e0 = 0; e0 < n; e0 += 256) {
+            unsigned key[4];
+            bool ok[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int t = e0 + 4 * lane + q;
+                const float dq = (float)t * tau;
+                const float pq = (float)(t - 1) * tau;
+                key[q] = f2u(dq - pq);
+                ok[q] = t >= 1 && t < n;
+                if (deliv && t < n) deliv[t] = dq;
+            }
+            if (need_keys) sink(key, ok);
+        }
+    }
+    return TimelineResult{-1, (float)(n - 1) * tau, 0};
+}
+
+}  // namespace

@@ -26,14 +26,12 @@
 // only picks the timeline of its dispatch winner.
 #include <string.h>
 
-#include "disco_tl_device.h"
+#include "disco_tl_walk.h"
 
 namespace {
 
-constexpr int TF_RB = 16;                    // requests per wave batch
 constexpr int TS_BLOCK = 256;                // statistics kernel: 4 waves, no histogram
 constexpr int TH_BLOCK = 1024;               // histogram kernel: 16 waves share 64 KB of bins
-constexpr unsigned KEY_SKIP = 0x80000000u;   // a key with the sign bit never matches a prefix
 
 struct WalkOut { int m; float M; };          // hand-off index (-1 none), running maximum over all tokens
 
@@ -182,33 +180,6 @@ __device__ __forceinline__ void load_first(const float* __restrict__ arr, i64 of
     if (4 * lane - mis < n) load4(arr, off - mis + 4 * lane, n_tok, out);
 }
 
-// Per-request fields of a wave batch, lane = request (lanes >= TF_RB idle).
-struct Batch {
-    int l, n;
-    float k, gd, gap;
-    i64 off;
-    u64 m[3];
-};
-
-__device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_policy* spol, int P, i64 first, int lane)
-{
-    Batch b;
-    const i64 i = first + lane;
-    const bool v = lane < TF_RB && i < tr.n_req;
-    b.l = 0; b.n = 1; b.k = tr.k_s; b.gd = tr.g_s; b.gap = 0.0f; b.off = 0;
-    float s = 0.0f;
-    if (v) {
-        b.l = tr.l[i]; b.n = tr.n[i]; s = tr.s[i];
-        if (tr.k) b.k = tr.k[i];
-        if (tr.g) b.gd = tr.g[i];
-        if (tr.off) b.off = tr.off[i];
-        if (tr.tbt) b.gap = tr.tbt[i];
-    }
-    request_sets(spol, P, b.l, s, __fmaf_rn((float)b.l, b.k, tr.c), i, b.m);
-    if (!v) b.m[0] = b.m[1] = b.m[2] = 0ull;
-    return b;
-}
-
 // ------------------------------------------------------------ statistics ---
 
 struct StatsArgs {
@@ -217,7 +188,6 @@ struct StatsArgs {
     int32_t* mig_idx; int32_t* n_src_tok; float* t_last;
     int32_t* delay_num;            // all zero here: only buffer hand-offs count delayed tokens
     MigPartial* totals;            // DISCO_NCOPY x 64 device-wide totals
-    const unsigned* buffer_flag;   // set: the table has a buffer hand-off column and the general kernel takes it
 };
 
 // Statistics walk of one request and source: the hand-off index and the
@@ -325,12 +295,12 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
     __shared__ u64 sh[6 * TS_BLOCK];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int P = a.P;
-    if (*a.buffer_flag != 0u) return;
     if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
     __syncthreads();
     // lane = column: tokens decoded by the server, re-prefilled tokens, hand-offs, sum of last deliveries;
     // the number of tokens and of gaps is the same for every column (wave-uniform)
-    u64 acc_s_dec = 0, acc_repre = 0, tot_n = 0, tot_cnt = 0;
+    // (pairs with a buffer hand-off are left to k_tl_stats_buf: acc_n counts the tokens of the pairs handled here)
+    u64 acc_s_dec = 0, acc_repre = 0, acc_n = 0, tot_cnt = 0;
     unsigned acc_mig = 0;
     double acc_tlast = 0.0;
     const float tau = a.tau, kt = a.kt;
@@ -353,7 +323,6 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
             const float cur[4] = {pre[0], pre[1], pre[2], pre[3]};
             if ((memw >> (rq + 1)) & 1ull)          // the next request's first chunk is loaded while this one is walked
                 load_first(tr.arr, (i64)bcast_u64((u64)b.off, rq + 1), bcast_i(b.n, rq + 1), n_tok, align, lane, pre);
-            tot_n += (u64)n;
             tot_cnt += (u64)(n - 1);
             const u64 mask_lag = bcast_u64(b.m[2], rq);
             const u64 mask_plain = any_plain ? bcast_u64(b.m[1], rq) : 0ull;
@@ -390,6 +359,7 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
                 const float t_last = __fmaf_rn((float)(n - 1), tau, w.M);
                 const int nsrc = in_dev ? 0 : ((w.m >= 0) ? w.m : n);
                 acc_s_dec += (u64)nsrc;
+                acc_n += (u64)n;
                 if (w.m >= 0) { acc_mig += 1u; acc_repre += (u64)bcast_i(b.l, rq) + (u64)w.m; }
                 acc_tlast += (double)t_last;
                 if (mat) {
@@ -402,7 +372,7 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
         }
     }
     // lane = column: fold the waves of the workgroup, then add into this workgroup's copy of the totals
-    sh[0 * TS_BLOCK + threadIdx.x] = acc_s_dec; sh[1 * TS_BLOCK + threadIdx.x] = tot_n - acc_s_dec;
+    sh[0 * TS_BLOCK + threadIdx.x] = acc_s_dec; sh[1 * TS_BLOCK + threadIdx.x] = acc_n - acc_s_dec;
     sh[2 * TS_BLOCK + threadIdx.x] = acc_repre; sh[3 * TS_BLOCK + threadIdx.x] = (u64)acc_mig;
     sh[4 * TS_BLOCK + threadIdx.x] = tot_cnt; sh[5 * TS_BLOCK + threadIdx.x] = (u64)__double_as_longlong(acc_tlast);
     __syncthreads();
@@ -425,84 +395,25 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
 }
 
 // Totals -> accumulators; puts the totals back to zero for the next pass.
-__global__ void k_tl_stats_fin(int P, MigPartial* totals, disco_accum* acc, const unsigned* buffer_flag)
+__global__ void k_tl_stats_fin(int P, MigPartial* totals, disco_accum* acc)
 {
     const int c = threadIdx.x;
-    if (c >= P || *buffer_flag != 0u) return;
+    if (c >= P) return;
     MigPartial x{0, 0, 0, 0, 0, 0.0, {0, 0}};
     for (int k = 0; k < DISCO_NCOPY; ++k) {
         MigPartial* t = &totals[k * 64 + c];
         x.s_dec += t->s_dec; x.d_dec += t->d_dec; x.d_repre += t->d_repre; x.migrated += t->migrated;
         x.tbt_count += t->tbt_count; x.tlast_sum += t->tlast_sum;
+        x.pad[0] += t->pad[0]; x.pad[1] += t->pad[1];          // server re-prefill, delayed tokens (buffer hand-offs)
         *t = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
     }
     disco_accum* o = &acc[c];
     o->m_s_dec = (i64)x.s_dec; o->m_d_dec = (i64)x.d_dec; o->m_d_repre = (i64)x.d_repre;
     o->n_migrated = (i64)x.migrated; o->tbt_count = (i64)x.tbt_count; o->tlast_sum = x.tlast_sum;
-    o->m_s_repre = 0; o->delay_sum = 0;
+    o->m_s_repre = (i64)x.pad[0]; o->delay_sum = (i64)x.pad[1];
 }
 
 // ------------------------------------------------------------- histogram ---
-
-struct HistArgs {
-    float tau, kt;
-    int P, pass;
-    SelState* S;
-    unsigned* ghist;
-    unsigned* ppcnt;
-};
-
-// Digit of this pass and the rows of the LDS histogram.
-struct HistCtx {
-    unsigned* hist;
-    int shift, width, up, G;
-    unsigned key_lo, key_cap;      // see tbt_key
-    unsigned stride;               // words per prefix group = nwalk << width
-    unsigned grp_prefix[DISCO_MAX_GRP];
-};
-
-// Every key of the chunk goes to the histogram row (prefix group of the key,
-// class of the timeline).  The bin shared by most of the wave is counted with
-// ballots and added once; the rest is added lane by lane.
-__device__ __forceinline__ void hist_keys(const HistCtx& h, const unsigned key[4], unsigned row_base, int lane)
-{
-    const unsigned dmask = (1u << h.width) - 1u;
-    unsigned idx[4];
-    bool pend[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const unsigned kq = tbt_key(key[q], h.key_lo, h.key_cap);
-        const unsigned hi = kq >> h.up;                          // the flag of skipped or clamped keys stays in
-        unsigned g = 0;
-        bool hit = hi == h.grp_prefix[0];
-        if (h.G > 1) {
-#pragma unroll
-            for (int k = 1; k < DISCO_MAX_GRP; ++k) {
-                const bool hk = k < h.G && hi == h.grp_prefix[k] && !hit;
-                g = hk ? (unsigned)k : g;
-                hit = hit || hk;
-            }
-        }
-        pend[q] = hit;
-        idx[q] = g * h.stride + row_base + ((kq >> h.shift) & dmask);
-    }
-    const u64 todo = __ballot(pend[0] || pend[1] || pend[2] || pend[3]);
-    if (!todo) return;
-    const int leader = __ffsll((long long)todo) - 1;
-    const unsigned mine = pend[0] ? idx[0] : (pend[1] ? idx[1] : (pend[2] ? idx[2] : idx[3]));
-    const unsigned i0 = (unsigned)bcast_i((int)mine, leader);
-    unsigned cnt = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const bool same = pend[q] && idx[q] == i0;
-        cnt += (unsigned)__popcll(__ballot(same));
-        pend[q] = pend[q] && !same;
-    }
-    if (lane == leader) atomicAdd(&h.hist[i0], cnt);
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        if (pend[q]) atomicAdd(&h.hist[idx[q]], 1u);
-}
 
 __global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok, int align, const disco_policy* __restrict__ pol,
                                                       HistArgs a)
@@ -612,14 +523,14 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
     s.tau = a.tau; s.kt = a.kt; s.P = a.P;
     s.mig_idx = a.mig_idx; s.n_src_tok = a.n_src_tok; s.t_last = a.t_last; s.delay_num = a.delay_num;
     s.totals = totals;
-    s.buffer_flag = a.buffer_flag;
     const i64 per_block = (i64)(TS_BLOCK / 64) * TF_RB;
     i64 b = (v.n_req + per_block - 1) / per_block;
     if (b < 1) b = 1;
     if (b > 2048) b = 2048;                    // eight resident workgroups per CU
     const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
     hipLaunchKernelGGL(k_tl_stats, dim3((unsigned)b), dim3(TS_BLOCK), 0, stream, v, n_tok, align, pol, s);
-    hipLaunchKernelGGL(k_tl_stats_fin, dim3(1), dim3(64), 0, stream, a.P, totals, a.acc, a.buffer_flag);
+    disco_launch_tl_stats_buf(v, n_tok, pol, a, totals, stream);        // pairs with a buffer hand-off, if any
+    hipLaunchKernelGGL(k_tl_stats_fin, dim3(1), dim3(64), 0, stream, a.P, totals, a.acc);
 }
 
 void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,

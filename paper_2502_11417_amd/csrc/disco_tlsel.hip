@@ -104,7 +104,7 @@ __device__ __forceinline__ void insert_sets(u64 m, bool walked, u64* loc, u64* l
 //   parts: gridDim.x x (DISCO_MAX_CLS + 2) words of scratch
 __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
                                                      float tau, SelState* S, unsigned* ppcnt, unsigned* ghist, u64* parts,
-                                                     unsigned* ticket, const unsigned* buffer_flag)
+                                                     unsigned* ticket)
 {
     __shared__ disco_policy sp[DISCO_MAX_COLS];
     __shared__ u64 loc[DISCO_MAX_CLS];
@@ -122,8 +122,8 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
     const i64 nround = (tr.n_req + CL_BLOCK - 1) / CL_BLOCK;
     for (i64 rnd = blockIdx.x; rnd < nround; rnd += gridDim.x) {
         const i64 i = rnd * CL_BLOCK + threadIdx.x;
-        u64 m[3] = {0ull, 0ull, 0ull};
-        bool walked[3] = {false, false, false};
+        u64 m[TL_KINDS] = {0ull, 0ull, 0ull, 0ull, 0ull};
+        bool walked[TL_KINDS] = {false, false, false, true, true};      // hand-off timelines are always walked
         if (i < tr.n_req) {
             const int l = tr.l[i], n = tr.n[i];
             const float s = tr.s[i];
@@ -133,10 +133,10 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
             request_sets(sp, P, l, s, __fmaf_rn((float)l, k, tr.c), i, m);
             const bool short_n = n <= DISCO_PP_NMAX;
             walked[0] = !(short_n && pure_pacing(true, gd, tau));
-            walked[1] = walked[2] = !(short_n && pure_pacing(tr.arr == nullptr, gap, tau));
+            walked[TL_SRV] = walked[TL_SRV_LAG] = !(short_n && pure_pacing(tr.arr == nullptr, gap, tau));
         }
 #pragma unroll
-        for (int kind = 0; kind < 3; ++kind) insert_sets(m[kind], walked[kind], loc, &loc_walk, &overflow, wt, lane);
+        for (int kind = 0; kind < TL_KINDS; ++kind) insert_sets(m[kind], walked[kind], loc, &loc_walk, &overflow, wt, lane);
     }
     __syncthreads();
     u64* mine = parts + (size_t)blockIdx.x * (DISCO_MAX_CLS + 2);
@@ -174,9 +174,7 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
         }
         tl.nwalk = nw;
         tl.error = 0;
-        // more than DISCO_MAX_CLS distinct sets, or a buffer hand-off column (its timelines are only known to
-        // the general kernel): per-slot histograms
-        if (overflow || *buffer_flag != 0u) tl.fallback = 1;
+        if (overflow) tl.fallback = 1;                 // more than DISCO_MAX_CLS distinct sets: per-slot histograms
         // gaps sit just above the pacing interval (down to a few thousand ulps below it after rounding): try a
         // 21-bit window of keys first
         const unsigned tb = f2u(tau);
@@ -392,12 +390,11 @@ __global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, in
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
                               unsigned* ppcnt, unsigned* ghist, u64* parts, unsigned* ticket, hipStream_t stream)
 {
-    const unsigned* buffer_flag = ticket + DISCO_FLAG_BUFFER;     // the ticket region's flag word
     i64 b = (v.n_req + CL_BLOCK - 1) / CL_BLOCK;
     if (b < 1) b = 1;
     if (b > 256) b = 256;
     hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau, S, ppcnt, ghist, parts,
-                       ticket, buffer_flag);
+                       ticket);
 }
 
 void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,
