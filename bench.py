@@ -51,7 +51,7 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this path runs on one GPU; --gpus must be 1 (requests shard trivially, see DESIGN.md)",
+        print("bench.py: this path runs on one GPU; --gpus must be 1 (requests are independent and would shard by request)",
               file=sys.stderr)
         return 2
 

@@ -455,3 +455,23 @@ def test_migration_late_handoffs(B, oracle, kappa, tau):
     if kappa >= 1.0 and tau >= 0.05:
         assert (m >= 256).sum() > 10 and (m >= 512).sum() > 3, ((m >= 256).sum(), (m >= 512).sum())
     check_stats(B, oracle, tr, specs, DI.COST_S, tau=tau, kappa=kappa)
+
+
+@pytest.mark.parametrize("kind", ["thresholds", "mixed"])
+def test_stats_heavy_ties_keep_the_histogram_passes(B, oracle, kind):
+    """Most TTFTs are one and the same value while a few outliers keep the key range wide: the values that still
+    match a slot after two radix passes are too many for the candidate list (its bound adds up over 128 slots),
+    so the selection has to go on with histogram passes."""
+    print(f"stats parity heavy ties {kind}", flush=True)
+    rng = np.random.default_rng(23)
+    n = 60_000                   # 64 median slots x 0.9 n tied values: 3.4 M against a list of 2 M entries
+    tr = DI.handmade_trace(61, n, tokens=False)
+    tr["srv_ttft"] = np.where(rng.random(n) < 0.9, np.float32(0.5), tr["srv_ttft"]).astype(np.float32)
+    tr["dev_pre_spt"] = (tr["dev_pre_spt"] * np.float32(50)).astype(np.float32)       # the server wins nearly every race
+    if kind == "thresholds":
+        specs = [dict(mode=0, l_th=int(t)) for t in np.linspace(0, 400, 64)]
+    else:
+        specs = [dict(mode=0, l_th=int(t)) for t in np.linspace(0, 400, 32)] + \
+                [dict(mode=1, l_th=-1, w_tail=DI.f32(w)) for w in np.linspace(0.6, 3.0, 32)]
+    got, want = check_stats(B, oracle, tr, specs, DI.COST_S)
+    assert sum(1 for w in want if np.float32(w["ttft_q"][0]) == np.float32(0.5)) > 32
