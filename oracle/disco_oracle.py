@@ -321,7 +321,7 @@ def stats(tr: dict, policies, cost: dict, quantiles=((50, 100), (99, 100)),
             st["ttft_rank"].append(k)
             st["ttft_q"].append(v)
         if tau is not None:
-            mg = migration(tr, [policies[j]], tau, kappa, materialise=False, tbt_col=0, cost=cost)
+            mg = migration(tr, [policies[j]], tau, kappa, materialise=True, tbt_col=0, cost=cost)
             st["s_dec"] = int(mg["m_s_dec"][0])
             st["d_dec"] = int(mg["m_d_dec"][0])
             st["d_pre"] += int(mg["m_d_repre"][0])
@@ -335,6 +335,10 @@ def stats(tr: dict, policies, cost: dict, quantiles=((50, 100), (99, 100)),
                 k, v = quantile(mg["tbt"], num, den)
                 st["tbt_rank"].append(k)
                 st["tbt_q"].append(v)
+            # delayed tokens per migrated request (TBT table of Sec. 5.2: mean and P99 delay_num over the requests
+            # that migrated); nearest-rank order statistic like the others
+            delays = mg["delay_num"][0][mg["mig_idx"][0] >= 0].astype(np.float32)
+            st["delay_q"] = [quantile(delays, num, den)[1] for num, den in quantiles]
         st["server_cost"] = server_cost(cost, st["s_pre"], st["s_dec"])
         st["device_energy"] = device_energy(cost, st["d_pre"], st["d_dec"])
         st["device_cost"] = cost["lam"] * st["device_energy"]

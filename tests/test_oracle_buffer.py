@@ -159,3 +159,23 @@ def test_accounting_and_first_target_token(oracle):
     r2 = oracle.migration(tr, [pol[2]], 0.2, 3.0, cost=DI.COST_D)
     src_dev2 = (d["decision"][2] & 4) != 0
     assert (r2["mig_idx"][0][src_dev2] >= 0).sum() > 20 and not (r2["mig_idx"][0][~src_dev2] >= 0).any()
+
+
+def test_delay_num_order_statistics(oracle):
+    """Mean and tail of the delayed tokens over the migrated requests (TBT table of Sec. 5.2), against numpy on the
+    per-request counts, which the tests above pin."""
+    import disco_inputs as DI
+    tr = DI.handmade_trace(5, 400, tokens=True, max_out=120, stall_p=0.01)
+    tr["prompt_len"] = (tr["prompt_len"] % 48 + 1).astype(np.int32)
+    tr["dev_pre_spt"] = (tr["dev_pre_spt"] * np.float32(64)).astype(np.float32)
+    tr["dev_dec_spt"] = (tr["dev_dec_spt"] * np.float32(6)).astype(np.float32)      # slow device: late tokens after a hand-off
+    pol = [oracle.Policy(mode=0, l_th=0, mig_mode=2), oracle.Policy(mode=0, l_th=0, mig_mode=0)]
+    st = oracle.stats(tr, pol, DI.COST_S, quantiles=((50, 100), (99, 100), (0, 1), (1, 1)), tau=0.2, kappa=3.0)
+    r = oracle.migration(tr, pol, 0.2, 3.0, cost=DI.COST_S)
+    d = np.sort(r["delay_num"][0][r["mig_idx"][0] >= 0])
+    m = len(d)
+    assert m > 50 and d[-1] > 0
+    want = [d[max(-(-50 * m // 100), 1) - 1], d[max(-(-99 * m // 100), 1) - 1], d[0], d[-1]]
+    assert [float(x) for x in st[0]["delay_q"]] == [float(x) for x in want]
+    assert st[0]["delay_sum"] == int(d.sum())
+    assert all(np.isnan(x) for x in st[1]["delay_q"])                 # no migration, no order statistic
