@@ -348,7 +348,10 @@ typedef struct disco_stats {
     float ttft_q[DISCO_MAX_Q];                 /* the order statistic of that rank */
     float tbt_q[DISCO_MAX_Q];
     double mean_delay_num;                     /* delay_sum / n_migrated (NaN without hand-offs or timelines) */
-    int64_t reserved[4];
+    float delay_q[DISCO_MAX_Q];                /* order statistics of delay_num over the migrated requests (the
+                                                * TBT table of Sec. 5.2 reports its mean and P99); counts above
+                                                * 8190 are taken as 8191; NaN without hand-offs or timelines */
+    int64_t reserved[2];
 } disco_stats;
 
 typedef struct disco_quantile { int32_t num, den; } disco_quantile;   /* q = num/den in [0,1] */

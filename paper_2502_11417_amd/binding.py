@@ -120,7 +120,7 @@ STATS_DTYPE = np.dtype([
     ("n_req", "<i8"), ("tbt_count", "<i8"), ("n_migrated", "<i8"), ("n_dev_started", "<i8"), ("n_dev_win", "<i8"),
     ("ttft_rank", "<i8", (MAX_Q,)), ("tbt_rank", "<i8", (MAX_Q,)),
     ("ttft_q", "<f4", (MAX_Q,)), ("tbt_q", "<f4", (MAX_Q,)), ("mean_delay_num", "<f8"),
-    ("reserved", "<i8", (4,))])
+    ("delay_q", "<f4", (MAX_Q,)), ("reserved", "<i8", (2,))])
 SEARCH_DTYPE = np.dtype([
     ("param", "<f8"), ("acc_at_param", "<f8"), ("lo", "<f8"), ("hi", "<f8"),
     ("hist_param", "<f8", (MAX_STEPS,)), ("hist_acc", "<f8", (MAX_STEPS,)), ("at_param", ACCUM_DTYPE)])

@@ -167,7 +167,7 @@ __global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, 
     st.device_cost = cost.lambda * st.device_energy;
     st.total_cost = st.server_cost + st.device_cost;
     for (int qi = 0; qi < DISCO_MAX_Q; ++qi) {
-        st.ttft_q[qi] = NAN; st.tbt_q[qi] = NAN;
+        st.ttft_q[qi] = NAN; st.tbt_q[qi] = NAN; st.delay_q[qi] = NAN;
         if (qi < nq) {
             const SelSlot s0 = S->slot[0][c * nq + qi];
             st.ttft_rank[qi] = s0.rank;
@@ -208,6 +208,49 @@ __global__ void k_average_runs(const disco_stats* __restrict__ in, int groups, i
     o.device_cost = d[4] / n; o.total_cost = d[5] / n; o.mean_delay_num = d[6] / n;
     for (int k = 0; k < DISCO_MAX_Q; ++k) { o.ttft_q[k] = (float)(q[k] / n); o.tbt_q[k] = (float)(q[DISCO_MAX_Q + k] / n); }
     out[g] = o;
+}
+
+// Order statistics of the delayed tokens per migrated request (workgroup = column): the counts by number of
+// delayed tokens come from the first histogram pass of the timelines with a buffer hand-off; migrations of the
+// lag trigger have none and count as zeros.  Nearest rank, like the other order statistics.
+__global__ __launch_bounds__(256) void k_delay_quantiles(int nq, disco_quantile q0, disco_quantile q1, disco_quantile q2,
+                                                         disco_quantile q3, const disco_accum* acc,
+                                                         const unsigned* __restrict__ dhist, disco_stats* out)
+{
+    constexpr int PER = DISCO_DELAY_BINS / 256;
+    __shared__ u64 part[256];
+    const disco_quantile qs[4] = {q0, q1, q2, q3};
+    const int c = blockIdx.x, t = threadIdx.x;
+    const i64 M = acc[c].n_migrated;
+    if (M <= 0) return;                                  // the fields stay NaN
+    const unsigned* row = dhist + (size_t)c * DISCO_DELAY_BINS;
+    unsigned v[PER];
+    u64 mine = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) { v[k] = row[t * PER + k]; mine += v[k]; }
+    part[t] = mine;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {                  // inclusive prefix sums of the per-thread totals
+        const u64 o = t >= d ? part[t - d] : 0;
+        __syncthreads();
+        part[t] += o;
+        __syncthreads();
+    }
+    const u64 counted = part[255];
+    const u64 zeros = (u64)M > counted ? (u64)M - counted : 0;      // hand-offs without a count: no delayed token
+    if (t == 0) v[0] += (unsigned)zeros;
+    const u64 below = t > 0 ? part[t - 1] + zeros : 0;               // migrated requests with fewer delayed tokens than t * PER
+    for (int qi = 0; qi < nq; ++qi) {
+        i64 k = ((i64)qs[qi].num * M + qs[qi].den - 1) / qs[qi].den;
+        if (k < 1) k = 1;
+        if (k > M) k = M;
+        u64 cum = below;
+#pragma unroll
+        for (int b = 0; b < PER; ++b) {
+            if (cum < (u64)k && cum + v[b] >= (u64)k) out[c].delay_q[qi] = (float)(t * PER + b);
+            cum += v[b];
+        }
+    }
 }
 
 // ----------------------------------------------------------- search setup --
@@ -346,6 +389,7 @@ WsLayout disco_ws_layout(int32_t P)
     (void)P;
     o += up((size_t)DISCO_MAX_BLOCKS * 64 * 64);     // workgroups x columns x 64-byte partial
     L.ppcnt = o; o += up(sizeof(unsigned) * DISCO_MAX_CLS * (DISCO_PP_NMAX + 1));
+    L.dhist = o; o += up(sizeof(unsigned) * DISCO_MAX_COLS * DISCO_DELAY_BINS);
     L.slices = o; o += up((size_t)256 * DISCO_MAX_SLOTS * 256 * sizeof(unsigned));
     L.total = o;
     return L;
@@ -498,13 +542,14 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             a.ticket = (unsigned*)(ws + L.ticket);
             a.S = S; a.ghist = gh;
             a.bc = buffer_prices(tl->cost);          // the prices the statistics pass used
+            a.dhist = (unsigned*)(ws + L.dhist);
             a.buffer_flag = (unsigned*)(ws + L.ticket) + DISCO_FLAG_BUFFER;
             // column sets -> classes, then the radix passes; the digits are sized on the device and
             // launches after the last needed pass return at once
             a.ppcnt = (unsigned*)(ws + L.ppcnt);
             const disco_policy* dpol = (const disco_policy*)(ws + L.pol);
-            disco_launch_tl_classify(v, dpol, P, nq, tl->tau, S, a.ppcnt, gh, (u64*)(ws + L.slices), (unsigned*)(ws + L.ticket),
-                                     stream);
+            disco_launch_tl_classify(v, dpol, P, nq, tl->tau, S, a.ppcnt, gh, a.dhist, (u64*)(ws + L.slices),
+                                     (unsigned*)(ws + L.ticket), stream);
             for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;
                 disco_launch_tl_hist_fast(v, trace->n_tok, dpol, a, stream);
@@ -515,6 +560,9 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
         }
     }
     hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, stream, P, nq, v.n_req, *cost, tl ? 1 : 0, acc, S, out);
+    if (tl && nq > 0)
+        hipLaunchKernelGGL(k_delay_quantiles, dim3((unsigned)P), dim3(256), 0, stream, nq, qs[0], qs[1], qs[2], qs[3], acc,
+                           (const unsigned*)(ws + L.dhist), out);
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }

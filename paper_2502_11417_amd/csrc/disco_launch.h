@@ -16,6 +16,7 @@ struct TimelineArgs {
     int32_t* delay_num;       // materialised delayed-token counts (buffer hand-off), nullable
     BufCostArgs bc;           // prices of the buffer hand-off's cost test
     const unsigned* buffer_flag;   // device: 1 if the staged table has a buffer hand-off column
+    unsigned* dhist;               // histogram passes: migrated requests by number of delayed tokens, per column
 };
 
 // How the last workgroup of a dispatch pass hands on the column totals.
@@ -72,7 +73,7 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
 void disco_launch_timeline_general(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                    hipStream_t stream);
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
-                              unsigned* ppcnt, unsigned* ghist, u64* parts /* 1024 x 66 words of scratch */,
+                              unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts /* 1024 x 66 words of scratch */,
                               unsigned* ticket, hipStream_t stream);
 void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                hipStream_t stream);

@@ -29,7 +29,8 @@ struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
 enum { DISCO_MAX_CLS = 64, DISCO_MAX_GRP = 4, DISCO_TBT_MAX_PASS = 6,
        DISCO_TL_HIST_WORDS = 16384,   // LDS bins of a timeline workgroup (64 KB: two workgroups per CU)
        DISCO_GHIST_WORDS = 262144,    // device-wide bins (1 MB)
-       DISCO_PP_NMAX = 4096 };        // pure-pacing timelines up to this length are histogrammed analytically
+       DISCO_PP_NMAX = 4096,          // pure-pacing timelines up to this length are histogrammed analytically
+       DISCO_DELAY_BINS = 8192 };     // counts of delayed tokens per migrated request, per column (last bin: that or more)
 struct TlSel {
     u64 cls_mask[DISCO_MAX_CLS];   // column set of each class, 0 = free
     u64 walk_mask;                 // classes with a timeline whose tokens have to be walked

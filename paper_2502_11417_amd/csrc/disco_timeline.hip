@@ -168,6 +168,11 @@ __global__ __launch_bounds__(TL_BLOCK) void k_timeline(TraceView tr, i64 n_tok, 
                                    lane, deliv, sink);
             }
             if (variant == 2) { res_lag = res; lag_done = true; }
+            if (hist_pass && a.pass == 0 && variant >= 3 && res.m >= 0 && ((mask >> lane) & 1ull)) {
+                // lane = column: migrated requests by number of delayed tokens
+                const int bin = res.delay < DISCO_DELAY_BINS - 1 ? res.delay : DISCO_DELAY_BINS - 1;
+                atomicAdd(&a.dhist[(size_t)lane * DISCO_DELAY_BINS + bin], 1u);
+            }
             if (!hist_pass && ((mask >> lane) & 1ull)) {
                 const bool mig = res.m >= 0;
                 const int nsrc = mig ? (variant >= 3 ? res.m + 1 : res.m) : n;      // tokens produced by the source

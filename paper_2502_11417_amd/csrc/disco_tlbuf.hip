@@ -107,6 +107,7 @@ struct BufHistArgs {
     HistArgs h;
     BufCostArgs bc;
     const unsigned* buffer_flag;
+    unsigned* dhist;               // first pass: migrated requests by number of delayed tokens, per column
 };
 
 __global__ __launch_bounds__(TBH_BLOCK) void k_tl_hist_buf(TraceView tr, i64 n_tok, int align, const disco_policy* __restrict__ pol,
@@ -166,8 +167,13 @@ __global__ __launch_bounds__(TBH_BLOCK) void k_tl_hist_buf(TraceView tr, i64 n_t
                                             ok[3] ? key[3] : KEY_SKIP};
                     hist_keys(h, kk, row_base, lane);
                 };
-                run_timeline(TL_SRV_BUF + kind, n, tr.arr, off, n_tok, align, gap, gd, l, k, tr.c, s_ttft, ba.bc, a.tau, a.kt, lane,
-                             nullptr, sink);
+                const TimelineResult res = run_timeline(TL_SRV_BUF + kind, n, tr.arr, off, n_tok, align, gap, gd, l, k, tr.c,
+                                                        s_ttft, ba.bc, a.tau, a.kt, lane, nullptr, sink);
+                if (a.pass == 0 && res.m >= 0) {           // lane = column: one count per migrated pair
+                    const u64 mask = bcast_u64(kind ? b.m[TL_DEV_BUF] : b.m[TL_SRV_BUF], rq);
+                    const int bin = res.delay < DISCO_DELAY_BINS - 1 ? res.delay : DISCO_DELAY_BINS - 1;
+                    if ((mask >> lane) & 1ull) atomicAdd(&ba.dhist[(size_t)lane * DISCO_DELAY_BINS + bin], 1u);
+                }
             }
         }
     }
@@ -213,6 +219,7 @@ void disco_launch_tl_hist_buf(const TraceView& v, i64 n_tok, const disco_policy*
     h.h.S = a.S; h.h.ghist = a.ghist; h.h.ppcnt = a.ppcnt;
     h.bc = a.bc;
     h.buffer_flag = a.buffer_flag;
+    h.dhist = a.dhist;
     const i64 per_block = (i64)(TBH_BLOCK / 64) * TF_RB;
     i64 b = (v.n_req + per_block - 1) / per_block;
     if (b < 1) b = 1;

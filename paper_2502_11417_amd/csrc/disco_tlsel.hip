@@ -103,8 +103,8 @@ __device__ __forceinline__ void insert_sets(u64 m, bool walked, u64* loc, u64* l
 // device-wide bins.
 //   parts: gridDim.x x (DISCO_MAX_CLS + 2) words of scratch
 __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
-                                                     float tau, SelState* S, unsigned* ppcnt, unsigned* ghist, u64* parts,
-                                                     unsigned* ticket)
+                                                     float tau, SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist,
+                                                     u64* parts, unsigned* ticket)
 {
     __shared__ disco_policy sp[DISCO_MAX_COLS];
     __shared__ u64 loc[DISCO_MAX_CLS];
@@ -116,6 +116,7 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
     for (i64 w = (i64)blockIdx.x * CL_BLOCK + threadIdx.x; w < (i64)DISCO_MAX_CLS * (DISCO_PP_NMAX + 1); w += (i64)gridDim.x * CL_BLOCK)
         ppcnt[w] = 0u;
     for (i64 w = (i64)blockIdx.x * CL_BLOCK + threadIdx.x; w < (i64)DISCO_GHIST_WORDS; w += (i64)gridDim.x * CL_BLOCK) ghist[w] = 0u;
+    for (i64 w = (i64)blockIdx.x * CL_BLOCK + threadIdx.x; w < (i64)P * DISCO_DELAY_BINS; w += (i64)gridDim.x * CL_BLOCK) dhist[w] = 0u;
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     WaveTable wt{0ull, 0, 0ull};
@@ -388,13 +389,14 @@ __global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, in
 }  // namespace
 
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
-                              unsigned* ppcnt, unsigned* ghist, u64* parts, unsigned* ticket, hipStream_t stream)
+                              unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts, unsigned* ticket,
+                              hipStream_t stream)
 {
     i64 b = (v.n_req + CL_BLOCK - 1) / CL_BLOCK;
     if (b < 1) b = 1;
     if (b > 256) b = 256;
-    hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau, S, ppcnt, ghist, parts,
-                       ticket);
+    hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau, S, ppcnt, ghist, dhist,
+                       parts, ticket);
 }
 
 void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,

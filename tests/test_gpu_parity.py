@@ -234,6 +234,11 @@ def check_stats(B, O, tr, specs, cost, tau=None, kappa=3.0, quantiles=((50, 100)
                 assert close(float(g["mean_delay_num"]), w["delay_sum"] / w["n_migrated"], 1e-15), j
             else:
                 assert math.isnan(g["mean_delay_num"]), j
+            for qi in range(len(quantiles)):
+                if w["n_migrated"]:
+                    assert float(g["delay_q"][qi]) == float(w["delay_q"][qi]), (j, qi, g["delay_q"][qi], w["delay_q"][qi])
+                else:
+                    assert math.isnan(g["delay_q"][qi]), (j, qi)
     return got, want
 
 
