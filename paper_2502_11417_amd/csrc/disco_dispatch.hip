@@ -102,66 +102,74 @@ __device__ void search_advance(int col, const DispFin& fin, const disco_accum& t
     }
 }
 
-__device__ __forceinline__ void add_partial(DispPartial& a, const DispPartial& o)
+// Device-wide totals of the dispatch passes: 8 words per column (the fields
+// of DispPartial), kept word-major in DISCO_NCOPY copies: word f of column c
+// in copy k sits at tot[(f * DISCO_NCOPY + k) * 64 + c], so the 64 columns of
+// one word are contiguous and a wave reads or updates them with one coalesced
+// instruction.  Word 7 holds the smallest TTFT bit pattern in its low half and
+// the largest in its high half.
+__device__ __forceinline__ u64 fold_word(int f, u64 a, u64 b)
 {
-    a.s_pre += o.s_pre; a.d_pre += o.d_pre; a.d_dec += o.d_dec; a.n_tot += o.n_tot;
-    a.started += o.started; a.won += o.won; a.ttft_sum += o.ttft_sum;
-    a.minb = min(a.minb, o.minb); a.maxb = max(a.maxb, o.maxb);
+    if (f < 6) return a + b;
+    if (f == 6) return (u64)__double_as_longlong(__longlong_as_double((long long)a) + __longlong_as_double((long long)b));
+    const unsigned lo = min((unsigned)a, (unsigned)b), hi = max((unsigned)(a >> 32), (unsigned)(b >> 32));
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ bool word_needed(int f, int need) { return f < 2 || (need >= 1 && f < 6) || need >= 2; }
+
+// Workgroup totals -> device-wide totals.  The per-wave partials are in LDS
+// (word f of partial r at sh[f * DP_BLOCK + r], rows = waves x G columns);
+// wave f folds word f over the waves and adds it into one of the copies with
+// one atomic instruction (exact integer atomics; the fp64 TTFT sum is
+// order-dependent in its last bits).
+template <int G>
+__device__ __forceinline__ void add_to_totals(const u64* sh, u64* tot, int P, int need)
+{
+    const int f = threadIdx.x >> 6, c = threadIdx.x & 63;
+    if (f >= 8 || c >= G || !word_needed(f, need)) return;
+    u64 x = sh[f * DP_BLOCK + c];
+#pragma unroll
+    for (int w = 1; w < DP_WAVES; ++w) x = fold_word(f, x, sh[f * DP_BLOCK + w * G + c]);
+    if (c >= P) return;
+    u64* dst = &tot[(f * DISCO_NCOPY + (int)(blockIdx.x % DISCO_NCOPY)) * 64 + c];
+    if (f < 6) atomicAdd((unsigned long long*)dst, (unsigned long long)x);
+    else if (f == 6) unsafeAtomicAdd(reinterpret_cast<double*>(dst), __longlong_as_double((long long)x));   // hardware fp64 add (the workspace is ordinary device memory)
+    else {
+        atomicMin(reinterpret_cast<unsigned*>(dst), (unsigned)x);
+        atomicMax(reinterpret_cast<unsigned*>(dst) + 1, (unsigned)(x >> 32));
+    }
 }
 
-// A workgroup adds its column totals into the device-wide totals (exact
-// integer atomics; the fp64 TTFT sum is order-dependent in its last bits).
-__device__ __forceinline__ void add_to_totals(DispPartial* tot, const DispPartial& a, int need)
+// Last workgroup: wave f reads the copies of word f, puts them back to their
+// identity for the next pass and folds them in order; then thread = column
+// hands the sums to the accumulator or to the search.
+__device__ __forceinline__ void finish_columns(u64* tot, int P, const DispFin& fin, u64* sh /* LDS */)
 {
-    atomicAdd((unsigned long long*)&tot->s_pre, (unsigned long long)a.s_pre);
-    atomicAdd((unsigned long long*)&tot->d_pre, (unsigned long long)a.d_pre);
-    if (need >= 1) {
-        atomicAdd((unsigned long long*)&tot->d_dec, (unsigned long long)a.d_dec);
-        atomicAdd((unsigned long long*)&tot->n_tot, (unsigned long long)a.n_tot);
-        atomicAdd((unsigned long long*)&tot->started, (unsigned long long)a.started);
-        atomicAdd((unsigned long long*)&tot->won, (unsigned long long)a.won);
-    }
-    if (need >= 2) {
-        unsafeAtomicAdd(&tot->ttft_sum, a.ttft_sum);      // hardware fp64 add (the workspace is ordinary device memory)
-        atomicMin(&tot->minb, a.minb);
-        atomicMax(&tot->maxb, a.maxb);
-    }
-}
-
-// Last workgroup: read the copies of the device-wide totals, put them back to
-// their identity for the next pass, add the copies of a column in order and
-// hand the sums to the accumulator or to the search.
-__device__ __forceinline__ void finish_columns(DispPartial* totals, int P, const DispFin& fin, u64* sh /* LDS */)
-{
-    for (int idx = threadIdx.x; idx < DISCO_NCOPY * 64; idx += DP_BLOCK) {
-        const int c = idx & 63;
-        if (c < P) {
-            DispPartial* src = &totals[idx];
-            DispPartial t;
-            t.s_pre = __hip_atomic_load(&src->s_pre, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            t.d_pre = __hip_atomic_load(&src->d_pre, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            t.d_dec = __hip_atomic_load(&src->d_dec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            t.n_tot = __hip_atomic_load(&src->n_tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            t.started = __hip_atomic_load(&src->started, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            t.won = __hip_atomic_load(&src->won, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            t.ttft_sum = __hip_atomic_load(&src->ttft_sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            t.minb = __hip_atomic_load(&src->minb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            t.maxb = __hip_atomic_load(&src->maxb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            *src = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
-            lds_put(sh, DP_BLOCK, idx, t);
-        }
+    const int f = threadIdx.x >> 6, c = threadIdx.x & 63;
+    if (f < 8 && c < P) {                              // (the ticket's barrier has separated this from the folds' LDS reads)
+        u64 v[DISCO_NCOPY];
+#pragma unroll
+        for (int k = 0; k < DISCO_NCOPY; ++k)
+            v[k] = __hip_atomic_load(&tot[(f * DISCO_NCOPY + k) * 64 + c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const u64 identity = f == 7 ? 0x00000000FFFFFFFFull : 0ull;
+#pragma unroll
+        for (int k = 0; k < DISCO_NCOPY; ++k) tot[(f * DISCO_NCOPY + k) * 64 + c] = identity;
+        u64 x = v[0];
+#pragma unroll
+        for (int k = 1; k < DISCO_NCOPY; ++k) x = fold_word(f, x, v[k]);
+        sh[f * 64 + c] = x;
     }
     __syncthreads();
     if ((int)threadIdx.x < P) {
         const int c = threadIdx.x;
-        DispPartial t = lds_get<DispPartial>(sh, DP_BLOCK, c);
-        for (int k = 1; k < DISCO_NCOPY; ++k) add_partial(t, lds_get<DispPartial>(sh, DP_BLOCK, k * 64 + c));
+        const u64 n_tot = sh[3 * 64 + c], d_dec = sh[2 * 64 + c];
         disco_accum acc;
         memset(&acc, 0, sizeof(acc));
-        acc.s_pre = (i64)t.s_pre; acc.d_pre = (i64)t.d_pre; acc.d_dec = (i64)t.d_dec;
-        acc.s_dec = (i64)(t.n_tot - t.d_dec);
-        acc.n_dev_started = (i64)t.started; acc.n_dev_win = (i64)t.won; acc.ttft_sum = t.ttft_sum;
-        acc.ttft_min_bits = t.minb; acc.ttft_max_bits = t.maxb;
+        acc.s_pre = (i64)sh[0 * 64 + c]; acc.d_pre = (i64)sh[1 * 64 + c]; acc.d_dec = (i64)d_dec;
+        acc.s_dec = (i64)(n_tot - d_dec);
+        acc.n_dev_started = (i64)sh[4 * 64 + c]; acc.n_dev_win = (i64)sh[5 * 64 + c];
+        acc.ttft_sum = __longlong_as_double((long long)sh[6 * 64 + c]);
+        acc.ttft_min_bits = (unsigned)sh[7 * 64 + c]; acc.ttft_max_bits = (unsigned)(sh[7 * 64 + c] >> 32);
         if (fin.kind == 0) {
             disco_accum* o = &fin.acc[c];
             o->s_pre = acc.s_pre; o->s_dec = acc.s_dec; o->d_pre = acc.d_pre; o->d_dec = acc.d_dec;
@@ -252,7 +260,7 @@ __device__ __forceinline__ void batch_pairs_need(const Staged* __restrict__ st, 
 
 template <int G>
 __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const disco_policy* __restrict__ pol, int P,
-                                                           DispPartial* __restrict__ part, unsigned* ticket, DispFin fin)
+                                                           u64* __restrict__ part, unsigned* ticket, DispFin fin)
 {
     __shared__ __align__(16) unsigned char smem[DP_BLOCK * sizeof(DispPartial)];    // 64 KB: staging, then folds
     Staged* stage = reinterpret_cast<Staged*>(smem);
@@ -308,11 +316,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
         lds_put(sh, DP_BLOCK, wave * G + col,
                 DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb});
     __syncthreads();
-    if (threadIdx.x < G) {
-        DispPartial a = lds_get<DispPartial>(sh, DP_BLOCK, threadIdx.x);
-        for (int w = 1; w < DP_WAVES; ++w) add_partial(a, lds_get<DispPartial>(sh, DP_BLOCK, w * G + threadIdx.x));
-        if ((int)threadIdx.x < P) add_to_totals(&part[(blockIdx.x % DISCO_NCOPY) * 64 + threadIdx.x], a, fin.need);
-    }
+    add_to_totals<G>(sh, part, P, fin.need);
     if (!take_last_ticket(ticket)) return;
     finish_columns(part, P, fin, sh);
     if (threadIdx.x == 0) *ticket = 0u;
@@ -322,7 +326,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
 // iteration (16-byte loads when VEC, i.e. all arrays 16-byte aligned).
 template <bool VEC>
 __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc1(TraceView tr, const disco_policy* __restrict__ pol,
-                                                            DispPartial* __restrict__ part, unsigned* ticket, DispFin fin)
+                                                            u64* __restrict__ part, unsigned* ticket, DispFin fin)
 {
     __shared__ __align__(16) unsigned char smem[DP_BLOCK * sizeof(DispPartial)];
     u64* sh = reinterpret_cast<u64*>(smem);
@@ -390,11 +394,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc1(TraceView tr, const 
     if (lane == 0)
         lds_put(sh, DP_BLOCK, wave, DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb});
     __syncthreads();
-    if (threadIdx.x == 0) {
-        DispPartial a = lds_get<DispPartial>(sh, DP_BLOCK, 0);
-        for (int w = 1; w < DP_WAVES; ++w) add_partial(a, lds_get<DispPartial>(sh, DP_BLOCK, w));
-        add_to_totals(&part[(blockIdx.x % DISCO_NCOPY) * 64], a, fin.need);
-    }
+    add_to_totals<1>(sh, part, 1, fin.need);
     if (!take_last_ticket(ticket)) return;
     finish_columns(part, 1, fin, sh);
     if (threadIdx.x == 0) *ticket = 0u;
@@ -557,7 +557,7 @@ unsigned dispatch_blocks(i64 units, i64 per_block)
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 template <int G>
-void launch_acc(const TraceView& v, const disco_policy* pol, int P, DispPartial* part, unsigned* ticket, const DispFin& fin,
+void launch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, unsigned* ticket, const DispFin& fin,
                 hipStream_t stream)
 {
     const unsigned blocks = dispatch_blocks((v.n_req + 63) / 64, DP_WAVES);
@@ -573,7 +573,7 @@ int pow2_cols(int P)
 
 }  // namespace
 
-void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, DispPartial* part, unsigned* ticket,
+void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, unsigned* ticket,
                                const DispFin& fin, hipStream_t stream)
 {
     switch (pow2_cols(P)) {

@@ -19,38 +19,40 @@
 namespace {
 
 // The timeline totals follow the dispatch totals in the same workspace region.
-__host__ __device__ inline MigPartial* tl_totals(DispPartial* totals)
+__host__ __device__ inline MigPartial* tl_totals(u64* totals)
 {
-    return reinterpret_cast<MigPartial*>(totals + DISCO_NCOPY * 64);
+    return reinterpret_cast<MigPartial*>(totals + DISCO_NCOPY * 64 * 8);
+}
+
+// Identity of the dispatch totals (8 words per column and copy, word-major; word 7 = {min bits, max bits}).
+__device__ inline void reset_dispatch_totals(u64* totals, int i /* 0..63 */)
+{
+    for (int w = 0; w < 8 * DISCO_NCOPY; ++w) totals[w * 64 + i] = w >= 7 * DISCO_NCOPY ? 0x00000000FFFFFFFFull : 0ull;
 }
 
 // Staging of the policy table; also puts the tickets and the per-column
 // totals that the workgroups of a pass add into at their identity.
-__global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets, DispPartial* totals)
+__global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets, u64* totals)
 {
     int i = threadIdx.x;
     if (i < P) dst[i] = t.p[i];
     const bool any_buffer = __ballot(i < P && t.p[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
     if (i < 64) {
         tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
-        for (int k = 0; k < DISCO_NCOPY; ++k) {
-            totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
-            tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
-        }
+        reset_dispatch_totals(totals, i);
+        for (int k = 0; k < DISCO_NCOPY; ++k) tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
     }
 }
 
-__global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* dst, unsigned* tickets, DispPartial* totals)
+__global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* dst, unsigned* tickets, u64* totals)
 {
     int i = threadIdx.x;
     if (i < P) dst[i] = src[i];
     const bool any_buffer = __ballot(i < P && src[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
     if (i < 64) {
         tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
-        for (int k = 0; k < DISCO_NCOPY; ++k) {
-            totals[k * 64 + i] = DispPartial{0, 0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
-            tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
-        }
+        reset_dispatch_totals(totals, i);
+        for (int k = 0; k < DISCO_NCOPY; ++k) tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
     }
 }
 
@@ -355,7 +357,7 @@ int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, 
     if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
     if (is_device_pointer(pol)) {
         hipLaunchKernelGGL(k_copy_policies, dim3(1), dim3(64), 0, stream, pol, P, (disco_policy*)(ws + L.pol),
-                           (unsigned*)(ws + L.ticket), (DispPartial*)(ws + L.part));
+                           (unsigned*)(ws + L.ticket), (u64*)(ws + L.part));
         return DISCO_OK;
     }
     int rc = check_policies(pol, P);
@@ -364,7 +366,7 @@ int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, 
     memset(&t, 0, sizeof(t));
     memcpy(t.p, pol, sizeof(disco_policy) * (size_t)P);
     hipLaunchKernelGGL(k_store_policies, dim3(1), dim3(64), 0, stream, t, P, (disco_policy*)(ws + L.pol),
-                       (unsigned*)(ws + L.ticket), (DispPartial*)(ws + L.part));
+                       (unsigned*)(ws + L.ticket), (u64*)(ws + L.part));
     return DISCO_OK;
 }
 
@@ -440,7 +442,7 @@ extern "C" int32_t disco_eval_dispatch(const disco_trace* trace, const disco_pol
     fin.kind = 0;
     fin.need = 2;
     fin.acc = acc;
-    disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), P, (DispPartial*)(ws + L.part),
+    disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), P, (u64*)(ws + L.part),
                               (unsigned*)(ws + L.ticket), fin, stream);
     if (out && (out->decision || out->ttft) && v.n_req > 0)
         disco_launch_dispatch_mat(v, (const disco_policy*)(ws + L.pol), P, out->decision, out->ttft, stream);
@@ -492,7 +494,7 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
         disco_launch_timeline_general(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
     else
         disco_launch_tl_stats_fast(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a,
-                                   tl_totals((DispPartial*)(ws + L.part)), stream);
+                                   tl_totals((u64*)(ws + L.part)), stream);
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }
@@ -707,7 +709,7 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
         if (spec[j].which_acc != DISCO_ACC_SERVER_PREFILL_TOK && spec[j].which_acc != DISCO_ACC_DEVICE_PREFILL_TOK) need = 1;
     for (int step = first_step; step <= n_steps; ++step) {
         fin.need = step < n_steps ? need : 2;
-        disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search, (DispPartial*)(ws + L.part),
+        disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search, (u64*)(ws + L.part),
                                   (unsigned*)(ws + L.ticket), fin, stream);
     }
     DISCO_HIP(hipGetLastError());
