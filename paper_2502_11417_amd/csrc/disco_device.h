@@ -127,6 +127,13 @@ __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m)
     hi = (unsigned)__shfl_xor((int)hi, m, 64);
     return ((u64)hi << 32) | lo;
 }
+__device__ __forceinline__ u64 shfl_down_u64(u64 v, int d)
+{
+    unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+    lo = (unsigned)__shfl_down((int)lo, d, 64);
+    hi = (unsigned)__shfl_down((int)hi, d, 64);
+    return ((u64)hi << 32) | lo;
+}
 __device__ __forceinline__ double shfl_xor_f64(double v, int m)
 {
     return __longlong_as_double((long long)shfl_xor_u64((u64)__double_as_longlong(v), m));

@@ -392,7 +392,7 @@ WsLayout disco_ws_layout(int32_t P)
     o += up((size_t)DISCO_MAX_BLOCKS * 64 * 64);     // workgroups x columns x 64-byte partial
     L.ppcnt = o; o += up(sizeof(unsigned) * DISCO_MAX_CLS * (DISCO_PP_NMAX + 1));
     L.dhist = o; o += up(sizeof(unsigned) * DISCO_MAX_COLS * DISCO_DELAY_BINS);
-    L.slices = o; o += up((size_t)256 * DISCO_MAX_SLOTS * 256 * sizeof(unsigned));
+    L.slices = o; o += up((size_t)256 * (2 * DISCO_MAX_COLS + 2) * 256 * sizeof(unsigned));   // 256 workgroups x rows x bins
     L.total = o;
     return L;
 }

@@ -46,7 +46,7 @@ constexpr int TH_ROWS = 2 * DISCO_MAX_COLS + 2;         // class pass 0: (device
 constexpr int TH_PAD = 1;                               // skew: equal digits of different rows hit different banks
 constexpr int TH_STRIDE = 256 + TH_PAD;
 constexpr int TH_WORDS = TH_ROWS * TH_STRIDE;           // 131 KB of LDS bins
-constexpr int TC_MAX_BLOCKS = 240;                      // class kernel: slices of all workgroups must fit the 32 MB slice region
+constexpr int TC_MAX_BLOCKS = 256;                      // class kernel: one workgroup per CU (its slices: TH_ROWS x 256 bins each)
 
 struct PassDigit { int width, shift, up; unsigned dmask; };
 
@@ -237,18 +237,19 @@ __device__ __forceinline__ int prefix_lookup(const ClsTables& T, unsigned prefix
     }
 }
 
-// ub = #{p : t_p <= l}: cached per request by the first pass when the caller's workspace has room for it,
-// otherwise a binary search over the 64 padded thresholds.
-__device__ __forceinline__ int request_ub(const ClsTables& T, int P, int l, const unsigned char* __restrict__ ubytes, i64 i,
-                                          bool cached)
+// ub = #{p : t_p <= l}: binary search over the 64 padded thresholds (the first pass leaves it in the request's
+// workspace byte for the later ones when the caller's workspace has room).
+__device__ __forceinline__ int request_ub(const ClsTables& T, int P, int l)
 {
-    if (cached) return (int)ubytes[i];
     int ub = 0;
 #pragma unroll
     for (int step = 64; step >= 1; step >>= 1)
         if (ub + step <= DISCO_MAX_COLS && T.sorted[ub + step - 1] <= l) ub += step;
     return ub < P ? ub : P;
 }
+
+// Requests of a workgroup are taken four strides at a time: the loads of all four are issued before the first is used.
+constexpr int TC_UNROLL = 4;
 
 __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int pass, SelState* S,
                                          unsigned* __restrict__ slices, unsigned* hist, ClsTables& T, int bid, int nblk,
@@ -262,121 +263,159 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
     const int nslot = P * nq;
     const int rows = (pass == 0) ? 2 * (P + 1) : nslot;
     const int t = threadIdx.x;
+    // the slot records travel from device memory while the bins are cleared
+    SelSlot sl;
+    const bool in = pass > 0 && t < nslot;
+    if (in) sl = S->slot[0][t];
     if (!gather)
         for (int i = t; i < rows * TH_STRIDE; i += DP_BLOCK) hist[i] = 0u;
     if (t < DISCO_MAX_COLS) { T.sorted[t] = t < P ? S->tc.sorted_lth[t] : 0x7FFFFFFF; T.col_of_pos[t] = S->tc.col_of_pos[t]; }
     if (pass > 0) {
-        // tables of this pass, built by the whole workgroup
+        // tables of this pass, built without atomics
         if (t < DISCO_MAX_SLOTS) {
-            const bool in = t < nslot;
-            SelSlot sl;
-            if (in) sl = S->slot[0][t];
-            T.sprefix[t] = in ? sl.prefix : 0u;
             T.slive[t] = in && !sl.done;
-            T.first_of[t] = t;
-            T.dmask[t][0] = 0ull; T.dmask[t][1] = 0ull;
+            T.sprefix[t] = (in && !sl.done) ? sl.prefix : 0xFFFFFFFFu;     // keys have 31 bits: never a prefix
         }
         if (t < 2 * DISCO_MAX_SLOTS) T.htab[t] = 0ull;
-        if (t <= DISCO_MAX_COLS) { T.dslots[t][0] = 0ull; T.dslots[t][1] = 0ull; }
         __syncthreads();
-        for (int pr = t; pr < DISCO_MAX_SLOTS * DISCO_MAX_SLOTS; pr += DP_BLOCK) {     // earliest slot with the same prefix
-            const int a = pr >> 7, z = pr & (DISCO_MAX_SLOTS - 1);
-            if (z < a && T.slive[z] && T.slive[a] && T.sprefix[z] == T.sprefix[a]) atomicMin(&T.first_of[a], z);
-        }
-        // slots of the sorted columns p >= ub
-        for (int pr = t; pr < (P + 1) * P; pr += DP_BLOCK) {
-            const int ub = pr / P, p = pr - ub * P;
-            if (p >= ub) {
-                const int c = T.col_of_pos[p];
-                for (int qi = 0; qi < nq; ++qi) {
-                    const int sidx = c * nq + qi;
-                    atomicOr((unsigned long long*)&T.dslots[ub][sidx >> 6], 1ull << (sidx & 63));
-                }
+        if (t < DISCO_MAX_SLOTS) {
+            // live slots with the same prefix: every thread walks the 128 prefixes (broadcast reads)
+            const unsigned mine = T.sprefix[t];
+            const bool live = mine != 0xFFFFFFFFu;
+            u64 m0 = 0ull, m1 = 0ull;
+#pragma unroll 8
+            for (int z = 0; z < 64; ++z) {
+                m0 |= (T.sprefix[z] == mine) ? (1ull << z) : 0ull;
+                m1 |= (T.sprefix[64 + z] == mine) ? (1ull << z) : 0ull;
             }
-        }
-        __syncthreads();
-        if (t < DISCO_MAX_SLOTS && T.slive[t]) {
-            const int f = T.first_of[t];
-            atomicOr((unsigned long long*)&T.dmask[f][t >> 6], 1ull << (t & 63));
-            if (f == t) {                               // one entry per distinct prefix
-                const unsigned pf = T.sprefix[t];
-                const u64 entry = ((u64)pf << 8) | (u64)t | (1ull << 63);
-                unsigned h = prefix_hash(pf);
+            if (!live) { m0 = 0ull; m1 = 0ull; }
+            T.dmask[t][0] = m0; T.dmask[t][1] = m1;
+            const int f = m0 ? __ffsll((long long)m0) - 1 : (m1 ? 64 + __ffsll((long long)m1) - 1 : t);
+            T.first_of[t] = f;
+            if (live && f == t) {                       // one hash entry per distinct prefix
+                const u64 entry = ((u64)mine << 8) | (u64)t | (1ull << 63);
+                unsigned h = prefix_hash(mine);
                 while (atomicCAS((unsigned long long*)&T.htab[h], 0ull, (unsigned long long)entry) != 0ull)
                     h = (h + 1u) & (2 * DISCO_MAX_SLOTS - 1);
             }
+        } else if (t < DISCO_MAX_SLOTS + 64) {
+            // slots of the sorted columns p >= ub: suffix OR over the wave (lane = sorted position)
+            const int p = t - DISCO_MAX_SLOTS;
+            u64 b0 = 0ull, b1 = 0ull;
+            if (p < P) {
+                const int c = T.col_of_pos[p];
+                for (int qi = 0; qi < nq; ++qi) {
+                    const int sidx = c * nq + qi;
+                    if (sidx < 64) b0 |= 1ull << sidx; else b1 |= 1ull << (sidx - 64);
+                }
+            }
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const u64 o0 = shfl_down_u64(b0, d), o1 = shfl_down_u64(b1, d);
+                if (p + d < 64) { b0 |= o0; b1 |= o1; }
+            }
+            T.dslots[p][0] = b0; T.dslots[p][1] = b1;
+            if (p == 0) { T.dslots[DISCO_MAX_COLS][0] = 0ull; T.dslots[DISCO_MAX_COLS][1] = 0ull; }
         }
     }
     __syncthreads();
     const bool cached = ubytes != nullptr && pass > 0;
+    const i64 stride = (i64)nblk * DP_BLOCK;
     if (gather) {
         // same matching as a histogram pass, but the value is appended to the candidate list (all lanes of a
         // wave stay together: the append is a wave operation)
         GEntry* list = reinterpret_cast<GEntry*>(slices);
         WaveList wl{reinterpret_cast<GEntry*>(hist) + (threadIdx.x >> 6) * TG_SEG, 0u};
-        for (i64 base = (i64)bid * DP_BLOCK; base < tr.n_req; base += (i64)nblk * DP_BLOCK) {
-            const i64 i = base + t;
-            const bool v = i < tr.n_req;
-            const int l = v ? tr.l[i] : 0;
-            const float s = v ? tr.s[i] : 0.0f;
-            const float k = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
-            const float d = __fmaf_rn((float)l, k, tr.c);
-            const int ub = v ? request_ub(T, P, l, ubytes, i, cached) : 0;
-            const bool dev_wins = d < s;
-            const int ub0 = dev_wins ? 0 : ub;
-            const bool two = !dev_wins && ub > 0;
+        for (i64 base = (i64)bid * DP_BLOCK; base < tr.n_req; base += TC_UNROLL * stride) {
+            bool v[TC_UNROLL];
+            int l[TC_UNROLL], ubc[TC_UNROLL];
+            float sv[TC_UNROLL], kv[TC_UNROLL];
 #pragma unroll
-            for (int which = 0; which < 2; ++which) {
-                const unsigned key = (which ? f2u(s) : f2u(d)) - g.minb;
-                const int u = which ? ub : ub0;
-                bool match = v && (which ? two : ub0 < P);
-                if (match) {
-                    const int f = prefix_lookup(T, key >> up);
-                    match = f >= 0;
+            for (int q = 0; q < TC_UNROLL; ++q) {
+                const i64 i = base + q * stride + t;
+                v[q] = i < tr.n_req;
+                l[q] = v[q] ? tr.l[i] : 0;
+                sv[q] = v[q] ? tr.s[i] : 0.0f;
+                kv[q] = tr.k ? (v[q] ? tr.k[i] : 0.0f) : tr.k_s;
+                ubc[q] = (cached && v[q]) ? (int)ubytes[i] : 0;
+            }
+#pragma unroll
+            for (int q = 0; q < TC_UNROLL; ++q) {
+                if (base + q * stride >= tr.n_req) break;           // the same for the whole workgroup
+                const float s = sv[q];
+                const float d = __fmaf_rn((float)l[q], kv[q], tr.c);
+                const int ub = v[q] ? (cached ? ubc[q] : request_ub(T, P, l[q])) : 0;
+                const bool dev_wins = d < s;
+                const int ub0 = dev_wins ? 0 : ub;
+                const bool two = !dev_wins && ub > 0;
+#pragma unroll
+                for (int which = 0; which < 2; ++which) {
+                    const unsigned key = (which ? f2u(s) : f2u(d)) - g.minb;
+                    const int u = which ? ub : ub0;
+                    bool match = v[q] && (which ? two : ub0 < P);
                     if (match) {
-                        u64 m0 = T.dmask[f][0], m1 = T.dmask[f][1];
-                        if (which) { m0 &= ~T.dslots[u][0]; m1 &= ~T.dslots[u][1]; }
-                        else { m0 &= T.dslots[u][0]; m1 &= T.dslots[u][1]; }
-                        match = (m0 | m1) != 0ull;
+                        const int f = prefix_lookup(T, key >> up);
+                        match = f >= 0;
+                        if (match) {
+                            u64 m0 = T.dmask[f][0], m1 = T.dmask[f][1];
+                            if (which) { m0 &= ~T.dslots[u][0]; m1 &= ~T.dslots[u][1]; }
+                            else { m0 &= T.dslots[u][0]; m1 &= T.dslots[u][1]; }
+                            match = (m0 | m1) != 0ull;
+                        }
                     }
+                    wl_append(wl, match, key, ((unsigned)which << 16) | (unsigned)u, list, &S->g[0]);
                 }
-                wl_append(wl, match, key, ((unsigned)which << 16) | (unsigned)u, list, &S->g[0]);
             }
         }
         wl_finish(wl, list, &S->g[0]);
         return;
     }
-    for (i64 i = (i64)bid * DP_BLOCK + t; i < tr.n_req; i += (i64)nblk * DP_BLOCK) {
-        const int l = tr.l[i];
-        const float s = tr.s[i];
-        const float k = tr.k ? tr.k[i] : tr.k_s;
-        const float d = __fmaf_rn((float)l, k, tr.c);
-        const int ub = request_ub(T, P, l, ubytes, i, cached);
-        if (pass == 0 && ubytes) ubytes[i] = (unsigned char)ub;
-        const bool dev_wins = d < s;                    // ties go to the server
-        // value 0: d for the columns p >= ub (for every column if the device also wins the races);
-        // value 1: s for the columns p < ub
-        const int ub0 = dev_wins ? 0 : ub;
-        const bool two = !dev_wins && ub > 0;
-        const unsigned key0 = f2u(d) - g.minb, key1 = f2u(s) - g.minb;
-        if (pass == 0) {
-            if (ub0 < P) atomicAdd(&hist[ub0 * TH_STRIDE + ((key0 >> shift) & dmask)], 1u);
-            if (two) atomicAdd(&hist[(P + 1 + ub) * TH_STRIDE + ((key1 >> shift) & dmask)], 1u);
-        } else {
+    for (i64 i0 = (i64)bid * DP_BLOCK + t; i0 < tr.n_req; i0 += TC_UNROLL * stride) {
+        bool v[TC_UNROLL];
+        int l[TC_UNROLL], ubc[TC_UNROLL];
+        float sv[TC_UNROLL], kv[TC_UNROLL];
 #pragma unroll
-            for (int which = 0; which < 2; ++which) {
-                if (which == 1 && !two) continue;
-                if (which == 0 && ub0 >= P) continue;
-                const unsigned key = which ? key1 : key0;
-                const int f = prefix_lookup(T, key >> up);          // up < 32 after the first pass
-                if (f < 0) continue;
-                const int u = which ? ub : ub0;
-                u64 m0 = T.dmask[f][0], m1 = T.dmask[f][1];
-                if (which) { m0 &= ~T.dslots[u][0]; m1 &= ~T.dslots[u][1]; }
-                else { m0 &= T.dslots[u][0]; m1 &= T.dslots[u][1]; }
-                const unsigned dgt = (key >> shift) & dmask;
-                while (m0) { const int sidx = __ffsll((long long)m0) - 1; m0 &= m0 - 1; atomicAdd(&hist[sidx * TH_STRIDE + dgt], 1u); }
-                while (m1) { const int sidx = 64 + __ffsll((long long)m1) - 1; m1 &= m1 - 1; atomicAdd(&hist[sidx * TH_STRIDE + dgt], 1u); }
+        for (int q = 0; q < TC_UNROLL; ++q) {
+            const i64 i = i0 + q * stride;
+            v[q] = i < tr.n_req;
+            l[q] = v[q] ? tr.l[i] : 0;
+            sv[q] = v[q] ? tr.s[i] : 0.0f;
+            kv[q] = tr.k ? (v[q] ? tr.k[i] : 0.0f) : tr.k_s;
+            ubc[q] = (cached && v[q]) ? (int)ubytes[i] : 0;
+        }
+#pragma unroll
+        for (int q = 0; q < TC_UNROLL; ++q) {
+            if (!v[q]) continue;
+            const i64 i = i0 + q * stride;
+            const float s = sv[q];
+            const float d = __fmaf_rn((float)l[q], kv[q], tr.c);
+            const int ub = cached ? ubc[q] : request_ub(T, P, l[q]);
+            if (pass == 0 && ubytes) ubytes[i] = (unsigned char)ub;
+            const bool dev_wins = d < s;                    // ties go to the server
+            // value 0: d for the columns p >= ub (for every column if the device also wins the races);
+            // value 1: s for the columns p < ub
+            const int ub0 = dev_wins ? 0 : ub;
+            const bool two = !dev_wins && ub > 0;
+            const unsigned key0 = f2u(d) - g.minb, key1 = f2u(s) - g.minb;
+            if (pass == 0) {
+                if (ub0 < P) atomicAdd(&hist[ub0 * TH_STRIDE + ((key0 >> shift) & dmask)], 1u);
+                if (two) atomicAdd(&hist[(P + 1 + ub) * TH_STRIDE + ((key1 >> shift) & dmask)], 1u);
+            } else {
+#pragma unroll
+                for (int which = 0; which < 2; ++which) {
+                    if (which == 1 && !two) continue;
+                    if (which == 0 && ub0 >= P) continue;
+                    const unsigned key = which ? key1 : key0;
+                    const int f = prefix_lookup(T, key >> up);          // up < 32 after the first pass
+                    if (f < 0) continue;
+                    const int u = which ? ub : ub0;
+                    u64 m0 = T.dmask[f][0], m1 = T.dmask[f][1];
+                    if (which) { m0 &= ~T.dslots[u][0]; m1 &= ~T.dslots[u][1]; }
+                    else { m0 &= T.dslots[u][0]; m1 &= T.dslots[u][1]; }
+                    const unsigned dgt = (key >> shift) & dmask;
+                    while (m0) { const int sidx = __ffsll((long long)m0) - 1; m0 &= m0 - 1; atomicAdd(&hist[sidx * TH_STRIDE + dgt], 1u); }
+                    while (m1) { const int sidx = 64 + __ffsll((long long)m1) - 1; m1 &= m1 - 1; atomicAdd(&hist[sidx * TH_STRIDE + dgt], 1u); }
+                }
             }
         }
     }
