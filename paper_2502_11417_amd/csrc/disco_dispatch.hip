@@ -224,6 +224,37 @@ __device__ __forceinline__ void batch_pairs_fast(const Staged* __restrict__ st, 
     t.minb = mn; t.maxb = mx;
 }
 
+// Threshold columns (Alg. 3) on a full batch with all l below 2^24 and all n below 2^16: per pair one
+// comparison l < l_th and selections between the request's device-only values and its race values, which the
+// loading lane has staged.  The selections are written with a bit mask (all ones iff l < l_th): written as
+// conditionals the compiler selects between the LDS addresses of the two candidates and loads afterwards, a
+// second, dependent trip to LDS per pair.
+template <int G, int NEED>
+__device__ __forceinline__ void batch_pairs_threshold(const StagedRace* __restrict__ sr, const unsigned* __restrict__ pnr, int sub,
+                                                      const disco_policy& p, ColTotals& t)
+{
+    const unsigned th = (unsigned)(p.l_th < 0 ? 0 : (p.l_th > (1 << 24) ? (1 << 24) : p.l_th));   // same outcome for l < 2^24
+    unsigned sp = 0, pk = 0;
+    double ts = 0.0;
+    unsigned mn = t.minb, mx = t.maxb;
+#pragma unroll 8
+    for (int it = 0; it < G; ++it) {
+        const StagedRace x = sr[sub * G + it];
+        const unsigned dev_only = (unsigned)((int)((unsigned)x.l - th) >> 31);     // strict: Alg. 3
+        sp += (unsigned)x.l & ~dev_only;
+        if (NEED >= 1) pk += (x.pn & dev_only) | (pnr[sub * G + it] & ~dev_only);
+        if (NEED >= 2) {
+            const unsigned tb = (x.d & dev_only) | (x.m & ~dev_only);
+            ts += (double)u2f(tb);
+            mn = min(mn, tb); mx = max(mx, tb);
+        }
+    }
+    t.s_pre += sp;
+    t.d_dec += pk & ((1u << PN_COUNT_SHIFT) - 1u); t.won += pk >> PN_COUNT_SHIFT;
+    t.ttft_sum += ts;
+    t.minb = mn; t.maxb = mx;
+}
+
 // General form: ragged last batch or huge lengths; everything in 64 bit, every update masked.
 template <int G>
 __device__ __forceinline__ void batch_pairs_slow(const Staged* __restrict__ st, int sub, int cnt, i64 base, const disco_policy& p,
@@ -269,26 +300,53 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
     const int col = lane & (G - 1), sub = lane / G;
     const bool colv = col < P;
     const disco_policy p = pol[colv ? col : 0];
-    const int mode = table_mode(p, colv);
     ColTotals t{0, 0, 0, 0, 0, 0.0, 0xFFFFFFFFu, 0u};
     u64 tot_l = 0, tot_n = 0, tot_c = 0;      // column-independent sums, kept by the loading lane
     Staged* st = stage + wave * 64;
+    StagedRace* sr = reinterpret_cast<StagedRace*>(smem + DP_BLOCK * sizeof(Staged)) + wave * 64;
+    unsigned* pnr = reinterpret_cast<unsigned*>(smem + DP_BLOCK * (sizeof(Staged) + sizeof(StagedRace))) + wave * 64;
     const i64 nbatch = (tr.n_req + 63) >> 6;
-    for (i64 b = (i64)blockIdx.x * DP_WAVES + wave; b < nbatch; b += (i64)gridDim.x * DP_WAVES) {
+    const i64 bstride = (i64)gridDim.x * DP_WAVES;
+    // one batch ahead: the loads of the next batch (at first: of the first one, together with the policy
+    // record) are in flight while the current one is evaluated
+    int lv_n = 0, nv_n = 0;
+    float sv_n = 0.0f, kv_n = tr.k_s;
+    auto load_batch = [&](i64 b) {
         const i64 i = b * 64 + lane;
-        const bool v = i < tr.n_req;
-        const int lv = v ? tr.l[i] : 0;
-        const int nv = v ? tr.n[i] : 0;
-        const float sv = v ? tr.s[i] : 0.0f;
-        const float kv = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
+        const bool v = b < nbatch && i < tr.n_req;
+        lv_n = v ? tr.l[i] : 0;
+        nv_n = v ? tr.n[i] : 0;
+        sv_n = v ? tr.s[i] : 0.0f;
+        kv_n = tr.k ? (v ? tr.k[i] : 0.0f) : tr.k_s;
+    };
+    i64 b = (i64)blockIdx.x * DP_WAVES + wave;
+    load_batch(b);
+    const int mode = table_mode(p, colv);
+    for (; b < nbatch; b += bstride) {
+        const bool v = b * 64 + lane < tr.n_req;
+        const int lv = lv_n, nv = nv_n;
+        const float sv = sv_n, kv = kv_n;
+        load_batch(b + bstride);
         const float dv = __fmaf_rn((float)lv, kv, tr.c);          // device TTFT T_d(l) = k l + c
         tot_l += (u64)lv; tot_n += (u64)nv; tot_c += v ? 1ull : 0ull;
-        st[lane] = Staged{lv, sv, nv, dv};
         const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
         const bool small = __ballot(((unsigned)lv | (unsigned)nv) >= (1u << 24)) == 0ull;
+        const bool threshold_form = mode == 0 && cnt == 64 && __ballot((unsigned)lv >= (1u << 24) || (unsigned)nv >= (1u << 16)) == 0ull;
+        if (threshold_form) {
+            const bool race_dev = dv < sv;                       // ties go to the server
+            const unsigned pn = (unsigned)nv | (1u << PN_COUNT_SHIFT);
+            sr[lane] = StagedRace{lv, f2u(dv), f2u(race_dev ? dv : sv), pn};
+            pnr[lane] = race_dev ? pn : 0u;
+        } else {
+            st[lane] = Staged{lv, sv, nv, dv};
+        }
         // the staging area is private to the wave: no workgroup barrier needed
         __builtin_amdgcn_wave_barrier();
-        if (small) {
+        if (threshold_form) {
+            if (fin.need == 0) batch_pairs_threshold<G, 0>(sr, pnr, sub, p, t);
+            else if (fin.need == 1) batch_pairs_threshold<G, 1>(sr, pnr, sub, p, t);
+            else batch_pairs_threshold<G, 2>(sr, pnr, sub, p, t);
+        } else if (small) {
             if (mode == 0) batch_pairs_need<G, 0>(st, sub, cnt, b * 64, p, fin.need, t);
             else if (mode == 1) batch_pairs_need<G, 1>(st, sub, cnt, b * 64, p, fin.need, t);
             else batch_pairs_need<G, 2>(st, sub, cnt, b * 64, p, fin.need, t);

@@ -24,36 +24,37 @@ __host__ __device__ inline MigPartial* tl_totals(u64* totals)
     return reinterpret_cast<MigPartial*>(totals + DISCO_NCOPY * 64 * 8);
 }
 
-// Identity of the dispatch totals (8 words per column and copy, word-major; word 7 = {min bits, max bits}).
-__device__ inline void reset_dispatch_totals(u64* totals, int i /* 0..63 */)
+// Staging of the policy table (wave 0); all 1024 threads also put the tickets and the per-column totals that
+// the workgroups of a pass add into at their identity: the dispatch totals (8 words per column and copy,
+// word-major; word 7 = {min bits, max bits}) and, behind them, the timeline totals (all zero).
+constexpr int STAGE_THREADS = 1024;
+__device__ inline void reset_totals(u64* totals)
 {
-    for (int w = 0; w < 8 * DISCO_NCOPY; ++w) totals[w * 64 + i] = w >= 7 * DISCO_NCOPY ? 0x00000000FFFFFFFFull : 0ull;
+    constexpr int DISP_WORDS = 8 * DISCO_NCOPY * 64, TL_WORDS = DISCO_NCOPY * 64 * (int)(sizeof(MigPartial) / 8);
+    for (int w = threadIdx.x; w < DISP_WORDS + TL_WORDS; w += STAGE_THREADS)
+        totals[w] = (w >= 7 * DISCO_NCOPY * 64 && w < DISP_WORDS) ? 0x00000000FFFFFFFFull : 0ull;
 }
 
-// Staging of the policy table; also puts the tickets and the per-column
-// totals that the workgroups of a pass add into at their identity.
-__global__ void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets, u64* totals)
+__global__ __launch_bounds__(STAGE_THREADS) void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets, u64* totals)
 {
-    int i = threadIdx.x;
-    if (i < P) dst[i] = t.p[i];
-    const bool any_buffer = __ballot(i < P && t.p[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
+    const int i = threadIdx.x;
     if (i < 64) {
+        if (i < P) dst[i] = t.p[i];
+        const bool any_buffer = __ballot(i < P && t.p[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
         tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
-        reset_dispatch_totals(totals, i);
-        for (int k = 0; k < DISCO_NCOPY; ++k) tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
     }
+    reset_totals(totals);
 }
 
-__global__ void k_copy_policies(const disco_policy* src, int P, disco_policy* dst, unsigned* tickets, u64* totals)
+__global__ __launch_bounds__(STAGE_THREADS) void k_copy_policies(const disco_policy* src, int P, disco_policy* dst, unsigned* tickets, u64* totals)
 {
-    int i = threadIdx.x;
-    if (i < P) dst[i] = src[i];
-    const bool any_buffer = __ballot(i < P && src[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
+    const int i = threadIdx.x;
     if (i < 64) {
+        if (i < P) dst[i] = src[i];
+        const bool any_buffer = __ballot(i < P && src[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
         tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
-        reset_dispatch_totals(totals, i);
-        for (int k = 0; k < DISCO_NCOPY; ++k) tl_totals(totals)[k * 64 + i] = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
     }
+    reset_totals(totals);
 }
 
 // ----------------------------------------------------------------- select --
@@ -356,7 +357,7 @@ int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, 
     if (!pol) return DISCO_ERR_NULL;
     if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
     if (is_device_pointer(pol)) {
-        hipLaunchKernelGGL(k_copy_policies, dim3(1), dim3(64), 0, stream, pol, P, (disco_policy*)(ws + L.pol),
+        hipLaunchKernelGGL(k_copy_policies, dim3(1), dim3(STAGE_THREADS), 0, stream, pol, P, (disco_policy*)(ws + L.pol),
                            (unsigned*)(ws + L.ticket), (u64*)(ws + L.part));
         return DISCO_OK;
     }
@@ -365,7 +366,7 @@ int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, 
     PolTable t;
     memset(&t, 0, sizeof(t));
     memcpy(t.p, pol, sizeof(disco_policy) * (size_t)P);
-    hipLaunchKernelGGL(k_store_policies, dim3(1), dim3(64), 0, stream, t, P, (disco_policy*)(ws + L.pol),
+    hipLaunchKernelGGL(k_store_policies, dim3(1), dim3(STAGE_THREADS), 0, stream, t, P, (disco_policy*)(ws + L.pol),
                        (unsigned*)(ws + L.ticket), (u64*)(ws + L.part));
     return DISCO_OK;
 }

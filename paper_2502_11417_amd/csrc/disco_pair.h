@@ -10,6 +10,12 @@ constexpr int DP_WAVES = DP_BLOCK / 64;
 constexpr int DP_MAX_BLOCKS = 256;          // one workgroup per CU: the ticket chain stays short
 
 struct Staged { int l; float s; int n; float d; };      // 16 bytes, one per request of the batch
+// What a race decides does not depend on the column: d = device TTFT, m = TTFT of a race (ties go to the server), pn = decode
+// tokens with a count of one above them (n < 2^16, so 64 of them add up below bit 22), and, in an array of its
+// own, pnr = pn if the device wins the race, else 0.  A threshold column (Alg. 3) only selects between the
+// device-only and the race values.
+struct StagedRace { int l; unsigned d, m, pn; };         // d, m: bit patterns of the two TTFT candidates
+constexpr unsigned PN_COUNT_SHIFT = 22;
 
 // ------------------------------------------------------------ per pair ----
 
