@@ -60,7 +60,18 @@ struct TtftCls {
     unsigned char col_of_pos[DISCO_MAX_COLS];
     int pad[3];
 };
-struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; TlSel tl; TtftCls tc; };   // [0] TTFT, [1] TBT
+// TTFT selection by classes, after the first pass: when all values that carry the first digit of some live slot
+// fit the candidate list, the second pass sorts them into buckets (one per distinct digit, named by the smallest
+// slot that has it) and every slot finishes its remaining digits from its bucket.
+struct TtftBuckets {
+    int on;
+    unsigned ticket;
+    unsigned base[DISCO_MAX_SLOTS];          // first entry of the bucket in the list (multiple of 4)
+    unsigned cap[DISCO_MAX_SLOTS];           // entries it can take: the values of the first pass with that digit
+    unsigned fill[DISCO_MAX_SLOTS];          // entries written
+    int of_slot[DISCO_MAX_SLOTS];            // bucket of a slot, -1: none
+};
+struct SelState { SelGlobal g[2]; SelSlot slot[2][DISCO_MAX_SLOTS]; TlSel tl; TtftCls tc; TtftBuckets tb; };   // [0] TTFT, [1] TBT
 
 // Device-wide totals are kept in DISCO_NCOPY copies (workgroup b adds into copy b % DISCO_NCOPY) so that
 // the atomics of different workgroups do not all queue up on one cache line.

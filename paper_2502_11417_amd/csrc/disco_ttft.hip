@@ -220,6 +220,9 @@ struct ClsTables {
     unsigned sprefix[DISCO_MAX_SLOTS];
     int slive[DISCO_MAX_SLOTS];
     int first_of[DISCO_MAX_SLOTS];               // smallest live slot with the same prefix
+    unsigned bcnt[DISCO_MAX_SLOTS];              // scatter pass: entries of this workgroup per bucket, ...
+    unsigned bat[DISCO_MAX_SLOTS];               // ... where they go in the list, and where the bucket ends
+    unsigned bend[DISCO_MAX_SLOTS];
     unsigned char col_of_pos[DISCO_MAX_COLS];
 };
 
@@ -263,11 +266,13 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
     const int nslot = P * nq;
     const int rows = (pass == 0) ? 2 * (P + 1) : nslot;
     const int t = threadIdx.x;
+    const bool scatter = pass == 1 && S->tb.on != 0;
     // the slot records travel from device memory while the bins are cleared
     SelSlot sl;
     const bool in = pass > 0 && t < nslot;
     if (in) sl = S->slot[0][t];
-    if (!gather)
+    if (scatter && t < DISCO_MAX_SLOTS) { T.bat[t] = S->tb.base[t]; T.bend[t] = S->tb.base[t] + S->tb.cap[t]; }
+    if (!gather && !scatter)
         for (int i = t; i < rows * TH_STRIDE; i += DP_BLOCK) hist[i] = 0u;
     if (t < DISCO_MAX_COLS) { T.sorted[t] = t < P ? S->tc.sorted_lth[t] : 0x7FFFFFFF; T.col_of_pos[t] = S->tc.col_of_pos[t]; }
     if (pass > 0) {
@@ -321,6 +326,69 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
     __syncthreads();
     const bool cached = ubytes != nullptr && pass > 0;
     const i64 stride = (i64)nblk * DP_BLOCK;
+    if (scatter) {
+        // same matching as a histogram pass, but the value goes to the bucket of its digit: positions inside the
+        // workgroup's share of a bucket from an LDS counter, the share itself from one device-wide atomic per
+        // bucket, workgroup and round of TC_UNROLL strides
+        GEntry* list = reinterpret_cast<GEntry*>(slices);
+        for (i64 base = (i64)bid * DP_BLOCK; base < tr.n_req; base += TC_UNROLL * stride) {
+            if (t < DISCO_MAX_SLOTS) T.bcnt[t] = 0u;
+            bool v[TC_UNROLL];
+            int l[TC_UNROLL], ubc[TC_UNROLL];
+            float sv[TC_UNROLL], kv[TC_UNROLL];
+#pragma unroll
+            for (int q = 0; q < TC_UNROLL; ++q) {
+                const i64 i = base + q * stride + t;
+                v[q] = i < tr.n_req;
+                l[q] = v[q] ? tr.l[i] : 0;
+                sv[q] = v[q] ? tr.s[i] : 0.0f;
+                kv[q] = tr.k ? (v[q] ? tr.k[i] : 0.0f) : tr.k_s;
+                ubc[q] = (cached && v[q]) ? (int)ubytes[i] : 0;
+            }
+            __syncthreads();
+            unsigned ekey[2 * TC_UNROLL], etag[2 * TC_UNROLL], epos[2 * TC_UNROLL];
+            int ebkt[2 * TC_UNROLL];
+#pragma unroll
+            for (int q = 0; q < TC_UNROLL; ++q) {
+                const float s = sv[q];
+                const float d = __fmaf_rn((float)l[q], kv[q], tr.c);
+                const int ub = v[q] ? (cached ? ubc[q] : request_ub(T, P, l[q])) : 0;
+                const bool dev_wins = d < s;
+                const int ub0 = dev_wins ? 0 : ub;
+                const bool two = !dev_wins && ub > 0;
+#pragma unroll
+                for (int which = 0; which < 2; ++which) {
+                    const int e = 2 * q + which;
+                    const unsigned key = (which ? f2u(s) : f2u(d)) - g.minb;
+                    const int u = which ? ub : ub0;
+                    int f = -1;
+                    if (v[q] && (which ? two : ub0 < P)) {
+                        f = prefix_lookup(T, key >> up);
+                        if (f >= 0) {
+                            u64 m0 = T.dmask[f][0], m1 = T.dmask[f][1];
+                            if (which) { m0 &= ~T.dslots[u][0]; m1 &= ~T.dslots[u][1]; }
+                            else { m0 &= T.dslots[u][0]; m1 &= T.dslots[u][1]; }
+                            if ((m0 | m1) == 0ull) f = -1;
+                        }
+                    }
+                    ekey[e] = key; etag[e] = ((unsigned)which << 16) | (unsigned)u; ebkt[e] = f;
+                    epos[e] = f >= 0 ? atomicAdd(&T.bcnt[f], 1u) : 0u;
+                }
+            }
+            __syncthreads();
+            if (t < DISCO_MAX_SLOTS && T.bcnt[t]) T.bat[t] = S->tb.base[t] + atomicAdd(&S->tb.fill[t], T.bcnt[t]);
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 2 * TC_UNROLL; ++e) {
+                if (ebkt[e] < 0) continue;
+                const unsigned at = T.bat[ebkt[e]] + epos[e];
+                if (at < T.bend[ebkt[e]]) list[at] = GEntry{ekey[e], etag[e]};
+                else S->g[0].gather_error = 1;                  // a bucket takes every value with its digit: never expected
+            }
+            __syncthreads();
+        }
+        return;
+    }
     if (gather) {
         // same matching as a histogram pass, but the value is appended to the candidate list (all lanes of a
         // wave stay together: the append is a wave operation)
@@ -435,6 +503,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disc
     __shared__ ClsTables T;
     const bool cls_block = (int)blockIdx.x < ncls_blocks;
     if (cls_block != (S->tc.on != 0)) return;
+    if (pass >= 2 && S->tb.on) return;                    // the buckets finished the selection
     const bool gather = pass >= 2 && gather_on(S->g[0]);
     if (gather && pass > 2) return;                       // the list finished the selection
     if (cls_block) cls_body(tr, P, nq, pass, S, slices, hist, T, blockIdx.x, ncls_blocks, gather, ubytes);
@@ -474,20 +543,18 @@ __global__ __launch_bounds__(1024) void k_ttft_reduce(const SelState* S, int pas
         rowsum[((size_t)row << dg.width) + bin] = part[bin] + part[256 + bin] + part[512 + bin] + part[768 + bin];
 }
 
-// The slot's remaining digits from the candidate list (workgroup = slot): histograms of up to 12 bits at a time
-// (one scan of the list when 12 bits or fewer are left) over the entries that carry the slot's prefix and belong
-// to its column; four entries per thread and iteration are in flight.
-__device__ void finish_from_list(SelState* S, int s, int col, SelSlot sl, const GEntry* __restrict__ list)
+// The slot's remaining R digits from n candidates (workgroup = slot; the whole list, or the bucket of the slot's
+// first digit): histograms of up to 12 bits at a time (one scan when 12 bits or fewer are left) over the entries
+// that carry the slot's prefix and belong to its column; four entries per thread and iteration are in flight
+// (`list` is 16-byte aligned and readable up to the next multiple of four entries).
+__device__ void finish_from_list(SelState* S, int s, int col, SelSlot sl, const GEntry* __restrict__ list, unsigned n, int R)
 {
     constexpr int FW = 12, FB = 1 << FW;
     __shared__ unsigned fh[FB];
     __shared__ unsigned chosen;
     __shared__ u64 k_next, fsum[16];
-    const SelGlobal g = S->g[0];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const unsigned pos = S->tc.on ? S->tc.pos_of_col[col] : 0u;
-    const unsigned n = g.n_list < TG_CAP ? g.n_list : TG_CAP;
-    int R = g.plan.shift[1];                         // undecided low bits
     unsigned prefix = sl.prefix;
     u64 k = (u64)sl.k_rem;
     while (R > 0) {
@@ -543,6 +610,56 @@ __device__ void finish_from_list(SelState* S, int s, int col, SelSlot sl, const 
     if (t == 0) { sl.prefix = prefix; sl.k_rem = (i64)k; S->slot[0][s] = sl; }
 }
 
+// After the first pass of a class-mode selection (last workgroup of k_ttft_select, all its threads): the live
+// slots are grouped by their first digit; a group's bucket can take every value of the first pass with that
+// digit (all rows of the row sums).  The buckets are used if they all fit the list.
+__device__ void plan_buckets(SelState* S, int P, int nq, const unsigned* __restrict__ rowsum, int width)
+{
+    __shared__ unsigned pfx[DISCO_MAX_SLOTS], cnt[DISCO_MAX_SLOTS], psum[1024];
+    __shared__ int head[DISCO_MAX_SLOTS];
+    const int t = threadIdx.x, nslot = P * nq, rows = 2 * (P + 1);
+    if (t < DISCO_MAX_SLOTS) {
+        bool live = false;
+        unsigned prefix = 0u;
+        if (t < nslot) { const SelSlot sl = S->slot[0][t]; live = !sl.done; prefix = sl.prefix; }
+        pfx[t] = live ? prefix : 0xFFFFFFFFu;               // keys have 31 bits: never a prefix
+    }
+    __syncthreads();
+    if (t < DISCO_MAX_SLOTS) {
+        const unsigned mine = pfx[t];
+        int f = -1;
+        if (mine != 0xFFFFFFFFu)
+            for (int z = DISCO_MAX_SLOTS - 1; z >= 0; --z) f = pfx[z] == mine ? z : f;       // smallest slot with my digit
+        head[t] = f;
+    }
+    __syncthreads();
+    {
+        const int f = t & (DISCO_MAX_SLOTS - 1), part = t / DISCO_MAX_SLOTS, nparts = 1024 / DISCO_MAX_SLOTS;
+        unsigned a = 0u;
+        if (head[f] == f)
+            for (int row = part; row < rows; row += nparts) a += rowsum[((size_t)row << width) + pfx[f]];
+        psum[t] = a;
+    }
+    __syncthreads();
+    if (t < DISCO_MAX_SLOTS) {
+        unsigned a = 0u;
+        for (int part = 0; part < 1024 / DISCO_MAX_SLOTS; ++part) a += psum[part * DISCO_MAX_SLOTS + t];
+        cnt[t] = a;
+    }
+    __syncthreads();
+    if (t == 0) {
+        u64 at = 0;
+        for (int f = 0; f < DISCO_MAX_SLOTS; ++f) {
+            if (head[f] != f) continue;
+            S->tb.base[f] = (unsigned)(at < TG_CAP ? at : TG_CAP);
+            S->tb.cap[f] = cnt[f];
+            at += ((u64)cnt[f] + 3ull) & ~3ull;
+        }
+        S->tb.on = at <= (u64)TG_CAP;
+    }
+    if (t < DISCO_MAX_SLOTS) { S->tb.of_slot[t] = head[t]; S->tb.fill[t] = 0u; }
+}
+
 // Workgroup = (column, quantile) slot: the slot's histogram from the row sums
 // (thread = (bin, quarter of the rows)), the digit that holds the remaining
 // rank, the extended prefix.
@@ -557,12 +674,27 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
     const int width = dg.width;
     const int s = blockIdx.x;
     SelSlot sl = S->slot[0][s];
-    if (sl.done) return;
+    // class mode, more than one digit: after the first pass the last workgroup plans the buckets (every workgroup
+    // of the launch takes a ticket, also those of finished slots)
+    const bool plan_here = pass == 0 && S->tc.on && S->g[0].plan.npass >= 2;
+    if (sl.done && !plan_here) return;
     const int col = s / nq;
-    if (pass >= 2 && gather_on(S->g[0])) {
-        if (pass == 2) finish_from_list(S, s, col, sl, reinterpret_cast<const GEntry*>(slices));
+    if (pass >= 1 && S->tb.on) {
+        if (pass == 1) {
+            const int b = S->tb.of_slot[s];
+            const unsigned fill = S->tb.fill[b], cap = S->tb.cap[b];
+            finish_from_list(S, s, col, sl, reinterpret_cast<const GEntry*>(slices) + S->tb.base[b], fill < cap ? fill : cap,
+                             S->g[0].plan.shift[0]);
+        }
         return;
     }
+    if (pass >= 2 && gather_on(S->g[0])) {
+        const unsigned nl = S->g[0].n_list;
+        if (pass == 2) finish_from_list(S, s, col, sl, reinterpret_cast<const GEntry*>(slices), nl < TG_CAP ? nl : TG_CAP,
+                                        S->g[0].plan.shift[1]);
+        return;
+    }
+    if (!sl.done) {
     const int nbins = 1 << width;                          // <= 256
     const int t = threadIdx.x & 255, q = threadIdx.x >> 8, lane = t & 63, wave = t >> 6;
     u64 mine = 0;
@@ -607,6 +739,11 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
         S->slot[0][s] = sl;
         // every value that still matches some slot after this pass is counted in that slot's bin
         if (pass == 1) atomicAdd((unsigned long long*)&S->g[0].gather_bound, (unsigned long long)mine);
+    }
+    }
+    if (plan_here && take_last_ticket(&S->tb.ticket)) {
+        plan_buckets(S, P, nq, rowsum, width);
+        if (threadIdx.x == 0) S->tb.ticket = 0u;
     }
 }
 

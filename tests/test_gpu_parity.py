@@ -480,3 +480,25 @@ def test_stats_heavy_ties_keep_the_histogram_passes(B, oracle, kind):
                 [dict(mode=1, l_th=-1, w_tail=DI.f32(w)) for w in np.linspace(0.6, 3.0, 32)]
     got, want = check_stats(B, oracle, tr, specs, DI.COST_S)
     assert sum(1 for w in want if np.float32(w["ttft_q"][0]) == np.float32(0.5)) > 32
+
+
+@pytest.mark.parametrize("kind", ["band", "ties"])
+def test_stats_threshold_table_too_large_for_buckets(B, oracle, kind):
+    """Threshold table (selection by classes) on 2.3 M requests whose server TTFTs nearly all carry one first radix
+    digit: the values with the digits of the wanted order statistics outnumber the candidate list (2^21 entries),
+    so the second pass is a histogram pass again.  'band': the values spread over the second digit and the list
+    takes over after that pass; 'ties': one value dominates and the histogram passes go on to the end."""
+    print(f"stats parity threshold table beyond the bucket capacity: {kind}", flush=True)
+    rng = np.random.default_rng(29)
+    n = 2_300_000
+    tr = DI.handmade_trace(67, n, tokens=False)
+    common = rng.random(n) < 0.96
+    if kind == "band":
+        near = (np.uint32(0x3F000000) + rng.integers(0, 1 << 17, n).astype(np.uint32)).view(np.float32)   # 2^17 bit patterns in a row from 0.5
+    else:
+        near = np.full(n, 0.5, np.float32)
+    tr["srv_ttft"] = np.where(common, near, tr["srv_ttft"]).astype(np.float32)
+    tr["dev_pre_spt"] = (tr["dev_pre_spt"] * np.float32(50)).astype(np.float32)       # the server wins nearly every race
+    specs = [dict(mode=0, l_th=int(t)) for t in np.linspace(0, 400, 8)]
+    got, want = check_stats(B, oracle, tr, specs, DI.COST_S)
+    assert sum(1 for w in want if 0.5 <= float(w["ttft_q"][0]) < 0.53) >= 6
