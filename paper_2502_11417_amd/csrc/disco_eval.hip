@@ -90,7 +90,7 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
             S->tc.pos_of_col[t] = (unsigned char)rank;
         }
         __syncthreads();
-        if (t == 0) { S->tc.on = all_thresholds; S->tb.on = 0; S->tb.ticket = 0u; }
+        if (t == 0) { S->tc.on = all_thresholds; S->tb.on = 0; S->tb.pad = 0; }
         if (t < DISCO_MAX_SLOTS) { S->tb.fill[t] = 0u; S->tb.of_slot[t] = -1; }
     }
     if (which == 0 && (int)threadIdx.x < P) {

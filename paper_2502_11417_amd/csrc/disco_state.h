@@ -62,10 +62,11 @@ struct TtftCls {
 };
 // TTFT selection by classes, after the first pass: when all values that carry the first digit of some live slot
 // fit the candidate list, the second pass sorts them into buckets (one per distinct digit, named by the smallest
-// slot that has it) and every slot finishes its remaining digits from its bucket.
+// slot that has it) and every slot finishes its remaining digits from its bucket.  The workgroups of the second
+// pass all derive the same plan from the row sums; the first one stores it here for the select kernel.
 struct TtftBuckets {
     int on;
-    unsigned ticket;
+    int pad;
     unsigned base[DISCO_MAX_SLOTS];          // first entry of the bucket in the list (multiple of 4)
     unsigned cap[DISCO_MAX_SLOTS];           // entries it can take: the values of the first pass with that digit
     unsigned fill[DISCO_MAX_SLOTS];          // entries written

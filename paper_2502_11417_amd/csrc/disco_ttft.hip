@@ -220,9 +220,11 @@ struct ClsTables {
     unsigned sprefix[DISCO_MAX_SLOTS];
     int slive[DISCO_MAX_SLOTS];
     int first_of[DISCO_MAX_SLOTS];               // smallest live slot with the same prefix
-    unsigned bcnt[DISCO_MAX_SLOTS];              // scatter pass: entries of this workgroup per bucket, ...
-    unsigned bat[DISCO_MAX_SLOTS];               // ... where they go in the list, and where the bucket ends
-    unsigned bend[DISCO_MAX_SLOTS];
+    unsigned bbase[DISCO_MAX_SLOTS];             // scatter pass: first entry of a bucket in the list and the entry
+    unsigned bend[DISCO_MAX_SLOTS];              // behind its last; entries of this workgroup for it in this round,
+    unsigned bcnt[DISCO_MAX_SLOTS];              // and where they go
+    unsigned bat[DISCO_MAX_SLOTS];
+    int scatter;
     unsigned char col_of_pos[DISCO_MAX_COLS];
 };
 
@@ -256,7 +258,7 @@ constexpr int TC_UNROLL = 4;
 
 __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int pass, SelState* S,
                                          unsigned* __restrict__ slices, unsigned* hist, ClsTables& T, int bid, int nblk,
-                                         bool gather, unsigned char* __restrict__ ubytes)
+                                         bool gather, unsigned char* __restrict__ ubytes, const unsigned* __restrict__ rowsum)
 {
     const SelGlobal g = S->g[0];
     const PassDigit dg = pass_digit(g, pass);
@@ -266,13 +268,12 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
     const int nslot = P * nq;
     const int rows = (pass == 0) ? 2 * (P + 1) : nslot;
     const int t = threadIdx.x;
-    const bool scatter = pass == 1 && S->tb.on != 0;
+    const bool may_scatter = pass == 1 && g.plan.npass >= 2;
     // the slot records travel from device memory while the bins are cleared
     SelSlot sl;
     const bool in = pass > 0 && t < nslot;
     if (in) sl = S->slot[0][t];
-    if (scatter && t < DISCO_MAX_SLOTS) { T.bat[t] = S->tb.base[t]; T.bend[t] = S->tb.base[t] + S->tb.cap[t]; }
-    if (!gather && !scatter)
+    if (!gather && !may_scatter)
         for (int i = t; i < rows * TH_STRIDE; i += DP_BLOCK) hist[i] = 0u;
     if (t < DISCO_MAX_COLS) { T.sorted[t] = t < P ? S->tc.sorted_lth[t] : 0x7FFFFFFF; T.col_of_pos[t] = S->tc.col_of_pos[t]; }
     if (pass > 0) {
@@ -324,6 +325,51 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
         }
     }
     __syncthreads();
+    bool scatter = false;
+    if (may_scatter) {
+        // Second pass: the live slots are grouped by their first digit (tables above: first_of names the group).
+        // A group's bucket can take every value of the first pass with that digit (all rows of the row sums); if
+        // the buckets of all groups fit the list, the values are sorted into them and the slots finish from there,
+        // else this is a histogram pass.  Every workgroup plans the same buckets; the first one leaves the plan
+        // to the select kernel.
+        unsigned* psum = hist;                              // the bins are idle
+        const int w0 = g.plan.width[0];
+        {
+            const int f = t & (DISCO_MAX_SLOTS - 1), part = t / DISCO_MAX_SLOTS;
+            unsigned a = 0u;
+            if (T.slive[f] && T.first_of[f] == f)
+                for (int row = part; row < 2 * (P + 1); row += DP_BLOCK / DISCO_MAX_SLOTS)
+                    a += rowsum[((size_t)row << w0) + T.sprefix[f]];
+            psum[t] = a;
+        }
+        __syncthreads();
+        if (t < DISCO_MAX_SLOTS) {
+            unsigned a = 0u;
+            for (int part = 0; part < DP_BLOCK / DISCO_MAX_SLOTS; ++part) a += psum[part * DISCO_MAX_SLOTS + t];
+            T.bcnt[t] = a;
+        }
+        __syncthreads();
+        if (t < DISCO_MAX_SLOTS) {
+            u64 at = 0;
+            for (int z = 0; z < t; ++z) at += ((u64)T.bcnt[z] + 3ull) & ~3ull;      // buckets start at multiples of four entries
+            const u64 end = at + T.bcnt[t];
+            T.bbase[t] = (unsigned)(at < TG_CAP ? at : TG_CAP);
+            T.bend[t] = (unsigned)(end < TG_CAP ? end : TG_CAP);
+            if (t == DISCO_MAX_SLOTS - 1) T.scatter = end <= (u64)TG_CAP;
+        }
+        __syncthreads();
+        scatter = T.scatter != 0;
+        if (bid == 0 && t < DISCO_MAX_SLOTS) {
+            S->tb.base[t] = T.bbase[t]; S->tb.cap[t] = T.bend[t] - T.bbase[t];
+            S->tb.of_slot[t] = T.slive[t] ? T.first_of[t] : -1;
+            if (t == 0) S->tb.on = scatter ? 1 : 0;
+        }
+        if (!scatter) {
+            __syncthreads();                                // psum has been read
+            for (int i = t; i < rows * TH_STRIDE; i += DP_BLOCK) hist[i] = 0u;
+            __syncthreads();
+        }
+    }
     const bool cached = ubytes != nullptr && pass > 0;
     const i64 stride = (i64)nblk * DP_BLOCK;
     if (scatter) {
@@ -376,7 +422,7 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
                 }
             }
             __syncthreads();
-            if (t < DISCO_MAX_SLOTS && T.bcnt[t]) T.bat[t] = S->tb.base[t] + atomicAdd(&S->tb.fill[t], T.bcnt[t]);
+            if (t < DISCO_MAX_SLOTS && T.bcnt[t]) T.bat[t] = T.bbase[t] + atomicAdd(&S->tb.fill[t], T.bcnt[t]);
             __syncthreads();
 #pragma unroll
             for (int e = 0; e < 2 * TC_UNROLL; ++e) {
@@ -496,7 +542,8 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
 template <int G>
 __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
                                                         int pass, SelState* S, unsigned* __restrict__ slices,
-                                                        int ncls_blocks, unsigned char* __restrict__ ubytes)
+                                                        int ncls_blocks, unsigned char* __restrict__ ubytes,
+                                                        const unsigned* __restrict__ rowsum)
 {
     __shared__ unsigned hist[TH_WORDS];
     __shared__ __align__(16) Staged stage[DP_BLOCK];
@@ -506,7 +553,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_ttft_hist(TraceView tr, const disc
     if (pass >= 2 && S->tb.on) return;                    // the buckets finished the selection
     const bool gather = pass >= 2 && gather_on(S->g[0]);
     if (gather && pass > 2) return;                       // the list finished the selection
-    if (cls_block) cls_body(tr, P, nq, pass, S, slices, hist, T, blockIdx.x, ncls_blocks, gather, ubytes);
+    if (cls_block) cls_body(tr, P, nq, pass, S, slices, hist, T, blockIdx.x, ncls_blocks, gather, ubytes, rowsum);
     else pair_body<G>(tr, pol, P, nq, pass, S, slices, hist, stage, (int)blockIdx.x - ncls_blocks, (int)gridDim.x - ncls_blocks,
                       gather);
 }
@@ -610,56 +657,6 @@ __device__ void finish_from_list(SelState* S, int s, int col, SelSlot sl, const 
     if (t == 0) { sl.prefix = prefix; sl.k_rem = (i64)k; S->slot[0][s] = sl; }
 }
 
-// After the first pass of a class-mode selection (last workgroup of k_ttft_select, all its threads): the live
-// slots are grouped by their first digit; a group's bucket can take every value of the first pass with that
-// digit (all rows of the row sums).  The buckets are used if they all fit the list.
-__device__ void plan_buckets(SelState* S, int P, int nq, const unsigned* __restrict__ rowsum, int width)
-{
-    __shared__ unsigned pfx[DISCO_MAX_SLOTS], cnt[DISCO_MAX_SLOTS], psum[1024];
-    __shared__ int head[DISCO_MAX_SLOTS];
-    const int t = threadIdx.x, nslot = P * nq, rows = 2 * (P + 1);
-    if (t < DISCO_MAX_SLOTS) {
-        bool live = false;
-        unsigned prefix = 0u;
-        if (t < nslot) { const SelSlot sl = S->slot[0][t]; live = !sl.done; prefix = sl.prefix; }
-        pfx[t] = live ? prefix : 0xFFFFFFFFu;               // keys have 31 bits: never a prefix
-    }
-    __syncthreads();
-    if (t < DISCO_MAX_SLOTS) {
-        const unsigned mine = pfx[t];
-        int f = -1;
-        if (mine != 0xFFFFFFFFu)
-            for (int z = DISCO_MAX_SLOTS - 1; z >= 0; --z) f = pfx[z] == mine ? z : f;       // smallest slot with my digit
-        head[t] = f;
-    }
-    __syncthreads();
-    {
-        const int f = t & (DISCO_MAX_SLOTS - 1), part = t / DISCO_MAX_SLOTS, nparts = 1024 / DISCO_MAX_SLOTS;
-        unsigned a = 0u;
-        if (head[f] == f)
-            for (int row = part; row < rows; row += nparts) a += rowsum[((size_t)row << width) + pfx[f]];
-        psum[t] = a;
-    }
-    __syncthreads();
-    if (t < DISCO_MAX_SLOTS) {
-        unsigned a = 0u;
-        for (int part = 0; part < 1024 / DISCO_MAX_SLOTS; ++part) a += psum[part * DISCO_MAX_SLOTS + t];
-        cnt[t] = a;
-    }
-    __syncthreads();
-    if (t == 0) {
-        u64 at = 0;
-        for (int f = 0; f < DISCO_MAX_SLOTS; ++f) {
-            if (head[f] != f) continue;
-            S->tb.base[f] = (unsigned)(at < TG_CAP ? at : TG_CAP);
-            S->tb.cap[f] = cnt[f];
-            at += ((u64)cnt[f] + 3ull) & ~3ull;
-        }
-        S->tb.on = at <= (u64)TG_CAP;
-    }
-    if (t < DISCO_MAX_SLOTS) { S->tb.of_slot[t] = head[t]; S->tb.fill[t] = 0u; }
-}
-
 // Workgroup = (column, quantile) slot: the slot's histogram from the row sums
 // (thread = (bin, quarter of the rows)), the digit that holds the remaining
 // rank, the extended prefix.
@@ -674,10 +671,7 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
     const int width = dg.width;
     const int s = blockIdx.x;
     SelSlot sl = S->slot[0][s];
-    // class mode, more than one digit: after the first pass the last workgroup plans the buckets (every workgroup
-    // of the launch takes a ticket, also those of finished slots)
-    const bool plan_here = pass == 0 && S->tc.on && S->g[0].plan.npass >= 2;
-    if (sl.done && !plan_here) return;
+    if (sl.done) return;
     const int col = s / nq;
     if (pass >= 1 && S->tb.on) {
         if (pass == 1) {
@@ -694,7 +688,6 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
                                         S->g[0].plan.shift[1]);
         return;
     }
-    if (!sl.done) {
     const int nbins = 1 << width;                          // <= 256
     const int t = threadIdx.x & 255, q = threadIdx.x >> 8, lane = t & 63, wave = t >> 6;
     u64 mine = 0;
@@ -740,19 +733,14 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
         // every value that still matches some slot after this pass is counted in that slot's bin
         if (pass == 1) atomicAdd((unsigned long long*)&S->g[0].gather_bound, (unsigned long long)mine);
     }
-    }
-    if (plan_here && take_last_ticket(&S->tb.ticket)) {
-        plan_buckets(S, P, nq, rowsum, width);
-        if (threadIdx.x == 0) S->tb.ticket = 0u;
-    }
 }
 
 template <int G>
 void launch_hist(const TraceView& v, const disco_policy* pol, int P, int nq, int pass, SelState* S, unsigned* slices,
-                 unsigned bp, unsigned bc, unsigned char* ubytes, hipStream_t stream)
+                 unsigned bp, unsigned bc, unsigned char* ubytes, const unsigned* rowsum, hipStream_t stream)
 {
     hipLaunchKernelGGL(k_ttft_hist<G>, dim3(bc + bp), dim3(DP_BLOCK), 0, stream, v, pol, P, nq, pass, S, slices, (int)bc,
-                       ubytes);
+                       ubytes, rowsum);
 }
 
 }  // namespace
@@ -769,13 +757,13 @@ void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, 
     int g = 1;
     while (g < P) g <<= 1;
     switch (g) {
-    case 1: launch_hist<1>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
-    case 2: launch_hist<2>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
-    case 4: launch_hist<4>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
-    case 8: launch_hist<8>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
-    case 16: launch_hist<16>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
-    case 32: launch_hist<32>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
-    default: launch_hist<64>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, stream); break;
+    case 1: launch_hist<1>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, rowsum, stream); break;
+    case 2: launch_hist<2>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, rowsum, stream); break;
+    case 4: launch_hist<4>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, rowsum, stream); break;
+    case 8: launch_hist<8>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, rowsum, stream); break;
+    case 16: launch_hist<16>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, rowsum, stream); break;
+    case 32: launch_hist<32>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, rowsum, stream); break;
+    default: launch_hist<64>(v, pol, P, nq, pass, S, slices, (unsigned)bp, (unsigned)bc, ubytes, rowsum, stream); break;
     }
     const int rows_pair = pass == 0 ? P : P * nq, rows_cls = pass == 0 ? 2 * (P + 1) : P * nq;
     const int rows_max = rows_pair > rows_cls ? rows_pair : rows_cls;
