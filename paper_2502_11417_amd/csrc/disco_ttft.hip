@@ -376,7 +376,9 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
         // same matching as a histogram pass, but the value goes to the bucket of its digit: positions inside the
         // workgroup's share of a bucket from an LDS counter, the share itself from one device-wide atomic per
         // bucket, workgroup and round of TC_UNROLL strides
-        GEntry* list = reinterpret_cast<GEntry*>(slices);
+        // (an entry: the key's undecided bits below the first digit, the tag's position in bits 24..30, its kind in bit 31)
+        unsigned* list = slices;
+        const unsigned lowmask = (1u << up) - 1u;
         for (i64 base = (i64)bid * DP_BLOCK; base < tr.n_req; base += TC_UNROLL * stride) {
             if (t < DISCO_MAX_SLOTS) T.bcnt[t] = 0u;
             bool v[TC_UNROLL];
@@ -392,7 +394,7 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
                 ubc[q] = (cached && v[q]) ? (int)ubytes[i] : 0;
             }
             __syncthreads();
-            unsigned ekey[2 * TC_UNROLL], etag[2 * TC_UNROLL], epos[2 * TC_UNROLL];
+            unsigned eent[2 * TC_UNROLL], epos[2 * TC_UNROLL];
             int ebkt[2 * TC_UNROLL];
 #pragma unroll
             for (int q = 0; q < TC_UNROLL; ++q) {
@@ -417,7 +419,7 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
                             if ((m0 | m1) == 0ull) f = -1;
                         }
                     }
-                    ekey[e] = key; etag[e] = ((unsigned)which << 16) | (unsigned)u; ebkt[e] = f;
+                    eent[e] = (key & lowmask) | ((unsigned)u << 24) | ((unsigned)which << 31); ebkt[e] = f;
                     epos[e] = f >= 0 ? atomicAdd(&T.bcnt[f], 1u) : 0u;
                 }
             }
@@ -428,7 +430,7 @@ __device__ __forceinline__ void cls_body(const TraceView& tr, int P, int nq, int
             for (int e = 0; e < 2 * TC_UNROLL; ++e) {
                 if (ebkt[e] < 0) continue;
                 const unsigned at = T.bat[ebkt[e]] + epos[e];
-                if (at < T.bend[ebkt[e]]) list[at] = GEntry{ekey[e], etag[e]};
+                if (at < T.bend[ebkt[e]]) list[at] = eent[e];
                 else S->g[0].gather_error = 1;                  // a bucket takes every value with its digit: never expected
             }
             __syncthreads();
@@ -590,11 +592,13 @@ __global__ __launch_bounds__(1024) void k_ttft_reduce(const SelState* S, int pas
         rowsum[((size_t)row << dg.width) + bin] = part[bin] + part[256 + bin] + part[512 + bin] + part[768 + bin];
 }
 
-// The slot's remaining R digits from n candidates (workgroup = slot; the whole list, or the bucket of the slot's
-// first digit): histograms of up to 12 bits at a time (one scan when 12 bits or fewer are left) over the entries
-// that carry the slot's prefix and belong to its column; four entries per thread and iteration are in flight
-// (`list` is 16-byte aligned and readable up to the next multiple of four entries).
-__device__ void finish_from_list(SelState* S, int s, int col, SelSlot sl, const GEntry* __restrict__ list, unsigned n, int R)
+// The slot's remaining R digits from n candidates (workgroup = slot): histograms of up to 12 bits at a time (one
+// scan when 12 bits or fewer are left) over the entries that carry the slot's prefix and belong to its column.
+// PACKED = false: the list of the third pass, 8-byte entries {key, tag}.  PACKED = true: the bucket of the slot's
+// first digit, 4-byte entries: the key's R undecided bits, above them (bits 24..30) the position u and (bit 31)
+// the kind of the tag.  `list` is 16-byte aligned and readable up to 8 entries past n.
+template <bool PACKED>
+__device__ void finish_from_list(SelState* S, int s, int col, SelSlot sl, const void* __restrict__ list_, unsigned n, int R)
 {
     constexpr int FW = 12, FB = 1 << FW;
     __shared__ unsigned fh[FB];
@@ -602,24 +606,38 @@ __device__ void finish_from_list(SelState* S, int s, int col, SelSlot sl, const 
     __shared__ u64 k_next, fsum[16];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const unsigned pos = S->tc.on ? S->tc.pos_of_col[col] : 0u;
+    const int R0 = R;
+    const unsigned low0 = R0 < 32 ? (1u << R0) - 1u : 0xFFFFFFFFu;
     unsigned prefix = sl.prefix;
     u64 k = (u64)sl.k_rem;
     while (R > 0) {
         const int w = R < FW ? R : FW, sh = R - w;
         const unsigned dm = (1u << w) - 1u;
+        const unsigned want = PACKED ? (prefix & ((1u << (R0 - R)) - 1u)) : prefix;     // PACKED: the digits found in the bucket
         for (int i = t; i < FB; i += blockDim.x) fh[i] = 0u;
         if (t == 0) chosen = 0xFFFFFFFFu;
         __syncthreads();
-        // the list is padded to its capacity, so whole groups of four can be loaded; entries past n are ignored
-        for (unsigned e0 = 4u * t; e0 < n; e0 += 4u * blockDim.x) {
-            const uint4 a = *reinterpret_cast<const uint4*>(&list[e0]);
-            const uint4 b = *reinterpret_cast<const uint4*>(&list[e0 + 2]);
-            const unsigned key[4] = {a.x, a.z, b.x, b.z}, tag[4] = {a.y, a.w, b.y, b.w};
+        auto take = [&](unsigned key, unsigned kind, unsigned u, bool valid) {
+            const bool mine = kind == 0u ? pos >= u : (kind == 1u ? pos < u : (unsigned)col == u);
+            if (valid && mine && (key >> R) == want) atomicAdd(&fh[(key >> sh) & dm], 1u);
+        };
+        if (PACKED) {
+            const unsigned* list = static_cast<const unsigned*>(list_);
+            for (unsigned e0 = 8u * t; e0 < n; e0 += 8u * blockDim.x) {
+                const uint4 a = *reinterpret_cast<const uint4*>(&list[e0]);
+                const uint4 b = *reinterpret_cast<const uint4*>(&list[e0 + 4]);
+                const unsigned e[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const unsigned kind = tag[q] >> 16, u = tag[q] & 0xFFFFu;
-                const bool mine = kind == 0u ? pos >= u : (kind == 1u ? pos < u : (unsigned)col == u);
-                if (e0 + q < n && mine && (key[q] >> R) == prefix) atomicAdd(&fh[(key[q] >> sh) & dm], 1u);
+                for (int q = 0; q < 8; ++q) take(e[q] & low0, e[q] >> 31, (e[q] >> 24) & 0x7Fu, e0 + q < n);
+            }
+        } else {
+            const GEntry* list = static_cast<const GEntry*>(list_);
+            for (unsigned e0 = 4u * t; e0 < n; e0 += 4u * blockDim.x) {
+                const uint4 a = *reinterpret_cast<const uint4*>(&list[e0]);
+                const uint4 b = *reinterpret_cast<const uint4*>(&list[e0 + 2]);
+                const unsigned key[4] = {a.x, a.z, b.x, b.z}, tag[4] = {a.y, a.w, b.y, b.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) take(key[q], tag[q] >> 16, tag[q] & 0xFFFFu, e0 + q < n);
             }
         }
         __syncthreads();
@@ -677,15 +695,13 @@ __global__ __launch_bounds__(1024) void k_ttft_select(SelState* S, int pass, int
         if (pass == 1) {
             const int b = S->tb.of_slot[s];
             const unsigned fill = S->tb.fill[b], cap = S->tb.cap[b];
-            finish_from_list(S, s, col, sl, reinterpret_cast<const GEntry*>(slices) + S->tb.base[b], fill < cap ? fill : cap,
-                             S->g[0].plan.shift[0]);
+            finish_from_list<true>(S, s, col, sl, slices + S->tb.base[b], fill < cap ? fill : cap, S->g[0].plan.shift[0]);
         }
         return;
     }
     if (pass >= 2 && gather_on(S->g[0])) {
         const unsigned nl = S->g[0].n_list;
-        if (pass == 2) finish_from_list(S, s, col, sl, reinterpret_cast<const GEntry*>(slices), nl < TG_CAP ? nl : TG_CAP,
-                                        S->g[0].plan.shift[1]);
+        if (pass == 2) finish_from_list<false>(S, s, col, sl, slices, nl < TG_CAP ? nl : TG_CAP, S->g[0].plan.shift[1]);
         return;
     }
     const int nbins = 1 << width;                          // <= 256
