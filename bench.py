@@ -24,15 +24,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
-# Vector-ALU peak for the non-packed fp32 / integer / compare instructions this path is made of:
+# Vector-ALU peak for the non-packed fp32 / fp64 / integer / compare instructions this path is made of:
 # 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz, one operation per lane and clock
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# Operations the method needs per evaluated (request, column) pair of a length-threshold column: two compares
-# (l < l_th, d < s) and the TTFT select; two conditional token sums of two operations each (server prefill, device
-# decode); the win count; the fp64 TTFT sum (convert + add); minimum and maximum of the TTFT bits
-OPS_PER_PAIR = 12
-# plain (non-packed) fp32 vector rate: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one operation per lane and clock
-ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# Operations per evaluated (request, column) pair of a length-threshold column (Alg. 3), with what a race decides
+# computed once per request: the comparison l < l_th; three selections (server prefill tokens, device decode
+# tokens and win count as one packed word, the TTFT); two integer adds; the fp64 TTFT sum (convert + add); minimum
+# and maximum of the TTFT bits.  It is also the number of vector instructions per pair that the kernel issues.
+OPS_PER_PAIR = 10
 
 
 def log(msg):

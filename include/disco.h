@@ -510,7 +510,7 @@ int32_t disco_budget_search(const disco_trace* trace /*host*/, const disco_cost_
 /* ---- helpers ------------------------------------------------------------ */
 
 /* Bytes of device workspace for n_req requests and P columns (or searches):
- * about 44 MB plus one byte per request.  Every call accepts a workspace of
+ * about 47 MB plus one byte per request.  Every call accepts a workspace of
  * disco_workspace_bytes(0, P) bytes; the per-request byte only lets the TTFT
  * selection of disco_reduce_stats keep a small per-request result between its
  * passes instead of recomputing it.  The
