@@ -140,13 +140,13 @@ __device__ __forceinline__ void add_to_totals(const u64* sh, u64* tot, int P, in
     }
 }
 
-// Last workgroup: wave f reads the copies of word f, puts them back to their
+// After the pass (k_dispatch_fin): wave f reads the copies of word f, puts them back to their
 // identity for the next pass and folds them in order; then thread = column
 // hands the sums to the accumulator or to the search.
 __device__ __forceinline__ void finish_columns(u64* tot, int P, const DispFin& fin, u64* sh /* LDS */)
 {
     const int f = threadIdx.x >> 6, c = threadIdx.x & 63;
-    if (f < 8 && c < P) {                              // (the ticket's barrier has separated this from the folds' LDS reads)
+    if (f < 8 && c < P) {
         u64 v[DISCO_NCOPY];
 #pragma unroll
         for (int k = 0; k < DISCO_NCOPY; ++k)
@@ -375,9 +375,6 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
                 DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb});
     __syncthreads();
     add_to_totals<G>(sh, part, P, fin.need);
-    if (!take_last_ticket(ticket)) return;
-    finish_columns(part, P, fin, sh);
-    if (threadIdx.x == 0) *ticket = 0u;
 }
 
 // Single column: lane = request, four consecutive requests per lane and
@@ -453,9 +450,14 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc1(TraceView tr, const 
         lds_put(sh, DP_BLOCK, wave, DispPartial{t.s_pre, t.d_pre, t.d_dec, tot_n, t.started, t.won, t.ttft_sum, t.minb, t.maxb});
     __syncthreads();
     add_to_totals<1>(sh, part, 1, fin.need);
-    if (!take_last_ticket(ticket)) return;
-    finish_columns(part, 1, fin, sh);
-    if (threadIdx.x == 0) *ticket = 0u;
+}
+
+// Device-wide totals -> accumulators or search steps (one workgroup, launched behind a dispatch pass: a kernel
+// boundary costs less than a ticket chain at the end of the pass).
+__global__ __launch_bounds__(512) void k_dispatch_fin(u64* __restrict__ part, int P, DispFin fin)
+{
+    __shared__ u64 sh[8 * 64];
+    finish_columns(part, P, fin, sh);
 }
 
 // Materialised per-pair outputs, lane = request so that every column is
@@ -620,6 +622,7 @@ void launch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, u
 {
     const unsigned blocks = dispatch_blocks((v.n_req + 63) / 64, DP_WAVES);
     hipLaunchKernelGGL(k_dispatch_acc<G>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, P, part, ticket, fin);
+    hipLaunchKernelGGL(k_dispatch_fin, dim3(1), dim3(512), 0, stream, part, P, fin);
 }
 
 int pow2_cols(int P)
@@ -640,6 +643,7 @@ void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int 
         const bool vec = aligned16(v.l) && aligned16(v.n) && aligned16(v.s) && (!v.k || aligned16(v.k));
         if (vec) hipLaunchKernelGGL(k_dispatch_acc1<true>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, part, ticket, fin);
         else hipLaunchKernelGGL(k_dispatch_acc1<false>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, part, ticket, fin);
+        hipLaunchKernelGGL(k_dispatch_fin, dim3(1), dim3(512), 0, stream, part, 1, fin);
         break;
     }
     case 2: launch_acc<2>(v, pol, P, part, ticket, fin, stream); break;
