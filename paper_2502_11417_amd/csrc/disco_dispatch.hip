@@ -291,7 +291,7 @@ __device__ __forceinline__ void batch_pairs_need(const Staged* __restrict__ st, 
 
 template <int G>
 __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const disco_policy* __restrict__ pol, int P,
-                                                           u64* __restrict__ part, unsigned* ticket, DispFin fin)
+                                                           u64* __restrict__ part, DispFin fin)
 {
     __shared__ __align__(16) unsigned char smem[DP_BLOCK * sizeof(DispPartial)];    // 64 KB: staging, then folds
     Staged* stage = reinterpret_cast<Staged*>(smem);
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
 // iteration (16-byte loads when VEC, i.e. all arrays 16-byte aligned).
 template <bool VEC>
 __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc1(TraceView tr, const disco_policy* __restrict__ pol,
-                                                            u64* __restrict__ part, unsigned* ticket, DispFin fin)
+                                                            u64* __restrict__ part, DispFin fin)
 {
     __shared__ __align__(16) unsigned char smem[DP_BLOCK * sizeof(DispPartial)];
     u64* sh = reinterpret_cast<u64*>(smem);
@@ -617,11 +617,11 @@ unsigned dispatch_blocks(i64 units, i64 per_block)
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 template <int G>
-void launch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, unsigned* ticket, const DispFin& fin,
+void launch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, const DispFin& fin,
                 hipStream_t stream)
 {
     const unsigned blocks = dispatch_blocks((v.n_req + 63) / 64, DP_WAVES);
-    hipLaunchKernelGGL(k_dispatch_acc<G>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, P, part, ticket, fin);
+    hipLaunchKernelGGL(k_dispatch_acc<G>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, P, part, fin);
     hipLaunchKernelGGL(k_dispatch_fin, dim3(1), dim3(512), 0, stream, part, P, fin);
 }
 
@@ -634,24 +634,24 @@ int pow2_cols(int P)
 
 }  // namespace
 
-void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, unsigned* ticket,
-                               const DispFin& fin, hipStream_t stream)
+void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, const DispFin& fin,
+                               hipStream_t stream)
 {
     switch (pow2_cols(P)) {
     case 1: {
         const unsigned blocks = dispatch_blocks((v.n_req + 3) / 4, DP_BLOCK);
         const bool vec = aligned16(v.l) && aligned16(v.n) && aligned16(v.s) && (!v.k || aligned16(v.k));
-        if (vec) hipLaunchKernelGGL(k_dispatch_acc1<true>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, part, ticket, fin);
-        else hipLaunchKernelGGL(k_dispatch_acc1<false>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, part, ticket, fin);
+        if (vec) hipLaunchKernelGGL(k_dispatch_acc1<true>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, part, fin);
+        else hipLaunchKernelGGL(k_dispatch_acc1<false>, dim3(blocks), dim3(DP_BLOCK), 0, stream, v, pol, part, fin);
         hipLaunchKernelGGL(k_dispatch_fin, dim3(1), dim3(512), 0, stream, part, 1, fin);
         break;
     }
-    case 2: launch_acc<2>(v, pol, P, part, ticket, fin, stream); break;
-    case 4: launch_acc<4>(v, pol, P, part, ticket, fin, stream); break;
-    case 8: launch_acc<8>(v, pol, P, part, ticket, fin, stream); break;
-    case 16: launch_acc<16>(v, pol, P, part, ticket, fin, stream); break;
-    case 32: launch_acc<32>(v, pol, P, part, ticket, fin, stream); break;
-    default: launch_acc<64>(v, pol, P, part, ticket, fin, stream); break;
+    case 2: launch_acc<2>(v, pol, P, part, fin, stream); break;
+    case 4: launch_acc<4>(v, pol, P, part, fin, stream); break;
+    case 8: launch_acc<8>(v, pol, P, part, fin, stream); break;
+    case 16: launch_acc<16>(v, pol, P, part, fin, stream); break;
+    case 32: launch_acc<32>(v, pol, P, part, fin, stream); break;
+    default: launch_acc<64>(v, pol, P, part, fin, stream); break;
     }
 }
 

@@ -24,50 +24,17 @@ __host__ __device__ inline MigPartial* tl_totals(u64* totals)
     return reinterpret_cast<MigPartial*>(totals + DISCO_NCOPY * 64 * 8);
 }
 
-// Staging of the policy table (wave 0); all 1024 threads also put the tickets and the per-column totals that
-// the workgroups of a pass add into at their identity: the dispatch totals (8 words per column and copy,
-// word-major; word 7 = {min bits, max bits}) and, behind them, the timeline totals (all zero).
-constexpr int STAGE_THREADS = 1024;
-__device__ inline void reset_totals(u64* totals)
-{
-    constexpr int DISP_WORDS = 8 * DISCO_NCOPY * 64, TL_WORDS = DISCO_NCOPY * 64 * (int)(sizeof(MigPartial) / 8);
-    for (int w = threadIdx.x; w < DISP_WORDS + TL_WORDS; w += STAGE_THREADS)
-        totals[w] = (w >= 7 * DISCO_NCOPY * 64 && w < DISP_WORDS) ? 0x00000000FFFFFFFFull : 0ull;
-}
+// Start of a selection (all threads of one workgroup): one thread per slot: rank from (num, den, M), empty
+// prefix; plan of the passes.
+struct SelInit { SelState* S; int nq; disco_quantile q[4]; const disco_accum* acc; i64 n_req; };
 
-__global__ __launch_bounds__(STAGE_THREADS) void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets, u64* totals)
+__device__ void select_init(const SelInit& si, int which, int P, const disco_policy* pol)
 {
-    const int i = threadIdx.x;
-    if (i < 64) {
-        if (i < P) dst[i] = t.p[i];
-        const bool any_buffer = __ballot(i < P && t.p[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
-        tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
-    }
-    reset_totals(totals);
-}
-
-__global__ __launch_bounds__(STAGE_THREADS) void k_copy_policies(const disco_policy* src, int P, disco_policy* dst, unsigned* tickets, u64* totals)
-{
-    const int i = threadIdx.x;
-    if (i < 64) {
-        if (i < P) dst[i] = src[i];
-        const bool any_buffer = __ballot(i < P && src[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
-        tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
-    }
-    reset_totals(totals);
-}
-
-// ----------------------------------------------------------------- select --
-// TTFT: key = bits - min_bits over nb = bit length of (max_bits - min_bits)
-// bits, 8 bits per pass (up to 128 (column, quantile) slots of 256 bins in
-// LDS).  TBT: the plan comes from the host (raw 31-bit keys).
-
-// One thread per slot: rank from (num, den, M), empty prefix; plan of the passes.
-__global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quantile q0, disco_quantile q1,
-                              disco_quantile q2, disco_quantile q3, const disco_accum* acc, i64 n_req,
-                              const disco_policy* pol)
-{
-    const disco_quantile qs[4] = {q0, q1, q2, q3};
+    SelState* S = si.S;
+    const int nq = si.nq;
+    const disco_accum* acc = si.acc;
+    const i64 n_req = si.n_req;
+    const disco_quantile qs[4] = {si.q[0], si.q[1], si.q[2], si.q[3]};
     __shared__ unsigned smin, smax;
     __shared__ int all_thresholds;
     if (threadIdx.x == 0) { smin = 0xFFFFFFFFu; smax = 0u; all_thresholds = 1; }
@@ -143,6 +110,58 @@ __global__ void k_select_init(SelState* S, int which, int P, int nq, disco_quant
         S->slot[which][s] = sl;
     }
 }
+
+__global__ void k_select_init(SelInit si, int which, int P, const disco_policy* pol) { select_init(si, which, P, pol); }
+
+// Staging of the policy table (wave 0); all 1024 threads also put the tickets and the per-column totals that
+// the workgroups of a pass add into at their identity: the dispatch totals (8 words per column and copy,
+// word-major; word 7 = {min bits, max bits}) and, behind them, the timeline totals (all zero).
+constexpr int STAGE_THREADS = 1024;
+__device__ inline void reset_totals(u64* totals)
+{
+    constexpr int DISP_WORDS = 8 * DISCO_NCOPY * 64, TL_WORDS = DISCO_NCOPY * 64 * (int)(sizeof(MigPartial) / 8);
+    for (int w = threadIdx.x; w < DISP_WORDS + TL_WORDS; w += STAGE_THREADS)
+        totals[w] = (w >= 7 * DISCO_NCOPY * 64 && w < DISP_WORDS) ? 0x00000000FFFFFFFFull : 0ull;
+}
+
+// With a selection state (si.S), the TTFT selection of the statistics is started in the same launch.
+__global__ __launch_bounds__(STAGE_THREADS) void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets, u64* totals,
+                                                                  SelInit si)
+{
+    const int i = threadIdx.x;
+    if (i < 64) {
+        if (i < P) dst[i] = t.p[i];
+        const bool any_buffer = __ballot(i < P && t.p[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
+        tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
+    }
+    reset_totals(totals);
+    if (si.S) {
+        __syncthreads();                       // the staged table is read back by this workgroup
+        select_init(si, 0, P, dst);
+    }
+}
+
+__global__ __launch_bounds__(STAGE_THREADS) void k_copy_policies(const disco_policy* src, int P, disco_policy* dst, unsigned* tickets, u64* totals,
+                                                                 SelInit si)
+{
+    const int i = threadIdx.x;
+    if (i < 64) {
+        if (i < P) dst[i] = src[i];
+        const bool any_buffer = __ballot(i < P && src[i < P ? i : 0].mig_mode == DISCO_MIG_BUFFER) != 0ull;
+        tickets[i] = (i == DISCO_FLAG_BUFFER && any_buffer) ? 1u : 0u;
+    }
+    reset_totals(totals);
+    if (si.S) {
+        __syncthreads();                       // the staged table is read back by this workgroup
+        select_init(si, 0, P, dst);
+    }
+}
+
+// ----------------------------------------------------------------- select --
+// TTFT: key = bits - min_bits over nb = bit length of (max_bits - min_bits)
+// bits, 8 bits per pass (up to 128 (column, quantile) slots of 256 bins in
+// LDS).  TBT: the plan comes from the host (raw 31-bit keys).
+
 
 // ------------------------------------------------------------ final stats --
 
@@ -353,13 +372,16 @@ bool is_device_pointer(const void* p)
 
 // Host tables are validated and travel as a kernel argument; device tables
 // (e.g. the pol_out of a budget search) are copied on the device, unvalidated.
-int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, hipStream_t stream)
+int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, hipStream_t stream, const SelInit* sel = nullptr)
 {
+    SelInit si;
+    memset(&si, 0, sizeof(si));
+    if (sel) si = *sel;
     if (!pol) return DISCO_ERR_NULL;
     if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;
     if (is_device_pointer(pol)) {
         hipLaunchKernelGGL(k_copy_policies, dim3(1), dim3(STAGE_THREADS), 0, stream, pol, P, (disco_policy*)(ws + L.pol),
-                           (unsigned*)(ws + L.ticket), (u64*)(ws + L.part));
+                           (unsigned*)(ws + L.ticket), (u64*)(ws + L.part), si);
         return DISCO_OK;
     }
     int rc = check_policies(pol, P);
@@ -368,7 +390,7 @@ int stage_policies(const disco_policy* pol, int P, char* ws, const WsLayout& L, 
     memset(&t, 0, sizeof(t));
     memcpy(t.p, pol, sizeof(disco_policy) * (size_t)P);
     hipLaunchKernelGGL(k_store_policies, dim3(1), dim3(STAGE_THREADS), 0, stream, t, P, (disco_policy*)(ws + L.pol),
-                       (unsigned*)(ws + L.ticket), (u64*)(ws + L.part));
+                       (unsigned*)(ws + L.ticket), (u64*)(ws + L.part), si);
     return DISCO_OK;
 }
 
@@ -444,8 +466,7 @@ extern "C" int32_t disco_eval_dispatch(const disco_trace* trace, const disco_pol
     fin.kind = 0;
     fin.need = 2;
     fin.acc = acc;
-    disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), P, (u64*)(ws + L.part),
-                              (unsigned*)(ws + L.ticket), fin, stream);
+    disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), P, (u64*)(ws + L.part), fin, stream);
     if (out && (out->decision || out->ttft) && v.n_req > 0)
         disco_launch_dispatch_mat(v, (const disco_policy*)(ws + L.pol), P, out->decision, out->ttft, stream);
     DISCO_HIP(hipGetLastError());
@@ -524,20 +545,21 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     const TraceView v = view_of(trace);
     SelState* S = (SelState*)(ws + L.sel);
     unsigned* gh = (unsigned*)(ws + L.ghist);
-    rc = stage_policies(pol, P, ws, L, stream);
-    if (rc) return rc;
     disco_quantile qs[4] = {{0, 1}, {0, 1}, {0, 1}, {0, 1}};
     for (int i = 0; i < nq; ++i) qs[i] = q[i];
+    SelInit si;
+    memset(&si, 0, sizeof(si));
+    si.S = S; si.nq = nq; si.acc = acc; si.n_req = v.n_req;
+    for (int i = 0; i < 4; ++i) si.q[i] = qs[i];
+    rc = stage_policies(pol, P, ws, L, stream, nq > 0 ? &si : nullptr);        // with the start of the TTFT selection
+    if (rc) return rc;
     if (nq > 0) {
-        hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 0, P, nq, qs[0], qs[1], qs[2], qs[3], acc,
-                           v.n_req, (const disco_policy*)(ws + L.pol));
         unsigned char* ubytes = ws_bytes >= L.total + (size_t)v.n_req ? (unsigned char*)(ws + L.total) : nullptr;
         for (int pass = 0; pass < 4; ++pass)
             disco_launch_ttft_pass(v, (const disco_policy*)(ws + L.pol), P, nq, pass, S, (unsigned*)(ws + L.slices), gh,
                                    ubytes, stream);
         if (tl) {
-            hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, S, 1, P, nq, qs[0], qs[1], qs[2], qs[3],
-                               acc, v.n_req, (const disco_policy*)(ws + L.pol));
+            hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, si, 1, P, (const disco_policy*)(ws + L.pol));
             TimelineArgs a;
             memset(&a, 0, sizeof(a));
             a.tau = tl->tau;
@@ -711,8 +733,7 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
         if (spec[j].which_acc != DISCO_ACC_SERVER_PREFILL_TOK && spec[j].which_acc != DISCO_ACC_DEVICE_PREFILL_TOK) need = 1;
     for (int step = first_step; step <= n_steps; ++step) {
         fin.need = step < n_steps ? need : 2;
-        disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search, (u64*)(ws + L.part),
-                                  (unsigned*)(ws + L.ticket), fin, stream);
+        disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search, (u64*)(ws + L.part), fin, stream);
     }
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;

@@ -31,8 +31,8 @@ struct DispFin {
     disco_policy* pol_rw;         // the table the next pass reads
 };
 
-void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, unsigned* ticket,
-                               const DispFin& fin, hipStream_t stream);
+void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, const DispFin& fin,
+                               hipStream_t stream);
 // Threshold search of server-constrained columns from a table of prompt-token sums by length.
 void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsigned* scratch, size_t scratch_bytes,
                                u64* table, u64* other, SearchState* st, disco_policy* pol, disco_search_out* sout,
