@@ -1,18 +1,19 @@
 // Dispatch passes (Sec. 4.2, Alg. 2 and 3): fused dispatch + per-column
-// reduction, TTFT histogram passes of the order-statistic selection, and the
+// reduction, the tabulated threshold search of Alg. 3 columns, and the
 // materialised per-pair outputs.
 //
 // Work decomposition: a wave holds up to 64 policy columns in its lanes
 // (lane = sub * G + column, G = columns rounded up to a power of two, 64 / G
 // request sub-groups) and walks the requests in batches of 64.  A batch is
-// loaded coalesced, one request per lane, staged in LDS as (l, s, n, d), and
-// every column lane reads the request of its sub-group with one broadcast
-// 16-byte LDS load.  With a single column (G = 1) lane = request and four
-// consecutive requests are fetched per lane with 16-byte loads.  Per-column
-// totals stay in registers (32-bit inside a batch, 64-bit across batches)
-// until the end of the kernel; the workgroup that takes the last ticket folds
-// the per-workgroup partials in a fixed order and, for a budget search,
-// advances the bisection on the device.
+// loaded coalesced, one request per lane and one batch ahead, staged in LDS,
+// and every column lane reads the request of its sub-group with broadcast LDS
+// loads.  With a single column (G = 1) lane = request and four consecutive
+// requests are fetched per lane with 16-byte loads.  Per-column totals stay
+// in registers (32-bit inside a batch, 64-bit across batches) until the end
+// of the kernel, are folded over the workgroup and added into a few copies
+// of the device-wide totals; a one-workgroup kernel behind the pass
+// (k_dispatch_fin) folds the copies in a fixed order and, for a budget
+// search, advances the bisection on the device.
 #include <math.h>
 #include <string.h>
 

@@ -15,18 +15,25 @@
 //     (request, column) pair.
 //       pass 0: rows (device, ub) and (race, ub); column p's histogram is the
 //         sum of the device rows ub <= p and the race rows ub > p.
-//       later passes: one row per (column, quantile) slot; a value goes to the
+//       second pass: the live (column, quantile) slots are grouped by their
+//         first digit.  If all values that carry one of these digits fit the
+//         candidate list, they are sorted into one bucket per digit (4-byte
+//         entries: the undecided key bits and the column range of the value)
+//         and every slot finishes its remaining digits from its bucket
+//         (k_ttft_select, one workgroup per slot): no further pass over the
+//         requests.
+//       otherwise, histogram passes: one row per slot; a value goes to the
 //         slots of its column range whose prefix equals the value's upper bits
-//         (looked up in the sorted list of distinct prefixes).
+//         (LDS hash of the distinct prefixes, 128-bit slot sets).
 //   pair kernel -- any table: lane = column, every (request, column) pair is
 //     evaluated and bumps the rows of its column.
 //
-// After two passes few values still match a slot's prefix (the second select
-// adds up an upper bound): the third pass then collects them in a list --
-// key and which columns the value belongs to -- and every slot finishes its
-// remaining digits from that list (k_ttft_select, one workgroup per slot),
-// instead of two more passes over the requests.  If the bound is too large
-// (heavy ties) the histogram passes simply go on.
+// Without buckets, few values still match a slot's prefix after two passes
+// (the second select adds up an upper bound): the third pass then collects
+// them in a list -- key and which columns the value belongs to -- and every
+// slot finishes its remaining digits from that list, instead of two more
+// passes over the requests.  If that bound is too large as well (heavy ties)
+// the histogram passes simply go on.
 //
 // A workgroup stores its LDS bins as one slice; k_ttft_reduce adds the slices
 // (merging them with device-wide atomics would serialise on the few hundred
