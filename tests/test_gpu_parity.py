@@ -196,11 +196,11 @@ def test_migration_generated_tokens(B, oracle):
 
 # -------------------------------------------------------------- statistics
 
-def check_stats(B, O, tr, specs, cost, tau=None, kappa=3.0, quantiles=((50, 100), (99, 100))):
+def check_stats(B, O, tr, specs, cost, tau=None, kappa=3.0, quantiles=((50, 100), (99, 100)), ws_requests=None):
     bp, op = both(B, O, specs)
     P = len(specs)
     dt = B.upload_trace(tr)
-    ws = B.workspace(tr["n_req"], P)
+    ws = B.workspace(tr["n_req"] if ws_requests is None else ws_requests, P)
     r = B.disco_eval_dispatch(dt, bp, ws=ws)
     if tau is not None:
         B.disco_eval_migration(dt, tau, kappa, bp, ws=ws, acc=r["acc"], cost=cost)
@@ -502,3 +502,21 @@ def test_stats_threshold_table_too_large_for_buckets(B, oracle, kind):
     specs = [dict(mode=0, l_th=int(t)) for t in np.linspace(0, 400, 8)]
     got, want = check_stats(B, oracle, tr, specs, DI.COST_S)
     assert sum(1 for w in want if 0.5 <= float(w["ttft_q"][0]) < 0.53) >= 6
+
+
+def test_stats_threshold_table_smallest_workspace(B, oracle):
+    """A workspace without the byte per request: the later passes of the selection by classes look the first racing
+    column of a request up again instead of reading it back."""
+    print("stats parity threshold table, workspace for zero requests", flush=True)
+    tr = DI.handmade_trace(71, 50_000, tokens=False)
+    specs = [dict(mode=0, l_th=int(t)) for t in np.linspace(0, 3100, 24)]
+    check_stats(B, oracle, tr, specs, DI.COST_S, ws_requests=0, quantiles=((50, 100), (99, 100), (999, 1000)))
+
+
+def test_stats_threshold_table_buckets_in_two_rounds(B, oracle):
+    """1.5 M requests: a workgroup of the scatter pass takes its requests in two rounds, each with its own share
+    of the buckets."""
+    print("stats parity threshold table, 1.5 M requests", flush=True)
+    tr = DI.handmade_trace(73, 1_500_000, tokens=False)
+    specs = [dict(mode=0, l_th=int(t)) for t in np.linspace(0, 3100, 8)]
+    check_stats(B, oracle, tr, specs, DI.COST_S)
