@@ -34,6 +34,7 @@ struct WsLayout {
     size_t part;       // device-wide totals (dispatch, then timeline), per-workgroup partials of the general timeline kernel
     size_t ppcnt;      // unsigned[DISCO_MAX_CLS][DISCO_PP_NMAX + 1]: pure-pacing timelines per class and length
     size_t dhist;      // unsigned[DISCO_MAX_COLS][DISCO_DELAY_BINS]: migrated requests by number of delayed tokens
+    size_t templ;      // disco_policy[64]: templates of a budget search (its candidate columns are in `pol`)
     size_t slices;     // per-workgroup histogram slices (TTFT passes, prompt-length table): 32 MB
     size_t total;
 };

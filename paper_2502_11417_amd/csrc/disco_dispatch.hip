@@ -57,48 +57,74 @@ __device__ __forceinline__ double acc_value(int which, const disco_cost_params& 
 // feasible end of the bracket).
 __device__ __forceinline__ void search_step(SearchState& st, disco_policy& p, double A, disco_search_out* o)
 {
-    const bool is_w = st.which_param == DISCO_PARAM_W_TAIL;
-    const double mid = is_w ? (double)p.w_tail : (double)p.l_th;
+    const bool is_w = search_on_wait(st);
+    const double mid = search_param(is_w, p);
     o->hist_param[st.step] = mid;
     o->hist_acc[st.step] = A;
-    if (is_w) {
-        if (A > st.target) st.lo = mid; else st.hi = mid;
-    } else if (st.lo < st.hi) {
-        if (A > st.target) st.lo = mid + 1.0; else st.hi = mid;
-    }
+    search_halve(is_w, st.lo, st.hi, mid, A > st.target);
     st.step += 1;
-    if (is_w) {
-        p.w_tail = (st.step < st.n_steps) ? 0.5f * ((float)st.lo + (float)st.hi) : (float)st.hi;
-    } else {
-        const int lo = (int)st.lo, hi = (int)st.hi;
-        p.l_th = (st.step < st.n_steps) ? lo + (hi - lo) / 2 : hi;
+    if (st.step < st.n_steps) search_set_mid(is_w, st.lo, st.hi, p);
+    else search_set_answer(is_w, st.hi, p);
+}
+
+// Final evaluation of search `col` (Sec. 4.2: the threshold / wait that meets the constrained endpoint's
+// budget), at the answer of its bisection.
+__device__ void search_finish(int col, const DispFin& fin, const disco_accum& tot)
+{
+    const SearchState st = fin.st[col];
+    const disco_policy p = fin.pol_rw[col];
+    const double A = acc_value(st.which_acc, fin.cost, tot.s_pre, tot.s_dec, tot.d_pre, tot.d_dec);
+    disco_search_out* o = &fin.sout[col];
+    o->param = st.hi;
+    o->acc_at_param = A;
+    o->lo = st.lo;
+    o->hi = st.hi;
+    o->at_param = tot;
+    if (fin.pol_out) fin.pol_out[col] = p;
+    if (fin.acc) {                                  // the evaluation at the answer, as disco_eval_dispatch would leave it
+        disco_accum* a = &fin.acc[col];
+        a->s_pre = tot.s_pre; a->s_dec = tot.s_dec; a->d_pre = tot.d_pre; a->d_dec = tot.d_dec;
+        a->n_dev_started = tot.n_dev_started; a->n_dev_win = tot.n_dev_win; a->ttft_sum = tot.ttft_sum;
+        a->ttft_min_bits = tot.ttft_min_bits; a->ttft_max_bits = tot.ttft_max_bits;
     }
 }
 
-// Bisection step or final evaluation of search `col` (Sec. 4.2: find the
-// threshold / wait that meets the constrained endpoint's budget).
-__device__ void search_advance(int col, const DispFin& fin, const disco_accum& tot)
+// A bisection pass has evaluated the next `depth` levels of search j's bisection tree (columns j * M + node - 1
+// in heap order, M = 2^depth - 1; folded totals in LDS, word f of column c at sh[f * 64 + c]): walk down the
+// tree, one recorded step per level, then write the candidates of the next pass (or, after the last bisection
+// pass, the answers).  Called by all threads of the workgroup.
+__device__ void search_walk(const DispFin& fin, const u64* sh)
 {
-    SearchState st = fin.st[col];
-    disco_policy p = fin.pol_rw[col];
-    const double A = acc_value(st.which_acc, fin.cost, tot.s_pre, tot.s_dec, tot.d_pre, tot.d_dec);
-    if (st.step < st.n_steps) {
-        search_step(st, p, A, &fin.sout[col]);
-        fin.st[col] = st;
-        fin.pol_rw[col] = p;
-    } else {
-        disco_search_out* o = &fin.sout[col];
-        o->param = st.hi;
-        o->acc_at_param = A;
-        o->lo = st.lo;
-        o->hi = st.hi;
-        o->at_param = tot;
-        if (fin.pol_out) fin.pol_out[col] = p;
-        if (fin.acc) {                                  // the evaluation at the answer, as disco_eval_dispatch would leave it
-            disco_accum* a = &fin.acc[col];
-            a->s_pre = tot.s_pre; a->s_dec = tot.s_dec; a->d_pre = tot.d_pre; a->d_dec = tot.d_dec;
-            a->n_dev_started = tot.n_dev_started; a->n_dev_win = tot.n_dev_win; a->ttft_sum = tot.ttft_sum;
-            a->ttft_min_bits = tot.ttft_min_bits; a->ttft_max_bits = tot.ttft_max_bits;
+    const int j = threadIdx.x, M = (1 << fin.depth) - 1;
+    SearchState st;
+    if (j < fin.n_search) {
+        st = fin.st[j];
+        const bool is_w = search_on_wait(st);
+        disco_search_out* o = &fin.sout[j];
+        int node = 1;
+        for (int d = 0; d < fin.depth && st.step < st.n_steps; ++d) {
+            const int c = j * M + node - 1;
+            const u64 s_pre = sh[0 * 64 + c], d_pre = sh[1 * 64 + c], d_dec = sh[2 * 64 + c], n_tot = sh[3 * 64 + c];
+            const double A = acc_value(st.which_acc, fin.cost, (i64)s_pre, (i64)(n_tot - d_dec), (i64)d_pre, (i64)d_dec);
+            const double mid = search_param(is_w, fin.pol_rw[c]);
+            o->hist_param[st.step] = mid;
+            o->hist_acc[st.step] = A;
+            const bool above = A > st.target;
+            search_halve(is_w, st.lo, st.hi, mid, above);
+            st.step += 1;
+            node = 2 * node + (above ? 1 : 0);
+        }
+        fin.st[j] = st;
+    }
+    __syncthreads();                                // every search has read the parameters of its candidates
+    if (j < fin.n_search) {
+        const disco_policy templ = fin.templ[j];
+        if (fin.last) {
+            disco_policy p = templ;
+            search_set_answer(search_on_wait(st), st.hi, p);
+            fin.pol_rw[j] = p;
+        } else {
+            search_write_candidates(st, templ, &fin.pol_rw[j * M], fin.depth);
         }
     }
 }
@@ -161,6 +187,10 @@ __device__ __forceinline__ void finish_columns(u64* tot, int P, const DispFin& f
         sh[f * 64 + c] = x;
     }
     __syncthreads();
+    if (fin.kind == 1 && fin.depth > 0) {
+        search_walk(fin, sh);
+        return;
+    }
     if ((int)threadIdx.x < P) {
         const int c = threadIdx.x;
         const u64 n_tot = sh[3 * 64 + c], d_dec = sh[2 * 64 + c];
@@ -177,7 +207,7 @@ __device__ __forceinline__ void finish_columns(u64* tot, int P, const DispFin& f
             o->n_dev_started = acc.n_dev_started; o->n_dev_win = acc.n_dev_win; o->ttft_sum = acc.ttft_sum;
             o->ttft_min_bits = acc.ttft_min_bits; o->ttft_max_bits = acc.ttft_max_bits;
         } else {
-            search_advance(c, fin, acc);
+            search_finish(c, fin, acc);
         }
     }
 }

@@ -278,23 +278,31 @@ __global__ __launch_bounds__(256) void k_delay_quantiles(int nq, disco_quantile 
 
 // ----------------------------------------------------------- search setup --
 
-__global__ void k_search_init(SpecTable t, int n, SearchState* st, disco_policy* pol)
+// Brackets of the searches; `pol` holds their templates on entry.  depth > 0: the templates move to `templ`
+// and `pol` gets the candidate columns of the first bisection pass (2^depth - 1 per search); depth 0 (tabulated
+// threshold search): `pol` keeps one record per search with the first midpoint.
+__global__ void k_search_init(SpecTable t, int n, SearchState* st, disco_policy* pol, disco_policy* templ, int depth)
 {
     const int c = threadIdx.x;
-    if (c >= n) return;
-    SearchState s = t.s[c];
-    disco_policy p = pol[c];
-    if (s.which_param == DISCO_PARAM_W_TAIL) {
-        s.lo = (double)(float)s.lo; s.hi = (double)(float)s.hi;
-        p.w_tail = 0.5f * ((float)s.lo + (float)s.hi);
-    } else {
-        int lo = (int)s.lo, hi = (int)s.hi;
-        s.lo = lo; s.hi = hi;
-        p.l_th = lo + (hi - lo) / 2;
+    SearchState s;
+    disco_policy p;
+    if (c < n) {
+        s = t.s[c];
+        p = pol[c];
+        if (search_on_wait(s)) { s.lo = (double)(float)s.lo; s.hi = (double)(float)s.hi; }
+        else { s.lo = (int)s.lo; s.hi = (int)s.hi; }
+        s.step = 0;
+        st[c] = s;
     }
-    s.step = 0;
-    st[c] = s;
-    pol[c] = p;
+    __syncthreads();                        // all templates have been read
+    if (c >= n) return;
+    if (depth > 0) {
+        templ[c] = p;
+        search_write_candidates(s, p, &pol[c * ((1 << depth) - 1)], depth);
+    } else {
+        search_set_mid(search_on_wait(s), s.lo, s.hi, p);
+        pol[c] = p;
+    }
 }
 
 // ------------------------------------------------------------- host side --
@@ -416,6 +424,7 @@ WsLayout disco_ws_layout(int32_t P)
     o += up((size_t)DISCO_MAX_BLOCKS * 64 * 64);     // workgroups x columns x 64-byte partial
     L.ppcnt = o; o += up(sizeof(unsigned) * DISCO_MAX_CLS * (DISCO_PP_NMAX + 1));
     L.dhist = o; o += up(sizeof(unsigned) * DISCO_MAX_COLS * DISCO_DELAY_BINS);
+    L.templ = o; o += up(sizeof(disco_policy) * DISCO_MAX_COLS);
     L.slices = o; o += up((size_t)256 * (2 * DISCO_MAX_COLS + 2) * 256 * sizeof(unsigned));   // 256 workgroups x rows x bins
     L.total = o;
     return L;
@@ -698,17 +707,6 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
     const TraceView v = view_of(trace);
     rc = stage_policies(templ, n_search, ws, L, stream);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_search_init, dim3(1), dim3(64), 0, stream, t, n_search, (SearchState*)(ws + L.search),
-                       (disco_policy*)(ws + L.pol));
-    DispFin fin;
-    memset(&fin, 0, sizeof(fin));
-    fin.kind = 1;
-    fin.cost = *cost;
-    fin.st = (SearchState*)(ws + L.search);
-    fin.sout = out;
-    fin.pol_out = pol_out;
-    fin.acc = acc_out;
-    fin.pol_rw = (disco_policy*)(ws + L.pol);
     // Length thresholds of server-constrained columns against a prompt-token budget: the accumulator is a
     // function of the threshold alone and is tabulated once (Alg. 3's sorted running totals); all bisection
     // steps then read the table.  Needs a host-resident template table (its modes are inspected here).
@@ -720,21 +718,43 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
                     spec[j].lo >= 0.0 && spec[j].hi + 2.0 <= (double)disco_search_table_max_bins();
         if (spec[j].hi > max_hi) max_hi = spec[j].hi;
     }
-    int first_step = 0;
+    // Otherwise every pass evaluates the next `depth` levels of each search's bisection tree as columns of their
+    // own and so takes `depth` bisection steps; the recorded steps are those of the plain bisection.
+    const int depth = tabulated ? 0 : disco_search_depth(n_search);
+    hipLaunchKernelGGL(k_search_init, dim3(1), dim3(64), 0, stream, t, n_search, (SearchState*)(ws + L.search),
+                       (disco_policy*)(ws + L.pol), (disco_policy*)(ws + L.templ), depth);
+    DispFin fin;
+    memset(&fin, 0, sizeof(fin));
+    fin.kind = 1;
+    fin.cost = *cost;
+    fin.st = (SearchState*)(ws + L.search);
+    fin.sout = out;
+    fin.pol_out = pol_out;
+    fin.acc = acc_out;
+    fin.pol_rw = (disco_policy*)(ws + L.pol);
+    fin.templ = (const disco_policy*)(ws + L.templ);
+    fin.n_search = n_search;
     if (tabulated) {
         disco_launch_search_table(v, n_search, (int)max_hi + 2, (unsigned*)(ws + L.slices), L.total - L.slices,
                                   (u64*)(ws + L.ppcnt), (u64*)((unsigned*)(ws + L.ticket) + 32),
                                   (SearchState*)(ws + L.search), (disco_policy*)(ws + L.pol), out, stream);
-        first_step = n_steps;
+    } else {
+        // bisection passes only need the totals their accumulators are made of
+        int need = 0;
+        for (int j = 0; j < n_search; ++j)
+            if (spec[j].which_acc != DISCO_ACC_SERVER_PREFILL_TOK && spec[j].which_acc != DISCO_ACC_DEVICE_PREFILL_TOK) need = 1;
+        const int npass = (n_steps + depth - 1) / depth;
+        fin.depth = depth;
+        fin.need = need;
+        for (int pass = 0; pass < npass; ++pass) {
+            fin.last = pass == npass - 1;
+            disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search * ((1 << depth) - 1), (u64*)(ws + L.part),
+                                      fin, stream);
+        }
     }
-    // bisection steps only need the totals their accumulators are made of; the last pass evaluates everything
-    int need = 0;
-    for (int j = 0; j < n_search; ++j)
-        if (spec[j].which_acc != DISCO_ACC_SERVER_PREFILL_TOK && spec[j].which_acc != DISCO_ACC_DEVICE_PREFILL_TOK) need = 1;
-    for (int step = first_step; step <= n_steps; ++step) {
-        fin.need = step < n_steps ? need : 2;
-        disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search, (u64*)(ws + L.part), fin, stream);
-    }
+    // the evaluation at the answers
+    fin.depth = 0; fin.last = 0; fin.need = 2;
+    disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), n_search, (u64*)(ws + L.part), fin, stream);
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }

@@ -29,7 +29,16 @@ struct DispFin {
     disco_search_out* sout;
     disco_policy* pol_out;
     disco_policy* pol_rw;         // the table the next pass reads
+    // Bisection passes of a search evaluate a whole subtree of the bisection at once: search j owns the
+    // 2^depth - 1 columns j * (2^depth - 1) ..., one per node of the next `depth` levels (heap order), so one pass
+    // takes `depth` bisection steps; depth 0: the columns are the searches themselves (final evaluation).
+    int n_search, depth;
+    int last;                     // the last bisection pass: leave the answers' policies in pol_rw[0 .. n_search)
+    const disco_policy* templ;    // the searches' template records
 };
+
+// Levels of the bisection tree one pass can evaluate for n searches (64 columns per pass).
+inline int disco_search_depth(int n) { return n <= 9 ? 3 : (n <= 21 ? 2 : 1); }
 
 void disco_launch_dispatch_acc(const TraceView& v, const disco_policy* pol, int P, u64* part, const DispFin& fin,
                                hipStream_t stream);

@@ -12,6 +12,50 @@ struct SearchState {
 };
 struct SpecTable { SearchState s[DISCO_MAX_COLS]; };
 
+// Bisection of a budget search (Sec. 4.2: the threshold or wait that meets the constrained endpoint's budget) on
+// the bracket [lo, hi] of its state: the parameter evaluated for a bracket is its midpoint, the answer once the
+// steps are used up its feasible end hi.
+__device__ __forceinline__ bool search_on_wait(const SearchState& st) { return st.which_param == DISCO_PARAM_W_TAIL; }
+__device__ __forceinline__ void search_set_mid(bool is_w, double lo, double hi, disco_policy& p)
+{
+    if (is_w) p.w_tail = 0.5f * ((float)lo + (float)hi);
+    else { const int l = (int)lo, h = (int)hi; p.l_th = l + (h - l) / 2; }
+}
+__device__ __forceinline__ void search_set_answer(bool is_w, double hi, disco_policy& p)
+{
+    if (is_w) p.w_tail = (float)hi; else p.l_th = (int)hi;
+}
+__device__ __forceinline__ double search_param(bool is_w, const disco_policy& p) { return is_w ? (double)p.w_tail : (double)p.l_th; }
+// above: the accumulator at `mid` exceeds the target
+__device__ __forceinline__ void search_halve(bool is_w, double& lo, double& hi, double mid, bool above)
+{
+    if (is_w) { if (above) lo = mid; else hi = mid; }
+    else if (lo < hi) { if (above) lo = mid + 1.0; else hi = mid; }
+}
+// The parameters of the next `depth` (<= 3) levels of the bisection below the bracket of `st`, as policy records
+// in heap order (node 1 = the midpoint of the bracket, node 2n = after "not above" at node n, 2n + 1 = after
+// "above"): dst[0 .. 2^depth - 1).  A search whose steps are used up gets copies of its answer.
+__device__ inline void search_write_candidates(const SearchState& st, const disco_policy& templ, disco_policy* dst, int depth)
+{
+    const bool is_w = search_on_wait(st);
+    const int M = (1 << depth) - 1;
+    double lo[8], hi[8];
+    lo[1] = st.lo; hi[1] = st.hi;
+    for (int node = 1; node <= M; ++node) {
+        disco_policy p = templ;
+        if (st.step >= st.n_steps) search_set_answer(is_w, st.hi, p);
+        else search_set_mid(is_w, lo[node], hi[node], p);
+        dst[node - 1] = p;
+        if (2 * node + 1 <= M) {
+            const double mid = search_param(is_w, p);
+            lo[2 * node] = lo[node]; hi[2 * node] = hi[node];
+            search_halve(is_w, lo[2 * node], hi[2 * node], mid, false);
+            lo[2 * node + 1] = lo[node]; hi[2 * node + 1] = hi[node];
+            search_halve(is_w, lo[2 * node + 1], hi[2 * node + 1], mid, true);
+        }
+    }
+}
+
 // Order-statistic selection: most-significant-digit-first radix histograms
 // over key = bits(value) - minb (non-negative floats order like their bit
 // patterns).  Pass p looks at `width[p]` bits at `shift[p]`.
