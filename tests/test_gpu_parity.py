@@ -520,3 +520,28 @@ def test_stats_threshold_table_buckets_in_two_rounds(B, oracle):
     tr = DI.handmade_trace(73, 1_500_000, tokens=False)
     specs = [dict(mode=0, l_th=int(t)) for t in np.linspace(0, 3100, 8)]
     check_stats(B, oracle, tr, specs, DI.COST_S)
+
+
+@pytest.mark.parametrize("n_search,n_steps", [(9, 7), (10, 5), (21, 32), (22, 3), (64, 4)])
+def test_wait_searches_side_by_side(B, oracle, n_search, n_steps):
+    """Many wait-time searches in one call: the number of searches decides how many levels of the bisection a pass
+    evaluates (three for up to 9 searches, two for up to 21, else one) and the steps need not fill the last pass;
+    the recorded history is that of the plain bisection for every one of them."""
+    print(f"search parity {n_search} searches x {n_steps} steps", flush=True)
+    tr = DI.handmade_trace(79, 20_011, tokens=False)
+    dt = B.upload_trace(tr)
+    total = int(tr["prompt_len"].astype(np.int64).sum())
+    targets = [total * (j + 1) / (n_search + 2) for j in range(n_search)]
+    templ = [B.Policy(mode=1, l_th=(j % 5) * 100 - 1) for j in range(n_search)]
+    specs = [dict(which_param=B.PARAM_W_TAIL, which_acc="device_prefill_tok", n_steps=n_steps, lo=0.0, hi=4.0, target=t)
+             for t in targets]
+    res = B.disco_budget_search(dt, DI.COST_D, templ, specs)
+    so = B.search_to_host(res["out"], n_search)
+    pol = B.policies_to_host(res["pol_out"], n_search)
+    for j in range(n_search):
+        op = oracle.Policy(mode=1, l_th=(j % 5) * 100 - 1)
+        w, hp, ha = oracle.search_wait(tr, op, 0.0, 4.0, n_steps, "device_prefill_tok", DI.COST_D, targets[j])
+        assert np.float32(so["param"][j]) == w == np.float32(pol[j].w_tail), (j, so["param"][j], w)
+        assert (so["hist_param"][j][:n_steps].astype(np.float32) == hp).all(), j
+        assert (so["hist_acc"][j][:n_steps] == ha).all(), j
+        assert pol[j].l_th == (j % 5) * 100 - 1
