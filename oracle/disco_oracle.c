@@ -699,6 +699,30 @@ float orc_search_wait(int64_t N, const int32_t* prompt_len, const float* srv_ttf
     return hi;
 }
 
+/* Bisection on the slope beta of the ramp w(l) = min(beta l, w_tail) of Eq. 1 for the prompts above l_th, so that
+ * an accumulator that does not increase with the slope meets `target`: Eq. 2 asks for the beta at which the device
+ * prefill of those prompts uses up what is left of the budget.  Here the left-hand side of Eq. 2 is taken on the
+ * trace itself (every request starts the device iff its own server TTFT exceeds its wait), not on the product of
+ * the two marginal distributions.  Same steps as orc_search_wait: fp32 midpoints, A(mid) > target moves lo up,
+ * the answer is hi.  hist_*[n_steps]. */
+float orc_search_slope(int64_t N, const int32_t* prompt_len, const float* srv_ttft,
+                       const int32_t* output_len, const float* dev_pre_spt, float dev_pre_spt_s,
+                       float dev_ttft_c, const orc_policy* templ, float lo, float hi,
+                       int32_t n_steps, int32_t which, const double* rates, double target,
+                       float* hist_param, double* hist_acc)
+{
+    orc_policy p = *templ;
+    for (int32_t step = 0; step < n_steps; ++step) {
+        float mid = 0.5f * (lo + hi);
+        p.beta = mid;
+        double a = eval_acc(N, prompt_len, srv_ttft, output_len, dev_pre_spt, dev_pre_spt_s,
+                            dev_ttft_c, &p, which, rates);
+        hist_param[step] = mid; hist_acc[step] = a;
+        if (a > target) lo = mid; else hi = mid;
+    }
+    return hi;
+}
+
 /* Integer bisection on the length threshold of a server-constrained policy
  * (Eq. 3 in discrete form): the smallest l_th in [lo, hi] whose accumulator
  * (non-increasing in l_th, e.g. server prefill tokens) does not exceed

@@ -96,6 +96,7 @@ def lib() -> C.CDLL:
         _lib.orc_wait.restype = C.c_float
         _lib.orc_quantile.restype = C.c_int64
         _lib.orc_search_wait.restype = C.c_float
+        _lib.orc_search_slope.restype = C.c_float
         _lib.orc_search_lth.restype = C.c_int32
         for name in ("orc_server_cost", "orc_device_energy", "orc_total_cost"):
             getattr(_lib, name).restype = C.c_double
@@ -396,6 +397,19 @@ def search_wait(tr: dict, templ: Policy, lo: float, hi: float, n_steps: int, whi
                               C.c_int32(ACC[which]), _rates(cost), C.c_double(target),
                               _ptr(hp, C.c_float), _ptr(ha, C.c_double))
     return np.float32(w), hp, ha
+
+
+def search_slope(tr: dict, templ: Policy, lo: float, hi: float, n_steps: int, which: str,
+                 cost: dict, target: float):
+    """Bisection on the ramp slope beta of Eq. 1 (the root of Eq. 2 on the trace)."""
+    a = _trace_args(tr)
+    hp = np.zeros(n_steps, np.float32)
+    ha = np.zeros(n_steps, np.float64)
+    b = lib().orc_search_slope(a["N"], a["l"], a["s"], a["n"], a["k"], a["ks"], a["c"],
+                               _pols([templ]), C.c_float(lo), C.c_float(hi), C.c_int32(n_steps),
+                               C.c_int32(ACC[which]), _rates(cost), C.c_double(target),
+                               _ptr(hp, C.c_float), _ptr(ha, C.c_double))
+    return np.float32(b), hp, ha
 
 
 def search_lth(tr: dict, templ: Policy, lo: int, hi: int, n_steps: int, which: str,

@@ -230,6 +230,55 @@ def test_wait_search_brackets_the_exact_root(oracle):
     assert spend(w) == spend(root)
 
 
+def test_slope_search_finds_the_root_of_eq2_on_the_trace(oracle):
+    """Eq. 2: the slope beta of the ramp w(l) = min(beta l, w_tail) at which the device prefill of the prompts above
+    l_th uses up the rest of the budget.  Its left-hand side is written out here on the trace (a request starts the
+    device iff its own server TTFT exceeds its wait), without the oracle's dispatch."""
+    P = oracle.Policy
+    tr = oracle.gen_trace(DI.config(3, n_req=3000)["gen"])
+    l = tr["prompt_len"].astype(np.int64)
+    s = tr["srv_ttft"]
+    l_th, w_tail, hi0 = 40, np.float32(2.0), 0.02
+    lf = tr["prompt_len"].astype(np.float32)
+
+    def device_prefill(beta):
+        ramp = (np.float32(beta) * lf).astype(np.float32)
+        w = np.where(ramp < w_tail, ramp, w_tail).astype(np.float32)
+        w = np.where(l <= l_th, np.float32(0.0), w)
+        return int(l[s > w].sum())
+    at_zero, at_hi = device_prefill(0.0), device_prefill(hi0)
+    assert at_hi < at_zero
+    target = at_hi + 0.4 * (at_zero - at_hi)
+    beta, hp, ha = oracle.search_slope(tr, P(mode=1, l_th=l_th, w_tail=float(w_tail), beta=0.0), 0.0, hi0, 32,
+                                       "device_prefill_tok", DI.COST_D, target)
+    assert hp[0] == np.float32(0.5 * hi0) and len(hp) == 32
+    for b, a in zip(hp, ha):                       # every recorded accumulator is Eq. 2's left-hand side at that slope
+        assert a == device_prefill(b), b
+    assert device_prefill(beta) <= target
+    lo = np.float32(hp[ha > target].max())
+    assert device_prefill(lo) > target
+    assert 0 <= float(beta) - float(lo) <= hi0 * 2.0 ** -32 * 1.0001 + float(np.spacing(np.float32(beta)))
+    # brute force: the sum only changes where beta l crosses a server TTFT; the smallest feasible fp32 slope next to
+    # those breakpoints is the exact root
+    big = l > l_th
+    cands = (s[big] / lf[big]).astype(np.float32)
+    cands = cands[(cands >= 0) & (cands <= hi0)]
+    near = np.unique(np.concatenate([cands] + [np.nextafter(cands, np.float32(d)) for d in (9, -9)]
+                                    + [np.nextafter(np.nextafter(cands, np.float32(d)), np.float32(d)) for d in (9, -9)]))
+    near = near[(near >= 0) & (near <= hi0)]
+    a, b = 0, len(near) - 1
+    assert device_prefill(near[b]) <= target
+    while a < b:
+        mid = (a + b) // 2
+        if device_prefill(near[mid]) <= target:
+            b = mid
+        else:
+            a = mid + 1
+    root = near[a]
+    assert abs(float(beta) - float(root)) <= hi0 * 2.0 ** -32 * 1.0001 + float(np.spacing(np.float32(beta)))
+    assert device_prefill(beta) == device_prefill(root)
+
+
 def test_quantile_is_sort_plus_nearest_rank(oracle):
     rng = np.random.default_rng(5)
     for M in (1, 2, 7, 100, 101, 9999):
