@@ -444,6 +444,7 @@ int32_t disco_solve_policy(const disco_trace* trace /*host*/, const disco_solve_
 
 #define DISCO_PARAM_L_TH    0   /* integer bisection on disco_policy.l_th */
 #define DISCO_PARAM_W_TAIL  1   /* fp32 bisection on disco_policy.w_tail */
+#define DISCO_PARAM_BETA    2   /* fp32 bisection on disco_policy.beta: the ramp slope of Eq. 1, root of Eq. 2 on the trace */
 
 #define DISCO_ACC_TOTAL_COST          0
 #define DISCO_ACC_SERVER_COST         1
@@ -456,8 +457,10 @@ int32_t disco_solve_policy(const disco_trace* trace /*host*/, const disco_solve_
  * is an allowance for the constrained endpoint; Eq. 3 and Alg. 2 ask for the
  * threshold / wait that meets it).  The accumulator is computed from exact
  * int64 token totals of a dispatch pass (decode charged to the winner).
- * W_TAIL: mid = 0.5f * (lo + hi) in fp32; A(mid) > target ? lo = mid : hi = mid;
- *   after n_steps the answer is hi.
+ * W_TAIL, BETA: mid = 0.5f * (lo + hi) in fp32; A(mid) > target ? lo = mid : hi = mid;
+ *   after n_steps the answer is hi.  (BETA: the slope of the ramp min(beta l, w_tail) of Eq. 1 for the prompts
+ *   above l_th; with which_acc = DEVICE_PREFILL_TOK and target = what is left of the budget this is Eq. 2, its
+ *   left-hand side taken on the trace.)
  * L_TH: mid = lo + (hi - lo) / 2; while lo < hi: A(mid) > target ? lo = mid + 1
  *   : hi = mid; later steps re-evaluate at the answer hi.
  * The caller guarantees A(hi) <= target at entry (e.g. hi = longest prompt + 1

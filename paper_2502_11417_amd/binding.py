@@ -29,7 +29,7 @@ MAX_COLS, MAX_Q, MAX_STEPS = 64, 4, 64
 GEN_REQUESTS, GEN_TOKENS = 1, 2
 MODE_S, MODE_D, MODE_STOCH_S, MODE_STOCH_D = 0, 1, 2, 3
 MIG_NONE, MIG_LAG, MIG_BUFFER = 0, 1, 2
-PARAM_L_TH, PARAM_W_TAIL = 0, 1
+PARAM_L_TH, PARAM_W_TAIL, PARAM_BETA = 0, 1, 2
 ACC = {"total_cost": 0, "server_cost": 1, "device_cost": 2, "server_prefill_tok": 3, "device_prefill_tok": 4}
 ERR = {"null": -1, "shape": -2, "range": -3, "csr": -4, "workspace": -5, "hip": -6}
 

@@ -57,14 +57,14 @@ __device__ __forceinline__ double acc_value(int which, const disco_cost_params& 
 // feasible end of the bracket).
 __device__ __forceinline__ void search_step(SearchState& st, disco_policy& p, double A, disco_search_out* o)
 {
-    const bool is_w = search_on_wait(st);
-    const double mid = search_param(is_w, p);
+    const int prm = st.which_param;
+    const double mid = search_param(prm, p);
     o->hist_param[st.step] = mid;
     o->hist_acc[st.step] = A;
-    search_halve(is_w, st.lo, st.hi, mid, A > st.target);
+    search_halve(prm, st.lo, st.hi, mid, A > st.target);
     st.step += 1;
-    if (st.step < st.n_steps) search_set_mid(is_w, st.lo, st.hi, p);
-    else search_set_answer(is_w, st.hi, p);
+    if (st.step < st.n_steps) search_set_mid(prm, st.lo, st.hi, p);
+    else search_set_answer(prm, st.hi, p);
 }
 
 // Final evaluation of search `col` (Sec. 4.2: the threshold / wait that meets the constrained endpoint's
@@ -99,18 +99,18 @@ __device__ void search_walk(const DispFin& fin, const u64* sh)
     SearchState st;
     if (j < fin.n_search) {
         st = fin.st[j];
-        const bool is_w = search_on_wait(st);
+        const int prm = st.which_param;
         disco_search_out* o = &fin.sout[j];
         int node = 1;
         for (int d = 0; d < fin.depth && st.step < st.n_steps; ++d) {
             const int c = j * M + node - 1;
             const u64 s_pre = sh[0 * 64 + c], d_pre = sh[1 * 64 + c], d_dec = sh[2 * 64 + c], n_tot = sh[3 * 64 + c];
             const double A = acc_value(st.which_acc, fin.cost, (i64)s_pre, (i64)(n_tot - d_dec), (i64)d_pre, (i64)d_dec);
-            const double mid = search_param(is_w, fin.pol_rw[c]);
+            const double mid = search_param(prm, fin.pol_rw[c]);
             o->hist_param[st.step] = mid;
             o->hist_acc[st.step] = A;
             const bool above = A > st.target;
-            search_halve(is_w, st.lo, st.hi, mid, above);
+            search_halve(prm, st.lo, st.hi, mid, above);
             st.step += 1;
             node = 2 * node + (above ? 1 : 0);
         }
@@ -121,7 +121,7 @@ __device__ void search_walk(const DispFin& fin, const u64* sh)
         const disco_policy templ = fin.templ[j];
         if (fin.last) {
             disco_policy p = templ;
-            search_set_answer(search_on_wait(st), st.hi, p);
+            search_set_answer(st.which_param, st.hi, p);
             fin.pol_rw[j] = p;
         } else {
             search_write_candidates(st, templ, &fin.pol_rw[j * M], fin.depth);

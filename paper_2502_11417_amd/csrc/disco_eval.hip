@@ -289,8 +289,8 @@ __global__ void k_search_init(SpecTable t, int n, SearchState* st, disco_policy*
     if (c < n) {
         s = t.s[c];
         p = pol[c];
-        if (search_on_wait(s)) { s.lo = (double)(float)s.lo; s.hi = (double)(float)s.hi; }
-        else { s.lo = (int)s.lo; s.hi = (int)s.hi; }
+        if (s.which_param == DISCO_PARAM_L_TH) { s.lo = (int)s.lo; s.hi = (int)s.hi; }
+        else { s.lo = (double)(float)s.lo; s.hi = (double)(float)s.hi; }
         s.step = 0;
         st[c] = s;
     }
@@ -300,7 +300,7 @@ __global__ void k_search_init(SpecTable t, int n, SearchState* st, disco_policy*
         templ[c] = p;
         search_write_candidates(s, p, &pol[c * ((1 << depth) - 1)], depth);
     } else {
-        search_set_mid(search_on_wait(s), s.lo, s.hi, p);
+        search_set_mid(s.which_param, s.lo, s.hi, p);
         pol[c] = p;
     }
 }
@@ -689,7 +689,7 @@ extern "C" int32_t disco_budget_search(const disco_trace* trace, const disco_cos
         if (templ[j].mode >= DISCO_MODE_STOCH_SERVER) return DISCO_ERR_RANGE;
     for (int j = 0; j < n_search; ++j) {
         if (spec[j].n_steps != n_steps) return DISCO_ERR_SHAPE;
-        if (spec[j].which_param != DISCO_PARAM_L_TH && spec[j].which_param != DISCO_PARAM_W_TAIL) return DISCO_ERR_RANGE;
+        if (spec[j].which_param < DISCO_PARAM_L_TH || spec[j].which_param > DISCO_PARAM_BETA) return DISCO_ERR_RANGE;
         if (spec[j].which_acc < DISCO_ACC_TOTAL_COST || spec[j].which_acc > DISCO_ACC_DEVICE_PREFILL_TOK)
             return DISCO_ERR_RANGE;
         if (!(spec[j].lo <= spec[j].hi) || spec[j].target != spec[j].target) return DISCO_ERR_RANGE;

@@ -12,24 +12,31 @@ struct SearchState {
 };
 struct SpecTable { SearchState s[DISCO_MAX_COLS]; };
 
-// Bisection of a budget search (Sec. 4.2: the threshold or wait that meets the constrained endpoint's budget) on
-// the bracket [lo, hi] of its state: the parameter evaluated for a bracket is its midpoint, the answer once the
-// steps are used up its feasible end hi.
-__device__ __forceinline__ bool search_on_wait(const SearchState& st) { return st.which_param == DISCO_PARAM_W_TAIL; }
-__device__ __forceinline__ void search_set_mid(bool is_w, double lo, double hi, disco_policy& p)
+// Bisection of a budget search (Sec. 4.2: the threshold, wait or ramp slope that meets the constrained
+// endpoint's budget) on the bracket [lo, hi] of its state: the parameter evaluated for a bracket is its midpoint,
+// the answer once the steps are used up its feasible end hi.  prm = DISCO_PARAM_*: l_th is bisected in integers,
+// w_tail and beta (Eq. 1's ramp slope, the unknown of Eq. 2) in fp32.
+__device__ __forceinline__ void search_set_value(int prm, float x, disco_policy& p)
 {
-    if (is_w) p.w_tail = 0.5f * ((float)lo + (float)hi);
-    else { const int l = (int)lo, h = (int)hi; p.l_th = l + (h - l) / 2; }
+    if (prm == DISCO_PARAM_W_TAIL) p.w_tail = x; else p.beta = x;
 }
-__device__ __forceinline__ void search_set_answer(bool is_w, double hi, disco_policy& p)
+__device__ __forceinline__ void search_set_mid(int prm, double lo, double hi, disco_policy& p)
 {
-    if (is_w) p.w_tail = (float)hi; else p.l_th = (int)hi;
+    if (prm == DISCO_PARAM_L_TH) { const int l = (int)lo, h = (int)hi; p.l_th = l + (h - l) / 2; }
+    else search_set_value(prm, 0.5f * ((float)lo + (float)hi), p);
 }
-__device__ __forceinline__ double search_param(bool is_w, const disco_policy& p) { return is_w ? (double)p.w_tail : (double)p.l_th; }
+__device__ __forceinline__ void search_set_answer(int prm, double hi, disco_policy& p)
+{
+    if (prm == DISCO_PARAM_L_TH) p.l_th = (int)hi; else search_set_value(prm, (float)hi, p);
+}
+__device__ __forceinline__ double search_param(int prm, const disco_policy& p)
+{
+    return prm == DISCO_PARAM_L_TH ? (double)p.l_th : (prm == DISCO_PARAM_W_TAIL ? (double)p.w_tail : (double)p.beta);
+}
 // above: the accumulator at `mid` exceeds the target
-__device__ __forceinline__ void search_halve(bool is_w, double& lo, double& hi, double mid, bool above)
+__device__ __forceinline__ void search_halve(int prm, double& lo, double& hi, double mid, bool above)
 {
-    if (is_w) { if (above) lo = mid; else hi = mid; }
+    if (prm != DISCO_PARAM_L_TH) { if (above) lo = mid; else hi = mid; }
     else if (lo < hi) { if (above) lo = mid + 1.0; else hi = mid; }
 }
 // The parameters of the next `depth` (<= 3) levels of the bisection below the bracket of `st`, as policy records
@@ -37,21 +44,21 @@ __device__ __forceinline__ void search_halve(bool is_w, double& lo, double& hi, 
 // "above"): dst[0 .. 2^depth - 1).  A search whose steps are used up gets copies of its answer.
 __device__ inline void search_write_candidates(const SearchState& st, const disco_policy& templ, disco_policy* dst, int depth)
 {
-    const bool is_w = search_on_wait(st);
+    const int prm = st.which_param;
     const int M = (1 << depth) - 1;
     double lo[8], hi[8];
     lo[1] = st.lo; hi[1] = st.hi;
     for (int node = 1; node <= M; ++node) {
         disco_policy p = templ;
-        if (st.step >= st.n_steps) search_set_answer(is_w, st.hi, p);
-        else search_set_mid(is_w, lo[node], hi[node], p);
+        if (st.step >= st.n_steps) search_set_answer(prm, st.hi, p);
+        else search_set_mid(prm, lo[node], hi[node], p);
         dst[node - 1] = p;
         if (2 * node + 1 <= M) {
-            const double mid = search_param(is_w, p);
+            const double mid = search_param(prm, p);
             lo[2 * node] = lo[node]; hi[2 * node] = hi[node];
-            search_halve(is_w, lo[2 * node], hi[2 * node], mid, false);
+            search_halve(prm, lo[2 * node], hi[2 * node], mid, false);
             lo[2 * node + 1] = lo[node]; hi[2 * node + 1] = hi[node];
-            search_halve(is_w, lo[2 * node + 1], hi[2 * node + 1], mid, true);
+            search_halve(prm, lo[2 * node + 1], hi[2 * node + 1], mid, true);
         }
     }
 }

@@ -545,3 +545,33 @@ def test_wait_searches_side_by_side(B, oracle, n_search, n_steps):
         assert (so["hist_param"][j][:n_steps].astype(np.float32) == hp).all(), j
         assert (so["hist_acc"][j][:n_steps] == ha).all(), j
         assert pol[j].l_th == (j % 5) * 100 - 1
+
+
+def test_slope_search_history_is_bit_identical(B, oracle):
+    """Bisection on the ramp slope beta (Eq. 2 on the trace), next to wait and threshold searches in one call."""
+    print("search parity ramp slope", flush=True)
+    tr = oracle.gen_trace(DI.config(3, n_req=30_011)["gen"])
+    dt = B.upload_trace(tr)
+    total = int(tr["prompt_len"].astype(np.int64).sum())
+    lmax = int(tr["prompt_len"].max())
+    templ = [B.Policy(mode=1, l_th=40, w_tail=2.0, beta=0.0), B.Policy(mode=1, l_th=-1, w_tail=1.0, beta=0.0),
+             B.Policy(mode=1, l_th=-1), B.Policy(mode=0)]
+    specs = [dict(which_param=B.PARAM_BETA, which_acc="device_prefill_tok", n_steps=20, lo=0.0, hi=0.02, target=0.55 * total),
+             dict(which_param=B.PARAM_BETA, which_acc="device_cost", n_steps=20, lo=0.0, hi=0.05, target=0.2 * DI.COST_D["lam"] * DI.COST_D["e_pre"] * total),
+             dict(which_param=B.PARAM_W_TAIL, which_acc="device_prefill_tok", n_steps=20, lo=0.0, hi=5.0, target=0.3 * total),
+             dict(which_param=B.PARAM_L_TH, which_acc="server_prefill_tok", n_steps=20, lo=0, hi=lmax + 1, target=0.5 * total)]
+    res = B.disco_budget_search(dt, DI.COST_D, templ, specs)
+    so = B.search_to_host(res["out"], 4)
+    pol = B.policies_to_host(res["pol_out"], 4)
+    for j in (0, 1):
+        op = oracle.Policy(mode=1, l_th=templ[j].l_th, w_tail=templ[j].w_tail, beta=0.0)
+        b, hp, ha = oracle.search_slope(tr, op, specs[j]["lo"], specs[j]["hi"], 20, specs[j]["which_acc"], DI.COST_D,
+                                        specs[j]["target"])
+        assert np.float32(so["param"][j]) == b == np.float32(pol[j].beta), (j, so["param"][j], b)
+        assert (so["hist_param"][j][:20].astype(np.float32) == hp).all(), j
+        assert (so["hist_acc"][j][:20] == ha).all(), j
+        assert len(set(ha)) > 3                    # the slope really moves the accumulator
+    w, hp, ha = oracle.search_wait(tr, oracle.Policy(mode=1, l_th=-1), 0.0, 5.0, 20, "device_prefill_tok", DI.COST_D, 0.3 * total)
+    assert np.float32(so["param"][2]) == w and (so["hist_acc"][2][:20] == ha).all()
+    lth, hp, ha = oracle.search_lth(tr, oracle.Policy(mode=0), 0, lmax + 1, 20, "server_prefill_tok", DI.COST_D, 0.5 * total)
+    assert int(so["param"][3]) == lth == pol[3].l_th and (so["hist_acc"][3][:20] == ha).all()
