@@ -11,7 +11,9 @@
  *    library never allocates, frees or retains device memory.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    All work is enqueued on it and the calls return without waiting, except
- *    where a call says it synchronises.
+ *    where a call says it synchronises.  The asynchronous calls enqueue kernel
+ *    launches only (no memset or copy operations), so a sequence of them can
+ *    be captured into a HIP graph on a capturing stream and replayed.
  *  - Policy tables (`pol`, `templ`) may live in host or in device memory; the
  *    library asks the HIP runtime which it is.  A host table is validated
  *    (DISCO_ERR_RANGE for unknown modes or NaN parameters); a device table,

@@ -575,3 +575,55 @@ def test_slope_search_history_is_bit_identical(B, oracle):
     assert np.float32(so["param"][2]) == w and (so["hist_acc"][2][:20] == ha).all()
     lth, hp, ha = oracle.search_lth(tr, oracle.Policy(mode=0), 0, lmax + 1, 20, "server_prefill_tok", DI.COST_D, 0.5 * total)
     assert int(so["param"][3]) == lth == pol[3].l_th and (so["hist_acc"][3][:20] == ha).all()
+
+
+def test_step_replayed_from_a_hip_graph(B, oracle):
+    """The entry points only enqueue kernels on the caller's stream (no memset or copy nodes, no synchronisation), so a
+    search + statistics step can be captured into a HIP graph: every replay, with eager steps in between, gives what
+    the eager step gives."""
+    print("graph replay of a search + statistics step", flush=True)
+    cfg = DI.config(1, n_req=60_000)
+    tr = oracle.gen_trace(cfg["gen"])
+    dt = B.upload_trace(tr)
+    P = 16
+    total = int(tr["prompt_len"].astype(np.int64).sum())
+    lmax = int(tr["prompt_len"].max())
+    templ = B.prepare_policies([B.Policy(mode=B.MODE_S) for _ in range(P)])
+    specs = B.prepare_specs([dict(which_param=B.PARAM_L_TH, which_acc="server_prefill_tok", n_steps=13, lo=0, hi=lmax + 1,
+                                  target=j * total / (P - 1)) for j in range(P)])
+    ws = B.workspace(tr["n_req"], P)
+    acc = torch.zeros(P * 128, dtype=torch.uint8, device="cuda")
+    sout = torch.zeros(P * B.SEARCH_DTYPE.itemsize, dtype=torch.uint8, device="cuda")
+    pol_out = torch.zeros(P * 32, dtype=torch.uint8, device="cuda")
+    stats = torch.zeros(P * 256, dtype=torch.uint8, device="cuda")
+
+    def step():
+        res = B.disco_budget_search(dt, cfg["cost"], templ, specs, ws=ws, out=sout, pol_out=pol_out, acc=acc)
+        B.disco_reduce_stats(dt, cfg["cost"], res["policies"], acc, ws=ws, out=stats)
+
+    step()
+    torch.cuda.synchronize()
+    want = B.stats_to_host(stats, P).copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                        # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for _ in range(3):
+        stats.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = B.stats_to_host(stats, P)
+        for f in want.dtype.names:
+            if want[f].dtype.kind in "iu":
+                assert (got[f] == want[f]).all(), f
+            else:
+                assert np.allclose(got[f], want[f], rtol=1e-9, atol=0, equal_nan=True), f
+        assert (got["ttft_q"].view(np.uint32) == want["ttft_q"].view(np.uint32)).all()
+        step()                                        # eager work between the replays
+        torch.cuda.synchronize()
