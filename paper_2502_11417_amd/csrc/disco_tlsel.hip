@@ -150,12 +150,22 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
     if (threadIdx.x == 0) loc_walk = 0ull;
     __syncthreads();
     wt = WaveTable{0ull, 0, 0ull};
-    for (unsigned b = wave; b < gridDim.x; b += CL_BLOCK / 64) {
-        const u64* part = parts + (size_t)b * (DISCO_MAX_CLS + 2);
-        const u64 m = part[lane];
-        const u64 wbits = part[DISCO_MAX_CLS];
-        if (part[DISCO_MAX_CLS + 1] != 0ull && lane == 0) overflow = 1;
-        insert_sets(m, (wbits >> lane) & 1ull, loc, &loc_walk, &overflow, wt, lane);
+    // a wave merges every 16th table: eight of them are loaded at a time, then inserted one after the other
+    constexpr int CL_AHEAD = 8;
+    for (unsigned b0 = wave; b0 < gridDim.x; b0 += CL_AHEAD * (CL_BLOCK / 64)) {
+        u64 m[CL_AHEAD], wbits[CL_AHEAD], ovf[CL_AHEAD];
+#pragma unroll
+        for (int j = 0; j < CL_AHEAD; ++j) {
+            const unsigned b = b0 + j * (CL_BLOCK / 64);
+            const u64* part = parts + (size_t)(b < gridDim.x ? b : b0) * (DISCO_MAX_CLS + 2);
+            m[j] = part[lane]; wbits[j] = part[DISCO_MAX_CLS]; ovf[j] = part[DISCO_MAX_CLS + 1];
+        }
+#pragma unroll
+        for (int j = 0; j < CL_AHEAD; ++j) {
+            if (b0 + j * (CL_BLOCK / 64) >= gridDim.x) break;
+            if (ovf[j] != 0ull && lane == 0) overflow = 1;
+            insert_sets(m[j], (wbits[j] >> lane) & 1ull, loc, &loc_walk, &overflow, wt, lane);
+        }
     }
     __syncthreads();
     TlSel& tl = S->tl;
