@@ -29,7 +29,8 @@
  *   buffer migration  constant-gap closed forms (hand-off index, delayed tokens), sequential
  *                     buffer simulation in exact rational arithmetic, cost-condition breakpoints
  *   quantile          numpy sort + nearest rank
- *   budget search     sort + prefix-sum solve; breakpoint enumeration
+ *   budget search     sort + prefix-sum solve; breakpoint enumeration (wait and ramp slope, the latter against
+ *                     Eq. 2's sum written out)
  *   stochastic        zero / full budget equal the single-endpoint columns, binomial routing
  *                     frequency and token share, nesting in the budget, independence of runs,
  *                     the draw rebuilt from the pinned generator with counter and key spelled out
