@@ -68,11 +68,12 @@ __device__ __forceinline__ float route_uniform(int run, i64 i)
 // times a pair of the method.  i = index of the request in the trace.
 //   decision bit0 = server started, bit1 = device started, bit2 = device won.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void dispatch_pair(const disco_policy& p, int l, float s, float d, i64 i,
-                                              unsigned& decision, float& ttft)
+//   u (dispatch_pair_u): the uniform variate of (run, request) when the caller has drawn it already.
+__device__ __forceinline__ void dispatch_pair_u(const disco_policy& p, int l, float s, float d, i64 i, bool have_u, float u,
+                                                unsigned& decision, float& ttft)
 {
     if (p.mode >= DISCO_MODE_STOCH_SERVER) {
-        const bool constrained = route_uniform(p.l_mid, i) < p.beta;
+        const bool constrained = (have_u ? u : route_uniform(p.l_mid, i)) < p.beta;
         const bool to_server = (p.mode == DISCO_MODE_STOCH_SERVER) ? constrained : !constrained;
         decision = to_server ? 1u : 6u;
         ttft = to_server ? s : d;
@@ -96,6 +97,12 @@ __device__ __forceinline__ void dispatch_pair(const disco_policy& p, int l, floa
     bool srv_mode = (p.mode == DISCO_MODE_SERVER_CONSTRAINED);
     decision = srv_mode ? s_dec : d_dec;
     ttft = srv_mode ? s_ttft : d_ttft;
+}
+
+__device__ __forceinline__ void dispatch_pair(const disco_policy& p, int l, float s, float d, i64 i,
+                                              unsigned& decision, float& ttft)
+{
+    dispatch_pair_u(p, l, s, d, i, false, 0.0f, decision, ttft);
 }
 
 // ---------------------------------------------------------------------------

@@ -223,15 +223,19 @@ __device__ __forceinline__ void finish_columns(u64* tot, int P, const DispFin& f
 // totals fit 32-bit registers.
 template <int G, int MODE, int NEED, bool RAGGED>
 __device__ __forceinline__ void batch_pairs_fast(const Staged* __restrict__ st, int sub, int cnt, i64 base, const disco_policy& p,
-                                                 ColTotals& t)
+                                                 ColTotals& t, const StochRuns& runs, const float* su)
 {
     unsigned sp = 0, dp = 0, dd = 0, ns = 0, nw = 0;
     double ts = 0.0;
     unsigned mn = t.minb, mx = t.maxb;
-#pragma unroll 8
+    // (the mixed form holds wave shuffles, which the compiler does not unroll partially)
+    constexpr int UNROLL = MODE == 2 ? 1 : 8;
+#pragma unroll UNROLL
     for (int it = 0; it < G; ++it) {
         const Staged r = st[sub * G + it];
-        PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d, base + sub * G + it);
+        const bool shared = MODE == 2 && runs.on;         // the variate of a stochastic column comes from the batch's draws
+        const float u = shared ? stoch_fetch<G == 64>(runs, su, sub * G + it) : 0.0f;
+        PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d, base + sub * G + it, shared, u);
         if (RAGGED) {                                  // requests past the end of the trace count for nothing
             const bool v = sub * G + it < cnt;
             e.srv_started = e.srv_started && v; e.dev_started = e.dev_started && v; e.dev_win = e.dev_win && v;
@@ -309,14 +313,14 @@ __device__ __forceinline__ void batch_pairs_slow(const Staged* __restrict__ st, 
 
 template <int G, int MODE>
 __device__ __forceinline__ void batch_pairs_need(const Staged* __restrict__ st, int sub, int cnt, i64 base, const disco_policy& p,
-                                                 int need, ColTotals& t)
+                                                 int need, ColTotals& t, const StochRuns& runs, const float* su)
 {
     if (cnt == 64) {
-        if (need == 0) batch_pairs_fast<G, MODE, 0, false>(st, sub, cnt, base, p, t);
-        else if (need == 1) batch_pairs_fast<G, MODE, 1, false>(st, sub, cnt, base, p, t);
-        else batch_pairs_fast<G, MODE, 2, false>(st, sub, cnt, base, p, t);
+        if (need == 0) batch_pairs_fast<G, MODE, 0, false>(st, sub, cnt, base, p, t, runs, su);
+        else if (need == 1) batch_pairs_fast<G, MODE, 1, false>(st, sub, cnt, base, p, t, runs, su);
+        else batch_pairs_fast<G, MODE, 2, false>(st, sub, cnt, base, p, t, runs, su);
     } else {
-        batch_pairs_fast<G, MODE, 2, true>(st, sub, cnt, base, p, t);
+        batch_pairs_fast<G, MODE, 2, true>(st, sub, cnt, base, p, t, runs, su);
     }
 }
 
@@ -353,6 +357,7 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
     i64 b = (i64)blockIdx.x * DP_WAVES + wave;
     load_batch(b);
     const int mode = table_mode(p, colv);
+    const StochRuns runs = stoch_runs(p, colv, lane);
     for (; b < nbatch; b += bstride) {
         const bool v = b * 64 + lane < tr.n_req;
         const int lv = lv_n, nv = nv_n;
@@ -378,9 +383,13 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
             else if (fin.need == 1) batch_pairs_threshold<G, 1>(sr, pnr, sub, p, t);
             else batch_pairs_threshold<G, 2>(sr, pnr, sub, p, t);
         } else if (small) {
-            if (mode == 0) batch_pairs_need<G, 0>(st, sub, cnt, b * 64, p, fin.need, t);
-            else if (mode == 1) batch_pairs_need<G, 1>(st, sub, cnt, b * 64, p, fin.need, t);
-            else batch_pairs_need<G, 2>(st, sub, cnt, b * 64, p, fin.need, t);
+            if (mode == 0) batch_pairs_need<G, 0>(st, sub, cnt, b * 64, p, fin.need, t, runs, nullptr);
+            else if (mode == 1) batch_pairs_need<G, 1>(st, sub, cnt, b * 64, p, fin.need, t, runs, nullptr);
+            else {
+                float su[STOCH_SHARE] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                if (runs.on) stoch_draw(runs, b * 64 + lane, su);       // this lane's request, every run of the table
+                batch_pairs_need<G, 2>(st, sub, cnt, b * 64, p, fin.need, t, runs, su);
+            }
         } else {
             batch_pairs_slow<G>(st, sub, cnt, b * 64, p, colv, mode, t);
         }

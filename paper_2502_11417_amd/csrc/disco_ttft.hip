@@ -153,6 +153,7 @@ __device__ __forceinline__ void pair_body(const TraceView& tr, const disco_polic
     const int col = lane & (G - 1), sub = lane / G;
     const bool colv = col < P;
     const disco_policy p = pol[colv ? col : 0];
+    const StochRuns runs = stoch_runs(p, colv, lane);
     unsigned prefix[DISCO_MAX_Q];
     bool live[DISCO_MAX_Q];
     bool any_live = false;
@@ -178,12 +179,16 @@ __device__ __forceinline__ void pair_body(const TraceView& tr, const disco_polic
             const float dv = __fmaf_rn((float)lv, kv, tr.c);
             st[lane] = Staged{lv, sv, 0, dv};
             const int cnt = (int)((tr.n_req - b * 64 < 64) ? (tr.n_req - b * 64) : 64);
+            const bool shared = MODE == 2 && runs.on;       // stochastic columns: one draw per request and run
+            float su[STOCH_SHARE] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (shared) stoch_draw(runs, i, su);
             __builtin_amdgcn_wave_barrier();
 #pragma unroll 4
             for (int it = 0; it < G; ++it) {
                 const int src = sub * G + it;
                 const Staged r = st[src];
-                const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d, b * 64 + src);
+                const float u = shared ? stoch_fetch<G == 64>(runs, su, src) : 0.0f;
+                const PairResult e = pair_eval<MODE>(p, r.l, r.s, r.d, b * 64 + src, shared, u);
                 if (gather) {                            // collect the pairs that still match a slot of their column
                     const unsigned key = f2u(e.ttft) - g.minb;
                     const unsigned hi = key >> up;
