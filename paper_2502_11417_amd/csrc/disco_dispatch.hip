@@ -357,7 +357,6 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
     i64 b = (i64)blockIdx.x * DP_WAVES + wave;
     load_batch(b);
     const int mode = table_mode(p, colv);
-    const StochRuns runs = stoch_runs(p, colv, lane);
     for (; b < nbatch; b += bstride) {
         const bool v = b * 64 + lane < tr.n_req;
         const int lv = lv_n, nv = nv_n;
@@ -383,9 +382,13 @@ __global__ __launch_bounds__(DP_BLOCK) void k_dispatch_acc(TraceView tr, const d
             else if (fin.need == 1) batch_pairs_threshold<G, 1>(sr, pnr, sub, p, t);
             else batch_pairs_threshold<G, 2>(sr, pnr, sub, p, t);
         } else if (small) {
-            if (mode == 0) batch_pairs_need<G, 0>(st, sub, cnt, b * 64, p, fin.need, t, runs, nullptr);
-            else if (mode == 1) batch_pairs_need<G, 1>(st, sub, cnt, b * 64, p, fin.need, t, runs, nullptr);
+            const StochRuns none{0, -1, 0, false};
+            if (mode == 0) batch_pairs_need<G, 0>(st, sub, cnt, b * 64, p, fin.need, t, none, nullptr);
+            else if (mode == 1) batch_pairs_need<G, 1>(st, sub, cnt, b * 64, p, fin.need, t, none, nullptr);
             else {
+                // (the runs of the table are worked out per batch: kept across the loop they cost the other
+                // forms scalar registers)
+                const StochRuns runs = stoch_runs(p, colv, lane);
                 float su[STOCH_SHARE] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                 if (runs.on) stoch_draw(runs, b * 64 + lane, su);       // this lane's request, every run of the table
                 batch_pairs_need<G, 2>(st, sub, cnt, b * 64, p, fin.need, t, runs, su);
