@@ -627,3 +627,27 @@ def test_step_replayed_from_a_hip_graph(B, oracle):
         assert (got["ttft_q"].view(np.uint32) == want["ttft_q"].view(np.uint32)).all()
         step()                                        # eager work between the replays
         torch.cuda.synchronize()
+
+
+def test_searches_on_an_empty_trace(B, oracle):
+    """No requests: every accumulator is zero, the bisection still walks its steps (never above the target, so the
+    bracket closes in on its lower end) and the answers' totals are zero."""
+    print("search parity empty trace", flush=True)
+    tr = DI.handmade_trace(81, 0, tokens=False)
+    dt = B.upload_trace(tr)
+    templ = [B.Policy(mode=1, l_th=-1), B.Policy(mode=0), B.Policy(mode=1, l_th=10, w_tail=1.0, beta=0.0)]
+    specs = [dict(which_param=B.PARAM_W_TAIL, which_acc="device_cost", n_steps=9, lo=0.0, hi=5.0, target=1.0),
+             dict(which_param=B.PARAM_L_TH, which_acc="server_prefill_tok", n_steps=9, lo=0, hi=100, target=0.0),
+             dict(which_param=B.PARAM_BETA, which_acc="device_prefill_tok", n_steps=9, lo=0.0, hi=1.0, target=0.0)]
+    res = B.disco_budget_search(dt, DI.COST_D, templ, specs)
+    so = B.search_to_host(res["out"], 3)
+    w, hp, ha = oracle.search_wait(tr, oracle.Policy(mode=1, l_th=-1), 0.0, 5.0, 9, "device_cost", DI.COST_D, 1.0)
+    assert np.float32(so["param"][0]) == w and (so["hist_param"][0][:9].astype(np.float32) == hp).all()
+    lth, hp, ha = oracle.search_lth(tr, oracle.Policy(mode=0), 0, 100, 9, "server_prefill_tok", DI.COST_D, 0.0)
+    assert int(so["param"][1]) == lth and (so["hist_param"][1][:9].astype(np.int32) == hp).all()
+    b, hp, ha = oracle.search_slope(tr, oracle.Policy(mode=1, l_th=10, w_tail=1.0, beta=0.0), 0.0, 1.0, 9,
+                                    "device_prefill_tok", DI.COST_D, 0.0)
+    assert np.float32(so["param"][2]) == b and (so["hist_param"][2][:9].astype(np.float32) == hp).all()
+    assert (so["hist_acc"][:, :9] == 0).all()
+    for j in range(3):
+        assert int(so["at_param"][j]["s_pre"]) == 0 and int(so["at_param"][j]["d_dec"]) == 0
