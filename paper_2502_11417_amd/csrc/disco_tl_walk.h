@@ -6,7 +6,7 @@
 
 namespace {
 
-constexpr int TF_RB = 16;                    // requests per wave batch
+constexpr int TF_RB = 16;                    // requests per wave batch (at most; fewer on small traces, see tl_batch)
 constexpr unsigned KEY_SKIP = 0x80000000u;   // a key with the sign bit never matches a prefix
 
 // Per-request fields of a wave batch, lane = request (lanes >= TF_RB idle).
@@ -17,11 +17,11 @@ struct Batch {
     u64 m[TL_KINDS];           // column sets by kind of timeline
 };
 
-__device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_policy* spol, int P, i64 first, int lane)
+__device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_policy* spol, int P, i64 first, int lane, int rb = TF_RB)
 {
     Batch b;
     const i64 i = first + lane;
-    const bool v = lane < TF_RB && i < tr.n_req;
+    const bool v = lane < rb && i < tr.n_req;
     b.l = 0; b.n = 1; b.k = tr.k_s; b.gd = tr.g_s; b.gap = 0.0f; b.off = 0; b.s = 0.0f;
     if (v) {
         b.l = tr.l[i]; b.n = tr.n[i]; b.s = tr.s[i];
@@ -35,9 +35,19 @@ __device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_pol
     return b;
 }
 
+// Requests a wave takes at a time: TF_RB on large traces; on small ones fewer, so that the waves the chip holds
+// (`waves`) get several batches each and finish together.
+inline int tl_batch(i64 n_req, i64 waves)
+{
+    int rb = TF_RB;
+    while (rb > 1 && (n_req + rb - 1) / rb < 2 * waves) rb >>= 1;
+    return rb;
+}
+
 struct HistArgs {
     float tau, kt;
     int P, pass;
+    int rb;                        // requests per wave batch
     SelState* S;
     unsigned* ghist;
     unsigned* ppcnt;

@@ -185,6 +185,7 @@ __device__ __forceinline__ void load_first(const float* __restrict__ arr, i64 of
 struct StatsArgs {
     float tau, kt;
     int P;
+    int rb;                        // requests per wave batch
     int32_t* mig_idx; int32_t* n_src_tok; float* t_last;
     int32_t* delay_num;            // all zero here: only buffer hand-offs count delayed tokens
     MigPartial* totals;            // DISCO_NCOPY x 64 device-wide totals
@@ -307,10 +308,11 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
     const bool mem = tr.arr != nullptr;
     const bool mat = a.mig_idx != nullptr || a.n_src_tok != nullptr || a.t_last != nullptr || a.delay_num != nullptr;
     const i64 nwaves = (i64)gridDim.x * (TS_BLOCK / 64);
-    const i64 nbatch = (tr.n_req + TF_RB - 1) / TF_RB;
+    const int rb = a.rb;
+    const i64 nbatch = (tr.n_req + rb - 1) / rb;
     for (i64 bt = (i64)blockIdx.x * (TS_BLOCK / 64) + wave; bt < nbatch; bt += nwaves) {
-        const Batch b = load_batch(tr, spol, P, bt * TF_RB, lane);
-        const int cnt = (int)((tr.n_req - bt * TF_RB < TF_RB) ? (tr.n_req - bt * TF_RB) : TF_RB);
+        const Batch b = load_batch(tr, spol, P, bt * rb, lane, rb);
+        const int cnt = (int)((tr.n_req - bt * rb < rb) ? (tr.n_req - bt * rb) : rb);
         const u64 srvw = __ballot((b.m[1] | b.m[2]) != 0ull);                  // requests with a server-sourced column
         const u64 memw = mem ? srvw : 0ull;                                    // ... that read the token array
         const bool any_plain = __ballot(b.m[1] != 0ull) != 0ull;
@@ -318,7 +320,7 @@ __global__ __launch_bounds__(TS_BLOCK) void k_tl_stats(TraceView tr, i64 n_tok, 
         if (memw & 1ull) load_first(tr.arr, (i64)bcast_u64((u64)b.off, 0), bcast_i(b.n, 0), n_tok, align, lane, pre);
 #pragma unroll 1
         for (int rq = 0; rq < cnt; ++rq) {
-            const i64 i = bt * TF_RB + rq;
+            const i64 i = bt * rb + rq;
             const int n = bcast_i(b.n, rq);
             const float cur[4] = {pre[0], pre[1], pre[2], pre[3]};
             if ((memw >> (rq + 1)) & 1ull)          // the next request's first chunk is loaded while this one is walked
@@ -442,9 +444,10 @@ __global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok
     const bool mem = tr.arr != nullptr;
     const bool count_pp = a.pass == 0;
     const i64 nwaves = (i64)gridDim.x * (TH_BLOCK / 64);
-    const i64 nbatch = (tr.n_req + TF_RB - 1) / TF_RB;
+    const int rb = a.rb;
+    const i64 nbatch = (tr.n_req + rb - 1) / rb;
     for (i64 bt = (i64)blockIdx.x * (TH_BLOCK / 64) + wave; bt < nbatch; bt += nwaves) {
-        const Batch b = load_batch(tr, spol, P, bt * TF_RB, lane);
+        const Batch b = load_batch(tr, spol, P, bt * rb, lane, rb);
         // lane = request: LDS row of each of the three timelines, 0xFF = nothing to walk
         unsigned desc = 0xFFFFFFu;
         {
@@ -523,7 +526,8 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
     s.tau = a.tau; s.kt = a.kt; s.P = a.P;
     s.mig_idx = a.mig_idx; s.n_src_tok = a.n_src_tok; s.t_last = a.t_last; s.delay_num = a.delay_num;
     s.totals = totals;
-    const i64 per_block = (i64)(TS_BLOCK / 64) * TF_RB;
+    s.rb = TF_RB;
+    const i64 per_block = (i64)(TS_BLOCK / 64) * s.rb;
     i64 b = (v.n_req + per_block - 1) / per_block;
     if (b < 1) b = 1;
     if (b > 2048) b = 2048;                    // eight resident workgroups per CU
@@ -540,7 +544,8 @@ void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy
     memset(&h, 0, sizeof(h));
     h.tau = a.tau; h.kt = a.kt; h.P = a.P; h.pass = a.pass;
     h.S = a.S; h.ghist = a.ghist; h.ppcnt = a.ppcnt;
-    const i64 per_block = (i64)(TH_BLOCK / 64) * TF_RB;
+    h.rb = tl_batch(v.n_req, 512 * (TH_BLOCK / 64));
+    const i64 per_block = (i64)(TH_BLOCK / 64) * h.rb;
     i64 b = (v.n_req + per_block - 1) / per_block;
     if (b < 1) b = 1;
     if (b > 512) b = 512;                      // two resident workgroups per CU
