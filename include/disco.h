@@ -308,6 +308,25 @@ int32_t disco_eval_dispatch(const disco_trace* trace /*host*/, const disco_polic
                             const disco_pair_out* out /*host, nullable*/, disco_accum* acc /*device*/,
                             void* ws /*device*/, size_t ws_bytes, void* stream);
 
+/* disco_eval_dispatch for callers that cannot allocate device memory or bring
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments, results and errors as
+ * disco_eval_dispatch without `ws`: the partial results (staged policy table,
+ * flag words, device-wide totals) live in a fixed area of
+ * DISCO_STATIC_SCRATCH_BYTES bytes of device memory inside the library's code
+ * object, which every GPU the library runs on holds until the process ends.
+ * Limits: P <= DISCO_MAX_COLS (SHAPE beyond it, nothing launched); n_req is
+ * not limited by the area.  The call allocates and frees nothing, on the host
+ * or the device.  The first call on a device looks up the area's address
+ * there (not an allocation; make that call outside a graph capture).  All
+ * calls on one GPU share the area: it is put back to its initial state at the
+ * start of every call, and calls that overlap in time on one GPU (different
+ * streams or threads) race -- serialise them.  Asynchronous. */
+#define DISCO_STATIC_SCRATCH_BYTES 133376
+int32_t disco_eval_dispatch_static(const disco_trace* trace /*host*/, const disco_policy* pol /*host or device*/, int32_t P,
+                                   const disco_pair_out* out /*host, nullable*/, disco_accum* acc /*device*/,
+                                   void* stream);
+
 /* Token timelines of every pair (Sec. 4.3).  The source of a pair is the
  * winner of its dispatch (recomputed from `pol`).  Arrival offsets r_t since
  * the first token: server = tok_arr (or t * srv_tbt without a token trace),

@@ -129,7 +129,7 @@ POLICY_DTYPE = np.dtype([("mode", "<i4"), ("l_th", "<i4"), ("l_mid", "<i4"), ("w
 assert ACCUM_DTYPE.itemsize == 128 and STATS_DTYPE.itemsize == 256 and POLICY_DTYPE.itemsize == 32
 assert C.sizeof(CPolicy) == 32 and C.sizeof(CSearchSpec) == 40
 
-EXPORTS = ["disco_gen_trace", "disco_eval_dispatch", "disco_eval_migration", "disco_reduce_stats",
+EXPORTS = ["disco_gen_trace", "disco_eval_dispatch", "disco_eval_dispatch_static", "disco_eval_migration", "disco_reduce_stats",
            "disco_average_runs", "disco_solve_policy", "disco_ingest_trace", "disco_fit_lognormal",
            "disco_device_profile", "disco_budget_search", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
            "disco_version"]
@@ -145,6 +145,9 @@ _lib.disco_gen_trace.argtypes = [C.POINTER(CGenParams), C.POINTER(CTrace), C.c_i
 _lib.disco_eval_dispatch.restype = C.c_int32
 _lib.disco_eval_dispatch.argtypes = [C.POINTER(CTrace), C.POINTER(CPolicy), C.c_int32, C.POINTER(CPairOut),
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.disco_eval_dispatch_static.restype = C.c_int32
+_lib.disco_eval_dispatch_static.argtypes = [C.POINTER(CTrace), C.POINTER(CPolicy), C.c_int32, C.POINTER(CPairOut),
+                                            C.c_void_p, C.c_void_p]
 _lib.disco_eval_migration.restype = C.c_int32
 _lib.disco_eval_migration.argtypes = [C.POINTER(CTrace), C.POINTER(CTimeline), C.POINTER(CPolicy), C.c_int32,
                                       C.POINTER(CMigOut), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -342,6 +345,17 @@ def disco_eval_dispatch(trace: Trace, policies, materialise: bool = False, ws: t
                                   acc.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "disco_eval_dispatch")
     return res
+
+
+def disco_eval_dispatch_static(trace: Trace, policies, acc: torch.Tensor, decision: torch.Tensor | None = None,
+                               ttft: torch.Tensor | None = None) -> None:
+    """The dispatch pass on the library's fixed scratch area: no workspace, nothing allocated (the caller brings
+    ``acc`` and, optionally, the [P][n_req] per-pair arrays)."""
+    out = CPairOut(decision.data_ptr() if decision is not None else None, ttft.data_ptr() if ttft is not None else None)
+    cs = trace.c_struct()
+    rc = _lib.disco_eval_dispatch_static(C.byref(cs), _policies(policies), len(policies), C.byref(out), acc.data_ptr(),
+                                         _stream())
+    _check(rc, "disco_eval_dispatch_static")
 
 
 def disco_eval_migration(trace: Trace, tau: float, kappa: float, policies, materialise: bool = False,

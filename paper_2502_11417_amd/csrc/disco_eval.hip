@@ -13,6 +13,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "disco_launch.h"
 #include "disco_state.h"
 
@@ -469,6 +471,74 @@ extern "C" int32_t disco_eval_dispatch(const disco_trace* trace, const disco_pol
     const WsLayout L = disco_ws_layout(P);
     const TraceView v = view_of(trace);
     rc = stage_policies(pol, P, ws, L, stream);
+    if (rc) return rc;
+    DispFin fin;
+    memset(&fin, 0, sizeof(fin));
+    fin.kind = 0;
+    fin.need = 2;
+    fin.acc = acc;
+    disco_launch_dispatch_acc(v, (const disco_policy*)(ws + L.pol), P, (u64*)(ws + L.part), fin, stream);
+    if (out && (out->decision || out->ttft) && v.n_req > 0)
+        disco_launch_dispatch_mat(v, (const disco_policy*)(ws + L.pol), P, out->decision, out->ttft, stream);
+    DISCO_HIP(hipGetLastError());
+    return DISCO_OK;
+}
+
+// ---------------------------------------------------- fixed scratch area --
+// Scratch of disco_eval_dispatch_static: the three workspace regions a dispatch pass touches (staged policy
+// table, flag words, device-wide totals), in device memory that belongs to the library's code object.  Every
+// GPU holds its own copy at its own address, which host code obtains once per device from the runtime; the
+// array's name is never used as an address on the host.
+namespace {
+constexpr size_t SS_POL = 0;
+constexpr size_t SS_TICKET = SS_POL + sizeof(disco_policy) * DISCO_MAX_COLS;
+constexpr size_t SS_PART = SS_TICKET + sizeof(unsigned) * 64;
+constexpr size_t SS_TOTALS_BYTES = (size_t)DISCO_NCOPY * 64 * (sizeof(DispPartial) + sizeof(MigPartial));
+constexpr size_t SS_BYTES = SS_PART + SS_TOTALS_BYTES;
+static_assert(SS_TICKET % 256 == 0 && SS_PART % 256 == 0, "regions of the fixed scratch are 256-byte aligned");
+static_assert(SS_BYTES == DISCO_STATIC_SCRATCH_BYTES, "the size the public header states");
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[SS_BYTES];
+
+namespace {
+constexpr int SS_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[SS_MAX_DEVICES];       // device address of `scratch` on each GPU, looked up on first use
+
+int static_scratch(char** out)
+{
+    int dev = -1;
+    DISCO_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= SS_MAX_DEVICES) return DISCO_ERR_RANGE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        DISCO_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255u) != 0) return DISCO_ERR_WORKSPACE;
+        g_scratch_ptr[dev] = (char*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DISCO_OK;
+}
+}  // namespace
+
+extern "C" int32_t disco_eval_dispatch_static(const disco_trace* trace, const disco_policy* pol, int32_t P,
+                                              const disco_pair_out* out, disco_accum* acc, void* stream_)
+{
+    int rc = check_trace(trace);
+    if (rc) return rc;
+    if (!pol || !acc) return DISCO_ERR_NULL;
+    if (P < 1 || P > DISCO_MAX_COLS) return DISCO_ERR_SHAPE;       // the scratch holds DISCO_MAX_COLS columns
+    char* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    WsLayout L;
+    memset(&L, 0, sizeof(L));
+    L.pol = SS_POL; L.ticket = SS_TICKET; L.part = SS_PART; L.total = SS_BYTES;
+    const TraceView v = view_of(trace);
+    rc = stage_policies(pol, P, ws, L, stream);        // also puts the flag words and the totals at their identity
     if (rc) return rc;
     DispFin fin;
     memset(&fin, 0, sizeof(fin));
