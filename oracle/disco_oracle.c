@@ -467,8 +467,13 @@ void orc_timeline(int32_t n, const float* r_srv, float gap_const, int32_t src_is
  *   r'_t      device: base + (t - m) g_dev;  server with a token trace:
  *             base + (r^S_t - r^S_m);  server with a constant gap:
  *             base + (t - m) gap_srv                            for t > m.
- * delay_num = number of tokens after the hand-off that reach the user later
- * than one pacing interval after their predecessor (TBT_t > tau).
+ * delay_num = number of tokens after the hand-off that reach the user late:
+ * token t is late when it arrives after its pacing slot, r_t > delta_{t-1} +
+ * tau (the buffer has run dry and the arrival, not the pacing, decides the
+ * delivery; lag_t > 0 in the notation of orc_timeline).  In exact arithmetic
+ * this is TBT_t > tau; stated on the arrival it does not depend on the
+ * rounding of two paced deliveries, whose computed difference scatters by an
+ * ulp around tau when tau is not a dyadic number.
  * Outputs: mig_last = m (-1 none), delay_num, t_last; nullable delivered, tbt. */
 void orc_timeline_buffer(int32_t n, const float* r_srv, float gap_srv, int32_t src_is_device,
                          double dc, double cp, float srv_ttft, float tau, int32_t l, float k, float c,
@@ -496,7 +501,9 @@ void orc_timeline_buffer(int32_t n, const float* r_srv, float gap_srv, int32_t s
         if (t >= 1) {
             float gap = del - prev;
             if (tbt) tbt[t - 1] = gap;
-            if (m >= 0 && gap > tau) delayed += 1;
+            float slot = prev + tau;
+            float lag = r - slot;
+            if (m >= 0 && lag > 0.0f) delayed += 1;
         }
         if (m < 0 && t + 1 < n) {
             float slack = del - r;

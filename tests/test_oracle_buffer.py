@@ -179,3 +179,79 @@ def test_delay_num_order_statistics(oracle):
     assert [float(x) for x in st[0]["delay_q"]] == [float(x) for x in want]
     assert st[0]["delay_sum"] == int(d.sum())
     assert all(np.isnan(x) for x in st[1]["delay_q"])                 # no migration, no order statistic
+
+
+# ---- delayed tokens at a pacing interval that is not a dyadic number (0.2 s: five tokens a second, Sec. 2.1) ----
+# There two paced deliveries fma(t, tau, M) and fma(t-1, tau, M) differ by tau only up to an ulp, so "late" must
+# be decided on the arrival (token arrives after its pacing slot), not on the rounded difference of deliveries.
+
+TAU5 = float(np.float32(0.2))
+
+
+def exact_late_count(n, r_src, tgt_arrival, t_mig, tau, m):
+    """Exact replay with the hand-off index given: number of tokens after m that arrive after their slot, and the
+    smallest distance |arrival - slot| met (to tell apart counts that hinge on a rounding)."""
+    tau = F(tau)
+    prev, late, margin = None, 0, None
+    base = None
+    for t in range(n):
+        r = F(r_src(t)) if t <= m else base + F(tgt_arrival(t, m))
+        d = r if t == 0 else max(r, prev + tau)
+        if t > m:
+            late += r > prev + tau
+            gap = abs(r - (prev + tau))
+            margin = gap if margin is None else min(margin, gap)
+        if t == m:
+            base = r + F(t_mig(t))
+        prev = d
+    return late, margin
+
+
+@pytest.mark.parametrize("g_src,g_tgt,n", [(0.03, 0.025, 600), (0.05, 0.125, 900), (0.11, 0.19, 300)])
+def test_no_token_is_late_behind_a_fast_target_at_tau_one_fifth(oracle, g_src, g_tgt, n):
+    # the target is faster than the reader: the buffer never runs dry after the hand-off, although about half of
+    # the paced gaps come out one ulp above tau
+    m, dn, tl, deliv, tbt = oracle.timeline_buffer(n, None, g_src, False, 1.0, 1e-3, 0.0, TAU5, 64, 1.0 / 800, 0.0, g_tgt)
+    assert m >= 0 and dn == 0
+    assert (tbt > np.float32(TAU5)).sum() > 10               # the rounding scatter the count must not see
+    assert np.abs(tbt.astype(np.float64) - TAU5).max() < 1e-4
+
+
+@pytest.mark.parametrize("g_src,g_tgt,k,l,n", [(0.05, 0.3, 1.0 / 800, 64, 400), (0.03, 0.21, 1.0 / 512, 200, 800),
+                                               (0.125, 0.22, 1.0 / 800, 17, 150), (0.02, 0.205, 1.0 / 800, 333, 500)])
+def test_late_tokens_behind_a_slow_target_closed_form_at_tau_one_fifth(oracle, g_src, g_tgt, k, l, n):
+    f = lambda x: F(float(np.float32(x)))
+    tau, gs, gt, kk = f(TAU5), f(g_src), f(g_tgt), f(k)
+    m, dn, tl, deliv, tbt = oracle.timeline_buffer(n, None, g_src, False, 1.0, 1e-3, 0.0, TAU5, l, float(np.float32(k)), 0.0,
+                                                   g_tgt)
+    # hand-off after the first token whose buffered playback t (tau - g_src) covers t_mig(t) = k (l + t + 1)
+    want_m = next(t for t in range(n) if t * (tau - gs) >= kk * (l + t + 1))
+    assert m == want_m
+    # token m + j arrives at r_m + t_mig + j g_tgt, its slot is delta_m + j tau: late iff j (g_tgt - tau) > room
+    room = m * (tau - gs) - kk * (l + m + 1)
+    on_time = int(room / (gt - tau))
+    assert min(room / (gt - tau) - on_time, on_time + 1 - room / (gt - tau)) > F(1, 1000)      # no rounding can move it
+    assert dn == (n - 1 - m) - on_time and 0 < dn
+    assert on_time >= 1 or g_tgt > 0.25
+
+
+def test_late_tokens_on_a_server_token_trace_at_tau_one_fifth(oracle):
+    # device source, server target whose arrivals follow a recorded trace with stalls: some tokens are late
+    rng = np.random.default_rng(11)
+    total = 0
+    for case in range(150):
+        n, l = int(rng.integers(60, 400)), int(rng.integers(8, 300))
+        gaps = np.exp(rng.normal(-3.5, 0.6, n)).astype(np.float32)
+        stall = rng.random(n) < 0.03
+        gaps[stall] = rng.uniform(0.5, 2.0, int(stall.sum())).astype(np.float32)
+        r_srv = np.concatenate([[0], np.cumsum(gaps[1:], dtype=np.float32)]).astype(np.float32)
+        g_dev, s = float(np.float32(1.0 / rng.uniform(8, 40))), float(np.float32(rng.uniform(0.2, 1.5)))
+        m, dn, tl, deliv, tbt = oracle.timeline_buffer(n, r_srv, 0.0, True, 2.0, 1.0 / 64, s, TAU5, l, 1.0 / 800, 0.0, g_dev)
+        if m < 0:
+            continue
+        late, margin = exact_late_count(n, lambda t: F(float(np.float32(t) * np.float32(g_dev))),
+                                        lambda t, mm: F(float(np.float32(r_srv[t] - r_srv[mm]))), lambda t: F(s), TAU5, m)
+        if margin > F(1, 10000):                # far from every slot: fp32 rounding of the deliveries cannot change a verdict
+            assert dn == late, case
+            total += late
+    assert total > 20
