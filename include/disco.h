@@ -256,8 +256,9 @@ typedef struct disco_pair_out {
  *   endpoint after a hand-off, -1 if none.  n_src_tok [P][n_req]: tokens
  *   produced by the endpoint that won the first token.  t_last [P][n_req]:
  *   delivery offset of the last token since the first one.  delay_num
- *   [P][n_req]: tokens after a buffer hand-off that reach the user more than
- *   tau after their predecessor (Sec. 5.2, delay_num), 0 without hand-off.
+ *   [P][n_req]: tokens after a buffer hand-off that arrive after their
+ *   pacing slot, r_t > delta_{t-1} + tau (Sec. 5.2, delay_num: the buffer ran
+ *   dry and the user waits for them), 0 without hand-off.
  * delivered [n_tok] (column `delivered_col` only; needs tok_off): delivery
  *   offset of every token. */
 typedef struct disco_mig_out {

@@ -149,7 +149,11 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
             const float gap = d[q] - prev[q];
             key[q] = f2u(gap);
             ok[q] = val[q] && tk[q] >= 1;
-            late[q] = buffer && m >= 0 && val[q] && tk[q] > m && gap > tau;
+            // delayed (Sec. 5.2, delay_num): the token arrives after its pacing slot -- decided on the arrival, so
+            // that the one-ulp scatter of paced gaps around tau cannot count
+            const float slot = prev[q] + tau;
+            const float lag = r[q] - slot;
+            late[q] = buffer && m >= 0 && val[q] && tk[q] > m && lag > 0.0f;
             if (deliv && val[q]) deliv[tk[q]] = d[q];
         }
         if (buffer && m >= 0)

@@ -18,7 +18,8 @@
 //     histogram of the timeline's class.
 //
 // Lag trigger (token t is overdue by more than kappa tau): evaluated exactly,
-// with the oracle's operations, in every chunk that passes a cheap necessary
+// one IEEE fp32 operation at a time in the order of the definition (slot =
+// delta_{t-1} + tau, lag = r_t - slot), in every chunk that passes a cheap necessary
 // condition (see walk_hist); the other chunks provably cannot trigger.
 //
 // A timeline is computed once per request and source, never per policy
@@ -249,7 +250,7 @@ __device__ __forceinline__ WalkOut walk_stats(bool mem, int n, const float* __re
             }
             const bool cheap = fast_ok && fabsf(C) <= 262144.0f * kt;
             if (!cheap || __ballot(i3 > C + 0.5f * kt) != 0ull) {
-                // exact evaluation: running maximum before each token, the oracle's operations for the lag
+                // exact evaluation: running maximum before each token, then slot and lag as defined (Sec. 4.3 pacing)
                 const float before = wave_max_f32(Mlane);
                 const float i0 = u[0], i1 = fmaxf(i0, u[1]), i2 = fmaxf(i1, u[2]);
                 const float incl = wave_incl_max_dpp(i3, lane);
