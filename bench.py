@@ -147,8 +147,9 @@ def main() -> int:
             if tau is not None:
                 D.disco_eval_migration(self.trace, tau, cfg["kappa"], self.pols, ws=self.ws, acc=self.acc,
                                        cost=cfg["cost"])
+            # (the statistics start from what the evaluation's token walk left in the workspace)
             st = D.disco_reduce_stats(self.trace, cfg["cost"], self.pols, self.acc, tau=tau, kappa=cfg["kappa"],
-                                      ws=self.ws, out=self.stats, mig_cost=cfg["cost"])
+                                      ws=self.ws, out=self.stats, mig_cost=cfg["cost"], reuse_walk=tau is not None)
             if self.stoch:
                 return D.disco_average_runs(st, len(self.levels), self.runs, out=self.avg)
             return st

@@ -233,11 +233,21 @@ typedef struct disco_cost_params {
  * than one per `tau` seconds (the user's consumption rate r_c = 1/tau); a
  * lag hand-off fires when a token is more than kappa_lag * tau overdue.
  * cost: host, nullable; the prices behind the buffer hand-off's cost test
- * (columns with DISCO_MIG_BUFFER never hand off without it). */
+ * (columns with DISCO_MIG_BUFFER never hand off without it).
+ * reuse_walk: disco_eval_migration (without `delivered`) leaves, in the
+ * per-request part of the workspace, what its walk over the token array found
+ * for every request (the running maximum of each of its timelines and the
+ * lag hand-off, 16 bytes).  A caller who passes the same workspace, untouched
+ * by other calls in between except disco_reduce_stats, with the same trace,
+ * policy table, tau and kappa_lag to disco_reduce_stats may set reuse_walk = 1:
+ * the TBT order statistics then start from those summaries instead of walking
+ * the tokens again. */
 typedef struct disco_timeline_params {
     float tau;
     float kappa_lag;
     const disco_cost_params* cost;
+    int32_t reuse_walk;      /* disco_reduce_stats only, see there; 0: walk the tokens again */
+    int32_t reserved;
 } disco_timeline_params;
 
 /* ---- per-pair outputs and per-column accumulators ----------------------- */
@@ -350,6 +360,7 @@ int32_t disco_eval_dispatch_static(const disco_trace* trace /*host*/, const disc
  * (tok_arr_t - tok_arr_m) (server without / with a token trace), t > m.
  * Tables with such columns run in a slower, general kernel.
  * acc: device, P entries, timeline block overwritten.  Asynchronous.
+ * ws: disco_workspace_bytes(n_req, P) bytes (the per-request part is needed).
  * Errors: NULL, SHAPE, RANGE (tau <= 0, kappa_lag < 0), CSR (delivered
  * requested without tok_off), WORKSPACE, HIP. */
 int32_t disco_eval_migration(const disco_trace* trace /*host*/, const disco_timeline_params* tl /*host*/,
@@ -535,15 +546,24 @@ int32_t disco_budget_search(const disco_trace* trace /*host*/, const disco_cost_
 /* ---- helpers ------------------------------------------------------------ */
 
 /* Bytes of device workspace for n_req requests and P columns (or searches):
- * about 47 MB plus one byte per request.  Every call accepts a workspace of
- * disco_workspace_bytes(0, P) bytes; the per-request byte only lets the TTFT
- * selection of disco_reduce_stats keep a small per-request result between its
- * passes instead of recomputing it.  The
- * workspace holds partial results only; its contents need not be initialised
- * or preserved between calls, and calls that share one workspace must not
- * overlap in time.  It must be ordinary (coarse-grained) device memory,
+ * about 47 MB plus 17 bytes per request.  The per-request part (one byte that
+ * the TTFT selection and the token walk use between their passes, 16 bytes of
+ * what the token walk found) is needed by disco_eval_migration and by
+ * disco_reduce_stats with timelines; every other call accepts a workspace of
+ * disco_workspace_bytes(0, P) bytes.  The workspace holds partial results
+ * only; its contents need not be initialised or preserved between calls
+ * (except for reuse_walk, see disco_timeline_params), and calls that share
+ * one workspace must not overlap in time.  It must be ordinary (coarse-grained) device memory,
  * 256-byte aligned: the kernels use hardware floating-point atomics on it. */
 size_t disco_workspace_bytes(int64_t n_req, int32_t P);
+
+/* Measurement aid (no part of the method): one read-and-reduce pass over
+ * `bytes` bytes of device memory (16-byte aligned, a multiple of 16), i.e. what
+ * the GPU sustains on a plain streaming read; the benchmark quotes it beside
+ * the HBM fractions of the token walk.  out64: device, 64 words the kernel may
+ * store to (it keeps the reads from being elided).  Asynchronous.
+ * Errors: NULL, SHAPE, HIP. */
+int32_t disco_read_probe(const void* src /*device*/, int64_t bytes, void* out64 /*device*/, void* stream);
 
 const char* disco_strerror(int32_t code);
 const char* disco_last_hip_error(void);   /* text of the last HIP failure seen by this thread */

@@ -78,7 +78,8 @@ class CCost(C.Structure):
 
 
 class CTimeline(C.Structure):
-    _fields_ = [("tau", C.c_float), ("kappa_lag", C.c_float), ("cost", C.POINTER(CCost))]
+    _fields_ = [("tau", C.c_float), ("kappa_lag", C.c_float), ("cost", C.POINTER(CCost)),
+                ("reuse_walk", C.c_int32), ("reserved", C.c_int32)]
 
 
 class CPairOut(C.Structure):
@@ -131,7 +132,7 @@ assert C.sizeof(CPolicy) == 32 and C.sizeof(CSearchSpec) == 40
 
 EXPORTS = ["disco_gen_trace", "disco_eval_dispatch", "disco_eval_dispatch_static", "disco_eval_migration", "disco_reduce_stats",
            "disco_average_runs", "disco_solve_policy", "disco_ingest_trace", "disco_fit_lognormal",
-           "disco_device_profile", "disco_budget_search", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
+           "disco_device_profile", "disco_budget_search", "disco_read_probe", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
            "disco_version"]
 
 _lib.disco_strerror.restype = C.c_char_p
@@ -177,6 +178,8 @@ _lib.disco_device_profile.argtypes = [C.c_int32, C.POINTER(CDevicePreset)]
 _lib.disco_solve_policy.restype = C.c_int32
 _lib.disco_solve_policy.argtypes = [C.POINTER(CTrace), C.POINTER(CSolveSpec), C.c_int32, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.disco_read_probe.restype = C.c_int32
+_lib.disco_read_probe.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
 _lib.disco_budget_search.restype = C.c_int32
 _lib.disco_budget_search.argtypes = [C.POINTER(CTrace), C.POINTER(CCost), C.POINTER(CPolicy),
                                      C.POINTER(CSearchSpec), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -385,7 +388,7 @@ def disco_eval_migration(trace: Trace, tau: float, kappa: float, policies, mater
         out.delivered = res["delivered"].data_ptr()
         out.delivered_col = delivered_col
     cc = _cost(cost) if cost is not None else None
-    tl = CTimeline(tau, kappa, C.pointer(cc) if cc is not None else None)
+    tl = CTimeline(tau, kappa, C.pointer(cc) if cc is not None else None, 0, 0)
     cs = trace.c_struct()
     rc = _lib.disco_eval_migration(C.byref(cs), C.byref(tl), _policies(policies), P, C.byref(out),
                                    acc.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
@@ -395,9 +398,11 @@ def disco_eval_migration(trace: Trace, tau: float, kappa: float, policies, mater
 
 def disco_reduce_stats(trace: Trace, cost: dict, policies, acc: torch.Tensor, quantiles=((50, 100), (99, 100)),
                        tau: float | None = None, kappa: float = 3.0, ws: torch.Tensor | None = None,
-                       out: torch.Tensor | None = None, mig_cost: dict | None = None) -> torch.Tensor:
+                       out: torch.Tensor | None = None, mig_cost: dict | None = None,
+                       reuse_walk: bool = False) -> torch.Tensor:
     """Returns the device buffer of P ``disco_stats`` records (see ``stats_to_host``).  ``tau``, ``kappa`` and
-    ``mig_cost`` must be the timeline parameters ``acc`` was accumulated with."""
+    ``mig_cost`` must be the timeline parameters ``acc`` was accumulated with.  ``reuse_walk``: ``ws`` is the
+    workspace ``disco_eval_migration`` just ran in, for the same trace, table and parameters."""
     P = len(policies)
     dev = acc.device
     if ws is None:
@@ -408,7 +413,7 @@ def disco_reduce_stats(trace: Trace, cost: dict, policies, acc: torch.Tensor, qu
     for i, (num, den) in enumerate(quantiles):
         q[i] = CQuantile(num, den)
     mc = _cost(mig_cost) if mig_cost is not None else None
-    tl = CTimeline(tau, kappa, C.pointer(mc) if mc is not None else None) if tau is not None else None
+    tl = CTimeline(tau, kappa, C.pointer(mc) if mc is not None else None, 1 if reuse_walk else 0, 0) if tau is not None else None
     cs = trace.c_struct()
     cc = _cost(cost)
     rc = _lib.disco_reduce_stats(C.byref(cs), C.byref(cc), C.byref(tl) if tl else None, _policies(policies), P,
@@ -514,6 +519,14 @@ def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Te
                                   ws.numel(), _stream())
     _check(rc, "disco_budget_search")
     return {"out": out, "pol_out": pol_out, "policies": DevicePolicies(pol_out, n)}
+
+
+def disco_read_probe(buf: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """One streaming read-and-reduce pass over ``buf`` (measurement aid)."""
+    if out is None:
+        out = torch.zeros(64, dtype=torch.int32, device=buf.device)
+    _check(_lib.disco_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), out.data_ptr(), _stream()), "disco_read_probe")
+    return out
 
 
 # ------------------------------------------------------- host-side parsing

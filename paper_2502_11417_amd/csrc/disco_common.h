@@ -35,7 +35,16 @@ struct WsLayout {
     size_t ppcnt;      // unsigned[DISCO_MAX_CLS][DISCO_PP_NMAX + 1]: pure-pacing timelines per class and length
     size_t dhist;      // unsigned[DISCO_MAX_COLS][DISCO_DELAY_BINS]: migrated requests by number of delayed tokens
     size_t templ;      // disco_policy[64]: templates of a budget search (its candidate columns are in `pol`)
+    size_t wcount;     // unsigned[1024]: batch counters of the token walk, one per queue, 128 bytes apart
     size_t slices;     // per-workgroup histogram slices (TTFT passes, prompt-length table): 32 MB
     size_t total;
 };
 WsLayout disco_ws_layout(int32_t P);
+// Behind the fixed regions: one byte per request (TTFT selection: thresholds not above the prompt length; token
+// walk: which timelines to walk), then 16 bytes per request (what the token walk found).
+inline size_t disco_ws_bytes_region(int64_t n_req) { return n_req > 0 ? (((size_t)n_req + 255) & ~(size_t)255) : 0; }
+inline size_t disco_ws_summary_offset(const WsLayout& L, int64_t n_req) { return L.total + disco_ws_bytes_region(n_req); }
+inline size_t disco_ws_full_bytes(const WsLayout& L, int64_t n_req)
+{
+    return disco_ws_summary_offset(L, n_req) + (n_req > 0 ? (size_t)n_req * 16 : 0);
+}

@@ -427,16 +427,16 @@ WsLayout disco_ws_layout(int32_t P)
     L.ppcnt = o; o += up(sizeof(unsigned) * DISCO_MAX_CLS * (DISCO_PP_NMAX + 1));
     L.dhist = o; o += up(sizeof(unsigned) * DISCO_MAX_COLS * DISCO_DELAY_BINS);
     L.templ = o; o += up(sizeof(disco_policy) * DISCO_MAX_COLS);
+    L.wcount = o; o += up(sizeof(unsigned) * 1024);
     L.slices = o; o += up((size_t)256 * (2 * DISCO_MAX_COLS + 2) * 256 * sizeof(unsigned));   // 256 workgroups x rows x bins
     L.total = o;
     return L;
 }
 
-// The fixed regions, then one byte per request (used by the TTFT selection; optional: a workspace without it works).
+// The fixed regions, then one byte and 16 bytes per request (see disco_ws_bytes_region).
 extern "C" size_t disco_workspace_bytes(int64_t n_req, int32_t P)
 {
-    const size_t per_request = n_req > 0 ? (((size_t)n_req + 255) & ~(size_t)255) : 0;
-    return disco_ws_layout(P).total + per_request;
+    return disco_ws_full_bytes(disco_ws_layout(P), n_req);
 }
 
 extern "C" const char* disco_strerror(int32_t code)
@@ -569,6 +569,7 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)ws_;
     const WsLayout L = disco_ws_layout(P);
+    if (!(out && out->delivered) && ws_bytes < disco_ws_full_bytes(L, trace->n_req)) return DISCO_ERR_WORKSPACE;
     TraceView v = view_of(trace);
     if (out && out->delivered) v.off = trace->tok_off;      // offsets index `delivered` even without tok_arr
     rc = stage_policies(pol, P, ws, L, stream);
@@ -590,13 +591,17 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
     a.acc = acc;
     a.S = (SelState*)(ws + L.sel);
     a.ghist = (unsigned*)(ws + L.ghist);
-    // Streaming kernels (lag-trigger and plain pairs, then the pairs with a buffer hand-off), unless per-token
-    // deliveries are wanted: then the general kernel.
-    if (a.delivered)
+    // Streaming kernels (token walk into per-request summaries, per-column totals from them, then the pairs with a
+    // buffer hand-off), unless per-token deliveries are wanted: then the general kernel.
+    if (a.delivered) {
         disco_launch_timeline_general(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a, stream);
-    else
+    } else {
+        a.wflags = (unsigned char*)(ws + L.total);
+        a.summary = ws + disco_ws_summary_offset(L, v.n_req);
+        a.counter = (unsigned*)(ws + L.wcount);
         disco_launch_tl_stats_fast(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a,
                                    tl_totals((u64*)(ws + L.part)), stream);
+    }
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }
@@ -621,6 +626,7 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     hipStream_t stream = (hipStream_t)stream_;
     char* ws = (char*)ws_;
     const WsLayout L = disco_ws_layout(P);
+    if (tl && nq > 0 && ws_bytes < disco_ws_full_bytes(L, trace->n_req)) return DISCO_ERR_WORKSPACE;
     const TraceView v = view_of(trace);
     SelState* S = (SelState*)(ws + L.sel);
     unsigned* gh = (unsigned*)(ws + L.ghist);
@@ -653,7 +659,13 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             // launches after the last needed pass return at once
             a.ppcnt = (unsigned*)(ws + L.ppcnt);
             const disco_policy* dpol = (const disco_policy*)(ws + L.pol);
-            disco_launch_tl_classify(v, dpol, P, nq, tl->tau, S, a.ppcnt, gh, a.dhist, (u64*)(ws + L.slices),
+            // what the token walk found per request: left in the workspace by disco_eval_migration, or walked now
+            a.wflags = (unsigned char*)(ws + L.total);
+            a.summary = ws + disco_ws_summary_offset(L, v.n_req);
+            a.counter = (unsigned*)(ws + L.wcount);
+            if (!tl->reuse_walk)
+                disco_launch_tl_walk(v, trace->n_tok, dpol, P, a.tau, a.kt, a.wflags, a.summary, a.counter, stream);
+            disco_launch_tl_classify(v, dpol, P, nq, tl->tau, a.summary, S, a.ppcnt, gh, a.dhist, (u64*)(ws + L.slices),
                                      (unsigned*)(ws + L.ticket), stream);
             for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;

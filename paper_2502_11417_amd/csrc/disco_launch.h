@@ -17,6 +17,9 @@ struct TimelineArgs {
     BufCostArgs bc;           // prices of the buffer hand-off's cost test
     const unsigned* buffer_flag;   // device: 1 if the staged table has a buffer hand-off column
     unsigned* dhist;               // histogram passes: migrated requests by number of delayed tokens, per column
+    unsigned char* wflags;         // one byte per request: the walks it needs (written by the statistics pass)
+    void* summary;                 // TlSummary per request: what the token walk found (16 bytes each)
+    unsigned* counter;             // batch counters of the token walk, one per queue (zeroed by the flags kernel)
 };
 
 // How the last workgroup of a dispatch pass hands on the column totals.
@@ -79,11 +82,15 @@ void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int 
 // decided on the device), then the digit selection.
 void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                 MigPartial* totals, hipStream_t stream);
+// The token walk alone (flags, then one 16-byte summary per request), for a statistics call that was not handed
+// the summaries of the evaluation.
+void disco_launch_tl_walk(const TraceView& v, i64 n_tok, const disco_policy* pol, int P, float tau, float kt,
+                          unsigned char* wflags, void* summary, unsigned* counter, hipStream_t stream);
 void disco_launch_timeline_general(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                    hipStream_t stream);
-void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
-                              unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts /* 1024 x 66 words of scratch */,
-                              unsigned* ticket, hipStream_t stream);
+void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, const void* summary,
+                              SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist,
+                              u64* parts /* 1024 x 66 words of scratch */, unsigned* ticket, hipStream_t stream);
 void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                hipStream_t stream);
 void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,

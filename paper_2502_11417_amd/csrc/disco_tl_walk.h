@@ -9,17 +9,78 @@ namespace {
 constexpr int TF_RB = 16;                    // requests per wave batch (at most; fewer on small traces, see tl_batch)
 constexpr unsigned KEY_SKIP = 0x80000000u;   // a key with the sign bit never matches a prefix
 
+// Four arrival offsets of a lane from the token array; `safe` (wave-uniform)
+// says that every 16-byte load of the request's window lies inside the array.
+__device__ __forceinline__ void load4s(const float* __restrict__ arr, i64 g, i64 n_tok, bool safe, float r[4])
+{
+    if (safe) {
+        const float4 v = *reinterpret_cast<const float4*>(arr + g);
+        r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
+    } else {
+        load4(arr, g, n_tok, r);
+    }
+}
+
+// Screening of the lag trigger (token t is overdue by more than kappa tau, Sec. 4.3 pacing) by a necessary
+// condition.  With C <= M_{t-1} (C = a running maximum taken earlier, e.g. u_0) and monotone rounding,
+//   lag_t = fl(r_t - fl(fl((t-1) tau + M_{t-1}) + tau)) <= fl(r_t - fl(fl((t-1) tau + C) + tau)),
+// which differs from u_t - C = fl(r_t - t tau) - C by at most four roundings of magnitudes below
+// 2 t tau + 2 |C| + kappa tau.  lag_fast_ok bounds t and the caller bounds |C| <= 2^18 kappa tau so that this
+// error stays below kappa tau / 4; hence lag_t > kappa tau implies u_t > C + kappa tau / 2, and a chunk where
+// no token satisfies the latter cannot trigger.
+__device__ __forceinline__ bool lag_fast_ok(int n, float tau, float kt)
+{
+    return (float)n + 2.0f <= 262144.0f * (kt / tau) && kt >= tau * 0.0009765625f;
+}
+
+// What the token walk of disco_eval_migration leaves per request (16 bytes): the running maximum M = max_t u_t
+// of each of its timelines that is not known in closed form -- the last delivery is fma(n-1, tau, M) -- and the
+// lag hand-off.  Fields of kinds the request does not have, and of closed-form (pure-pacing) timelines, hold
+// M = 0 and no hand-off, which is what such a timeline has.
+//   M_lag    server source with the lag trigger (spliced device arrivals included)
+//   m_enc    -1: no hand-off; -2: no hand-off and the first arrival offset is not 0; >= 0: first token produced
+//            by the device in its low 30 bits, bit 30: the first arrival offset is not 0
+//   M_plain  server source without hand-off
+//   M_dev    device source
+struct TlSummary { float M_lag; int m_enc; float M_plain; float M_dev; };
+static_assert(sizeof(TlSummary) == 16, "one 16-byte store per request");
+
+__device__ __forceinline__ int summary_m(int m_enc) { return m_enc < 0 ? -1 : (m_enc & 0x3FFFFFFF); }
+__device__ __forceinline__ bool summary_r0_nonzero(int m_enc) { return m_enc == -2 || (m_enc >= 0 && ((m_enc >> 30) & 1)); }
+// A server timeline whose running maximum never left its start 0: delta_t = round(t tau), like a pure-pacing
+// constant-gap source; its gaps depend on its length alone.
+__device__ __forceinline__ bool summary_pure_lag(const TlSummary& s) { return f2u(s.M_lag) == 0u && s.m_enc == -1; }
+__device__ __forceinline__ bool summary_pure_plain(const TlSummary& s) { return f2u(s.M_plain) == 0u && !summary_r0_nonzero(s.m_enc); }
+
+// Which walks a request needs (one byte per request, written before the walk): bit 0 server source with the
+// lag trigger, bit 1 server source without hand-off, bit 2 device source; closed-form timelines need none.
+// bit 3 (set by the streaming walk): its screening could not rule out a lag hand-off, the request is walked again, exactly.
+enum { WF_LAG = 1, WF_PLAIN = 2, WF_DEV = 4, WF_REDO = 8 };
+
 // Per-request fields of a wave batch, lane = request (lanes >= TF_RB idle).
 struct Batch {
     int l, n;
     float k, gd, gap, s;
     i64 off;
     u64 m[TL_KINDS];           // column sets by kind of timeline
+    TlSummary sum;             // what the token walk found (all zero / no hand-off without summaries)
 };
 
-__device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_policy* spol, int P, i64 first, int lane, int rb = TF_RB)
+// Is a timeline of kind TL_DEV, TL_SRV or TL_SRV_LAG histogrammed analytically?  Its running maximum never left 0
+// and it has no hand-off, so delta_t = round(t tau) and its gaps depend on its length alone (counted per class
+// and length up to DISCO_PP_NMAX).
+__device__ __forceinline__ bool timeline_is_analytic(int kind, int n, const TlSummary& s)
+{
+    if (n < 0 || n > DISCO_PP_NMAX) return false;
+    if (kind == TL_DEV) return f2u(s.M_dev) == 0u;
+    return kind == TL_SRV ? summary_pure_plain(s) : summary_pure_lag(s);
+}
+
+__device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_policy* spol, int P, i64 first, int lane, int rb = TF_RB,
+                                            const TlSummary* summary = nullptr)
 {
     Batch b;
+    b.sum = TlSummary{0.0f, -1, 0.0f, 0.0f};
     const i64 i = first + lane;
     const bool v = lane < rb && i < tr.n_req;
     b.l = 0; b.n = 1; b.k = tr.k_s; b.gd = tr.g_s; b.gap = 0.0f; b.off = 0; b.s = 0.0f;
@@ -29,6 +90,7 @@ __device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_pol
         if (tr.g) b.gd = tr.g[i];
         if (tr.off) b.off = tr.off[i];
         if (tr.tbt) b.gap = tr.tbt[i];
+        if (summary) b.sum = summary[i];
     }
     request_sets(spol, P, b.l, b.s, __fmaf_rn((float)b.l, b.k, tr.c), i, b.m);
     if (!v) b.m[0] = b.m[1] = b.m[2] = b.m[3] = b.m[4] = 0ull;
@@ -51,6 +113,7 @@ struct HistArgs {
     SelState* S;
     unsigned* ghist;
     unsigned* ppcnt;
+    const TlSummary* summary;      // per request, from the token walk
 };
 
 // Digit of this pass and the rows of the LDS histogram.

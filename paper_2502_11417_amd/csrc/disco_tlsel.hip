@@ -9,7 +9,7 @@
 // pacing interval) need no token walk at all: the gap in front of token t is
 // round(t tau) - round((t-1) tau) for every one of them, so counting the
 // timelines per class and length gives their histogram.
-#include "disco_tl_device.h"
+#include "disco_tl_walk.h"
 
 namespace {
 
@@ -103,8 +103,9 @@ __device__ __forceinline__ void insert_sets(u64 m, bool walked, u64* loc, u64* l
 // device-wide bins.
 //   parts: gridDim.x x (DISCO_MAX_CLS + 2) words of scratch
 __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
-                                                     float tau, SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist,
-                                                     u64* parts, unsigned* ticket)
+                                                     float tau, const TlSummary* __restrict__ summary, SelState* S,
+                                                     unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts,
+                                                     unsigned* ticket)
 {
     __shared__ disco_policy sp[DISCO_MAX_COLS];
     __shared__ u64 loc[DISCO_MAX_CLS];
@@ -129,12 +130,11 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
             const int l = tr.l[i], n = tr.n[i];
             const float s = tr.s[i];
             const float k = tr.k ? tr.k[i] : tr.k_s;
-            const float gd = tr.g ? tr.g[i] : tr.g_s;
-            const float gap = tr.tbt ? tr.tbt[i] : 0.0f;
             request_sets(sp, P, l, s, __fmaf_rn((float)l, k, tr.c), i, m);
-            const bool short_n = n <= DISCO_PP_NMAX;
-            walked[0] = !(short_n && pure_pacing(true, gd, tau));
-            walked[TL_SRV] = walked[TL_SRV_LAG] = !(short_n && pure_pacing(tr.arr == nullptr, gap, tau));
+            const TlSummary sm = summary[i];
+            walked[TL_DEV] = !timeline_is_analytic(TL_DEV, n, sm);
+            walked[TL_SRV] = !timeline_is_analytic(TL_SRV, n, sm);
+            walked[TL_SRV_LAG] = !timeline_is_analytic(TL_SRV_LAG, n, sm);
         }
 #pragma unroll
         for (int kind = 0; kind < TL_KINDS; ++kind) insert_sets(m[kind], walked[kind], loc, &loc_walk, &overflow, wt, lane);
@@ -398,15 +398,15 @@ __global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, in
 
 }  // namespace
 
-void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, SelState* S,
-                              unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts, unsigned* ticket,
+void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, const void* summary,
+                              SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts, unsigned* ticket,
                               hipStream_t stream)
 {
     i64 b = (v.n_req + CL_BLOCK - 1) / CL_BLOCK;
     if (b < 1) b = 1;
     if (b > 256) b = 256;
-    hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau, S, ppcnt, ghist, dhist,
-                       parts, ticket);
+    hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau,
+                       (const TlSummary*)summary, S, ppcnt, ghist, dhist, parts, ticket);
 }
 
 void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,

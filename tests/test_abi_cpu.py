@@ -38,7 +38,7 @@ def test_struct_sizes_match_the_header(B):
 def test_struct_layouts_match_a_c_compiler(B, tmp_path):
     """sizeof / offsetof as gcc sees the public header against the binding's ctypes and numpy records."""
     import subprocess
-    probes = [("disco_timeline_params", ["tau", "kappa_lag", "cost"], B.CTimeline),
+    probes = [("disco_timeline_params", ["tau", "kappa_lag", "cost", "reuse_walk"], B.CTimeline),
               ("disco_mig_out", ["mig_idx", "n_src_tok", "t_last", "delivered", "delivered_col", "delay_num"], B.CMigOut),
               ("disco_accum", ["m_s_dec", "tlast_sum", "ttft_min_bits", "m_s_repre", "delay_sum"], B.ACCUM_DTYPE),
               ("disco_stats", ["mean_tbt", "ttft_rank", "tbt_q", "mean_delay_num"], B.STATS_DTYPE),
@@ -95,7 +95,7 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     tr.n_req = 5          # arrays missing
     assert lib.disco_eval_dispatch(C.byref(tr), pol, 1, None, 256, 256, 1 << 30, None) == B.ERR["null"]
     tr.n_req = 0
-    tl = B.CTimeline(0.0, 3.0, None)
+    tl = B.CTimeline(0.0, 3.0, None, 0, 0)
     assert lib.disco_eval_migration(C.byref(tr), C.byref(tl), pol, 1, None, 256, 256, 1 << 30, None) == B.ERR["range"]
     q = (B.CQuantile * 1)(B.CQuantile(3, 2))
     cost = B.CCost(1, 1, 1, 1, 1)

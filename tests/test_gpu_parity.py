@@ -204,9 +204,17 @@ def check_stats(B, O, tr, specs, cost, tau=None, kappa=3.0, quantiles=((50, 100)
     r = B.disco_eval_dispatch(dt, bp, ws=ws)
     if tau is not None:
         B.disco_eval_migration(dt, tau, kappa, bp, ws=ws, acc=r["acc"], cost=cost)
-    out = B.disco_reduce_stats(dt, cost, bp, r["acc"], quantiles=quantiles, tau=tau, kappa=kappa, ws=ws, mig_cost=cost)
-    got = B.stats_to_host(out, P)
     want = O.stats(tr, op, cost, quantiles=quantiles, tau=tau, kappa=kappa)
+    # with timelines: once from the summaries the evaluation's token walk left in the workspace, once walking again
+    for reuse in ((True, False) if tau is not None else (False,)):
+        out = B.disco_reduce_stats(dt, cost, bp, r["acc"], quantiles=quantiles, tau=tau, kappa=kappa, ws=ws, mig_cost=cost,
+                                   reuse_walk=reuse)
+        got = B.stats_to_host(out, P)
+        compare_stats(got, want, tr, P, quantiles, tau)
+    return got, want
+
+
+def compare_stats(got, want, tr, P, quantiles, tau):
     for j in range(P):
         w, g = want[j], got[j]
         for f in ("s_pre", "s_dec", "d_pre", "d_dec", "n_dev_started", "n_dev_win", "n_migrated", "tbt_count", "n_req"):
@@ -239,7 +247,6 @@ def check_stats(B, O, tr, specs, cost, tau=None, kappa=3.0, quantiles=((50, 100)
                     assert float(g["delay_q"][qi]) == float(w["delay_q"][qi]), (j, qi, g["delay_q"][qi], w["delay_q"][qi])
                 else:
                     assert math.isnan(g["delay_q"][qi]), (j, qi)
-    return got, want
 
 
 @pytest.mark.parametrize("n_req", [0, 1, 100, 4_097])
