@@ -565,6 +565,18 @@ size_t disco_workspace_bytes(int64_t n_req, int32_t P);
  * Errors: NULL, SHAPE, HIP. */
 int32_t disco_read_probe(const void* src /*device*/, int64_t bytes, void* out64 /*device*/, void* stream);
 
+/* Measurement aid: runs the token-walk part of disco_eval_migration (which
+ * requests to walk, the streaming walk over the token array, the exact
+ * re-walk of the few requests it leaves) reps + 1 times and reports the mean
+ * and the minimum duration, in milliseconds, of the streaming kernel alone
+ * over the last reps runs, taken with HIP events on `stream` around that
+ * kernel's launch.  SYNCHRONISES.  mean_ms, min_ms: host.  Needs a trace with
+ * a token array.  Errors: as disco_eval_migration; SHAPE (reps outside
+ * [1, 1000]), CSR (no token array or no request). */
+int32_t disco_time_token_walk(const disco_trace* trace /*host*/, const disco_timeline_params* tl /*host*/,
+                              const disco_policy* pol /*host or device*/, int32_t P, void* ws /*device*/, size_t ws_bytes,
+                              int32_t reps, double* mean_ms /*host*/, double* min_ms /*host*/, void* stream);
+
 const char* disco_strerror(int32_t code);
 const char* disco_last_hip_error(void);   /* text of the last HIP failure seen by this thread */
 int32_t disco_version(void);

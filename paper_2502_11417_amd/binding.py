@@ -132,7 +132,7 @@ assert C.sizeof(CPolicy) == 32 and C.sizeof(CSearchSpec) == 40
 
 EXPORTS = ["disco_gen_trace", "disco_eval_dispatch", "disco_eval_dispatch_static", "disco_eval_migration", "disco_reduce_stats",
            "disco_average_runs", "disco_solve_policy", "disco_ingest_trace", "disco_fit_lognormal",
-           "disco_device_profile", "disco_budget_search", "disco_read_probe", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
+           "disco_device_profile", "disco_budget_search", "disco_read_probe", "disco_time_token_walk", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
            "disco_version"]
 
 _lib.disco_strerror.restype = C.c_char_p
@@ -180,6 +180,9 @@ _lib.disco_solve_policy.argtypes = [C.POINTER(CTrace), C.POINTER(CSolveSpec), C.
                                     C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.disco_read_probe.restype = C.c_int32
 _lib.disco_read_probe.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+_lib.disco_time_token_walk.restype = C.c_int32
+_lib.disco_time_token_walk.argtypes = [C.POINTER(CTrace), C.POINTER(CTimeline), C.POINTER(CPolicy), C.c_int32, C.c_void_p,
+                                       C.c_size_t, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
 _lib.disco_budget_search.restype = C.c_int32
 _lib.disco_budget_search.argtypes = [C.POINTER(CTrace), C.POINTER(CCost), C.POINTER(CPolicy),
                                      C.POINTER(CSearchSpec), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -519,6 +522,17 @@ def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Te
                                   ws.numel(), _stream())
     _check(rc, "disco_budget_search")
     return {"out": out, "pol_out": pol_out, "policies": DevicePolicies(pol_out, n)}
+
+
+def disco_time_token_walk(trace: Trace, tau: float, kappa: float, policies, ws: torch.Tensor, reps: int = 10) -> tuple:
+    """(mean, minimum) duration in ms of the streaming token-walk kernel alone (HIP events; synchronises)."""
+    tl = CTimeline(tau, kappa, None, 0, 0)
+    cs = trace.c_struct()
+    mean, best = C.c_double(0.0), C.c_double(0.0)
+    rc = _lib.disco_time_token_walk(C.byref(cs), C.byref(tl), _policies(policies), len(policies), ws.data_ptr(), ws.numel(),
+                                    reps, C.byref(mean), C.byref(best), _stream())
+    _check(rc, "disco_time_token_walk")
+    return mean.value, best.value
 
 
 def disco_read_probe(buf: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:

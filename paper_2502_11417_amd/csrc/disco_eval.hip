@@ -606,6 +606,49 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
     return DISCO_OK;
 }
 
+// Measurement aid: the streaming token walk of disco_eval_migration, timed alone with HIP events on `stream`.
+extern "C" int32_t disco_time_token_walk(const disco_trace* trace, const disco_timeline_params* tl, const disco_policy* pol,
+                                         int32_t P, void* ws_, size_t ws_bytes, int32_t reps, double* mean_ms, double* min_ms,
+                                         void* stream_)
+{
+    int rc = check_trace(trace);
+    if (rc) return rc;
+    if (!tl || !pol || !mean_ms || !min_ms) return DISCO_ERR_NULL;
+    if (P < 1 || P > DISCO_MAX_COLS || reps < 1 || reps > 1000) return DISCO_ERR_SHAPE;
+    if (!(tl->tau > 0.0f) || !(tl->kappa_lag >= 0.0f)) return DISCO_ERR_RANGE;
+    if (trace->n_req <= 0 || !trace->tok_arr) return DISCO_ERR_CSR;          // the streaming walk reads a token array
+    rc = check_ws(ws_, ws_bytes, P);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = (char*)ws_;
+    const WsLayout L = disco_ws_layout(P);
+    if (ws_bytes < disco_ws_full_bytes(L, trace->n_req)) return DISCO_ERR_WORKSPACE;
+    const TraceView v = view_of(trace);
+    rc = stage_policies(pol, P, ws, L, stream);
+    if (rc) return rc;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    DISCO_HIP(hipEventCreate(&e0));
+    DISCO_HIP(hipEventCreate(&e1));
+    double sum = 0.0, best = 1e300;
+    for (int r = 0; r <= reps && rc == DISCO_OK; ++r) {          // the first run warms up and is not counted
+        disco_launch_tl_walk(v, trace->n_tok, (const disco_policy*)(ws + L.pol), P, tl->tau, tl->kappa_lag * tl->tau,
+                             (unsigned char*)(ws + L.total), ws + disco_ws_summary_offset(L, v.n_req), (unsigned*)(ws + L.wcount),
+                             stream, e0, e1);
+        hipError_t e = hipEventSynchronize(e1);
+        float ms = 0.0f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) { disco_set_hip_error(e, "timing the token walk"); rc = DISCO_ERR_HIP; }
+        if (r > 0) { sum += ms; if (ms < best) best = ms; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    *mean_ms = sum / reps;
+    *min_ms = best;
+    return DISCO_OK;
+}
+
 extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost_params* cost,
                                       const disco_timeline_params* tl, const disco_policy* pol, int32_t P,
                                       const disco_accum* acc, const disco_quantile* q, int32_t nq, disco_stats* out,

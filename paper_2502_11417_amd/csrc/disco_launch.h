@@ -85,7 +85,8 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
 // The token walk alone (flags, then one 16-byte summary per request), for a statistics call that was not handed
 // the summaries of the evaluation.
 void disco_launch_tl_walk(const TraceView& v, i64 n_tok, const disco_policy* pol, int P, float tau, float kt,
-                          unsigned char* wflags, void* summary, unsigned* counter, hipStream_t stream);
+                          unsigned char* wflags, void* summary, unsigned* counter, hipStream_t stream,
+                          hipEvent_t before = nullptr, hipEvent_t after = nullptr);
 void disco_launch_timeline_general(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                    hipStream_t stream);
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, const void* summary,

@@ -702,9 +702,11 @@ __global__ __launch_bounds__(256) void k_tl_mat(TraceView tr, const disco_policy
 
 }  // namespace
 
-// The token walk alone: flags, the streaming walk (traces with a token array), then what it leaves.
+// The token walk alone: flags, the streaming walk (traces with a token array), then what it leaves.  With
+// events, the streaming kernel's launch is bracketed by them (measurement aid).
 void disco_launch_tl_walk(const TraceView& v, i64 n_tok, const disco_policy* pol, int P, float tau, float kt,
-                          unsigned char* wflags, void* summary, unsigned* counter, hipStream_t stream)
+                          unsigned char* wflags, void* summary, unsigned* counter, hipStream_t stream,
+                          hipEvent_t before, hipEvent_t after)
 {
     if (v.n_req <= 0) return;
     i64 fb = (v.n_req + 255) / 256;
@@ -725,7 +727,9 @@ void disco_launch_tl_walk(const TraceView& v, i64 n_tok, const disco_policy* pol
         if (b > 2048) b = 2048;
         w.nqueue = b >= 2 * TW_QUEUES ? TW_QUEUES : 1;
         b -= b % w.nqueue;                         // every queue is served by the same number of workgroups
+        if (before) (void)hipEventRecord(before, stream);
         hipLaunchKernelGGL(k_tl_walk, dim3((unsigned)b), dim3(TW_BLOCK), 0, stream, v, n_tok, w);
+        if (after) (void)hipEventRecord(after, stream);
     } else {
         hipLaunchKernelGGL(k_tl_summary_clear, dim3((unsigned)fb), dim3(256), 0, stream, v.n_req, (TlSummary*)summary);
     }
@@ -738,7 +742,7 @@ void disco_launch_tl_walk(const TraceView& v, i64 n_tok, const disco_policy* pol
 void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                 MigPartial* totals, hipStream_t stream)
 {
-    disco_launch_tl_walk(v, n_tok, pol, a.P, a.tau, a.kt, a.wflags, a.summary, a.counter, stream);
+    disco_launch_tl_walk(v, n_tok, pol, a.P, a.tau, a.kt, a.wflags, a.summary, a.counter, stream, nullptr, nullptr);
     if (v.n_req > 0) {
         AccumArgs c;
         memset(&c, 0, sizeof(c));
