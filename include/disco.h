@@ -40,8 +40,8 @@ extern "C" {
 #define DISCO_OK              0
 #define DISCO_ERR_NULL      (-1)  /* a required pointer is NULL */
 #define DISCO_ERR_SHAPE     (-2)  /* negative or inconsistent sizes, P outside [1, DISCO_MAX_COLS] */
-#define DISCO_ERR_RANGE     (-3)  /* a parameter outside its documented range */
-#define DISCO_ERR_CSR       (-4)  /* token arrays required by the call are missing */
+#define DISCO_ERR_RANGE     (-3)  /* a parameter (or, disco_validate_trace, a trace value) outside its documented range */
+#define DISCO_ERR_CSR       (-4)  /* token arrays required by the call are missing (disco_validate_trace: inconsistent) */
 #define DISCO_ERR_WORKSPACE (-5)  /* workspace missing or smaller than disco_workspace_bytes() */
 #define DISCO_ERR_HIP       (-6)  /* a HIP runtime call failed; see disco_last_hip_error() */
 
@@ -149,6 +149,25 @@ typedef struct disco_raw_trace {
  * dropped before evaluation.  Asynchronous.  Errors: NULL, SHAPE, HIP. */
 int32_t disco_ingest_trace(const disco_raw_trace* raw /*host*/, disco_trace* trace /*host, device arrays*/, void* stream);
 
+/* Optional check of a trace's data before it is evaluated (the evaluation calls
+ * check pointers and sizes only and trust the arrays: offsets that do not
+ * match the output lengths make them read outside the token array).  One pass
+ * over the requests and, with check_tokens != 0 and a token array, one over
+ * the tokens.  SYNCHRONISES the stream and returns
+ *   DISCO_ERR_CSR    tok_off does not start at 0, decreases, does not end at
+ *                    n_tok (with a token array), or tok_off[i+1] - tok_off[i]
+ *                    != output_len[i];
+ *   DISCO_ERR_RANGE  a prompt length < 0, an output length < 1, a NaN,
+ *                    negative or infinite server TTFT, gap or device rate, or
+ *                    (tokens) an arrival offset that is NaN, negative, not 0
+ *                    for a request's first token or smaller than its predecessor;
+ *   DISCO_OK         otherwise.
+ * (A request without tokens, as disco_ingest_trace marks it, is a RANGE error:
+ * drop it first.)  ws: device, at least 256 bytes, 256-byte aligned.
+ * Other errors: NULL, SHAPE, WORKSPACE, HIP. */
+int32_t disco_validate_trace(const disco_trace* trace /*host, device arrays*/, int32_t check_tokens,
+                             void* ws /*device*/, size_t ws_bytes, void* stream);
+
 /* Log-normal law fitted "by the mean and standard deviation of the logarithm"
  * (Sec. 5.3): mu = mean of ln x, sigma = population standard deviation of
  * ln x, over the positive values of x (the others are counted in n_skipped);
@@ -228,6 +247,12 @@ typedef struct disco_cost_params {
     double e_pre, e_dec;     /* J per device prefill / decode token (linear in FLOPs) */
     double lambda;           /* $ per J */
 } disco_cost_params;
+
+/* Policy type (Alg. 1): *mode = DISCO_MODE_DEVICE_CONSTRAINED if the cheaper
+ * device token (lambda e_pre or lambda e_dec, in money) costs more than the
+ * dearer server token (cs_pre or cs_dec), else DISCO_MODE_SERVER_CONSTRAINED
+ * (equality included).  Host only.  Errors: NULL, RANGE (a NaN rate). */
+int32_t disco_policy_type(const disco_cost_params* cost /*host*/, int32_t* mode /*host*/);
 
 /* Pacing of the token buffer (Sec. 4.3): tokens leave the buffer no faster
  * than one per `tau` seconds (the user's consumption rate r_c = 1/tau); a
@@ -576,6 +601,11 @@ int32_t disco_read_probe(const void* src /*device*/, int64_t bytes, void* out64 
 int32_t disco_time_token_walk(const disco_trace* trace /*host*/, const disco_timeline_params* tl /*host*/,
                               const disco_policy* pol /*host or device*/, int32_t P, void* ws /*device*/, size_t ws_bytes,
                               int32_t reps, double* mean_ms /*host*/, double* min_ms /*host*/, void* stream);
+
+/* Testing aid: from now on the grids of the dispatch pass and of the token
+ * walk are divided by d (1 = the normal geometry) before launch, process-wide.
+ * Integer results must not depend on it.  Errors: RANGE (d outside [1, 1024]). */
+int32_t disco_set_grid_divisor(int32_t d);
 
 const char* disco_strerror(int32_t code);
 const char* disco_last_hip_error(void);   /* text of the last HIP failure seen by this thread */

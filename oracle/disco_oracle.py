@@ -295,6 +295,15 @@ def total_cost(cost: dict, s_pre, s_dec, d_pre, d_dec) -> float:
                                       cost["lam"], int(s_pre), int(s_dec), int(d_pre), int(d_dec)))
 
 
+def policy_type(cost: dict) -> int:
+    """Alg. 1: device-constrained (1) if both device token costs exceed both server token costs, else
+    server-constrained (0).  Device costs in money: lambda times the energy per token (Sec. 4.1)."""
+    cd_p, cd_d = cost["lam"] * cost["e_pre"], cost["lam"] * cost["e_dec"]
+    if min(cd_p, cd_d) > max(cost["cs_pre"], cost["cs_dec"]):
+        return 1
+    return 0
+
+
 def server_cost(cost: dict, s_pre, s_dec) -> float:
     return float(lib().orc_server_cost(cost["cs_pre"], cost["cs_dec"], int(s_pre), int(s_dec)))
 

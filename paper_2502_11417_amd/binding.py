@@ -132,7 +132,7 @@ assert C.sizeof(CPolicy) == 32 and C.sizeof(CSearchSpec) == 40
 
 EXPORTS = ["disco_gen_trace", "disco_eval_dispatch", "disco_eval_dispatch_static", "disco_eval_migration", "disco_reduce_stats",
            "disco_average_runs", "disco_solve_policy", "disco_ingest_trace", "disco_fit_lognormal",
-           "disco_device_profile", "disco_budget_search", "disco_read_probe", "disco_time_token_walk", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
+           "disco_device_profile", "disco_budget_search", "disco_read_probe", "disco_time_token_walk", "disco_validate_trace", "disco_set_grid_divisor", "disco_policy_type", "disco_workspace_bytes", "disco_strerror", "disco_last_hip_error",
            "disco_version"]
 
 _lib.disco_strerror.restype = C.c_char_p
@@ -183,6 +183,12 @@ _lib.disco_read_probe.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
 _lib.disco_time_token_walk.restype = C.c_int32
 _lib.disco_time_token_walk.argtypes = [C.POINTER(CTrace), C.POINTER(CTimeline), C.POINTER(CPolicy), C.c_int32, C.c_void_p,
                                        C.c_size_t, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
+_lib.disco_validate_trace.restype = C.c_int32
+_lib.disco_validate_trace.argtypes = [C.POINTER(CTrace), C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+_lib.disco_set_grid_divisor.restype = C.c_int32
+_lib.disco_set_grid_divisor.argtypes = [C.c_int32]
+_lib.disco_policy_type.restype = C.c_int32
+_lib.disco_policy_type.argtypes = [C.POINTER(CCost), C.POINTER(C.c_int32)]
 _lib.disco_budget_search.restype = C.c_int32
 _lib.disco_budget_search.argtypes = [C.POINTER(CTrace), C.POINTER(CCost), C.POINTER(CPolicy),
                                      C.POINTER(CSearchSpec), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -522,6 +528,24 @@ def disco_budget_search(trace: Trace, cost: dict, templates, specs, ws: torch.Te
                                   ws.numel(), _stream())
     _check(rc, "disco_budget_search")
     return {"out": out, "pol_out": pol_out, "policies": DevicePolicies(pol_out, n)}
+
+
+def disco_policy_type(cost: dict) -> int:
+    """MODE_D or MODE_S from the unified cost rates (Alg. 1)."""
+    cc, mode = _cost(cost), C.c_int32(-1)
+    _check(_lib.disco_policy_type(C.byref(cc), C.byref(mode)), "disco_policy_type")
+    return mode.value
+
+
+def disco_validate_trace(trace: Trace, check_tokens: bool = True, ws: torch.Tensor | None = None) -> int:
+    """0 if the trace's data are sound, else the (negative) code: ERR['csr'] or ERR['range'].  Other failures raise."""
+    if ws is None:
+        ws = torch.empty(256, dtype=torch.uint8, device=trace.prompt_len.device if trace.prompt_len is not None else "cuda")
+    cs = trace.c_struct()
+    rc = _lib.disco_validate_trace(C.byref(cs), 1 if check_tokens else 0, ws.data_ptr(), ws.numel(), _stream())
+    if rc not in (0, ERR["csr"], ERR["range"]):
+        _check(rc, "disco_validate_trace")
+    return rc
 
 
 def disco_time_token_walk(trace: Trace, tau: float, kappa: float, policies, ws: torch.Tensor, reps: int = 10) -> tuple:

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdisco.so")
-SOURCES = ["disco_gen.hip", "disco_eval.hip", "disco_dispatch.hip", "disco_ttft.hip", "disco_timeline.hip", "disco_tlfast.hip", "disco_tlwalk.hip", "disco_tlsel.hip", "disco_tlbuf.hip", "disco_solve.hip", "disco_ingest.hip", "disco_probe.hip"]
+SOURCES = ["disco_gen.hip", "disco_eval.hip", "disco_dispatch.hip", "disco_ttft.hip", "disco_timeline.hip", "disco_tlfast.hip", "disco_tlwalk.hip", "disco_tlsel.hip", "disco_tlbuf.hip", "disco_solve.hip", "disco_ingest.hip", "disco_probe.hip", "disco_validate.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

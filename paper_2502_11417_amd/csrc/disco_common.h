@@ -16,6 +16,10 @@ void disco_set_hip_error(hipError_t e, const char* what);
         }                                                 \
     } while (0)
 
+// Testing aid: every grid of the dispatch pass and of the token walk is divided by this (>= 1) before launch, so
+// that a test can run the same input under two launch geometries and compare the results bit for bit.
+int disco_grid_divisor();
+
 // Launch geometry shared by the streaming kernels.
 enum {
     DISCO_BLOCK = 256,           // threads per workgroup (4 waves)

@@ -652,8 +652,9 @@ __global__ __launch_bounds__(1024) void k_len_suffix(int nbins, u64* table, u64*
 unsigned dispatch_blocks(i64 units, i64 per_block)
 {
     i64 b = (units + per_block - 1) / per_block;
-    if (b < 1) b = 1;
     if (b > DP_MAX_BLOCKS) b = DP_MAX_BLOCKS;
+    b /= disco_grid_divisor();
+    if (b < 1) b = 1;
     return (unsigned)b;
 }
 

@@ -454,6 +454,26 @@ extern "C" const char* disco_strerror(int32_t code)
 }
 
 extern "C" const char* disco_last_hip_error(void) { return g_hip_error; }
+
+// Alg. 1: the policy type from the unified cost rates (device costs in money = lambda x energy per token).
+extern "C" int32_t disco_policy_type(const disco_cost_params* c, int32_t* mode)
+{
+    if (!c || !mode) return DISCO_ERR_NULL;
+    const double cd_p = c->lambda * c->e_pre, cd_d = c->lambda * c->e_dec;
+    const double dev_min = cd_p < cd_d ? cd_p : cd_d, srv_max = c->cs_pre > c->cs_dec ? c->cs_pre : c->cs_dec;
+    if (dev_min != dev_min || srv_max != srv_max || c->cs_pre != c->cs_pre || c->cs_dec != c->cs_dec) return DISCO_ERR_RANGE;
+    *mode = dev_min > srv_max ? DISCO_MODE_DEVICE_CONSTRAINED : DISCO_MODE_SERVER_CONSTRAINED;
+    return DISCO_OK;
+}
+
+static int g_grid_divisor = 1;
+int disco_grid_divisor() { return g_grid_divisor; }
+extern "C" int32_t disco_set_grid_divisor(int32_t d)
+{
+    if (d < 1 || d > 1024) return DISCO_ERR_RANGE;
+    g_grid_divisor = d;
+    return DISCO_OK;
+}
 extern "C" int32_t disco_version(void) { return 100; }
 
 extern "C" int32_t disco_eval_dispatch(const disco_trace* trace, const disco_policy* pol, int32_t P,

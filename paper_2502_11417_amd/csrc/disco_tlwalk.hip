@@ -723,8 +723,9 @@ void disco_launch_tl_walk(const TraceView& v, i64 n_tok, const disco_policy* pol
         w.rb = tl_batch(v.n_req, waves);
         const i64 per_block = (i64)TW_WAVES * w.rb;
         i64 b = (v.n_req + per_block - 1) / per_block;
-        if (b < 1) b = 1;
         if (b > 2048) b = 2048;
+        b /= disco_grid_divisor();
+        if (b < 1) b = 1;
         w.nqueue = b >= 2 * TW_QUEUES ? TW_QUEUES : 1;
         b -= b % w.nqueue;                         // every queue is served by the same number of workgroups
         if (before) (void)hipEventRecord(before, stream);
@@ -752,8 +753,9 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
         c.summary = (const TlSummary*)a.summary;
         c.totals = totals;
         i64 b = ((v.n_req + 63) / 64 + TA_WAVES - 1) / TA_WAVES;
-        if (b < 1) b = 1;
         if (b > 256) b = 256;
+        b /= disco_grid_divisor();
+        if (b < 1) b = 1;
         hipLaunchKernelGGL(k_tl_accum, dim3((unsigned)b), dim3(TA_BLOCK), 0, stream, v, pol, c);
         if (a.mig_idx || a.n_src_tok || a.t_last || a.delay_num) {
             MatArgs m;

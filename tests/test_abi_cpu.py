@@ -134,3 +134,61 @@ def test_device_profiles_match_the_printed_speeds(B):
     assert B._lib.disco_fit_lognormal(None, 0, 5, 256, 256, 1 << 30, None) == B.ERR["null"]
     assert B._lib.disco_fit_lognormal(256, 7, 5, 256, 256, 1 << 30, None) == B.ERR["range"]
     assert B._lib.disco_ingest_trace(None, None, None) == B.ERR["null"]
+
+
+def test_new_entry_points_reject_bad_arguments_on_the_host(B):
+    """disco_validate_trace, disco_time_token_walk, disco_read_probe, disco_policy_type, disco_set_grid_divisor:
+    everything that can be refused without touching a GPU is refused before anything is launched."""
+    import disco_inputs as DI
+    lib = B._lib
+    tr = B.CTrace()
+    # validation
+    assert lib.disco_validate_trace(None, 1, 256, 256, None) == B.ERR["null"]
+    tr.n_req = -1
+    assert lib.disco_validate_trace(C.byref(tr), 1, 256, 256, None) == B.ERR["shape"]
+    tr.n_req = 4
+    assert lib.disco_validate_trace(C.byref(tr), 1, 256, 256, None) == B.ERR["null"]            # arrays missing
+    tr.n_req = 0
+    assert lib.disco_validate_trace(C.byref(tr), 1, None, 256, None) == B.ERR["workspace"]
+    assert lib.disco_validate_trace(C.byref(tr), 1, 256, 16, None) == B.ERR["workspace"]
+    assert lib.disco_validate_trace(C.byref(tr), 1, 260, 1024, None) == B.ERR["workspace"]      # misaligned
+    tr.dev_ttft_c = float("nan")
+    assert lib.disco_validate_trace(C.byref(tr), 1, 256, 256, None) == B.ERR["range"]
+    tr.dev_ttft_c = 0.0
+    tr.dev_pre_spt_s = -1.0
+    assert lib.disco_validate_trace(C.byref(tr), 1, 256, 256, None) == B.ERR["range"]
+    tr.dev_pre_spt_s = 0.0
+    tr.tok_arr = 512                                                                            # token array without offsets
+    assert lib.disco_validate_trace(C.byref(tr), 1, 256, 256, None) == B.ERR["csr"]
+    tr.tok_arr = None
+    assert lib.disco_validate_trace(C.byref(tr), 1, 256, 256, None) == 0                        # an empty trace is sound
+    # timing aid
+    pol = (B.CPolicy * 1)(B.CPolicy(0, 0, -1, 0.0, float("inf"), float("inf"), 1, 0))
+    tl = B.CTimeline(0.2, 3.0, None, 0, 0)
+    a, b = C.c_double(0), C.c_double(0)
+    assert lib.disco_time_token_walk(C.byref(tr), C.byref(tl), pol, 1, 256, 1 << 30, 5, None, None, None) == B.ERR["null"]
+    assert lib.disco_time_token_walk(C.byref(tr), C.byref(tl), pol, 1, 256, 1 << 30, 0, C.byref(a), C.byref(b), None) == B.ERR["shape"]
+    assert lib.disco_time_token_walk(C.byref(tr), C.byref(tl), pol, 1, 256, 1 << 30, 5, C.byref(a), C.byref(b), None) == B.ERR["csr"]
+    # read probe
+    assert lib.disco_read_probe(None, 1024, 256, None) == B.ERR["null"]
+    assert lib.disco_read_probe(256, 1000, 256, None) == B.ERR["shape"]                         # not a multiple of 16
+    assert lib.disco_read_probe(264, 1024, 256, None) == B.ERR["shape"]                         # misaligned
+    assert lib.disco_read_probe(256, 0, 256, None) == 0
+    # policy type (Alg. 1)
+    assert B.disco_policy_type(DI.COST_S) == B.MODE_S and B.disco_policy_type(DI.COST_D) == B.MODE_D
+    assert B.disco_policy_type(dict(DI.COST_S, lam=DI.COST_S["cs_pre"] / DI.COST_S["e_pre"])) == B.MODE_S     # equality
+    assert lib.disco_policy_type(None, None) == B.ERR["null"]
+    nan = B.CCost(float("nan"), 1, 1, 1, 1)
+    m = C.c_int32(0)
+    assert lib.disco_policy_type(C.byref(nan), C.byref(m)) == B.ERR["range"]
+    # grid divisor
+    assert lib.disco_set_grid_divisor(0) == B.ERR["range"] and lib.disco_set_grid_divisor(2000) == B.ERR["range"]
+    assert lib.disco_set_grid_divisor(1) == 0
+
+
+def test_policy_type_agrees_with_the_oracle(B, oracle):
+    import itertools
+    vals = (0.5, 1.0, 2.0, 3.0)
+    for cs_pre, cs_dec, e_pre, e_dec, lam in itertools.product(vals, vals, vals, vals, (0.5, 1.0, 1.5)):
+        cost = {"cs_pre": cs_pre, "cs_dec": cs_dec, "e_pre": e_pre, "e_dec": e_dec, "lam": lam}
+        assert B.disco_policy_type(cost) == oracle.policy_type(cost), cost

@@ -144,8 +144,11 @@ def test_workload3_full_size(B, oracle):
 
 @pytest.mark.timeout(600)
 def test_workload4_full_size(B, oracle):
-    """10^6 requests x 8 levels, 4.9e8 token events.  Request-level results against the oracle in full;
-    token-level results against the oracle on sampled requests, totals and order statistics by properties."""
+    """10^6 requests x 8 levels, 4.9e8 token events, in the benchmark's launch configuration.  Request-level results
+    against the oracle in full; token-level results against the oracle on sampled requests (hand-off index, source
+    tokens and last delivery in all eight columns, every delivery of the all-race column), totals and order
+    statistics by properties.  The class-mode TBT selection is compared with the oracle itself on a contiguous slice
+    of the same recipe in test_workload4_slice_against_the_oracle."""
     print("full size: workload 4", flush=True)
     cfg = DI.config(4)
     tau, kappa, P = cfg["tau"], cfg["kappa"], cfg["levels"]
@@ -158,9 +161,16 @@ def test_workload4_full_size(B, oracle):
     dpol, opol, sacc = _levels_search(B, oracle, cfg, tr, dt, 1)
     ws = B.workspace(N, P)
     r = {"acc": sacc}
-    mg = B.disco_eval_migration(dt, tau, kappa, dpol, materialise=True, delivered_col=0, ws=ws, acc=r["acc"])
+    # the benchmark's launch configuration: streaming token walk (per-pair outputs from its summaries), then the
+    # statistics starting from what the walk left in the workspace
+    mg = B.disco_eval_migration(dt, tau, kappa, dpol, materialise=True, ws=ws, acc=r["acc"])
     acc = B.accum_to_host(r["acc"], P)
-    got = B.stats_to_host(B.disco_reduce_stats(dt, cfg["cost"], dpol, r["acc"], tau=tau, kappa=kappa, ws=ws), P)
+    got = B.stats_to_host(B.disco_reduce_stats(dt, cfg["cost"], dpol, r["acc"], tau=tau, kappa=kappa, ws=ws, reuse_walk=True), P)
+    # ... and once more walking the tokens again: the same statistics
+    got2 = B.stats_to_host(B.disco_reduce_stats(dt, cfg["cost"], dpol, r["acc"], tau=tau, kappa=kappa, ws=ws), P)
+    assert got.tobytes() == got2.tobytes()
+    # per-token deliveries of the all-race column (the general kernel): server-sourced and migrated timelines
+    mg["delivered"] = B.disco_eval_migration(dt, tau, kappa, dpol, materialise=False, delivered_col=P - 1, ws=ws)["delivered"]
     torch.cuda.synchronize()
 
     # (1) request-level: dispatch totals and TTFT statistics of every column, whole
@@ -197,7 +207,9 @@ def test_workload4_full_size(B, oracle):
            "dev_pre_spt_s": 0.0, "dev_dec_spt_s": 0.0, "dev_ttft_c": 0.0}
     for name in ("prompt_len", "output_len", "srv_ttft", "srv_tbt", "dev_pre_spt", "dev_dec_spt"):
         sub[name] = np.ascontiguousarray(tr[name][picks])
-    want_m = oracle.migration(sub, opol, tau, kappa, materialise=True, tbt_col=0, want_delivered=True)
+    want_m = oracle.migration(sub, opol, tau, kappa, materialise=True, tbt_col=P - 1, want_delivered=True)
+    sub_dec = oracle.dispatch(sub, opol, materialise=True)["decision"][P - 1]
+    assert ((sub_dec & 4) == 0).sum() > 500, "the sampled deliveries must cover server-sourced timelines"
     pk = torch.from_numpy(picks).cuda()
     for name in ("mig_idx", "n_src_tok", "t_last"):
         assert_same_bits(mg[name][:, pk].cpu().numpy(), want_m[name], name)
@@ -237,9 +249,11 @@ def test_workload4_full_size(B, oracle):
     print("full size: workload 4 order statistics", flush=True)
     starts = torch.from_numpy(tr["tok_off"][:-1]).cuda()
     for j in range(P):
-        if j > 0:
+        if j < P - 1:
             mj = B.disco_eval_migration(dt, tau, kappa, dpol, materialise=False, delivered_col=j, ws=ws)
             deliv = mj["delivered"]
+        else:
+            deliv = mg["delivered"]
         gaps = deliv[1:] - deliv[:-1]
         keep = torch.ones(T - 1, dtype=torch.bool, device="cuda")
         keep[starts[1:] - 1] = False          # the difference across a request boundary is no gap
@@ -253,3 +267,32 @@ def test_workload4_full_size(B, oracle):
             assert below < k <= upto, (j, qi, below, k, upto)
         del gaps, keep
         print(f"full size: workload 4 column {j} done", flush=True)
+
+
+@pytest.mark.timeout(600)
+def test_workload4_slice_against_the_oracle(B, oracle):
+    """The first 50 000 requests of workload 4 (2.4e7 token events: requests of many 256-token iterations, the
+    two-round TTFT buckets, eight columns of nested classes), evaluated whole by the oracle: thresholds, every
+    total, and the rank and bit pattern of every TTFT and TBT order statistic of all eight columns, through the
+    same sequence of calls as the benchmark's step."""
+    print("workload 4, 50k-request slice: GPU", flush=True)
+    cfg = DI.config(4, n_req=50_000)
+    tau, kappa, P = cfg["tau"], cfg["kappa"], cfg["levels"]
+    tr = oracle.gen_trace(cfg["gen"])
+    dt = B.disco_gen_trace(cfg["gen"])
+    assert dt.n_tok == tr["n_tok"]
+    assert_same_bits(dt.tok_arr.cpu().numpy(), tr["tok_arr"], "tok_arr")
+    dpol, opol, acc = _levels_search(B, oracle, cfg, tr, dt, 1)
+    ws = B.workspace(dt.n_req, P)
+    mg = B.disco_eval_migration(dt, tau, kappa, dpol, materialise=True, ws=ws, acc=acc)
+    got = B.stats_to_host(B.disco_reduce_stats(dt, cfg["cost"], dpol, acc, tau=tau, kappa=kappa, ws=ws, reuse_walk=True), P)
+    print("workload 4, 50k-request slice: oracle", flush=True)
+    want_m = oracle.migration(tr, opol, tau, kappa, materialise=True)
+    for name in ("mig_idx", "n_src_tok", "t_last"):
+        assert_same_bits(mg[name].cpu().numpy(), want_m[name], name)
+    want = oracle.stats(tr, opol, cfg["cost"], tau=tau, kappa=kappa)
+    _compare_stats(got, want, True)
+    assert want[P - 1]["n_migrated"] > 300 and want[0]["n_migrated"] == 0
+    for j in range(P):
+        assert int(got[j]["s_dec"]) == want[j]["s_dec"] and int(got[j]["d_dec"]) == want[j]["d_dec"], j
+        assert int(got[j]["d_pre"]) == want[j]["d_pre"], j

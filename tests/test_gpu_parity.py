@@ -300,6 +300,37 @@ def test_config0_end_to_end(B, oracle):
     assert want[0]["s_pre"] == 0 and want[-1]["s_pre"] == total
 
 
+def test_config0_device_constrained_sweep(B, oracle):
+    """Workload 0 with its 16 budget levels read as device-constrained columns: one global wait per level, bisected
+    so that the device's share of the prompt tokens meets b_j (Sec. 4.2), then every statistic incl. timelines."""
+    print("config0 device-constrained sweep", flush=True)
+    cfg = DI.config(0)
+    tr = oracle.gen_trace(cfg["gen"])
+    dt = B.disco_gen_trace(cfg["gen"])
+    levels = DI.budget_levels(cfg["levels"])
+    total = int(tr["prompt_len"].astype(np.int64).sum())
+    templ = [B.Policy(mode=1, l_th=-1, mig_mode=1) for _ in levels]
+    specs = [dict(which_param=B.PARAM_W_TAIL, which_acc="device_prefill_tok", n_steps=24, lo=0.0, hi=128.0,
+                  target=num * total / den) for num, den in levels]
+    res = B.disco_budget_search(dt, DI.COST_D, templ, specs)
+    so = B.search_to_host(res["out"], len(levels))
+    found = B.policies_to_host(res["pol_out"], len(levels))
+    waits = []
+    for j, (num, den) in enumerate(levels):
+        w, hp, ha = oracle.search_wait(tr, oracle.Policy(mode=1, l_th=-1), 0.0, 128.0, 24, "device_prefill_tok", DI.COST_D,
+                                       num * total / den)
+        assert np.float32(so["param"][j]) == w == np.float32(found[j].w_tail), j
+        assert (so["hist_param"][j][:24].astype(np.float32) == hp).all() and (so["hist_acc"][j][:24] == ha).all(), j
+        waits.append(float(w))
+    assert float(tr["srv_ttft"].max()) < 128.0 and waits[0] == 128.0      # no budget: wait out every server
+    assert all(a >= b for a, b in zip(waits, waits[1:])) and waits[-1] < 1e-4    # full budget: start (almost) at once
+    pol_specs = [dict(mode=1, l_th=-1, w_tail=w, mig_mode=1) for w in waits]
+    tr_host = dict(tr, tok_arr=None)
+    got, want = check_stats(B, oracle, tr_host, pol_specs, DI.COST_D, tau=cfg["tau"], kappa=cfg["kappa"])
+    assert all(want[j]["d_pre"] <= num * total / den for j, (num, den) in enumerate(levels))
+    assert oracle.policy_type(DI.COST_D) == 1
+
+
 # ----------------------------------------------------------- budget search
 
 def test_wait_search_history_is_bit_identical(B, oracle):

@@ -307,3 +307,18 @@ def test_stats_assembly(oracle, tr0):
         assert st[j]["ttft_q"][0] == np.sort(dp["ttft"][j])[math.ceil(0.5 * tr0["n_req"]) - 1]
         assert st[j]["ttft_q"][1] == np.sort(dp["ttft"][j])[math.ceil(0.99 * tr0["n_req"]) - 1]
         assert st[j]["total_cost"] == pytest.approx(st[j]["server_cost"] + DI.COST_S["lam"] * st[j]["device_energy"], rel=1e-15)
+
+
+def test_policy_type_follows_alg1(oracle):
+    """Alg. 1: device-constrained iff min(device prefill, decode cost) > max(server prefill, decode cost); the two
+    exchange rates of the workloads put a device token at 0.3 and at 5 server tokens (App. E)."""
+    import disco_inputs as DI
+    assert oracle.policy_type(DI.COST_S) == 0 and oracle.policy_type(DI.COST_D) == 1
+    base = {"cs_pre": 2.0, "cs_dec": 3.0, "e_pre": 1.0, "e_dec": 1.0, "lam": 1.0}
+    # all four orderings of the cheaper device token against the dearer server token, and the boundary
+    assert oracle.policy_type(dict(base, e_pre=4.0, e_dec=5.0)) == 1        # both device tokens dearer than both server tokens
+    assert oracle.policy_type(dict(base, e_pre=2.5, e_dec=5.0)) == 0        # device prefill cheaper than server decode
+    assert oracle.policy_type(dict(base, e_pre=5.0, e_dec=2.5)) == 0        # device decode cheaper than server decode
+    assert oracle.policy_type(dict(base, e_pre=3.0, e_dec=3.0)) == 0        # equality is not "greater": server-constrained
+    assert oracle.policy_type(dict(base, e_pre=3.0, e_dec=3.0, lam=1.0 + 1e-9)) == 1
+    assert oracle.policy_type(dict(base, e_pre=4.0, e_dec=5.0, lam=0.5)) == 0     # the exchange rate scales the device side only
