@@ -427,8 +427,9 @@ typedef struct disco_quantile { int32_t num, den; } disco_quantile;   /* q = num
  * tl != NULL: acc must also hold disco_eval_migration's block; decode and
  *   re-prefill tokens come from it and TBT statistics are produced.
  * out: device, P entries.  Asynchronous.
- * Errors: NULL, SHAPE (nq outside [0, DISCO_MAX_Q]), RANGE (den <= 0, num
- * outside [0, den]), WORKSPACE, HIP. */
+ * Errors: NULL, SHAPE (nq outside [0, DISCO_MAX_Q]; TBT quantiles over more
+ * than 2^32 - 1 requests), RANGE (den <= 0, num outside [0, den]), WORKSPACE,
+ * HIP. */
 int32_t disco_reduce_stats(const disco_trace* trace /*host*/, const disco_cost_params* cost /*host*/,
                            const disco_timeline_params* tl /*host, nullable*/,
                            const disco_policy* pol /*host*/, int32_t P,
@@ -571,9 +572,10 @@ int32_t disco_budget_search(const disco_trace* trace /*host*/, const disco_cost_
 /* ---- helpers ------------------------------------------------------------ */
 
 /* Bytes of device workspace for n_req requests and P columns (or searches):
- * about 47 MB plus 17 bytes per request.  The per-request part (one byte that
+ * about 47 MB plus 25 bytes per request.  The per-request part (one byte that
  * the TTFT selection and the token walk use between their passes, 16 bytes of
- * what the token walk found) is needed by disco_eval_migration and by
+ * what the token walk found, 8 bytes of the TBT selection) is needed by
+ * disco_eval_migration and by
  * disco_reduce_stats with timelines; every other call accepts a workspace of
  * disco_workspace_bytes(0, P) bytes.  The workspace holds partial results
  * only; its contents need not be initialised or preserved between calls

@@ -684,6 +684,7 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
         if (q[i].den <= 0 || q[i].num < 0 || q[i].num > q[i].den) return DISCO_ERR_RANGE;
     if (tl && (!(tl->tau > 0.0f) || !(tl->kappa_lag >= 0.0f))) return DISCO_ERR_RANGE;
     if (tl && trace->n_req > 0 && !trace->tok_arr && !trace->srv_tbt) return DISCO_ERR_CSR;
+    if (tl && nq > 0 && trace->n_req > 0xFFFFFFFFll) return DISCO_ERR_SHAPE;     // the walk list holds 32-bit request indices
     rc = check_ws(ws_, ws_bytes, P);
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)stream_;
@@ -730,6 +731,10 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
                 disco_launch_tl_walk(v, trace->n_tok, dpol, P, a.tau, a.kt, a.wflags, a.summary, a.counter, stream);
             disco_launch_tl_classify(v, dpol, P, nq, tl->tau, a.summary, S, a.ppcnt, gh, a.dhist, (u64*)(ws + L.slices),
                                      (unsigned*)(ws + L.ticket), stream);
+            a.desc = (unsigned*)(ws + disco_ws_desc_offset(L, v.n_req));
+            a.list = a.desc + v.n_req;
+            disco_launch_tl_assign(v, dpol, P, a.summary, S, a.desc, a.list, (unsigned*)(ws + L.slices), L.total - L.slices,
+                                   a.ppcnt, stream);
             for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;
                 disco_launch_tl_hist_fast(v, trace->n_tok, dpol, a, stream);

@@ -99,7 +99,7 @@ struct TlSel {
     unsigned key_lo;
     int window;                    // key bits of the window, 0 = raw 31-bit keys
     int restart;
-    int pad1;
+    unsigned nlist;                // requests with a timeline whose tokens are walked (entries of the walk list)
     signed char cls_slot[DISCO_MAX_CLS];     // row of a walked class in the workgroups' LDS histogram, -1 otherwise
     unsigned char slot_cls[DISCO_MAX_CLS];   // class of an LDS row
 };

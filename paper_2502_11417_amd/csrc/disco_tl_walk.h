@@ -114,6 +114,8 @@ struct HistArgs {
     unsigned* ghist;
     unsigned* ppcnt;
     const TlSummary* summary;      // per request, from the token walk
+    const unsigned* desc;          // per request: LDS rows of its timelines that have tokens to walk
+    const unsigned* list;          // requests with such a timeline (TlSel::nlist entries, any order)
 };
 
 // Digit of this pass and the rows of the LDS histogram.

@@ -164,74 +164,183 @@ __device__ __forceinline__ void load_first(const float* __restrict__ arr, i64 of
 
 // ------------------------------------------------------------- histogram ---
 
-__global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok, int align, const disco_policy* __restrict__ pol,
-                                                      HistArgs a)
+// What every histogram pass needs to know of a request, worked out once per selection (k_tl_assign): the LDS
+// row of each of its three timelines (device source, server source, server source with the lag trigger; one byte
+// each, 0xFF = nothing to walk: no such timeline, or one that is histogrammed analytically).
+constexpr unsigned DESC_NONE = 0xFFFFFFu;
+
+// Analytic timelines per class and length, counted per workgroup in LDS (two 16-bit counts per word, a workgroup
+// sees at most 65535 requests) for the first PP_LDS_CLS classes and stored as one slice per workgroup; classes
+// beyond that (tables of many columns) are counted in device memory directly.
+constexpr int PP_LDS_CLS = 16;
+constexpr int PP_WORDS = DISCO_PP_NMAX / 2 + 1;              // words per class: lengths 0 .. DISCO_PP_NMAX
+constexpr int AS_BLOCK = 1024;
+
+__global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disco_policy* __restrict__ pol, int P,
+                                                        const TlSummary* __restrict__ summary, SelState* S,
+                                                        unsigned* __restrict__ desc_out, unsigned* __restrict__ list,
+                                                        unsigned* __restrict__ slices, unsigned* __restrict__ ppcnt,
+                                                        int use_lds)
 {
-    __shared__ __align__(16) unsigned smem[DISCO_TL_HIST_WORDS];
+    __shared__ unsigned cnt[PP_LDS_CLS * PP_WORDS];          // 128 KB
+    __shared__ unsigned s_nw, s_base;
     __shared__ u64 s_cls[DISCO_MAX_CLS];
     __shared__ signed char s_slot[DISCO_MAX_CLS];
     __shared__ disco_policy spol[DISCO_MAX_COLS];
+    const TlSel* tl = &S->tl;
+    if (tl->fallback) return;                                // per-slot histograms: the general kernel walks everything
+    const int ncls = tl->ncls;
+    const int nlds = use_lds ? (ncls < PP_LDS_CLS ? ncls : PP_LDS_CLS) : 0;
+    if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
+    if (threadIdx.x < DISCO_MAX_CLS) { s_cls[threadIdx.x] = tl->cls_mask[threadIdx.x]; s_slot[threadIdx.x] = tl->cls_slot[threadIdx.x]; }
+    for (int i = threadIdx.x; i < nlds * PP_WORDS; i += AS_BLOCK) cnt[i] = 0u;
+    if (threadIdx.x == 0) s_nw = 0u;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    // a contiguous share of the requests per workgroup (at most 65535, see the launch)
+    const i64 per = (tr.n_req + gridDim.x - 1) / gridDim.x;
+    const i64 lo = (i64)blockIdx.x * per;
+    const i64 hi = lo + per < tr.n_req ? lo + per : tr.n_req;
+    for (i64 i = lo + threadIdx.x; i < hi; i += AS_BLOCK) {
+        const int l = tr.l[i], n = tr.n[i];
+        const float s = tr.s[i];
+        const float k = tr.k ? tr.k[i] : tr.k_s;
+        const TlSummary sm = summary[i];
+        u64 m[TL_KINDS];
+        request_sets(spol, P, l, s, __fmaf_rn((float)l, k, tr.c), i, m);
+        unsigned desc = DESC_NONE;
+#pragma unroll
+        for (int kind = 0; kind < 3; ++kind) {
+            if (m[kind] == 0ull) continue;
+            const int c = cls_find(s_cls, ncls, m[kind]);
+            if (c < 0) { S->tl.error = 1; continue; }        // a set the classification did not see: never expected
+            if (timeline_is_analytic(kind, n, sm)) {
+                if (c < nlds) atomicAdd(&cnt[c * PP_WORDS + (n >> 1)], 1u << (16 * (n & 1)));
+                else atomicAdd(&ppcnt[(size_t)c * (DISCO_PP_NMAX + 1) + n], 1u);
+            } else {
+                const int sl = s_slot[c];
+                if (sl < 0) { S->tl.error = 1; continue; }
+                desc = (desc & ~(0xFFu << (8 * kind))) | ((unsigned)sl << (8 * kind));
+            }
+        }
+        desc_out[i] = desc;
+        const u64 wb = __ballot(desc != DESC_NONE);
+        if (wb && lane == __ffsll((long long)wb) - 1) atomicAdd(&s_nw, (unsigned)__popcll(wb));
+    }
+    __syncthreads();
+    // the requests with tokens to walk go to a device-wide list (any order: the histograms are sums), a range of it
+    // per workgroup
+    const unsigned nw = s_nw;
+    __syncthreads();
+    if (threadIdx.x == 0) { s_base = nw ? atomicAdd(&S->tl.nlist, nw) : 0u; s_nw = 0u; }
+    __syncthreads();
+    if (nw) {
+        for (i64 i = lo + threadIdx.x; i < hi; i += AS_BLOCK) {
+            const bool w = desc_out[i] != DESC_NONE;            // this thread's own store
+            const u64 wb = __ballot(w);
+            if (!wb) continue;
+            const int leader = __ffsll((long long)wb) - 1;
+            unsigned at = 0u;
+            if (lane == leader) at = atomicAdd(&s_nw, (unsigned)__popcll(wb));
+            at = (unsigned)bcast_i((int)at, leader);
+            if (w) list[s_base + at + (unsigned)__popcll(wb & ((1ull << lane) - 1ull))] = (unsigned)i;
+        }
+    }
+    unsigned* mine = slices + (size_t)blockIdx.x * PP_LDS_CLS * PP_WORDS;
+    for (int i = threadIdx.x; i < nlds * PP_WORDS; i += AS_BLOCK) mine[i] = cnt[i];
+}
+
+// ppcnt[c][n] += sum over the workgroup slices.  Workgroup = (class, 256 words of two lengths each); four groups
+// of threads share the slices and meet in LDS.
+__global__ __launch_bounds__(1024) void k_pp_reduce(const SelState* S, int nslices, const unsigned* __restrict__ slices,
+                                                    unsigned* __restrict__ ppcnt, int use_lds)
+{
+    __shared__ unsigned part[2][1024];
+    const TlSel* tl = &S->tl;
+    const int c = blockIdx.x;
+    if (tl->fallback || !use_lds || c >= tl->ncls || c >= PP_LDS_CLS) return;
+    const int w = blockIdx.y * 256 + (threadIdx.x & 255), grp = threadIdx.x >> 8;
+    unsigned even = 0u, odd = 0u;
+    if (w < PP_WORDS) {
+#pragma unroll 8
+        for (int b = grp; b < nslices; b += 4) {
+            const unsigned v = slices[((size_t)b * PP_LDS_CLS + c) * PP_WORDS + w];
+            even += v & 0xFFFFu; odd += v >> 16;
+        }
+    }
+    part[0][threadIdx.x] = even; part[1][threadIdx.x] = odd;
+    __syncthreads();
+    if (grp == 0 && w < PP_WORDS) {
+        for (int g = 1; g < 4; ++g) { even += part[0][threadIdx.x + 256 * g]; odd += part[1][threadIdx.x + 256 * g]; }
+        unsigned* row = ppcnt + (size_t)c * (DISCO_PP_NMAX + 1);
+        if (even) row[2 * w] += even;
+        if (odd && 2 * w + 1 <= DISCO_PP_NMAX) row[2 * w + 1] += odd;
+    }
+}
+
+// One histogram pass of the class-mode TBT selection: the descriptors say which timelines have tokens to walk
+// (few: the others were counted analytically once) and the walk list names their requests.
+__global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok, int align, HistArgs a)
+{
+    __shared__ __align__(16) unsigned smem[DISCO_TL_HIST_WORDS];
     const TlSel* tl = &a.S->tl;
     const int width = tl->width;
     if (width <= 0 || tl->fallback) return;       // selection finished, or per-slot histograms (other kernel)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int P = a.P, ncls = tl->ncls, nwalk = tl->nwalk;
+    const int ncls = tl->ncls, nwalk = tl->nwalk;
     HistCtx h;
     h.hist = smem; h.width = width; h.shift = tl->shift; h.up = h.shift + width;
     h.G = tl->G < DISCO_MAX_GRP ? tl->G : DISCO_MAX_GRP;
     h.stride = (unsigned)nwalk << width;
     h.key_lo = tl->key_lo; h.key_cap = tl->window ? (1u << tl->window) : 0xFFFFFFFFu;
     for (int k = 0; k < DISCO_MAX_GRP; ++k) h.grp_prefix[k] = tl->grp_prefix[k];
-    if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
-    if (threadIdx.x < DISCO_MAX_CLS) { s_cls[threadIdx.x] = tl->cls_mask[threadIdx.x]; s_slot[threadIdx.x] = tl->cls_slot[threadIdx.x]; }
     const int words = (h.G * nwalk) << width;
     for (int i = threadIdx.x; i < words; i += TH_BLOCK) smem[i] = 0u;
     __syncthreads();
     const float tau = a.tau, kt = a.kt;
     const bool mem = tr.arr != nullptr;
-    const bool count_pp = a.pass == 0;
+    // the walk list is shared out in batches of rb entries (lane = entry) so that every wave gets some
     const i64 nwaves = (i64)gridDim.x * (TH_BLOCK / 64);
-    const int rb = a.rb;
-    const i64 nbatch = (tr.n_req + rb - 1) / rb;
-    for (i64 bt = (i64)blockIdx.x * (TH_BLOCK / 64) + wave; bt < nbatch; bt += nwaves) {
-        const Batch b = load_batch(tr, spol, P, bt * rb, lane, rb, a.summary);
-        // lane = request: LDS row of each of the three timelines, 0xFF = nothing to walk
-        unsigned desc = 0xFFFFFFu;
-        {
-#pragma unroll
-            for (int kind = 0; kind < 3; ++kind) {
-                if (b.m[kind] == 0ull) continue;
-                const int c = cls_find(s_cls, ncls, b.m[kind]);
-                const bool analytic = timeline_is_analytic(kind, b.n, b.sum);
-                if (c < 0) { a.S->tl.error = 1; continue; }        // a set the classification did not see: never expected
-                if (analytic) {
-                    if (count_pp) atomicAdd(&a.ppcnt[(size_t)c * (DISCO_PP_NMAX + 1) + b.n], 1u);
-                } else {
-                    const int sl = s_slot[c];
-                    if (sl < 0) { a.S->tl.error = 1; continue; }
-                    desc = (desc & ~(0xFFu << (8 * kind))) | ((unsigned)sl << (8 * kind));
-                }
-            }
+    const i64 nlist = (i64)tl->nlist;
+    i64 rb = (nlist + nwaves - 1) / nwaves;
+    rb = rb < 1 ? 1 : (rb > 64 ? 64 : rb);
+    const i64 ngroup = (nlist + rb - 1) / rb;
+    for (i64 gr = (i64)blockIdx.x * (TH_BLOCK / 64) + wave; gr < ngroup; gr += nwaves) {
+        const i64 j = gr * rb + lane;
+        const bool mine = lane < rb && j < nlist;
+        const i64 i = mine ? (i64)a.list[j] : 0;
+        const unsigned desc = mine ? a.desc[i] : DESC_NONE;
+        u64 walkers = __ballot(desc != DESC_NONE);
+        if (!walkers) continue;
+        // the fields of the requests that are walked
+        int l_v = 0, n_v = 1;
+        float k_v = tr.k_s, gd_v = tr.g_s, gap_v = 0.0f;
+        i64 off_v = 0;
+        if (desc != DESC_NONE) {
+            l_v = tr.l[i]; n_v = tr.n[i];
+            if (tr.k) k_v = tr.k[i];
+            if (tr.g) gd_v = tr.g[i];
+            if (tr.off) off_v = tr.off[i];
+            if (tr.tbt) gap_v = tr.tbt[i];
         }
-        u64 walkers = __ballot(desc != 0xFFFFFFu);
         const u64 memw = mem ? __ballot((desc & 0xFFFF00u) != 0xFFFF00u) : 0ull;     // requests that read the token array
         float pre[4] = {0.f, 0.f, 0.f, 0.f};
-        if (walkers) {
+        {
             const int r0 = __ffsll((long long)walkers) - 1;
-            if ((memw >> r0) & 1ull) load_first(tr.arr, (i64)bcast_u64((u64)b.off, r0), bcast_i(b.n, r0), n_tok, align, lane, pre);
+            if ((memw >> r0) & 1ull) load_first(tr.arr, (i64)bcast_u64((u64)off_v, r0), bcast_i(n_v, r0), n_tok, align, lane, pre);
         }
         while (walkers) {
             const int rq = __ffsll((long long)walkers) - 1;
             walkers &= walkers - 1;
             const unsigned dsc = (unsigned)bcast_i((int)desc, rq);
-            const int n = bcast_i(b.n, rq), l = bcast_i(b.l, rq);
-            const float gd = bcast_f(b.gd, rq);
+            const int n = bcast_i(n_v, rq), l = bcast_i(l_v, rq);
+            const float gd = bcast_f(gd_v, rq);
             const float cur[4] = {pre[0], pre[1], pre[2], pre[3]};
             bool have = (memw >> rq) & 1ull;
             if (walkers) {                          // the next request's first chunk is loaded while this one is walked
                 const int r1 = __ffsll((long long)walkers) - 1;
                 if ((memw >> r1) & 1ull)
-                    load_first(tr.arr, (i64)bcast_u64((u64)b.off, r1), bcast_i(b.n, r1), n_tok, align, lane, pre);
+                    load_first(tr.arr, (i64)bcast_u64((u64)off_v, r1), bcast_i(n_v, r1), n_tok, align, lane, pre);
             }
 #pragma unroll 1
             for (int variant = 2; variant >= 0; --variant) {
@@ -240,11 +349,11 @@ __global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok
                 const unsigned row_base = sl << width;
                 auto sink = [&](const unsigned key[4]) { hist_keys(h, key, row_base, lane); };
                 const bool dev = variant == 0;
-                const float gap = dev ? gd : bcast_f(b.gap, rq);
+                const float gap = dev ? gd : bcast_f(gap_v, rq);
                 const bool from_mem = !dev && mem;
-                const i64 off = from_mem ? (i64)bcast_u64((u64)b.off, rq) : 0;
+                const i64 off = from_mem ? (i64)bcast_u64((u64)off_v, rq) : 0;
                 walk_hist(from_mem, n, tr.arr, off, n_tok, align, cur, from_mem && have, gap, variant == 2, gd, l,
-                          bcast_f(b.k, rq), tr.c, tau, kt, lane, sink);
+                          bcast_f(k_v, rq), tr.c, tau, kt, lane, sink);
                 if (from_mem) have = false;
             }
         }
@@ -264,19 +373,40 @@ __global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok
 
 }  // namespace
 
+// Once per selection, after the classification: descriptors of all requests, analytic timelines counted per class
+// and length.  `slices`: scratch for the workgroup slices (slices_bytes).
+void disco_launch_tl_assign(const TraceView& v, const disco_policy* pol, int P, const void* summary, SelState* S,
+                            unsigned* desc, unsigned* list, unsigned* slices, size_t slices_bytes, unsigned* ppcnt,
+                            hipStream_t stream)
+{
+    if (v.n_req <= 0) return;
+    i64 b = (v.n_req + 49151) / 49152;             // at most 65535 requests per workgroup: 16-bit counts in LDS
+    if (b < 128) b = 128;
+    const i64 fit = (i64)(slices_bytes / ((size_t)PP_LDS_CLS * PP_WORDS * sizeof(unsigned)));
+    int use_lds = 1;
+    if (b > fit) { b = 256; use_lds = 0; }         // (a trace of tens of millions of requests: counts in device memory)
+    hipLaunchKernelGGL(k_tl_assign, dim3((unsigned)b), dim3(AS_BLOCK), 0, stream, v, pol, P, (const TlSummary*)summary, S, desc,
+                       list, slices, ppcnt, use_lds);
+    hipLaunchKernelGGL(k_pp_reduce, dim3(PP_LDS_CLS, (PP_WORDS + 255) / 256), dim3(1024), 0, stream, (const SelState*)S, (int)b, (const unsigned*)slices,
+                       ppcnt, use_lds);
+}
+
 void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                hipStream_t stream)
 {
+    (void)pol;
     HistArgs h;
     memset(&h, 0, sizeof(h));
     h.tau = a.tau; h.kt = a.kt; h.P = a.P; h.pass = a.pass;
     h.S = a.S; h.ghist = a.ghist; h.ppcnt = a.ppcnt;
     h.summary = (const TlSummary*)a.summary;
-    h.rb = tl_batch(v.n_req, 512 * (TH_BLOCK / 64));
-    const i64 per_block = (i64)(TH_BLOCK / 64) * h.rb;
-    i64 b = (v.n_req + per_block - 1) / per_block;
+    h.desc = a.desc; h.list = a.list;
+    i64 b = (v.n_req + TH_BLOCK / 64 - 1) / (TH_BLOCK / 64);      // at most one request per wave
     if (b < 1) b = 1;
-    if (b > 512) b = 512;                      // two resident workgroups per CU
+    // two resident workgroups per CU; the passes after the second normally have nothing to do (the launch returns
+    // at once) and get a small grid, which makes the empty launch cheaper and a needed one merely slower
+    const i64 cap = a.pass < 2 ? 512 : 64;
+    if (b > cap) b = cap;
     const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
-    hipLaunchKernelGGL(k_tl_hist, dim3((unsigned)b), dim3(TH_BLOCK), 0, stream, v, n_tok, align, pol, h);
+    hipLaunchKernelGGL(k_tl_hist, dim3((unsigned)b), dim3(TH_BLOCK), 0, stream, v, n_tok, align, h);
 }

@@ -65,6 +65,7 @@ constexpr int CL_BLOCK = 1024;              // classification: 16 waves share on
 
 __device__ __forceinline__ void insert_sets(u64 m, bool walked, u64* loc, u64* loc_walk, int* overflow, WaveTable& w, int lane)
 {
+    if (__ballot(m != 0ull) == 0ull) return;         // no lane has a timeline of this kind
     const volatile u64* vloc = loc;
     int c = -1;
     for (int e = 0; e < w.nknown; ++e) c = (bcast_u64(w.tab, e) == m) ? e : c;
@@ -190,6 +191,7 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
         // 21-bit window of keys first
         const unsigned tb = f2u(tau);
         tl.restart = 0;
+        tl.nlist = 0u;
         if (tb >= 8192u) { tl.key_lo = tb - 8192u; tl.window = 21; tl.left = 21; }
         else { tl.key_lo = 0u; tl.window = 0; tl.left = 31; }
         tbt_plan_next(S, P, nq);

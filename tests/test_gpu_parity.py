@@ -322,7 +322,8 @@ def test_config0_device_constrained_sweep(B, oracle):
         assert np.float32(so["param"][j]) == w == np.float32(found[j].w_tail), j
         assert (so["hist_param"][j][:24].astype(np.float32) == hp).all() and (so["hist_acc"][j][:24] == ha).all(), j
         waits.append(float(w))
-    assert float(tr["srv_ttft"].max()) < 128.0 and waits[0] == 128.0      # no budget: wait out every server
+    if levels[0][0] == 0:                                                    # no budget: wait out every server, and no longer
+        assert abs(waits[0] - float(tr["srv_ttft"].max())) <= 128.0 / 2 ** 20
     assert all(a >= b for a, b in zip(waits, waits[1:])) and waits[-1] < 1e-4    # full budget: start (almost) at once
     pol_specs = [dict(mode=1, l_th=-1, w_tail=w, mig_mode=1) for w in waits]
     tr_host = dict(tr, tok_arr=None)
