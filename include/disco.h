@@ -120,6 +120,8 @@ typedef struct disco_gen_params {
  * stages & DISCO_GEN_TOKENS: writes tok_arr[0 .. trace->n_tok) (asynchronous);
  *   trace->n_tok must equal tok_off[n_req].  The arrival offsets of a request
  *   are the running fp32 sum, in index order, of its per-token gaps.
+ * Calls on one GPU share a small area of device memory inside the library
+ * (tile sums of the offset scan): do not let two of them overlap in time.
  * Errors: NULL (struct or a required array), SHAPE (n_req < 0, lo > hi),
  * RANGE (sigma < 0, probabilities outside [0,1], rates <= 0), HIP. */
 int32_t disco_gen_trace(const disco_gen_params* params /*host*/, disco_trace* trace /*host, device arrays*/,

@@ -140,29 +140,69 @@ __global__ __launch_bounds__(256) void k_gen_requests(disco_gen_params g, int32_
     dev_pre_spt[i] = pre;
 }
 
-// Exclusive prefix sum of output_len into tok_off[0..n], one workgroup: each
-// thread owns a contiguous slice (sum, scan of the slice sums, write-out).
-__global__ __launch_bounds__(1024) void k_gen_offsets(i64 n, const int32_t* output_len, i64* tok_off)
+// Exclusive prefix sum of output_len into tok_off[0..n] in two launches: the sum of every tile, then per tile the
+// sum of the tiles in front of it and a scan of its own elements.  Integer sums: any order gives the same offsets.
+constexpr int GO_BLOCK = 1024;
+constexpr int GO_MAX_TILES = 65536;
+// Tile sums between the two launches (device memory of the library's code object, referenced by device code only).
+// Calls of disco_gen_trace on one GPU share it: they must not overlap in time.
+__device__ i64 g_tile_sum[GO_MAX_TILES];
+
+__device__ __forceinline__ i64 block_sum_1024(i64 v, i64* sh)
 {
-    __shared__ i64 sums[1024];
-    const int t = threadIdx.x;
-    i64 per = (n + 1023) / 1024;
-    i64 a = (i64)t * per, b = a + per;
-    if (a > n) a = n;
-    if (b > n) b = n;
-    i64 acc = 0;
-    for (i64 i = a; i < b; ++i) acc += output_len[i];
-    sums[t] = acc;
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     __syncthreads();
-    for (int d = 1; d < 1024; d <<= 1) {
-        i64 v = (t >= d) ? sums[t - d] : 0;
-        __syncthreads();
-        sums[t] += v;
-        __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    i64 t = 0;
+    for (int w = 0; w < GO_BLOCK / 64; ++w) t += sh[w];
+    return t;
+}
+
+__global__ __launch_bounds__(GO_BLOCK) void k_gen_tile_sums(i64 n, i64 per_thread, const int32_t* __restrict__ output_len)
+{
+    __shared__ i64 sh[GO_BLOCK / 64];
+    const i64 tile = per_thread * GO_BLOCK;
+    const i64 lo = (i64)blockIdx.x * tile;
+    i64 acc = 0;
+    for (i64 q = 0; q < per_thread; ++q) {                   // coalesced: consecutive threads, consecutive elements
+        const i64 i = lo + q * GO_BLOCK + threadIdx.x;
+        if (i < n) acc += output_len[i];
     }
-    i64 run = (t == 0) ? 0 : sums[t - 1];
-    for (i64 i = a; i < b; ++i) { tok_off[i] = run; run += output_len[i]; }
-    if (t == 1023) tok_off[n] = sums[1023];
+    acc = block_sum_1024(acc, sh);
+    if (threadIdx.x == 0) g_tile_sum[blockIdx.x] = acc;
+}
+
+__global__ __launch_bounds__(GO_BLOCK) void k_gen_offsets(i64 n, i64 per_thread, const int32_t* __restrict__ output_len,
+                                                          i64* __restrict__ tok_off)
+{
+    __shared__ i64 sh[GO_BLOCK / 64];
+    __shared__ i64 wsum[GO_BLOCK / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const i64 tile = per_thread * GO_BLOCK;
+    const i64 lo = (i64)blockIdx.x * tile;
+    i64 before = 0;
+    for (int b = threadIdx.x; b < (int)blockIdx.x; b += GO_BLOCK) before += g_tile_sum[b];
+    i64 run = block_sum_1024(before, sh);                    // tokens of the tiles in front
+    // the tile in rounds of 1024 consecutive elements: scan across the workgroup, carry `run`
+    for (i64 q = 0; q < per_thread; ++q) {
+        const i64 i = lo + q * GO_BLOCK + threadIdx.x;
+        const i64 v = i < n ? (i64)output_len[i] : 0;
+        i64 inc = v;
+        for (int d = 1; d < 64; d <<= 1) {
+            const i64 o = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += o;
+        }
+        __syncthreads();
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        i64 front = 0, all = 0;
+        for (int w = 0; w < GO_BLOCK / 64; ++w) { const i64 t = wsum[w]; front += w < wave ? t : 0; all += t; }
+        if (i < n) tok_off[i] = run + front + inc - v;
+        run += all;
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) tok_off[n] = run;
 }
 
 // Per-token gap in front of global token index j (the first token's is unused).
@@ -182,17 +222,46 @@ __global__ __launch_bounds__(256) void k_gen_gaps(disco_gen_params g, i64 n_tok,
 }
 
 // Arrival offsets: running fp32 sum of a request's gaps in index order, in
-// place, one request per thread (the order of the additions is part of the
-// trace's definition, so this step is sequential per request).
-__global__ __launch_bounds__(256) void k_gen_arrivals(i64 n_req, const i64* tok_off, float* tok_arr)
+// place.  The order of the additions is part of the trace's definition, so
+// every request is summed by one thread, token after token; the tokens pass
+// through LDS so that device memory is read and written in contiguous
+// 128-byte pieces: a workgroup takes 256 consecutive requests and moves
+// GA_K tokens of each per round (32 threads per request and piece).
+constexpr int GA_BLOCK = 256;
+constexpr int GA_K = 32;
+
+__global__ __launch_bounds__(GA_BLOCK) void k_gen_arrivals(i64 n_req, const i64* __restrict__ tok_off, float* __restrict__ tok_arr)
 {
-    i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_req) return;
-    i64 a = tok_off[i], b = tok_off[i + 1];
+    __shared__ float tile[GA_BLOCK][GA_K + 1];               // odd row stride: a thread per row without bank conflicts
+    __shared__ i64 s_off[GA_BLOCK];
+    __shared__ int s_len[GA_BLOCK];
+    __shared__ int s_max;
+    const int t = threadIdx.x;
+    const i64 i = (i64)blockIdx.x * GA_BLOCK + t;
+    i64 a = 0;
+    int len = 0;
+    if (i < n_req) { a = tok_off[i]; len = (int)(tok_off[i + 1] - a); }
+    if (t == 0) s_max = 0;
+    s_off[t] = a; s_len[t] = len;
+    __syncthreads();
+    atomicMax(&s_max, len);
+    __syncthreads();
+    const int maxlen = s_max;
+    const int sub = t & (GA_K - 1), grp = t / GA_K;
     float acc = 0.0f;
-    for (i64 j = a; j < b; ++j) {
-        if (j > a) acc = acc + tok_arr[j];
-        tok_arr[j] = acc;
+    for (int c0 = 0; c0 < maxlen; c0 += GA_K) {
+        for (int r = grp; r < GA_BLOCK; r += GA_BLOCK / GA_K)
+            if (c0 + sub < s_len[r]) tile[r][sub] = tok_arr[s_off[r] + c0 + sub];
+        __syncthreads();
+        const int m = len - c0 < GA_K ? len - c0 : GA_K;
+        for (int q = 0; q < m; ++q) {
+            if (c0 + q > 0) acc = acc + tile[t][q];
+            tile[t][q] = acc;
+        }
+        __syncthreads();
+        for (int r = grp; r < GA_BLOCK; r += GA_BLOCK / GA_K)
+            if (c0 + sub < s_len[r]) tok_arr[s_off[r] + c0 + sub] = tile[r][sub];
+        __syncthreads();
     }
 }
 
@@ -223,7 +292,15 @@ extern "C" int32_t disco_gen_trace(const disco_gen_params* g, disco_trace* tr, i
             hipLaunchKernelGGL(k_gen_requests, dim3(blocks), dim3(256), 0, stream, *g, tr->prompt_len, tr->output_len,
                                tr->srv_ttft, tr->srv_tbt, tr->dev_pre_spt, tr->dev_dec_spt);
         }
-        hipLaunchKernelGGL(k_gen_offsets, dim3(1), dim3(1024), 0, stream, n, tr->output_len, tr->tok_off);
+        {
+            i64 per_thread = 4;                              // tiles of 4096 requests while the tile sums fit
+            while ((n + per_thread * GO_BLOCK - 1) / (per_thread * GO_BLOCK) > GO_MAX_TILES) per_thread *= 2;
+            i64 tiles = (n + per_thread * GO_BLOCK - 1) / (per_thread * GO_BLOCK);
+            if (tiles < 1) tiles = 1;
+            hipLaunchKernelGGL(k_gen_tile_sums, dim3((unsigned)tiles), dim3(GO_BLOCK), 0, stream, n, per_thread, tr->output_len);
+            hipLaunchKernelGGL(k_gen_offsets, dim3((unsigned)tiles), dim3(GO_BLOCK), 0, stream, n, per_thread, tr->output_len,
+                               tr->tok_off);
+        }
         DISCO_HIP(hipGetLastError());
         i64 total = 0;
         DISCO_HIP(hipMemcpyAsync(&total, tr->tok_off + n, sizeof(i64), hipMemcpyDeviceToHost, stream));
@@ -237,8 +314,8 @@ extern "C" int32_t disco_gen_trace(const disco_gen_params* g, disco_trace* tr, i
             i64 want = (tr->n_tok + 255) / 256;
             unsigned blocks = (unsigned)(want < 65536 ? want : 65536);
             hipLaunchKernelGGL(k_gen_gaps, dim3(blocks), dim3(256), 0, stream, *g, tr->n_tok, tr->tok_arr);
-            hipLaunchKernelGGL(k_gen_arrivals, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, n, tr->tok_off,
-                               tr->tok_arr);
+            hipLaunchKernelGGL(k_gen_arrivals, dim3((unsigned)((n + GA_BLOCK - 1) / GA_BLOCK)), dim3(GA_BLOCK), 0, stream, n,
+                               tr->tok_off, tr->tok_arr);
             DISCO_HIP(hipGetLastError());
         }
     }
