@@ -574,9 +574,10 @@ int32_t disco_budget_search(const disco_trace* trace /*host*/, const disco_cost_
 /* ---- helpers ------------------------------------------------------------ */
 
 /* Bytes of device workspace for n_req requests and P columns (or searches):
- * about 47 MB plus 25 bytes per request.  The per-request part (one byte that
+ * about 47 MB plus 61 bytes per request.  The per-request part (one byte that
  * the TTFT selection and the token walk use between their passes, 16 bytes of
- * what the token walk found, 8 bytes of the TBT selection) is needed by
+ * what the token walk found, 32 bytes of the same for buffer hand-offs, 12 bytes
+ * of the TBT selection) is needed by
  * disco_eval_migration and by
  * disco_reduce_stats with timelines; every other call accepts a workspace of
  * disco_workspace_bytes(0, P) bytes.  The workspace holds partial results

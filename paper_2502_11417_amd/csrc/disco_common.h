@@ -45,15 +45,20 @@ struct WsLayout {
 };
 WsLayout disco_ws_layout(int32_t P);
 // Behind the fixed regions: one byte per request (TTFT selection: thresholds not above the prompt length; token
-// walk: which timelines to walk), then 16 bytes per request (what the token walk found), then 8 bytes per request
-// (TBT selection: which of its timelines have tokens to walk and into which histogram rows; the list of such requests).
+// walk: which timelines to walk), then 16 bytes per request (what the token walk found), then 32 bytes per request (what the walk of its
+// buffer hand-off timelines found), then 12 bytes per request (TBT selection: which of its timelines have tokens to
+// walk and into which histogram rows; the list of such requests).
 inline size_t disco_ws_bytes_region(int64_t n_req) { return n_req > 0 ? (((size_t)n_req + 255) & ~(size_t)255) : 0; }
 inline size_t disco_ws_summary_offset(const WsLayout& L, int64_t n_req) { return L.total + disco_ws_bytes_region(n_req); }
-inline size_t disco_ws_desc_offset(const WsLayout& L, int64_t n_req)
+inline size_t disco_ws_bufsum_offset(const WsLayout& L, int64_t n_req)
 {
     return disco_ws_summary_offset(L, n_req) + (n_req > 0 ? (size_t)n_req * 16 : 0);
 }
+inline size_t disco_ws_desc_offset(const WsLayout& L, int64_t n_req)
+{
+    return disco_ws_bufsum_offset(L, n_req) + (n_req > 0 ? (size_t)n_req * 32 : 0);
+}
 inline size_t disco_ws_full_bytes(const WsLayout& L, int64_t n_req)
 {
-    return disco_ws_desc_offset(L, n_req) + (n_req > 0 ? (size_t)n_req * 8 : 0);      // descriptors, then the walk list
+    return disco_ws_desc_offset(L, n_req) + (n_req > 0 ? (size_t)n_req * 12 : 0);     // descriptors (8), then the walk list (4)
 }

@@ -619,6 +619,7 @@ extern "C" int32_t disco_eval_migration(const disco_trace* trace, const disco_ti
         a.wflags = (unsigned char*)(ws + L.total);
         a.summary = ws + disco_ws_summary_offset(L, v.n_req);
         a.counter = (unsigned*)(ws + L.wcount);
+        a.bufsum = ws + disco_ws_bufsum_offset(L, v.n_req);
         disco_launch_tl_stats_fast(v, trace->n_tok, (const disco_policy*)(ws + L.pol), a,
                                    tl_totals((u64*)(ws + L.part)), stream);
     }
@@ -727,14 +728,17 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             a.wflags = (unsigned char*)(ws + L.total);
             a.summary = ws + disco_ws_summary_offset(L, v.n_req);
             a.counter = (unsigned*)(ws + L.wcount);
-            if (!tl->reuse_walk)
+            a.bufsum = ws + disco_ws_bufsum_offset(L, v.n_req);
+            if (!tl->reuse_walk) {
                 disco_launch_tl_walk(v, trace->n_tok, dpol, P, a.tau, a.kt, a.wflags, a.summary, a.counter, stream);
-            disco_launch_tl_classify(v, dpol, P, nq, tl->tau, a.summary, S, a.ppcnt, gh, a.dhist, (u64*)(ws + L.slices),
-                                     (unsigned*)(ws + L.ticket), stream);
-            a.desc = (unsigned*)(ws + disco_ws_desc_offset(L, v.n_req));
-            a.list = a.desc + v.n_req;
-            disco_launch_tl_assign(v, dpol, P, a.summary, S, a.desc, a.list, (unsigned*)(ws + L.slices), L.total - L.slices,
-                                   a.ppcnt, stream);
+                disco_launch_tl_stats_buf(v, trace->n_tok, dpol, a, nullptr, stream);      // summaries only
+            }
+            disco_launch_tl_classify(v, dpol, P, nq, tl->tau, a.summary, a.bufsum, S, a.ppcnt, gh, a.dhist,
+                                     (u64*)(ws + L.slices), (unsigned*)(ws + L.ticket), stream);
+            a.desc = (u64*)(ws + disco_ws_desc_offset(L, v.n_req));
+            a.list = (unsigned*)(a.desc + v.n_req);
+            disco_launch_tl_assign(v, dpol, P, a.summary, S, a.bufsum, a.desc, a.list, (unsigned*)(ws + L.slices),
+                                   L.total - L.slices, a.ppcnt, a.dhist, stream);
             for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;
                 disco_launch_tl_hist_fast(v, trace->n_tok, dpol, a, stream);

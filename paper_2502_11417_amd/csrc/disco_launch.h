@@ -20,7 +20,8 @@ struct TimelineArgs {
     unsigned char* wflags;         // one byte per request: the walks it needs (written by the statistics pass)
     void* summary;                 // TlSummary per request: what the token walk found (16 bytes each)
     unsigned* counter;             // batch counters of the token walk, one per queue (zeroed by the flags kernel)
-    unsigned* desc;                // one word per request: LDS rows of its timelines with tokens to walk (histogram passes)
+    u64* desc;                     // per request: LDS rows of its timelines with tokens to walk, one byte per kind (histogram passes)
+    void* bufsum;                  // BufSummary per request: what the walk of its buffer hand-off timelines found
     unsigned* list;                // the requests that have such a timeline, one word each (histogram passes)
 };
 
@@ -92,12 +93,12 @@ void disco_launch_tl_walk(const TraceView& v, i64 n_tok, const disco_policy* pol
 void disco_launch_timeline_general(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                    hipStream_t stream);
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, const void* summary,
-                              SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist,
+                              const void* bufsum, SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist,
                               u64* parts /* 1024 x 66 words of scratch */, unsigned* ticket, hipStream_t stream);
 void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                hipStream_t stream);
 void disco_launch_tl_assign(const TraceView& v, const disco_policy* pol, int P, const void* summary, SelState* S,
-                            unsigned* desc, unsigned* list, unsigned* slices, size_t slices_bytes, unsigned* ppcnt,
-                            hipStream_t stream);
+                            const void* bufsum, u64* desc, unsigned* list, unsigned* slices, size_t slices_bytes,
+                            unsigned* ppcnt, unsigned* dhist, hipStream_t stream);
 void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,
                               hipStream_t stream);

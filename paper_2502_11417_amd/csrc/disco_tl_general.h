@@ -10,7 +10,7 @@ namespace {
 
 // ------------------------------------------------------------- timeline ----
 
-struct TimelineResult { int m; float t_last; int delay; };
+struct TimelineResult { int m; float t_last; int delay; float M; float r0; };     // M: final running maximum, r0: arrival of token 0
 
 // Prices behind the buffer hand-off's cost test (Sec. 4.3: saving > overhead).
 typedef BufCostArgs BufCost;
@@ -38,7 +38,7 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
     // element 0 of the window is the aligned-down start: the first `mis` elements precede the request
     const int mis = use_mem ? (int)((off + align) & 3) : 0;
     const i64 gbase = off - mis + 4 * lane;
-    float carryM = -INFINITY, carryD = INFINITY, base = 0.0f, t_last = 0.0f, a_m = 0.0f;
+    float carryM = -INFINITY, carryD = INFINITY, base = 0.0f, t_last = 0.0f, a_m = 0.0f, r_first = 0.0f;
     int m = -1, delay = 0;
     float nxt[4] = {0.f, 0.f, 0.f, 0.f};
     if (use_mem && 4 * lane - mis < n) load4(arr, gbase, n_tok, nxt);
@@ -69,6 +69,10 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
         };
 #pragma unroll
         for (int q = 0; q < 4; ++q) r[q] = val[q] ? arrival(q) : -INFINITY;
+        if (e0 == 0) {                      // token 0 is element `mis` of lane 0
+            const float rf = mis == 0 ? r[0] : (mis == 1 ? r[1] : (mis == 2 ? r[2] : r[3]));
+            r_first = bcast_f(rf, 0);
+        }
         float d[4], prev[4];
         float Mlast;
         auto scan = [&]() {
@@ -169,7 +173,7 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
             t_last = bcast_f(dl, e >> 2);
         }
     }
-    return TimelineResult{m, t_last, delay};
+    return TimelineResult{m, t_last, delay, carryM, r_first};
 }
 
 // Pure pacing: a source whose constant gap is safely below tau (gap < 0.999 tau).
@@ -197,7 +201,7 @@ __device__ __forceinline__ TimelineResult run_pure_pacing(int n, float tau, int 
             if (need_keys) sink(key, ok);
         }
     }
-    return TimelineResult{-1, (float)(n - 1) * tau, 0};
+    return TimelineResult{-1, (float)(n - 1) * tau, 0, 0.0f, 0.0f};
 }
 
 }  // namespace

@@ -66,6 +66,27 @@ struct Batch {
     TlSummary sum;             // what the token walk found (all zero / no hand-off without summaries)
 };
 
+// What the walk of the two buffer hand-off timelines of a request found (server source handed to the device,
+// device source handed to the server): final running maximum, hand-off token in the encoding of
+// TlSummary::m_enc (the source's last token), delayed tokens after the hand-off.
+struct __attribute__((aligned(16))) BufSummary { float M_s; int m_s; int delay_s; int pad0; float M_d; int m_d; int delay_d; int pad1; };
+
+__device__ __forceinline__ int buf_m_enc(int m, float r0)
+{
+    const bool nz = r0 != 0.0f;
+    return m >= 0 ? (m | (nz ? (1 << 30) : 0)) : (nz ? -2 : -1);
+}
+
+// A buffer hand-off timeline whose running maximum never left 0 (first arrival 0 included) delivers token t at
+// round(t tau) whatever its hand-off: histogrammed analytically like the pure-pacing timelines.
+__device__ __forceinline__ bool buf_timeline_is_analytic(int kind, int n, const BufSummary& b)
+{
+    if (n < 0 || n > DISCO_PP_NMAX) return false;
+    const float M = kind == TL_SRV_BUF ? b.M_s : b.M_d;
+    const int me = kind == TL_SRV_BUF ? b.m_s : b.m_d;
+    return f2u(M) == 0u && !summary_r0_nonzero(me);
+}
+
 // Is a timeline of kind TL_DEV, TL_SRV or TL_SRV_LAG histogrammed analytically?  Its running maximum never left 0
 // and it has no hand-off, so delta_t = round(t tau) and its gaps depend on its length alone (counted per class
 // and length up to DISCO_PP_NMAX).
@@ -114,7 +135,7 @@ struct HistArgs {
     unsigned* ghist;
     unsigned* ppcnt;
     const TlSummary* summary;      // per request, from the token walk
-    const unsigned* desc;          // per request: LDS rows of its timelines that have tokens to walk
+    const u64* desc;               // per request: LDS rows of its timelines that have tokens to walk (one byte per kind)
     const unsigned* list;          // requests with such a timeline (TlSel::nlist entries, any order)
 };
 

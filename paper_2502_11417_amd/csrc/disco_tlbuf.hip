@@ -6,7 +6,11 @@
 // histogram rows, so a table may mix hand-off kinds freely.  One wave walks
 // one request and kind with the general walker (a scan per chunk; the hand-off
 // condition compares the delivery slack of every token with the migration
-// time).  Both kernels return at once when the staged table has no such column.
+// time).  The statistics pass also leaves 32 bytes per request (BufSummary):
+// a hand-off timeline whose running maximum never left 0 delivers at
+// round(t tau) like a pure-pacing one, so the histogram passes only walk the
+// others (the walk list of the TBT selection names them).  Both kernels
+// return at once when the staged table has no such column.
 #include <string.h>
 
 #include "disco_tl_general.h"
@@ -21,7 +25,8 @@ struct BufStatsArgs {
     float tau, kt;
     int P;
     int32_t* mig_idx; int32_t* n_src_tok; float* t_last; int32_t* delay_num;
-    MigPartial* totals;            // DISCO_NCOPY x 64 device-wide totals, shared with the streaming kernel
+    MigPartial* totals;            // DISCO_NCOPY x 64 device-wide totals, shared with the streaming kernel; nullptr: summaries only
+    BufSummary* bufsum;            // per request, written for the requests with a hand-off timeline
     BufCostArgs bc;
     const unsigned* buffer_flag;
 };
@@ -51,6 +56,7 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
             const int n = bcast_i(b.n, rq), l = bcast_i(b.l, rq);
             const float k = bcast_f(b.k, rq), gd = bcast_f(b.gd, rq), gap = bcast_f(b.gap, rq), s_ttft = bcast_f(b.s, rq);
             const i64 off = tr.arr ? (i64)bcast_u64((u64)b.off, rq) : 0;
+            BufSummary bs{0.0f, -1, 0, 0, 0.0f, -1, 0, 0};
 #pragma unroll 1
             for (int variant = TL_DEV_BUF; variant >= TL_SRV_BUF; --variant) {
                 const u64 mask = bcast_u64(variant == TL_DEV_BUF ? b.m[TL_DEV_BUF] : b.m[TL_SRV_BUF], rq);
@@ -58,7 +64,9 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
                 auto sink = [](const unsigned*, const bool*) {};
                 const TimelineResult res = run_timeline(variant, n, tr.arr, off, n_tok, align, gap, gd, l, k, tr.c, s_ttft, a.bc,
                                                         a.tau, a.kt, lane, nullptr, sink);
-                if ((mask >> lane) & 1ull) {
+                if (variant == TL_DEV_BUF) { bs.M_d = res.M; bs.m_d = buf_m_enc(res.m, res.r0); bs.delay_d = res.delay; }
+                else { bs.M_s = res.M; bs.m_s = buf_m_enc(res.m, res.r0); bs.delay_s = res.delay; }
+                if (a.totals != nullptr && ((mask >> lane) & 1ull)) {
                     const bool src_dev = variant == TL_DEV_BUF;
                     const bool mig = res.m >= 0;
                     const int nsrc = mig ? res.m + 1 : n;              // tokens produced by the source
@@ -76,8 +84,10 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
                     if (a.delay_num) a.delay_num[(size_t)lane * tr.n_req + i] = mig ? res.delay : 0;
                 }
             }
+            if (lane == 0) a.bufsum[i] = bs;                 // (every field is the same on all lanes)
         }
     }
+    if (a.totals == nullptr) return;
     // fold the waves of the workgroup, then add into this workgroup's copy of the totals
     sh[0 * TB_BLOCK + threadIdx.x] = acc_s_dec; sh[1 * TB_BLOCK + threadIdx.x] = acc_d_dec;
     sh[2 * TB_BLOCK + threadIdx.x] = acc_repre; sh[3 * TB_BLOCK + threadIdx.x] = acc_mig;
@@ -107,56 +117,57 @@ struct BufHistArgs {
     HistArgs h;
     BufCostArgs bc;
     const unsigned* buffer_flag;
-    unsigned* dhist;               // first pass: migrated requests by number of delayed tokens, per column
 };
 
-__global__ __launch_bounds__(TBH_BLOCK) void k_tl_hist_buf(TraceView tr, i64 n_tok, int align, const disco_policy* __restrict__ pol,
-                                                           BufHistArgs ba)
+// One histogram pass over the hand-off timelines that have tokens to walk: bytes 3 and 4 of a request's
+// descriptor name the LDS rows of its two hand-off kinds, the walk list of the selection names the requests.
+__global__ __launch_bounds__(TBH_BLOCK) void k_tl_hist_buf(TraceView tr, i64 n_tok, int align, BufHistArgs ba)
 {
     __shared__ __align__(16) unsigned smem[DISCO_TL_HIST_WORDS];
-    __shared__ u64 s_cls[DISCO_MAX_CLS];
-    __shared__ signed char s_slot[DISCO_MAX_CLS];
-    __shared__ disco_policy spol[DISCO_MAX_COLS];
     const HistArgs& a = ba.h;
     const TlSel* tl = &a.S->tl;
     const int width = tl->width;
     if (*ba.buffer_flag == 0u || width <= 0 || tl->fallback) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int P = a.P, ncls = tl->ncls, nwalk = tl->nwalk;
+    const int ncls = tl->ncls, nwalk = tl->nwalk;
     HistCtx h;
     h.hist = smem; h.width = width; h.shift = tl->shift; h.up = h.shift + width;
     h.G = tl->G < DISCO_MAX_GRP ? tl->G : DISCO_MAX_GRP;
     h.stride = (unsigned)nwalk << width;
     h.key_lo = tl->key_lo; h.key_cap = tl->window ? (1u << tl->window) : 0xFFFFFFFFu;
     for (int k = 0; k < DISCO_MAX_GRP; ++k) h.grp_prefix[k] = tl->grp_prefix[k];
-    if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
-    if (threadIdx.x < DISCO_MAX_CLS) { s_cls[threadIdx.x] = tl->cls_mask[threadIdx.x]; s_slot[threadIdx.x] = tl->cls_slot[threadIdx.x]; }
     const int words = (h.G * nwalk) << width;
     for (int i = threadIdx.x; i < words; i += TBH_BLOCK) smem[i] = 0u;
     __syncthreads();
     const i64 nwaves = (i64)gridDim.x * (TBH_BLOCK / 64);
-    const i64 nbatch = (tr.n_req + TF_RB - 1) / TF_RB;
-    for (i64 bt = (i64)blockIdx.x * (TBH_BLOCK / 64) + wave; bt < nbatch; bt += nwaves) {
-        const Batch b = load_batch(tr, spol, P, bt * TF_RB, lane);
-        // lane = request: LDS row of its two hand-off timelines, 0xFF = none
-        unsigned desc = 0xFFFFu;
-#pragma unroll
-        for (int kind = 0; kind < 2; ++kind) {
-            const u64 m = b.m[TL_SRV_BUF + kind];
-            if (m == 0ull) continue;
-            const int c = cls_find(s_cls, ncls, m);
-            const int sl = c >= 0 ? (int)s_slot[c] : -1;
-            if (sl < 0) { a.S->tl.error = 1; continue; }       // a set the classification did not see: never expected
-            desc = (desc & ~(0xFFu << (8 * kind))) | ((unsigned)sl << (8 * kind));
-        }
+    const i64 nlist = (i64)tl->nlist;
+    i64 rb = (nlist + nwaves - 1) / nwaves;
+    rb = rb < 1 ? 1 : (rb > 64 ? 64 : rb);
+    const i64 ngroup = (nlist + rb - 1) / rb;
+    for (i64 gr = (i64)blockIdx.x * (TBH_BLOCK / 64) + wave; gr < ngroup; gr += nwaves) {
+        const i64 j = gr * rb + lane;
+        const bool mine = lane < rb && j < nlist;
+        const i64 il = mine ? (i64)a.list[j] : 0;
+        const unsigned desc = mine ? (unsigned)((a.desc[il] >> 24) & 0xFFFFull) : 0xFFFFu;
         u64 walkers = __ballot(desc != 0xFFFFu);
+        if (!walkers) continue;
+        int l_v = 0, n_v = 1;
+        float k_v = tr.k_s, gd_v = tr.g_s, gap_v = 0.0f, s_v = 0.0f;
+        i64 off_v = 0;
+        if (desc != 0xFFFFu) {
+            l_v = tr.l[il]; n_v = tr.n[il]; s_v = tr.s[il];
+            if (tr.k) k_v = tr.k[il];
+            if (tr.g) gd_v = tr.g[il];
+            if (tr.off) off_v = tr.off[il];
+            if (tr.tbt) gap_v = tr.tbt[il];
+        }
         while (walkers) {
             const int rq = __ffsll((long long)walkers) - 1;
             walkers &= walkers - 1;
             const unsigned dsc = (unsigned)bcast_i((int)desc, rq);
-            const int n = bcast_i(b.n, rq), l = bcast_i(b.l, rq);
-            const float k = bcast_f(b.k, rq), gd = bcast_f(b.gd, rq), gap = bcast_f(b.gap, rq), s_ttft = bcast_f(b.s, rq);
-            const i64 off = tr.arr ? (i64)bcast_u64((u64)b.off, rq) : 0;
+            const int n = bcast_i(n_v, rq), l = bcast_i(l_v, rq);
+            const float k = bcast_f(k_v, rq), gd = bcast_f(gd_v, rq), gap = bcast_f(gap_v, rq), s_ttft = bcast_f(s_v, rq);
+            const i64 off = tr.arr ? (i64)bcast_u64((u64)off_v, rq) : 0;
 #pragma unroll 1
             for (int kind = 1; kind >= 0; --kind) {
                 const unsigned sl = (dsc >> (8 * kind)) & 0xFFu;
@@ -167,13 +178,8 @@ __global__ __launch_bounds__(TBH_BLOCK) void k_tl_hist_buf(TraceView tr, i64 n_t
                                             ok[3] ? key[3] : KEY_SKIP};
                     hist_keys(h, kk, row_base, lane);
                 };
-                const TimelineResult res = run_timeline(TL_SRV_BUF + kind, n, tr.arr, off, n_tok, align, gap, gd, l, k, tr.c,
-                                                        s_ttft, ba.bc, a.tau, a.kt, lane, nullptr, sink);
-                if (a.pass == 0 && res.m >= 0) {           // lane = column: one count per migrated pair
-                    const u64 mask = bcast_u64(kind ? b.m[TL_DEV_BUF] : b.m[TL_SRV_BUF], rq);
-                    const int bin = res.delay < DISCO_DELAY_BINS - 1 ? res.delay : DISCO_DELAY_BINS - 1;
-                    if ((mask >> lane) & 1ull) atomicAdd(&ba.dhist[(size_t)lane * DISCO_DELAY_BINS + bin], 1u);
-                }
+                (void)run_timeline(TL_SRV_BUF + kind, n, tr.arr, off, n_tok, align, gap, gd, l, k, tr.c, s_ttft, ba.bc, a.tau, a.kt,
+                                   lane, nullptr, sink);
             }
         }
     }
@@ -200,6 +206,7 @@ void disco_launch_tl_stats_buf(const TraceView& v, i64 n_tok, const disco_policy
     s.tau = a.tau; s.kt = a.kt; s.P = a.P;
     s.mig_idx = a.mig_idx; s.n_src_tok = a.n_src_tok; s.t_last = a.t_last; s.delay_num = a.delay_num;
     s.totals = totals;
+    s.bufsum = (BufSummary*)a.bufsum;
     s.bc = a.bc;
     s.buffer_flag = a.buffer_flag;
     const i64 per_block = (i64)(TB_BLOCK / 64) * TF_RB;
@@ -217,13 +224,14 @@ void disco_launch_tl_hist_buf(const TraceView& v, i64 n_tok, const disco_policy*
     memset(&h, 0, sizeof(h));
     h.h.tau = a.tau; h.h.kt = a.kt; h.h.P = a.P; h.h.pass = a.pass;
     h.h.S = a.S; h.h.ghist = a.ghist; h.h.ppcnt = a.ppcnt;
+    h.h.desc = a.desc; h.h.list = a.list;
     h.bc = a.bc;
     h.buffer_flag = a.buffer_flag;
-    h.dhist = a.dhist;
-    const i64 per_block = (i64)(TBH_BLOCK / 64) * TF_RB;
-    i64 b = (v.n_req + per_block - 1) / per_block;
+    (void)pol;
+    i64 b = (v.n_req + TBH_BLOCK / 64 - 1) / (TBH_BLOCK / 64);    // at most one request per wave
     if (b < 1) b = 1;
-    if (b > 512) b = 512;
+    const i64 cap = a.pass < 2 ? 512 : 64;                       // (the late passes normally return at once)
+    if (b > cap) b = cap;
     const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
-    hipLaunchKernelGGL(k_tl_hist_buf, dim3((unsigned)b), dim3(TBH_BLOCK), 0, stream, v, n_tok, align, pol, h);
+    hipLaunchKernelGGL(k_tl_hist_buf, dim3((unsigned)b), dim3(TBH_BLOCK), 0, stream, v, n_tok, align, h);
 }

@@ -165,8 +165,10 @@ __device__ __forceinline__ void load_first(const float* __restrict__ arr, i64 of
 // ------------------------------------------------------------- histogram ---
 
 // What every histogram pass needs to know of a request, worked out once per selection (k_tl_assign): the LDS
-// row of each of its three timelines (device source, server source, server source with the lag trigger; one byte
-// each, 0xFF = nothing to walk: no such timeline, or one that is histogrammed analytically).
+// row of each of its timelines (device source, server source, server source with the lag trigger, the two buffer
+// hand-off kinds; one byte each in the order of the TL_ kinds, 0xFF = nothing to walk: no such timeline, or one
+// that is histogrammed analytically).  The kernel below walks the first three kinds.
+constexpr u64 DESC_NONE5 = 0xFFFFFFFFFFull;
 constexpr unsigned DESC_NONE = 0xFFFFFFu;
 
 // Analytic timelines per class and length, counted per workgroup in LDS (two 16-bit counts per word, a workgroup
@@ -177,10 +179,11 @@ constexpr int PP_WORDS = DISCO_PP_NMAX / 2 + 1;              // words per class:
 constexpr int AS_BLOCK = 1024;
 
 __global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disco_policy* __restrict__ pol, int P,
-                                                        const TlSummary* __restrict__ summary, SelState* S,
-                                                        unsigned* __restrict__ desc_out, unsigned* __restrict__ list,
+                                                        const TlSummary* __restrict__ summary,
+                                                        const BufSummary* __restrict__ bufsum, SelState* S,
+                                                        u64* __restrict__ desc_out, unsigned* __restrict__ list,
                                                         unsigned* __restrict__ slices, unsigned* __restrict__ ppcnt,
-                                                        int use_lds)
+                                                        unsigned* __restrict__ dhist, int use_lds)
 {
     __shared__ unsigned cnt[PP_LDS_CLS * PP_WORDS];          // 128 KB
     __shared__ unsigned s_nw, s_base;
@@ -208,23 +211,38 @@ __global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disc
         const TlSummary sm = summary[i];
         u64 m[TL_KINDS];
         request_sets(spol, P, l, s, __fmaf_rn((float)l, k, tr.c), i, m);
-        unsigned desc = DESC_NONE;
+        u64 desc = DESC_NONE5;
+        BufSummary bs{0.0f, -1, 0, 0, 0.0f, -1, 0, 0};
+        if ((m[TL_SRV_BUF] | m[TL_DEV_BUF]) != 0ull) {
+            bs = bufsum[i];
+            // migrated requests by number of delayed tokens, per column (those without one are implied by the
+            // migration count)
 #pragma unroll
-        for (int kind = 0; kind < 3; ++kind) {
+            for (int kind = TL_SRV_BUF; kind <= TL_DEV_BUF; ++kind) {
+                const int me = kind == TL_SRV_BUF ? bs.m_s : bs.m_d;
+                const int dl = kind == TL_SRV_BUF ? bs.delay_s : bs.delay_d;
+                if (m[kind] == 0ull || summary_m(me) < 0 || dl <= 0) continue;
+                const int bin = dl < DISCO_DELAY_BINS - 1 ? dl : DISCO_DELAY_BINS - 1;
+                for (u64 left = m[kind]; left != 0ull; left &= left - 1ull)
+                    atomicAdd(&dhist[(size_t)(__ffsll((long long)left) - 1) * DISCO_DELAY_BINS + bin], 1u);
+            }
+        }
+#pragma unroll
+        for (int kind = 0; kind < TL_KINDS; ++kind) {
             if (m[kind] == 0ull) continue;
             const int c = cls_find(s_cls, ncls, m[kind]);
             if (c < 0) { S->tl.error = 1; continue; }        // a set the classification did not see: never expected
-            if (timeline_is_analytic(kind, n, sm)) {
+            if (kind < TL_SRV_BUF ? timeline_is_analytic(kind, n, sm) : buf_timeline_is_analytic(kind, n, bs)) {
                 if (c < nlds) atomicAdd(&cnt[c * PP_WORDS + (n >> 1)], 1u << (16 * (n & 1)));
                 else atomicAdd(&ppcnt[(size_t)c * (DISCO_PP_NMAX + 1) + n], 1u);
             } else {
                 const int sl = s_slot[c];
                 if (sl < 0) { S->tl.error = 1; continue; }
-                desc = (desc & ~(0xFFu << (8 * kind))) | ((unsigned)sl << (8 * kind));
+                desc = (desc & ~(0xFFull << (8 * kind))) | ((u64)(unsigned)sl << (8 * kind));
             }
         }
         desc_out[i] = desc;
-        const u64 wb = __ballot(desc != DESC_NONE);
+        const u64 wb = __ballot(desc != DESC_NONE5);
         if (wb && lane == __ffsll((long long)wb) - 1) atomicAdd(&s_nw, (unsigned)__popcll(wb));
     }
     __syncthreads();
@@ -236,7 +254,7 @@ __global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disc
     __syncthreads();
     if (nw) {
         for (i64 i = lo + threadIdx.x; i < hi; i += AS_BLOCK) {
-            const bool w = desc_out[i] != DESC_NONE;            // this thread's own store
+            const bool w = desc_out[i] != DESC_NONE5;           // this thread's own store
             const u64 wb = __ballot(w);
             if (!wb) continue;
             const int leader = __ffsll((long long)wb) - 1;
@@ -309,7 +327,7 @@ __global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok
         const i64 j = gr * rb + lane;
         const bool mine = lane < rb && j < nlist;
         const i64 i = mine ? (i64)a.list[j] : 0;
-        const unsigned desc = mine ? a.desc[i] : DESC_NONE;
+        const unsigned desc = mine ? (unsigned)(a.desc[i] & 0xFFFFFFull) : DESC_NONE;
         u64 walkers = __ballot(desc != DESC_NONE);
         if (!walkers) continue;
         // the fields of the requests that are walked
@@ -376,8 +394,8 @@ __global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok
 // Once per selection, after the classification: descriptors of all requests, analytic timelines counted per class
 // and length.  `slices`: scratch for the workgroup slices (slices_bytes).
 void disco_launch_tl_assign(const TraceView& v, const disco_policy* pol, int P, const void* summary, SelState* S,
-                            unsigned* desc, unsigned* list, unsigned* slices, size_t slices_bytes, unsigned* ppcnt,
-                            hipStream_t stream)
+                            const void* bufsum, u64* desc, unsigned* list, unsigned* slices, size_t slices_bytes,
+                            unsigned* ppcnt, unsigned* dhist, hipStream_t stream)
 {
     if (v.n_req <= 0) return;
     i64 b = (v.n_req + 49151) / 49152;             // at most 65535 requests per workgroup: 16-bit counts in LDS
@@ -385,8 +403,8 @@ void disco_launch_tl_assign(const TraceView& v, const disco_policy* pol, int P, 
     const i64 fit = (i64)(slices_bytes / ((size_t)PP_LDS_CLS * PP_WORDS * sizeof(unsigned)));
     int use_lds = 1;
     if (b > fit) { b = 256; use_lds = 0; }         // (a trace of tens of millions of requests: counts in device memory)
-    hipLaunchKernelGGL(k_tl_assign, dim3((unsigned)b), dim3(AS_BLOCK), 0, stream, v, pol, P, (const TlSummary*)summary, S, desc,
-                       list, slices, ppcnt, use_lds);
+    hipLaunchKernelGGL(k_tl_assign, dim3((unsigned)b), dim3(AS_BLOCK), 0, stream, v, pol, P, (const TlSummary*)summary,
+                       (const BufSummary*)bufsum, S, desc, list, slices, ppcnt, dhist, use_lds);
     hipLaunchKernelGGL(k_pp_reduce, dim3(PP_LDS_CLS, (PP_WORDS + 255) / 256), dim3(1024), 0, stream, (const SelState*)S, (int)b, (const unsigned*)slices,
                        ppcnt, use_lds);
 }

@@ -104,7 +104,8 @@ __device__ __forceinline__ void insert_sets(u64 m, bool walked, u64* loc, u64* l
 // device-wide bins.
 //   parts: gridDim.x x (DISCO_MAX_CLS + 2) words of scratch
 __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
-                                                     float tau, const TlSummary* __restrict__ summary, SelState* S,
+                                                     float tau, const TlSummary* __restrict__ summary,
+                                                     const BufSummary* __restrict__ bufsum, SelState* S,
                                                      unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts,
                                                      unsigned* ticket)
 {
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
     for (i64 rnd = blockIdx.x; rnd < nround; rnd += gridDim.x) {
         const i64 i = rnd * CL_BLOCK + threadIdx.x;
         u64 m[TL_KINDS] = {0ull, 0ull, 0ull, 0ull, 0ull};
-        bool walked[TL_KINDS] = {false, false, false, true, true};      // hand-off timelines are always walked
+        bool walked[TL_KINDS] = {false, false, false, false, false};
         if (i < tr.n_req) {
             const int l = tr.l[i], n = tr.n[i];
             const float s = tr.s[i];
@@ -136,6 +137,11 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
             walked[TL_DEV] = !timeline_is_analytic(TL_DEV, n, sm);
             walked[TL_SRV] = !timeline_is_analytic(TL_SRV, n, sm);
             walked[TL_SRV_LAG] = !timeline_is_analytic(TL_SRV_LAG, n, sm);
+            if ((m[TL_SRV_BUF] | m[TL_DEV_BUF]) != 0ull) {
+                const BufSummary bs = bufsum[i];
+                walked[TL_SRV_BUF] = !buf_timeline_is_analytic(TL_SRV_BUF, n, bs);
+                walked[TL_DEV_BUF] = !buf_timeline_is_analytic(TL_DEV_BUF, n, bs);
+            }
         }
 #pragma unroll
         for (int kind = 0; kind < TL_KINDS; ++kind) insert_sets(m[kind], walked[kind], loc, &loc_walk, &overflow, wt, lane);
@@ -401,14 +407,14 @@ __global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, in
 }  // namespace
 
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, const void* summary,
-                              SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts, unsigned* ticket,
+                              const void* bufsum, SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts, unsigned* ticket,
                               hipStream_t stream)
 {
     i64 b = (v.n_req + CL_BLOCK - 1) / CL_BLOCK;
     if (b < 1) b = 1;
     if (b > 256) b = 256;
     hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau,
-                       (const TlSummary*)summary, S, ppcnt, ghist, dhist, parts, ticket);
+                       (const TlSummary*)summary, (const BufSummary*)bufsum, S, ppcnt, ghist, dhist, parts, ticket);
 }
 
 void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,
