@@ -204,7 +204,9 @@ __global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disc
     const i64 per = (tr.n_req + gridDim.x - 1) / gridDim.x;
     const i64 lo = (i64)blockIdx.x * per;
     const i64 hi = lo + per < tr.n_req ? lo + per : tr.n_req;
-    for (i64 i = lo + threadIdx.x; i < hi; i += AS_BLOCK) {
+    u64 wmask = 0ull;                                        // bit r: this thread's request of round r has tokens to walk
+    int round = 0;
+    for (i64 i = lo + threadIdx.x; i < hi; i += AS_BLOCK, ++round) {
         const int l = tr.l[i], n = tr.n[i];
         const float s = tr.s[i];
         const float k = tr.k ? tr.k[i] : tr.k_s;
@@ -242,6 +244,7 @@ __global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disc
             }
         }
         desc_out[i] = desc;
+        if (desc != DESC_NONE5) wmask |= 1ull << round;
         const u64 wb = __ballot(desc != DESC_NONE5);
         if (wb && lane == __ffsll((long long)wb) - 1) atomicAdd(&s_nw, (unsigned)__popcll(wb));
     }
@@ -253,8 +256,9 @@ __global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disc
     if (threadIdx.x == 0) { s_base = nw ? atomicAdd(&S->tl.nlist, nw) : 0u; s_nw = 0u; }
     __syncthreads();
     if (nw) {
-        for (i64 i = lo + threadIdx.x; i < hi; i += AS_BLOCK) {
-            const bool w = desc_out[i] != DESC_NONE5;           // this thread's own store
+        round = 0;
+        for (i64 i = lo + threadIdx.x; i < hi; i += AS_BLOCK, ++round) {
+            const bool w = (wmask >> round) & 1ull;
             const u64 wb = __ballot(w);
             if (!wb) continue;
             const int leader = __ffsll((long long)wb) - 1;
@@ -399,10 +403,10 @@ void disco_launch_tl_assign(const TraceView& v, const disco_policy* pol, int P, 
 {
     if (v.n_req <= 0) return;
     i64 b = (v.n_req + 49151) / 49152;             // at most 65535 requests per workgroup: 16-bit counts in LDS
-    if (b < 128) b = 128;
+    if (b < 250) b = 250;                          // one workgroup per CU (128 KB of LDS each); at most 64 rounds per thread
     const i64 fit = (i64)(slices_bytes / ((size_t)PP_LDS_CLS * PP_WORDS * sizeof(unsigned)));
     int use_lds = 1;
-    if (b > fit) { b = 256; use_lds = 0; }         // (a trace of tens of millions of requests: counts in device memory)
+    if (b > fit) { b = (v.n_req + 65535) / 65536; use_lds = 0; }     // (tens of millions of requests: counts in device memory)
     hipLaunchKernelGGL(k_tl_assign, dim3((unsigned)b), dim3(AS_BLOCK), 0, stream, v, pol, P, (const TlSummary*)summary,
                        (const BufSummary*)bufsum, S, desc, list, slices, ppcnt, dhist, use_lds);
     hipLaunchKernelGGL(k_pp_reduce, dim3(PP_LDS_CLS, (PP_WORDS + 255) / 256), dim3(1024), 0, stream, (const SelState*)S, (int)b, (const unsigned*)slices,

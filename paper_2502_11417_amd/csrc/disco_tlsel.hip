@@ -53,55 +53,73 @@ __device__ void tbt_plan_next(SelState* S, int P, int nq)
     tl.shift = tl.left - w;
 }
 
-// Inserts the column sets held by the lanes of a wave (0 = none) into a
-// workgroup's LDS table `loc` (entries are claimed in order, so the table is
-// dense) and records in `loc_walk` which entries have a member that needs a
-// token walk.  Common case, lane-private: the set is among the entries this
-// wave has already seen (`tab`: lane e holds entry e) and so is its walk flag;
-// only new sets or flags go through the cooperative insertion.
-struct WaveTable { u64 tab; int nknown; u64 seen_walk; };
+// Distinct column sets of a workgroup's requests: an open-addressing hash table in LDS (CL_SLOTS slots, far more
+// than the DISCO_MAX_CLS sets a class-mode selection can hold).  A lane looks its set up with one LDS read in the
+// common case (lanes with the same set read the same slot); a new set is claimed with a compare-and-swap.
+constexpr int CL_BLOCK = 1024;              // classification: 16 waves share one table, few tables to merge
+constexpr int CL_SLOTS = 256;
 
-constexpr int CL_BLOCK = 1024;              // classification: 16 waves share one LDS table, few tables to merge
+struct ClassTable {
+    u64 slot[CL_SLOTS];            // 0 = free
+    unsigned walk[CL_SLOTS];       // a member of the set needs a token walk
+    u64 dense[DISCO_MAX_CLS];      // the sets, compacted (table_compact)
+    unsigned long long dense_walk;
+    unsigned wave_cnt[CL_BLOCK / 64];
+    int overflow;
+};
 
-__device__ __forceinline__ void insert_sets(u64 m, bool walked, u64* loc, u64* loc_walk, int* overflow, WaveTable& w, int lane)
+__device__ __forceinline__ void table_clear(ClassTable& T)
 {
-    if (__ballot(m != 0ull) == 0ull) return;         // no lane has a timeline of this kind
-    const volatile u64* vloc = loc;
-    int c = -1;
-    for (int e = 0; e < w.nknown; ++e) c = (bcast_u64(w.tab, e) == m) ? e : c;
-    const bool todo = m != 0ull && (c < 0 || (walked && !((w.seen_walk >> c) & 1ull)));
-    u64 pend = __ballot(todo);
-    while (pend) {
-        const int leader = __ffsll((long long)pend) - 1;
-        const u64 m0 = bcast_u64(m, leader);
-        const u64 same = __ballot(todo && m == m0);
-        const bool wk = __ballot(todo && m == m0 && walked) != 0ull;
-        pend &= ~same;
-        int e = -1;
-        for (int attempt = 0; attempt < DISCO_MAX_CLS + 1 && e < 0; ++attempt) {
-            const u64 cur = vloc[lane];
-            const u64 hit = __ballot(cur == m0);
-            if (hit) { e = __ffsll((long long)hit) - 1; break; }
-            const u64 free = __ballot(cur == 0ull);
-            if (!free) { if (lane == 0) *overflow = 1; break; }
-            const int f = __ffsll((long long)free) - 1;
-            if (lane == 0) atomicCAS((unsigned long long*)&loc[f], 0ull, (unsigned long long)m0);
-        }
-        if (e >= 0 && wk) {
-            if (lane == 0) atomicOr((unsigned long long*)loc_walk, 1ull << e);
-            w.seen_walk |= 1ull << e;
-        }
-        w.tab = vloc[lane];
-        w.nknown = __popcll(__ballot(w.tab != 0ull));
-    }
+    for (int i = threadIdx.x; i < CL_SLOTS; i += CL_BLOCK) { T.slot[i] = 0ull; T.walk[i] = 0u; }
+    if (threadIdx.x < DISCO_MAX_CLS) T.dense[threadIdx.x] = 0ull;
+    if (threadIdx.x == 0) { T.dense_walk = 0ull; T.overflow = 0; }
 }
 
-// Column sets of every request -> classes.  Every workgroup collects its
-// distinct sets in LDS and stores that table; the last workgroup merges the
-// tables (a device-wide table claimed with atomics made a thousand workgroups
-// queue up on a few cache lines), numbers the classes that need a token walk
-// and plans the first histogram pass.  Also clears the length counts and the
-// device-wide bins.
+__device__ __forceinline__ void table_insert(ClassTable& T, u64 m, bool walked)
+{
+    if (m == 0ull) return;
+    unsigned h = (unsigned)((m * 0x9E3779B97F4A7C15ull) >> 56) & (CL_SLOTS - 1);
+    volatile u64* vs = T.slot;
+    for (int probe = 0; probe < CL_SLOTS; ++probe) {
+        u64 cur = vs[h];
+        if (cur == 0ull) cur = (u64)atomicCAS((unsigned long long*)&T.slot[h], 0ull, (unsigned long long)m);
+        if (cur == 0ull || cur == m) {           // claimed now, or already there
+            if (walked && ((volatile unsigned*)T.walk)[h] == 0u) ((volatile unsigned*)T.walk)[h] = 1u;
+            return;
+        }
+        h = (h + 1) & (CL_SLOTS - 1);
+    }
+    T.overflow = 1;                              // (more than CL_SLOTS distinct sets)
+}
+
+// All threads: the occupied slots in slot order -> dense[0 .. count), dense_walk; more than DISCO_MAX_CLS -> overflow.
+__device__ __forceinline__ int table_compact(ClassTable& T)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    const u64 v = threadIdx.x < CL_SLOTS ? T.slot[threadIdx.x] : 0ull;
+    const u64 occ = __ballot(v != 0ull);
+    if (lane == 0) T.wave_cnt[wave] = (unsigned)__popcll(occ);
+    __syncthreads();
+    int before = 0, total = 0;
+    for (int w = 0; w < CL_SLOTS / 64; ++w) { const int c = (int)T.wave_cnt[w]; before += w < wave ? c : 0; total += c; }
+    if (v != 0ull) {
+        const int pos = before + __popcll(occ & ((1ull << lane) - 1ull));
+        if (pos < DISCO_MAX_CLS) {
+            T.dense[pos] = v;
+            if (T.walk[threadIdx.x]) atomicOr(&T.dense_walk, 1ull << pos);
+        }
+    }
+    if (threadIdx.x == 0 && total > DISCO_MAX_CLS) T.overflow = 1;
+    __syncthreads();
+    return total < DISCO_MAX_CLS ? total : DISCO_MAX_CLS;
+}
+
+// Column sets of every request -> classes.  Every workgroup collects its distinct sets in an LDS hash table
+// and stores them compacted; the workgroup that takes the last ticket merges the tables of all workgroups the same
+// way, puts the sets in ascending order (so that the class numbers do not depend on timing), numbers the classes
+// that need a token walk and plans the first histogram pass.  Also clears the length counts and the device-wide
+// bins.
 //   parts: gridDim.x x (DISCO_MAX_CLS + 2) words of scratch
 __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
                                                      float tau, const TlSummary* __restrict__ summary,
@@ -110,89 +128,93 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
                                                      unsigned* ticket)
 {
     __shared__ disco_policy sp[DISCO_MAX_COLS];
-    __shared__ u64 loc[DISCO_MAX_CLS];
-    __shared__ u64 loc_walk;
-    __shared__ int overflow;
+    __shared__ ClassTable T;
     if ((int)threadIdx.x < P) sp[threadIdx.x] = pol[threadIdx.x];
-    if (threadIdx.x < DISCO_MAX_CLS) loc[threadIdx.x] = 0ull;
-    if (threadIdx.x == 0) { overflow = 0; loc_walk = 0ull; }
+    table_clear(T);
     for (i64 w = (i64)blockIdx.x * CL_BLOCK + threadIdx.x; w < (i64)DISCO_MAX_CLS * (DISCO_PP_NMAX + 1); w += (i64)gridDim.x * CL_BLOCK)
         ppcnt[w] = 0u;
     for (i64 w = (i64)blockIdx.x * CL_BLOCK + threadIdx.x; w < (i64)DISCO_GHIST_WORDS; w += (i64)gridDim.x * CL_BLOCK) ghist[w] = 0u;
     for (i64 w = (i64)blockIdx.x * CL_BLOCK + threadIdx.x; w < (i64)P * DISCO_DELAY_BINS; w += (i64)gridDim.x * CL_BLOCK) dhist[w] = 0u;
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    WaveTable wt{0ull, 0, 0ull};
     const i64 nround = (tr.n_req + CL_BLOCK - 1) / CL_BLOCK;
     for (i64 rnd = blockIdx.x; rnd < nround; rnd += gridDim.x) {
         const i64 i = rnd * CL_BLOCK + threadIdx.x;
-        u64 m[TL_KINDS] = {0ull, 0ull, 0ull, 0ull, 0ull};
-        bool walked[TL_KINDS] = {false, false, false, false, false};
-        if (i < tr.n_req) {
-            const int l = tr.l[i], n = tr.n[i];
-            const float s = tr.s[i];
-            const float k = tr.k ? tr.k[i] : tr.k_s;
-            request_sets(sp, P, l, s, __fmaf_rn((float)l, k, tr.c), i, m);
-            const TlSummary sm = summary[i];
-            walked[TL_DEV] = !timeline_is_analytic(TL_DEV, n, sm);
-            walked[TL_SRV] = !timeline_is_analytic(TL_SRV, n, sm);
-            walked[TL_SRV_LAG] = !timeline_is_analytic(TL_SRV_LAG, n, sm);
-            if ((m[TL_SRV_BUF] | m[TL_DEV_BUF]) != 0ull) {
-                const BufSummary bs = bufsum[i];
-                walked[TL_SRV_BUF] = !buf_timeline_is_analytic(TL_SRV_BUF, n, bs);
-                walked[TL_DEV_BUF] = !buf_timeline_is_analytic(TL_DEV_BUF, n, bs);
+        if (i >= tr.n_req) continue;
+        const int l = tr.l[i], n = tr.n[i];
+        const float s = tr.s[i];
+        const float k = tr.k ? tr.k[i] : tr.k_s;
+        u64 m[TL_KINDS];
+        request_sets(sp, P, l, s, __fmaf_rn((float)l, k, tr.c), i, m);
+        const TlSummary sm = summary[i];
+        table_insert(T, m[TL_DEV], !timeline_is_analytic(TL_DEV, n, sm));
+        table_insert(T, m[TL_SRV], !timeline_is_analytic(TL_SRV, n, sm));
+        table_insert(T, m[TL_SRV_LAG], !timeline_is_analytic(TL_SRV_LAG, n, sm));
+        if ((m[TL_SRV_BUF] | m[TL_DEV_BUF]) != 0ull) {
+            const BufSummary bs = bufsum[i];
+            table_insert(T, m[TL_SRV_BUF], !buf_timeline_is_analytic(TL_SRV_BUF, n, bs));
+            table_insert(T, m[TL_DEV_BUF], !buf_timeline_is_analytic(TL_DEV_BUF, n, bs));
+        }
+    }
+    table_compact(T);
+    u64* mine = parts + (size_t)blockIdx.x * (DISCO_MAX_CLS + 2);
+    if (threadIdx.x < DISCO_MAX_CLS) mine[threadIdx.x] = T.dense[threadIdx.x];
+    if (threadIdx.x == 0) { mine[DISCO_MAX_CLS] = T.dense_walk; mine[DISCO_MAX_CLS + 1] = (u64)T.overflow; }
+    if (!take_last_ticket(ticket)) return;
+    // last workgroup: the tables of all workgroups into one
+    __syncthreads();
+    table_clear(T);
+    __syncthreads();
+    {
+        constexpr int MG = 8;                                // entries per thread in flight
+        const unsigned nent = gridDim.x * (unsigned)DISCO_MAX_CLS;
+        for (unsigned base = 0; base < nent; base += CL_BLOCK * MG) {
+            u64 mv[MG], wb[MG], ov[MG];
+#pragma unroll
+            for (int j = 0; j < MG; ++j) {
+                const unsigned idx = base + j * CL_BLOCK + threadIdx.x;
+                const bool ok = idx < nent;
+                const u64* part = parts + (size_t)(ok ? idx / DISCO_MAX_CLS : 0) * (DISCO_MAX_CLS + 2);
+                mv[j] = ok ? part[idx % DISCO_MAX_CLS] : 0ull;
+                wb[j] = part[DISCO_MAX_CLS];
+                ov[j] = ok ? part[DISCO_MAX_CLS + 1] : 0ull;
+            }
+#pragma unroll
+            for (int j = 0; j < MG; ++j) {
+                if (ov[j] != 0ull) T.overflow = 1;
+                table_insert(T, mv[j], (wb[j] >> (threadIdx.x % DISCO_MAX_CLS)) & 1ull);
             }
         }
-#pragma unroll
-        for (int kind = 0; kind < TL_KINDS; ++kind) insert_sets(m[kind], walked[kind], loc, &loc_walk, &overflow, wt, lane);
     }
-    __syncthreads();
-    u64* mine = parts + (size_t)blockIdx.x * (DISCO_MAX_CLS + 2);
-    if (threadIdx.x < DISCO_MAX_CLS) mine[threadIdx.x] = loc[threadIdx.x];
-    if (threadIdx.x == 0) { mine[DISCO_MAX_CLS] = loc_walk; mine[DISCO_MAX_CLS + 1] = (u64)overflow; }
-    if (!take_last_ticket(ticket)) return;
-    // last workgroup: merge the tables of all workgroups with the same insertion
-    __syncthreads();
-    if (threadIdx.x < DISCO_MAX_CLS) loc[threadIdx.x] = 0ull;
-    if (threadIdx.x == 0) loc_walk = 0ull;
-    __syncthreads();
-    wt = WaveTable{0ull, 0, 0ull};
-    // a wave merges every 16th table: eight of them are loaded at a time, then inserted one after the other
-    constexpr int CL_AHEAD = 8;
-    for (unsigned b0 = wave; b0 < gridDim.x; b0 += CL_AHEAD * (CL_BLOCK / 64)) {
-        u64 m[CL_AHEAD], wbits[CL_AHEAD], ovf[CL_AHEAD];
-#pragma unroll
-        for (int j = 0; j < CL_AHEAD; ++j) {
-            const unsigned b = b0 + j * (CL_BLOCK / 64);
-            const u64* part = parts + (size_t)(b < gridDim.x ? b : b0) * (DISCO_MAX_CLS + 2);
-            m[j] = part[lane]; wbits[j] = part[DISCO_MAX_CLS]; ovf[j] = part[DISCO_MAX_CLS + 1];
-        }
-#pragma unroll
-        for (int j = 0; j < CL_AHEAD; ++j) {
-            if (b0 + j * (CL_BLOCK / 64) >= gridDim.x) break;
-            if (ovf[j] != 0ull && lane == 0) overflow = 1;
-            insert_sets(m[j], (wbits[j] >> lane) & 1ull, loc, &loc_walk, &overflow, wt, lane);
-        }
-    }
-    __syncthreads();
+    const int total = table_compact(T);
+    if (wave != 0) return;
+    // ascending order: lane e holds a set, its rank is the number of smaller ones
+    const u64 v = lane < total ? T.dense[lane] : ~0ull;
+    int rank = 0;
+    for (int j = 0; j < total; ++j) rank += bcast_u64(v, j) < v ? 1 : 0;
     TlSel& tl = S->tl;
-    if (threadIdx.x < DISCO_MAX_CLS) tl.cls_mask[threadIdx.x] = loc[threadIdx.x];
-    if (threadIdx.x == 0) {
-        int n = 0;
-        for (int k = 0; k < DISCO_MAX_CLS; ++k)
-            if (loc[k] != 0ull) n = k + 1;
-        tl.ncls = n > 0 ? n : 1;
-        const u64 wm = loc_walk;
+    tl.cls_mask[lane < total ? rank : lane] = lane < total ? v : 0ull;
+    // walk mask in the new numbering: bit `rank` of the lanes whose set is walked
+    u64 wm = 0ull;
+    for (int j = 0; j < total; ++j) {
+        const int rj = bcast_i(rank, j);
+        if ((T.dense_walk >> j) & 1ull) wm |= 1ull << rj;
+    }
+    {
+        // rows of the walked classes in the workgroups' LDS histogram, in class order
+        const bool wl = (wm >> lane) & 1ull;
+        const int row = __popcll(wm & ((1ull << lane) - 1ull));
+        tl.cls_slot[lane] = wl ? (signed char)row : (signed char)-1;
+        u64 t = wm;                                          // class of row `lane`: the lane-th walked class
+        for (int q = 0; q < lane && t != 0ull; ++q) t &= t - 1ull;
+        tl.slot_cls[lane] = t != 0ull ? (unsigned char)(__ffsll((long long)t) - 1) : (unsigned char)0;
+    }
+    if (lane == 0) {
+        tl.ncls = total > 0 ? total : 1;
         tl.walk_mask = wm;
-        int nw = 0;
-        for (int k = 0; k < DISCO_MAX_CLS; ++k) {
-            tl.slot_cls[k] = 0;
-            if ((wm >> k) & 1ull) { tl.cls_slot[k] = (signed char)nw; tl.slot_cls[nw] = (unsigned char)k; nw += 1; }
-            else tl.cls_slot[k] = -1;
-        }
-        tl.nwalk = nw;
+        tl.nwalk = __popcll(wm);
         tl.error = 0;
-        if (overflow) tl.fallback = 1;                 // more than DISCO_MAX_CLS distinct sets: per-slot histograms
+        if (T.overflow) tl.fallback = 1;               // more than DISCO_MAX_CLS distinct sets: per-slot histograms
         // gaps sit just above the pacing interval (down to a few thousand ulps below it after rounding): try a
         // 21-bit window of keys first
         const unsigned tb = f2u(tau);
@@ -269,7 +291,11 @@ __device__ void analytic_class(SelState* S, unsigned* ghist, const unsigned* ppc
 // class histograms of the classes that contain the slot's column (or take the
 // slot's own histogram in the fallback), walk to the digit that holds the
 // remaining rank, extend the prefix.
-__device__ void select_slot(SelState* S, int nq, const unsigned* ghist, int s, u64* wsum /* LDS, 16 */, int* s_digit, u64* s_rem)
+//   binsum: LDS scratch of binsum_cap words: the slot's bin counts are summed over its classes there with
+//   coalesced reads of the class rows (a thread then scans consecutive bins from LDS); wider digits and the
+//   fallback read the rows directly.
+__device__ void select_slot(SelState* S, int nq, const unsigned* ghist, int s, u64* wsum /* LDS, 16 */, int* s_digit, u64* s_rem,
+                            u64* binsum, int binsum_cap)
 {
     const TlSel& tl = S->tl;
     const int width = tl.width, ncls = tl.ncls, fallback = tl.fallback;
@@ -281,7 +307,19 @@ __device__ void select_slot(SelState* S, int nq, const unsigned* ghist, int s, u
     const int nbins = 1 << width;
     const int per = (nbins + (int)blockDim.x - 1) / (int)blockDim.x;      // consecutive bins per thread
     const int b0 = threadIdx.x * per;
+    const bool staged = !fallback && nbins <= binsum_cap;
+    if (staged) {
+        __syncthreads();
+        for (int b = threadIdx.x; b < nbins; b += (int)blockDim.x) {
+            u64 c = 0;
+            for (int k = 0; k < ncls; ++k)
+                if ((tl.cls_mask[k] >> col) & 1ull) c += ghist[((size_t)(g * ncls + k) << width) | b];
+            binsum[b] = c;
+        }
+        __syncthreads();
+    }
     auto bin_count = [&](int b) -> u64 {
+        if (staged) return binsum[b];
         if (fallback) return ghist[((size_t)s << width) | b];
         u64 c = 0;
         for (int k = 0; k < ncls; ++k)
@@ -371,8 +409,9 @@ __global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const u
     __shared__ u64 wsum[16];
     __shared__ int s_digit;
     __shared__ u64 s_rem;
+    __shared__ u64 binsum[2048];
     if (S->tl.width <= 0) return;
-    select_slot(S, nq, ghist, blockIdx.x, wsum, &s_digit, &s_rem);
+    select_slot(S, nq, ghist, blockIdx.x, wsum, &s_digit, &s_rem, binsum, 2048);
 }
 
 __global__ __launch_bounds__(1024) void k_tbt_plan(SelState* S, int P, int nq, unsigned* ghist)
@@ -388,7 +427,7 @@ __global__ __launch_bounds__(1024) void k_tbt_plan(SelState* S, int P, int nq, u
 __global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, int nq, unsigned* ghist, const unsigned* ppcnt,
                                                           float tau)
 {
-    __shared__ unsigned lds[DISCO_TL_HIST_WORDS];
+    __shared__ __align__(16) unsigned lds[DISCO_TL_HIST_WORDS];
     __shared__ u64 wsum[16];
     __shared__ int s_digit;
     __shared__ u64 s_rem;
@@ -398,7 +437,7 @@ __global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, in
         for (int c = 0; c < tl.ncls; ++c) analytic_class(S, ghist, ppcnt, tau, c, lds);
     __syncthreads();
     for (int s = 0; s < P * nq; ++s) {
-        select_slot(S, nq, ghist, s, wsum, &s_digit, &s_rem);
+        select_slot(S, nq, ghist, s, wsum, &s_digit, &s_rem, reinterpret_cast<u64*>(lds), DISCO_TL_HIST_WORDS / 2);
         __syncthreads();
     }
     plan_pass(S, P, nq, ghist);
@@ -412,7 +451,7 @@ void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P
 {
     i64 b = (v.n_req + CL_BLOCK - 1) / CL_BLOCK;
     if (b < 1) b = 1;
-    if (b > 256) b = 256;
+    if (b > 256) b = 256;                          // (more workgroups cost more in the merge than they save in the scan)
     hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau,
                        (const TlSummary*)summary, (const BufSummary*)bufsum, S, ppcnt, ghist, dhist, parts, ticket);
 }
