@@ -53,6 +53,7 @@ def main() -> int:
     ap.add_argument("--workload", default="config4")
     ap.add_argument("--extras", default="config1,config2,config3,config4buffer,config1stoch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--kernel-reps", type=int, default=20)
     ap.add_argument("--copy-calibration", type=int, default=0)
     args = ap.parse_args()
@@ -61,6 +62,7 @@ def main() -> int:
               file=sys.stderr)
         return 2
 
+    import numpy as np
     import torch
 
     import disco_inputs as DI
@@ -175,6 +177,39 @@ def main() -> int:
             t_enq = time.perf_counter() - t0
             sync()
             return (time.perf_counter() - t0) / steps, t_enq / steps
+
+        def time_graph_replay(self, steps):
+            """The same step captured once into a HIP graph and replayed: what is left of a step when the host only
+            issues one launch.  Returns (seconds per replayed step, the replay's statistics equal the eager step's)."""
+            if self.idx != 3 and not self.stoch:
+                self.search()
+            self.step()
+            sync()
+            want = self.stats.clone() if self.idx != 3 else None
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                self.step()                               # warm-up on the capture stream
+            torch.cuda.current_stream().wait_stream(side)
+            sync()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                self.step()
+            graph.replay()
+            sync()
+            same = None
+            if want is not None:
+                a = D.stats_to_host(self.stats, self.P)
+                b = D.stats_to_host(want, self.P)
+                same = all((a[f] == b[f]).all() if a[f].dtype.kind in "iu" else
+                           bool(np.allclose(a[f], b[f], rtol=1e-9, atol=0, equal_nan=True)) for f in a.dtype.names)
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                graph.replay()
+            sync()
+            sec = (time.perf_counter() - t0) / steps
+            del graph
+            return sec, same
 
         # ---- what a step's throughput is quoted in
         def throughput(self, sec):
@@ -311,6 +346,11 @@ def main() -> int:
         **{k: v for k, v in thr.items()},
         "roofline": roofline,
     }
+    if not args.no_graph and idx != 3 and not stoch:
+        g_sec, g_same = w.time_graph_replay(args.steps)
+        result["graph_replay"] = {"ms_per_step": g_sec * 1e3, "matches_eager_step": g_same,
+                                  "what": "the step above captured once into a HIP graph and replayed (reported beside "
+                                          "the eager step; `value` is the eager one)"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(idx)
 
@@ -328,6 +368,10 @@ def main() -> int:
         s, hs = w.time_steps(steps, 1)
         ex = {"n_req": w.N, "policy_columns": w.P, "token_events": w.T, "ms_per_step": s * 1e3, "host_ms_per_step": hs * 1e3}
         ex.update(w.throughput(s))
+        if not args.no_graph and not stoch and k != 3:
+            g_sec, g_same = w.time_graph_replay(steps)
+            ex["graph_replay_ms_per_step"] = g_sec * 1e3
+            ex["graph_replay_matches_eager_step"] = g_same
         if w.cfg["timelines"] and not buffer:
             ex["roofline"] = w.walk_roofline(name, 10)
         elif not w.cfg["timelines"] and not stoch:

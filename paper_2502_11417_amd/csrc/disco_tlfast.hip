@@ -406,7 +406,8 @@ void disco_launch_tl_assign(const TraceView& v, const disco_policy* pol, int P, 
     if (b < 250) b = 250;                          // one workgroup per CU (128 KB of LDS each); at most 64 rounds per thread
     const i64 fit = (i64)(slices_bytes / ((size_t)PP_LDS_CLS * PP_WORDS * sizeof(unsigned)));
     int use_lds = 1;
-    if (b > fit) { b = (v.n_req + 65535) / 65536; use_lds = 0; }     // (tens of millions of requests: counts in device memory)
+    // tens of millions of requests (or the testing aid that shrinks the grids): counts in device memory
+    if (b > fit || disco_grid_divisor() > 1) { b = (v.n_req + 65535) / 65536; use_lds = 0; }
     hipLaunchKernelGGL(k_tl_assign, dim3((unsigned)b), dim3(AS_BLOCK), 0, stream, v, pol, P, (const TlSummary*)summary,
                        (const BufSummary*)bufsum, S, desc, list, slices, ppcnt, dhist, use_lds);
     hipLaunchKernelGGL(k_pp_reduce, dim3(PP_LDS_CLS, (PP_WORDS + 255) / 256), dim3(1024), 0, stream, (const SelState*)S, (int)b, (const unsigned*)slices,
@@ -429,6 +430,8 @@ void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy
     // at once) and get a small grid, which makes the empty launch cheaper and a needed one merely slower
     const i64 cap = a.pass < 2 ? 512 : 64;
     if (b > cap) b = cap;
+    b /= disco_grid_divisor();
+    if (b < 1) b = 1;
     const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
     hipLaunchKernelGGL(k_tl_hist, dim3((unsigned)b), dim3(TH_BLOCK), 0, stream, v, n_tok, align, h);
 }

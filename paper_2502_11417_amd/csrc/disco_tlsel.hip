@@ -452,6 +452,8 @@ void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P
     i64 b = (v.n_req + CL_BLOCK - 1) / CL_BLOCK;
     if (b < 1) b = 1;
     if (b > 256) b = 256;                          // (more workgroups cost more in the merge than they save in the scan)
+    b /= disco_grid_divisor();
+    if (b < 1) b = 1;
     hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau,
                        (const TlSummary*)summary, (const BufSummary*)bufsum, S, ppcnt, ghist, dhist, parts, ticket);
 }

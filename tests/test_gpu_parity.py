@@ -419,6 +419,29 @@ def test_stats_timelines_many_column_sets(B, oracle):
     check_stats(B, oracle, tr2, mixed_policies(lag=True), DI.COST_S, tau=DI.TAU, kappa=DI.KAPPA_LAG)
 
 
+def test_stats_timelines_more_classes_than_counted_in_lds(B, oracle):
+    """24 length-threshold columns with alternating hand-off kinds: up to 50 nested column sets, i.e. more classes
+    than the selection counts per workgroup in LDS (the rest is counted in device memory), most of them analytic."""
+    print("stats parity timelines 24 threshold columns", flush=True)
+    tr = DI.handmade_trace(77, 3000, tokens=True, max_out=200, stall_p=0.004)
+    lths = np.unique(np.quantile(tr["prompt_len"], np.linspace(0.02, 0.98, 24)).astype(np.int64))
+    specs = [dict(mode=0, l_th=int(l), mig_mode=j % 2) for j, l in enumerate(lths)]
+    assert len(specs) > 16
+    check_stats(B, oracle, tr, specs, DI.COST_S, tau=DI.TAU, kappa=DI.KAPPA_LAG)
+
+
+def test_stats_timelines_under_shrunk_grids(B, oracle):
+    """The same statistics with every grid shrunk (testing aid of the library): few workgroups take many rounds each,
+    and the selection counts its analytic timelines in device memory instead of LDS."""
+    print("stats parity timelines, grids / 16", flush=True)
+    tr = DI.handmade_trace(78, 5000, tokens=True, max_out=160, stall_p=0.01)
+    try:
+        assert B._lib.disco_set_grid_divisor(16) == 0
+        check_stats(B, oracle, tr, mixed_policies(lag=True), DI.COST_S, tau=DI.TAU, kappa=DI.KAPPA_LAG)
+    finally:
+        assert B._lib.disco_set_grid_divisor(1) == 0
+
+
 @pytest.mark.parametrize("hi_extra,which", [(1, "server_prefill_tok"), (60_000, "server_prefill_tok"),
                                             (1, "device_prefill_tok"), (1, "total_cost")])
 def test_threshold_search_paths(B, oracle, hi_extra, which):
