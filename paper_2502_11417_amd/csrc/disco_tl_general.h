@@ -23,11 +23,23 @@ typedef BufCostArgs BufCost;
 //   deliv: nullable, delivery offsets of the request's tokens
 //   sink(key[4], ok[4]): called once per chunk by all lanes (ok marks real gaps)
 // Returns m = the lag trigger's first device token, or the last source token of a buffer hand-off.
+//   stop_paced: the caller needs only the result (no deliveries, no gaps): a hand-off to the device whose tail is
+//           provably paced ends the walk (see below)
+//
+// Paced tail behind a buffer hand-off to the device (variant 3).  At the hand-off token m the slack
+// S = fl(delta_m - r_m) covers the migration time TM, the target's arrivals are R_t = fma(t - m, g, fl(r_m + TM))
+// and delta_m = fl(m tau + M_m).  With e = 2^-24 and every quantity non-negative (first arrival, r_m, TM, g: checked),
+//   fl(r_m + TM) <= (r_m + S)(1 + e) <= delta_m (1 + e)^2 <= (m tau + M_m)(1 + e)^3,
+// so for t = m + j:  fl(R_t - t tau) <= M_m - j (tau - g) + 6 e (t tau + M_m), and the pacing slot
+// fl(delta_{t-1} + tau) >= t tau + M_m - 2 e (t tau + M_m).  If tau - g >= 2^-20 ((m + 2) tau + M_m), i.e. 16 e
+// of the largest magnitude, then j (tau - g) exceeds both error terms for every j >= 1: u_t = fl(R_t - t tau)
+// <= M_m (the running maximum stays M_m, the last delivery is fma(n - 1, tau, M_m)) and R_t is never above its
+// pacing slot (no delayed token).  Requests that miss the condition are walked to the end.
 template <class Sink>
 __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const float* __restrict__ arr, i64 off, i64 n_tok,
                                                        int align, float gap_srv, float g_dev, int l, float k, float c,
                                                        float s_ttft, const BufCost& bc, float tau, float kt, int lane,
-                                                       float* __restrict__ deliv, Sink&& sink)
+                                                       float* __restrict__ deliv, Sink&& sink, bool stop_paced = false)
 {
     const bool src_dev = variant == 0 || variant == 4;
     const bool buffer = variant >= 3;
@@ -73,7 +85,7 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
             const float rf = mis == 0 ? r[0] : (mis == 1 ? r[1] : (mis == 2 ? r[2] : r[3]));
             r_first = bcast_f(rf, 0);
         }
-        float d[4], prev[4];
+        float d[4], prev[4], Mq[4];
         float Mlast;
         auto scan = [&]() {
             float u[4], mx[4];
@@ -83,7 +95,7 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
             const float incl = wave_incl_max_dpp(mx[3], lane);
             const float excl = fmaxf(wave_prev(incl, -INFINITY), carryM);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) d[q] = __fmaf_rn(tf[q], tau, fmaxf(excl, mx[q]));
+            for (int q = 0; q < 4; ++q) { Mq[q] = fmaxf(excl, mx[q]); d[q] = __fmaf_rn(tf[q], tau, Mq[q]); }
             Mlast = fmaxf(excl, mx[3]);
             prev[0] = wave_prev(d[3], carryD);
             prev[1] = d[0]; prev[2] = d[1]; prev[3] = d[2];
@@ -139,6 +151,19 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
                 m = bcast_i(tb, ml) + bcast_i(qf, ml);
                 base = bcast_f(rm, ml) + bcast_f(tmm, ml);
                 a_m = bcast_f(am, ml);
+                if (stop_paced && variant == 3) {
+                    const float tfm = trig[0] ? tf[0] : (trig[1] ? tf[1] : (trig[2] ? tf[2] : tf[3]));
+                    // M_m: the running maximum through token m, from the hand-off lane
+                    const float mq = trig[0] ? Mq[0] : (trig[1] ? Mq[1] : (trig[2] ? Mq[2] : Mq[3]));
+                    const float M_m = bcast_f(mq, ml);
+                    const float r_m = bcast_f(rm, ml);
+                    const float reach = __fmaf_rn(bcast_f(tfm, ml) + 2.0f, tau, fabsf(M_m));
+                    if (r_m >= 0.0f && r_first >= 0.0f && bcast_f(tmm, ml) >= 0.0f && g_dev >= 0.0f &&
+                        tau - g_dev >= 9.5367431640625e-07f * reach) {
+                        const float tl_ = __fmaf_rn((float)(n - 1), tau, M_m);
+                        return TimelineResult{m, tl_, 0, M_m, r_first};
+                    }
+                }
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
                     if (tk[q] > m) r[q] = val[q] ? arrival(q) : -INFINITY;

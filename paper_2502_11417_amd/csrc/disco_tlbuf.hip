@@ -63,7 +63,7 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
                 if (!mask) continue;
                 auto sink = [](const unsigned*, const bool*) {};
                 const TimelineResult res = run_timeline(variant, n, tr.arr, off, n_tok, align, gap, gd, l, k, tr.c, s_ttft, a.bc,
-                                                        a.tau, a.kt, lane, nullptr, sink);
+                                                        a.tau, a.kt, lane, nullptr, sink, true);
                 if (variant == TL_DEV_BUF) { bs.M_d = res.M; bs.m_d = buf_m_enc(res.m, res.r0); bs.delay_d = res.delay; }
                 else { bs.M_s = res.M; bs.m_s = buf_m_enc(res.m, res.r0); bs.delay_s = res.delay; }
                 if (a.totals != nullptr && ((mask >> lane) & 1ull)) {

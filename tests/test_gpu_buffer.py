@@ -102,6 +102,33 @@ def test_buffer_migration_late_handoffs(B, oracle):
         check_stats(B, oracle, tr, specs, cost, tau=tau, kappa=3.0)
 
 
+def test_buffer_handoff_to_devices_barely_faster_than_the_pacing(B, oracle):
+    """Devices whose gap is tau (1 - 2^-k), k = 6 .. 23: behind a hand-off the target's arrivals creep ahead of the
+    pacing slots by less and less, down to where fp32 rounding decides whether a token is late.  The statistics walk
+    ends at the hand-off where it can prove the tail paced and walks on otherwise; both must give the oracle's bits."""
+    print("buffer migration parity, device gap just below tau", flush=True)
+    tau = 0.2
+    rng = np.random.default_rng(23)
+    tr = DI.handmade_trace(211, 360, tokens=True, max_out=1500, stall_p=0.0)
+    tr["prompt_len"] = (tr["prompt_len"] % 500 + 1).astype(np.int32)
+    n, off = tr["output_len"], tr["tok_off"]
+    gaps = rng.lognormal(math.log(tau) - 0.35, 0.45, int(off[-1])).astype(np.float32)
+    arr = np.empty(int(off[-1]), np.float32)
+    for i in range(len(n)):
+        a, b = int(off[i]), int(off[i + 1])
+        arr[a] = 0
+        arr[a + 1:b] = np.cumsum(gaps[a + 1:b], dtype=np.float32)
+    tr = dict(tr, tok_arr=arr)
+    k = 6 + np.arange(len(n)) % 18
+    tr["dev_dec_spt"] = (np.float32(tau) * (np.float32(1.0) - np.exp2(-k.astype(np.float32)))).astype(np.float32)
+    tr["dev_pre_spt"] = (tr["dev_dec_spt"] / np.float32(10.0)).astype(np.float32)      # the server wins the races
+    specs = [dict(mode=0, l_th=0, mig_mode=2), dict(mode=0, l_th=60, mig_mode=2)]
+    _, acc, want = check_migration(B, oracle, tr, specs, tau, 3.0, delivered_col=0, cost=DI.COST_S)
+    m = want["mig_idx"][0]
+    assert (m >= 0).sum() > 100 and (m >= 256).sum() > 3, ((m >= 0).sum(), (m >= 256).sum())
+    check_stats(B, oracle, tr, specs, DI.COST_S, tau=tau, kappa=3.0)
+
+
 @pytest.mark.parametrize("cost", ["S", "D"])
 def test_buffer_stats(B, oracle, cost):
     print(f"buffer statistics parity cost={cost}", flush=True)
