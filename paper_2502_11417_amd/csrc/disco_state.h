@@ -99,7 +99,9 @@ struct TlSel {
     unsigned key_lo;
     int window;                    // key bits of the window, 0 = raw 31-bit keys
     int restart;
-    unsigned nlist;                // requests with a timeline whose tokens are walked (entries of the walk list)
+    unsigned nlist;                // requests with a timeline whose tokens are walked: entries at the front of the walk list
+    unsigned nlist_back;           // ... and entries at its back (the short requests, see walk_list_entry)
+    unsigned pad2;
     signed char cls_slot[DISCO_MAX_CLS];     // row of a walked class in the workgroups' LDS histogram, -1 otherwise
     unsigned char slot_cls[DISCO_MAX_CLS];   // class of an LDS row
 };

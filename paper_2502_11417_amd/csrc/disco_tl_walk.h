@@ -136,7 +136,7 @@ struct HistArgs {
     unsigned* ppcnt;
     const TlSummary* summary;      // per request, from the token walk
     const u64* desc;               // per request: LDS rows of its timelines that have tokens to walk (one byte per kind)
-    const unsigned* list;          // requests with such a timeline (TlSel::nlist entries, any order)
+    const unsigned* list;          // requests with such a timeline (see walk_list_entry)
 };
 
 // Digit of this pass and the rows of the LDS histogram.
@@ -147,6 +147,15 @@ struct HistCtx {
     unsigned stride;               // words per prefix group = nwalk << width
     unsigned grp_prefix[DISCO_MAX_GRP];
 };
+
+// The walk list of the TBT selection: requests with 3 or more 256-token chunks are entered from the front, the
+// others from the back of an array of `cap` slots.  The histogram kernels deal entry v to wave v mod W, so the long
+// requests (which decide how long a pass takes) are spread evenly over the waves before the short ones fill in.
+constexpr int WALK_LONG_TOKENS = 513;
+__device__ __forceinline__ unsigned walk_list_entry(const unsigned* __restrict__ list, i64 cap, i64 nfront, i64 v)
+{
+    return v < nfront ? list[v] : list[cap - 1 - (v - nfront)];
+}
 
 // Every key of the chunk goes to the histogram row (prefix group of the key,
 // class of the timeline).  The bin shared by most of the wave is counted with

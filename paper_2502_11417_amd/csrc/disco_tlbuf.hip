@@ -140,14 +140,15 @@ __global__ __launch_bounds__(TBH_BLOCK) void k_tl_hist_buf(TraceView tr, i64 n_t
     for (int i = threadIdx.x; i < words; i += TBH_BLOCK) smem[i] = 0u;
     __syncthreads();
     const i64 nwaves = (i64)gridDim.x * (TBH_BLOCK / 64);
-    const i64 nlist = (i64)tl->nlist;
+    const i64 nfront = (i64)tl->nlist, nlist = nfront + (i64)tl->nlist_back;
     i64 rb = (nlist + nwaves - 1) / nwaves;
     rb = rb < 1 ? 1 : (rb > 64 ? 64 : rb);
-    const i64 ngroup = (nlist + rb - 1) / rb;
-    for (i64 gr = (i64)blockIdx.x * (TBH_BLOCK / 64) + wave; gr < ngroup; gr += nwaves) {
-        const i64 j = gr * rb + lane;
+    const i64 nround = (nlist + rb * nwaves - 1) / (rb * nwaves);
+    for (i64 rnd = 0; rnd < nround; ++rnd) {
+        const i64 gw = (i64)blockIdx.x * (TBH_BLOCK / 64) + wave;
+        const i64 j = rnd * rb * nwaves + gw + (i64)lane * nwaves;
         const bool mine = lane < rb && j < nlist;
-        const i64 il = mine ? (i64)a.list[j] : 0;
+        const i64 il = mine ? (i64)walk_list_entry(a.list, tr.n_req, nfront, j) : 0;
         const unsigned desc = mine ? (unsigned)((a.desc[il] >> 24) & 0xFFFFull) : 0xFFFFu;
         u64 walkers = __ballot(desc != 0xFFFFu);
         if (!walkers) continue;

@@ -186,7 +186,7 @@ __global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disc
                                                         unsigned* __restrict__ dhist, int use_lds)
 {
     __shared__ unsigned cnt[PP_LDS_CLS * PP_WORDS];          // 128 KB
-    __shared__ unsigned s_nw, s_base;
+    __shared__ unsigned s_nw[2], s_base[2];                  // [0] long requests (front of the list), [1] the others (back)
     __shared__ u64 s_cls[DISCO_MAX_CLS];
     __shared__ signed char s_slot[DISCO_MAX_CLS];
     __shared__ disco_policy spol[DISCO_MAX_COLS];
@@ -197,14 +197,14 @@ __global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disc
     if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
     if (threadIdx.x < DISCO_MAX_CLS) { s_cls[threadIdx.x] = tl->cls_mask[threadIdx.x]; s_slot[threadIdx.x] = tl->cls_slot[threadIdx.x]; }
     for (int i = threadIdx.x; i < nlds * PP_WORDS; i += AS_BLOCK) cnt[i] = 0u;
-    if (threadIdx.x == 0) s_nw = 0u;
+    if (threadIdx.x < 2) s_nw[threadIdx.x] = 0u;
     __syncthreads();
     const int lane = threadIdx.x & 63;
     // a contiguous share of the requests per workgroup (at most 65535, see the launch)
     const i64 per = (tr.n_req + gridDim.x - 1) / gridDim.x;
     const i64 lo = (i64)blockIdx.x * per;
     const i64 hi = lo + per < tr.n_req ? lo + per : tr.n_req;
-    u64 wmask = 0ull;                                        // bit r: this thread's request of round r has tokens to walk
+    u64 wmask = 0ull, lmask = 0ull;                          // bit r: this thread's request of round r has tokens to walk / is long
     int round = 0;
     for (i64 i = lo + threadIdx.x; i < hi; i += AS_BLOCK, ++round) {
         const int l = tr.l[i], n = tr.n[i];
@@ -244,28 +244,47 @@ __global__ __launch_bounds__(AS_BLOCK) void k_tl_assign(TraceView tr, const disc
             }
         }
         desc_out[i] = desc;
-        if (desc != DESC_NONE5) wmask |= 1ull << round;
-        const u64 wb = __ballot(desc != DESC_NONE5);
-        if (wb && lane == __ffsll((long long)wb) - 1) atomicAdd(&s_nw, (unsigned)__popcll(wb));
+        const bool walk = desc != DESC_NONE5, lng = n >= WALK_LONG_TOKENS;
+        if (walk) wmask |= 1ull << round;
+        if (walk && lng) lmask |= 1ull << round;
+        const u64 wb = __ballot(walk);
+        if (wb) {
+            const u64 lb = __ballot(walk && lng);
+            if (lane == __ffsll((long long)wb) - 1) {
+                if (lb) atomicAdd(&s_nw[0], (unsigned)__popcll(lb));
+                if (wb & ~lb) atomicAdd(&s_nw[1], (unsigned)__popcll(wb & ~lb));
+            }
+        }
     }
     __syncthreads();
     // the requests with tokens to walk go to a device-wide list (any order: the histograms are sums), a range of it
     // per workgroup
-    const unsigned nw = s_nw;
+    const unsigned nw0 = s_nw[0], nw1 = s_nw[1];
     __syncthreads();
-    if (threadIdx.x == 0) { s_base = nw ? atomicAdd(&S->tl.nlist, nw) : 0u; s_nw = 0u; }
+    if (threadIdx.x == 0) {
+        s_base[0] = nw0 ? atomicAdd(&S->tl.nlist, nw0) : 0u;
+        s_base[1] = nw1 ? atomicAdd(&S->tl.nlist_back, nw1) : 0u;
+        s_nw[0] = 0u; s_nw[1] = 0u;
+    }
     __syncthreads();
-    if (nw) {
+    if (nw0 | nw1) {
         round = 0;
         for (i64 i = lo + threadIdx.x; i < hi; i += AS_BLOCK, ++round) {
-            const bool w = (wmask >> round) & 1ull;
+            const bool w = (wmask >> round) & 1ull, lng = (lmask >> round) & 1ull;
             const u64 wb = __ballot(w);
             if (!wb) continue;
+            const u64 lb = __ballot(w && lng), sb = wb & ~lb;
             const int leader = __ffsll((long long)wb) - 1;
-            unsigned at = 0u;
-            if (lane == leader) at = atomicAdd(&s_nw, (unsigned)__popcll(wb));
-            at = (unsigned)bcast_i((int)at, leader);
-            if (w) list[s_base + at + (unsigned)__popcll(wb & ((1ull << lane) - 1ull))] = (unsigned)i;
+            unsigned at0 = 0u, at1 = 0u;
+            if (lane == leader) {
+                if (lb) at0 = atomicAdd(&s_nw[0], (unsigned)__popcll(lb));
+                if (sb) at1 = atomicAdd(&s_nw[1], (unsigned)__popcll(sb));
+            }
+            at0 = (unsigned)bcast_i((int)at0, leader);
+            at1 = (unsigned)bcast_i((int)at1, leader);
+            const u64 below = (1ull << lane) - 1ull;
+            if (w && lng) list[s_base[0] + at0 + (unsigned)__popcll(lb & below)] = (unsigned)i;
+            if (w && !lng) list[(size_t)tr.n_req - 1 - (s_base[1] + at1 + (unsigned)__popcll(sb & below))] = (unsigned)i;
         }
     }
     unsigned* mine = slices + (size_t)blockIdx.x * PP_LDS_CLS * PP_WORDS;
@@ -323,14 +342,16 @@ __global__ __launch_bounds__(TH_BLOCK, 8) void k_tl_hist(TraceView tr, i64 n_tok
     const bool mem = tr.arr != nullptr;
     // the walk list is shared out in batches of rb entries (lane = entry) so that every wave gets some
     const i64 nwaves = (i64)gridDim.x * (TH_BLOCK / 64);
-    const i64 nlist = (i64)tl->nlist;
+    const i64 nfront = (i64)tl->nlist, nlist = nfront + (i64)tl->nlist_back;
     i64 rb = (nlist + nwaves - 1) / nwaves;
     rb = rb < 1 ? 1 : (rb > 64 ? 64 : rb);
-    const i64 ngroup = (nlist + rb - 1) / rb;
-    for (i64 gr = (i64)blockIdx.x * (TH_BLOCK / 64) + wave; gr < ngroup; gr += nwaves) {
-        const i64 j = gr * rb + lane;
+    // wave w of a round takes the entries w, w + W, ... (lane = which of them), W = waves x rounds needed
+    const i64 nround = (nlist + rb * nwaves - 1) / (rb * nwaves);
+    for (i64 rnd = 0; rnd < nround; ++rnd) {
+        const i64 gw = (i64)blockIdx.x * (TH_BLOCK / 64) + wave;
+        const i64 j = rnd * rb * nwaves + gw + (i64)lane * nwaves;
         const bool mine = lane < rb && j < nlist;
-        const i64 i = mine ? (i64)a.list[j] : 0;
+        const i64 i = mine ? (i64)walk_list_entry(a.list, tr.n_req, nfront, j) : 0;
         const unsigned desc = mine ? (unsigned)(a.desc[i] & 0xFFFFFFull) : DESC_NONE;
         u64 walkers = __ballot(desc != DESC_NONE);
         if (!walkers) continue;

@@ -220,6 +220,7 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
         const unsigned tb = f2u(tau);
         tl.restart = 0;
         tl.nlist = 0u;
+        tl.nlist_back = 0u;
         if (tb >= 8192u) { tl.key_lo = tb - 8192u; tl.window = 21; tl.left = 21; }
         else { tl.key_lo = 0u; tl.window = 0; tl.left = 31; }
         tbt_plan_next(S, P, nq);
