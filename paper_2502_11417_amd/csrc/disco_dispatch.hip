@@ -623,15 +623,18 @@ __global__ __launch_bounds__(1024) void k_len_suffix(int nbins, u64* table, u64*
         u64 sum = 0;
 #pragma unroll
         for (int q = 0; q < 8; ++q) if (8 * t + q < len) sum += tile[9 * t + q];
-        part[t] = sum;
-        __syncthreads();
-        for (int d = 1; d < 1024; d <<= 1) {        // inclusive suffix sums of the per-thread totals
-            const u64 o = (t + d < 1024) ? part[t + d] : 0;
-            __syncthreads();
-            part[t] += o;
-            __syncthreads();
+        // suffix sums of the per-thread totals: within the wave by shuffles, across the 16 waves through LDS
+        u64 incl = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const unsigned lo32 = (unsigned)__shfl_down((int)(unsigned)incl, d, 64);
+            const unsigned hi32 = (unsigned)__shfl_down((int)(unsigned)(incl >> 32), d, 64);
+            if ((t & 63) + d < 64) incl += ((u64)hi32 << 32) | lo32;
         }
-        u64 above = ((t + 1 < 1024) ? part[t + 1] : 0) + carry;
+        if ((t & 63) == 0) part[t >> 6] = incl;     // the wave's total
+        __syncthreads();
+        u64 above = incl - sum + carry;             // the threads above this one in its wave
+        for (int w = (t >> 6) + 1; w < 16; ++w) above += part[w];
 #pragma unroll
         for (int q = 7; q >= 0; --q)
             if (8 * t + q < len) { above += tile[9 * t + q]; tile[9 * t + q] = above; }

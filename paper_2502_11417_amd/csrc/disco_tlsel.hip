@@ -295,7 +295,7 @@ __device__ void analytic_class(SelState* S, unsigned* ghist, const unsigned* ppc
 //   binsum: LDS scratch of binsum_cap words: the slot's bin counts are summed over its classes there with
 //   coalesced reads of the class rows (a thread then scans consecutive bins from LDS); wider digits and the
 //   fallback read the rows directly.
-__device__ void select_slot(SelState* S, int nq, const unsigned* ghist, int s, u64* wsum /* LDS, 16 */, int* s_digit, u64* s_rem,
+__device__ void select_slot(SelState* S, int nq, const unsigned* ghist, int s, u64* wsum /* LDS, 64 */, int* s_digit, u64* s_rem,
                             u64* binsum, int binsum_cap)
 {
     const TlSel& tl = S->tl;
@@ -310,11 +310,21 @@ __device__ void select_slot(SelState* S, int nq, const unsigned* ghist, int s, u
     const int b0 = threadIdx.x * per;
     const bool staged = !fallback && nbins <= binsum_cap;
     if (staged) {
+        // the classes that contain the column (the first wave lists them in wsum[0 .. nk), nk in *s_digit), then
+        // every bin is the sum over their rows: all loads independent and coalesced
         __syncthreads();
+        if (wave == 0) {
+            const bool in = lane < ncls && ((tl.cls_mask[lane] >> col) & 1ull);
+            const u64 inb = __ballot(in);
+            if (in) wsum[__popcll(inb & ((1ull << lane) - 1ull))] = (u64)lane;
+            if (lane == 0) *s_digit = __popcll(inb);
+        }
+        __syncthreads();
+        const int nk = *s_digit;
         for (int b = threadIdx.x; b < nbins; b += (int)blockDim.x) {
             u64 c = 0;
-            for (int k = 0; k < ncls; ++k)
-                if ((tl.cls_mask[k] >> col) & 1ull) c += ghist[((size_t)(g * ncls + k) << width) | b];
+#pragma unroll 4
+            for (int j = 0; j < nk; ++j) c += ghist[((size_t)(g * ncls + (int)wsum[j]) << width) | b];
             binsum[b] = c;
         }
         __syncthreads();
@@ -407,7 +417,7 @@ __global__ __launch_bounds__(1024) void k_tbt_analytic(SelState* S, unsigned* gh
 
 __global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const unsigned* ghist)
 {
-    __shared__ u64 wsum[16];
+    __shared__ u64 wsum[DISCO_MAX_CLS];
     __shared__ int s_digit;
     __shared__ u64 s_rem;
     __shared__ u64 binsum[2048];
@@ -429,7 +439,7 @@ __global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, in
                                                           float tau)
 {
     __shared__ __align__(16) unsigned lds[DISCO_TL_HIST_WORDS];
-    __shared__ u64 wsum[16];
+    __shared__ u64 wsum[DISCO_MAX_CLS];
     __shared__ int s_digit;
     __shared__ u64 s_rem;
     const TlSel& tl = S->tl;

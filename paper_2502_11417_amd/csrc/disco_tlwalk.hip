@@ -465,18 +465,19 @@ __global__ __launch_bounds__(TW_BLOCK) void k_tl_walk_rest(TraceView tr, i64 n_t
 {
     // row maxima per wave, slot (0 server walk, 1 server walk without hand-off beside a hand-off that fired,
     // 2 device source) and request of the batch
-    __shared__ __align__(16) float red[TW_WAVES][3][TF_RB][4];
+    constexpr int WR_RB = 64;                                // requests per wave and round: one flag byte per lane
+    __shared__ __align__(16) float red[TW_WAVES][3][WR_RB][4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float lane4f = (float)(4 * lane);
     const float tau = a.tau, kt = a.kt;
     const LagConst lc{262144.0f * (kt / tau), 262144.0f * kt, kt >= tau * 0.0009765625f};
     const bool mem = tr.arr != nullptr;
-    float (*myred)[TF_RB][4] = red[wave];
-    const i64 nbatch = (tr.n_req + TF_RB - 1) / TF_RB;
+    float (*myred)[WR_RB][4] = red[wave];
+    const i64 nbatch = (tr.n_req + WR_RB - 1) / WR_RB;
     for (i64 bt = (i64)blockIdx.x * TW_WAVES + wave; bt < nbatch; bt += (i64)gridDim.x * TW_WAVES) {
-        const i64 first = bt * TF_RB;
+        const i64 first = bt * WR_RB;
         const i64 il = first + lane;
-        const bool valid = lane < TF_RB && il < tr.n_req;
+        const bool valid = il < tr.n_req;
         const unsigned f = valid ? a.wflags[il] : 0u;
         const bool srv_here = (f & (WF_LAG | WF_PLAIN)) != 0u && (!streamed || (f & WF_REDO) != 0u);
         u64 todo0 = __ballot(srv_here), todo1 = 0ull;
@@ -734,7 +735,7 @@ void disco_launch_tl_walk(const TraceView& v, i64 n_tok, const disco_policy* pol
     } else {
         hipLaunchKernelGGL(k_tl_summary_clear, dim3((unsigned)fb), dim3(256), 0, stream, v.n_req, (TlSummary*)summary);
     }
-    i64 rb_ = (v.n_req + (i64)TW_WAVES * TF_RB - 1) / ((i64)TW_WAVES * TF_RB);
+    i64 rb_ = (v.n_req + (i64)TW_WAVES * 64 - 1) / ((i64)TW_WAVES * 64);          // 64 requests per wave and round
     if (rb_ < 1) rb_ = 1;
     if (rb_ > 2048) rb_ = 2048;
     hipLaunchKernelGGL(k_tl_walk_rest, dim3((unsigned)rb_), dim3(TW_BLOCK), 0, stream, v, n_tok, w, mem ? 1 : 0);
