@@ -98,6 +98,8 @@ __device__ void select_init(const SelInit& si, int which, int P, const disco_pol
     }
     if (which == 1) {
         for (int i = threadIdx.x; i < DISCO_MAX_CLS; i += blockDim.x) S->tl.cls_mask[i] = 0ull;
+        for (int i = threadIdx.x; i < DISCO_CLS_SLOTS; i += blockDim.x) { S->tl.gslot[i] = 0ull; S->tl.gwalk[i] = 0u; }
+        if (threadIdx.x == 0) S->tl.goverflow = 0;
         for (int i = threadIdx.x; i < DISCO_MAX_SLOTS; i += blockDim.x) S->tl.slot_grp[i] = -1;
     }
     for (int s = threadIdx.x; s < P * nq; s += blockDim.x) {

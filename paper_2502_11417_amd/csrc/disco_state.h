@@ -77,7 +77,7 @@ struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
 // nested, so there are at most P + 1 of them), not once per column.  Keys are
 // the raw 31-bit patterns of the gaps.  The digit of each pass is sized on the
 // device from the number of classes and of distinct prefixes still alive.
-enum { DISCO_MAX_CLS = 64, DISCO_MAX_GRP = 4, DISCO_TBT_MAX_PASS = 6,
+enum { DISCO_MAX_CLS = 64, DISCO_CLS_SLOTS = 256, DISCO_MAX_GRP = 4, DISCO_TBT_MAX_PASS = 6,
        DISCO_TL_HIST_WORDS = 16384,   // LDS bins of a timeline workgroup (64 KB: two workgroups per CU)
        DISCO_GHIST_WORDS = 262144,    // device-wide bins (1 MB)
        DISCO_PP_NMAX = 4096,          // pure-pacing timelines up to this length are histogrammed analytically
@@ -102,6 +102,12 @@ struct TlSel {
     unsigned nlist;                // requests with a timeline whose tokens are walked: entries at the front of the walk list
     unsigned nlist_back;           // ... and entries at its back (the short requests, see walk_list_entry)
     unsigned pad2;
+    // device-wide hash table of the column sets (classification): every workgroup enters its distinct sets, the last
+    // one numbers them; zeroed when a selection starts
+    u64 gslot[DISCO_CLS_SLOTS];
+    unsigned gwalk[DISCO_CLS_SLOTS];
+    int goverflow;
+    int pad3;
     signed char cls_slot[DISCO_MAX_CLS];     // row of a walked class in the workgroups' LDS histogram, -1 otherwise
     unsigned char slot_cls[DISCO_MAX_CLS];   // class of an LDS row
 };

@@ -57,7 +57,7 @@ __device__ void tbt_plan_next(SelState* S, int P, int nq)
 // than the DISCO_MAX_CLS sets a class-mode selection can hold).  A lane looks its set up with one LDS read in the
 // common case (lanes with the same set read the same slot); a new set is claimed with a compare-and-swap.
 constexpr int CL_BLOCK = 1024;              // classification: 16 waves share one table, few tables to merge
-constexpr int CL_SLOTS = 256;
+constexpr int CL_SLOTS = DISCO_CLS_SLOTS;
 
 struct ClassTable {
     u64 slot[CL_SLOTS];            // 0 = free
@@ -116,11 +116,10 @@ __device__ __forceinline__ int table_compact(ClassTable& T)
 }
 
 // Column sets of every request -> classes.  Every workgroup collects its distinct sets in an LDS hash table
-// and stores them compacted; the workgroup that takes the last ticket merges the tables of all workgroups the same
-// way, puts the sets in ascending order (so that the class numbers do not depend on timing), numbers the classes
-// that need a token walk and plans the first histogram pass.  Also clears the length counts and the device-wide
-// bins.
-//   parts: gridDim.x x (DISCO_MAX_CLS + 2) words of scratch
+// and enters them (a few dozen) into a device-wide table of the same kind; the workgroup that takes the last
+// ticket compacts that table, puts the sets in ascending order (so that the class numbers do not depend on
+// timing), numbers the classes that need a token walk and plans the first histogram pass.  Also clears the length
+// counts and the device-wide bins.  The device-wide table was zeroed when the selection started (k_select_init).
 __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
                                                      float tau, const TlSummary* __restrict__ summary,
                                                      const BufSummary* __restrict__ bufsum, SelState* S,
@@ -156,36 +155,42 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
             table_insert(T, m[TL_DEV_BUF], !buf_timeline_is_analytic(TL_DEV_BUF, n, bs));
         }
     }
-    table_compact(T);
-    u64* mine = parts + (size_t)blockIdx.x * (DISCO_MAX_CLS + 2);
-    if (threadIdx.x < DISCO_MAX_CLS) mine[threadIdx.x] = T.dense[threadIdx.x];
-    if (threadIdx.x == 0) { mine[DISCO_MAX_CLS] = T.dense_walk; mine[DISCO_MAX_CLS + 1] = (u64)T.overflow; }
+    {
+        // this workgroup's distinct sets into the device-wide table (same probing; entries are never changed once
+        // claimed, so a stale read can only cost an extra compare-and-swap)
+        const int mine_n = table_compact(T);
+        TlSel& g = S->tl;
+        if ((int)threadIdx.x < mine_n) {
+            const u64 m = T.dense[threadIdx.x];
+            const bool walked = (T.dense_walk >> threadIdx.x) & 1ull;
+            unsigned h = (unsigned)((m * 0x9E3779B97F4A7C15ull) >> 56) & (CL_SLOTS - 1);
+            volatile u64* vs = g.gslot;
+            bool placed = false;
+            for (int probe = 0; probe < CL_SLOTS && !placed; ++probe) {
+                u64 cur = vs[h];
+                if (cur == 0ull) cur = (u64)atomicCAS((unsigned long long*)&g.gslot[h], 0ull, (unsigned long long)m);
+                if (cur == 0ull || cur == m) {
+                    if (walked && ((volatile unsigned*)g.gwalk)[h] == 0u) atomicOr(&g.gwalk[h], 1u);
+                    placed = true;
+                } else {
+                    h = (h + 1) & (CL_SLOTS - 1);
+                }
+            }
+            if (!placed) g.goverflow = 1;
+        }
+        if (threadIdx.x == 0 && T.overflow) g.goverflow = 1;
+    }
+    (void)parts;
     if (!take_last_ticket(ticket)) return;
-    // last workgroup: the tables of all workgroups into one
+    // last workgroup: the device-wide table (read where the atomics put it), compacted and put in order
     __syncthreads();
     table_clear(T);
     __syncthreads();
-    {
-        constexpr int MG = 8;                                // entries per thread in flight
-        const unsigned nent = gridDim.x * (unsigned)DISCO_MAX_CLS;
-        for (unsigned base = 0; base < nent; base += CL_BLOCK * MG) {
-            u64 mv[MG], wb[MG], ov[MG];
-#pragma unroll
-            for (int j = 0; j < MG; ++j) {
-                const unsigned idx = base + j * CL_BLOCK + threadIdx.x;
-                const bool ok = idx < nent;
-                const u64* part = parts + (size_t)(ok ? idx / DISCO_MAX_CLS : 0) * (DISCO_MAX_CLS + 2);
-                mv[j] = ok ? part[idx % DISCO_MAX_CLS] : 0ull;
-                wb[j] = part[DISCO_MAX_CLS];
-                ov[j] = ok ? part[DISCO_MAX_CLS + 1] : 0ull;
-            }
-#pragma unroll
-            for (int j = 0; j < MG; ++j) {
-                if (ov[j] != 0ull) T.overflow = 1;
-                table_insert(T, mv[j], (wb[j] >> (threadIdx.x % DISCO_MAX_CLS)) & 1ull);
-            }
-        }
+    if (threadIdx.x < CL_SLOTS) {
+        T.slot[threadIdx.x] = (u64)atomicCAS((unsigned long long*)&S->tl.gslot[threadIdx.x], 0ull, 0ull);
+        T.walk[threadIdx.x] = atomicOr(&S->tl.gwalk[threadIdx.x], 0u);
     }
+    if (threadIdx.x == 0 && atomicOr((unsigned*)&S->tl.goverflow, 0u) != 0u) T.overflow = 1;
     const int total = table_compact(T);
     if (wave != 0) return;
     // ascending order: lane e holds a set, its rank is the number of smaller ones
