@@ -130,11 +130,8 @@ inline int tl_batch(i64 n_req, i64 waves)
 struct HistArgs {
     float tau, kt;
     int P, pass;
-    int rb;                        // requests per wave batch
     SelState* S;
     unsigned* ghist;
-    unsigned* ppcnt;
-    const TlSummary* summary;      // per request, from the token walk
     const u64* desc;               // per request: LDS rows of its timelines that have tokens to walk (one byte per kind)
     const unsigned* list;          // requests with such a timeline (see walk_list_entry)
 };

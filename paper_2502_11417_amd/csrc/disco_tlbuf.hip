@@ -224,7 +224,7 @@ void disco_launch_tl_hist_buf(const TraceView& v, i64 n_tok, const disco_policy*
     BufHistArgs h;
     memset(&h, 0, sizeof(h));
     h.h.tau = a.tau; h.h.kt = a.kt; h.h.P = a.P; h.h.pass = a.pass;
-    h.h.S = a.S; h.h.ghist = a.ghist; h.h.ppcnt = a.ppcnt;
+    h.h.S = a.S; h.h.ghist = a.ghist;
     h.h.desc = a.desc; h.h.list = a.list;
     h.bc = a.bc;
     h.buffer_flag = a.buffer_flag;

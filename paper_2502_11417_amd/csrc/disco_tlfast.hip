@@ -1,21 +1,24 @@
-// Token timelines (Sec. 4.3), streaming kernels: the statistics pass of
-// disco_eval_migration and the class-mode TBT histogram passes of
-// disco_reduce_stats.
+// Token timelines (Sec. 4.3): the class-mode TBT histogram passes of
+// disco_reduce_stats and what prepares them once per selection.
 //
-// One wave walks one request at a time in chunks of 256 tokens, four
-// consecutive tokens per lane (one 16-byte load per lane and chunk, the next
-// chunk's load issued before the current one is used).  The delivery
-// recurrence delta_t = max(r_t, delta_{t-1} + tau) is evaluated in the shifted
-// domain u_t = r_t - t tau, where it is a running maximum M_t and
-// delta_t = fma(t, tau, M_t).  `max` is exact and associative, so any
-// evaluation order gives the sequential definition bit for bit.
+//   k_tl_assign  lane = request: timelines that the token walk's summaries
+//                prove analytic (running maximum never left 0, so
+//                delta_t = round(t tau)) are counted per class and length;
+//                the others get their histogram row into the request's
+//                descriptor and the request into the walk list
+//   k_pp_reduce  per-workgroup count slices -> counts per class and length
+//   k_tl_hist    one pass over the walk list: a wave walks one request at a
+//                time in chunks of 256 tokens, four consecutive tokens per
+//                lane (one 16-byte load per lane and chunk, the next chunk's
+//                load issued before the current one is used)
 //
-//   statistics pass: only the last delivery fma(n-1, tau, M_{n-1}) and the
-//     hand-off index are needed, so a chunk costs one fma and one max per
-//     token and the wave reduces its lanes once per request.
-//   histogram pass: M_t per token by a 4-element scan in registers and a DPP
-//     scan across the wave; the gaps delta_t - delta_{t-1} go to the LDS
-//     histogram of the timeline's class.
+// The delivery recurrence delta_t = max(r_t, delta_{t-1} + tau) is evaluated
+// in the shifted domain u_t = r_t - t tau, where it is a running maximum M_t
+// and delta_t = fma(t, tau, M_t).  `max` is exact and associative, so any
+// evaluation order gives the sequential definition bit for bit.  The
+// histogram walk needs M_t per token: a 4-element scan in registers and a DPP
+// scan across the wave; the gaps delta_t - delta_{t-1} go to the LDS
+// histogram of the timeline's class.
 //
 // Lag trigger (token t is overdue by more than kappa tau): evaluated exactly,
 // one IEEE fp32 operation at a time in the order of the definition (slot =
@@ -442,8 +445,7 @@ void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy
     HistArgs h;
     memset(&h, 0, sizeof(h));
     h.tau = a.tau; h.kt = a.kt; h.P = a.P; h.pass = a.pass;
-    h.S = a.S; h.ghist = a.ghist; h.ppcnt = a.ppcnt;
-    h.summary = (const TlSummary*)a.summary;
+    h.S = a.S; h.ghist = a.ghist;
     h.desc = a.desc; h.list = a.list;
     i64 b = (v.n_req + TH_BLOCK / 64 - 1) / (TH_BLOCK / 64);      // at most one request per wave
     if (b < 1) b = 1;

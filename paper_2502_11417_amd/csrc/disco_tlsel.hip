@@ -420,7 +420,7 @@ __global__ __launch_bounds__(1024) void k_tbt_analytic(SelState* S, unsigned* gh
     analytic_class(S, ghist, ppcnt, tau, blockIdx.x, lds);
 }
 
-__global__ __launch_bounds__(256) void k_tbt_select(SelState* S, int nq, const unsigned* ghist)
+__global__ __launch_bounds__(1024) void k_tbt_select(SelState* S, int nq, const unsigned* ghist)
 {
     __shared__ u64 wsum[DISCO_MAX_CLS];
     __shared__ int s_digit;
@@ -480,7 +480,7 @@ void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsig
     if (pass == 0) hipLaunchKernelGGL(k_pp_suffix, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ppcnt);
     if (pass < 2) {
         hipLaunchKernelGGL(k_tbt_analytic, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ghist, ppcnt, tau);
-        hipLaunchKernelGGL(k_tbt_select, dim3((unsigned)(P * nq)), dim3(256), 0, stream, S, nq, ghist);
+        hipLaunchKernelGGL(k_tbt_select, dim3((unsigned)(P * nq)), dim3(1024), 0, stream, S, nq, ghist);
         hipLaunchKernelGGL(k_tbt_plan, dim3(1), dim3(1024), 0, stream, S, P, nq, ghist);
     } else {
         hipLaunchKernelGGL(k_tbt_advance_one, dim3(1), dim3(1024), 0, stream, S, P, nq, ghist, ppcnt, tau);
