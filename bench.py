@@ -464,7 +464,7 @@ def measured_traffic(kernel: str, workload: str):
 
 # Requests of each workload that the CPU baseline evaluates: the whole workload where the oracle finishes it in a
 # few seconds, else its first requests (same generator and seed, so the same requests the GPU evaluates first).
-CPU_SAMPLE = {0: 10_000, 1: 400_000, 2: 100_000, 3: 4_000_000, 4: 20_000}
+CPU_SAMPLE = {0: 10_000, 1: 400_000, 2: 100_000, 3: 4_000_000, 4: 50_000}
 
 
 def cpu_baseline(idx: int) -> dict:
