@@ -225,24 +225,31 @@ __global__ __launch_bounds__(256) void k_gen_gaps(disco_gen_params g, i64 n_tok,
 // place.  The order of the additions is part of the trace's definition, so
 // every request is summed by one thread, token after token; the tokens pass
 // through LDS so that device memory is read and written in contiguous
-// 128-byte pieces: a workgroup takes 256 consecutive requests and moves
-// GA_K tokens of each per round (32 threads per request and piece).
+// whole 128-byte lines: a workgroup takes 256 consecutive requests and moves
+// one line (GA_K tokens) of each per round, 32 threads per request and line;
+// the lines a request shares with its neighbours are touched by both, each
+// moving only its own tokens.
 constexpr int GA_BLOCK = 256;
 constexpr int GA_K = 32;
 
 __global__ __launch_bounds__(GA_BLOCK) void k_gen_arrivals(i64 n_req, const i64* __restrict__ tok_off, float* __restrict__ tok_arr)
 {
     __shared__ float tile[GA_BLOCK][GA_K + 1];               // odd row stride: a thread per row without bank conflicts
-    __shared__ i64 s_off[GA_BLOCK];
-    __shared__ int s_len[GA_BLOCK];
+    __shared__ i64 s_off[GA_BLOCK];                          // the 128-byte boundary at or below the request's first token
+    __shared__ int s_lo[GA_BLOCK], s_len[GA_BLOCK];          // first token counted from that boundary, number of tokens
     __shared__ int s_max;
     const int t = threadIdx.x;
     const i64 i = (i64)blockIdx.x * GA_BLOCK + t;
     i64 a = 0;
-    int len = 0;
-    if (i < n_req) { a = tok_off[i]; len = (int)(tok_off[i + 1] - a); }
+    int lo = 0, len = 0;
+    if (i < n_req) {
+        const i64 first = tok_off[i];
+        a = first & ~(i64)(GA_K - 1);                        // (tok_arr itself is at least 128-byte aligned)
+        lo = (int)(first - a);
+        len = (int)(tok_off[i + 1] - a);
+    }
     if (t == 0) s_max = 0;
-    s_off[t] = a; s_len[t] = len;
+    s_off[t] = a; s_lo[t] = lo; s_len[t] = len - lo;
     __syncthreads();
     atomicMax(&s_max, len);
     __syncthreads();
@@ -250,17 +257,20 @@ __global__ __launch_bounds__(GA_BLOCK) void k_gen_arrivals(i64 n_req, const i64*
     const int sub = t & (GA_K - 1), grp = t / GA_K;
     float acc = 0.0f;
     for (int c0 = 0; c0 < maxlen; c0 += GA_K) {
+        // pieces of GA_K tokens = whole 128-byte lines of the token array, 32 threads per request and piece
+#pragma unroll 8
         for (int r = grp; r < GA_BLOCK; r += GA_BLOCK / GA_K)
-            if (c0 + sub < s_len[r]) tile[r][sub] = tok_arr[s_off[r] + c0 + sub];
+            if ((unsigned)(c0 + sub - s_lo[r]) < (unsigned)s_len[r]) tile[r][sub] = tok_arr[s_off[r] + c0 + sub];
         __syncthreads();
-        const int m = len - c0 < GA_K ? len - c0 : GA_K;
-        for (int q = 0; q < m; ++q) {
-            if (c0 + q > 0) acc = acc + tile[t][q];
+        const int q0 = lo - c0 > 0 ? lo - c0 : 0, q1 = len - c0 < GA_K ? len - c0 : GA_K;
+        for (int q = q0; q < q1; ++q) {
+            if (c0 + q > lo) acc = acc + tile[t][q];         // (the first token's offset is 0, its gap unused)
             tile[t][q] = acc;
         }
         __syncthreads();
+#pragma unroll 8
         for (int r = grp; r < GA_BLOCK; r += GA_BLOCK / GA_K)
-            if (c0 + sub < s_len[r]) tok_arr[s_off[r] + c0 + sub] = tile[r][sub];
+            if ((unsigned)(c0 + sub - s_lo[r]) < (unsigned)s_len[r]) tok_arr[s_off[r] + c0 + sub] = tile[r][sub];
         __syncthreads();
     }
 }
