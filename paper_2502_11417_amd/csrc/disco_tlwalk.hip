@@ -405,30 +405,28 @@ __global__ __launch_bounds__(TW_BLOCK) void k_tl_walk(TraceView tr, i64 n_tok, W
             auto step = [&](const float v[4], float tq, int e) {
                 float u0 = __fmaf_rn(tq, ntau, v[0]), u1 = __fmaf_rn(tq + 1.0f, ntau, v[1]);
                 float u2 = __fmaf_rn(tq + 2.0f, ntau, v[2]), u3 = __fmaf_rn(tq + 3.0f, ntau, v[3]);
-                if (e + 256 > n) {                           // the request ends inside this iteration
-                    const int left = n - e - (int)lane4u;
-                    u0 = 0 < left ? u0 : ninf; u1 = 1 < left ? u1 : ninf; u2 = 2 < left ? u2 : ninf; u3 = 3 < left ? u3 : ninf;
-                }
-                if (e == 0 && mis > 0) {                     // elements of the window in front of the request
-                    const int head = mis - (int)lane4u;
-                    u0 = 0 >= head ? u0 : ninf; u1 = 1 >= head ? u1 : ninf; u2 = 2 >= head ? u2 : ninf; u3 = 3 >= head ? u3 : ninf;
+                if (e + 256 > n || e == 0) {                 // the request ends inside this iteration, or the window's lead is in it
+                    // element index in the window, less the lead: valid iff in [0, n - mis)
+                    const unsigned at = (unsigned)(e + (int)lane4u - mis), cnt = (unsigned)(n - mis);
+                    u0 = at < cnt ? u0 : ninf; u1 = at + 1u < cnt ? u1 : ninf; u2 = at + 2u < cnt ? u2 : ninf; u3 = at + 3u < cnt ? u3 : ninf;
                 }
                 const float imax = fmaxf(fmaxf(u0, u1), fmaxf(u2, u3));
-                if (lag) leave = __ballot(imax > thr) != 0ull;
                 Mlane = fmaxf(Mlane, imax);
             };
 #pragma unroll 1
             for (int e0 = 0; e0 < n && !leave; e0 += 768) {
                 step(x, tf, e0);
                 if (e0 + 768 < n) load_vec(p, e0 + 768, lane4u, n, x);
-                if (e0 + 256 < n && !leave) {
+                if (e0 + 256 < n) {
                     step(y, tf + 256.0f, e0 + 256);
                     if (e0 + 1024 < n) load_vec(p, e0 + 1024, lane4u, n, y);
-                    if (e0 + 512 < n && !leave) {
+                    if (e0 + 512 < n) {
                         step(z, tf + 512.0f, e0 + 512);
                         if (e0 + 1280 < n) load_vec(p, e0 + 1280, lane4u, n, z);
                     }
                 }
+                // screening once per round of 768 tokens: the maximum so far against the bound
+                if (lag) leave = leave || __ballot(Mlane > thr) != 0ull;
                 tf += 768.0f;
             }
             put_rows(Mlane, myred[rq], lane);
