@@ -11,14 +11,16 @@
 // nothing else:
 //   k_tl_flags   lane = request: which timelines of the request are not known
 //                in closed form and have to be walked (one byte per request)
-//   k_tl_walk    the token walk: one wave per request at a time, 512 arrival
-//                offsets per iteration (two 16-byte loads per lane, the next
-//                iteration and the next request's first one in flight), one
-//                fma and one max per token, the lag trigger evaluated exactly
-//                only where a proven necessary condition holds; batches of
-//                requests are handed out through a device-wide counter, since
-//                the token count of a batch varies by far more than its mean;
-//                leaves 16 bytes per request (TlSummary)
+//   k_tl_walk    the token walk: one wave per request at a time, 256 arrival
+//                offsets per step (one 16-byte load per lane, the next two
+//                steps and the next request's first one in flight), one fma
+//                and one max per token; the lag trigger is only screened by
+//                a proven necessary condition; batches of requests are handed
+//                out through device-wide counters, since the token count of
+//                a batch varies by far more than its mean; leaves 16 bytes
+//                per request (TlSummary)
+//   k_tl_walk_rest  the requests the screening flags, walked exactly; sources
+//                without a token array and slow device sources
 //   k_tl_accum   lane = column: per-column totals from the summaries
 //   k_tl_mat     optional per-pair outputs from the summaries
 #include <string.h>
@@ -305,11 +307,11 @@ __device__ __forceinline__ void load_vec(const float* __restrict__ p, int t0, un
 // The streaming walk: the server-sourced timeline of every request that has one in the token array, as long as
 // nothing but the running maximum is asked of it.  256 tokens per iteration (one 16-byte load per lane), the two
 // following iterations of the request and the first one of the next request in flight; per token one fma
-// (u_t = r_t - t tau) and one max.  Where a column wants the lag trigger, the iteration's maximum is compared
-// with the bound of the necessary condition (see lag_fast_ok): an iteration that passes it could hold a hand-off,
-// and the request is left, flagged WF_REDO, to the kernel behind this one, which evaluates the trigger exactly.
-// The kernel is bound by instruction issue as much as by memory, so everything per request is either done for
-// the whole batch at once (lane = request) or kept in scalar registers.
+// (u_t = r_t - t tau) and one max.  Where a column wants the lag trigger, the maximum so far is compared once
+// per round of three iterations with the bound of the necessary condition (see lag_fast_ok): a request that
+// passes it could hold a hand-off and is left, flagged WF_REDO, to the kernel behind this one, which evaluates
+// the trigger exactly.  Everything per request is either done for the whole batch at once (lane = request) or
+// kept in scalar registers.
 enum { WP_NOK = 32 };                                        // beside the walk flags in a request's packed word
 
 __global__ __launch_bounds__(TW_BLOCK) void k_tl_walk(TraceView tr, i64 n_tok, WalkArgs a)
