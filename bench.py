@@ -62,6 +62,14 @@ def main() -> int:
               file=sys.stderr)
         return 2
 
+    # the CPU baselines of the timed workload first: the all-cores one forks, which must happen before the GPU is initialised
+    cpu_pre = {}
+    if not args.no_cpu_baseline and not args.copy_calibration:
+        idx0 = int("".join(ch for ch in args.workload if ch.isdigit()) or 4)
+        log(f"[bench] CPU baselines of config{idx0} (oracle) ...")
+        cpu_pre["one"] = {a: b for a, b in cpu_baseline(idx0).items() if not a.startswith("_")}
+        cpu_pre["all"] = cpu_baseline_all_cores(idx0)
+
     import numpy as np
     import torch
 
@@ -352,7 +360,8 @@ def main() -> int:
                                   "what": "the step above captured once into a HIP graph and replayed (reported beside "
                                           "the eager step; `value` is the eager one)"}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(idx)
+        result["cpu_baseline"] = cpu_pre["one"]
+        result["cpu_baseline_all_cores"] = cpu_pre["all"]
 
     # ------------------------------------------------------------------ the other workloads
     extras = {"read_ceiling": ceiling}
@@ -416,7 +425,7 @@ def main() -> int:
             ex["migrated_requests"] = [int(x) for x in st["n_migrated"]]
             ex["mean_delay_num"] = [None if x != x else float(x) for x in st["mean_delay_num"]]
         if not args.no_cpu_baseline and not buffer and not stoch:
-            ex["cpu_baseline"] = cpu_baseline(k)
+            ex["cpu_baseline"] = {a: b for a, b in cpu_baseline(k).items() if not a.startswith("_")}
         extras[name] = ex
         log(f"[bench] {name}: {json.dumps(ex)}")
     if idx == 4 and timelines and not buffer and "config4" not in extras:
@@ -467,15 +476,15 @@ def measured_traffic(kernel: str, workload: str):
 CPU_SAMPLE = {0: 10_000, 1: 400_000, 2: 100_000, 3: 4_000_000, 4: 50_000}
 
 
-def cpu_baseline(idx: int) -> dict:
+def cpu_baseline(idx: int, n_sample: int | None = None, seed: int = 0) -> dict:
     """The oracle as it stands, on a bounded sample of the same workload, on one host core, in the workload's unit."""
     import numpy as np
 
     import disco_inputs as DI
     from oracle import disco_oracle as O
 
-    n_sample = CPU_SAMPLE[idx]
-    cfg = DI.config(idx, n_req=n_sample)
+    n_sample = n_sample or CPU_SAMPLE[idx]
+    cfg = DI.config(idx, n_req=n_sample, seed=seed)
     tr = O.gen_trace(cfg["gen"])
     t0 = time.perf_counter()
     if idx == 3:
@@ -501,10 +510,38 @@ def cpu_baseline(idx: int) -> dict:
     whole = n_sample == DI.config(idx)["gen"]["n_req"]
     sample = (f"all {n_sample} requests" if whole else f"first {n_sample} requests") + \
         f" of config{idx} (same generator and seed), same step, {dt:.1f} s"
-    out = {"value": pairs / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle", "sample": sample, "pairs_per_s": pairs / dt}
+    out = {"value": pairs / dt, "unit": "pairs/s", "cores": 1, "kind": "oracle", "sample": sample, "pairs_per_s": pairs / dt,
+           "_pairs": pairs, "_tokens": int(tr["n_tok"]) if cfg["timelines"] else 0, "_seconds": dt}
     if cfg["timelines"]:
         out["value"], out["unit"] = int(tr["n_tok"]) / dt, "token-events/s"
     return out
+
+
+def _cpu_worker(job):
+    idx, n_sample, seed = job
+    return cpu_baseline(idx, n_sample, seed)
+
+
+def cpu_baseline_all_cores(idx: int) -> dict:
+    """The same oracle step in one process per host core (at most 16), each on its own sample of the workload's recipe
+    (seed = process number): what the host manages when every core evaluates a batch of its own.  Forks: call it
+    before the GPU is initialised."""
+    import multiprocessing as mp
+
+    k = max(1, min(16, os.cpu_count() or 1))
+    n_each = max(1, CPU_SAMPLE[idx] // 2)
+    t0 = time.perf_counter()
+    with mp.get_context("fork").Pool(k) as pool:
+        parts = pool.map(_cpu_worker, [(idx, n_each, 1 + j) for j in range(k)])
+    wall = time.perf_counter() - t0
+    tokens, pairs = sum(p["_tokens"] for p in parts), sum(p["_pairs"] for p in parts)
+    slowest = max(p["_seconds"] for p in parts)              # the processes run their steps side by side
+    timelines = tokens > 0
+    return {"value": (tokens if timelines else pairs) / slowest, "unit": "token-events/s" if timelines else "pairs/s", "cores": k,
+            "kind": "oracle", "sample": f"{k} processes side by side, each the same step on {n_each} requests of config{idx}'s "
+                                        f"recipe (seeds 1..{k}); slowest step {slowest:.1f} s, {wall:.1f} s wall with generating "
+                                        f"the samples",
+            "pairs_per_s": pairs / slowest}
 
 
 if __name__ == "__main__":
