@@ -736,7 +736,7 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
                 disco_launch_tl_stats_buf(v, trace->n_tok, dpol, a, nullptr, stream);      // summaries only
             }
             disco_launch_tl_classify(v, dpol, P, nq, tl->tau, a.summary, a.bufsum, S, a.ppcnt, gh, a.dhist,
-                                     (u64*)(ws + L.slices), (unsigned*)(ws + L.ticket), stream);
+                                     (unsigned*)(ws + L.ticket), stream);
             a.desc = (u64*)(ws + disco_ws_desc_offset(L, v.n_req));
             a.list = (unsigned*)(a.desc + v.n_req);
             disco_launch_tl_assign(v, dpol, P, a.summary, S, a.bufsum, a.desc, a.list, (unsigned*)(ws + L.slices),

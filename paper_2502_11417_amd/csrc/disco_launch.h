@@ -94,7 +94,7 @@ void disco_launch_timeline_general(const TraceView& v, i64 n_tok, const disco_po
                                    hipStream_t stream);
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, const void* summary,
                               const void* bufsum, SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist,
-                              u64* parts /* 1024 x 66 words of scratch */, unsigned* ticket, hipStream_t stream);
+                              unsigned* ticket, hipStream_t stream);
 void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                hipStream_t stream);
 void disco_launch_tl_assign(const TraceView& v, const disco_policy* pol, int P, const void* summary, SelState* S,

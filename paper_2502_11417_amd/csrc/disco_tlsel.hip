@@ -56,7 +56,7 @@ __device__ void tbt_plan_next(SelState* S, int P, int nq)
 // Distinct column sets of a workgroup's requests: an open-addressing hash table in LDS (CL_SLOTS slots, far more
 // than the DISCO_MAX_CLS sets a class-mode selection can hold).  A lane looks its set up with one LDS read in the
 // common case (lanes with the same set read the same slot); a new set is claimed with a compare-and-swap.
-constexpr int CL_BLOCK = 1024;              // classification: 16 waves share one table, few tables to merge
+constexpr int CL_BLOCK = 1024;              // classification: 16 waves share one table
 constexpr int CL_SLOTS = DISCO_CLS_SLOTS;
 
 struct ClassTable {
@@ -123,8 +123,7 @@ __device__ __forceinline__ int table_compact(ClassTable& T)
 __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
                                                      float tau, const TlSummary* __restrict__ summary,
                                                      const BufSummary* __restrict__ bufsum, SelState* S,
-                                                     unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts,
-                                                     unsigned* ticket)
+                                                     unsigned* ppcnt, unsigned* ghist, unsigned* dhist, unsigned* ticket)
 {
     __shared__ disco_policy sp[DISCO_MAX_COLS];
     __shared__ ClassTable T;
@@ -180,7 +179,6 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
         }
         if (threadIdx.x == 0 && T.overflow) g.goverflow = 1;
     }
-    (void)parts;
     if (!take_last_ticket(ticket)) return;
     // last workgroup: the device-wide table (read where the atomics put it), compacted and put in order
     __syncthreads();
@@ -462,7 +460,7 @@ __global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, in
 }  // namespace
 
 void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P, int nq, float tau, const void* summary,
-                              const void* bufsum, SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist, u64* parts, unsigned* ticket,
+                              const void* bufsum, SelState* S, unsigned* ppcnt, unsigned* ghist, unsigned* dhist, unsigned* ticket,
                               hipStream_t stream)
 {
     i64 b = (v.n_req + CL_BLOCK - 1) / CL_BLOCK;
@@ -471,7 +469,7 @@ void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P
     b /= disco_grid_divisor();
     if (b < 1) b = 1;
     hipLaunchKernelGGL(k_tl_classify, dim3((unsigned)b), dim3(CL_BLOCK), 0, stream, v, pol, P, nq, tau,
-                       (const TlSummary*)summary, (const BufSummary*)bufsum, S, ppcnt, ghist, dhist, parts, ticket);
+                       (const TlSummary*)summary, (const BufSummary*)bufsum, S, ppcnt, ghist, dhist, ticket);
 }
 
 void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,
