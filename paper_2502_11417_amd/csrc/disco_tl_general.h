@@ -25,6 +25,8 @@ typedef BufCostArgs BufCost;
 // Returns m = the lag trigger's first device token, or the last source token of a buffer hand-off.
 //   stop_paced: the caller needs only the result (no deliveries, no gaps): a hand-off to the device whose tail is
 //           provably paced ends the walk (see below)
+//   first_chunk: nullable; this lane's four elements of the first chunk, loaded by the caller exactly as
+//           first_chunk_load does (so that the load can be in flight while another request is walked)
 //
 // Paced tail behind a buffer hand-off to the device (variant 3).  At the hand-off token m the slack
 // S = fl(delta_m - r_m) covers the migration time TM, the target's arrivals are R_t = fma(t - m, g, fl(r_m + TM))
@@ -35,11 +37,21 @@ typedef BufCostArgs BufCost;
 // of the largest magnitude, then j (tau - g) exceeds both error terms for every j >= 1: u_t = fl(R_t - t tau)
 // <= M_m (the running maximum stays M_m, the last delivery is fma(n - 1, tau, M_m)) and R_t is never above its
 // pacing slot (no delayed token).  Requests that miss the condition are walked to the end.
+// This lane's elements of the first chunk of a request's window in the token array (zeros beyond the request).
+__device__ __forceinline__ void first_chunk_load(const float* __restrict__ arr, i64 off, i64 n_tok, int align, int n, int lane,
+                                                 float out[4])
+{
+    const int mis = (int)((off + align) & 3);
+    out[0] = out[1] = out[2] = out[3] = 0.0f;
+    if (4 * lane - mis < n) load4(arr, off - mis + 4 * lane, n_tok, out);
+}
+
 template <class Sink>
 __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const float* __restrict__ arr, i64 off, i64 n_tok,
                                                        int align, float gap_srv, float g_dev, int l, float k, float c,
                                                        float s_ttft, const BufCost& bc, float tau, float kt, int lane,
-                                                       float* __restrict__ deliv, Sink&& sink, bool stop_paced = false)
+                                                       float* __restrict__ deliv, Sink&& sink, bool stop_paced = false,
+                                                       const float* first_chunk = nullptr)
 {
     const bool src_dev = variant == 0 || variant == 4;
     const bool buffer = variant >= 3;
@@ -53,7 +65,12 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
     float carryM = -INFINITY, carryD = INFINITY, base = 0.0f, t_last = 0.0f, a_m = 0.0f, r_first = 0.0f;
     int m = -1, delay = 0;
     float nxt[4] = {0.f, 0.f, 0.f, 0.f};
-    if (use_mem && 4 * lane - mis < n) load4(arr, gbase, n_tok, nxt);
+    if (use_mem && first_chunk != nullptr) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) nxt[q] = first_chunk[q];
+    } else if (use_mem && 4 * lane - mis < n) {
+        load4(arr, gbase, n_tok, nxt);
+    }
     const int total = n + mis;
     for (int e0 = 0; e0 < total; e0 += 256) {
         const int tb = e0 + 4 * lane - mis;                 // token index of this lane's first element

@@ -49,6 +49,12 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
     for (i64 bt = (i64)blockIdx.x * (TB_BLOCK / 64) + wave; bt < nbatch; bt += nwaves) {
         const Batch b = load_batch(tr, spol, P, bt * TF_RB, lane);
         u64 walkers = __ballot((b.m[TL_SRV_BUF] | b.m[TL_DEV_BUF]) != 0ull);
+        // the first chunk of the next request to walk is loaded while this one is walked
+        float ahead[4] = {0.f, 0.f, 0.f, 0.f};
+        if (walkers && tr.arr) {
+            const int r0 = __ffsll((long long)walkers) - 1;
+            first_chunk_load(tr.arr, (i64)bcast_u64((u64)b.off, r0), n_tok, align, bcast_i(b.n, r0), lane, ahead);
+        }
         while (walkers) {
             const int rq = __ffsll((long long)walkers) - 1;
             walkers &= walkers - 1;
@@ -56,6 +62,11 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
             const int n = bcast_i(b.n, rq), l = bcast_i(b.l, rq);
             const float k = bcast_f(b.k, rq), gd = bcast_f(b.gd, rq), gap = bcast_f(b.gap, rq), s_ttft = bcast_f(b.s, rq);
             const i64 off = tr.arr ? (i64)bcast_u64((u64)b.off, rq) : 0;
+            const float chunk[4] = {ahead[0], ahead[1], ahead[2], ahead[3]};
+            if (walkers && tr.arr) {
+                const int r1 = __ffsll((long long)walkers) - 1;
+                first_chunk_load(tr.arr, (i64)bcast_u64((u64)b.off, r1), n_tok, align, bcast_i(b.n, r1), lane, ahead);
+            }
             BufSummary bs{0.0f, -1, 0, 0, 0.0f, -1, 0, 0};
 #pragma unroll 1
             for (int variant = TL_DEV_BUF; variant >= TL_SRV_BUF; --variant) {
@@ -63,7 +74,7 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
                 if (!mask) continue;
                 auto sink = [](const unsigned*, const bool*) {};
                 const TimelineResult res = run_timeline(variant, n, tr.arr, off, n_tok, align, gap, gd, l, k, tr.c, s_ttft, a.bc,
-                                                        a.tau, a.kt, lane, nullptr, sink, true);
+                                                        a.tau, a.kt, lane, nullptr, sink, true, tr.arr ? chunk : nullptr);
                 if (variant == TL_DEV_BUF) { bs.M_d = res.M; bs.m_d = buf_m_enc(res.m, res.r0); bs.delay_d = res.delay; }
                 else { bs.M_s = res.M; bs.m_s = buf_m_enc(res.m, res.r0); bs.delay_s = res.delay; }
                 if (a.totals != nullptr && ((mask >> lane) & 1ull)) {
