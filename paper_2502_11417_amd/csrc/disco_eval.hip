@@ -741,12 +741,11 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             a.list = (unsigned*)(a.desc + v.n_req);
             disco_launch_tl_assign(v, dpol, P, a.summary, S, a.bufsum, a.desc, a.list, (unsigned*)(ws + L.slices),
                                    L.total - L.slices, a.ppcnt, a.dhist, stream);
+            disco_launch_pp_suffix(S, a.ppcnt, stream);
             for (int pass = 0; pass < DISCO_TBT_MAX_PASS; ++pass) {
                 a.pass = pass;
-                disco_launch_tl_hist_fast(v, trace->n_tok, dpol, a, stream);
-                disco_launch_tl_hist_buf(v, trace->n_tok, dpol, a, stream);
-                disco_launch_timeline_general(v, trace->n_tok, dpol, a, stream);
-                disco_launch_tbt_advance(S, P, nq, gh, a.ppcnt, tl->tau, pass, stream);
+                if (pass < DISCO_TBT_REGULAR_PASS) disco_launch_tl_hist_fast(v, trace->n_tok, dpol, a, stream);
+                disco_launch_tbt_pass(v, trace->n_tok, dpol, a, stream);
             }
         }
     }

@@ -58,8 +58,6 @@ void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, si
 // Pairs with the buffer hand-off in class mode (both return at once when the staged table has no such column).
 void disco_launch_tl_stats_buf(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                MigPartial* totals, hipStream_t stream);
-void disco_launch_tl_hist_buf(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
-                              hipStream_t stream);
 // Recorded traces: timestamps to relative arrays; log-normal fit (`scratch`: disco_fit_scratch_bytes() bytes).
 void disco_launch_ingest(i64 n_req, const double* t_send, const double* t_token, const i64* off, float* srv_ttft,
                          int32_t* output_len, float* tok_arr, hipStream_t stream);
@@ -80,9 +78,11 @@ void disco_launch_ttft_pass(const TraceView& v, const disco_policy* pol, int P, 
 void disco_launch_dispatch_mat(const TraceView& v, const disco_policy* pol, int P, uint8_t* decision, float* ttft,
                                hipStream_t stream);
 // Token timelines.  Statistics pass (a.pass = -1): streaming kernel, or the general kernel when the
-// per-token deliveries of a column are wanted.  TBT selection: classification, then per pass the class
-// histograms (streaming kernel) or the per-slot histograms (general kernel; exactly one of the two acts,
-// decided on the device), then the digit selection.
+// per-token deliveries of a column are wanted.  TBT selection: classification, assignment and the "longer than"
+// counts of the analytic timelines once; then per regular pass (a.pass < DISCO_TBT_REGULAR_PASS) the walk of the
+// streaming kinds (disco_launch_tl_hist_fast) followed by disco_launch_tbt_pass (the other histogram work of the
+// pass, the digits, the plan of the next pass); a spare pass is disco_launch_tbt_pass alone, one launch that
+// normally returns at once.
 void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                 MigPartial* totals, hipStream_t stream);
 // The token walk alone (flags, then one 16-byte summary per request), for a statistics call that was not handed
@@ -100,5 +100,5 @@ void disco_launch_tl_hist_fast(const TraceView& v, i64 n_tok, const disco_policy
 void disco_launch_tl_assign(const TraceView& v, const disco_policy* pol, int P, const void* summary, SelState* S,
                             const void* bufsum, u64* desc, unsigned* list, unsigned* slices, size_t slices_bytes,
                             unsigned* ppcnt, unsigned* dhist, hipStream_t stream);
-void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,
-                              hipStream_t stream);
+void disco_launch_pp_suffix(SelState* S, unsigned* ppcnt, hipStream_t stream);
+void disco_launch_tbt_pass(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a, hipStream_t stream);

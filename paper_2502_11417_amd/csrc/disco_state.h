@@ -78,6 +78,7 @@ struct SelSlot { unsigned prefix; int done; i64 k_rem; i64 rank; i64 M; };
 // the raw 31-bit patterns of the gaps.  The digit of each pass is sized on the
 // device from the number of classes and of distinct prefixes still alive.
 enum { DISCO_MAX_CLS = 64, DISCO_CLS_SLOTS = 256, DISCO_MAX_GRP = 4, DISCO_TBT_MAX_PASS = 6,
+       DISCO_TBT_REGULAR_PASS = 2,    // passes that normally decide every slot (the later ones are spare)
        DISCO_TL_HIST_WORDS = 16384,   // LDS bins of a timeline workgroup (64 KB: two workgroups per CU)
        DISCO_GHIST_WORDS = 262144,    // device-wide bins (1 MB)
        DISCO_PP_NMAX = 4096,          // pure-pacing timelines up to this length are histogrammed analytically

@@ -1,16 +1,15 @@
 // Token timelines with the buffer-based, cost-triggered hand-off (Sec. 4.3) in
-// class mode: the statistics pass and the TBT histogram passes for the
-// (request, column) pairs whose source is the column's constrained endpoint
-// in a column with that hand-off.  The streaming kernels leave these pairs
-// out; the kernels here add them into the same device-wide totals and
-// histogram rows, so a table may mix hand-off kinds freely.  One wave walks
-// one request and kind with the general walker (a scan per chunk; the hand-off
-// condition compares the delivery slack of every token with the migration
-// time).  The statistics pass also leaves 32 bytes per request (BufSummary):
-// a hand-off timeline whose running maximum never left 0 delivers at
-// round(t tau) like a pure-pacing one, so the histogram passes only walk the
-// others (the walk list of the TBT selection names them).  Both kernels
-// return at once when the staged table has no such column.
+// class mode: the statistics pass for the (request, column) pairs whose
+// source is the column's constrained endpoint in a column with that hand-off.
+// The streaming kernels leave these pairs out; the kernel here adds them into
+// the same device-wide totals, so a table may mix hand-off kinds freely.  One
+// wave walks one request and kind with the general walker (a scan per chunk;
+// the hand-off condition compares the delivery slack of every token with the
+// migration time).  The pass also leaves 32 bytes per request (BufSummary): a
+// hand-off timeline whose running maximum never left 0 delivers at
+// round(t tau) like a pure-pacing one, so the histogram passes of the TBT
+// selection only walk the others (its walk list names them).  The kernel
+// returns at once when the staged table has no such column.
 #include <string.h>
 
 #include "disco_tl_general.h"
@@ -19,7 +18,6 @@
 namespace {
 
 constexpr int TB_BLOCK = 256;                // statistics kernel: 4 waves
-constexpr int TBH_BLOCK = 1024;              // histogram kernel: 16 waves share the LDS bins
 
 struct BufStatsArgs {
     float tau, kt;
@@ -124,89 +122,6 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
     }
 }
 
-struct BufHistArgs {
-    HistArgs h;
-    BufCostArgs bc;
-    const unsigned* buffer_flag;
-};
-
-// One histogram pass over the hand-off timelines that have tokens to walk: bytes 3 and 4 of a request's
-// descriptor name the LDS rows of its two hand-off kinds, the walk list of the selection names the requests.
-__global__ __launch_bounds__(TBH_BLOCK) void k_tl_hist_buf(TraceView tr, i64 n_tok, int align, BufHistArgs ba)
-{
-    __shared__ __align__(16) unsigned smem[DISCO_TL_HIST_WORDS];
-    const HistArgs& a = ba.h;
-    const TlSel* tl = &a.S->tl;
-    const int width = tl->width;
-    if (*ba.buffer_flag == 0u || width <= 0 || tl->fallback) return;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int ncls = tl->ncls, nwalk = tl->nwalk;
-    HistCtx h;
-    h.hist = smem; h.width = width; h.shift = tl->shift; h.up = h.shift + width;
-    h.G = tl->G < DISCO_MAX_GRP ? tl->G : DISCO_MAX_GRP;
-    h.stride = (unsigned)nwalk << width;
-    h.key_lo = tl->key_lo; h.key_cap = tl->window ? (1u << tl->window) : 0xFFFFFFFFu;
-    for (int k = 0; k < DISCO_MAX_GRP; ++k) h.grp_prefix[k] = tl->grp_prefix[k];
-    const int words = (h.G * nwalk) << width;
-    for (int i = threadIdx.x; i < words; i += TBH_BLOCK) smem[i] = 0u;
-    __syncthreads();
-    const i64 nwaves = (i64)gridDim.x * (TBH_BLOCK / 64);
-    const i64 nfront = (i64)tl->nlist, nlist = nfront + (i64)tl->nlist_back;
-    i64 rb = (nlist + nwaves - 1) / nwaves;
-    rb = rb < 1 ? 1 : (rb > 64 ? 64 : rb);
-    const i64 nround = (nlist + rb * nwaves - 1) / (rb * nwaves);
-    for (i64 rnd = 0; rnd < nround; ++rnd) {
-        const i64 gw = (i64)blockIdx.x * (TBH_BLOCK / 64) + wave;
-        const i64 j = rnd * rb * nwaves + gw + (i64)lane * nwaves;
-        const bool mine = lane < rb && j < nlist;
-        const i64 il = mine ? (i64)walk_list_entry(a.list, tr.n_req, nfront, j) : 0;
-        const unsigned desc = mine ? (unsigned)((a.desc[il] >> 24) & 0xFFFFull) : 0xFFFFu;
-        u64 walkers = __ballot(desc != 0xFFFFu);
-        if (!walkers) continue;
-        int l_v = 0, n_v = 1;
-        float k_v = tr.k_s, gd_v = tr.g_s, gap_v = 0.0f, s_v = 0.0f;
-        i64 off_v = 0;
-        if (desc != 0xFFFFu) {
-            l_v = tr.l[il]; n_v = tr.n[il]; s_v = tr.s[il];
-            if (tr.k) k_v = tr.k[il];
-            if (tr.g) gd_v = tr.g[il];
-            if (tr.off) off_v = tr.off[il];
-            if (tr.tbt) gap_v = tr.tbt[il];
-        }
-        while (walkers) {
-            const int rq = __ffsll((long long)walkers) - 1;
-            walkers &= walkers - 1;
-            const unsigned dsc = (unsigned)bcast_i((int)desc, rq);
-            const int n = bcast_i(n_v, rq), l = bcast_i(l_v, rq);
-            const float k = bcast_f(k_v, rq), gd = bcast_f(gd_v, rq), gap = bcast_f(gap_v, rq), s_ttft = bcast_f(s_v, rq);
-            const i64 off = tr.arr ? (i64)bcast_u64((u64)off_v, rq) : 0;
-#pragma unroll 1
-            for (int kind = 1; kind >= 0; --kind) {
-                const unsigned sl = (dsc >> (8 * kind)) & 0xFFu;
-                if (sl == 0xFFu) continue;
-                const unsigned row_base = sl << width;
-                auto sink = [&](const unsigned key[4], const bool ok[4]) {
-                    const unsigned kk[4] = {ok[0] ? key[0] : KEY_SKIP, ok[1] ? key[1] : KEY_SKIP, ok[2] ? key[2] : KEY_SKIP,
-                                            ok[3] ? key[3] : KEY_SKIP};
-                    hist_keys(h, kk, row_base, lane);
-                };
-                (void)run_timeline(TL_SRV_BUF + kind, n, tr.arr, off, n_tok, align, gap, gd, l, k, tr.c, s_ttft, ba.bc, a.tau, a.kt,
-                                   lane, nullptr, sink);
-            }
-        }
-    }
-    __syncthreads();
-    // LDS rows (group, walked class) -> device-wide rows (group, class)
-    const unsigned dmask = (1u << width) - 1u;
-    for (int i = threadIdx.x; i < words; i += TBH_BLOCK) {
-        const unsigned cnt = smem[i];
-        if (!cnt) continue;
-        const int row = i >> width;
-        const int g = row / nwalk, sl = row - g * nwalk;
-        const int c = tl->slot_cls[sl];
-        atomicAdd(&a.ghist[((size_t)(g * ncls + c) << width) | ((unsigned)i & dmask)], cnt);
-    }
-}
 
 }  // namespace
 
@@ -227,23 +142,4 @@ void disco_launch_tl_stats_buf(const TraceView& v, i64 n_tok, const disco_policy
     if (b > 2048) b = 2048;
     const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
     hipLaunchKernelGGL(k_tl_stats_buf, dim3((unsigned)b), dim3(TB_BLOCK), 0, stream, v, n_tok, align, pol, s);
-}
-
-void disco_launch_tl_hist_buf(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
-                              hipStream_t stream)
-{
-    BufHistArgs h;
-    memset(&h, 0, sizeof(h));
-    h.h.tau = a.tau; h.h.kt = a.kt; h.h.P = a.P; h.h.pass = a.pass;
-    h.h.S = a.S; h.h.ghist = a.ghist;
-    h.h.desc = a.desc; h.h.list = a.list;
-    h.bc = a.bc;
-    h.buffer_flag = a.buffer_flag;
-    (void)pol;
-    i64 b = (v.n_req + TBH_BLOCK / 64 - 1) / (TBH_BLOCK / 64);    // at most one request per wave
-    if (b < 1) b = 1;
-    const i64 cap = a.pass < 2 ? 512 : 64;                       // (the late passes normally return at once)
-    if (b > cap) b = cap;
-    const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
-    hipLaunchKernelGGL(k_tl_hist_buf, dim3((unsigned)b), dim3(TBH_BLOCK), 0, stream, v, n_tok, align, h);
 }

@@ -9,7 +9,19 @@
 // pacing interval) need no token walk at all: the gap in front of token t is
 // round(t tau) - round((t-1) tau) for every one of them, so counting the
 // timelines per class and length gives their histogram.
-#include "disco_tl_walk.h"
+//
+// Launches of a selection: classification, assignment (other file), the
+// "longer than" counts; per regular pass the walk of the streaming kinds
+// (other file), k_tbt_side (analytic bins, buffer hand-off timelines,
+// per-slot histograms: workgroups by kind) and k_tbt_select (one workgroup
+// per slot; the last one plans the next pass); per spare pass k_tbt_spare
+// alone.  A launch that finds the selection finished returns at once, which
+// still costs about 2 us on the device: hence few launches.
+#include <string.h>
+
+#include "disco_tl_general_kernel.h"
+#include "disco_tl_hist_buf.h"
+#include "disco_tl_hist_fast.h"
 
 namespace {
 
@@ -257,9 +269,9 @@ __global__ __launch_bounds__(1024) void k_pp_suffix(SelState* S, unsigned* ppcnt
     }
 }
 
-// After a TBT histogram pass, step 1 (all threads of a workgroup, class c):
-// add the analytic bins of the class's pure-pacing timelines to its
-// device-wide rows.  ppcnt[c][t] timelines of class c have a token t, and the
+// Step 1 of a TBT pass (all threads of a workgroup, class c; beside the
+// workgroups that walk tokens, hence atomic adds): add the analytic bins of
+// the class's pure-pacing timelines to its device-wide rows.  ppcnt[c][t] timelines of class c have a token t, and the
 // gap in front of it is the same number for all of them.
 __device__ void analytic_class(SelState* S, unsigned* ghist, const unsigned* ppcnt, float tau, int c, unsigned* lds)
 {
@@ -287,7 +299,7 @@ __device__ void analytic_class(SelState* S, unsigned* ghist, const unsigned* ppc
     __syncthreads();
     for (int i = threadIdx.x; i < words; i += blockDim.x) {
         const unsigned v = lds[i];
-        if (v) ghist[((size_t)((i >> width) * ncls + c) << width) | (i & dmask)] += v;
+        if (v) atomicAdd(&ghist[((size_t)((i >> width) * ncls + c) << width) | (i & dmask)], v);
     }
 }
 
@@ -410,15 +422,48 @@ __device__ void plan_pass(SelState* S, int P, int nq, unsigned* ghist)
     }
 }
 
-__global__ __launch_bounds__(1024) void k_tbt_analytic(SelState* S, unsigned* ghist, const unsigned* ppcnt, float tau)
+// Workgroups of the launches below, by what they run.
+struct PassGrid { unsigned analytic, fast, buf, general; };
+
+__device__ __forceinline__ BufHistArgs buf_hist_args(const TimelineArgs& a)
 {
-    __shared__ unsigned lds[DISCO_TL_HIST_WORDS];
-    const TlSel& tl = S->tl;
-    if (tl.width <= 0 || tl.fallback || (int)blockIdx.x >= tl.ncls) return;
-    analytic_class(S, ghist, ppcnt, tau, blockIdx.x, lds);
+    BufHistArgs h;
+    h.h.tau = a.tau; h.h.kt = a.kt; h.h.P = a.P; h.h.pass = a.pass;
+    h.h.S = a.S; h.h.ghist = a.ghist; h.h.desc = a.desc; h.h.list = a.list;
+    h.bc = a.bc;
+    h.buffer_flag = a.buffer_flag;
+    return h;
 }
 
-__global__ __launch_bounds__(1024) void k_tbt_select(SelState* S, int nq, const unsigned* ghist)
+static_assert(TH_BLOCK == 1024 && TBH_BLOCK == 1024 && TL_BLOCK == 1024, "the kinds of workgroup share launches");
+
+// A regular pass, everything but the streaming kinds' walk (which has a kernel of its own, built for occupancy):
+// the analytic bins of the classes, the buffer hand-off timelines, the per-slot histograms of a table whose
+// column sets do not fit the class scheme.  One launch, workgroups by kind; the kinds a table does not use
+// return at once.
+__global__ __launch_bounds__(1024) void k_tbt_side(TraceView tr, i64 n_tok, int align, const disco_policy* __restrict__ pol,
+                                                   TimelineArgs a, PassGrid g)
+{
+    __shared__ __align__(16) unsigned smem[DISCO_TL_HIST_WORDS];
+    __shared__ TimelineLds lds;
+    const TlSel& tl = a.S->tl;
+    if (tl.width <= 0) return;                          // selection finished
+    unsigned bid = blockIdx.x;
+    if (bid < g.analytic) {
+        if (!tl.fallback && (int)bid < tl.ncls) analytic_class(a.S, a.ghist, a.ppcnt, a.tau, (int)bid, smem);
+        return;
+    }
+    bid -= g.analytic;
+    if (bid < g.buf) {
+        if (!tl.fallback && *a.buffer_flag != 0u) tl_hist_buf_body(smem, tr, n_tok, align, buf_hist_args(a), bid, g.buf);
+        return;
+    }
+    bid -= g.buf;
+    if (tl.fallback) timeline_body<true>(smem, lds, tr, n_tok, align, pol, a, bid, g.general);
+}
+
+// Workgroup = slot: the digit of the slot; the workgroup that finishes last clears the bins and plans the next pass.
+__global__ __launch_bounds__(1024) void k_tbt_select(SelState* S, int P, int nq, unsigned* ghist, unsigned* ticket)
 {
     __shared__ u64 wsum[DISCO_MAX_CLS];
     __shared__ int s_digit;
@@ -426,35 +471,46 @@ __global__ __launch_bounds__(1024) void k_tbt_select(SelState* S, int nq, const 
     __shared__ u64 binsum[2048];
     if (S->tl.width <= 0) return;
     select_slot(S, nq, ghist, blockIdx.x, wsum, &s_digit, &s_rem, binsum, 2048);
-}
-
-__global__ __launch_bounds__(1024) void k_tbt_plan(SelState* S, int P, int nq, unsigned* ghist)
-{
-    if (S->tl.width <= 0) return;
+    if (!take_last_ticket(ticket)) return;
     plan_pass(S, P, nq, ghist);
+    if (threadIdx.x == 0) *ticket = 0u;
 }
 
-// The three steps in one workgroup: for the launches after the passes that
-// normally finish the selection (they return at once unless the window was
-// missed or the digits are narrow), where one launch instead of three matters
-// more than speed.
-__global__ __launch_bounds__(1024) void k_tbt_advance_one(SelState* S, int P, int nq, unsigned* ghist, const unsigned* ppcnt,
-                                                          float tau)
+// A spare pass (after the passes that normally finish the selection: needed when the window was missed or the
+// digits are narrow) in one launch: workgroups by kind walk the tokens, the one that finishes last adds the
+// analytic bins, takes every slot's digit, clears the bins and plans the next pass.  One launch per pass matters
+// more here than speed: normally all of them return at once.
+__global__ __launch_bounds__(1024) void k_tbt_spare(TraceView tr, i64 n_tok, int align, const disco_policy* __restrict__ pol,
+                                                    TimelineArgs a, PassGrid g)
 {
-    __shared__ __align__(16) unsigned lds[DISCO_TL_HIST_WORDS];
+    __shared__ __align__(16) unsigned smem[DISCO_TL_HIST_WORDS];
+    __shared__ TimelineLds lds;
     __shared__ u64 wsum[DISCO_MAX_CLS];
     __shared__ int s_digit;
     __shared__ u64 s_rem;
+    SelState* S = a.S;
     const TlSel& tl = S->tl;
-    if (tl.width <= 0) return;
+    if (tl.width <= 0) return;                          // selection finished (the same answer in every workgroup)
+    const unsigned bid = blockIdx.x;
+    if (tl.fallback) {
+        if (bid >= g.fast + g.buf) timeline_body<true>(smem, lds, tr, n_tok, align, pol, a, bid - g.fast - g.buf, g.general);
+    } else if (bid < g.fast) {
+        HistArgs h;
+        h.tau = a.tau; h.kt = a.kt; h.P = a.P; h.pass = a.pass; h.S = a.S; h.ghist = a.ghist; h.desc = a.desc; h.list = a.list;
+        tl_hist_fast_body(smem, tr, n_tok, align, h, bid, g.fast);
+    } else if (bid < g.fast + g.buf) {
+        if (*a.buffer_flag != 0u) tl_hist_buf_body(smem, tr, n_tok, align, buf_hist_args(a), bid - g.fast, g.buf);
+    }
+    if (!take_last_ticket(a.ticket)) return;
     if (!tl.fallback)
-        for (int c = 0; c < tl.ncls; ++c) analytic_class(S, ghist, ppcnt, tau, c, lds);
+        for (int c = 0; c < tl.ncls; ++c) analytic_class(S, a.ghist, a.ppcnt, a.tau, c, smem);
     __syncthreads();
-    for (int s = 0; s < P * nq; ++s) {
-        select_slot(S, nq, ghist, s, wsum, &s_digit, &s_rem, reinterpret_cast<u64*>(lds), DISCO_TL_HIST_WORDS / 2);
+    for (int s = 0; s < a.P * a.nq; ++s) {
+        select_slot(S, a.nq, a.ghist, s, wsum, &s_digit, &s_rem, reinterpret_cast<u64*>(smem), DISCO_TL_HIST_WORDS / 2);
         __syncthreads();
     }
-    plan_pass(S, P, nq, ghist);
+    plan_pass(S, a.P, a.nq, a.ghist);
+    if (threadIdx.x == 0) *a.ticket = 0u;
 }
 
 }  // namespace
@@ -472,15 +528,26 @@ void disco_launch_tl_classify(const TraceView& v, const disco_policy* pol, int P
                        (const TlSummary*)summary, (const BufSummary*)bufsum, S, ppcnt, ghist, dhist, ticket);
 }
 
-void disco_launch_tbt_advance(SelState* S, int P, int nq, unsigned* ghist, unsigned* ppcnt, float tau, int pass,
-                              hipStream_t stream)
+void disco_launch_pp_suffix(SelState* S, unsigned* ppcnt, hipStream_t stream)
 {
-    if (pass == 0) hipLaunchKernelGGL(k_pp_suffix, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ppcnt);
-    if (pass < 2) {
-        hipLaunchKernelGGL(k_tbt_analytic, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ghist, ppcnt, tau);
-        hipLaunchKernelGGL(k_tbt_select, dim3((unsigned)(P * nq)), dim3(1024), 0, stream, S, nq, ghist);
-        hipLaunchKernelGGL(k_tbt_plan, dim3(1), dim3(1024), 0, stream, S, P, nq, ghist);
+    hipLaunchKernelGGL(k_pp_suffix, dim3(DISCO_MAX_CLS), dim3(1024), 0, stream, S, ppcnt);
+}
+
+// One pass of the TBT selection over everything but the streaming kinds' walk in the regular passes (that walk:
+// disco_launch_tl_hist_fast, before this), then the step to the next pass.
+void disco_launch_tbt_pass(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a, hipStream_t stream)
+{
+    const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
+    const i64 per_wave = (v.n_req + 15) / 16;                    // workgroups if every wave took one request
+    auto cap = [&](i64 c) { return (unsigned)(per_wave < 1 ? 1 : (per_wave > c ? c : per_wave)); };
+    PassGrid g;
+    if (a.pass < DISCO_TBT_REGULAR_PASS) {
+        g.analytic = DISCO_MAX_CLS; g.fast = 0; g.buf = cap(512); g.general = cap(512);
+        hipLaunchKernelGGL(k_tbt_side, dim3(g.analytic + g.buf + g.general), dim3(1024), 0, stream, v, n_tok, align, pol, a, g);
+        hipLaunchKernelGGL(k_tbt_select, dim3((unsigned)(a.P * a.nq)), dim3(1024), 0, stream, a.S, a.P, a.nq, a.ghist, a.ticket);
     } else {
-        hipLaunchKernelGGL(k_tbt_advance_one, dim3(1), dim3(1024), 0, stream, S, P, nq, ghist, ppcnt, tau);
+        // small grids: an empty launch is cheaper and a needed one merely slower
+        g.analytic = 0; g.fast = cap(64); g.buf = cap(64); g.general = cap(128);
+        hipLaunchKernelGGL(k_tbt_spare, dim3(g.fast + g.buf + g.general), dim3(1024), 0, stream, v, n_tok, align, pol, a, g);
     }
 }
