@@ -55,7 +55,9 @@ void disco_launch_search_table(const TraceView& v, int n_search, int nbins, unsi
 int disco_search_table_max_bins(void);
 void disco_launch_len_table(const TraceView& v, int nbins, unsigned* scratch, size_t scratch_bytes, u64* table, u64* other,
                             hipStream_t stream);
-// Pairs with the buffer hand-off in class mode (both return at once when the staged table has no such column).
+// Pairs with the buffer hand-off in class mode: their per-request summaries (a.bufsum), from the summaries of the
+// streaming walk (a.summary) and the tokens; returns at once when the staged table has no such column.
+// `totals` nullable: summaries only.
 void disco_launch_tl_stats_buf(const TraceView& v, i64 n_tok, const disco_policy* pol, const TimelineArgs& a,
                                MigPartial* totals, hipStream_t stream);
 // Recorded traces: timestamps to relative arrays; log-normal fit (`scratch`: disco_fit_scratch_bytes() bytes).

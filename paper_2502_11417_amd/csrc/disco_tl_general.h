@@ -10,10 +10,46 @@ namespace {
 
 // ------------------------------------------------------------- timeline ----
 
-struct TimelineResult { int m; float t_last; int delay; float M; float r0; };     // M: final running maximum, r0: arrival of token 0
+// M: final running maximum, r0: arrival of token 0; partial: the walk ended at the caller's token limit without a
+// hand-off (m = -1; t_last, delay and M are not set)
+struct TimelineResult { int m; float t_last; int delay; float M; float r0; int partial; };
 
 // Prices behind the buffer hand-off's cost test (Sec. 4.3: saving > overhead).
 typedef BufCostArgs BufCost;
+
+// The cost test at token t of a request with prompt l and n output tokens: the decode saving on the n - 1 - t
+// tokens still to come against the target's prefill of the l + t + 1 tokens so far.
+__device__ __forceinline__ bool buffer_cost_ok(double dc, double cp, int n, int l, int t)
+{
+    const double saved = dc * (double)(n - 1 - t);
+    const double overhead = cp * (double)(l + t + 1);
+    return saved > overhead;
+}
+
+// Last token at which the cost test can pass, -1 if none.  For dc > 0 and cp >= 0 the saving does not grow and the
+// overhead does not shrink with t (a product with a constant of fixed sign is monotone under rounding), so the
+// tokens that pass are 0 .. t_max: bisection with the test itself.  Other signs: no bound (n - 2, the last
+// token a hand-off may follow).
+__device__ __forceinline__ int buffer_cost_last(double dc, double cp, int n, int l)
+{
+    if (n < 2) return -1;
+    if (!(dc > 0.0 && cp >= 0.0)) return n - 2;
+    if (!buffer_cost_ok(dc, cp, n, l, 0)) return -1;
+    int lo = 0, hi = n - 1;                 // passes at lo; hi: fails or is past the last candidate
+    while (hi - lo > 1) {
+        const int mid = lo + ((hi - lo) >> 1);
+        if (buffer_cost_ok(dc, cp, n, l, mid)) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Paced tail behind a buffer hand-off to the device at token m (see run_timeline): r_m, r_first the arrivals of
+// tokens m and 0, tm the migration time, M_m the running maximum through token m.
+__device__ __forceinline__ bool paced_tail_proven(float r_m, float r_first, float tm, float g_dev, float tau, float m_f, float M_m)
+{
+    const float reach = __fmaf_rn(m_f + 2.0f, tau, fabsf(M_m));
+    return r_m >= 0.0f && r_first >= 0.0f && tm >= 0.0f && g_dev >= 0.0f && tau - g_dev >= 9.5367431640625e-07f * reach;
+}
 
 // Timeline of one request and source.
 //   variant 0: device source, 1: server source, 2: server source with the lag trigger,
@@ -27,6 +63,10 @@ typedef BufCostArgs BufCost;
 //           provably paced ends the walk (see below)
 //   first_chunk: nullable; this lane's four elements of the first chunk, loaded by the caller exactly as
 //           first_chunk_load does (so that the load can be in flight while another request is walked)
+//   t_limit: a buffer hand-off is known to be impossible after this token (buffer_cost_last): a walk that has
+//           tested every token up to it without a hand-off ends with `partial` set, unless it is in its last
+//           chunk anyway; for callers that have the final running maximum of the source's own timeline from
+//           elsewhere
 //
 // Paced tail behind a buffer hand-off to the device (variant 3).  At the hand-off token m the slack
 // S = fl(delta_m - r_m) covers the migration time TM, the target's arrivals are R_t = fma(t - m, g, fl(r_m + TM))
@@ -51,7 +91,7 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
                                                        int align, float gap_srv, float g_dev, int l, float k, float c,
                                                        float s_ttft, const BufCost& bc, float tau, float kt, int lane,
                                                        float* __restrict__ deliv, Sink&& sink, bool stop_paced = false,
-                                                       const float* first_chunk = nullptr)
+                                                       const float* first_chunk = nullptr, int t_limit = 0x7FFFFFFF)
 {
     const bool src_dev = variant == 0 || variant == 4;
     const bool buffer = variant >= 3;
@@ -154,9 +194,7 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
             for (int q = 0; q < 4; ++q) {
                 const float slack = d[q] - r[q];
                 tm[q] = variant == 4 ? s_ttft : __fmaf_rn((float)(l + tk[q] + 1), k, c);
-                const double saved = dc * (double)(n - 1 - tk[q]);
-                const double overhead = cp * (double)(l + tk[q] + 1);
-                trig[q] = val[q] && tk[q] + 1 < n && slack >= tm[q] && saved > overhead;
+                trig[q] = val[q] && tk[q] + 1 < n && slack >= tm[q] && buffer_cost_ok(dc, cp, n, l, tk[q]);
             }
             const u64 any = __ballot(trig[0] || trig[1] || trig[2] || trig[3]);
             if (any) {
@@ -174,11 +212,9 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
                     const float mq = trig[0] ? Mq[0] : (trig[1] ? Mq[1] : (trig[2] ? Mq[2] : Mq[3]));
                     const float M_m = bcast_f(mq, ml);
                     const float r_m = bcast_f(rm, ml);
-                    const float reach = __fmaf_rn(bcast_f(tfm, ml) + 2.0f, tau, fabsf(M_m));
-                    if (r_m >= 0.0f && r_first >= 0.0f && bcast_f(tmm, ml) >= 0.0f && g_dev >= 0.0f &&
-                        tau - g_dev >= 9.5367431640625e-07f * reach) {
+                    if (paced_tail_proven(r_m, r_first, bcast_f(tmm, ml), g_dev, tau, bcast_f(tfm, ml), M_m)) {
                         const float tl_ = __fmaf_rn((float)(n - 1), tau, M_m);
-                        return TimelineResult{m, tl_, 0, M_m, r_first};
+                        return TimelineResult{m, tl_, 0, M_m, r_first, 0};
                     }
                 }
 #pragma unroll
@@ -187,6 +223,8 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
                 scan();
             }
         }
+        if (buffer && m < 0 && e0 + 255 - mis >= t_limit && e0 + 256 < total)
+            return TimelineResult{-1, 0.0f, 0, 0.0f, r_first, 1};
         unsigned key[4];
         bool ok[4];
         bool late[4];
@@ -215,7 +253,7 @@ __device__ __forceinline__ TimelineResult run_timeline(int variant, int n, const
             t_last = bcast_f(dl, e >> 2);
         }
     }
-    return TimelineResult{m, t_last, delay, carryM, r_first};
+    return TimelineResult{m, t_last, delay, carryM, r_first, 0};
 }
 
 // Pure pacing: a source whose constant gap is safely below tau (gap < 0.999 tau).
@@ -243,7 +281,7 @@ __device__ __forceinline__ TimelineResult run_pure_pacing(int n, float tau, int 
             if (need_keys) sink(key, ok);
         }
     }
-    return TimelineResult{-1, (float)(n - 1) * tau, 0, 0.0f, 0.0f};
+    return TimelineResult{-1, (float)(n - 1) * tau, 0, 0.0f, 0.0f, 0};
 }
 
 }  // namespace

@@ -21,7 +21,8 @@
 //                per request (TlSummary)
 //   k_tl_walk_rest  the requests the screening flags, walked exactly; sources
 //                without a token array and slow device sources
-//   k_tl_accum   lane = column: per-column totals from the summaries
+//   k_tl_accum   lane = column: per-column totals from the summaries (the pairs with a buffer hand-off are
+//                added by the kernel that settles those hand-offs)
 //   k_tl_mat     optional per-pair outputs from the summaries
 #include <string.h>
 
@@ -62,8 +63,10 @@ __global__ __launch_bounds__(256) void k_tl_flags(TraceView tr, i64 n_tok, const
         const bool srv_closed = pure_pacing(!mem, gap, tau);
         unsigned f = 0;
         if (m[TL_SRV_LAG] != 0ull && !srv_closed) f |= WF_LAG;
-        if (m[TL_SRV] != 0ull && !srv_closed) f |= WF_PLAIN;
-        if (m[TL_DEV] != 0ull && !pure_pacing(true, gd, tau)) f |= WF_DEV;
+        // (a buffer hand-off timeline that never hands off is the source's own timeline: the kernel of those
+        // pairs takes its final maximum from here instead of walking it)
+        if ((m[TL_SRV] | m[TL_SRV_BUF]) != 0ull && !srv_closed) f |= WF_PLAIN;
+        if ((m[TL_DEV] | m[TL_DEV_BUF]) != 0ull && !pure_pacing(true, gd, tau)) f |= WF_DEV;
         // the streaming walk loads 16 bytes per lane without bounds checks, from the 128-byte boundary at or below
         // the request's first token: the requests at the very ends of the token array, where such a load could
         // leave it, are left to the general walker
@@ -668,35 +671,50 @@ struct MatArgs {
     float tau;
     int P;
     const TlSummary* summary;
+    const BufSummary* bufsum;      // read when the staged table has a buffer hand-off column
+    const unsigned* buffer_flag;
     int32_t* mig_idx; int32_t* n_src_tok; float* t_last; int32_t* delay_num;
 };
 
-// lane = request, so that every column is written coalesced (pairs with a buffer hand-off: their own kernel).
+// lane = request, so that every column is written coalesced.  A pair with a buffer hand-off (its source is the
+// constrained endpoint of a column with that hand-off) reads the summary of that hand-off: the source's last
+// token is m, the target takes over at m + 1.
 __global__ __launch_bounds__(256) void k_tl_mat(TraceView tr, const disco_policy* __restrict__ pol, MatArgs a)
 {
     __shared__ disco_policy sp[DISCO_MAX_COLS];
     if ((int)threadIdx.x < a.P) sp[threadIdx.x] = pol[threadIdx.x];
     __syncthreads();
+    const bool any_buf = *a.buffer_flag != 0u;
     for (i64 i = (i64)blockIdx.x * blockDim.x + threadIdx.x; i < tr.n_req; i += (i64)gridDim.x * blockDim.x) {
         const int l = tr.l[i], n = tr.n[i];
         const float s = tr.s[i];
         const float d = __fmaf_rn((float)l, tr.k ? tr.k[i] : tr.k_s, tr.c);
         const TlSummary sum = a.summary[i];
+        BufSummary bs{0.0f, -1, 0, 0, 0.0f, -1, 0, 0};
+        if (any_buf) bs = a.bufsum[i];
         for (int j = 0; j < a.P; ++j) {
             unsigned dec; float t;
             dispatch_pair(sp[j], l, s, d, i, dec, t);
             const bool dev = (dec & 4u) != 0u;
             const int mg = sp[j].mig_mode, mode = sp[j].mode;
             const bool dev_constrained = mode == DISCO_MODE_DEVICE_CONSTRAINED || mode == DISCO_MODE_STOCH_DEVICE;
-            if (mg == DISCO_MIG_BUFFER && dev == dev_constrained) continue;
-            const bool lag = !dev && mg == DISCO_MIG_LAG;
-            const int m = lag ? summary_m(sum.m_enc) : -1;
-            const float M = dev ? sum.M_dev : (lag ? sum.M_lag : sum.M_plain);
+            int m, delay = 0;                                // first token of the target, -1: no hand-off
+            float M;
+            if (mg == DISCO_MIG_BUFFER && dev == dev_constrained) {
+                const int last = summary_m(dev ? bs.m_d : bs.m_s);
+                m = last >= 0 ? last + 1 : -1;
+                M = dev ? bs.M_d : bs.M_s;
+                if (last >= 0) delay = dev ? bs.delay_d : bs.delay_s;
+            } else {
+                const bool lag = !dev && mg == DISCO_MIG_LAG;
+                m = lag ? summary_m(sum.m_enc) : -1;
+                M = dev ? sum.M_dev : (lag ? sum.M_lag : sum.M_plain);
+            }
             const size_t at = (size_t)j * tr.n_req + i;
             if (a.mig_idx) a.mig_idx[at] = m;
             if (a.n_src_tok) a.n_src_tok[at] = m >= 0 ? m : n;
             if (a.t_last) a.t_last[at] = __fmaf_rn((float)(n - 1), a.tau, M);
-            if (a.delay_num) a.delay_num[at] = 0;
+            if (a.delay_num) a.delay_num[at] = delay;
         }
     }
 }
@@ -745,6 +763,7 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
                                 MigPartial* totals, hipStream_t stream)
 {
     disco_launch_tl_walk(v, n_tok, pol, a.P, a.tau, a.kt, a.wflags, a.summary, a.counter, stream, nullptr, nullptr);
+    disco_launch_tl_stats_buf(v, n_tok, pol, a, totals, stream);        // pairs with a buffer hand-off, if any
     if (v.n_req > 0) {
         AccumArgs c;
         memset(&c, 0, sizeof(c));
@@ -762,12 +781,12 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
             MatArgs m;
             memset(&m, 0, sizeof(m));
             m.tau = a.tau; m.P = a.P; m.summary = (const TlSummary*)a.summary;
+            m.bufsum = (const BufSummary*)a.bufsum; m.buffer_flag = a.buffer_flag;
             m.mig_idx = a.mig_idx; m.n_src_tok = a.n_src_tok; m.t_last = a.t_last; m.delay_num = a.delay_num;
             i64 mb = (v.n_req + 255) / 256;
             if (mb > 4096) mb = 4096;
             hipLaunchKernelGGL(k_tl_mat, dim3((unsigned)mb), dim3(256), 0, stream, v, pol, m);
         }
     }
-    disco_launch_tl_stats_buf(v, n_tok, pol, a, totals, stream);        // pairs with a buffer hand-off, if any
     hipLaunchKernelGGL(k_tl_stats_fin, dim3(1), dim3(64), 0, stream, a.P, totals, a.acc);
 }
