@@ -28,7 +28,7 @@ __host__ __device__ inline MigPartial* tl_totals(u64* totals)
 
 // Start of a selection (all threads of one workgroup): one thread per slot: rank from (num, den, M), empty
 // prefix; plan of the passes.
-struct SelInit { SelState* S; int nq; disco_quantile q[4]; const disco_accum* acc; i64 n_req; };
+struct SelInit { SelState* S; int nq; disco_quantile q[4]; const disco_accum* acc; i64 n_req; int with_tbt; };
 
 __device__ void select_init(const SelInit& si, int which, int P, const disco_policy* pol)
 {
@@ -115,7 +115,6 @@ __device__ void select_init(const SelInit& si, int which, int P, const disco_pol
     }
 }
 
-__global__ void k_select_init(SelInit si, int which, int P, const disco_policy* pol) { select_init(si, which, P, pol); }
 
 // Staging of the policy table (wave 0); all 1024 threads also put the tickets and the per-column totals that
 // the workgroups of a pass add into at their identity: the dispatch totals (8 words per column and copy,
@@ -128,7 +127,8 @@ __device__ inline void reset_totals(u64* totals)
         totals[w] = (w >= 7 * DISCO_NCOPY * 64 && w < DISP_WORDS) ? 0x00000000FFFFFFFFull : 0ull;
 }
 
-// With a selection state (si.S), the TTFT selection of the statistics is started in the same launch.
+// With a selection state (si.S), the TTFT selection of the statistics (and, if asked, the TBT selection) is started
+// in the same launch.
 __global__ __launch_bounds__(STAGE_THREADS) void k_store_policies(PolTable t, int P, disco_policy* dst, unsigned* tickets, u64* totals,
                                                                   SelInit si)
 {
@@ -142,6 +142,10 @@ __global__ __launch_bounds__(STAGE_THREADS) void k_store_policies(PolTable t, in
     if (si.S) {
         __syncthreads();                       // the staged table is read back by this workgroup
         select_init(si, 0, P, dst);
+        if (si.with_tbt) {
+            __syncthreads();
+            select_init(si, 1, P, dst);
+        }
     }
 }
 
@@ -158,6 +162,10 @@ __global__ __launch_bounds__(STAGE_THREADS) void k_copy_policies(const disco_pol
     if (si.S) {
         __syncthreads();                       // the staged table is read back by this workgroup
         select_init(si, 0, P, dst);
+        if (si.with_tbt) {
+            __syncthreads();
+            select_init(si, 1, P, dst);
+        }
     }
 }
 
@@ -169,11 +177,69 @@ __global__ __launch_bounds__(STAGE_THREADS) void k_copy_policies(const disco_pol
 
 // ------------------------------------------------------------ final stats --
 
-__global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, int with_tl, const disco_accum* acc,
-                              const SelState* S, disco_stats* out)
+// Order statistics of the delayed tokens per migrated request (all threads of a workgroup, column c): the counts
+// by number of delayed tokens come from the first histogram pass of the timelines with a buffer hand-off;
+// migrations of the lag trigger have none and count as zeros.  Nearest rank, like the other order statistics.
+// dq[qi] keeps its value for a column without migrations.
+__device__ void delay_quantiles(int c, int nq, const disco_quantile* qs, const disco_accum* acc, const unsigned* __restrict__ dhist,
+                                u64* part /* LDS, 256 */, float* dq /* LDS */)
 {
-    const int c = threadIdx.x;
-    if (c >= P) return;
+    constexpr int PER = DISCO_DELAY_BINS / 256;
+    const int t = threadIdx.x;
+    const i64 M = acc[c].n_migrated;
+    if (M <= 0) return;                                  // (the same answer in every thread)
+    const unsigned* row = dhist + (size_t)c * DISCO_DELAY_BINS;
+    unsigned v[PER];
+    u64 mine = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) { v[k] = row[t * PER + k]; mine += v[k]; }
+    part[t] = mine;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {                  // inclusive prefix sums of the per-thread totals
+        const u64 o = t >= d ? part[t - d] : 0;
+        __syncthreads();
+        part[t] += o;
+        __syncthreads();
+    }
+    const u64 counted = part[255];
+    const u64 zeros = (u64)M > counted ? (u64)M - counted : 0;      // hand-offs without a count: no delayed token
+    if (t == 0) v[0] += (unsigned)zeros;
+    const u64 below = t > 0 ? part[t - 1] + zeros : 0;               // migrated requests with fewer delayed tokens than t * PER
+    for (int qi = 0; qi < nq; ++qi) {
+        i64 k = ((i64)qs[qi].num * M + qs[qi].den - 1) / qs[qi].den;
+        if (k < 1) k = 1;
+        if (k > M) k = M;
+        u64 cum = below;
+#pragma unroll
+        for (int b = 0; b < PER; ++b) {
+            if (cum < (u64)k && cum + v[b] >= (u64)k) dq[qi] = (float)(t * PER + b);
+            cum += v[b];
+        }
+    }
+}
+
+// The record of a column from its accumulators and the selections' results.  With delayed-token order statistics
+// to work out (timelines and quantiles asked for): workgroup = column, 256 threads; otherwise one workgroup,
+// thread = column.
+__global__ __launch_bounds__(256) void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, int with_tl,
+                                                     const disco_accum* acc, const SelState* S, disco_quantile q0,
+                                                     disco_quantile q1, disco_quantile q2, disco_quantile q3,
+                                                     const unsigned* __restrict__ dhist, disco_stats* out)
+{
+    __shared__ u64 part[256];
+    __shared__ float dq[DISCO_MAX_Q];
+    const bool per_column = with_tl && nq > 0;
+    const int c = per_column ? blockIdx.x : threadIdx.x;
+    if (threadIdx.x < DISCO_MAX_Q) dq[threadIdx.x] = NAN;
+    __syncthreads();
+    if (per_column) {
+        const disco_quantile qs[4] = {q0, q1, q2, q3};
+        delay_quantiles(c, nq, qs, acc, dhist, part, dq);
+        __syncthreads();
+        if (threadIdx.x != 0) return;
+    } else if (c >= P) {
+        return;
+    }
     const disco_accum a = acc[c];
     disco_stats st;
     memset(&st, 0, sizeof(st));
@@ -194,7 +260,7 @@ __global__ void k_stats_final(int P, int nq, i64 n_req, disco_cost_params cost, 
     st.device_cost = cost.lambda * st.device_energy;
     st.total_cost = st.server_cost + st.device_cost;
     for (int qi = 0; qi < DISCO_MAX_Q; ++qi) {
-        st.ttft_q[qi] = NAN; st.tbt_q[qi] = NAN; st.delay_q[qi] = NAN;
+        st.ttft_q[qi] = NAN; st.tbt_q[qi] = NAN; st.delay_q[qi] = dq[qi];
         if (qi < nq) {
             const SelSlot s0 = S->slot[0][c * nq + qi];
             st.ttft_rank[qi] = s0.rank;
@@ -235,49 +301,6 @@ __global__ void k_average_runs(const disco_stats* __restrict__ in, int groups, i
     o.device_cost = d[4] / n; o.total_cost = d[5] / n; o.mean_delay_num = d[6] / n;
     for (int k = 0; k < DISCO_MAX_Q; ++k) { o.ttft_q[k] = (float)(q[k] / n); o.tbt_q[k] = (float)(q[DISCO_MAX_Q + k] / n); }
     out[g] = o;
-}
-
-// Order statistics of the delayed tokens per migrated request (workgroup = column): the counts by number of
-// delayed tokens come from the first histogram pass of the timelines with a buffer hand-off; migrations of the
-// lag trigger have none and count as zeros.  Nearest rank, like the other order statistics.
-__global__ __launch_bounds__(256) void k_delay_quantiles(int nq, disco_quantile q0, disco_quantile q1, disco_quantile q2,
-                                                         disco_quantile q3, const disco_accum* acc,
-                                                         const unsigned* __restrict__ dhist, disco_stats* out)
-{
-    constexpr int PER = DISCO_DELAY_BINS / 256;
-    __shared__ u64 part[256];
-    const disco_quantile qs[4] = {q0, q1, q2, q3};
-    const int c = blockIdx.x, t = threadIdx.x;
-    const i64 M = acc[c].n_migrated;
-    if (M <= 0) return;                                  // the fields stay NaN
-    const unsigned* row = dhist + (size_t)c * DISCO_DELAY_BINS;
-    unsigned v[PER];
-    u64 mine = 0;
-#pragma unroll
-    for (int k = 0; k < PER; ++k) { v[k] = row[t * PER + k]; mine += v[k]; }
-    part[t] = mine;
-    __syncthreads();
-    for (int d = 1; d < 256; d <<= 1) {                  // inclusive prefix sums of the per-thread totals
-        const u64 o = t >= d ? part[t - d] : 0;
-        __syncthreads();
-        part[t] += o;
-        __syncthreads();
-    }
-    const u64 counted = part[255];
-    const u64 zeros = (u64)M > counted ? (u64)M - counted : 0;      // hand-offs without a count: no delayed token
-    if (t == 0) v[0] += (unsigned)zeros;
-    const u64 below = t > 0 ? part[t - 1] + zeros : 0;               // migrated requests with fewer delayed tokens than t * PER
-    for (int qi = 0; qi < nq; ++qi) {
-        i64 k = ((i64)qs[qi].num * M + qs[qi].den - 1) / qs[qi].den;
-        if (k < 1) k = 1;
-        if (k > M) k = M;
-        u64 cum = below;
-#pragma unroll
-        for (int b = 0; b < PER; ++b) {
-            if (cum < (u64)k && cum + v[b] >= (u64)k) out[c].delay_q[qi] = (float)(t * PER + b);
-            cum += v[b];
-        }
-    }
 }
 
 // ----------------------------------------------------------- search setup --
@@ -703,6 +726,7 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
     memset(&si, 0, sizeof(si));
     si.S = S; si.nq = nq; si.acc = acc; si.n_req = v.n_req;
     for (int i = 0; i < 4; ++i) si.q[i] = qs[i];
+    si.with_tbt = tl != nullptr;
     rc = stage_policies(pol, P, ws, L, stream, nq > 0 ? &si : nullptr);        // with the start of the TTFT selection
     if (rc) return rc;
     if (nq > 0) {
@@ -711,7 +735,6 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             disco_launch_ttft_pass(v, (const disco_policy*)(ws + L.pol), P, nq, pass, S, (unsigned*)(ws + L.slices), gh,
                                    ubytes, stream);
         if (tl) {
-            hipLaunchKernelGGL(k_select_init, dim3(1), dim3(256), 0, stream, si, 1, P, (const disco_policy*)(ws + L.pol));
             TimelineArgs a;
             memset(&a, 0, sizeof(a));
             a.tau = tl->tau;
@@ -749,10 +772,9 @@ extern "C" int32_t disco_reduce_stats(const disco_trace* trace, const disco_cost
             }
         }
     }
-    hipLaunchKernelGGL(k_stats_final, dim3(1), dim3(64), 0, stream, P, nq, v.n_req, *cost, tl ? 1 : 0, acc, S, out);
-    if (tl && nq > 0)
-        hipLaunchKernelGGL(k_delay_quantiles, dim3((unsigned)P), dim3(256), 0, stream, nq, qs[0], qs[1], qs[2], qs[3], acc,
-                           (const unsigned*)(ws + L.dhist), out);
+    const bool per_column = tl && nq > 0;
+    hipLaunchKernelGGL(k_stats_final, dim3(per_column ? (unsigned)P : 1u), dim3(per_column ? 256 : 64), 0, stream, P, nq, v.n_req,
+                       *cost, tl ? 1 : 0, acc, S, qs[0], qs[1], qs[2], qs[3], (const unsigned*)(ws + L.dhist), out);
     DISCO_HIP(hipGetLastError());
     return DISCO_OK;
 }

@@ -118,6 +118,26 @@ __device__ __forceinline__ Batch load_batch(const TraceView& tr, const disco_pol
     return b;
 }
 
+// Totals of the timeline statistics -> accumulators (threads 0 .. P-1 of one workgroup, once every addition has
+// been made); puts the totals back to zero for the next pass.
+__device__ __forceinline__ void tl_stats_fin(int P, MigPartial* totals, disco_accum* acc)
+{
+    const int c = threadIdx.x;
+    if (c >= P) return;
+    MigPartial x{0, 0, 0, 0, 0, 0.0, {0, 0}};
+    for (int k = 0; k < DISCO_NCOPY; ++k) {
+        MigPartial* t = &totals[k * 64 + c];
+        x.s_dec += t->s_dec; x.d_dec += t->d_dec; x.d_repre += t->d_repre; x.migrated += t->migrated;
+        x.tbt_count += t->tbt_count; x.tlast_sum += t->tlast_sum;
+        x.pad[0] += t->pad[0]; x.pad[1] += t->pad[1];          // server re-prefill, delayed tokens (buffer hand-offs)
+        *t = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
+    }
+    disco_accum* o = &acc[c];
+    o->m_s_dec = (i64)x.s_dec; o->m_d_dec = (i64)x.d_dec; o->m_d_repre = (i64)x.d_repre;
+    o->n_migrated = (i64)x.migrated; o->tbt_count = (i64)x.tbt_count; o->tlast_sum = x.tlast_sum;
+    o->m_s_repre = (i64)x.pad[0]; o->delay_sum = (i64)x.pad[1];
+}
+
 // Requests a wave takes at a time: TF_RB on large traces; on small ones fewer, so that the waves the chip holds
 // (`waves`) get several batches each and finish together.
 inline int tl_batch(i64 n_req, i64 waves)

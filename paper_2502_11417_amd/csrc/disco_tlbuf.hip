@@ -18,8 +18,10 @@
 //     with the operations of the general walker (probe_handoff); a hand-off
 //     to the device whose tail is provably paced, or the end of the tokens
 //     that pass the cost test, settles the request.
-// The rest is walked one request per wave with the general walker.  The
-// kernel returns at once when the staged table has no such column.
+// The rest is walked one request per wave with the general walker.  With
+// totals, the kernel is the last of the statistics pass to add into them: its
+// last workgroup turns them into the columns' accumulators (without a buffer
+// column the kernel does only that).
 #include <string.h>
 
 #include "disco_tl_general.h"
@@ -35,6 +37,8 @@ struct BufStatsArgs {
     float tau, kt;
     int P, G;                      // columns, columns rounded up to a power of two
     MigPartial* totals;            // DISCO_NCOPY x 64 device-wide totals, shared with the streaming kernels; nullptr: summaries only
+    disco_accum* acc;              // with totals: where the workgroup that finishes last puts the columns' totals
+    unsigned* ticket;
     BufSummary* bufsum;            // per request, written for the requests with a hand-off timeline
     const TlSummary* summary;      // what the streaming walk found: the source's own timelines
     BufCostArgs bc;
@@ -108,9 +112,12 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
     __shared__ disco_policy spol[DISCO_MAX_COLS];
     __shared__ __align__(16) BufStaged stage[TB_BLOCK];
     __shared__ u64 sh[7 * TB_BLOCK];
-    if (*a.buffer_flag == 0u) return;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int P = a.P;
+    if (*a.buffer_flag == 0u) {                              // no such column: the totals are complete as they are
+        if (a.totals != nullptr && blockIdx.x == 0) tl_stats_fin(P, a.totals, a.acc);
+        return;
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if ((int)threadIdx.x < P) spol[threadIdx.x] = pol[threadIdx.x];
     __syncthreads();
     // totals: lane = sub * G + column, every column lane reads the G requests of its sub-group from LDS
@@ -224,6 +231,9 @@ __global__ __launch_bounds__(TB_BLOCK) void k_tl_stats_buf(TraceView tr, i64 n_t
         if (f[5]) atomicAdd((unsigned long long*)&t->pad[1], (unsigned long long)f[5]);
         if (tl != 0.0) unsafeAtomicAdd(&t->tlast_sum, tl);     // hardware fp64 add; order-dependent in its last bits
     }
+    if (!take_last_ticket(a.ticket)) return;
+    tl_stats_fin(P, a.totals, a.acc);
+    if (threadIdx.x == 0) *a.ticket = 0u;
 }
 
 }  // namespace
@@ -237,6 +247,7 @@ void disco_launch_tl_stats_buf(const TraceView& v, i64 n_tok, const disco_policy
     s.G = 1;
     while (s.G < a.P) s.G <<= 1;
     s.totals = totals;
+    s.acc = a.acc; s.ticket = a.ticket;
     s.bufsum = (BufSummary*)a.bufsum;
     s.summary = (const TlSummary*)a.summary;
     s.bc = a.bc;
@@ -244,7 +255,7 @@ void disco_launch_tl_stats_buf(const TraceView& v, i64 n_tok, const disco_policy
     const i64 per_block = (i64)(TB_BLOCK / 64) * TB_RB;
     i64 b = (v.n_req + per_block - 1) / per_block;
     if (b < 1) b = 1;
-    if (b > 2048) b = 2048;
+    if (b > 768) b = 768;                      // what the chip holds at once (3 waves per SIMD): every workgroup ends with a ticket
     const int align = (int)(((uintptr_t)v.arr >> 2) & 3);
     hipLaunchKernelGGL(k_tl_stats_buf, dim3((unsigned)b), dim3(TB_BLOCK), 0, stream, v, n_tok, align, pol, s);
 }

@@ -646,25 +646,6 @@ __global__ __launch_bounds__(TA_BLOCK) void k_tl_accum(TraceView tr, const disco
     }
 }
 
-// Totals -> accumulators; puts the totals back to zero for the next pass.
-__global__ void k_tl_stats_fin(int P, MigPartial* totals, disco_accum* acc)
-{
-    const int c = threadIdx.x;
-    if (c >= P) return;
-    MigPartial x{0, 0, 0, 0, 0, 0.0, {0, 0}};
-    for (int k = 0; k < DISCO_NCOPY; ++k) {
-        MigPartial* t = &totals[k * 64 + c];
-        x.s_dec += t->s_dec; x.d_dec += t->d_dec; x.d_repre += t->d_repre; x.migrated += t->migrated;
-        x.tbt_count += t->tbt_count; x.tlast_sum += t->tlast_sum;
-        x.pad[0] += t->pad[0]; x.pad[1] += t->pad[1];          // server re-prefill, delayed tokens (buffer hand-offs)
-        *t = MigPartial{0, 0, 0, 0, 0, 0.0, {0, 0}};
-    }
-    disco_accum* o = &acc[c];
-    o->m_s_dec = (i64)x.s_dec; o->m_d_dec = (i64)x.d_dec; o->m_d_repre = (i64)x.d_repre;
-    o->n_migrated = (i64)x.migrated; o->tbt_count = (i64)x.tbt_count; o->tlast_sum = x.tlast_sum;
-    o->m_s_repre = (i64)x.pad[0]; o->delay_sum = (i64)x.pad[1];
-}
-
 // ----------------------------------------------------- per-pair outputs ----
 
 struct MatArgs {
@@ -763,7 +744,6 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
                                 MigPartial* totals, hipStream_t stream)
 {
     disco_launch_tl_walk(v, n_tok, pol, a.P, a.tau, a.kt, a.wflags, a.summary, a.counter, stream, nullptr, nullptr);
-    disco_launch_tl_stats_buf(v, n_tok, pol, a, totals, stream);        // pairs with a buffer hand-off, if any
     if (v.n_req > 0) {
         AccumArgs c;
         memset(&c, 0, sizeof(c));
@@ -777,6 +757,10 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
         b /= disco_grid_divisor();
         if (b < 1) b = 1;
         hipLaunchKernelGGL(k_tl_accum, dim3((unsigned)b), dim3(TA_BLOCK), 0, stream, v, pol, c);
+    }
+    // the pairs with a buffer hand-off, if any; its last workgroup turns the totals into the accumulators
+    disco_launch_tl_stats_buf(v, n_tok, pol, a, totals, stream);
+    if (v.n_req > 0) {
         if (a.mig_idx || a.n_src_tok || a.t_last || a.delay_num) {
             MatArgs m;
             memset(&m, 0, sizeof(m));
@@ -788,5 +772,4 @@ void disco_launch_tl_stats_fast(const TraceView& v, i64 n_tok, const disco_polic
             hipLaunchKernelGGL(k_tl_mat, dim3((unsigned)mb), dim3(256), 0, stream, v, pol, m);
         }
     }
-    hipLaunchKernelGGL(k_tl_stats_fin, dim3(1), dim3(64), 0, stream, a.P, totals, a.acc);
 }
