@@ -43,7 +43,9 @@ def test_buffer_migration_matches_oracle(B, oracle, n_req, max_out, cost):
     print(f"buffer migration parity n_req={n_req} max_out={max_out} cost={cost}", flush=True)
     cost = DI.COST_S if cost == "S" else DI.COST_D
     tr = slow_prefill(DI.handmade_trace(23 + n_req, n_req, tokens=True, max_out=max_out, stall_p=0.02, ties=True))
-    for col in (0, 3):
+    # with the deliveries of a column the general kernel walks every pair; without them the buffer pairs are settled
+    # from the cost bound, the probe of the first tokens and the streaming walk's summaries
+    for col in (0, 3, None):
         _, acc, want = check_migration(B, oracle, tr, buffer_policies(), DI.TAU, DI.KAPPA_LAG, delivered_col=col, cost=cost)
     if n_req >= 300:
         # both hand-off directions occur under the price that favours the target
@@ -70,6 +72,7 @@ def test_buffer_migration_constant_gap_server(B, oracle):
     tr["srv_tbt"] = (tr["srv_tbt"] * np.float32(6.0)).astype(np.float32)
     _, acc, want = check_migration(B, oracle, tr, buffer_policies(), DI.TAU, DI.KAPPA_LAG, delivered_col=3, cost=DI.COST_D)
     assert want["delay_sum"][3] > 0
+    check_migration(B, oracle, tr, buffer_policies(), DI.TAU, DI.KAPPA_LAG, delivered_col=None, cost=DI.COST_D)
 
 
 def test_buffer_migration_late_handoffs(B, oracle):
@@ -96,6 +99,7 @@ def test_buffer_migration_late_handoffs(B, oracle):
              dict(mode=1, l_th=-1, w_tail=math.inf, mig_mode=1)]
     for cost, col in ((DI.COST_S, 0), (DI.COST_D, 1)):
         _, acc, want = check_migration(B, oracle, tr, specs, tau, 3.0, delivered_col=col, cost=cost)
+        check_migration(B, oracle, tr, specs, tau, 3.0, delivered_col=None, cost=cost)       # hand-offs beyond the probed tokens
         m = want["mig_idx"][col]
         assert (m >= 256).sum() > 5, (col, (m >= 0).sum(), (m >= 256).sum())
         assert want["delay_sum"][col] > 0
@@ -124,8 +128,10 @@ def test_buffer_handoff_to_devices_barely_faster_than_the_pacing(B, oracle):
     tr["dev_pre_spt"] = (tr["dev_dec_spt"] / np.float32(10.0)).astype(np.float32)      # the server wins the races
     specs = [dict(mode=0, l_th=0, mig_mode=2), dict(mode=0, l_th=60, mig_mode=2)]
     _, acc, want = check_migration(B, oracle, tr, specs, tau, 3.0, delivered_col=0, cost=DI.COST_S)
+    check_migration(B, oracle, tr, specs, tau, 3.0, delivered_col=None, cost=DI.COST_S)
     m = want["mig_idx"][0]
     assert (m >= 0).sum() > 100 and (m >= 256).sum() > 3, ((m >= 0).sum(), (m >= 256).sum())
+    assert ((m >= 0) & (m < 128)).sum() > 20          # ... and hand-offs the probe of the first tokens sees
     check_stats(B, oracle, tr, specs, DI.COST_S, tau=tau, kappa=3.0)
 
 
