@@ -26,43 +26,70 @@
 namespace {
 
 // Prepares the next pass: prefix groups of the live slots, digit width that
-// fits, or the per-slot fallback.  One thread.
-__device__ void tbt_plan_next(SelState* S, int P, int nq)
+// fits, or the per-slot fallback.  All threads of a workgroup (wave_only: of
+// its first wave, the only one still running); the slots are fetched side by
+// side into LDS (s_prefix, s_grp: DISCO_MAX_SLOTS words each), one thread
+// groups them there.  reset: every slot starts over (empty prefix, full rank).
+__device__ void tbt_plan_next(SelState* S, int P, int nq, unsigned* s_prefix, int* s_grp, bool wave_only, bool reset)
 {
     TlSel& tl = S->tl;
-    int G = 0;
-    bool over = tl.ncls > DISCO_MAX_CLS || tl.ncls < 1;
-    for (int s = 0; s < P * nq; ++s) {
-        const SelSlot sl = S->slot[1][s];
-        int g = -1;
-        if (!sl.done) {
-            for (int k = 0; k < G && k < DISCO_MAX_GRP; ++k)
-                if (tl.grp_prefix[k] == sl.prefix) g = k;
-            if (g < 0) {
-                if (G < DISCO_MAX_GRP) { tl.grp_prefix[G] = sl.prefix; g = G; }
-                else g = 0;            // too many distinct prefixes: the per-slot fallback does not use groups
-                G += 1;
+    const int ns = P * nq, nt = wave_only ? 64 : (int)blockDim.x;
+    auto sync = [&]() { if (wave_only) __builtin_amdgcn_wave_barrier(); else __syncthreads(); };
+    for (int s = threadIdx.x; s < ns; s += nt) {
+        SelSlot sl = S->slot[1][s];
+        if (reset) { sl.prefix = 0u; sl.k_rem = sl.rank; S->slot[1][s] = sl; }
+        s_prefix[s] = sl.prefix;
+        s_grp[s] = sl.done ? -2 : -1;
+    }
+    sync();
+    if (threadIdx.x == 0) {
+        int G = 0;
+        bool over = tl.ncls > DISCO_MAX_CLS || tl.ncls < 1;
+        unsigned gp[DISCO_MAX_GRP] = {0u, 0u, 0u, 0u};
+        for (int s = 0; s < ns; ++s) {
+            int g = -1;
+            if (s_grp[s] != -2) {
+                const unsigned prefix = s_prefix[s];
+#pragma unroll
+                for (int k = 0; k < DISCO_MAX_GRP; ++k)
+                    if (k < G && gp[k] == prefix) g = k;
+                if (g < 0) {
+                    if (G < DISCO_MAX_GRP) {
+#pragma unroll
+                        for (int k = 0; k < DISCO_MAX_GRP; ++k)
+                            if (k == G) gp[k] = prefix;
+                        g = G;
+                    } else {
+                        g = 0;         // too many distinct prefixes: the per-slot fallback does not use groups
+                    }
+                    G += 1;
+                }
             }
+            s_grp[s] = g;
         }
-        tl.slot_grp[s] = g;
+#pragma unroll
+        for (int k = 0; k < DISCO_MAX_GRP; ++k)
+            if (k < G) tl.grp_prefix[k] = gp[k];
+        if (G > DISCO_MAX_GRP) over = true;
+        if (over) tl.fallback = 1;
+        tl.G = G;
+        int w;
+        if (over || tl.fallback) {
+            w = fit_width(P * nq, DISCO_TL_HIST_WORDS);
+        } else {
+            const int g1 = G > 0 ? G : 1;
+            w = fit_width((long)g1 * (tl.nwalk > 0 ? tl.nwalk : 1), DISCO_TL_HIST_WORDS);
+            const int wg = fit_width((long)g1 * tl.ncls, DISCO_GHIST_WORDS);
+            if (wg < w) w = wg;
+        }
+        if (w < 1) w = 1;
+        if (w > tl.left) w = tl.left;
+        if (G == 0) w = 0;                 // nothing left to select
+        tl.width = w;
+        tl.shift = tl.left - w;
     }
-    if (G > DISCO_MAX_GRP) over = true;
-    if (over) tl.fallback = 1;
-    tl.G = G;
-    int w;
-    if (tl.fallback) {
-        w = fit_width(P * nq, DISCO_TL_HIST_WORDS);
-    } else {
-        const int g1 = G > 0 ? G : 1;
-        w = fit_width((long)g1 * (tl.nwalk > 0 ? tl.nwalk : 1), DISCO_TL_HIST_WORDS);
-        const int wg = fit_width((long)g1 * tl.ncls, DISCO_GHIST_WORDS);
-        if (wg < w) w = wg;
-    }
-    if (w < 1) w = 1;
-    if (w > tl.left) w = tl.left;
-    if (G == 0) w = 0;                 // nothing left to select
-    tl.width = w;
-    tl.shift = tl.left - w;
+    sync();
+    for (int s = threadIdx.x; s < ns; s += nt) tl.slot_grp[s] = s_grp[s];
 }
 
 // Distinct column sets of a workgroup's requests: an open-addressing hash table in LDS (CL_SLOTS slots, far more
@@ -78,6 +105,8 @@ struct ClassTable {
     unsigned long long dense_walk;
     unsigned wave_cnt[CL_BLOCK / 64];
     int overflow;
+    unsigned plan_prefix[DISCO_MAX_SLOTS];     // scratch of the first plan (tbt_plan_next)
+    int plan_grp[DISCO_MAX_SLOTS];
 };
 
 __device__ __forceinline__ void table_clear(ClassTable& T)
@@ -224,6 +253,7 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
         for (int q = 0; q < lane && t != 0ull; ++q) t &= t - 1ull;
         tl.slot_cls[lane] = t != 0ull ? (unsigned char)(__ffsll((long long)t) - 1) : (unsigned char)0;
     }
+    __builtin_amdgcn_wave_barrier();
     if (lane == 0) {
         tl.ncls = total > 0 ? total : 1;
         tl.walk_mask = wm;
@@ -238,9 +268,10 @@ __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const di
         tl.nlist_back = 0u;
         if (tb >= 8192u) { tl.key_lo = tb - 8192u; tl.window = 21; tl.left = 21; }
         else { tl.key_lo = 0u; tl.window = 0; tl.left = 31; }
-        tbt_plan_next(S, P, nq);
         *ticket = 0u;
     }
+    __builtin_amdgcn_wave_barrier();
+    tbt_plan_next(S, P, nq, T.plan_prefix, T.plan_grp, true, false);
 }
 
 // Per class: counts by length -> number of timelines longer than t (in place).
@@ -396,7 +427,7 @@ __device__ void select_slot(SelState* S, int nq, const unsigned* ghist, int s, u
 }
 
 // Step 3 (one workgroup): clear the bins that were used and plan the next pass.
-__device__ void plan_pass(SelState* S, int P, int nq, unsigned* ghist)
+__device__ void plan_pass(SelState* S, int P, int nq, unsigned* ghist, unsigned* s_prefix, int* s_grp)
 {
     TlSel& tl = S->tl;
     const int width = tl.width;
@@ -405,21 +436,16 @@ __device__ void plan_pass(SelState* S, int P, int nq, unsigned* ghist)
     __syncthreads();
     for (int i = threadIdx.x; i < words; i += blockDim.x) ghist[i] = 0u;
     __syncthreads();
+    const bool restart = tl.window && tl.restart;          // the window missed a rank: all slots start over on raw keys
+    const bool more = restart || tl.left - width > 0;
+    __syncthreads();                                       // (every thread has read the state thread 0 now changes)
     if (threadIdx.x == 0) {
-        if (tl.window && tl.restart) {                     // the window missed a rank: all slots start over on raw keys
-            tl.window = 0; tl.key_lo = 0u; tl.restart = 0; tl.left = 31;
-            for (int s = 0; s < P * nq; ++s) {
-                SelSlot sl = S->slot[1][s];
-                sl.prefix = 0u; sl.k_rem = sl.rank;
-                S->slot[1][s] = sl;
-            }
-            tbt_plan_next(S, P, nq);
-        } else {
-            tl.left -= width;
-            if (tl.left <= 0) { tl.left = 0; tl.width = 0; tl.G = 0; }
-            else tbt_plan_next(S, P, nq);
-        }
+        if (restart) { tl.window = 0; tl.key_lo = 0u; tl.restart = 0; tl.left = 31; }
+        else if (more) tl.left -= width;
+        else { tl.left = 0; tl.width = 0; tl.G = 0; }
     }
+    __syncthreads();
+    if (more) tbt_plan_next(S, P, nq, s_prefix, s_grp, false, restart);
 }
 
 // Workgroups of the launches below, by what they run.
@@ -472,7 +498,7 @@ __global__ __launch_bounds__(1024) void k_tbt_select(SelState* S, int P, int nq,
     if (S->tl.width <= 0) return;
     select_slot(S, nq, ghist, blockIdx.x, wsum, &s_digit, &s_rem, binsum, 2048);
     if (!take_last_ticket(ticket)) return;
-    plan_pass(S, P, nq, ghist);
+    plan_pass(S, P, nq, ghist, reinterpret_cast<unsigned*>(binsum), reinterpret_cast<int*>(binsum + DISCO_MAX_SLOTS));
     if (threadIdx.x == 0) *ticket = 0u;
 }
 
@@ -509,7 +535,7 @@ __global__ __launch_bounds__(1024) void k_tbt_spare(TraceView tr, i64 n_tok, int
         select_slot(S, a.nq, a.ghist, s, wsum, &s_digit, &s_rem, reinterpret_cast<u64*>(smem), DISCO_TL_HIST_WORDS / 2);
         __syncthreads();
     }
-    plan_pass(S, a.P, a.nq, a.ghist);
+    plan_pass(S, a.P, a.nq, a.ghist, smem, reinterpret_cast<int*>(smem + DISCO_MAX_SLOTS));
     if (threadIdx.x == 0) *a.ticket = 0u;
 }
 
