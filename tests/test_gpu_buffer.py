@@ -148,6 +148,25 @@ def test_buffer_stats(B, oracle, cost):
         assert want[3]["s_pre"] > oracle.stats(tr, [oracle.Policy(mode=1, l_th=-1, w_tail=0.0)], cost)[0]["s_pre"]
 
 
+def test_buffer_many_columns(B, oracle):
+    """40 columns of both hand-off directions and both prices: the per-column totals of the buffer pairs are added by
+    column lanes that each read every request of a batch (no sub-groups left at more than 32 columns), on a request
+    count that fills the last batch only partly."""
+    print("buffer parity 40 columns", flush=True)
+    rng = np.random.default_rng(77)
+    tr = slow_prefill(DI.handmade_trace(57, 1003, tokens=True, max_out=180, stall_p=0.02))
+    specs = []
+    for j in range(40):
+        if j % 2 == 0:
+            specs.append(dict(mode=0, l_th=int(rng.integers(0, 60)), mig_mode=2 if j % 6 else 1))
+        else:
+            specs.append(dict(mode=1, l_th=int(rng.integers(-1, 30)), w_tail=DI.f32(rng.uniform(0, 0.8)), mig_mode=2 if j % 5 else 0))
+    for cost in (DI.COST_S, DI.COST_D):
+        _, acc, want = check_migration(B, oracle, tr, specs, DI.TAU, DI.KAPPA_LAG, delivered_col=None, cost=cost)
+        assert max(want["n_migrated"]) > 20
+    check_stats(B, oracle, tr, specs, DI.COST_S, tau=DI.TAU, kappa=DI.KAPPA_LAG)
+
+
 def test_buffer_columns_in_a_device_resident_table(B, oracle):
     """The table never visits the host: the library cannot inspect it and picks the kernel on the device."""
     print("buffer migration parity device-resident table", flush=True)
