@@ -7,10 +7,11 @@
 //                the others get their histogram row into the request's
 //                descriptor and the request into the walk list
 //   k_pp_reduce  per-workgroup count slices -> counts per class and length
-//   k_tl_hist    one pass over the walk list: a wave walks one request at a
-//                time in chunks of 256 tokens, four consecutive tokens per
-//                lane (one 16-byte load per lane and chunk, the next chunk's
-//                load issued before the current one is used)
+//   k_tl_hist    one pass over the walk list (workgroup body and walker in
+//                disco_tl_hist_fast.h): a wave walks one request at a time in
+//                chunks of 256 tokens, four consecutive tokens per lane (one
+//                16-byte load per lane and chunk, the next chunk's load
+//                issued before the current one is used)
 //
 // The delivery recurrence delta_t = max(r_t, delta_{t-1} + tau) is evaluated
 // in the shifted domain u_t = r_t - t tau, where it is a running maximum M_t

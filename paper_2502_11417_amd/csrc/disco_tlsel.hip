@@ -160,7 +160,8 @@ __device__ __forceinline__ int table_compact(ClassTable& T)
 // and enters them (a few dozen) into a device-wide table of the same kind; the workgroup that takes the last
 // ticket compacts that table, puts the sets in ascending order (so that the class numbers do not depend on
 // timing), numbers the classes that need a token walk and plans the first histogram pass.  Also clears the length
-// counts and the device-wide bins.  The device-wide table was zeroed when the selection started (k_select_init).
+// counts and the device-wide bins.  The device-wide table was zeroed when the selection started (select_init, in
+// the launch that stages the policy table).
 __global__ __launch_bounds__(CL_BLOCK) void k_tl_classify(TraceView tr, const disco_policy* __restrict__ pol, int P, int nq,
                                                      float tau, const TlSummary* __restrict__ summary,
                                                      const BufSummary* __restrict__ bufsum, SelState* S,
